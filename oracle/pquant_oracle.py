@@ -1,0 +1,372 @@
+"""CPU oracle for the pQuant decoupled linear layer.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, NumPy transcription of the paper's definitions: fp64 arithmetic everywhere a value
+is accumulated, one rounding to fp32 where a value is later compared or thresholded (mu, gamma, the
+quantiser product, router logits).  It shares no code with the HIP library and never calls it; only
+tests, the smoke check and the bench's cpu_baseline leg may import it.  The product path must not.
+
+Notation follows the paper: W latent weight [m=d_out, n=d_in] (Y = W X), mu/lambda the weight
+statistics (Sec. 3.1, eq. for mu and lambda), gamma the per-token AbsMax scale, Q(.) the INT8
+quantiser (Sec. 3.1), alpha/beta the feature scales (Sec. 3.2, FFN equation), N experts with a
+linear softmax router and top-k selection (Sec. 3.3).
+
+Pins (tests/test_oracle_*.py) cover every function below; none is "parity unpinned".
+
+Readings taken where the paper is silent or garbled (each also listed in the design notes):
+  * Sign(0): W >= mu maps to +1 (a two-valued code needs a choice).
+  * lambda is the mean of |W| on the raw (un-centred) weights, as printed.
+  * RoundClip bounds: gamma = 128/absmax, round half to even, clamp to [-128, 127].
+  * one gamma per token (row of X); a zero row uses max(absmax, 1e-5).
+  * the high-precision branch reads the raw X (not Q(X)) and keeps 16-bit weights (Sec. 4.6 FP16 variant).
+  * router: logits on raw X, top-k on logits (ties -> lower index), gates = softmax over all experts,
+    not renormalised.
+  * STE: identity through Sign and Q; mu, lambda, gamma carry no gradient.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F32 = np.float32
+F64 = np.float64
+
+
+# ----------------------------------------------------------------------------------------------
+# Sec. 3.1: weight statistics, binarisation, packing (App. A: offline packing)
+# ----------------------------------------------------------------------------------------------
+def weight_stats(W):
+    """mu = mean(W), lambda = mean(|W|) over the whole matrix (Sec. 3.1, eq. mu/lambda); fp64 sums,
+    one rounding to fp32."""
+    W64 = np.asarray(W, dtype=F64)
+    n = W64.size
+    mu = F32(W64.sum() / n)
+    lam = F32(np.abs(W64).sum() / n)
+    return mu, lam
+
+
+def binarise(W, mu):
+    """W^INT1 = Sign(W - mu) (Sec. 3.1); the compare is done in fp32 without forming W - mu."""
+    W32 = np.asarray(W, dtype=F32)
+    return np.where(W32 >= F32(mu), np.int8(1), np.int8(-1)).astype(np.int8)
+
+
+def pack_sign(S):
+    """Pack +/-1 into uint32 words along d_in, bit j of word w <-> column 32 w + j, bit 1 <-> +1
+    (App. A: packed 1-bit storage; the paper packs 8 per byte, which is the same byte stream)."""
+    S = np.asarray(S)
+    m, n = S.shape
+    assert n % 32 == 0
+    bits = (S > 0).reshape(m, n // 32, 32).astype(np.uint64)
+    place = np.uint64(1) << np.arange(32, dtype=np.uint64)
+    return (bits * place).sum(axis=2).astype(np.uint32)
+
+
+def unpack_sign(P, n):
+    P = np.asarray(P, dtype=np.uint32)
+    m = P.shape[0]
+    j = np.arange(32, dtype=np.uint32)
+    bits = (P[:, :, None] >> j) & np.uint32(1)
+    return np.where(bits.reshape(m, -1)[:, :n] == 1, np.int8(1), np.int8(-1)).astype(np.int8)
+
+
+def ste_mask(W, mu, tau):
+    """Optional weight-gradient clipping mask 1[|W - mu| <= tau]; tau = inf is the paper's plain STE."""
+    W64 = np.asarray(W, dtype=F64)
+    return (np.abs(W64 - F64(mu)) <= F64(tau))
+
+
+# ----------------------------------------------------------------------------------------------
+# Sec. 3.1: AbsMax INT8 activation quantiser
+# ----------------------------------------------------------------------------------------------
+def quant_act(X):
+    """Q(X) = RoundClip(X * gamma), gamma = 2^7 / max_k |x_k| per token (Sec. 3.1). fp32 throughout:
+    IEEE division, one fp32 product, round half to even, clamp to [-128, 127]."""
+    X32 = np.asarray(X, dtype=F32)
+    a = np.max(np.abs(X32), axis=1) if X32.shape[1] else np.zeros(X32.shape[0], F32)
+    gamma = (F32(128.0) / np.maximum(a, F32(1e-5))).astype(F32)
+    y = (X32 * gamma[:, None]).astype(F32)
+    q = np.clip(np.rint(y), -128, 127).astype(np.int8)
+    return q, gamma
+
+
+def onebit_acc(q, S):
+    """Integer accumulator acc[t, i] = sum_j q[t, j] * S[i, j] (the W1A8 product of Sec. 3.1)."""
+    return np.asarray(q, dtype=np.int64) @ np.asarray(S, dtype=np.int64).T
+
+
+# ----------------------------------------------------------------------------------------------
+# Sec. 3.3: router
+# ----------------------------------------------------------------------------------------------
+def router_topk(X, Wr, k):
+    """Linear router + softmax gate + top-k (Sec. 3.3).  logits are fp64 dot products rounded once to
+    fp32; selection is on the logits, descending, ties to the lower expert index."""
+    X64 = np.asarray(X, dtype=F64)
+    Wr64 = np.asarray(Wr, dtype=F64)
+    logits = (X64 @ Wr64.T).astype(F32)
+    l64 = logits.astype(F64)
+    z = l64 - l64.max(axis=1, keepdims=True)
+    e = np.exp(z)
+    p = e / e.sum(axis=1, keepdims=True)
+    idx = np.argsort(-l64, axis=1, kind="stable")[:, :k].astype(np.int32)
+    gate = np.take_along_axis(p, idx.astype(np.int64), axis=1)
+    return idx, gate, p, logits
+
+
+def _router_bwd(dgate, idx, p, X64, Wr64):
+    """Gradient of gate[t,j] = softmax(logits)[t, idx[t,j]] w.r.t. logits, then Wr and X."""
+    T, E = p.shape
+    dlogit = np.zeros((T, E), F64)
+    for j in range(idx.shape[1]):
+        pj = np.take_along_axis(p, idx[:, j:j + 1].astype(np.int64), axis=1)[:, 0]
+        onehot = np.zeros((T, E), F64)
+        onehot[np.arange(T), idx[:, j]] = 1.0
+        dlogit += (dgate[:, j] * pj)[:, None] * (onehot - p)
+    return dlogit.T @ X64, dlogit @ Wr64, dlogit
+
+
+# ----------------------------------------------------------------------------------------------
+# Sec. 3.1-3.3: the decoupled linear layer, forward
+# ----------------------------------------------------------------------------------------------
+def linear_fwd(X, W, alpha, beta, A=None, B=None, Wr=None, top_k=1, packed=None, mu_lambda=None,
+               scale_fp16=False):
+    """Y = beta * (lambda/gamma) W^INT1 Q(X)  +  alpha * HP(X)   (Sec. 3.1 last eq.; Sec. 3.2 FFN eq.)
+
+    HP is absent (A is None: the pure 1-bit linear of the attention projections), a single
+    two-factor branch B (A x), or E routed low-rank experts B_e (A_e x) weighted by their gates.
+    With `packed` given the weight side is read back from packed bits and `mu_lambda` (inference).
+    `scale_fp16` rounds beta*lambda to fp16 once (the stored inference scale).
+    """
+    X32 = np.asarray(X, dtype=F32)
+    X64 = X32.astype(F64)
+    T, n = X32.shape
+    if packed is None:
+        mu, lam = weight_stats(W)
+        S = binarise(W, mu)
+        P = pack_sign(S)
+    else:
+        mu, lam = F32(mu_lambda[0]), F32(mu_lambda[1])
+        P = np.asarray(packed, dtype=np.uint32)
+        S = unpack_sign(P, n)
+    q, gamma = quant_act(X32)
+    acc = onebit_acc(q, S)
+    assert np.all(np.abs(acc) < 2 ** 24)
+    bl = F32(F32(beta) * lam)
+    if scale_fp16:
+        bl = F32(np.float16(bl))
+    s = (bl / gamma).astype(F32)
+    Y1 = (s[:, None] * acc.astype(F32)).astype(F32)               # beta already inside
+    Y1_nobeta = (F64(lam) / gamma.astype(F64))[:, None] * acc       # for d beta
+    out = dict(mu=mu, lam=lam, S=S, P=P, q=q, gamma=gamma, acc=acc, Y1=Y1, Y1_nobeta=Y1_nobeta)
+
+    m = S.shape[0]
+    Yhp = np.zeros((T, m), F64)
+    if A is not None:
+        A64 = np.asarray(A, dtype=F64)
+        B64 = np.asarray(B, dtype=F64)
+        if A64.ndim == 2:                                           # one dense branch
+            H = X64 @ A64.T
+            Yhp = H @ B64.T
+            out["H"] = H
+        else:                                                       # routed experts
+            idx, gate, p, logits = router_topk(X32, Wr, top_k)
+            E = A64.shape[0]
+            Hs = np.zeros((T, top_k, A64.shape[1]), F64)
+            Ys = np.zeros((T, top_k, m), F64)
+            for j in range(top_k):
+                for e in range(E):
+                    sel = np.nonzero(idx[:, j] == e)[0]
+                    if sel.size:
+                        h = X64[sel] @ A64[e].T
+                        Hs[sel, j] = h
+                        Ys[sel, j] = h @ B64[e].T
+            Yhp = (gate[:, :, None] * Ys).sum(axis=1)
+            out.update(idx=idx, gate=gate, probs=p, logits=logits, Hs=Hs, Ys=Ys)
+    out["Yhp"] = Yhp
+    out["Y"] = Y1.astype(F64) + F64(alpha) * Yhp
+    return out
+
+
+# ----------------------------------------------------------------------------------------------
+# STE backward (Sec. 4 intro; App. B.1)
+# ----------------------------------------------------------------------------------------------
+def linear_bwd(dY, X, W, alpha, beta, fwd, A=None, B=None, Wr=None, ste_tau=np.inf):
+    """Gradients of the decoupled linear with the straight-through estimator: the quantised
+    activation q/gamma and the binarised weight lambda*S are treated as if they were X and W."""
+    dY64 = np.asarray(dY, dtype=F64)
+    X64 = np.asarray(X, dtype=F64)
+    S64 = fwd["S"].astype(F64)
+    q64 = fwd["q"].astype(F64)
+    g64 = fwd["gamma"].astype(F64)
+    lam = F64(fwd["lam"])
+    al, be = F64(alpha), F64(beta)
+
+    g = dict()
+    g["dbeta"] = float((dY64 * fwd["Y1_nobeta"]).sum())
+    g["dalpha"] = float((dY64 * fwd["Yhp"]).sum())
+    dX = be * lam * (dY64 @ S64)
+    dW = be * ((dY64 / g64[:, None]).T @ q64)
+    if np.isfinite(ste_tau):
+        dW = dW * ste_mask(W, fwd["mu"], ste_tau)
+    g["dW"] = dW
+
+    if A is not None:
+        A64 = np.asarray(A, dtype=F64)
+        B64 = np.asarray(B, dtype=F64)
+        G = al * dY64
+        if A64.ndim == 2:
+            H = fwd["H"]
+            dH = G @ B64
+            g["dB"] = G.T @ H
+            g["dA"] = dH.T @ X64
+            dX = dX + dH @ A64
+        else:
+            idx, gate, p = fwd["idx"], fwd["gate"], fwd["probs"]
+            E = A64.shape[0]
+            dA = np.zeros_like(A64)
+            dB = np.zeros_like(B64)
+            dgate = np.einsum("ti,tji->tj", G, fwd["Ys"])
+            for j in range(idx.shape[1]):
+                for e in range(E):
+                    sel = np.nonzero(idx[:, j] == e)[0]
+                    if not sel.size:
+                        continue
+                    dy = gate[sel, j][:, None] * G[sel]
+                    dB[e] += dy.T @ fwd["Hs"][sel, j]
+                    dh = dy @ B64[e]
+                    dA[e] += dh.T @ X64[sel]
+                    dX[sel] += dh @ A64[e]
+            dWr, dX_r, dlogit = _router_bwd(dgate, idx, p, X64, np.asarray(Wr, dtype=F64))
+            dX = dX + dX_r
+            g.update(dA=dA, dB=dB, dWr=dWr, dgate=dgate, dlogit=dlogit)
+    g["dX"] = dX
+    return g
+
+
+# ----------------------------------------------------------------------------------------------
+# Sec. 3.2 / 3.3: the decoupled FFN (1-bit up/gate/down + routed high-precision FFN experts)
+# ----------------------------------------------------------------------------------------------
+def _sigmoid(x):
+    return 1.0 / (1.0 + np.exp(-x))
+
+
+def _silu(x):
+    return x * _sigmoid(x)
+
+
+def _dsilu(x):
+    s = _sigmoid(x)
+    return s * (1.0 + x * (1.0 - s))
+
+
+def _round_io(x, bf16):
+    """Round to the storage format of saved activations (bf16 via the library cast, else fp32)."""
+    if not bf16:
+        return np.asarray(x, dtype=F32)
+    import torch
+    return torch.from_numpy(np.asarray(x, dtype=F32)).to(torch.bfloat16).to(torch.float32).numpy()
+
+
+def ffn_fwd(X, W_up, W_gate, W_down, Up, Gate, Down, Wr, alpha, beta, top_k=1, bf16=True):
+    """Y = alpha * sum_j gate_j FFN_e_j(X) + beta * FFN^INT1(X)   (Sec. 3.2 FFN equation, Sec. 3.3).
+
+    FFN^INT1: three pure 1-bit linears around a gated unit, hidden state re-quantised before the
+    down projection:  U = L_up(Q(X)), G = L_gate(Q(X)), Hd = silu(G) * U, Y1 = L_down(Q(Hd)).
+    U and G are rounded to the storage format (they are saved for the backward pass); Hd is formed
+    from the rounded values and quantised from fp32.  Experts are gated FFNs of hidden width r.
+    """
+    X32 = np.asarray(X, dtype=F32)
+    X64 = X32.astype(F64)
+    T, d = X32.shape
+    q, gamma = quant_act(X32)
+    st = {}
+    for name, Wm in (("up", W_up), ("gate", W_gate), ("down", W_down)):
+        mu, lam = weight_stats(Wm)
+        st[name] = dict(mu=mu, lam=lam, S=binarise(Wm, mu))
+    U = ((st["up"]["lam"] / gamma).astype(F32)[:, None] * onebit_acc(q, st["up"]["S"]).astype(F32)).astype(F32)
+    G = ((st["gate"]["lam"] / gamma).astype(F32)[:, None] * onebit_acc(q, st["gate"]["S"]).astype(F32)).astype(F32)
+    U = _round_io(U, bf16)
+    G = _round_io(G, bf16)
+    Hd = (_silu(G.astype(F64)) * U.astype(F64)).astype(F32)
+    qh, gamma_h = quant_act(Hd)
+    acc_d = onebit_acc(qh, st["down"]["S"])
+    Y1 = (F64(st["down"]["lam"]) / gamma_h.astype(F64))[:, None] * acc_d     # before beta
+
+    idx, gate, p, logits = router_topk(X32, Wr, top_k)
+    E, r, _ = np.asarray(Up).shape
+    Up64, Gate64, Down64 = (np.asarray(a, dtype=F64) for a in (Up, Gate, Down))
+    ue = np.zeros((T, top_k, r), F64)
+    ge = np.zeros((T, top_k, r), F64)
+    Ys = np.zeros((T, top_k, d), F64)
+    for j in range(top_k):
+        for e in range(E):
+            sel = np.nonzero(idx[:, j] == e)[0]
+            if sel.size:
+                ue[sel, j] = X64[sel] @ Up64[e].T
+                ge[sel, j] = X64[sel] @ Gate64[e].T
+                Ys[sel, j] = (_silu(ge[sel, j]) * ue[sel, j]) @ Down64[e].T
+    Yhp = (gate[:, :, None] * Ys).sum(axis=1)
+    Y = F64(beta) * Y1 + F64(alpha) * Yhp
+    return dict(Y=Y, Y1=Y1, Yhp=Yhp, q=q, gamma=gamma, U=U, G=G, Hd=Hd, qh=qh, gamma_h=gamma_h,
+                st=st, idx=idx, gate=gate, probs=p, logits=logits, ue=ue, ge=ge, Ys=Ys, acc_d=acc_d)
+
+
+def ffn_bwd(dY, X, Up, Gate, Down, Wr, alpha, beta, fwd):
+    """STE backward of ffn_fwd: identity through every quantiser, rounding and Sign."""
+    dY64 = np.asarray(dY, dtype=F64)
+    X64 = np.asarray(X, dtype=F64)
+    al, be = F64(alpha), F64(beta)
+    st = fwd["st"]
+    g = dict(dbeta=float((dY64 * fwd["Y1"]).sum()), dalpha=float((dY64 * fwd["Yhp"]).sum()))
+
+    dY1 = be * dY64
+    Sd = st["down"]["S"].astype(F64)
+    dHd = F64(st["down"]["lam"]) * (dY1 @ Sd)
+    g["dW_down"] = (dY1 / fwd["gamma_h"].astype(F64)[:, None]).T @ fwd["qh"].astype(F64)
+    U64, G64 = fwd["U"].astype(F64), fwd["G"].astype(F64)
+    dU = dHd * _silu(G64)
+    dG = dHd * U64 * _dsilu(G64)
+    q64 = fwd["q"].astype(F64)
+    gx = fwd["gamma"].astype(F64)[:, None]
+    g["dW_up"] = (dU / gx).T @ q64
+    g["dW_gate"] = (dG / gx).T @ q64
+    dX = F64(st["up"]["lam"]) * (dU @ st["up"]["S"].astype(F64)) \
+        + F64(st["gate"]["lam"]) * (dG @ st["gate"]["S"].astype(F64))
+
+    Up64, Gate64, Down64 = (np.asarray(a, dtype=F64) for a in (Up, Gate, Down))
+    idx, gate, p = fwd["idx"], fwd["gate"], fwd["probs"]
+    E = Up64.shape[0]
+    Gr = al * dY64
+    dUp, dGate, dDown = np.zeros_like(Up64), np.zeros_like(Gate64), np.zeros_like(Down64)
+    dgate = np.einsum("ti,tji->tj", Gr, fwd["Ys"])
+    for j in range(idx.shape[1]):
+        for e in range(E):
+            sel = np.nonzero(idx[:, j] == e)[0]
+            if not sel.size:
+                continue
+            u, gg = fwd["ue"][sel, j], fwd["ge"][sel, j]
+            a = _silu(gg) * u
+            dy = gate[sel, j][:, None] * Gr[sel]
+            dDown[e] += dy.T @ a
+            da = dy @ Down64[e]
+            du = da * _silu(gg)
+            dg = da * u * _dsilu(gg)
+            dUp[e] += du.T @ X64[sel]
+            dGate[e] += dg.T @ X64[sel]
+            dX[sel] += du @ Up64[e] + dg @ Gate64[e]
+    dWr, dX_r, dlogit = _router_bwd(dgate, idx, p, X64, np.asarray(Wr, dtype=F64))
+    g.update(dX=dX + dX_r, dUp=dUp, dGate=dGate, dDown=dDown, dWr=dWr, dU=dU, dG=dG, dHd=dHd)
+    return g
+
+
+# ----------------------------------------------------------------------------------------------
+# App. A: inference on packed weights (decode GEMV)
+# ----------------------------------------------------------------------------------------------
+def decode_gemv(x, P, mu_lambda, alpha, beta, A=None, B=None, Wr=None, top_k=2):
+    """One decode step on packed 1-bit weights: linear_fwd read from packed bits, with beta*lambda
+    folded into a single fp16 scale (App. A: scalars merged for inference)."""
+    return linear_fwd(x, None, alpha, beta, A=A, B=B, Wr=Wr, top_k=top_k, packed=P,
+                      mu_lambda=mu_lambda, scale_fp16=True)
+
+
+def bits_per_weight(frac_1bit, frac_8bit):
+    """Average bit-width of a decoupled layer (Table 1 percentages -> the 'Bit' column of Table 2)."""
+    return frac_1bit * 1.0 + frac_8bit * 8.0

@@ -1,0 +1,425 @@
+"""Pins of the CPU oracle against things other than itself: hand-worked cases, brute force with
+Python integers, exactly-rounded sums, library routines, the lookup-table route of App. A, closed
+forms, error bounds and finite differences.  None of these need a GPU."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import pquant_oracle as po
+from paper_2602_22592_amd import workloads as wl
+
+GOLD = {}
+with open(os.path.join(os.path.dirname(__file__), "golden", "paper_values.txt")) as fh:
+    for line in fh:
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = line.split("=")
+            GOLD[k.strip()] = float(v)
+
+
+# ---------------------------------------------------------------- weight statistics / binariser
+def test_weight_stats_hand_case():
+    W = np.array([[1.0, -3.0], [2.0, 4.0]], np.float32)
+    mu, lam = po.weight_stats(W)
+    assert mu == np.float32(1.0) and lam == np.float32(2.5)          # lambda on raw |W|, not |W - mu|
+
+
+@pytest.mark.parametrize("seed,shape,bf16", [(0, (37, 64), False), (1, (256, 256), True), (2, (2048, 2048), True)])
+def test_weight_stats_vs_exactly_rounded_sum(seed, shape, bf16):
+    W = wl.normal(np.random.default_rng(seed), shape, 0.02, bf16)
+    mu, lam = po.weight_stats(W)
+    flat = [float(v) for v in W.ravel()]
+    assert mu == np.float32(math.fsum(flat) / W.size)
+    assert lam == np.float32(math.fsum(abs(v) for v in flat) / W.size)
+
+
+def test_binarise_hand_cases():
+    W = np.array([[1.0, -3.0], [2.0, 4.0]], np.float32)             # mu = 1 is an element: -> +1
+    assert po.binarise(W, np.float32(1.0)).tolist() == [[1, -1], [1, 1]]
+    C = np.full((3, 32), 0.125, np.float32)                          # all equal: W == mu everywhere
+    mu, lam = po.weight_stats(C)
+    assert mu == np.float32(0.125) and lam == np.float32(0.125)
+    assert np.all(po.binarise(C, mu) == 1)
+
+
+def test_binarise_is_sign_of_centred_weight():
+    W = wl.normal(np.random.default_rng(3), (64, 96), 0.02)
+    mu, _ = po.weight_stats(W)
+    S = po.binarise(W, mu)
+    d = W.astype(np.float64) - float(mu)
+    assert np.all(S[d > 0] == 1) and np.all(S[d < 0] == -1)
+    assert set(np.unique(S)) <= {-1, 1}
+    # centring balances the code: about half the weights land on each side
+    assert abs(S.astype(np.int64).sum()) < 0.1 * S.size
+
+
+def test_pack_bruteforce_roundtrip_popcount_and_bytes():
+    rng = np.random.default_rng(4)
+    S = np.where(rng.random((16, 64)) < 0.4, 1, -1).astype(np.int8)
+    P = po.pack_sign(S)
+    assert P.dtype == np.uint32 and P.shape == (16, 2)
+    for i in range(16):                                               # brute force, Python ints
+        for w in range(2):
+            word = 0
+            for j in range(32):
+                if S[i, 32 * w + j] == 1:
+                    word |= 1 << j
+            assert int(P[i, w]) == word
+    assert np.array_equal(po.unpack_sign(P, 64), S)
+    assert sum(bin(int(v)).count("1") for v in P.ravel()) == int((S == 1).sum())
+    # library route: little-endian bit packing of the same booleans gives the same byte stream
+    assert np.array_equal(np.packbits(S > 0, axis=1, bitorder="little"), P.view(np.uint8).reshape(16, -1))
+    # App. A: 8 parameters per byte = 1/16 of FP16 storage
+    assert P.nbytes / (S.size * 2) == GOLD["packed_vs_fp16"]
+
+
+def test_bits_per_weight_matches_paper_tables():
+    assert round(po.bits_per_weight(GOLD["frac_1bit_300m"], GOLD["frac_8bit_300m"]), 2) == GOLD["bits_300m"]
+    assert round(po.bits_per_weight(GOLD["frac_1bit_1p3b"], GOLD["frac_8bit_1p3b"]), 2) == GOLD["bits_1p3b"]
+
+
+# ---------------------------------------------------------------- activation quantiser
+def test_quant_hand_cases():
+    X = np.array([[2.0, -2.0, 1.0, 0.5],            # gamma = 64: +absmax saturates 128 -> 127
+                  [0.0, 0.0, 0.0, 0.0],             # zero row -> gamma = 128 / 1e-5, codes 0
+                  [128.0, 0.5, 1.5, 2.5],           # gamma = 1: ties go to even
+                  [-4.0, 1.0, 3.0, 0.03125]],       # gamma = 32: -absmax -> -128, no clamp needed
+                 np.float32)
+    q, g = po.quant_act(X)
+    assert q.tolist() == [[127, -128, 64, 32], [0, 0, 0, 0], [127, 0, 2, 2], [-128, 32, 96, 1]]
+    assert g[0] == 64 and g[2] == 1 and g[3] == 32
+    assert g[1] == np.float32(128.0) / np.float32(1e-5)
+    assert 2 ** GOLD["act_range_log2"] == 128
+
+
+def test_quant_bruteforce_and_invariants():
+    X = wl.activations(np.random.default_rng(5), 33, 96, outlier_count=3, outlier_scale=10.0)
+    q, g = po.quant_act(X)
+    for t in range(X.shape[0]):
+        a = max(abs(float(v)) for v in X[t])
+        gt = np.float32(128.0) / np.float32(a)
+        assert g[t] == gt
+        for k in range(X.shape[1]):
+            y = float(np.float32(X[t, k]) * gt)                       # fp32 product, then Python round (half-even)
+            assert int(q[t, k]) == max(-128, min(127, round(y)))
+    amax = np.abs(q.astype(np.int32)).max(axis=1)
+    assert np.all((amax == 127) | (amax == 128))
+    err = np.abs(X.astype(np.float64) - q / g.astype(np.float64)[:, None]) * g.astype(np.float64)[:, None]
+    is_pos_max = X == np.abs(X).max(axis=1, keepdims=True)
+    assert np.all(err[~is_pos_max] <= 0.5 + 1e-4) and np.all(err <= 1.0 + 1e-4)
+
+
+def test_quant_idempotent_on_integer_rows():
+    rng = np.random.default_rng(6)
+    Z = rng.integers(-127, 128, size=(8, 64)).astype(np.float32)
+    Z[:, 0] = -128.0                                                  # absmax = 128 -> gamma = 1
+    q, g = po.quant_act(Z)
+    assert np.all(g == 1) and np.array_equal(q.astype(np.float32), Z)
+
+
+# ---------------------------------------------------------------- integer GEMM
+def _lut_dot(qrow, Prow):
+    """App. A lookup-table route: per group of 4 activations a 16-entry table of signed sums,
+    indexed by the 4 weight bits; the dot product is a sum of looked-up entries."""
+    total = 0
+    for gidx in range(len(qrow) // 4):
+        xs = [int(v) for v in qrow[4 * gidx:4 * gidx + 4]]
+        table = [sum(x if (pat >> j) & 1 else -x for j, x in enumerate(xs)) for pat in range(16)]
+        k = 4 * gidx
+        pat = (int(Prow[k // 32]) >> (k % 32)) & 0xF
+        total += table[pat]
+    return total
+
+
+def test_onebit_acc_bruteforce_and_lut_route():
+    rng = np.random.default_rng(7)
+    q = rng.integers(-128, 128, size=(5, 64)).astype(np.int8)
+    S = np.where(rng.random((7, 64)) < 0.5, 1, -1).astype(np.int8)
+    acc = po.onebit_acc(q, S)
+    P = po.pack_sign(S)
+    assert GOLD["lut_entries"] == 2 ** GOLD["lut_group"] == 16
+    for t in range(5):
+        for i in range(7):
+            assert int(acc[t, i]) == sum(int(q[t, k]) * int(S[i, k]) for k in range(64))
+            assert int(acc[t, i]) == _lut_dot(q[t], P[i])
+
+
+def test_onebit_acc_fp32_blas_is_an_exact_second_route():
+    rng = np.random.default_rng(8)
+    q = rng.integers(-128, 128, size=(64, 5504)).astype(np.int8)
+    S = np.where(rng.random((96, 5504)) < 0.5, 1, -1).astype(np.int8)
+    acc = po.onebit_acc(q, S)
+    blas = q.astype(np.float32) @ S.astype(np.float32).T             # all partial sums are integers < 2^24
+    assert np.array_equal(acc, blas.astype(np.int64))
+    assert np.abs(acc).max() < 2 ** 24
+
+
+# ---------------------------------------------------------------- forward
+def test_forward_reduces_to_textbook_onebit_linear():
+    c = wl.linear_case(9, 12, 64, 40)
+    f = po.linear_fwd(c["X"], c["W"], 0.0, 1.0)
+    mu = c["W"].astype(np.float64).mean()
+    lam = np.abs(c["W"].astype(np.float64)).mean()
+    S = np.sign(c["W"].astype(np.float64) - mu)
+    a = np.abs(c["X"]).max(axis=1).astype(np.float64)
+    q = np.clip(np.rint(c["X"].astype(np.float64) * (128.0 / a)[:, None]), -128, 127)
+    ref = (lam * a / 128.0)[:, None] * (q @ S.T)                      # Y = lambda/gamma * W1 * Q(X)
+    assert np.allclose(f["Y"], ref, rtol=1e-5, atol=1e-7)
+
+
+def test_forward_within_quantisation_error_of_float_binary_linear():
+    c = wl.linear_case(10, 20, 128, 48)
+    beta = 0.7
+    f = po.linear_fwd(c["X"], c["W"], 0.0, beta)
+    ideal = beta * float(f["lam"]) * (c["X"].astype(np.float64) @ f["S"].astype(np.float64).T)
+    bound = beta * float(f["lam"]) * c["X"].shape[1] * (1.0 / f["gamma"].astype(np.float64))  # |x - q/gamma| <= 1/gamma
+    assert np.all(np.abs(f["Y"] - ideal) <= bound[:, None] * 1.0001)
+    # and much closer on average: rounding errors are centred
+    assert np.abs(f["Y"] - ideal).mean() < 0.1 * bound.mean()
+
+
+def test_forward_beta_zero_is_plain_lowrank_matmul():
+    c = wl.linear_case(11, 9, 64, 40, hp_rank=8)
+    f = po.linear_fwd(c["X"], c["W"], 1.5, 0.0, A=c["A"], B=c["B"])
+    ref = 1.5 * (c["X"].astype(np.float64) @ c["A"].astype(np.float64).T) @ c["B"].astype(np.float64).T
+    assert np.allclose(f["Y"], ref, rtol=1e-12, atol=1e-15)
+
+
+def test_forward_sums_the_two_branches_with_feature_scales():
+    c = wl.linear_case(12, 9, 64, 40, hp_rank=8)
+    a, b = 2.0, 0.2
+    assert a == GOLD["alpha_init"] and b == GOLD["beta_init"]
+    f = po.linear_fwd(c["X"], c["W"], a, b, A=c["A"], B=c["B"])
+    one = po.linear_fwd(c["X"], c["W"], 0.0, 1.0)["Y"]
+    hp = po.linear_fwd(c["X"], c["W"], 1.0, 0.0, A=c["A"], B=c["B"])["Y"]
+    assert np.allclose(f["Y"], b * one + a * hp, rtol=1e-6, atol=1e-7)         # fp32 rounding of the 1-bit scale
+
+
+def test_packed_forward_equals_master_forward():
+    c = wl.linear_case(13, 6, 64, 40)
+    f = po.linear_fwd(c["X"], c["W"], 0.0, 0.3)
+    f2 = po.linear_fwd(c["X"], None, 0.0, 0.3, packed=f["P"], mu_lambda=(f["mu"], f["lam"]))
+    assert np.array_equal(f["acc"], f2["acc"]) and np.array_equal(f["Y"], f2["Y"])
+    f3 = po.decode_gemv(c["X"], f["P"], (f["mu"], f["lam"]), 0.0, 0.3)
+    s16 = float(np.float16(np.float32(0.3) * f["lam"]))
+    assert np.array_equal(f3["acc"], f["acc"])
+    assert np.allclose(f3["Y"], (s16 / f["gamma"].astype(np.float64))[:, None] * f["acc"], rtol=1e-6)
+
+
+# ---------------------------------------------------------------- router
+def test_router_hand_case_ties_and_softmax():
+    X = np.array([[1.0, 0.0], [0.0, 1.0], [1.0, 1.0]], np.float32)
+    Wr = np.array([[1.0, 0.0], [1.0, 0.0], [0.0, 2.0], [0.0, -1.0]], np.float32)   # experts 0,1 identical
+    idx, gate, p, logits = po.router_topk(X, Wr, 2)
+    assert logits.tolist() == [[1, 1, 0, 0], [0, 0, 2, -1], [1, 1, 2, -1]]
+    assert idx.tolist() == [[0, 1], [2, 0], [2, 0]]                    # ties -> lower index first
+    e = np.exp(np.array([1.0, 1.0, 0.0, 0.0]))
+    assert np.allclose(p[0], e / e.sum(), rtol=1e-12)
+    assert np.allclose(gate[0], (e / e.sum())[[0, 1]], rtol=1e-12)
+
+
+def test_router_invariants():
+    c = wl.linear_case(14, 200, 64, 32, hp_rank=4, n_experts=8)
+    for k in (1, 2):
+        idx, gate, p, logits = po.router_topk(c["X"], c["Wr"], k)
+        assert idx.shape == (200, k) and all(len(set(r)) == k for r in idx.tolist())
+        assert np.bincount(idx.ravel(), minlength=8).sum() == 200 * k
+        assert np.allclose(p.sum(axis=1), 1.0) and np.all(gate > 0) and np.all(gate <= 1)
+        assert np.array_equal(idx[:, 0], np.argmax(logits, axis=1))
+        if k == 2:
+            assert np.all(gate[:, 0] >= gate[:, 1])
+
+
+def test_routed_forward_bruteforce():
+    c = wl.linear_case(15, 10, 32, 24, hp_rank=4, n_experts=4)
+    f = po.linear_fwd(c["X"], c["W"], 1.0, 0.0, A=c["A"], B=c["B"], Wr=c["Wr"], top_k=2)
+    X, A, B, Wr = (c[k].astype(np.float64) for k in ("X", "A", "B", "Wr"))
+    for t in range(10):
+        lg = np.float32(Wr @ X[t]).astype(np.float64)
+        pr = np.exp(lg - lg.max()); pr /= pr.sum()
+        order = sorted(range(4), key=lambda e: (-lg[e], e))[:2]
+        y = sum(pr[e] * (B[e] @ (A[e] @ X[t])) for e in order)
+        assert f["idx"][t].tolist() == order
+        assert np.allclose(f["Y"][t], y, rtol=1e-10, atol=1e-14)
+
+
+# ---------------------------------------------------------------- backward
+def _fd(fun, x, eps):
+    g = np.zeros_like(x, dtype=np.float64)
+    it = np.nditer(x, flags=["multi_index"])
+    for _ in it:
+        i = it.multi_index
+        old = x[i]
+        x[i] = old + eps; fp = fun()
+        x[i] = old - eps; fm = fun()
+        x[i] = old
+        g[i] = (fp - fm) / (2 * eps)
+    return g
+
+
+def test_ste_terms_equal_gradients_of_the_bilinear_surrogate():
+    """With the STE the 1-bit branch is differentiated as beta * Xv Wv^T at Xv = q/gamma, Wv = lambda S."""
+    c = wl.linear_case(16, 6, 32, 8)
+    beta = 0.4
+    f = po.linear_fwd(c["X"], c["W"], 0.0, beta)
+    g = po.linear_bwd(c["dY"], c["X"], c["W"], 0.0, beta, f)
+    dY = c["dY"].astype(np.float64)
+    Xv = f["q"] / f["gamma"].astype(np.float64)[:, None]
+    Wv = float(f["lam"]) * f["S"].astype(np.float64)
+    loss = lambda: float((dY * (beta * Xv @ Wv.T)).sum())
+    assert np.allclose(g["dX"], _fd(loss, Xv, 1e-3), rtol=1e-6, atol=1e-9)
+    assert np.allclose(g["dW"], _fd(loss, Wv, 1e-4), rtol=1e-6, atol=1e-9)
+    # brute-force loops of the same formula
+    for n in range(8):
+        for k in range(0, 32, 7):
+            assert np.isclose(g["dW"][n, k], beta * sum(dY[t, n] * Xv[t, k] for t in range(6)), rtol=1e-10)
+    bfn = lambda b: float((dY * po.linear_fwd(c["X"], c["W"], 0.0, b)["Y"]).sum())
+    assert np.isclose(g["dbeta"], (bfn(beta + 1e-2) - bfn(beta - 1e-2)) / 2e-2, rtol=1e-4)
+
+
+def test_dense_hp_and_scale_gradients_by_finite_differences():
+    c = wl.linear_case(17, 7, 32, 12, hp_rank=4)
+    al, be = 1.7, 0.3
+    X, A, B = c["X"].astype(np.float64), c["A"].astype(np.float64), c["B"].astype(np.float64)
+    dY = c["dY"].astype(np.float64)
+    f = po.linear_fwd(X, c["W"], al, be, A=A, B=B)
+    g = po.linear_bwd(dY, X, c["W"], al, be, f, A=A, B=B)
+    loss = lambda: float((dY * po.linear_fwd(X, c["W"], al, be, A=A, B=B)["Yhp"]).sum()) * al
+    assert np.allclose(g["dA"], _fd(loss, A, 1e-5), rtol=1e-5, atol=1e-8)
+    assert np.allclose(g["dB"], _fd(loss, B, 1e-5), rtol=1e-5, atol=1e-8)
+    # dX = STE part (bilinear surrogate) + true derivative of the hp branch
+    ste = be * float(f["lam"]) * dY @ f["S"].astype(np.float64)
+    # (X is rounded to fp32 inside the oracle; the hp branch is linear in X, so a coarse probe is exact)
+    assert np.allclose(g["dX"] - ste, _fd(loss, X, 2.0 ** -6), rtol=1e-4, atol=1e-7)
+    fa = lambda a: float((dY * po.linear_fwd(X, c["W"], a, be, A=A, B=B)["Y"]).sum())
+    assert np.isclose(g["dalpha"], (fa(al + 1e-3) - fa(al - 1e-3)) / 2e-3, rtol=1e-6)
+
+
+def test_gradient_scaling_invariants():
+    """Sec. 3.2: alpha scales the hp-branch gradients, beta the 1-bit weight gradient."""
+    c = wl.linear_case(18, 7, 32, 12, hp_rank=4)
+    f1 = po.linear_fwd(c["X"], c["W"], 1.0, 1.0, A=c["A"], B=c["B"])
+    g1 = po.linear_bwd(c["dY"], c["X"], c["W"], 1.0, 1.0, f1, A=c["A"], B=c["B"])
+    f2 = po.linear_fwd(c["X"], c["W"], 2.0, 0.2, A=c["A"], B=c["B"])
+    g2 = po.linear_bwd(c["dY"], c["X"], c["W"], 2.0, 0.2, f2, A=c["A"], B=c["B"])
+    assert np.allclose(g2["dA"], 2.0 * g1["dA"]) and np.allclose(g2["dB"], 2.0 * g1["dB"])
+    assert np.allclose(g2["dW"], 0.2 * g1["dW"])
+    assert np.isclose(g2["dbeta"], g1["dbeta"]) and np.isclose(g2["dalpha"], g1["dalpha"])
+
+
+def test_ste_clip_mask():
+    c = wl.linear_case(19, 5, 32, 8)
+    f = po.linear_fwd(c["X"], c["W"], 0.0, 1.0)
+    g_inf = po.linear_bwd(c["dY"], c["X"], c["W"], 0.0, 1.0, f)
+    g_tau = po.linear_bwd(c["dY"], c["X"], c["W"], 0.0, 1.0, f, ste_tau=0.02)
+    keep = np.abs(c["W"].astype(np.float64) - float(f["mu"])) <= 0.02
+    assert 0 < keep.sum() < keep.size
+    assert np.array_equal(g_tau["dW"][keep], g_inf["dW"][keep]) and np.all(g_tau["dW"][~keep] == 0)
+
+
+def test_routed_gradients_by_finite_differences():
+    c = wl.linear_case(20, 9, 32, 10, hp_rank=3, n_experts=4, w_std=0.2)
+    al, be, k = 1.3, 0.25, 2
+    X, A, B, Wr = (c[n].astype(np.float64) for n in ("X", "A", "B", "Wr"))
+    dY = c["dY"].astype(np.float64)
+    f = po.linear_fwd(X, c["W"], al, be, A=A, B=B, Wr=Wr, top_k=k)
+    g = po.linear_bwd(dY, X, c["W"], al, be, f, A=A, B=B, Wr=Wr)
+
+    def loss():
+        ff = po.linear_fwd(X, c["W"], al, be, A=A, B=B, Wr=Wr, top_k=k)
+        assert np.array_equal(ff["idx"], f["idx"])                    # selection must not flip under the probe
+        return al * float((dY * ff["Yhp"]).sum())
+    # router logits are rounded to fp32 inside the oracle, so use a probe well above fp32 noise
+    assert np.allclose(g["dA"], _fd(loss, A, 1e-3), rtol=2e-3, atol=1e-5)
+    assert np.allclose(g["dB"], _fd(loss, B, 1e-3), rtol=2e-3, atol=1e-5)
+    assert np.allclose(g["dWr"], _fd(loss, Wr, 1e-3), rtol=2e-3, atol=2e-5)
+    ste = be * float(f["lam"]) * dY @ f["S"].astype(np.float64)
+    assert np.allclose(g["dX"] - ste, _fd(loss, X, 1e-3), rtol=2e-3, atol=2e-5)
+
+
+# ---------------------------------------------------------------- decoupled FFN
+def test_ffn_forward_is_composition_of_pinned_pieces():
+    c = wl.ffn_case(21, 11, 32, 64, 4, 4, bf16=True)
+    f = po.ffn_fwd(c["X"], c["W_up"], c["W_gate"], c["W_down"], c["Up"], c["Gate"], c["Down"], c["Wr"],
+                   2.0, 0.2, top_k=1, bf16=True)
+    up = po.linear_fwd(c["X"], c["W_up"], 0.0, 1.0)["Y"]
+    gt = po.linear_fwd(c["X"], c["W_gate"], 0.0, 1.0)["Y"]
+    U = wl.bf16_round(up.astype(np.float32)); G = wl.bf16_round(gt.astype(np.float32))
+    assert np.array_equal(U, f["U"]) and np.array_equal(G, f["G"])
+    hd = (G.astype(np.float64) / (1 + np.exp(-G.astype(np.float64))) * U).astype(np.float32)
+    y1 = po.linear_fwd(hd, c["W_down"], 0.0, 1.0)["Y"]
+    assert np.allclose(f["Y1"], y1, rtol=1e-6, atol=1e-9)
+    X = c["X"].astype(np.float64)
+    for t in range(11):
+        lg = np.float32(c["Wr"].astype(np.float64) @ X[t]).astype(np.float64)
+        e = int(np.argmax(lg)); pr = np.exp(lg - lg.max()); pr /= pr.sum()
+        u = c["Up"][e].astype(np.float64) @ X[t]; gg = c["Gate"][e].astype(np.float64) @ X[t]
+        y = pr[e] * (c["Down"][e].astype(np.float64) @ (gg / (1 + np.exp(-gg)) * u))
+        assert f["idx"][t, 0] == e
+        assert np.allclose(f["Y"][t], 0.2 * f["Y1"][t] + 2.0 * y, rtol=1e-9, atol=1e-12)
+
+
+def test_ffn_expert_and_router_gradients_by_finite_differences():
+    c = wl.ffn_case(22, 8, 32, 32, 4, 3, bf16=False, w_std=0.2, outlier_frac=0.0)
+    al, be = 1.4, 0.3
+    X, Up, Gate, Down, Wr = (c[n].astype(np.float64) for n in ("X", "Up", "Gate", "Down", "Wr"))
+    dY = c["dY"].astype(np.float64)
+    run = lambda: po.ffn_fwd(X, c["W_up"], c["W_gate"], c["W_down"], Up, Gate, Down, Wr, al, be, top_k=2, bf16=False)
+    f = run()
+    g = po.ffn_bwd(dY, X, Up, Gate, Down, Wr, al, be, f)
+
+    def loss():
+        ff = run()
+        assert np.array_equal(ff["idx"], f["idx"])
+        return al * float((dY * ff["Yhp"]).sum())
+    assert np.allclose(g["dUp"], _fd(loss, Up, 1e-3), rtol=2e-3, atol=2e-5)
+    assert np.allclose(g["dGate"], _fd(loss, Gate, 1e-3), rtol=2e-3, atol=2e-5)
+    assert np.allclose(g["dDown"], _fd(loss, Down, 1e-3), rtol=2e-3, atol=2e-5)
+    assert np.allclose(g["dWr"], _fd(loss, Wr, 1e-3), rtol=2e-3, atol=5e-5)
+    fa = lambda a, b: float((dY * po.ffn_fwd(X, c["W_up"], c["W_gate"], c["W_down"], Up, Gate, Down, Wr, a, b,
+                                             top_k=2, bf16=False)["Y"]).sum())
+    assert np.isclose(g["dalpha"], (fa(al + 1e-3, be) - fa(al - 1e-3, be)) / 2e-3, rtol=1e-6)
+    assert np.isclose(g["dbeta"], (fa(al, be + 1e-3) - fa(al, be - 1e-3)) / 2e-3, rtol=1e-6)
+
+
+def test_ffn_ste_chain_equals_gradients_of_the_smooth_surrogate():
+    """The 1-bit FFN differentiated with every quantiser replaced by identity, evaluated at the
+    quantised operands: Y1 = (silu(Xv Wg^T) * (Xv Wu^T)) Wd^T with STE around the re-quantiser."""
+    c = wl.ffn_case(23, 5, 32, 32, 2, 2, bf16=False, outlier_frac=0.0)
+    be = 0.6
+    f = po.ffn_fwd(c["X"], c["W_up"], c["W_gate"], c["W_down"], c["Up"], c["Gate"], c["Down"], c["Wr"],
+                   0.0, be, top_k=1, bf16=False)
+    g = po.ffn_bwd(c["dY"], c["X"], c["Up"], c["Gate"], c["Down"], c["Wr"], 0.0, be, f)
+    dY = c["dY"].astype(np.float64)
+    st = f["st"]
+    Wd = float(st["down"]["lam"]) * st["down"]["S"].astype(np.float64)
+    # down projection: bilinear surrogate in (Hv, Wd) at Hv = qh/gamma_h
+    Hv = f["qh"] / f["gamma_h"].astype(np.float64)[:, None]
+    l_down = lambda: be * float((dY * (Hv @ Wd.T)).sum())
+    assert np.allclose(g["dHd"], _fd(l_down, Hv, 1e-4), rtol=1e-6, atol=1e-9)
+    assert np.allclose(g["dW_down"], _fd(l_down, Wd, 1e-4), rtol=1e-6, atol=1e-9)   # beta is upstream of the whole FFN
+    # gated unit: true derivative of silu(G) * U given upstream dHd
+    U, G = f["U"].astype(np.float64), f["G"].astype(np.float64)
+    l_act = lambda: float((g["dHd"] * (G / (1 + np.exp(-G)) * U)).sum())
+    assert np.allclose(g["dU"], _fd(l_act, U, 1e-6), rtol=1e-6, atol=1e-10)
+    assert np.allclose(g["dG"], _fd(l_act, G, 1e-6), rtol=1e-5, atol=1e-10)
+    # up / gate projections: bilinear surrogates at Xv = q/gamma
+    Xv = f["q"] / f["gamma"].astype(np.float64)[:, None]
+    Wu = float(st["up"]["lam"]) * st["up"]["S"].astype(np.float64)
+    Wg = float(st["gate"]["lam"]) * st["gate"]["S"].astype(np.float64)
+    l_in = lambda: float((g["dU"] * (Xv @ Wu.T)).sum() + (g["dG"] * (Xv @ Wg.T)).sum())
+    assert np.allclose(g["dX"], _fd(l_in, Xv, 1e-4), rtol=1e-6, atol=1e-9)       # alpha = 0: no expert/router term
+    assert np.allclose(g["dW_up"], _fd(l_in, Wu, 1e-5), rtol=1e-6, atol=1e-9)
+    assert np.allclose(g["dW_gate"], _fd(l_in, Wg, 1e-5), rtol=1e-6, atol=1e-9)
+
+
+def test_workload_generators_are_seeded_and_bf16_exact():
+    a, b = wl.config1(), wl.config1()
+    assert all(np.array_equal(a[k], b[k]) for k in ("W", "X", "dY", "A", "B"))
+    c = wl.linear_case(1, 8, 64, 32, hp_rank=8, bf16=True)
+    for k in ("W", "X", "dY", "A", "B"):
+        wl.bf16_bits(c[k])                                            # asserts representability
+    col_energy = (a["X"].astype(np.float64) ** 2).mean(axis=0)
+    assert (col_energy > 30).sum() == 4                               # the four x10 outlier channels
