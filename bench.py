@@ -1,0 +1,147 @@
+#!/usr/bin/env python3
+"""Benchmark of the pQuant decoupled linear on one MI355X.
+
+A step is one forward + STE backward of the whole hot path on the 1.3B-shaped attention projection
+(tokens=8192, 2048x2048 1-bit branch, rank-128 high-precision branch, bf16 I/O, fp32 weight
+gradients): weight statistics, binarise+pack, activation quantiser, int8 MFMA GEMM, hp branch,
+and the backward GEMMs with the alpha/beta reductions.  Inputs are synthetic, seeded, and already
+resident in HBM when the timed region starts.
+
+Prints ONE JSON line (see the keys below).  `roofline` is for the dominant kernel, its duration
+measured with HIP events recorded by the library around each launch inside the timed region;
+`cpu_baseline` is the NumPy oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16 = 2.5e15      # dense MFMA bf16, FLOP/s
+PEAK_I8 = 5.0e15        # dense MFMA int8, OP/s
+
+
+def gemm_flops(T, K, N, r):
+    """Algorithmic flops of one launch of each GEMM label (2 * M * N * K each)."""
+    return {
+        "gemm_onebit_fwd": 2.0 * T * K * N,
+        "gemm_hp_H": 2.0 * T * r * K, "gemm_hp_Y": 2.0 * T * N * r,
+        "gemm_dH": 2.0 * T * r * N, "gemm_dX": 2.0 * T * K * N, "gemm_dX_hp": 2.0 * T * K * r,
+        "gemm_dW": 2.0 * T * K * N, "gemm_dB": 2.0 * T * N * r, "gemm_dA": 2.0 * T * r * K,
+    }
+
+
+def cpu_baseline(sample_tokens):
+    """The oracle as it stands, on the host cores, on the first `sample_tokens` tokens of the workload."""
+    from oracle import pquant_oracle as po
+    from paper_2602_22592_amd import workloads as wl
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    c = wl.config2(tokens=sample_tokens)
+    t0 = time.perf_counter()
+    f = po.linear_fwd(c["X"], c["W"], c["alpha"], c["beta"], A=c["A"], B=c["B"])
+    po.linear_bwd(c["dY"], c["X"], c["W"], c["alpha"], c["beta"], f, A=c["A"], B=c["B"])
+    dt = time.perf_counter() - t0
+    return {"value": sample_tokens / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {sample_tokens} tokens of the workload, fwd+bwd, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--tokens", type=int, default=8192)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_22592_amd import binding as pq
+    from paper_2602_22592_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    if not os.path.exists(pq.LIB_PATH):
+        from paper_2602_22592_amd.build import build
+        build(verbose=False)
+
+    c = wl.config2(tokens=args.tokens)
+    T, K, N, r = c["tokens"], c["d_in"], c["d_out"], c["hp_rank"]
+    bf = torch.bfloat16
+    to = lambda x: torch.from_numpy(x).cuda().to(bf)
+    X, W, dY, A, B = to(c["X"]), to(c["W"]), to(c["dY"]), to(c["A"]), to(c["B"])
+    desc = pq.make_desc(T, K, N, hp_rank=r, io_dtype=pq.PQ_BF16, alpha=c["alpha"], beta=c["beta"])
+    bufs = pq.LinearBuffers(desc)
+    Y = torch.empty((T, N), dtype=bf, device="cuda")
+    dX = torch.empty((T, K), dtype=bf, device="cuda")
+    dW = torch.empty((N, K), dtype=torch.float32, device="cuda")
+    dA = torch.empty((r, K), dtype=torch.float32, device="cuda")
+    dB = torch.empty((N, r), dtype=torch.float32, device="cuda")
+    dab = torch.empty((2,), dtype=torch.float32, device="cuda")
+
+    def step():
+        pq.linear_fwd(desc, X, W, Y, bufs, A=A, B=B)
+        pq.linear_bwd(desc, dY, X, W, bufs, dX, dW, dab, A=A, B=B, dA=dA, dB=dB)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    pq.prof_reset()
+    pq.prof_enable(True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    pq.prof_enable(False)
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    prof = pq.prof_read()
+    pq.prof_reset()
+
+    kernels = {k: {"avg_us": 1e3 * ms / n, "launches": n} for k, (ms, n) in prof.items()}
+    fl = gemm_flops(T, K, N, r)
+    dom = max((k for k in kernels if k in fl), key=lambda k: kernels[k]["avg_us"] * kernels[k]["launches"])
+    is_i8 = dom == "gemm_onebit_fwd"
+    achieved = fl[dom] / (kernels[dom]["avg_us"] * 1e-6) / 1e12
+    peak = (PEAK_I8 if is_i8 else PEAK_BF16) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": peak,
+                "unit": "TOP/s" if is_i8 else "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
+                "avg_us": round(kernels[dom]["avg_us"], 2)}
+    # whole-step MFMA utilisation: int8 ops at the int8 peak + bf16 flops at the bf16 peak
+    t_mfma = fl["gemm_onebit_fwd"] / PEAK_I8 + sum(v for k, v in fl.items() if k != "gemm_onebit_fwd") / PEAK_BF16
+    out = {
+        "metric": "decoupled-linear fwd+bwd tokens/s", "value": round(T / (ms_per_step * 1e-3), 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8 (1-bit branch fwd) + bf16 (hp branch, backward), fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"1.3B-shaped attention projection: tokens={T}, d_in=d_out={K}, hp rank {r}, "
+                               "bf16 master weights, fwd + STE bwd (dX, dW, dA, dB, dalpha, dbeta)"},
+        "mfma_frac_of_step": round(t_mfma / (ms_per_step * 1e-3), 4),
+        "roofline": roofline,
+        "kernels_us": {k: round(v["avg_us"], 2) for k, v in sorted(kernels.items())},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.cpu_sample_tokens)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,143 @@
+/* libpquant — the pQuant decoupled linear layer on MI355X (gfx950), C ABI.
+ *
+ * The layer (paper Sec. 3.1-3.3):
+ *     Y = beta * (lambda / gamma_t) * Sign(W - mu) * Q(x_t)  +  alpha * HP(x_t)
+ * with mu = mean(W), lambda = mean(|W|) per tensor, Q the per-token AbsMax INT8 quantiser
+ * (gamma_t = 128 / max_k |x_tk|, round half to even, clamp to [-128, 127]), alpha/beta the
+ * learnable feature scales, and HP a compact 16-bit branch: absent, one low-rank pair B(Ax), or
+ * E routed experts selected by a linear softmax router with top-k gating.
+ *
+ * Conventions for every call
+ *   - Every pointer is a DEVICE pointer owned by the caller unless marked "host".  The library
+ *     never allocates, frees or keeps a pointer after the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued on
+ *     it and the call returns without waiting.
+ *   - Matrices are row-major.  W is [d_out][d_in] (Y = W x).  16-bit tensors are bfloat16.
+ *   - Device buffers must be 16-byte aligned; d_in must be a multiple of 32; the training calls
+ *     also need d_out % 32 == 0 and hp_rank % 8 == 0.
+ *   - Return value: PQ_OK (0) or a negative pq_status.  Nothing throws or aborts;
+ *     pq_last_error_string() gives the calling thread's last message.  Arguments are validated on
+ *     the host before any kernel is launched, so a failed call has enqueued nothing.
+ */
+#ifndef PQUANT_H
+#define PQUANT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum pq_status {
+  PQ_OK = 0,
+  PQ_ERR_BAD_ARG = -1,   /* NULL where a buffer is required, negative size, unknown enum */
+  PQ_ERR_SHAPE = -2,     /* alignment / divisibility rule violated */
+  PQ_ERR_DTYPE = -3,     /* dtype not supported by this call */
+  PQ_ERR_WORKSPACE = -4, /* ctx or workspace smaller than pq_*_bytes() says */
+  PQ_ERR_HIP = -5        /* a HIP runtime call or kernel launch failed */
+} pq_status;
+
+typedef enum pq_dtype { PQ_F32 = 0, PQ_BF16 = 1 } pq_dtype;
+typedef enum pq_w_kind { PQ_W_MASTER = 0, PQ_W_PACKED = 1 } pq_w_kind;
+typedef enum pq_ste_mode { PQ_STE_IDENTITY = 0, PQ_STE_CLIP = 1 } pq_ste_mode;
+
+/* One decoupled linear.  Plain data, passed by pointer (host memory). */
+typedef struct pq_linear_desc {
+  int32_t tokens;    /* T */
+  int32_t d_in;      /* K, multiple of 32 */
+  int32_t d_out;     /* N */
+  int32_t hp_rank;   /* r per expert; 0 = pure 1-bit linear (the attention projections, Sec. 3.1) */
+  int32_t n_experts; /* E >= 1; E == 1 is the single dense branch of Sec. 3.2 (no router) */
+  int32_t top_k;     /* experts per token, 1 <= top_k <= E (Sec. 3.3 uses 1; Sec. 4.6 tries 2) */
+  int32_t io_dtype;  /* pq_dtype of X, Y, dY, dX, the hp weights and the router weights */
+  int32_t w_kind;    /* PQ_W_MASTER: latent W given, binarised in the call; PQ_W_PACKED: bits given */
+  int32_t ste_mode;  /* PQ_STE_IDENTITY (the paper's STE) or PQ_STE_CLIP: dW *= 1[|W - mu| <= tau] */
+  float ste_tau;
+  float alpha;       /* scale of the high-precision branch (Sec. 3.2) */
+  float beta;        /* scale of the 1-bit branch (Sec. 3.2) */
+} pq_linear_desc;
+
+int pq_version(void);
+const char* pq_last_error_string(void); /* host string, valid until the thread's next failing call */
+
+/* AbsMax INT8 activation quantiser (Sec. 3.1): per token t, gamma_t = 128 / max(max_k |x_tk|, 1e-5)
+ * (IEEE fp32 division), q = clamp(rne(fl32(x * gamma_t)), -128, 127).
+ *   X [T][K] of `dtype`; Xq [T][K] int8 out; gamma [T] fp32 out.  K % 32 == 0. */
+int pq_quant_act(const void* X, int32_t dtype, int32_t T, int32_t K, int8_t* Xq, float* gamma,
+                 void* stream);
+
+/* Weight statistics + binariser + packer (Sec. 3.1 eqs. for W^INT1, mu, lambda; App. A packing).
+ * mu and lambda are fp64 sums divided in fp64 and rounded once to fp32; bit = [W >= mu] (so W == mu
+ * maps to +1).  packed [N][K/32] uint32: bit j of word w <-> column 32 w + j, 1 <-> +1 (the same byte
+ * stream as 8 weights per byte, LSB first).  packed_t, if not NULL, receives the transposed packing
+ * [K][N/32] (bit j of word w <-> row 32 w + j; needs N % 32 == 0).  mu_lambda [2] fp32 out.
+ * workspace: at least pq_pack_workspace_bytes(N, K) bytes of scratch. */
+size_t pq_pack_workspace_bytes(int32_t N, int32_t K);
+int pq_pack_sign(const void* W, int32_t w_dtype, int32_t N, int32_t K, uint32_t* packed,
+                 uint32_t* packed_t, float* mu_lambda, void* workspace, size_t workspace_bytes,
+                 void* stream);
+
+/* Router (Sec. 3.3): logits = X Wr^T accumulated in fp64 and rounded once to fp32; the k largest
+ * logits per token in descending order, ties to the lower expert index; gate = softmax(logits)
+ * over all E experts at the selected indices (not renormalised).
+ *   X [T][K], Wr [E][K] of `dtype`; idx [T][k] int32, gate [T][k] fp32, probs [T][E] fp32 or NULL.
+ *   E <= 64. */
+int pq_router_topk(const void* X, const void* Wr, int32_t dtype, int32_t T, int32_t K, int32_t E,
+                   int32_t k, int32_t* idx, float* gate, float* probs, void* stream);
+
+/* Integer accumulator of the 1-bit branch, acc[t][n] = sum_k Xq[t][k] * S[n][k] with S read from
+ * packed bits (Sec. 3.1, the W1A8 product).  Exact int32.  For tests and tools; pq_linear_fwd
+ * runs the same kernel with the de-quantising epilogue.  acc [T][N] int32 out; N % 8 == 0. */
+int pq_onebit_acc(const int8_t* Xq, const uint32_t* packed, int32_t T, int32_t K, int32_t N,
+                  int32_t* acc, void* stream);
+
+/* Sizes of the caller-owned buffers of pq_linear_fwd / pq_linear_bwd for a descriptor.
+ * ctx holds what forward saves for backward (packed bits in both orientations, mu/lambda, the
+ * quantised activations and gamma, the hp hidden state, routing decisions); workspace is scratch
+ * whose contents need not survive between calls.  Both sizes cover forward and backward. */
+size_t pq_linear_ctx_bytes(const pq_linear_desc* desc);
+size_t pq_linear_workspace_bytes(const pq_linear_desc* desc);
+
+/* Forward of the decoupled linear (Sec. 3.1 last eq., Sec. 3.2 FFN eq., Sec. 3.3).
+ *   X [T][K] io_dtype.
+ *   W_or_packed: PQ_W_MASTER -> latent W [N][K] io_dtype; PQ_W_PACKED -> uint32 [N][K/32].
+ *   mu_lambda [2] fp32: read when PQ_W_PACKED; ignored (may be NULL) when PQ_W_MASTER, where the
+ *     statistics are computed and stored in ctx.
+ *   hpA: E == 1: [r][K]; E > 1: [E][r][K].   hpB: E == 1: [N][r]; E > 1: [E][N][r].  io_dtype.
+ *   Wr [E][K] io_dtype, only for E > 1.  All three NULL when hp_rank == 0.
+ *   Y [T][N] io_dtype out.
+ *   ctx: pq_linear_ctx_bytes() bytes, or NULL for inference (nothing saved; no backward).
+ *   workspace: pq_linear_workspace_bytes() bytes. */
+int pq_linear_fwd(const pq_linear_desc* desc, const void* X, const void* W_or_packed,
+                  const float* mu_lambda, const void* hpA, const void* hpB, const void* Wr, void* Y,
+                  void* ctx, size_t ctx_bytes, void* workspace, size_t workspace_bytes, void* stream);
+
+/* STE backward (Sec. 4 intro, App. B.1): Sign and Q are differentiated as identity; mu, lambda and
+ * gamma carry no gradient.
+ *   dY [T][N] io_dtype; X, W, hpA, hpB, Wr as given to forward; ctx as written by forward.
+ *   dX [T][K] io_dtype out.  dW [N][K] fp32 out (gradient of the latent weight).
+ *   dhpA, dhpB, dWr: fp32 out, shaped like hpA, hpB, Wr (NULL when that input is absent).
+ *   dalpha_dbeta [2] fp32 out: {dL/dalpha, dL/dbeta}.
+ * Reductions are two-stage with a fixed order: results are bit-identical from run to run. */
+int pq_linear_bwd(const pq_linear_desc* desc, const void* dY, const void* X, const void* W,
+                  const void* hpA, const void* hpB, const void* Wr, const void* ctx, size_t ctx_bytes,
+                  void* dX, float* dW, float* dhpA, float* dhpB, float* dWr, float* dalpha_dbeta,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* Per-kernel timing for benchmarks.  While enabled, every kernel launch made by the library is
+ * bracketed by a pair of HIP events on the caller's stream (events are created on demand, so this
+ * mode allocates; it is off by default).  pq_prof_count() = number of kernel labels;
+ * pq_prof_label(i) = host string naming label i; pq_prof_read(i, &ms, &launches) waits for the
+ * recorded events of label i and returns their summed duration in milliseconds and their count;
+ * pq_prof_reset() drops all recorded samples. */
+int pq_prof_enable(int on);
+int pq_prof_count(void);
+const char* pq_prof_label(int label);
+int pq_prof_read(int label, double* total_ms, int* launches);
+int pq_prof_reset(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PQUANT_H */

@@ -1,0 +1,171 @@
+"""Thin ctypes binding over libpquant.so: argument marshalling only.
+
+Every computation runs in the HIP kernels behind the C ABI (include/pquant.h).  PyTorch is used for
+device memory and the current stream.  There is no CPU fallback: if the library has not been
+built, the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpquant.so")
+
+PQ_F32, PQ_BF16 = 0, 1
+PQ_W_MASTER, PQ_W_PACKED = 0, 1
+PQ_STE_IDENTITY, PQ_STE_CLIP = 0, 1
+
+EXPORTS = [
+    "pq_version", "pq_last_error_string", "pq_quant_act", "pq_pack_workspace_bytes", "pq_pack_sign",
+    "pq_router_topk", "pq_onebit_acc", "pq_linear_ctx_bytes", "pq_linear_workspace_bytes",
+    "pq_linear_fwd", "pq_linear_bwd", "pq_prof_enable", "pq_prof_count", "pq_prof_label", "pq_prof_read",
+    "pq_prof_reset",
+]
+
+
+class LinearDesc(C.Structure):
+    _fields_ = [("tokens", C.c_int32), ("d_in", C.c_int32), ("d_out", C.c_int32), ("hp_rank", C.c_int32),
+                ("n_experts", C.c_int32), ("top_k", C.c_int32), ("io_dtype", C.c_int32), ("w_kind", C.c_int32),
+                ("ste_mode", C.c_int32), ("ste_tau", C.c_float), ("alpha", C.c_float), ("beta", C.c_float)]
+
+
+class PQError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_22592_amd.build` "
+                               "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        L.pq_last_error_string.restype = C.c_char_p
+        L.pq_prof_label.restype = C.c_char_p
+        for name in ("pq_pack_workspace_bytes", "pq_linear_ctx_bytes", "pq_linear_workspace_bytes"):
+            getattr(L, name).restype = C.c_size_t
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise PQError(f"libpquant error {rc}: {lib().pq_last_error_string().decode()}")
+
+
+def _p(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dt(t):
+    if t.dtype == torch.float32:
+        return PQ_F32
+    if t.dtype == torch.bfloat16:
+        return PQ_BF16
+    raise PQError(f"unsupported dtype {t.dtype}")
+
+
+def _bytes(n, device):
+    return torch.empty(max(int(n), 256), dtype=torch.uint8, device=device)
+
+
+def version():
+    return lib().pq_version()
+
+
+def quant_act(X):
+    T, K = X.shape
+    Xq = torch.empty((T, K), dtype=torch.int8, device=X.device)
+    gamma = torch.empty((T,), dtype=torch.float32, device=X.device)
+    _check(lib().pq_quant_act(_p(X), _dt(X), T, K, _p(Xq), _p(gamma), _stream()))
+    return Xq, gamma
+
+
+def pack_sign(W, transposed=False):
+    N, K = W.shape
+    P = torch.empty((N, K // 32), dtype=torch.int32, device=W.device)
+    Pt = torch.empty((K, N // 32), dtype=torch.int32, device=W.device) if transposed else None
+    ml = torch.empty((2,), dtype=torch.float32, device=W.device)
+    nws = lib().pq_pack_workspace_bytes(N, K)
+    ws = _bytes(nws, W.device)
+    _check(lib().pq_pack_sign(_p(W), _dt(W), N, K, _p(P), _p(Pt), _p(ml), _p(ws), C.c_size_t(ws.numel()), _stream()))
+    return P, Pt, ml
+
+
+def router_topk(X, Wr, k, want_probs=True):
+    T, K = X.shape
+    E = Wr.shape[0]
+    idx = torch.empty((T, k), dtype=torch.int32, device=X.device)
+    gate = torch.empty((T, k), dtype=torch.float32, device=X.device)
+    probs = torch.empty((T, E), dtype=torch.float32, device=X.device) if want_probs else None
+    _check(lib().pq_router_topk(_p(X), _p(Wr), _dt(X), T, K, E, k, _p(idx), _p(gate), _p(probs), _stream()))
+    return idx, gate, probs
+
+
+def onebit_acc(Xq, P, N):
+    T, K = Xq.shape
+    acc = torch.empty((T, N), dtype=torch.int32, device=Xq.device)
+    _check(lib().pq_onebit_acc(_p(Xq), _p(P), T, K, N, _p(acc), _stream()))
+    return acc
+
+
+def make_desc(tokens, d_in, d_out, hp_rank=0, n_experts=1, top_k=1, io_dtype=PQ_BF16, w_kind=PQ_W_MASTER,
+              ste_mode=PQ_STE_IDENTITY, ste_tau=0.0, alpha=2.0, beta=0.2):
+    return LinearDesc(tokens, d_in, d_out, hp_rank, n_experts, top_k, io_dtype, w_kind, ste_mode, ste_tau,
+                      alpha, beta)
+
+
+class LinearBuffers:
+    """Caller-owned ctx / workspace for one descriptor (allocated once, reused across steps)."""
+
+    def __init__(self, desc, device="cuda"):
+        nctx = lib().pq_linear_ctx_bytes(C.byref(desc))
+        nws = lib().pq_linear_workspace_bytes(C.byref(desc))
+        if nctx == 0 or nws == 0:
+            raise PQError(f"bad descriptor: {lib().pq_last_error_string().decode()}")
+        self.ctx = _bytes(nctx, device)
+        self.ws = _bytes(nws, device)
+
+
+def linear_fwd(desc, X, W, Y, bufs, A=None, B=None, Wr=None, mu_lambda=None, save=True):
+    ctx = bufs.ctx if save else None
+    _check(lib().pq_linear_fwd(C.byref(desc), _p(X), _p(W), _p(mu_lambda), _p(A), _p(B), _p(Wr), _p(Y),
+                               _p(ctx), C.c_size_t(0 if ctx is None else ctx.numel()),
+                               _p(bufs.ws), C.c_size_t(bufs.ws.numel()), _stream()))
+    return Y
+
+
+def linear_bwd(desc, dY, X, W, bufs, dX, dW, d_ab, A=None, B=None, Wr=None, dA=None, dB=None, dWr=None):
+    _check(lib().pq_linear_bwd(C.byref(desc), _p(dY), _p(X), _p(W), _p(A), _p(B), _p(Wr),
+                               _p(bufs.ctx), C.c_size_t(bufs.ctx.numel()), _p(dX), _p(dW), _p(dA), _p(dB),
+                               _p(dWr), _p(d_ab), _p(bufs.ws), C.c_size_t(bufs.ws.numel()), _stream()))
+    return dX, dW, d_ab
+
+
+def prof_enable(on=True):
+    _check(lib().pq_prof_enable(1 if on else 0))
+
+
+def prof_reset():
+    _check(lib().pq_prof_reset())
+
+
+def prof_read():
+    """{label: (total_ms, launches)} for every kernel label with at least one recorded launch."""
+    out = {}
+    for i in range(lib().pq_prof_count()):
+        ms, n = C.c_double(0), C.c_int(0)
+        _check(lib().pq_prof_read(i, C.byref(ms), C.byref(n)))
+        if n.value:
+            out[lib().pq_prof_label(i).decode()] = (ms.value, n.value)
+    return out

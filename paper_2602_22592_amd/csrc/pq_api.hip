@@ -1,0 +1,402 @@
+// C-ABI entry points of libpquant: argument validation, buffer layout, kernel sequencing.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+#include "pq_internal.h"
+
+static thread_local char g_err[512] = "";
+
+int pq_set_error(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+extern "C" const char* pq_last_error_string(void) { return g_err; }
+extern "C" int pq_version(void) { return 100; }
+
+// ---------------------------------------------------------------------------------------------
+// Optional per-kernel event timing
+// ---------------------------------------------------------------------------------------------
+#include <mutex>
+#include <vector>
+namespace {
+struct prof_sample { hipEvent_t a, b; int label; bool closed; };
+bool g_prof_on = false;
+std::mutex g_prof_mu;
+std::vector<prof_sample*> g_prof_samples;
+const char* const g_prof_names[PQP_COUNT] = {
+    "quant_act", "wstats_partial", "pack_sign", "router", "reduce_partials",
+    "gemm_onebit_fwd", "gemm_hp_H", "gemm_hp_Y", "gemm_dH", "gemm_dX", "gemm_dX_hp",
+    "gemm_dW", "gemm_dB", "gemm_dA", "gemm_other"};
+}  // namespace
+
+pq_prof_scope::pq_prof_scope(int label_, hipStream_t s_) : label(label_), s(s_), slot(nullptr) {
+  if (!g_prof_on) return;
+  prof_sample* ps = new prof_sample{nullptr, nullptr, label_, false};
+  if (hipEventCreate(&ps->a) != hipSuccess || hipEventCreate(&ps->b) != hipSuccess) { delete ps; return; }
+  hipEventRecord(ps->a, s);
+  slot = ps;
+}
+pq_prof_scope::~pq_prof_scope() {
+  if (!slot) return;
+  prof_sample* ps = (prof_sample*)slot;
+  hipEventRecord(ps->b, s);
+  ps->closed = true;
+  std::lock_guard<std::mutex> g(g_prof_mu);
+  g_prof_samples.push_back(ps);
+}
+
+extern "C" int pq_prof_enable(int on) { g_prof_on = on != 0; return PQ_OK; }
+extern "C" int pq_prof_count(void) { return PQP_COUNT; }
+extern "C" const char* pq_prof_label(int label) { return (label >= 0 && label < PQP_COUNT) ? g_prof_names[label] : ""; }
+extern "C" int pq_prof_read(int label, double* total_ms, int* launches) {
+  if (!total_ms || !launches) return pq_set_error(PQ_ERR_BAD_ARG, "NULL output");
+  std::lock_guard<std::mutex> g(g_prof_mu);
+  double tot = 0.0; int n = 0;
+  for (prof_sample* ps : g_prof_samples) {
+    if (ps->label != label || !ps->closed) continue;
+    float ms = 0.f;
+    PQ_CHECK_HIP(hipEventSynchronize(ps->b));
+    PQ_CHECK_HIP(hipEventElapsedTime(&ms, ps->a, ps->b));
+    tot += ms; ++n;
+  }
+  *total_ms = tot; *launches = n;
+  return PQ_OK;
+}
+extern "C" int pq_prof_reset(void) {
+  std::lock_guard<std::mutex> g(g_prof_mu);
+  for (prof_sample* ps : g_prof_samples) { hipEventDestroy(ps->a); hipEventDestroy(ps->b); delete ps; }
+  g_prof_samples.clear();
+  return PQ_OK;
+}
+
+namespace {
+
+inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+inline size_t esize(int dtype) { return dtype == PQ_BF16 ? 2 : 4; }
+inline int out_kind_of(int dtype) { return dtype == PQ_BF16 ? PQ_OUT_BF16 : PQ_OUT_F32; }
+
+#define PQ_REQUIRE(cond, code, ...) \
+  do { if (!(cond)) return pq_set_error(code, __VA_ARGS__); } while (0)
+
+int check_dtype(int dtype) {
+  PQ_REQUIRE(dtype == PQ_F32 || dtype == PQ_BF16, PQ_ERR_DTYPE, "dtype %d is not PQ_F32 or PQ_BF16", dtype);
+  return PQ_OK;
+}
+
+pq_epilogue epi_zero() {
+  pq_epilogue e;
+  memset(&e, 0, sizeof(e));
+  e.scale = 1.0f;
+  return e;
+}
+
+// Buffer layout of one linear.  Sections are 256-byte aligned.
+struct lin_layout {
+  // ctx (saved by forward for backward)
+  size_t mulam, P, Pt, Xq, gamma, Xt, H, ctx_total;
+  // workspace (scratch)
+  size_t stat_partials, red_a, red_b, dH, w_Xq, w_gamma, w_H, ws_total;
+  int n_red_a, n_red_b;
+};
+
+struct cursor {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    size_t o = off;
+    off = pq_align_up(off + bytes, 256);
+    return o;
+  }
+};
+
+lin_layout make_layout(const pq_linear_desc& d) {
+  lin_layout L;
+  memset(&L, 0, sizeof(L));
+  const size_t T = d.tokens, K = d.d_in, N = d.d_out, r = d.hp_rank, es = esize(d.io_dtype);
+  const int engine = d.io_dtype == PQ_BF16 ? 0 : 1;
+  cursor c;
+  L.mulam = c.take(2 * sizeof(float));
+  L.P = c.take(N * K / 8);
+  L.Pt = c.take(N * K / 8);
+  L.Xq = c.take(T * K);
+  L.gamma = c.take(T * sizeof(float));
+  L.Xt = c.take(d.io_dtype == PQ_BF16 ? T * K * 2 : 0);
+  L.H = c.take(T * r * es);
+  L.ctx_total = c.off > 0 ? c.off : 256;
+  cursor w;
+  L.stat_partials = w.take(2 * sizeof(double) * 1024);
+  L.n_red_a = r ? pq_gemm_blocks(engine, (int)T, (int)r) : 0;
+  L.n_red_b = pq_gemm_blocks(engine, (int)N, (int)K);
+  L.red_a = w.take(sizeof(double) * (size_t)(L.n_red_a > 0 ? L.n_red_a : 1));
+  L.red_b = w.take(sizeof(double) * (size_t)L.n_red_b);
+  L.dH = w.take(T * r * es);
+  L.w_Xq = w.take(T * K);          // used when forward runs without a ctx (inference)
+  L.w_gamma = w.take(T * sizeof(float));
+  L.w_H = w.take(T * r * es);
+  L.ws_total = w.off;
+  return L;
+}
+
+int check_desc(const pq_linear_desc* d, bool training) {
+  PQ_REQUIRE(d != nullptr, PQ_ERR_BAD_ARG, "desc is NULL");
+  PQ_REQUIRE(d->tokens >= 0 && d->d_in > 0 && d->d_out > 0 && d->hp_rank >= 0, PQ_ERR_BAD_ARG,
+             "negative or zero dimension (tokens=%d d_in=%d d_out=%d hp_rank=%d)", d->tokens, d->d_in,
+             d->d_out, d->hp_rank);
+  if (int e = check_dtype(d->io_dtype)) return e;
+  PQ_REQUIRE(d->w_kind == PQ_W_MASTER || d->w_kind == PQ_W_PACKED, PQ_ERR_BAD_ARG, "unknown w_kind %d", d->w_kind);
+  PQ_REQUIRE(d->ste_mode == PQ_STE_IDENTITY || d->ste_mode == PQ_STE_CLIP, PQ_ERR_BAD_ARG, "unknown ste_mode %d", d->ste_mode);
+  PQ_REQUIRE(d->d_in % 32 == 0, PQ_ERR_SHAPE, "d_in=%d must be a multiple of 32", d->d_in);
+  PQ_REQUIRE(d->d_out % 8 == 0, PQ_ERR_SHAPE, "d_out=%d must be a multiple of 8", d->d_out);
+  PQ_REQUIRE(d->hp_rank % 8 == 0, PQ_ERR_SHAPE, "hp_rank=%d must be a multiple of 8", d->hp_rank);
+  PQ_REQUIRE(d->n_experts >= 1 && d->n_experts <= 64, PQ_ERR_BAD_ARG, "n_experts=%d must be in 1..64", d->n_experts);
+  PQ_REQUIRE(d->top_k >= 1 && d->top_k <= d->n_experts, PQ_ERR_BAD_ARG, "top_k=%d must be in 1..n_experts", d->top_k);
+  if (training) {
+    PQ_REQUIRE(d->d_out % 32 == 0, PQ_ERR_SHAPE, "training needs d_out=%d to be a multiple of 32", d->d_out);
+    PQ_REQUIRE(d->w_kind == PQ_W_MASTER, PQ_ERR_BAD_ARG, "backward needs latent weights (PQ_W_MASTER)");
+  }
+  PQ_REQUIRE(d->n_experts == 1 || d->hp_rank == 0, PQ_ERR_BAD_ARG,
+             "routed experts inside pq_linear_* are not available in this build (n_experts=%d)", d->n_experts);
+  return PQ_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+extern "C" int pq_quant_act(const void* X, int32_t dtype, int32_t T, int32_t K, int8_t* Xq, float* gamma,
+                            void* stream) {
+  if (int e = check_dtype(dtype)) return e;
+  PQ_REQUIRE(T >= 0 && K > 0, PQ_ERR_BAD_ARG, "bad size T=%d K=%d", T, K);
+  PQ_REQUIRE(K % 32 == 0, PQ_ERR_SHAPE, "K=%d must be a multiple of 32", K);
+  if (T == 0) return PQ_OK;
+  PQ_REQUIRE(X && Xq && gamma, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(aligned16(X) && aligned16(Xq), PQ_ERR_SHAPE, "X and Xq must be 16-byte aligned");
+  return pq_launch_quant_act(X, dtype, T, K, Xq, gamma, nullptr, (hipStream_t)stream);
+}
+
+extern "C" size_t pq_pack_workspace_bytes(int32_t N, int32_t K) {
+  (void)N; (void)K;
+  return 2 * sizeof(double) * 1024;
+}
+
+extern "C" int pq_pack_sign(const void* W, int32_t w_dtype, int32_t N, int32_t K, uint32_t* packed,
+                            uint32_t* packed_t, float* mu_lambda, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+  if (int e = check_dtype(w_dtype)) return e;
+  PQ_REQUIRE(N > 0 && K > 0, PQ_ERR_BAD_ARG, "bad size N=%d K=%d", N, K);
+  PQ_REQUIRE(K % 32 == 0, PQ_ERR_SHAPE, "K=%d must be a multiple of 32", K);
+  PQ_REQUIRE(packed_t == nullptr || N % 32 == 0, PQ_ERR_SHAPE, "transposed packing needs N=%d %% 32 == 0", N);
+  PQ_REQUIRE(W && packed && mu_lambda && workspace, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(aligned16(W) && aligned16(workspace), PQ_ERR_SHAPE, "W and workspace must be 16-byte aligned");
+  PQ_REQUIRE(workspace_bytes >= pq_pack_workspace_bytes(N, K), PQ_ERR_WORKSPACE, "workspace too small: %zu < %zu",
+             workspace_bytes, pq_pack_workspace_bytes(N, K));
+  hipStream_t s = (hipStream_t)stream;
+  const size_t n = (size_t)N * K;
+  const int nb = pq_stats_blocks(n);
+  if (int e = pq_launch_wstats_partial(W, w_dtype, n, (double*)workspace, nb, s)) return e;
+  return pq_launch_pack(W, w_dtype, N, K, (const double*)workspace, nb, packed, packed_t, mu_lambda, s);
+}
+
+extern "C" int pq_router_topk(const void* X, const void* Wr, int32_t dtype, int32_t T, int32_t K, int32_t E,
+                              int32_t k, int32_t* idx, float* gate, float* probs, void* stream) {
+  if (int e = check_dtype(dtype)) return e;
+  PQ_REQUIRE(T >= 0 && K > 0, PQ_ERR_BAD_ARG, "bad size T=%d K=%d", T, K);
+  PQ_REQUIRE(E >= 1 && E <= 64, PQ_ERR_BAD_ARG, "E=%d must be in 1..64", E);
+  PQ_REQUIRE(k >= 1 && k <= E, PQ_ERR_BAD_ARG, "k=%d must be in 1..E", k);
+  PQ_REQUIRE(K % 8 == 0, PQ_ERR_SHAPE, "K=%d must be a multiple of 8", K);
+  if (T == 0) return PQ_OK;
+  PQ_REQUIRE(X && Wr && idx && gate, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(aligned16(X) && aligned16(Wr), PQ_ERR_SHAPE, "X and Wr must be 16-byte aligned");
+  return pq_launch_router(X, Wr, dtype, T, K, E, k, idx, gate, probs, (hipStream_t)stream);
+}
+
+extern "C" int pq_onebit_acc(const int8_t* Xq, const uint32_t* packed, int32_t T, int32_t K, int32_t N,
+                             int32_t* acc, void* stream) {
+  PQ_REQUIRE(T >= 0 && K > 0 && N > 0, PQ_ERR_BAD_ARG, "bad size T=%d K=%d N=%d", T, K, N);
+  PQ_REQUIRE(K % 32 == 0, PQ_ERR_SHAPE, "K=%d must be a multiple of 32", K);
+  if (T == 0) return PQ_OK;
+  PQ_REQUIRE(Xq && packed && acc, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(N % 8 == 0 && aligned16(acc), PQ_ERR_SHAPE, "N=%d must be a multiple of 8 and acc 16-byte aligned", N);
+  PQ_REQUIRE(aligned16(Xq) && aligned16(packed), PQ_ERR_SHAPE, "Xq and packed must be 16-byte aligned");
+  pq_operand A{Xq, K, PQ_SRC_KC8, nullptr};
+  pq_operand B{packed, K / 8, PQ_SRC_BITS8, nullptr};
+  pq_epilogue e = epi_zero();
+  e.C = acc; e.ldc = N; e.out_kind = PQ_OUT_I32;
+  return pq_launch_gemm(0, T, N, K, A, B, e, (hipStream_t)stream);
+}
+
+extern "C" size_t pq_linear_ctx_bytes(const pq_linear_desc* d) {
+  if (check_desc(d, false) != PQ_OK) return 0;
+  return make_layout(*d).ctx_total;
+}
+
+extern "C" size_t pq_linear_workspace_bytes(const pq_linear_desc* d) {
+  if (check_desc(d, false) != PQ_OK) return 0;
+  return make_layout(*d).ws_total;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Forward: [stats -> pack] -> quantise -> int8 MFMA GEMM with de-quantising epilogue -> hp branch
+// ---------------------------------------------------------------------------------------------
+extern "C" int pq_linear_fwd(const pq_linear_desc* d, const void* X, const void* W_or_packed,
+                             const float* mu_lambda, const void* hpA, const void* hpB, const void* Wr, void* Y,
+                             void* ctx, size_t ctx_bytes, void* workspace, size_t workspace_bytes, void* stream) {
+  (void)Wr;
+  if (int e = check_desc(d, false)) return e;
+  const lin_layout L = make_layout(*d);
+  const int T = d->tokens, K = d->d_in, N = d->d_out, r = d->hp_rank;
+  PQ_REQUIRE(X && W_or_packed && Y && workspace, PQ_ERR_BAD_ARG, "NULL buffer (X, W, Y or workspace)");
+  PQ_REQUIRE(r == 0 || (hpA && hpB), PQ_ERR_BAD_ARG, "hp_rank=%d but hpA/hpB is NULL", r);
+  PQ_REQUIRE(d->w_kind == PQ_W_MASTER || mu_lambda, PQ_ERR_BAD_ARG, "packed weights need mu_lambda");
+  PQ_REQUIRE(d->w_kind == PQ_W_PACKED || ctx, PQ_ERR_BAD_ARG, "latent weights need a ctx to hold the packed bits");
+  PQ_REQUIRE(aligned16(X) && aligned16(W_or_packed) && aligned16(Y) && aligned16(workspace) && aligned16(ctx) &&
+                 aligned16(hpA) && aligned16(hpB), PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
+  PQ_REQUIRE(workspace_bytes >= L.ws_total, PQ_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, L.ws_total);
+  PQ_REQUIRE(!ctx || ctx_bytes >= L.ctx_total, PQ_ERR_WORKSPACE, "ctx too small: %zu < %zu", ctx_bytes, L.ctx_total);
+  hipStream_t s = (hipStream_t)stream;
+  char* cx = (char*)ctx;
+  char* ws = (char*)workspace;
+  const bool bf16 = d->io_dtype == PQ_BF16;
+  const int engine = bf16 ? 0 : 1;
+  const int ok = out_kind_of(d->io_dtype);
+
+  const uint32_t* P;
+  const float* mulam;
+  if (d->w_kind == PQ_W_MASTER) {
+    const size_t n = (size_t)N * K;
+    const int nb = pq_stats_blocks(n);
+    double* part = (double*)(ws + L.stat_partials);
+    if (int e = pq_launch_wstats_partial(W_or_packed, d->io_dtype, n, part, nb, s)) return e;
+    uint32_t* Pt = (N % 32 == 0) ? (uint32_t*)(cx + L.Pt) : nullptr;
+    if (int e = pq_launch_pack(W_or_packed, d->io_dtype, N, K, part, nb, (uint32_t*)(cx + L.P), Pt,
+                               (float*)(cx + L.mulam), s)) return e;
+    P = (const uint32_t*)(cx + L.P);
+    mulam = (const float*)(cx + L.mulam);
+  } else {
+    P = (const uint32_t*)W_or_packed;
+    mulam = mu_lambda;
+  }
+  if (T == 0) return PQ_OK;   // the weight side is still prepared, so a backward with no tokens is well defined
+
+  int8_t* Xq = (int8_t*)(ctx ? cx + L.Xq : ws + L.w_Xq);
+  float* gamma = (float*)(ctx ? cx + L.gamma : ws + L.w_gamma);
+  uint16_t* Xt = (ctx && bf16) ? (uint16_t*)(cx + L.Xt) : nullptr;
+  if (int e = pq_launch_quant_act(X, d->io_dtype, T, K, Xq, gamma, Xt, s)) return e;
+
+  {  // 1-bit branch: Y = fl32(fl32(beta*lambda)/gamma_t) * acc
+    pq_operand A{Xq, K, PQ_SRC_KC8, nullptr};
+    pq_operand B{P, K / 8, PQ_SRC_BITS8, nullptr};
+    pq_epilogue e = epi_zero();
+    e.C = Y; e.ldc = N; e.out_kind = ok;
+    e.scale = d->beta; e.dev_scale = mulam + 1; e.row_div = gamma;
+    if (int err = pq_launch_gemm(0, T, N, K, A, B, e, s, PQP_GEMM_ONEBIT)) return err;
+  }
+  if (r > 0) {
+    void* H = ctx ? (void*)(cx + L.H) : (void*)(ws + L.w_H);
+    {  // H = X A^T
+      pq_operand A{X, K, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
+      pq_operand B{hpA, K, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
+      pq_epilogue e = epi_zero();
+      e.C = H; e.ldc = r; e.out_kind = ok;
+      if (int err = pq_launch_gemm(engine, T, r, K, A, B, e, s, PQP_GEMM_HP_H)) return err;
+    }
+    {  // Y += alpha * H B^T
+      pq_operand A{H, r, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
+      pq_operand B{hpB, r, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
+      pq_epilogue e = epi_zero();
+      e.C = Y; e.ldc = N; e.out_kind = ok; e.accumulate = 1; e.scale = d->alpha;
+      if (int err = pq_launch_gemm(engine, T, N, r, A, B, e, s, PQP_GEMM_HP_Y)) return err;
+    }
+  }
+  return PQ_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// STE backward
+// ---------------------------------------------------------------------------------------------
+extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void* X, const void* W,
+                             const void* hpA, const void* hpB, const void* Wr, const void* ctx, size_t ctx_bytes,
+                             void* dX, float* dW, float* dhpA, float* dhpB, float* dWr, float* dalpha_dbeta,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+  (void)Wr; (void)dWr;
+  if (int e = check_desc(d, true)) return e;
+  const lin_layout L = make_layout(*d);
+  const int T = d->tokens, K = d->d_in, N = d->d_out, r = d->hp_rank;
+  PQ_REQUIRE(dY && X && ctx && dX && dW && dalpha_dbeta && workspace, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(r == 0 || (hpA && hpB && dhpA && dhpB), PQ_ERR_BAD_ARG, "hp_rank=%d but an hp buffer is NULL", r);
+  PQ_REQUIRE(d->ste_mode == PQ_STE_IDENTITY || W, PQ_ERR_BAD_ARG, "PQ_STE_CLIP needs the latent W");
+  PQ_REQUIRE(aligned16(dY) && aligned16(X) && aligned16(ctx) && aligned16(dX) && aligned16(dW) && aligned16(workspace) &&
+                 aligned16(hpA) && aligned16(hpB) && aligned16(W), PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
+  PQ_REQUIRE(workspace_bytes >= L.ws_total, PQ_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, L.ws_total);
+  PQ_REQUIRE(ctx_bytes >= L.ctx_total, PQ_ERR_WORKSPACE, "ctx too small: %zu < %zu", ctx_bytes, L.ctx_total);
+  hipStream_t s = (hipStream_t)stream;
+  const char* cx = (const char*)ctx;
+  char* ws = (char*)workspace;
+  const bool bf16 = d->io_dtype == PQ_BF16;
+  const int engine = bf16 ? 0 : 1;
+  const int ok = out_kind_of(d->io_dtype);
+  const int KC = bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, KS = bf16 ? PQ_SRC_KS16 : PQ_SRC_KS32;
+  const float* mulam = (const float*)(cx + L.mulam);
+  const float* gamma = (const float*)(cx + L.gamma);
+  const void* H = cx + L.H;
+  void* dH = ws + L.dH;
+  double* red_a = (double*)(ws + L.red_a);
+  double* red_b = (double*)(ws + L.red_b);
+
+  if (T > 0 && r > 0) {  // dH = alpha * dY B ; d alpha = <H, dY B>
+    pq_operand A{dY, N, KC, nullptr};
+    pq_operand B{hpB, r, KS, nullptr};
+    pq_epilogue e = epi_zero();
+    e.C = dH; e.ldc = r; e.out_kind = ok; e.scale = d->alpha;
+    e.dot_comp = H; e.ld_comp = r; e.comp_kind = ok; e.partials = red_a;
+    if (int err = pq_launch_gemm(engine, T, r, N, A, B, e, s, PQP_GEMM_DH)) return err;
+  }
+  if (int err = pq_launch_reduce_partials(red_a, (T > 0 && r > 0) ? L.n_red_a : 0, 1.0f, nullptr, dalpha_dbeta, s)) return err;
+
+  if (T > 0) {  // dX = beta*lambda * dY S  (+ dH A)
+    pq_operand A{dY, N, KC, nullptr};
+    pq_operand B{cx + L.Pt, N / 8, bf16 ? PQ_SRC_BITS16 : PQ_SRC_BITSF, nullptr};
+    pq_epilogue e = epi_zero();
+    e.C = dX; e.ldc = K; e.out_kind = ok; e.scale = d->beta; e.dev_scale = mulam + 1;
+    if (int err = pq_launch_gemm(engine, T, K, N, A, B, e, s, PQP_GEMM_DX)) return err;
+    if (r > 0) {
+      pq_operand A2{dH, r, KC, nullptr};
+      pq_operand B2{hpA, K, KS, nullptr};
+      pq_epilogue e2 = epi_zero();
+      e2.C = dX; e2.ldc = K; e2.out_kind = ok; e2.accumulate = 1;
+      if (int err = pq_launch_gemm(engine, T, K, r, A2, B2, e2, s, PQP_GEMM_DX_HP)) return err;
+    }
+  }
+  {  // dW = beta * (dY/gamma)^T q  [masked];  d beta = lambda * sum S .* (dY/gamma)^T q
+    pq_operand A{dY, N, KS, nullptr};
+    pq_operand B = bf16 ? pq_operand{cx + L.Xt, K, PQ_SRC_KS16, nullptr}
+                        : pq_operand{cx + L.Xq, K, PQ_SRC_KS8, gamma};
+    pq_epilogue e = epi_zero();
+    e.C = dW; e.ldc = K; e.out_kind = PQ_OUT_F32; e.scale = d->beta;
+    e.sign_bytes = (const uint8_t*)(cx + L.P); e.ld_sign = K / 8; e.partials = red_b;
+    if (d->ste_mode == PQ_STE_CLIP) {
+      e.maskW = W; e.mask_kind = ok; e.mu_dev = mulam; e.tau = d->ste_tau;
+    }
+    if (int err = pq_launch_gemm(engine, N, K, T, A, B, e, s, PQP_GEMM_DW)) return err;
+    if (int err = pq_launch_reduce_partials(red_b, L.n_red_b, 1.0f, mulam + 1, dalpha_dbeta + 1, s)) return err;
+  }
+  if (r > 0) {
+    {  // dB = alpha * dY^T H
+      pq_operand A{dY, N, KS, nullptr};
+      pq_operand B{H, r, KS, nullptr};
+      pq_epilogue e = epi_zero();
+      e.C = dhpB; e.ldc = r; e.out_kind = PQ_OUT_F32; e.scale = d->alpha;
+      if (int err = pq_launch_gemm(engine, N, r, T, A, B, e, s, PQP_GEMM_DB)) return err;
+    }
+    {  // dA = dH^T X   (dH already carries alpha)
+      pq_operand A{dH, r, KS, nullptr};
+      pq_operand B{X, K, KS, nullptr};
+      pq_epilogue e = epi_zero();
+      e.C = dhpA; e.ldc = K; e.out_kind = PQ_OUT_F32;
+      if (int err = pq_launch_gemm(engine, r, K, T, A, B, e, s, PQP_GEMM_DA)) return err;
+    }
+  }
+  return PQ_OK;
+}

@@ -1,0 +1,86 @@
+// Internal launch interface between the C-ABI layer (pq_api.hip) and the kernel files.
+#pragma once
+#include "pq_common.h"
+
+// ---- profiling labels (pq_api.hip) ---------------------------------------------------------
+enum pq_prof_id {
+  PQP_QUANT = 0, PQP_WSTATS, PQP_PACK, PQP_ROUTER, PQP_REDUCE,
+  PQP_GEMM_ONEBIT, PQP_GEMM_HP_H, PQP_GEMM_HP_Y, PQP_GEMM_DH, PQP_GEMM_DX, PQP_GEMM_DX_HP,
+  PQP_GEMM_DW, PQP_GEMM_DB, PQP_GEMM_DA, PQP_GEMM_OTHER, PQP_COUNT
+};
+struct pq_prof_scope {   // records an event pair around the launches made while it is alive
+  int label; hipStream_t s; void* slot;
+  pq_prof_scope(int label, hipStream_t s);
+  ~pq_prof_scope();
+};
+
+// ---- pq_quant.hip -------------------------------------------------------------------------
+// Per-token AbsMax INT8 quantiser.  Xt (optional, bf16) receives q/gamma, the de-quantised
+// activation that the STE backward multiplies with.
+int pq_launch_quant_act(const void* X, int dtype, int T, int K, int8_t* Xq, float* gamma,
+                        uint16_t* Xt, hipStream_t s);
+// Weight statistics, stage 1: per-block fp64 partial sums {sum W, sum |W|}.
+int pq_stats_blocks(size_t n_elems);
+int pq_launch_wstats_partial(const void* W, int dtype, size_t n_elems, double* partials, int nblocks,
+                             hipStream_t s);
+// Stage 2 + binarise + pack (both orientations).  Every block re-reduces the partials in the
+// same order, block 0 writes mu_lambda.
+int pq_launch_pack(const void* W, int dtype, int N, int K, const double* partials, int nblocks,
+                   uint32_t* P, uint32_t* Pt, float* mu_lambda, hipStream_t s);
+int pq_launch_router(const void* X, const void* Wr, int dtype, int T, int K, int E, int k, int* idx,
+                     float* gate, float* probs, hipStream_t s);
+// out[0] = factor * sum(partials[0..n)) (+ optionally factor2 read from device: *dev_factor)
+int pq_launch_reduce_partials(const double* partials, int n, float factor, const float* dev_factor,
+                              float* out, hipStream_t s);
+
+// ---- pq_gemm.hip --------------------------------------------------------------------------
+enum pq_src_kind {
+  PQ_SRC_KC16 = 0,   // bf16, contraction index contiguous: elem(row,k) = p[row*ld + k]
+  PQ_SRC_KS16 = 1,   // bf16, contraction index strided:   elem(row,k) = p[k*ld + row]
+  PQ_SRC_KC8 = 2,    // int8, contraction contiguous
+  PQ_SRC_BITS8 = 3,  // +/-1 as int8 from packed bits, ld = bytes per row
+  PQ_SRC_BITS16 = 4, // +/-1 as bf16 from packed bits, ld = bytes per row
+  // reference-precision engine only:
+  PQ_SRC_KC32 = 5,   // fp32, contraction contiguous
+  PQ_SRC_KS32 = 6,   // fp32, contraction strided
+  PQ_SRC_KS8 = 7,    // int8, contraction strided
+  PQ_SRC_BITSF = 8   // +/-1 from packed bits as a real number
+};
+
+struct pq_operand {
+  const void* p;
+  long ld;             // leading dimension in elements (bytes per row for the BITS kinds)
+  int kind;
+  const float* kdiv;   // optional: divide element by kdiv[k] (per contraction index); ref engine only
+};
+
+enum pq_out_kind { PQ_OUT_F32 = 0, PQ_OUT_BF16 = 1, PQ_OUT_I32 = 2 };
+
+struct pq_epilogue {
+  void* C;                    // [M][ldc]
+  long ldc;
+  int out_kind;
+  int accumulate;             // C = C + value
+  float scale;                // value = scale * acc, or (scale / row_div[m]) * acc
+  const float* dev_scale;     // optional device scalar multiplied into `scale` first (fp32 product)
+  const float* row_div;       // optional per-row divisor (gamma_t)
+  // optional fixed-order partial reductions, one double per block:
+  const void* dot_comp;       // sum_{m,n} comp[m][n] * acc   (comp of the io dtype)
+  long ld_comp;
+  int comp_kind;              // PQ_OUT_F32 / PQ_OUT_BF16
+  const uint8_t* sign_bytes;  // sum_{m,n} (+/-1 from bit n of packed row m) * acc
+  long ld_sign;               // bytes per packed row
+  double* partials;
+  // optional STE clipping mask on the stored value: keep iff |W[m][n] - mu| <= tau
+  const void* maskW;
+  int mask_kind;              // PQ_OUT_F32 / PQ_OUT_BF16
+  const float* mu_dev;        // device pointer to mu
+  float tau;
+};
+
+// C[M][N] (+)= epilogue( sum_k A(m,k) * B(n,k) ).  `engine` 0 = MFMA (bf16 or int8 operands),
+// 1 = reference precision (fp64 accumulate, any operand kind).  Returns the number of blocks
+// launched through *nblocks (= number of partial sums written when a reduction is requested).
+int pq_gemm_blocks(int engine, int M, int N);
+int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const pq_operand& B,
+                   const pq_epilogue& epi, hipStream_t s, int prof_label = PQP_GEMM_OTHER);
