@@ -20,6 +20,11 @@
 
 namespace {
 
+__device__ __forceinline__ uint4 mask4(const uint4& t, bool keep) {
+  const uint32_t m = keep ? 0xFFFFFFFFu : 0u;
+  return make_uint4(t.x & m, t.y & m, t.z & m, t.w & m);
+}
+
 __device__ __forceinline__ int lds_off(int r, int c) { return r * 128 + (((c ^ r ^ (r >> 3)) & 7) << 4); }
 
 // ---------------------------------------------------------------------------------------------
@@ -34,9 +39,12 @@ struct tile_stage {
   static constexpr int NU = (ROWS + NT - 1) / NT;  // 8x8 transpose units per thread (KS16)
   uint4 v[kBits ? 1 : (kStrided ? NU * 8 : NCH)];
   uint32_t raw[kBits ? NCH : 1];
+  uint32_t okbits;  // validity of each loaded chunk, applied when the tile is written to LDS
 
+  // Loads are unconditional (an out-of-range chunk reads element (0,0), which always exists, and is
+  // then replaced by zeros) so that all of a thread's loads are in flight together.
   __device__ __forceinline__ void load(const pq_operand& op, int row0, int rows, int k0, int K, int tid) {
-    const uint4 zero = make_uint4(0, 0, 0, 0);
+    okbits = 0u;
     if constexpr (kStrided) {
       const uint16_t* p = (const uint16_t*)op.p;
 #pragma unroll
@@ -44,11 +52,14 @@ struct tile_stage {
         const int u = tid + i * NT;
         const int r8 = u >> 3, k8 = u & 7;
         const int col = row0 + r8 * 8;
+        const bool okc = (u < ROWS) && (col < rows);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const int kk = k0 + k8 * 8 + j;
-          const bool ok = (u < ROWS) && (col < rows) && (kk < K);
-          v[i * 8 + j] = ok ? *reinterpret_cast<const uint4*>(p + (size_t)kk * op.ld + col) : zero;
+          const bool ok = okc && (kk < K);
+          const size_t off = ok ? (size_t)kk * op.ld + col : 0;
+          v[i * 8 + j] = *reinterpret_cast<const uint4*>(p + off);
+          okbits |= (ok ? 1u : 0u) << (i * 8 + j);
         }
       }
     } else {
@@ -59,13 +70,21 @@ struct tile_stage {
         const int grow = row0 + r, k = k0 + kc * EPC;
         const bool ok = (c < ROWS * 8) && (grow < rows) && (k < K);
         if constexpr (KIND == PQ_SRC_KC16) {
-          v[i] = ok ? *reinterpret_cast<const uint4*>((const uint16_t*)op.p + (size_t)grow * op.ld + k) : zero;
+          const size_t off = ok ? (size_t)grow * op.ld + k : 0;
+          v[i] = *reinterpret_cast<const uint4*>((const uint16_t*)op.p + off);
+          okbits |= (ok ? 1u : 0u) << i;
         } else if constexpr (KIND == PQ_SRC_KC8) {
-          v[i] = ok ? *reinterpret_cast<const uint4*>((const int8_t*)op.p + (size_t)grow * op.ld + k) : zero;
+          const size_t off = ok ? (size_t)grow * op.ld + k : 0;
+          v[i] = *reinterpret_cast<const uint4*>((const int8_t*)op.p + off);
+          okbits |= (ok ? 1u : 0u) << i;
         } else if constexpr (KIND == PQ_SRC_BITS8) {
-          raw[i] = ok ? (0x80000000u | *reinterpret_cast<const uint16_t*>((const uint8_t*)op.p + (size_t)grow * op.ld + (k >> 3))) : 0u;
+          const size_t off = ok ? (size_t)grow * op.ld + (k >> 3) : 0;
+          raw[i] = *reinterpret_cast<const uint16_t*>((const uint8_t*)op.p + off);
+          okbits |= (ok ? 1u : 0u) << i;
         } else {  // BITS16
-          raw[i] = ok ? (0x80000000u | ((const uint8_t*)op.p)[(size_t)grow * op.ld + (k >> 3)]) : 0u;
+          const size_t off = ok ? (size_t)grow * op.ld + (k >> 3) : 0;
+          raw[i] = ((const uint8_t*)op.p)[off];
+          okbits |= (ok ? 1u : 0u) << i;
         }
       }
     }
@@ -84,8 +103,8 @@ struct tile_stage {
             uint32_t o[4];
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-              const uint4& lo4 = v[i * 8 + 2 * p];
-              const uint4& hi4 = v[i * 8 + 2 * p + 1];
+              const uint4 lo4 = mask4(v[i * 8 + 2 * p], (okbits >> (i * 8 + 2 * p)) & 1u);
+              const uint4 hi4 = mask4(v[i * 8 + 2 * p + 1], (okbits >> (i * 8 + 2 * p + 1)) & 1u);
               const uint32_t lo = (rr >> 1) == 0 ? lo4.x : (rr >> 1) == 1 ? lo4.y : (rr >> 1) == 2 ? lo4.z : lo4.w;
               const uint32_t hi = (rr >> 1) == 0 ? hi4.x : (rr >> 1) == 1 ? hi4.y : (rr >> 1) == 2 ? hi4.z : hi4.w;
               // result bytes: [lo.half, hi.half]; v_perm selects bytes 0-3 from the 2nd operand, 4-7 from the 1st
@@ -114,7 +133,7 @@ struct tile_stage {
               const uint32_t m = __umul24(nib, 0x00204081u) & 0x01010101u;
               o[d] = __builtin_amdgcn_perm(0x000001FFu, 0x000001FFu, m);
             }
-            out = (b & 0x80000000u) ? make_uint4(o[0], o[1], o[2], o[3]) : make_uint4(0, 0, 0, 0);
+            out = mask4(make_uint4(o[0], o[1], o[2], o[3]), (okbits >> i) & 1u);
           } else if constexpr (KIND == PQ_SRC_BITS16) {
             // 8 bits -> 8 bf16 of +1 (0x3F80) / -1 (0xBF80)
             const uint32_t b = raw[i];
@@ -124,9 +143,9 @@ struct tile_stage {
               const uint32_t x = (b >> (2 * d)) & 3u;
               o[d] = 0xBF80BF80u ^ (((x & 1u) << 15) | ((x & 2u) << 30));
             }
-            out = (b & 0x80000000u) ? make_uint4(o[0], o[1], o[2], o[3]) : make_uint4(0, 0, 0, 0);
+            out = mask4(make_uint4(o[0], o[1], o[2], o[3]), (okbits >> i) & 1u);
           } else {
-            out = v[i];
+            out = mask4(v[i], (okbits >> i) & 1u);
           }
           *reinterpret_cast<uint4*>(lds + lds_off(r, kc)) = out;
         }
@@ -298,10 +317,12 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
   tile_stage<AK, BM, NT> sa;
   tile_stage<BKIND, BN, NT> sb;
   const int nkt = (K + EPB - 1) / EPB;
-  sa.load(A, m0, M, 0, K, tid);
-  sb.load(B, n0, N, 0, K, tid);
-  sa.store(As, tid);
-  sb.store(Bs, tid);
+  if (nkt > 0) {
+    sa.load(A, m0, M, 0, K, tid);
+    sb.load(B, n0, N, 0, K, tid);
+    sa.store(As, tid);
+    sb.store(Bs, tid);
+  }
   __syncthreads();
 
   for (int kt = 0; kt < nkt; ++kt) {
@@ -351,7 +372,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int rr = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        stg[rr * 36 + (lane & 31)] = __builtin_bit_cast(uint32_t, acc[i][j][v]);
+        const auto elem = acc[i][j][v];  // copy out first: a vector element is not a bit_cast-able lvalue
+        stg[rr * 36 + (lane & 31)] = __builtin_bit_cast(uint32_t, elem);
       }
       // wave-private patch: order this wave's LDS writes before its reads (other lanes' data)
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
