@@ -99,7 +99,7 @@ struct lin_layout {
   // ctx (saved by forward for backward)
   size_t mulam, P, Pt, Xq, gamma, Xt, H, ctx_total;
   // workspace (scratch)
-  size_t stat_partials, red_a, red_b, dH, w_Xq, w_gamma, w_H, ws_total;
+  size_t stat_partials, red_a, red_b, dH, w_Xq, w_gamma, w_H, splitk, ws_total;
   int n_red_a, n_red_b;
 };
 
@@ -128,14 +128,24 @@ lin_layout make_layout(const pq_linear_desc& d) {
   L.ctx_total = c.off > 0 ? c.off : 256;
   cursor w;
   L.stat_partials = w.take(2 * sizeof(double) * 1024);
-  L.n_red_a = r ? pq_gemm_blocks(engine, (int)T, (int)r) : 0;
-  L.n_red_b = pq_gemm_blocks(engine, (int)N, (int)K);
+  const int Ti = d.tokens, Ki = d.d_in, Ni = d.d_out, ri = d.hp_rank;
+  L.n_red_a = r ? pq_plan_gemm(engine, Ti, ri, Ni).red_blocks : 0;       // dH GEMM
+  L.n_red_b = pq_plan_gemm(engine, Ni, Ki, Ti).red_blocks;                // dW GEMM
+  size_t sk = 0;
+  const int shapes[8][3] = {{Ti, ri, Ki}, {Ti, Ni, ri}, {Ti, ri, Ni}, {Ti, Ki, Ni},
+                            {Ti, Ki, ri}, {Ni, Ki, Ti}, {Ni, ri, Ti}, {ri, Ki, Ti}};
+  for (const auto& sh : shapes) {
+    if (sh[0] <= 0 || sh[1] <= 0) continue;
+    const size_t b = pq_plan_gemm(engine, sh[0], sh[1], sh[2]).ws_bytes;
+    if (b > sk) sk = b;
+  }
   L.red_a = w.take(sizeof(double) * (size_t)(L.n_red_a > 0 ? L.n_red_a : 1));
   L.red_b = w.take(sizeof(double) * (size_t)L.n_red_b);
   L.dH = w.take(T * r * es);
   L.w_Xq = w.take(T * K);          // used when forward runs without a ctx (inference)
   L.w_gamma = w.take(T * sizeof(float));
   L.w_H = w.take(T * r * es);
+  L.splitk = w.take(sk);
   L.ws_total = w.off;
   return L;
 }
@@ -258,6 +268,7 @@ extern "C" int pq_linear_fwd(const pq_linear_desc* d, const void* X, const void*
   hipStream_t s = (hipStream_t)stream;
   char* cx = (char*)ctx;
   char* ws = (char*)workspace;
+  void* sk_ws = ws + L.splitk;
   const bool bf16 = d->io_dtype == PQ_BF16;
   const int engine = bf16 ? 0 : 1;
   const int ok = out_kind_of(d->io_dtype);
@@ -291,7 +302,7 @@ extern "C" int pq_linear_fwd(const pq_linear_desc* d, const void* X, const void*
     pq_epilogue e = epi_zero();
     e.C = Y; e.ldc = N; e.out_kind = ok;
     e.scale = d->beta; e.dev_scale = mulam + 1; e.row_div = gamma;
-    if (int err = pq_launch_gemm(0, T, N, K, A, B, e, s, PQP_GEMM_ONEBIT)) return err;
+    if (int err = pq_launch_gemm(0, T, N, K, A, B, e, s, PQP_GEMM_ONEBIT, sk_ws)) return err;
   }
   if (r > 0) {
     void* H = ctx ? (void*)(cx + L.H) : (void*)(ws + L.w_H);
@@ -300,14 +311,14 @@ extern "C" int pq_linear_fwd(const pq_linear_desc* d, const void* X, const void*
       pq_operand B{hpA, K, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
       pq_epilogue e = epi_zero();
       e.C = H; e.ldc = r; e.out_kind = ok;
-      if (int err = pq_launch_gemm(engine, T, r, K, A, B, e, s, PQP_GEMM_HP_H)) return err;
+      if (int err = pq_launch_gemm(engine, T, r, K, A, B, e, s, PQP_GEMM_HP_H, sk_ws)) return err;
     }
     {  // Y += alpha * H B^T
       pq_operand A{H, r, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
       pq_operand B{hpB, r, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
       pq_epilogue e = epi_zero();
       e.C = Y; e.ldc = N; e.out_kind = ok; e.accumulate = 1; e.scale = d->alpha;
-      if (int err = pq_launch_gemm(engine, T, N, r, A, B, e, s, PQP_GEMM_HP_Y)) return err;
+      if (int err = pq_launch_gemm(engine, T, N, r, A, B, e, s, PQP_GEMM_HP_Y, sk_ws)) return err;
     }
   }
   return PQ_OK;
@@ -334,6 +345,7 @@ extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void
   hipStream_t s = (hipStream_t)stream;
   const char* cx = (const char*)ctx;
   char* ws = (char*)workspace;
+  void* sk_ws = ws + L.splitk;
   const bool bf16 = d->io_dtype == PQ_BF16;
   const int engine = bf16 ? 0 : 1;
   const int ok = out_kind_of(d->io_dtype);
@@ -351,7 +363,7 @@ extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void
     pq_epilogue e = epi_zero();
     e.C = dH; e.ldc = r; e.out_kind = ok; e.scale = d->alpha;
     e.dot_comp = H; e.ld_comp = r; e.comp_kind = ok; e.partials = red_a;
-    if (int err = pq_launch_gemm(engine, T, r, N, A, B, e, s, PQP_GEMM_DH)) return err;
+    if (int err = pq_launch_gemm(engine, T, r, N, A, B, e, s, PQP_GEMM_DH, sk_ws)) return err;
   }
   if (int err = pq_launch_reduce_partials(red_a, (T > 0 && r > 0) ? L.n_red_a : 0, 1.0f, nullptr, dalpha_dbeta, s)) return err;
 
@@ -360,13 +372,13 @@ extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void
     pq_operand B{cx + L.Pt, N / 8, bf16 ? PQ_SRC_BITS16 : PQ_SRC_BITSF, nullptr};
     pq_epilogue e = epi_zero();
     e.C = dX; e.ldc = K; e.out_kind = ok; e.scale = d->beta; e.dev_scale = mulam + 1;
-    if (int err = pq_launch_gemm(engine, T, K, N, A, B, e, s, PQP_GEMM_DX)) return err;
+    if (int err = pq_launch_gemm(engine, T, K, N, A, B, e, s, PQP_GEMM_DX, sk_ws)) return err;
     if (r > 0) {
       pq_operand A2{dH, r, KC, nullptr};
       pq_operand B2{hpA, K, KS, nullptr};
       pq_epilogue e2 = epi_zero();
       e2.C = dX; e2.ldc = K; e2.out_kind = ok; e2.accumulate = 1;
-      if (int err = pq_launch_gemm(engine, T, K, r, A2, B2, e2, s, PQP_GEMM_DX_HP)) return err;
+      if (int err = pq_launch_gemm(engine, T, K, r, A2, B2, e2, s, PQP_GEMM_DX_HP, sk_ws)) return err;
     }
   }
   {  // dW = beta * (dY/gamma)^T q  [masked];  d beta = lambda * sum S .* (dY/gamma)^T q
@@ -379,7 +391,7 @@ extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void
     if (d->ste_mode == PQ_STE_CLIP) {
       e.maskW = W; e.mask_kind = ok; e.mu_dev = mulam; e.tau = d->ste_tau;
     }
-    if (int err = pq_launch_gemm(engine, N, K, T, A, B, e, s, PQP_GEMM_DW)) return err;
+    if (int err = pq_launch_gemm(engine, N, K, T, A, B, e, s, PQP_GEMM_DW, sk_ws)) return err;
     if (int err = pq_launch_reduce_partials(red_b, L.n_red_b, 1.0f, mulam + 1, dalpha_dbeta + 1, s)) return err;
   }
   if (r > 0) {
@@ -388,14 +400,14 @@ extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void
       pq_operand B{H, r, KS, nullptr};
       pq_epilogue e = epi_zero();
       e.C = dhpB; e.ldc = r; e.out_kind = PQ_OUT_F32; e.scale = d->alpha;
-      if (int err = pq_launch_gemm(engine, N, r, T, A, B, e, s, PQP_GEMM_DB)) return err;
+      if (int err = pq_launch_gemm(engine, N, r, T, A, B, e, s, PQP_GEMM_DB, sk_ws)) return err;
     }
     {  // dA = dH^T X   (dH already carries alpha)
       pq_operand A{dH, r, KS, nullptr};
       pq_operand B{X, K, KS, nullptr};
       pq_epilogue e = epi_zero();
       e.C = dhpA; e.ldc = K; e.out_kind = PQ_OUT_F32;
-      if (int err = pq_launch_gemm(engine, r, K, T, A, B, e, s, PQP_GEMM_DA)) return err;
+      if (int err = pq_launch_gemm(engine, r, K, T, A, B, e, s, PQP_GEMM_DA, sk_ws)) return err;
     }
   }
   return PQ_OK;

@@ -15,6 +15,7 @@
 //   v_mfma_f32_32x32x16_bf16 / v_mfma_i32_32x32x32_i8, 16 bytes of operand per lane per issue.
 // LDS rows are 128 bytes with the 16-byte chunk index XOR-swizzled by the row so that the MFMA
 // operand reads, the row-wise stores and the transposed stores are all free of bank conflicts.
+#include <string.h>
 #include <type_traits>
 #include "pq_internal.h"
 
@@ -36,8 +37,11 @@ struct tile_stage {
   static constexpr bool kBits = (KIND == PQ_SRC_BITS8 || KIND == PQ_SRC_BITS16);
   static constexpr bool kStrided = (KIND == PQ_SRC_KS16);
   static constexpr int EPC = (KIND == PQ_SRC_KC8 || KIND == PQ_SRC_BITS8) ? 16 : 8;  // elements per chunk
-  static constexpr int NU = (ROWS + NT - 1) / NT;  // 8x8 transpose units per thread (KS16)
-  uint4 v[kBits ? 1 : (kStrided ? NU * 8 : NCH)];
+  // KS16: a unit is 8 rows x KQ contraction indices (KQ 16-byte loads, transposed in registers)
+  static constexpr int KQ = (ROWS >= NT) ? 8 : 4;
+  static constexpr int UPR = 64 / KQ;                     // units per 8-row group
+  static constexpr int NU = (ROWS / 8 * UPR + NT - 1) / NT;  // units per thread
+  uint4 v[kBits ? 1 : (kStrided ? NU * KQ : NCH)];
   uint32_t raw[kBits ? NCH : 1];
   uint32_t okbits;  // validity of each loaded chunk, applied when the tile is written to LDS
 
@@ -50,16 +54,16 @@ struct tile_stage {
 #pragma unroll
       for (int i = 0; i < NU; ++i) {
         const int u = tid + i * NT;
-        const int r8 = u >> 3, k8 = u & 7;
+        const int r8 = u / UPR, kq = u % UPR;
         const int col = row0 + r8 * 8;
-        const bool okc = (u < ROWS) && (col < rows);
+        const bool okc = (u < ROWS / 8 * UPR) && (col < rows);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int kk = k0 + k8 * 8 + j;
+        for (int j = 0; j < KQ; ++j) {
+          const int kk = k0 + kq * KQ + j;
           const bool ok = okc && (kk < K);
           const size_t off = ok ? (size_t)kk * op.ld + col : 0;
-          v[i * 8 + j] = *reinterpret_cast<const uint4*>(p + off);
-          okbits |= (ok ? 1u : 0u) << (i * 8 + j);
+          v[i * KQ + j] = *reinterpret_cast<const uint4*>(p + off);
+          okbits |= (ok ? 1u : 0u) << (i * KQ + j);
         }
       }
     } else {
@@ -95,23 +99,27 @@ struct tile_stage {
 #pragma unroll
       for (int i = 0; i < NU; ++i) {
         const int u = tid + i * NT;
-        if (u < ROWS) {
-          const int r8 = u >> 3, k8 = u & 7;
-          // 8x8 transpose of 16-bit elements: v[i*8+j] holds rows r8*8..+7 at contraction index j
+        if (u < ROWS / 8 * UPR) {
+          const int r8 = u / UPR, kq = u % UPR;
+          // transpose of 16-bit elements: v[i*KQ+j] holds rows r8*8..+7 at contraction index j
 #pragma unroll
           for (int rr = 0; rr < 8; ++rr) {
-            uint32_t o[4];
+            uint32_t o[KQ / 2];
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
-              const uint4 lo4 = mask4(v[i * 8 + 2 * p], (okbits >> (i * 8 + 2 * p)) & 1u);
-              const uint4 hi4 = mask4(v[i * 8 + 2 * p + 1], (okbits >> (i * 8 + 2 * p + 1)) & 1u);
+            for (int p = 0; p < KQ / 2; ++p) {
+              const uint4 lo4 = mask4(v[i * KQ + 2 * p], (okbits >> (i * KQ + 2 * p)) & 1u);
+              const uint4 hi4 = mask4(v[i * KQ + 2 * p + 1], (okbits >> (i * KQ + 2 * p + 1)) & 1u);
               const uint32_t lo = (rr >> 1) == 0 ? lo4.x : (rr >> 1) == 1 ? lo4.y : (rr >> 1) == 2 ? lo4.z : lo4.w;
               const uint32_t hi = (rr >> 1) == 0 ? hi4.x : (rr >> 1) == 1 ? hi4.y : (rr >> 1) == 2 ? hi4.z : hi4.w;
-              // result bytes: [lo.half, hi.half]; v_perm selects bytes 0-3 from the 2nd operand, 4-7 from the 1st
+              // result = [lo.half, hi.half]; v_perm selects bytes 0-3 from the 2nd operand, 4-7 from the 1st
               o[p] = (rr & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u)
                               : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
             }
-            *reinterpret_cast<uint4*>(lds + lds_off(r8 * 8 + rr, k8)) = make_uint4(o[0], o[1], o[2], o[3]);
+            if constexpr (KQ == 8) {
+              *reinterpret_cast<uint4*>(lds + lds_off(r8 * 8 + rr, kq)) = make_uint4(o[0], o[1], o[2], o[3]);
+            } else {
+              *reinterpret_cast<uint2*>(lds + lds_off(r8 * 8 + rr, kq >> 1) + (kq & 1) * 8) = make_uint2(o[0], o[1]);
+            }
           }
         }
       }
@@ -281,27 +289,33 @@ __device__ __forceinline__ void epi_vec8(const pq_epilogue& e, epi_state& st, in
 // ---------------------------------------------------------------------------------------------
 // MFMA engine
 // ---------------------------------------------------------------------------------------------
+// One workgroup computes a BM x BN tile over the contraction range [z*kchunk, (z+1)*kchunk), z =
+// blockIdx.y.  LDS holds two stages of both operand tiles; per 128-byte step there is a single
+// barrier: after it, the registers prefetched during the previous step are written to the idle
+// stage, the loads of the step after next are issued, and the MFMAs run on the ready stage.
 template <int BM, int BN, int WGM, int WGN, bool INT8, int AK, int BKIND>
 __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N, int K, pq_operand A,
                                                                      pq_operand B, pq_epilogue epi,
-                                                                     int nbn, int total_blocks) {
+                                                                     int nbn, int total_tiles, int kchunk,
+                                                                     float* splitk_part) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int EPB = INT8 ? 128 : 64;  // contraction elements per 128-byte LDS row
+  constexpr int STAGE = (BM + BN) * 128;
   using acc_t = typename std::conditional<INT8, i32x16_t, f32x16_t>::type;
 
-  __shared__ __attribute__((aligned(16))) unsigned char smem[(BM + BN) * 128];
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * STAGE];
   __shared__ double red[NT / 64];
-  unsigned char* As = smem;
-  unsigned char* Bs = smem + BM * 128;
 
   // XCD-aware tile order: consecutive workgroups go to different XCDs, so give each XCD a
   // contiguous range of tiles (its L2 then sees the same A row-panel for a run of tiles).
   int pid = blockIdx.x;
-  if ((total_blocks & 7) == 0) pid = (pid & 7) * (total_blocks >> 3) + (pid >> 3);
+  if ((total_tiles & 7) == 0) pid = (pid & 7) * (total_tiles >> 3) + (pid >> 3);
   const int bm = pid / nbn, bn = pid % nbn;
   const int m0 = bm * BM, n0 = bn * BN;
+  const int kb = blockIdx.y * kchunk;
+  const int ke = min(K, kb + kchunk);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
@@ -316,21 +330,32 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
 
   tile_stage<AK, BM, NT> sa;
   tile_stage<BKIND, BN, NT> sb;
-  const int nkt = (K + EPB - 1) / EPB;
+  const int nkt = ke > kb ? (ke - kb + EPB - 1) / EPB : 0;
   if (nkt > 0) {
-    sa.load(A, m0, M, 0, K, tid);
-    sb.load(B, n0, N, 0, K, tid);
-    sa.store(As, tid);
-    sb.store(Bs, tid);
+    sa.load(A, m0, M, kb, ke, tid);
+    sb.load(B, n0, N, kb, ke, tid);
+    sa.store(smem, tid);
+    sb.store(smem + BM * 128, tid);
+    if (nkt > 1) {
+      sa.load(A, m0, M, kb + EPB, ke, tid);
+      sb.load(B, n0, N, kb + EPB, ke, tid);
+    }
   }
-  __syncthreads();
 
   for (int kt = 0; kt < nkt; ++kt) {
-    const bool more = (kt + 1 < nkt);
-    if (more) {
-      sa.load(A, m0, M, (kt + 1) * EPB, K, tid);
-      sb.load(B, n0, N, (kt + 1) * EPB, K, tid);
+    __syncthreads();  // stage kt&1 is complete; nobody still reads the other stage
+    unsigned char* cur = smem + (kt & 1) * STAGE;
+    unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
+    if (kt + 1 < nkt) {
+      sa.store(nxt, tid);
+      sb.store(nxt + BM * 128, tid);
     }
+    if (kt + 2 < nkt) {
+      sa.load(A, m0, M, kb + (kt + 2) * EPB, ke, tid);
+      sb.load(B, n0, N, kb + (kt + 2) * EPB, ke, tid);
+    }
+    const unsigned char* As = cur;
+    const unsigned char* Bs = cur + BM * 128;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       uint4 af[TM], bf[TN];
@@ -351,19 +376,16 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
                                                                 __builtin_bit_cast(bf16x8_t, bf[j]), acc[i][j], 0, 0, 0);
         }
     }
-    __syncthreads();
-    if (more) {
-      sa.store(As, tid);
-      sb.store(Bs, tid);
-      __syncthreads();
-    }
   }
+  __syncthreads();  // all MFMA operand reads are done: LDS is reused below
 
   // Epilogue: each wavefront passes its 32x32 accumulator blocks through a private LDS patch
   // (row stride 36 words: conflict-free both ways) so that a lane ends up with 8 consecutive
-  // columns of one row and global loads/stores are 16 bytes wide.
+  // columns of one row and global loads/stores are 16 bytes wide.  With a split contraction the
+  // raw fp32 accumulators go to this split's slab instead; splitk_reduce_kernel finishes the job.
   epi_state st;
   epi_begin(epi, st);
+  float* slab = splitk_part ? splitk_part + (size_t)blockIdx.y * M * N : nullptr;
   uint32_t* stg = reinterpret_cast<uint32_t*>(smem) + wave * (32 * 36);
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -384,12 +406,46 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
         const int m = m0 + wm0 + i * 32 + rr, n = n0 + wn0 + j * 32 + c0;
         const uint4 r0 = *reinterpret_cast<const uint4*>(stg + rr * 36 + c0);
         const uint4 r1 = *reinterpret_cast<const uint4*>(stg + rr * 36 + c0 + 4);
-        if (m < M && n < N) epi_vec8<INT8>(epi, st, m, n, r0, r1);
+        if (m < M && n < N) {
+          if (slab) {
+            *reinterpret_cast<uint4*>(slab + (size_t)m * N + n) = r0;
+            *reinterpret_cast<uint4*>(slab + (size_t)m * N + n + 4) = r1;
+          } else {
+            epi_vec8<INT8>(epi, st, m, n, r0, r1);
+          }
+        }
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
       __builtin_amdgcn_wave_barrier();
     }
-  epi_end<NT>(epi, st, red, blockIdx.x);
+  if (!slab) epi_end<NT>(epi, st, red, blockIdx.x);
+}
+
+// Second stage of a split contraction: sum the slabs in index order (deterministic), then apply
+// the caller's epilogue.  One thread per 8 consecutive columns.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(int M, int N, int splits, const float* __restrict__ part,
+                                                            pq_epilogue epi) {
+  __shared__ double red[4];
+  const size_t n8 = (size_t)N / 8, total = (size_t)M * n8;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  epi_state st;
+  epi_begin(epi, st);
+  if (idx < total) {
+    const int m = (int)(idx / n8), n = (int)(idx % n8) * 8;
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+    const size_t slab = (size_t)M * N;
+    for (int z = 0; z < splits; ++z) {
+      const float* p = part + z * slab + (size_t)m * N + n;
+      const float4 x = *reinterpret_cast<const float4*>(p);
+      const float4 y = *reinterpret_cast<const float4*>(p + 4);
+      a.x += x.x; a.y += x.y; a.z += x.z; a.w += x.w;
+      b.x += y.x; b.y += y.y; b.z += y.z; b.w += y.w;
+    }
+    const uint4 r0 = make_uint4(__float_as_uint(a.x), __float_as_uint(a.y), __float_as_uint(a.z), __float_as_uint(a.w));
+    const uint4 r1 = make_uint4(__float_as_uint(b.x), __float_as_uint(b.y), __float_as_uint(b.z), __float_as_uint(b.w));
+    epi_vec8<false>(epi, st, m, n, r0, r1);
+  }
+  epi_end<256>(epi, st, red, blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -428,43 +484,59 @@ __global__ __launch_bounds__(256) void ref_gemm_kernel(int M, int N, int K, pq_o
   epi_end<256>(epi, st, red, blockIdx.y * gridDim.x + blockIdx.x);
 }
 
-struct tile_cfg { int bm, bn; };
-
-inline tile_cfg pick_tile(int M, int N) {
-  // Largest tile that still gives every one of the 256 compute units a workgroup.
-  const long b256 = (long)((M + 255) / 256) * ((N + 255) / 256);
-  if (M >= 256 && N >= 256 && b256 >= 256) return {256, 256};
-  return {128, 128};
-}
-
-template <int BM, int BN, bool INT8, int AK, int BKIND>
-int launch_mfma(int M, int N, int K, const pq_operand& A, const pq_operand& B, const pq_epilogue& epi,
-                hipStream_t s) {
+template <int BM, int BN, int WGM, int WGN, bool INT8, int AK, int BKIND>
+int launch_mfma(const pq_gemm_plan& pl, int M, int N, int K, const pq_operand& A, const pq_operand& B,
+                const pq_epilogue& epi, hipStream_t s, float* part) {
   const int nbm = (M + BM - 1) / BM, nbn = (N + BN - 1) / BN;
-  const int total = nbm * nbn;
-  mfma_gemm_kernel<BM, BN, 2, 2, INT8, AK, BKIND><<<total, 256, 0, s>>>(M, N, K, A, B, epi, nbn, total);
+  const int tiles = nbm * nbn;
+  dim3 grid(tiles, pl.splits), block(WGM * WGN * 64);
+  mfma_gemm_kernel<BM, BN, WGM, WGN, INT8, AK, BKIND><<<grid, block, 0, s>>>(M, N, K, A, B, epi, nbn, tiles, pl.kchunk,
+                                                                               pl.splits > 1 ? part : nullptr);
   PQ_CHECK_LAUNCH("mfma_gemm_kernel");
   return PQ_OK;
 }
 
 template <bool INT8, int AK, int BKIND>
-int launch_mfma_cfg(int M, int N, int K, const pq_operand& A, const pq_operand& B, const pq_epilogue& epi,
-                    hipStream_t s) {
-  const tile_cfg c = pick_tile(M, N);
-  if (c.bm == 256) return launch_mfma<256, 256, INT8, AK, BKIND>(M, N, K, A, B, epi, s);
-  return launch_mfma<128, 128, INT8, AK, BKIND>(M, N, K, A, B, epi, s);
+int launch_mfma_cfg(const pq_gemm_plan& pl, int M, int N, int K, const pq_operand& A, const pq_operand& B,
+                    const pq_epilogue& epi, hipStream_t s, float* part) {
+  if (pl.bm == 256) return launch_mfma<256, 256, 2, 4, INT8, AK, BKIND>(pl, M, N, K, A, B, epi, s, part);
+  return launch_mfma<128, 128, 2, 2, INT8, AK, BKIND>(pl, M, N, K, A, B, epi, s, part);
 }
 
 }  // namespace
 
-int pq_gemm_blocks(int engine, int M, int N) {
-  if (engine == 1) return ((M + 15) / 16) * ((N + 15) / 16);
-  const tile_cfg c = pick_tile(M, N);
-  return ((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
+// Tile shape and contraction split for one GEMM.  A 256x256 tile (8 wavefronts, 128x64 each) when
+// the output is large enough, else 128x128 (4 wavefronts); when the tiles alone cannot occupy the
+// 256 compute units the contraction is split and reduced in a second, fixed-order pass.
+pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8) {
+  pq_gemm_plan pl;
+  memset(&pl, 0, sizeof(pl));
+  pl.splits = 1;
+  if (engine == 1) {
+    pl.bm = pl.bn = 16;
+    pl.kchunk = K;
+    pl.red_blocks = ((M + 15) / 16) * ((N + 15) / 16);
+    return pl;
+  }
+  const bool big = (M >= 256 && N >= 256);
+  pl.bm = pl.bn = big ? 256 : 128;
+  const long tiles = (long)((M + pl.bm - 1) / pl.bm) * ((N + pl.bn - 1) / pl.bn);
+  pl.kchunk = K > 0 ? K : 1;
+  if (!int8 && tiles > 0 && tiles <= 128 && K >= 512) {
+    long want = 256 / tiles;
+    if (want > 16) want = 16;
+    long chunk = (K + want - 1) / want;
+    chunk = (chunk + 255) / 256 * 256;          // whole 128-byte steps, at least four of them
+    pl.kchunk = (int)chunk;
+    pl.splits = (int)((K + chunk - 1) / chunk);
+  }
+  pl.red_blocks = pl.splits > 1 ? (int)(((size_t)M * (N / 8) + 255) / 256) : (int)tiles;
+  pl.ws_bytes = pl.splits > 1 ? (size_t)pl.splits * M * N * sizeof(float) : 0;
+  return pl;
 }
 
 int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const pq_operand& B,
-                   const pq_epilogue& epi, hipStream_t s, int prof_label) {
+                   const pq_epilogue& epi, hipStream_t s, int prof_label, void* splitk_ws) {
   if (M <= 0 || N <= 0) return PQ_OK;
   pq_prof_scope prof(prof_label, s);
   if (engine == 1) {
@@ -474,10 +546,21 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
     return PQ_OK;
   }
   const int ak = A.kind, bk = B.kind;
-  if (ak == PQ_SRC_KC8 && bk == PQ_SRC_BITS8) return launch_mfma_cfg<true, PQ_SRC_KC8, PQ_SRC_BITS8>(M, N, K, A, B, epi, s);
-  if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KC16) return launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KC16>(M, N, K, A, B, epi, s);
-  if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KS16) return launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KS16>(M, N, K, A, B, epi, s);
-  if (ak == PQ_SRC_KC16 && bk == PQ_SRC_BITS16) return launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_BITS16>(M, N, K, A, B, epi, s);
-  if (ak == PQ_SRC_KS16 && bk == PQ_SRC_KS16) return launch_mfma_cfg<false, PQ_SRC_KS16, PQ_SRC_KS16>(M, N, K, A, B, epi, s);
-  return pq_set_error(PQ_ERR_BAD_ARG, "no MFMA kernel for operand kinds (%d, %d)", ak, bk);
+  const bool int8 = (ak == PQ_SRC_KC8);
+  const pq_gemm_plan pl = pq_plan_gemm(0, M, N, K, int8);
+  if (pl.splits > 1 && !splitk_ws) return pq_set_error(PQ_ERR_WORKSPACE, "split contraction needs scratch");
+  float* part = (float*)splitk_ws;
+  int rc;
+  if (ak == PQ_SRC_KC8 && bk == PQ_SRC_BITS8) rc = launch_mfma_cfg<true, PQ_SRC_KC8, PQ_SRC_BITS8>(pl, M, N, K, A, B, epi, s, part);
+  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KC16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KC16>(pl, M, N, K, A, B, epi, s, part);
+  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KS16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part);
+  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_BITS16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_BITS16>(pl, M, N, K, A, B, epi, s, part);
+  else if (ak == PQ_SRC_KS16 && bk == PQ_SRC_KS16) rc = launch_mfma_cfg<false, PQ_SRC_KS16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part);
+  else return pq_set_error(PQ_ERR_BAD_ARG, "no MFMA kernel for operand kinds (%d, %d)", ak, bk);
+  if (rc != PQ_OK) return rc;
+  if (pl.splits > 1) {
+    splitk_reduce_kernel<<<pl.red_blocks, 256, 0, s>>>(M, N, pl.splits, part, epi);
+    PQ_CHECK_LAUNCH("splitk_reduce_kernel");
+  }
+  return PQ_OK;
 }

@@ -79,8 +79,15 @@ struct pq_epilogue {
 };
 
 // C[M][N] (+)= epilogue( sum_k A(m,k) * B(n,k) ).  `engine` 0 = MFMA (bf16 or int8 operands),
-// 1 = reference precision (fp64 accumulate, any operand kind).  Returns the number of blocks
-// launched through *nblocks (= number of partial sums written when a reduction is requested).
-int pq_gemm_blocks(int engine, int M, int N);
+// 1 = reference precision (fp64 accumulate, any operand kind).
+struct pq_gemm_plan {
+  int bm, bn;        // tile
+  int splits;        // contraction splits (1 = none)
+  int kchunk;        // contraction elements per split
+  int red_blocks;    // number of per-block partial sums written when a reduction is requested
+  size_t ws_bytes;   // scratch for the split slabs
+};
+pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8 = false);
 int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const pq_operand& B,
-                   const pq_epilogue& epi, hipStream_t s, int prof_label = PQP_GEMM_OTHER);
+                   const pq_epilogue& epi, hipStream_t s, int prof_label = PQP_GEMM_OTHER,
+                   void* splitk_ws = nullptr);
