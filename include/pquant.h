@@ -125,6 +125,33 @@ int pq_linear_bwd(const pq_linear_desc* desc, const void* dY, const void* X, con
                   void* dX, float* dW, float* dhpA, float* dhpB, float* dWr, float* dalpha_dbeta,
                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* Inference on packed weights for small token batches (App. A): the decode product
+ *     y[l][b][n] = (s_l / gamma_lb) * sum_k q[l][b][k] * S_l[n][k]
+ *                  + alpha * sum_j gate[l][b][j] * B_le (A_le x_lb),   e = idx[l][b][j]
+ * for n_layers independent weight sets l in one launch (n_layers = 1 is a single layer).
+ * Everything runs in the call: AbsMax INT8 quantisation of x (Sec. 3.1), router top-k (Sec. 3.3),
+ * the expert hidden state, the packed-bit product with exact int32 accumulation, the experts.
+ *   X [L][B][K] bf16;  packed [L][N][K/32] uint32 (layout of pq_pack_sign);
+ *   scale_fp16 [L]: the bits of fp16(beta * lambda), the single stored scale of a packed layer;
+ *   hpA [L][E][r][K], hpB [L][E][N][r], Wr [L][E][K] bf16 (all NULL when hp_rank == 0);
+ *   Y [L][B][N] bf16 out;  acc_out [L][B][N] int32 out or NULL (the exact accumulators, for tests).
+ * Limits: 1 <= B <= 16; K % 128 == 0 (B == 1) or K % 512 == 0 (B > 1); N % 4 == 0; r % 8 == 0
+ * (B == 1) or r % 32 == 0 and (E r) % 64 == 0 (B > 1); 16 K + 32 E r <= 160 KiB for B > 1. */
+typedef struct pq_decode_desc {
+  int32_t batch;     /* B, tokens per layer */
+  int32_t d_in;      /* K */
+  int32_t d_out;     /* N */
+  int32_t hp_rank;   /* r per expert, 0 = no high-precision branch */
+  int32_t n_experts; /* E */
+  int32_t top_k;     /* experts per token */
+  int32_t n_layers;  /* L */
+  float alpha;
+} pq_decode_desc;
+size_t pq_decode_workspace_bytes(const pq_decode_desc* desc);
+int pq_decode_gemv(const pq_decode_desc* desc, const void* X, const uint32_t* packed, const uint16_t* scale_fp16,
+                   const void* hpA, const void* hpB, const void* Wr, void* Y, int32_t* acc_out, void* workspace,
+                   size_t workspace_bytes, void* stream);
+
 /* Per-kernel timing for benchmarks.  While enabled, every kernel launch made by the library is
  * bracketed by a pair of HIP events on the caller's stream (events are created on demand, so this
  * mode allocates; it is off by default).  pq_prof_count() = number of kernel labels;

@@ -22,7 +22,7 @@ EXPORTS = [
     "pq_version", "pq_last_error_string", "pq_quant_act", "pq_pack_workspace_bytes", "pq_pack_sign",
     "pq_router_topk", "pq_onebit_acc", "pq_linear_ctx_bytes", "pq_linear_workspace_bytes",
     "pq_linear_fwd", "pq_linear_bwd", "pq_prof_enable", "pq_prof_count", "pq_prof_label", "pq_prof_read",
-    "pq_prof_reset",
+    "pq_prof_reset", "pq_decode_workspace_bytes", "pq_decode_gemv",
 ]
 
 
@@ -30,6 +30,11 @@ class LinearDesc(C.Structure):
     _fields_ = [("tokens", C.c_int32), ("d_in", C.c_int32), ("d_out", C.c_int32), ("hp_rank", C.c_int32),
                 ("n_experts", C.c_int32), ("top_k", C.c_int32), ("io_dtype", C.c_int32), ("w_kind", C.c_int32),
                 ("ste_mode", C.c_int32), ("ste_tau", C.c_float), ("alpha", C.c_float), ("beta", C.c_float)]
+
+
+class DecodeDesc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("d_in", C.c_int32), ("d_out", C.c_int32), ("hp_rank", C.c_int32),
+                ("n_experts", C.c_int32), ("top_k", C.c_int32), ("n_layers", C.c_int32), ("alpha", C.c_float)]
 
 
 class PQError(RuntimeError):
@@ -48,7 +53,8 @@ def lib():
         L = C.CDLL(LIB_PATH)
         L.pq_last_error_string.restype = C.c_char_p
         L.pq_prof_label.restype = C.c_char_p
-        for name in ("pq_pack_workspace_bytes", "pq_linear_ctx_bytes", "pq_linear_workspace_bytes"):
+        for name in ("pq_pack_workspace_bytes", "pq_linear_ctx_bytes", "pq_linear_workspace_bytes",
+                     "pq_decode_workspace_bytes"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -169,3 +175,17 @@ def prof_read():
         if n.value:
             out[lib().pq_prof_label(i).decode()] = (ms.value, n.value)
     return out
+
+
+def decode_workspace(desc, device="cuda"):
+    n = lib().pq_decode_workspace_bytes(C.byref(desc))
+    if n == 0:
+        raise PQError(f"bad decode descriptor: {lib().pq_last_error_string().decode()}")
+    return _bytes(n, device)
+
+
+def decode_gemv(desc, X, packed, scale_fp16, Y, ws, A=None, B=None, Wr=None, acc_out=None):
+    """scale_fp16: int16/uint16 tensor [L] holding the fp16 bits of beta*lambda per layer."""
+    _check(lib().pq_decode_gemv(C.byref(desc), _p(X), _p(packed), _p(scale_fp16), _p(A), _p(B), _p(Wr), _p(Y),
+                                _p(acc_out), _p(ws), C.c_size_t(ws.numel()), _stream()))
+    return Y

@@ -30,7 +30,7 @@ std::vector<prof_sample*> g_prof_samples;
 const char* const g_prof_names[PQP_COUNT] = {
     "quant_act", "wstats_partial", "pack_sign", "router", "reduce_partials",
     "gemm_onebit_fwd", "gemm_hp_H", "gemm_hp_Y", "gemm_dH", "gemm_dX", "gemm_dX_hp",
-    "gemm_dW", "gemm_dB", "gemm_dA", "gemm_other"};
+    "gemm_dW", "gemm_dB", "gemm_dA", "gemm_other", "decode_prep", "decode_main"};
 }  // namespace
 
 pq_prof_scope::pq_prof_scope(int label_, hipStream_t s_) : label(label_), s(s_), slot(nullptr) {
@@ -411,4 +411,59 @@ extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void
     }
   }
   return PQ_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Decode on packed weights
+// ---------------------------------------------------------------------------------------------
+namespace {
+int check_decode(const pq_decode_desc* d) {
+  PQ_REQUIRE(d != nullptr, PQ_ERR_BAD_ARG, "desc is NULL");
+  PQ_REQUIRE(d->batch >= 1 && d->batch <= 16, PQ_ERR_BAD_ARG, "batch=%d must be in 1..16", d->batch);
+  PQ_REQUIRE(d->d_in > 0 && d->d_out > 0 && d->hp_rank >= 0 && d->n_layers >= 1, PQ_ERR_BAD_ARG, "bad dimension");
+  PQ_REQUIRE(d->d_out % 4 == 0, PQ_ERR_SHAPE, "d_out=%d must be a multiple of 4", d->d_out);
+  if (d->batch == 1) {
+    PQ_REQUIRE(d->d_in % 128 == 0, PQ_ERR_SHAPE, "d_in=%d must be a multiple of 128", d->d_in);
+    PQ_REQUIRE(d->hp_rank % 8 == 0, PQ_ERR_SHAPE, "hp_rank=%d must be a multiple of 8", d->hp_rank);
+  } else {
+    PQ_REQUIRE(d->d_in % 512 == 0, PQ_ERR_SHAPE, "batch > 1 needs d_in=%d to be a multiple of 512", d->d_in);
+    PQ_REQUIRE(d->hp_rank % 32 == 0, PQ_ERR_SHAPE, "batch > 1 needs hp_rank=%d to be a multiple of 32", d->hp_rank);
+  }
+  if (d->hp_rank > 0) {
+    PQ_REQUIRE(d->n_experts >= 1 && d->n_experts <= 64, PQ_ERR_BAD_ARG, "n_experts=%d must be in 1..64", d->n_experts);
+    PQ_REQUIRE(d->top_k >= 1 && d->top_k <= d->n_experts, PQ_ERR_BAD_ARG, "top_k=%d must be in 1..n_experts", d->top_k);
+    if (d->batch > 1) {
+      PQ_REQUIRE((d->n_experts * d->hp_rank) % 64 == 0, PQ_ERR_SHAPE, "batch > 1 needs n_experts*hp_rank %% 64 == 0");
+      PQ_REQUIRE(16 * (size_t)d->d_in + 32 * (size_t)d->n_experts * d->hp_rank <= 160 * 1024, PQ_ERR_SHAPE,
+                 "activations and expert hidden states do not fit the 160 KiB LDS");
+    }
+  } else {
+    PQ_REQUIRE(d->batch == 1 || 16 * (size_t)d->d_in <= 160 * 1024, PQ_ERR_SHAPE, "activations do not fit the 160 KiB LDS");
+  }
+  return PQ_OK;
+}
+}  // namespace
+
+extern "C" size_t pq_decode_workspace_bytes(const pq_decode_desc* d) {
+  if (check_decode(d) != PQ_OK) return 0;
+  pq_decode_desc dd = *d;
+  if (dd.hp_rank == 0) dd.top_k = 0;
+  size_t off[7];
+  return pq_decode_ws_layout(dd, off);
+}
+
+extern "C" int pq_decode_gemv(const pq_decode_desc* d, const void* X, const uint32_t* packed, const uint16_t* scale_fp16,
+                              const void* hpA, const void* hpB, const void* Wr, void* Y, int32_t* acc_out, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  if (int e = check_decode(d)) return e;
+  PQ_REQUIRE(X && packed && scale_fp16 && Y && workspace, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(d->hp_rank == 0 || (hpA && hpB && Wr), PQ_ERR_BAD_ARG, "hp_rank=%d but an expert buffer is NULL", d->hp_rank);
+  PQ_REQUIRE(aligned16(X) && aligned16(packed) && aligned16(Y) && aligned16(workspace) && aligned16(hpA) && aligned16(hpB) &&
+                 aligned16(Wr) && aligned16(acc_out), PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
+  pq_decode_desc dd = *d;
+  if (dd.hp_rank == 0) dd.top_k = 0;
+  size_t off[7];
+  const size_t need = pq_decode_ws_layout(dd, off);
+  PQ_REQUIRE(workspace_bytes >= need, PQ_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, need);
+  return pq_launch_decode(dd, X, packed, scale_fp16, hpA, hpB, Wr, Y, acc_out, workspace, (hipStream_t)stream);
 }

@@ -1,0 +1,465 @@
+// Inference on packed 1-bit weights (App. A): the decode product for small token batches.
+//
+//   y[b][n] = (s / gamma_b) * sum_k q[b][k] * S[n][k]  +  alpha * sum_j gate[b][j] * B_e(A_e x_b),  e = idx[b][j]
+//
+// with S read from packed bits, s = beta*lambda stored as one fp16 scale, q the INT8 AbsMax codes of
+// x_b (Sec. 3.1) and the experts in bf16 (Sec. 3.3, top-k routing).  The packed matrix is the only
+// large operand: the kernels stream it through coalesced 16-byte loads exactly once.
+//
+//   batch 1   bit-plane product: q is split into its 8 two's-complement bit planes (one uint32 per
+//             32 columns), so sum_k [S=+1] q_k = sum_p c_p * popcount(bits & plane_p), c_7 = -128;
+//             2 VALU ops per (word, plane) with the popcount's built-in accumulate, no multiplies,
+//             and sum_k q S = 2 * (that) - sum_k q.  Eight lanes share a row; the planes a lane
+//             needs stay in registers for all of its rows.
+//   batch >1  int8 MFMA (v_mfma_i32_16x16x64_i8): the weight bits are expanded to {0,1} bytes in
+//             registers (3 VALU ops per 4 weights) once for all tokens, the activations sit in
+//             LDS; the same 2*dot - rowsum identity restores the +/-1 product.  Experts run as a
+//             dense-masked bf16 MFMA over the experts that some token of the batch selected.
+// Several independent layers (weight sets) can be processed by one launch (grid.y), which is how
+// the bench keeps the working set larger than the Infinity Cache.
+#include "pq_internal.h"
+
+namespace {
+
+__device__ __forceinline__ float fp16_bits_to_f32(uint16_t h) {
+  _Float16 x = __builtin_bit_cast(_Float16, h);
+  return (float)x;
+}
+
+// ------------------------------------------------------------------------------------------
+// Prep: one workgroup per (layer, token): quantise, bit planes, row sum, router.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void decode_prep_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wr,
+                                                          int B, int K, int E, int topk, int8_t* __restrict__ xq,
+                                                          uint32_t* __restrict__ planes, int* __restrict__ rowsum,
+                                                          float* __restrict__ gamma, int* __restrict__ idx,
+                                                          float* __restrict__ gate) {
+  __shared__ float s_red[4];
+  __shared__ double s_dred[4];
+  __shared__ float s_gamma;
+  __shared__ int s_isum[4];
+  __shared__ double s_logit[64];
+  const int tok = blockIdx.x;            // layer * B + b
+  const int layer = tok / B;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const uint16_t* x = X + (size_t)tok * K;
+
+  float amax = 0.0f;
+  for (int k = tid; k < K; k += 256) amax = fmaxf(amax, fabsf(bf16_to_f32(x[k])));
+  amax = wave_max(amax);
+  if (lane == 0) s_red[wave] = amax;
+  __syncthreads();
+  if (tid == 0) {
+    const float a = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+    const float g = 128.0f / fmaxf(a, 1e-5f);
+    s_gamma = g;
+    gamma[tok] = g;
+  }
+  __syncthreads();
+  const float g = s_gamma;
+
+  // codes, bit planes (one thread per 32 columns) and the row sum
+  int isum = 0;
+  for (int w = tid; w < K / 32; w += 256) {
+    uint32_t pl[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int j = 0; j < 32; ++j) {
+      float y = __fmul_rn(bf16_to_f32(x[32 * w + j]), g);
+      float r = fminf(fmaxf(rintf(y), -128.0f), 127.0f);
+      const int q = (int)r;
+      xq[(size_t)tok * K + 32 * w + j] = (int8_t)q;
+      isum += q;
+#pragma unroll
+      for (int p = 0; p < 8; ++p) pl[p] |= (((uint32_t)q >> p) & 1u) << j;
+    }
+#pragma unroll
+    for (int p = 0; p < 8; ++p) planes[((size_t)tok * 8 + p) * (K / 32) + w] = pl[p];
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) isum += __shfl_xor(isum, o, 64);
+  if (lane == 0) s_isum[wave] = isum;
+  __syncthreads();
+  if (tid == 0) rowsum[tok] = s_isum[0] + s_isum[1] + s_isum[2] + s_isum[3];
+
+  if (E <= 0) return;
+  // router: fp64 logits rounded once to fp32, top-k on logits (ties to the lower index), softmax gates
+  for (int e = 0; e < E; ++e) {
+    const uint16_t* wr = Wr + ((size_t)layer * E + e) * K;
+    double acc = 0.0;
+    for (int k = tid; k < K; k += 256) acc += (double)bf16_to_f32(x[k]) * (double)bf16_to_f32(wr[k]);
+    acc = wave_sum_d(acc);
+    __syncthreads();
+    if (lane == 0) s_dred[wave] = acc;
+    __syncthreads();
+    if (tid == 0) s_logit[e] = (double)(float)(s_dred[0] + s_dred[1] + s_dred[2] + s_dred[3]);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    double mx = -1e300, den = 0.0;
+    for (int e = 0; e < E; ++e) mx = fmax(mx, s_logit[e]);
+    for (int e = 0; e < E; ++e) den += exp(s_logit[e] - mx);
+    unsigned long long taken = 0ull;
+    for (int j = 0; j < topk; ++j) {
+      int best = -1;
+      for (int e = 0; e < E; ++e)
+        if (!((taken >> e) & 1ull) && (best < 0 || s_logit[e] > s_logit[best])) best = e;
+      taken |= 1ull << best;
+      idx[(size_t)tok * topk + j] = best;
+      gate[(size_t)tok * topk + j] = (float)(exp(s_logit[best] - mx) / den);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Expert hidden state: one wavefront per (layer, token, slot, r): h = A_e[r,:] . x   (bf16 in, fp32 out)
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void decode_h_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ hpA,
+                                                       const int* __restrict__ idx, int B, int K, int E, int r, int topk,
+                                                       int total, float* __restrict__ h) {
+  const int lane = threadIdx.x & 63;
+  const int o = blockIdx.x * 4 + (threadIdx.x >> 6);   // ((layer*B + b)*topk + j)*r + rr
+  if (o >= total) return;
+  const int rr = o % r, slot = o / r;
+  const int tok = slot / topk, layer = tok / B;
+  const int e = idx[slot];
+  const uint4* a4 = reinterpret_cast<const uint4*>(hpA + (((size_t)layer * E + e) * r + rr) * K);
+  const uint4* x4 = reinterpret_cast<const uint4*>(X + (size_t)tok * K);
+  float acc = 0.0f;
+  for (int c = lane; c < K / 8; c += 64) {
+    const uint4 a = a4[c], x = x4[c];
+    acc += __uint_as_float(a.x << 16) * __uint_as_float(x.x << 16) + __uint_as_float(a.x & 0xFFFF0000u) * __uint_as_float(x.x & 0xFFFF0000u);
+    acc += __uint_as_float(a.y << 16) * __uint_as_float(x.y << 16) + __uint_as_float(a.y & 0xFFFF0000u) * __uint_as_float(x.y & 0xFFFF0000u);
+    acc += __uint_as_float(a.z << 16) * __uint_as_float(x.z << 16) + __uint_as_float(a.z & 0xFFFF0000u) * __uint_as_float(x.z & 0xFFFF0000u);
+    acc += __uint_as_float(a.w << 16) * __uint_as_float(x.w << 16) + __uint_as_float(a.w & 0xFFFF0000u) * __uint_as_float(x.w & 0xFFFF0000u);
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) h[o] = acc;
+}
+
+// ------------------------------------------------------------------------------------------
+// Batch 1: bit-plane GEMV.  A wavefront owns ROWS_PER_WAVE consecutive rows; 8 lanes share a row.
+// In step i a lane holds words 32 i + 4 (lane % 8) + {0..3} of its row, so the 8 lanes of a row read
+// 128 contiguous bytes per load instruction.
+// ------------------------------------------------------------------------------------------
+constexpr int GEMV_ITERS = 8;                       // 8 rows per iteration -> 64 rows per wavefront
+constexpr int GEMV_ROWS_PER_WAVE = 8 * GEMV_ITERS;
+constexpr int GEMV_ROWS_PER_BLOCK = 4 * GEMV_ROWS_PER_WAVE;
+
+struct gemv_params {
+  const uint32_t* P;      // [L][N][K/32]
+  const uint16_t* scale;  // [L] fp16 bits
+  const uint32_t* planes; // [L][8][K/32]
+  const int* rowsum;      // [L]
+  const float* gamma;     // [L]
+  const uint16_t* hpB;    // [L][E][N][r] bf16
+  const int* idx;         // [L][topk]
+  const float* gate;      // [L][topk]
+  const float* h;         // [L][topk][r]
+  uint16_t* Y;            // [L][N] bf16
+  int* acc_out;           // [L][N] or null
+  int N, K, E, r, topk;
+  float alpha;
+};
+
+__global__ __launch_bounds__(256) void decode_gemv_b1_kernel(gemv_params p) {
+  const int layer = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int sub = lane & 7, rl = lane >> 3;          // 8 lanes per row, 8 rows per iteration
+  const int nw = p.K / 32;                           // words per row
+  const int row_base = blockIdx.x * GEMV_ROWS_PER_BLOCK + wave * GEMV_ROWS_PER_WAVE;
+  if (row_base >= p.N) return;
+  const uint32_t* P = p.P + (size_t)layer * p.N * nw;
+  const uint32_t* planes = p.planes + (size_t)layer * 8 * nw;
+
+  int dot[GEMV_ITERS];
+#pragma unroll
+  for (int it = 0; it < GEMV_ITERS; ++it) dot[it] = 0;
+
+  for (int wc = 0; wc < nw; wc += 128) {             // 128 words (4096 columns) of planes in registers at a time
+    uint32_t pl[4][8][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int w0 = wc + 32 * i + 4 * sub;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const uint4 v = (w0 < nw) ? *reinterpret_cast<const uint4*>(planes + (size_t)q * nw + w0) : make_uint4(0, 0, 0, 0);
+        pl[i][q][0] = v.x; pl[i][q][1] = v.y; pl[i][q][2] = v.z; pl[i][q][3] = v.w;
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < GEMV_ITERS; ++it) {
+      const int row = row_base + it * 8 + rl;
+      const bool okr = row < p.N;
+      const uint32_t* prow = P + (size_t)(okr ? row : 0) * nw;
+      uint4 w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int w0 = wc + 32 * i + 4 * sub;
+        const bool ok = okr && (w0 < nw);
+        const uint4 t = *reinterpret_cast<const uint4*>(prow + (ok ? w0 : 0));
+        const uint32_t m = ok ? 0xFFFFFFFFu : 0u;
+        w[i] = make_uint4(t.x & m, t.y & m, t.z & m, t.w & m);
+      }
+      int a[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t ww[4] = {w[i].x, w[i].y, w[i].z, w[i].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int q = 0; q < 8; ++q) a[q] += __builtin_popcount(ww[j] & pl[i][q][j]);
+      }
+      int d = 0;
+#pragma unroll
+      for (int q = 0; q < 7; ++q) d += a[q] << q;
+      d -= a[7] << 7;
+      dot[it] += d;
+    }
+  }
+
+  // experts: lane `sub` covers r-chunks sub, sub+8, ... (8 bf16 each) of its row, for every selected expert
+  const float gam = p.gamma[layer];
+  const float sc = fp16_bits_to_f32(p.scale[layer]) / gam;
+  const int rs = p.rowsum[layer];
+#pragma unroll
+  for (int it = 0; it < GEMV_ITERS; ++it) {
+    const int row = row_base + it * 8 + rl;
+    const bool okr = row < p.N;
+    float yh = 0.0f;
+    if (p.r > 0) {
+      for (int j = 0; j < p.topk; ++j) {
+        const int e = p.idx[layer * p.topk + j];
+        const float gt = p.gate[layer * p.topk + j];
+        const uint16_t* brow = p.hpB + (((size_t)layer * p.E + e) * p.N + (okr ? row : 0)) * p.r;
+        const float* hh = p.h + ((size_t)layer * p.topk + j) * p.r;
+        float part = 0.0f;
+        for (int c = sub; c < p.r / 8; c += 8) {
+          const uint4 b = *reinterpret_cast<const uint4*>(brow + c * 8);
+          const float4 h0 = *reinterpret_cast<const float4*>(hh + c * 8);
+          const float4 h1 = *reinterpret_cast<const float4*>(hh + c * 8 + 4);
+          part += __uint_as_float(b.x << 16) * h0.x + __uint_as_float(b.x & 0xFFFF0000u) * h0.y;
+          part += __uint_as_float(b.y << 16) * h0.z + __uint_as_float(b.y & 0xFFFF0000u) * h0.w;
+          part += __uint_as_float(b.z << 16) * h1.x + __uint_as_float(b.z & 0xFFFF0000u) * h1.y;
+          part += __uint_as_float(b.w << 16) * h1.z + __uint_as_float(b.w & 0xFFFF0000u) * h1.w;
+        }
+        yh += gt * part;
+      }
+    }
+    int d = dot[it];
+#pragma unroll
+    for (int o = 4; o > 0; o >>= 1) {
+      d += __shfl_xor(d, o, 64);
+      yh += __shfl_xor(yh, o, 64);
+    }
+    if (sub == 0 && okr) {
+      const int acc = 2 * d - rs;
+      if (p.acc_out) p.acc_out[(size_t)layer * p.N + row] = acc;
+      const float y = __fmul_rn(sc, (float)acc) + p.alpha * yh;
+      p.Y[(size_t)layer * p.N + row] = f32_to_bf16(y);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Batch 2..16: int8 MFMA with {0,1} weight bytes expanded in registers.
+// ------------------------------------------------------------------------------------------
+struct gemm16_params {
+  const uint32_t* P;      // [L][N][K/32]
+  const uint16_t* scale;  // [L]
+  const int8_t* xq;       // [L][B][K]
+  const int* rowsum;      // [L][B]
+  const float* gamma;     // [L][B]
+  const uint16_t* hpB;    // [L][E][N][r]
+  const int* idx;         // [L][B][topk]
+  const float* gate;      // [L][B][topk]
+  const float* h;         // [L][B][topk][r]
+  uint16_t* Y;            // [L][B][N]
+  int* acc_out;           // [L][B][N] or null
+  int B, N, K, E, r, topk;
+  float alpha;
+};
+
+constexpr int G16_RT = 4;                           // 16-row MFMA tiles per wavefront
+constexpr int G16_ROWS_PER_WAVE = 16 * G16_RT;
+constexpr int G16_ROWS_PER_BLOCK = 4 * G16_ROWS_PER_WAVE;
+
+__device__ __forceinline__ uint32_t expand01(uint32_t nib) { return __umul24(nib, 0x00204081u) & 0x01010101u; }
+
+__global__ __launch_bounds__(256) void decode_gemm16_kernel(gemm16_params p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char dsm[];
+  // dsm: xq [16][K] int8 (16-byte chunk c of token j stored at chunk c ^ (j & 7)), then Hm [16][E*r] bf16
+  const int layer = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int K = p.K, Er = p.E * p.r;
+  unsigned char* xs = dsm;
+  uint16_t* hm = reinterpret_cast<uint16_t*>(dsm + 16 * (size_t)K);
+  const int kch = K / 16;
+  for (int c = tid; c < 16 * kch; c += 256) {
+    const int j = c / kch, cc = c % kch;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (j < p.B) v = *reinterpret_cast<const uint4*>(p.xq + ((size_t)layer * p.B + j) * K + cc * 16);
+    *reinterpret_cast<uint4*>(xs + (size_t)j * K + ((cc ^ (j & 7)) << 4)) = v;
+  }
+  for (int c = tid; c < 16 * Er / 8; c += 256) reinterpret_cast<uint4*>(hm)[c] = make_uint4(0, 0, 0, 0);
+  __syncthreads();
+  unsigned long long used = 0ull;
+  if (p.r > 0) {
+    for (int s = 0; s < p.B * p.topk; ++s) used |= 1ull << p.idx[(size_t)layer * p.B * p.topk + s];
+    for (int c = tid; c < p.B * p.topk * p.r; c += 256) {
+      const int rr = c % p.r, s = c / p.r, j = s / p.topk;
+      const int e = p.idx[(size_t)layer * p.B * p.topk + s];
+      const float v = p.gate[(size_t)layer * p.B * p.topk + s] * p.h[((size_t)layer * p.B * p.topk + s) * p.r + rr];
+      const int col = e * p.r + rr;                  // 16-byte chunk (col/8) stored at chunk ^ (j & 7)
+      hm[(size_t)j * Er + ((((col >> 3) ^ (j & 7)) << 3) | (col & 7))] = f32_to_bf16(v);
+    }
+  }
+  __syncthreads();
+
+  const int i = lane & 15, g = lane >> 4;
+  const int row0 = blockIdx.x * G16_ROWS_PER_BLOCK + wave * G16_ROWS_PER_WAVE;
+  if (row0 >= p.N) return;
+  const int nw = K / 32;
+  const uint32_t* P = p.P + (size_t)layer * p.N * nw;
+
+  i32x4_t acc[G16_RT];
+  f32x4_t accf[G16_RT];
+#pragma unroll
+  for (int t = 0; t < G16_RT; ++t) {
+    acc[t] = i32x4_t{0, 0, 0, 0};
+    accf[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  }
+  // 512 columns per step: lane (i, g) holds words 4g..4g+3 of the step for row 16 t + i; MFMA issue s
+  // consumes bits [16 s, 16 s + 16) of that 128-bit group, i.e. columns 512 c + 128 g + 16 s + [0,16),
+  // and the activation fragment is read from the same columns.
+  for (int c = 0; c < K / 512; ++c) {
+    uint4 w[G16_RT];
+#pragma unroll
+    for (int t = 0; t < G16_RT; ++t) {
+      const int row = row0 + 16 * t + i;
+      const bool ok = row < p.N;
+      const uint4 v = *reinterpret_cast<const uint4*>(P + (size_t)(ok ? row : 0) * nw + c * 16 + 4 * g);
+      const uint32_t m = ok ? 0xFFFFFFFFu : 0u;
+      w[t] = make_uint4(v.x & m, v.y & m, v.z & m, v.w & m);
+    }
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const int chunk = 32 * c + 8 * g + s;
+      const uint4 act = *reinterpret_cast<const uint4*>(xs + (size_t)i * K + ((chunk ^ (i & 7)) << 4));
+#pragma unroll
+      for (int t = 0; t < G16_RT; ++t) {
+        const uint32_t word = (s >> 1) == 0 ? w[t].x : (s >> 1) == 1 ? w[t].y : (s >> 1) == 2 ? w[t].z : w[t].w;
+        const uint32_t bits = (s & 1) ? (word >> 16) : (word & 0xFFFFu);
+        const uint4 ex = make_uint4(expand01(bits & 0xFu), expand01((bits >> 4) & 0xFu), expand01((bits >> 8) & 0xFu),
+                                    expand01((bits >> 12) & 0xFu));
+        acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4_t, ex), __builtin_bit_cast(i32x4_t, act),
+                                                       acc[t], 0, 0, 0);
+      }
+    }
+  }
+  // experts selected by at least one token of the batch: dense-masked bf16 MFMA, 32 columns of r per issue
+  if (p.r > 0) {
+    for (int e = 0; e < p.E; ++e) {
+      if (!((used >> e) & 1ull)) continue;
+      for (int hf = 0; hf < p.r / 32; ++hf) {
+        const int col = e * p.r + 32 * hf + 8 * g;
+        const uint4 bfrag = *reinterpret_cast<const uint4*>(hm + (size_t)i * Er + (((col >> 3) ^ (i & 7)) << 3));
+#pragma unroll
+        for (int t = 0; t < G16_RT; ++t) {
+          const int row = row0 + 16 * t + i;
+          const bool ok = row < p.N;
+          const uint4 v = *reinterpret_cast<const uint4*>(p.hpB + (((size_t)layer * p.E + e) * p.N + (ok ? row : 0)) * p.r + 32 * hf + 8 * g);
+          const uint32_t m = ok ? 0xFFFFFFFFu : 0u;
+          const uint4 afrag = make_uint4(v.x & m, v.y & m, v.z & m, v.w & m);
+          accf[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, afrag), __builtin_bit_cast(bf16x8_t, bfrag),
+                                                            accf[t], 0, 0, 0);
+        }
+      }
+    }
+  }
+  // D[row 4 g + v][token i]
+  const int j = i;
+  if (j < p.B) {
+    const float sc = fp16_bits_to_f32(p.scale[layer]) / p.gamma[layer * p.B + j];
+    const int rs = p.rowsum[layer * p.B + j];
+#pragma unroll
+    for (int t = 0; t < G16_RT; ++t) {
+      const int n0 = row0 + 16 * t + 4 * g;
+      if (n0 < p.N) {                                // N % 4 == 0: a group of four rows is all in or all out
+        float y[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int a = 2 * acc[t][v] - rs;
+          if (p.acc_out) p.acc_out[((size_t)layer * p.B + j) * p.N + n0 + v] = a;
+          y[v] = __fmul_rn(sc, (float)a) + p.alpha * accf[t][v];
+        }
+        *reinterpret_cast<uint2*>(p.Y + ((size_t)layer * p.B + j) * p.N + n0) =
+            make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+      }
+    }
+  }
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
+size_t pq_decode_ws_layout(const pq_decode_desc& d, size_t* off /* [7]: xq planes rowsum gamma idx gate h */) {
+  const size_t L = d.n_layers, B = d.batch, K = d.d_in;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t r = o; o = pq_align_up(o + bytes, 256); return r; };
+  off[0] = take(L * B * K);
+  off[1] = take(L * B * 8 * (K / 32) * sizeof(uint32_t));
+  off[2] = take(L * B * sizeof(int));
+  off[3] = take(L * B * sizeof(float));
+  off[4] = take(L * B * (size_t)d.top_k * sizeof(int));
+  off[5] = take(L * B * (size_t)d.top_k * sizeof(float));
+  off[6] = take(L * B * (size_t)d.top_k * d.hp_rank * sizeof(float));
+  return o;
+}
+
+int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* packed, const uint16_t* scale_fp16,
+                     const void* hpA, const void* hpB, const void* Wr, void* Y, int32_t* acc_out, void* workspace,
+                     hipStream_t s) {
+  size_t off[7];
+  pq_decode_ws_layout(d, off);
+  char* ws = (char*)workspace;
+  int8_t* xq = (int8_t*)(ws + off[0]);
+  uint32_t* planes = (uint32_t*)(ws + off[1]);
+  int* rowsum = (int*)(ws + off[2]);
+  float* gamma = (float*)(ws + off[3]);
+  int* idx = (int*)(ws + off[4]);
+  float* gate = (float*)(ws + off[5]);
+  float* h = (float*)(ws + off[6]);
+  const int L = d.n_layers, B = d.batch, K = d.d_in, N = d.d_out, r = d.hp_rank, E = r > 0 ? d.n_experts : 0;
+  {
+    pq_prof_scope prof(PQP_DECODE_PREP, s);
+    decode_prep_kernel<<<L * B, 256, 0, s>>>((const uint16_t*)X, (const uint16_t*)Wr, B, K, E, d.top_k, xq, planes, rowsum,
+                                            gamma, idx, gate);
+    PQ_CHECK_LAUNCH("decode_prep_kernel");
+    if (r > 0) {
+      const int total = L * B * d.top_k * r;
+      decode_h_kernel<<<(total + 3) / 4, 256, 0, s>>>((const uint16_t*)X, (const uint16_t*)hpA, idx, B, K, d.n_experts, r,
+                                                     d.top_k, total, h);
+      PQ_CHECK_LAUNCH("decode_h_kernel");
+    }
+  }
+  pq_prof_scope prof(PQP_DECODE_MAIN, s);
+  if (B == 1) {
+    gemv_params p{packed, scale_fp16, planes, rowsum, gamma, (const uint16_t*)hpB, idx, gate, h, (uint16_t*)Y, acc_out,
+                  N, K, d.n_experts, r, d.top_k, d.alpha};
+    dim3 grid((N + GEMV_ROWS_PER_BLOCK - 1) / GEMV_ROWS_PER_BLOCK, L);
+    decode_gemv_b1_kernel<<<grid, 256, 0, s>>>(p);
+    PQ_CHECK_LAUNCH("decode_gemv_b1_kernel");
+  } else {
+    gemm16_params p{packed, scale_fp16, xq, rowsum, gamma, (const uint16_t*)hpB, idx, gate, h, (uint16_t*)Y, acc_out,
+                    B, N, K, d.n_experts, r, d.top_k, d.alpha};
+    const size_t lds = 16 * (size_t)K + 32 * (size_t)d.n_experts * r;
+    static bool attr_set = false;
+    if (!attr_set) {
+      PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+      attr_set = true;
+    }
+    dim3 grid((N + G16_ROWS_PER_BLOCK - 1) / G16_ROWS_PER_BLOCK, L);
+    decode_gemm16_kernel<<<grid, 256, lds, s>>>(p);
+    PQ_CHECK_LAUNCH("decode_gemm16_kernel");
+  }
+  return PQ_OK;
+}

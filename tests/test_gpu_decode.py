@@ -1,0 +1,87 @@
+"""Parity of the packed-1-bit decode product (App. A) against the CPU oracle: int32 accumulators
+bit-exact, bf16 outputs within 2e-2 (max-norm relative)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pquant_oracle as po
+from paper_2602_22592_amd import binding as pq
+from paper_2602_22592_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(x, bf16=False):
+    t = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    return t.to(torch.bfloat16) if bf16 else t
+
+
+def relerr(a, b):
+    a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
+    return float(np.abs(a - b).max() / max(np.abs(b).max(), 1e-30))
+
+
+def run_decode(c, top_k, alpha, beta):
+    L, B, K, N, E, r = c["n_layers"], c["batch"], c["d_in"], c["d_out"], c["n_experts"], c["hp_rank"]
+    Ps, scales, mls = [], [], []
+    for l in range(L):                                   # offline: binarise + pack + fold beta*lambda to fp16
+        P, _, ml = pq.pack_sign(dev(c["W"][l], True))
+        Ps.append(P); mls.append(ml.cpu().numpy())
+        scales.append(np.float16(np.float32(beta) * mls[-1][1]))
+    P = torch.stack(Ps).contiguous()
+    scale = dev(np.array(scales, np.float16).view(np.int16))
+    desc = pq.DecodeDesc(B, K, N, r, E if r else 1, top_k if r else 1, L, alpha)
+    ws = pq.decode_workspace(desc)
+    X = dev(c["X"], True)
+    A = dev(c["A"], True) if r else None
+    Bm = dev(c["B"], True) if r else None
+    Wr = dev(c["Wr"], True) if r else None
+    Y = torch.empty((L, B, N), dtype=torch.bfloat16, device="cuda")
+    acc = torch.empty((L, B, N), dtype=torch.int32, device="cuda")
+    pq.decode_gemv(desc, X, P, scale, Y, ws, A=A, B=Bm, Wr=Wr, acc_out=acc)
+    torch.cuda.synchronize()
+    return Y.float().cpu().numpy(), acc.cpu().numpy(), P.cpu().numpy().view(np.uint32), mls
+
+
+def check_decode(c, top_k=2, alpha=2.0, beta=0.2):
+    Y, acc, P, mls = run_decode(c, top_k, alpha, beta)
+    r = c["hp_rank"]
+    worst = 0.0
+    for l in range(c["n_layers"]):
+        mu, lam = po.weight_stats(c["W"][l])
+        assert mls[l][0] == mu and mls[l][1] == lam
+        Pref = po.pack_sign(po.binarise(c["W"][l], mu))
+        assert np.array_equal(P[l], Pref)
+        f = po.decode_gemv(c["X"][l], Pref, (mu, lam), alpha, beta, A=c["A"][l] if r else None,
+                           B=c["B"][l] if r else None, Wr=c["Wr"][l] if r else None, top_k=top_k)
+        assert np.array_equal(acc[l].astype(np.int64), f["acc"]), f"layer {l}: int32 accumulators differ"
+        worst = max(worst, relerr(Y[l], f["Y"]))
+    print(f"  decode max-norm relative error {worst:.2e}", flush=True)
+    assert worst <= 2e-2
+
+
+@pytest.mark.parametrize("L,B,K,N,E,r,k", [(1, 1, 256, 136, 4, 16, 2), (2, 1, 4096, 1000, 8, 64, 2), (1, 1, 128, 64, 1, 0, 1),
+                                           (3, 1, 640, 328, 8, 8, 1), (1, 1, 8192, 260, 4, 24, 3)])
+def test_decode_gemv_batch1(L, B, K, N, E, r, k):
+    print(f"decode B=1: L={L} K={K} N={N} E={E} r={r} k={k}", flush=True)
+    check_decode(wl.decode_case(40 + K + N, B, d_in=K, d_out=N, n_experts=E, hp_rank=r, n_layers=L), top_k=k)
+
+
+@pytest.mark.parametrize("L,B,K,N,E,r,k", [(1, 3, 512, 200, 4, 32, 2), (2, 8, 1024, 1028, 8, 64, 2), (1, 16, 512, 64, 2, 32, 1),
+                                           (1, 2, 4096, 300, 1, 0, 1), (1, 5, 1536, 520, 8, 32, 3)])
+def test_decode_small_batch(L, B, K, N, E, r, k):
+    print(f"decode B={B}: L={L} K={K} N={N} E={E} r={r} k={k}", flush=True)
+    check_decode(wl.decode_case(50 + K + N + B, B, d_in=K, d_out=N, n_experts=E, hp_rank=r, n_layers=L), top_k=k)
+
+
+@pytest.mark.parametrize("B", [1, 8])
+def test_decode_config4_full_size(B):
+    """4096 -> 11008, E=8 top-2 experts of rank 64 (the bench shape), two layers."""
+    print(f"decode config 4, B={B}", flush=True)
+    check_decode(wl.decode_case(4, B, n_layers=2), top_k=2)
+
+
+def test_decode_alpha_zero_and_beta_edge():
+    c = wl.decode_case(60, 1, d_in=512, d_out=256, n_experts=4, hp_rank=16, n_layers=1)
+    check_decode(c, alpha=0.0, beta=0.7)
+    check_decode(c, alpha=1.5, beta=0.0)
