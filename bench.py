@@ -56,6 +56,52 @@ def cpu_baseline(sample_tokens):
             "sample": f"first {sample_tokens} tokens of the workload, fwd+bwd, {dt:.1f} s"}
 
 
+def decode_bench(pq, torch, batch, n_layers=64, steps=20, warmup=3):
+    """Packed-1-bit decode product, 4096 -> 11008 with E=8 top-2 rank-64 bf16 experts, over
+    `n_layers` distinct weight sets per launch (361 MB of bits: larger than the Infinity Cache)."""
+    K, N, E, r, k = 4096, 11008, 8, 64, 2
+    g = torch.Generator(device="cuda").manual_seed(4)
+    bf = torch.bfloat16
+    P = torch.randint(-2**31, 2**31 - 1, (n_layers, N, K // 32), dtype=torch.int32, device="cuda", generator=g)
+    X = torch.randn((n_layers, batch, K), device="cuda", generator=g).to(bf)
+    A = (torch.randn((n_layers, E, r, K), device="cuda", generator=g) * 0.02).to(bf)
+    Bm = (torch.randn((n_layers, E, N, r), device="cuda", generator=g) * 0.02).to(bf)
+    Wr = (torch.randn((n_layers, E, K), device="cuda", generator=g) * 0.02).to(bf)
+    scale = torch.from_numpy(np.full(n_layers, np.float16(0.2 * 0.016)).view(np.int16)).cuda()
+    Y = torch.empty((n_layers, batch, N), dtype=bf, device="cuda")
+    tiled = batch == 1        # batch 1 streams the row-interleaved packing (re-tiled offline)
+    if tiled:
+        P = torch.stack([pq.pack_retile64(P[l], K) for l in range(n_layers)]).contiguous()
+    desc = pq.DecodeDesc(batch, K, N, r, E, k, n_layers, pq.PQ_PACKED_TILED64 if tiled else pq.PQ_PACKED_ROWMAJOR, 2.0)
+    ws = pq.decode_workspace(desc)
+    run = lambda: pq.decode_gemv(desc, X, P, scale, Y, ws, A=A, B=Bm, Wr=Wr)
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    pq.prof_reset(); pq.prof_enable(True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    pq.prof_enable(False)
+    prof = pq.prof_read(); pq.prof_reset()
+    main_us = 1e3 * prof["decode_main"][0] / prof["decode_main"][1]
+    prep_us = 1e3 * prof["decode_prep"][0] / prof["decode_prep"][1]
+    h_us = 1e3 * prof["decode_h"][0] / prof["decode_h"][1]
+    total_us = 1e3 * e0.elapsed_time(e1) / steps
+    # algorithmic bytes of the main kernel per layer: packed bits + the selected experts' B rows + x, y
+    n_sel = k if batch == 1 else min(E, batch * k)          # upper bound on distinct experts per layer
+    main_bytes = n_layers * (N * K // 8 + n_sel * N * r * 2 + batch * (K + 2 * N))
+    prep_bytes = n_layers * (batch * (2 * K + k * r * K * 2) + E * K * 2)
+    return {"batch": batch, "layers_per_launch": n_layers, "main_kernel_us": round(main_us, 2),
+            "prep_kernel_us": round(prep_us, 2), "h_kernel_us": round(h_us, 2), "launch_us": round(total_us, 2),
+            "main_kernel_GBps": round(main_bytes / main_us / 1e3, 1), "main_kernel_frac_hbm": round(main_bytes / main_us / 1e3 / 8000.0, 4),
+            "whole_call_GBps": round((main_bytes + prep_bytes) / total_us / 1e3, 1),
+            "us_per_layer": round(total_us / n_layers, 3), "bytes_per_layer": (main_bytes + prep_bytes) // n_layers}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -64,6 +110,7 @@ def main():
     ap.add_argument("--tokens", type=int, default=8192)
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -138,6 +185,9 @@ def main():
         "roofline": roofline,
         "kernels_us": {k: round(v["avg_us"], 2) for k, v in sorted(kernels.items())},
     }
+    if not args.no_decode:
+        out["decode_gemv"] = {"metric": "1-bit decode GEMV HBM GB/s (4096->11008, E=8 top-2 r=64 experts)",
+                              "B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample_tokens)
     print(json.dumps(out), flush=True)

@@ -137,6 +137,10 @@ int pq_linear_bwd(const pq_linear_desc* desc, const void* dY, const void* X, con
  *   Y [L][B][N] bf16 out;  acc_out [L][B][N] int32 out or NULL (the exact accumulators, for tests).
  * Limits: 1 <= B <= 16; K % 128 == 0 (B == 1) or K % 512 == 0 (B > 1); N % 4 == 0; r % 8 == 0
  * (B == 1) or r % 32 == 0 and (E r) % 64 == 0 (B > 1); 16 K + 32 E r <= 160 KiB for B > 1. */
+typedef enum pq_packed_layout {
+  PQ_PACKED_ROWMAJOR = 0, /* [N][K/32], as written by pq_pack_sign */
+  PQ_PACKED_TILED64 = 1   /* [ceil(N/64)][K/128][64][4]: rows interleaved by 64 (pq_pack_retile64); batch 1 only */
+} pq_packed_layout;
 typedef struct pq_decode_desc {
   int32_t batch;     /* B, tokens per layer */
   int32_t d_in;      /* K */
@@ -145,9 +149,16 @@ typedef struct pq_decode_desc {
   int32_t n_experts; /* E */
   int32_t top_k;     /* experts per token */
   int32_t n_layers;  /* L */
+  int32_t packed_layout; /* pq_packed_layout of `packed` */
   float alpha;
 } pq_decode_desc;
 size_t pq_decode_workspace_bytes(const pq_decode_desc* desc);
+/* Offline re-tiling for batch-1 decode: packed [N][K/32] -> tiled, pq_pack_tiled64_bytes(N, K) bytes, word
+ * (row, w) stored at (((row/64) * (K/128) + w/4) * 64 + row%64) * 4 + w%4, rows padded with zeros to a
+ * multiple of 64.  In this order a wavefront reads 1 KiB of contiguous memory per load and every
+ * lane owns one output row.  K % 128 == 0. */
+size_t pq_pack_tiled64_bytes(int32_t N, int32_t K);
+int pq_pack_retile64(const uint32_t* packed, int32_t N, int32_t K, uint32_t* tiled, void* stream);
 int pq_decode_gemv(const pq_decode_desc* desc, const void* X, const uint32_t* packed, const uint16_t* scale_fp16,
                    const void* hpA, const void* hpB, const void* Wr, void* Y, int32_t* acc_out, void* workspace,
                    size_t workspace_bytes, void* stream);

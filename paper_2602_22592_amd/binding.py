@@ -17,12 +17,13 @@ LIB_PATH = os.path.join(_HERE, "libpquant.so")
 PQ_F32, PQ_BF16 = 0, 1
 PQ_W_MASTER, PQ_W_PACKED = 0, 1
 PQ_STE_IDENTITY, PQ_STE_CLIP = 0, 1
+PQ_PACKED_ROWMAJOR, PQ_PACKED_TILED64 = 0, 1
 
 EXPORTS = [
     "pq_version", "pq_last_error_string", "pq_quant_act", "pq_pack_workspace_bytes", "pq_pack_sign",
     "pq_router_topk", "pq_onebit_acc", "pq_linear_ctx_bytes", "pq_linear_workspace_bytes",
     "pq_linear_fwd", "pq_linear_bwd", "pq_prof_enable", "pq_prof_count", "pq_prof_label", "pq_prof_read",
-    "pq_prof_reset", "pq_decode_workspace_bytes", "pq_decode_gemv",
+    "pq_prof_reset", "pq_decode_workspace_bytes", "pq_decode_gemv", "pq_pack_tiled64_bytes", "pq_pack_retile64",
 ]
 
 
@@ -34,7 +35,8 @@ class LinearDesc(C.Structure):
 
 class DecodeDesc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("d_in", C.c_int32), ("d_out", C.c_int32), ("hp_rank", C.c_int32),
-                ("n_experts", C.c_int32), ("top_k", C.c_int32), ("n_layers", C.c_int32), ("alpha", C.c_float)]
+                ("n_experts", C.c_int32), ("top_k", C.c_int32), ("n_layers", C.c_int32),
+                ("packed_layout", C.c_int32), ("alpha", C.c_float)]
 
 
 class PQError(RuntimeError):
@@ -54,7 +56,7 @@ def lib():
         L.pq_last_error_string.restype = C.c_char_p
         L.pq_prof_label.restype = C.c_char_p
         for name in ("pq_pack_workspace_bytes", "pq_linear_ctx_bytes", "pq_linear_workspace_bytes",
-                     "pq_decode_workspace_bytes"):
+                     "pq_decode_workspace_bytes", "pq_pack_tiled64_bytes"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -189,3 +191,14 @@ def decode_gemv(desc, X, packed, scale_fp16, Y, ws, A=None, B=None, Wr=None, acc
     _check(lib().pq_decode_gemv(C.byref(desc), _p(X), _p(packed), _p(scale_fp16), _p(A), _p(B), _p(Wr), _p(Y),
                                 _p(acc_out), _p(ws), C.c_size_t(ws.numel()), _stream()))
     return Y
+
+
+def pack_retile64(P, K):
+    """Row-major packed words [N][K/32] -> the row-interleaved order used by batch-1 decode."""
+    N = P.shape[0]
+    n = lib().pq_pack_tiled64_bytes(N, K)
+    if n == 0:
+        raise PQError("pq_pack_tiled64_bytes: bad shape")
+    T = torch.empty((n // 4,), dtype=torch.int32, device=P.device)
+    _check(lib().pq_pack_retile64(_p(P), N, K, _p(T), _stream()))
+    return T

@@ -30,7 +30,7 @@ std::vector<prof_sample*> g_prof_samples;
 const char* const g_prof_names[PQP_COUNT] = {
     "quant_act", "wstats_partial", "pack_sign", "router", "reduce_partials",
     "gemm_onebit_fwd", "gemm_hp_H", "gemm_hp_Y", "gemm_dH", "gemm_dX", "gemm_dX_hp",
-    "gemm_dW", "gemm_dB", "gemm_dA", "gemm_other", "decode_prep", "decode_main"};
+    "gemm_dW", "gemm_dB", "gemm_dA", "gemm_other", "decode_prep", "decode_h", "decode_main"};
 }  // namespace
 
 pq_prof_scope::pq_prof_scope(int label_, hipStream_t s_) : label(label_), s(s_), slot(nullptr) {
@@ -422,6 +422,9 @@ int check_decode(const pq_decode_desc* d) {
   PQ_REQUIRE(d->batch >= 1 && d->batch <= 16, PQ_ERR_BAD_ARG, "batch=%d must be in 1..16", d->batch);
   PQ_REQUIRE(d->d_in > 0 && d->d_out > 0 && d->hp_rank >= 0 && d->n_layers >= 1, PQ_ERR_BAD_ARG, "bad dimension");
   PQ_REQUIRE(d->d_out % 4 == 0, PQ_ERR_SHAPE, "d_out=%d must be a multiple of 4", d->d_out);
+  PQ_REQUIRE(d->d_in <= 16384, PQ_ERR_SHAPE, "d_in=%d exceeds 16384 (one token's activations are staged in LDS)", d->d_in);
+  PQ_REQUIRE(d->packed_layout == PQ_PACKED_ROWMAJOR || (d->packed_layout == PQ_PACKED_TILED64 && d->batch == 1),
+             PQ_ERR_BAD_ARG, "packed_layout=%d is not valid for batch=%d", d->packed_layout, d->batch);
   if (d->batch == 1) {
     PQ_REQUIRE(d->d_in % 128 == 0, PQ_ERR_SHAPE, "d_in=%d must be a multiple of 128", d->d_in);
     PQ_REQUIRE(d->hp_rank % 8 == 0, PQ_ERR_SHAPE, "hp_rank=%d must be a multiple of 8", d->hp_rank);
@@ -466,4 +469,17 @@ extern "C" int pq_decode_gemv(const pq_decode_desc* d, const void* X, const uint
   const size_t need = pq_decode_ws_layout(dd, off);
   PQ_REQUIRE(workspace_bytes >= need, PQ_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, need);
   return pq_launch_decode(dd, X, packed, scale_fp16, hpA, hpB, Wr, Y, acc_out, workspace, (hipStream_t)stream);
+}
+
+extern "C" size_t pq_pack_tiled64_bytes(int32_t N, int32_t K) {
+  if (N <= 0 || K <= 0 || K % 128 != 0) return 0;
+  return (size_t)((N + 63) / 64) * 64 * (K / 32) * sizeof(uint32_t);
+}
+
+extern "C" int pq_pack_retile64(const uint32_t* packed, int32_t N, int32_t K, uint32_t* tiled, void* stream) {
+  PQ_REQUIRE(N > 0 && K > 0, PQ_ERR_BAD_ARG, "bad size N=%d K=%d", N, K);
+  PQ_REQUIRE(K % 128 == 0, PQ_ERR_SHAPE, "K=%d must be a multiple of 128", K);
+  PQ_REQUIRE(packed && tiled, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(aligned16(packed) && aligned16(tiled), PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
+  return pq_launch_retile64(packed, N, K, tiled, (hipStream_t)stream);
 }

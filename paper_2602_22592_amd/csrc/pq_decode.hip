@@ -34,18 +34,28 @@ __global__ __launch_bounds__(256) void decode_prep_kernel(const uint16_t* __rest
                                                           uint32_t* __restrict__ planes, int* __restrict__ rowsum,
                                                           float* __restrict__ gamma, int* __restrict__ idx,
                                                           float* __restrict__ gate) {
+  extern __shared__ __attribute__((aligned(16))) float xs[];   // the token's activations as fp32 [K]
   __shared__ float s_red[4];
-  __shared__ double s_dred[4];
+  __shared__ double s_dred[4][8];
   __shared__ float s_gamma;
   __shared__ int s_isum[4];
   __shared__ double s_logit[64];
   const int tok = blockIdx.x;            // layer * B + b
   const int layer = tok / B;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const uint16_t* x = X + (size_t)tok * K;
+  const uint4* x4 = reinterpret_cast<const uint4*>(X + (size_t)tok * K);
 
   float amax = 0.0f;
-  for (int k = tid; k < K; k += 256) amax = fmaxf(amax, fabsf(bf16_to_f32(x[k])));
+  for (int c = tid; c < K / 8; c += 256) {
+    const uint4 u = x4[c];
+    const float f[8] = {__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u), __uint_as_float(u.y << 16),
+                        __uint_as_float(u.y & 0xFFFF0000u), __uint_as_float(u.z << 16), __uint_as_float(u.z & 0xFFFF0000u),
+                        __uint_as_float(u.w << 16), __uint_as_float(u.w & 0xFFFF0000u)};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(f[j]));
+    *reinterpret_cast<float4*>(xs + 8 * c) = make_float4(f[0], f[1], f[2], f[3]);
+    *reinterpret_cast<float4*>(xs + 8 * c + 4) = make_float4(f[4], f[5], f[6], f[7]);
+  }
   amax = wave_max(amax);
   if (lane == 0) s_red[wave] = amax;
   __syncthreads();
@@ -58,21 +68,19 @@ __global__ __launch_bounds__(256) void decode_prep_kernel(const uint16_t* __rest
   __syncthreads();
   const float g = s_gamma;
 
-  // codes, bit planes (one thread per 32 columns) and the row sum
+  // codes, bit planes and the row sum: lane <-> column, a wave-wide ballot per bit plane yields two words
   int isum = 0;
-  for (int w = tid; w < K / 32; w += 256) {
-    uint32_t pl[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int j = 0; j < 32; ++j) {
-      float y = __fmul_rn(bf16_to_f32(x[32 * w + j]), g);
-      float r = fminf(fmaxf(rintf(y), -128.0f), 127.0f);
-      const int q = (int)r;
-      xq[(size_t)tok * K + 32 * w + j] = (int8_t)q;
-      isum += q;
+  for (int k0 = wave * 64; k0 < K; k0 += 256) {
+    const float y = __fmul_rn(xs[k0 + lane], g);
+    const float r = fminf(fmaxf(rintf(y), -128.0f), 127.0f);
+    const int q = (int)r;
+    xq[(size_t)tok * K + k0 + lane] = (int8_t)q;
+    isum += q;
 #pragma unroll
-      for (int p = 0; p < 8; ++p) pl[p] |= (((uint32_t)q >> p) & 1u) << j;
+    for (int p = 0; p < 8; ++p) {
+      const unsigned long long m = __ballot(((uint32_t)q >> p) & 1u);
+      if (lane < 2) planes[((size_t)tok * 8 + p) * (K / 32) + (k0 >> 5) + lane] = (uint32_t)(m >> (32 * lane));
     }
-#pragma unroll
-    for (int p = 0; p < 8; ++p) planes[((size_t)tok * 8 + p) * (K / 32) + w] = pl[p];
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) isum += __shfl_xor(isum, o, 64);
@@ -81,16 +89,32 @@ __global__ __launch_bounds__(256) void decode_prep_kernel(const uint16_t* __rest
   if (tid == 0) rowsum[tok] = s_isum[0] + s_isum[1] + s_isum[2] + s_isum[3];
 
   if (E <= 0) return;
-  // router: fp64 logits rounded once to fp32, top-k on logits (ties to the lower index), softmax gates
-  for (int e = 0; e < E; ++e) {
-    const uint16_t* wr = Wr + ((size_t)layer * E + e) * K;
-    double acc = 0.0;
-    for (int k = tid; k < K; k += 256) acc += (double)bf16_to_f32(x[k]) * (double)bf16_to_f32(wr[k]);
-    acc = wave_sum_d(acc);
+  // router: fp64 logits rounded once to fp32, top-k on logits (ties to the lower index), softmax gates;
+  // eight experts per pass over x
+  for (int e0 = 0; e0 < E; e0 += 8) {
+    double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int c = tid; c < K / 8; c += 256) {
+      const float4 xa = *reinterpret_cast<const float4*>(xs + 8 * c), xb = *reinterpret_cast<const float4*>(xs + 8 * c + 4);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (e0 + u < E) {
+          const uint4 w = reinterpret_cast<const uint4*>(Wr + ((size_t)layer * E + e0 + u) * K)[c];
+          acc[u] += (double)xa.x * (double)__uint_as_float(w.x << 16) + (double)xa.y * (double)__uint_as_float(w.x & 0xFFFF0000u);
+          acc[u] += (double)xa.z * (double)__uint_as_float(w.y << 16) + (double)xa.w * (double)__uint_as_float(w.y & 0xFFFF0000u);
+          acc[u] += (double)xb.x * (double)__uint_as_float(w.z << 16) + (double)xb.y * (double)__uint_as_float(w.z & 0xFFFF0000u);
+          acc[u] += (double)xb.z * (double)__uint_as_float(w.w << 16) + (double)xb.w * (double)__uint_as_float(w.w & 0xFFFF0000u);
+        }
+      }
+    }
     __syncthreads();
-    if (lane == 0) s_dred[wave] = acc;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const double t = wave_sum_d(acc[u]);
+      if (lane == 0) s_dred[wave][u] = t;
+    }
     __syncthreads();
-    if (tid == 0) s_logit[e] = (double)(float)(s_dred[0] + s_dred[1] + s_dred[2] + s_dred[3]);
+    if (tid < 8 && e0 + tid < E)
+      s_logit[e0 + tid] = (double)(float)(s_dred[0][tid] + s_dred[1][tid] + s_dred[2][tid] + s_dred[3][tid]);
   }
   __syncthreads();
   if (tid == 0) {
@@ -257,6 +281,99 @@ __global__ __launch_bounds__(256) void decode_gemv_b1_kernel(gemv_params p) {
       p.Y[(size_t)layer * p.N + row] = f32_to_bf16(y);
     }
   }
+}
+
+// ------------------------------------------------------------------------------------------
+// Batch 1 on the row-interleaved packing (PQ_PACKED_TILED64): rows are grouped by 64 and stored as
+// [group][word/4][row % 64][word % 4], so lane l of a wavefront owns row 64 g + l and a wave-wide
+// 16-byte load is 1 KiB of contiguous HBM.  The activation bit planes are then the same for all
+// lanes: they are fetched with scalar loads and used as scalar operands, no cross-lane reduction is
+// needed, and a lane needs only its weight words and 8 counters in VGPRs, so many waves are
+// resident and many loads are in flight.  The 4 wavefronts of a workgroup split the columns.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void decode_gemv_tiled_kernel(gemv_params p) {
+  __shared__ int s_dot[4][64];
+  __shared__ float s_yh[4][64];
+  const int layer = blockIdx.y, grp = blockIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int nw = p.K / 32, nq = nw / 4;
+  const int G = (p.N + 63) / 64;
+  const uint4* __restrict__ Pg = reinterpret_cast<const uint4*>(p.P) + ((size_t)layer * G + grp) * nq * 64;
+  const uint32_t* __restrict__ planes = p.planes + (size_t)layer * 8 * nw;
+  const int row = grp * 64 + lane;
+  const bool okr = row < p.N;
+
+  int a[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int q0 = 0; q0 < nq; q0 += 32) {
+    uint4 w[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int q = q0 + 4 * i + wave;
+      w[i] = (q < nq) ? Pg[(size_t)q * 64 + lane] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int q = q0 + 4 * i + wave;
+      if (q < nq) {                                   // wave-uniform
+        const uint32_t ww[4] = {w[i].x, w[i].y, w[i].z, w[i].w};
+#pragma unroll
+        for (int pp = 0; pp < 8; ++pp) {
+          const uint32_t* pl = planes + (size_t)pp * nw + 4 * q;   // uniform address: scalar loads
+#pragma unroll
+          for (int j = 0; j < 4; ++j) a[pp] += __builtin_popcount(ww[j] & pl[j]);
+        }
+      }
+    }
+  }
+  int d = 0;
+#pragma unroll
+  for (int pp = 0; pp < 7; ++pp) d += a[pp] << pp;
+  d -= a[7] << 7;
+
+  float yh = 0.0f;
+  if (p.r > 0) {
+    for (int j = 0; j < p.topk; ++j) {
+      const int e = p.idx[layer * p.topk + j];
+      const float gt = p.gate[layer * p.topk + j];
+      const uint16_t* brow = p.hpB + (((size_t)layer * p.E + e) * p.N + (okr ? row : 0)) * p.r;
+      const float* __restrict__ hh = p.h + ((size_t)layer * p.topk + j) * p.r;
+      float part = 0.0f;
+      for (int c = wave; c < p.r / 8; c += 4) {       // the 4 wavefronts split the expert's rank
+        const uint4 b = *reinterpret_cast<const uint4*>(brow + c * 8);
+        const float* h8 = hh + c * 8;                 // uniform
+        part += __uint_as_float(b.x << 16) * h8[0] + __uint_as_float(b.x & 0xFFFF0000u) * h8[1];
+        part += __uint_as_float(b.y << 16) * h8[2] + __uint_as_float(b.y & 0xFFFF0000u) * h8[3];
+        part += __uint_as_float(b.z << 16) * h8[4] + __uint_as_float(b.z & 0xFFFF0000u) * h8[5];
+        part += __uint_as_float(b.w << 16) * h8[6] + __uint_as_float(b.w & 0xFFFF0000u) * h8[7];
+      }
+      yh += gt * part;
+    }
+  }
+  s_dot[wave][lane] = d;
+  s_yh[wave][lane] = yh;
+  __syncthreads();
+  if (wave == 0 && okr) {
+    const int dd = s_dot[0][lane] + s_dot[1][lane] + s_dot[2][lane] + s_dot[3][lane];
+    const float yy = (s_yh[0][lane] + s_yh[1][lane]) + (s_yh[2][lane] + s_yh[3][lane]);
+    const int acc = 2 * dd - p.rowsum[layer];
+    if (p.acc_out) p.acc_out[(size_t)layer * p.N + row] = acc;
+    const float sc = fp16_bits_to_f32(p.scale[layer]) / p.gamma[layer];
+    p.Y[(size_t)layer * p.N + row] = f32_to_bf16(__fmul_rn(sc, (float)acc) + p.alpha * yy);
+  }
+}
+
+// Offline re-tiling of the row-major packing [N][K/32] into the row-interleaved one (rows padded to 64).
+__global__ __launch_bounds__(256) void retile64_kernel(const uint32_t* __restrict__ P, int N, int nw, uint32_t* __restrict__ T,
+                                                       size_t total) {
+  const size_t o = (size_t)blockIdx.x * 256 + threadIdx.x;   // ((g*nq + q)*64 + lane)*4 + j
+  if (o >= total) return;
+  const int j = o & 3, lane = (o >> 2) & 63;
+  const size_t gq = o >> 8;
+  const int nq = nw / 4;
+  const int q = (int)(gq % nq), g = (int)(gq / nq);
+  const int row = g * 64 + lane;
+  T[o] = row < N ? P[(size_t)row * nw + 4 * q + j] : 0u;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -431,10 +548,13 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
   const int L = d.n_layers, B = d.batch, K = d.d_in, N = d.d_out, r = d.hp_rank, E = r > 0 ? d.n_experts : 0;
   {
     pq_prof_scope prof(PQP_DECODE_PREP, s);
-    decode_prep_kernel<<<L * B, 256, 0, s>>>((const uint16_t*)X, (const uint16_t*)Wr, B, K, E, d.top_k, xq, planes, rowsum,
+    decode_prep_kernel<<<L * B, 256, (size_t)K * sizeof(float), s>>>((const uint16_t*)X, (const uint16_t*)Wr, B, K, E, d.top_k, xq, planes, rowsum,
                                             gamma, idx, gate);
     PQ_CHECK_LAUNCH("decode_prep_kernel");
-    if (r > 0) {
+  }
+  if (r > 0) {
+    {
+      pq_prof_scope prof(PQP_DECODE_H, s);
       const int total = L * B * d.top_k * r;
       decode_h_kernel<<<(total + 3) / 4, 256, 0, s>>>((const uint16_t*)X, (const uint16_t*)hpA, idx, B, K, d.n_experts, r,
                                                      d.top_k, total, h);
@@ -445,9 +565,15 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
   if (B == 1) {
     gemv_params p{packed, scale_fp16, planes, rowsum, gamma, (const uint16_t*)hpB, idx, gate, h, (uint16_t*)Y, acc_out,
                   N, K, d.n_experts, r, d.top_k, d.alpha};
-    dim3 grid((N + GEMV_ROWS_PER_BLOCK - 1) / GEMV_ROWS_PER_BLOCK, L);
-    decode_gemv_b1_kernel<<<grid, 256, 0, s>>>(p);
-    PQ_CHECK_LAUNCH("decode_gemv_b1_kernel");
+    if (d.packed_layout == PQ_PACKED_TILED64) {
+      dim3 grid((N + 63) / 64, L);
+      decode_gemv_tiled_kernel<<<grid, 256, 0, s>>>(p);
+      PQ_CHECK_LAUNCH("decode_gemv_tiled_kernel");
+    } else {
+      dim3 grid((N + GEMV_ROWS_PER_BLOCK - 1) / GEMV_ROWS_PER_BLOCK, L);
+      decode_gemv_b1_kernel<<<grid, 256, 0, s>>>(p);
+      PQ_CHECK_LAUNCH("decode_gemv_b1_kernel");
+    }
   } else {
     gemm16_params p{packed, scale_fp16, xq, rowsum, gamma, (const uint16_t*)hpB, idx, gate, h, (uint16_t*)Y, acc_out,
                     B, N, K, d.n_experts, r, d.top_k, d.alpha};
@@ -461,5 +587,13 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
     decode_gemm16_kernel<<<grid, 256, lds, s>>>(p);
     PQ_CHECK_LAUNCH("decode_gemm16_kernel");
   }
+  return PQ_OK;
+}
+
+int pq_launch_retile64(const uint32_t* packed, int N, int K, uint32_t* tiled, hipStream_t s) {
+  const int nw = K / 32;
+  const size_t total = (size_t)((N + 63) / 64) * 64 * nw;
+  retile64_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(packed, N, nw, tiled, total);
+  PQ_CHECK_LAUNCH("retile64_kernel");
   return PQ_OK;
 }

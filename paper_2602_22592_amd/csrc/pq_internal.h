@@ -6,7 +6,7 @@
 enum pq_prof_id {
   PQP_QUANT = 0, PQP_WSTATS, PQP_PACK, PQP_ROUTER, PQP_REDUCE,
   PQP_GEMM_ONEBIT, PQP_GEMM_HP_H, PQP_GEMM_HP_Y, PQP_GEMM_DH, PQP_GEMM_DX, PQP_GEMM_DX_HP,
-  PQP_GEMM_DW, PQP_GEMM_DB, PQP_GEMM_DA, PQP_GEMM_OTHER, PQP_DECODE_PREP, PQP_DECODE_MAIN, PQP_COUNT
+  PQP_GEMM_DW, PQP_GEMM_DB, PQP_GEMM_DA, PQP_GEMM_OTHER, PQP_DECODE_PREP, PQP_DECODE_H, PQP_DECODE_MAIN, PQP_COUNT
 };
 struct pq_prof_scope {   // records an event pair around the launches made while it is alive
   int label; hipStream_t s; void* slot;
@@ -97,3 +97,4 @@ size_t pq_decode_ws_layout(const pq_decode_desc& d, size_t* off);
 int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* packed, const uint16_t* scale_fp16,
                      const void* hpA, const void* hpB, const void* Wr, void* Y, int32_t* acc_out, void* workspace,
                      hipStream_t s);
+int pq_launch_retile64(const uint32_t* packed, int N, int K, uint32_t* tiled, hipStream_t s);

@@ -21,7 +21,7 @@ def relerr(a, b):
     return float(np.abs(a - b).max() / max(np.abs(b).max(), 1e-30))
 
 
-def run_decode(c, top_k, alpha, beta):
+def run_decode(c, top_k, alpha, beta, tiled=False):
     L, B, K, N, E, r = c["n_layers"], c["batch"], c["d_in"], c["d_out"], c["n_experts"], c["hp_rank"]
     Ps, scales, mls = [], [], []
     for l in range(L):                                   # offline: binarise + pack + fold beta*lambda to fp16
@@ -29,8 +29,10 @@ def run_decode(c, top_k, alpha, beta):
         Ps.append(P); mls.append(ml.cpu().numpy())
         scales.append(np.float16(np.float32(beta) * mls[-1][1]))
     P = torch.stack(Ps).contiguous()
+    Pin = torch.stack([pq.pack_retile64(p_, K) for p_ in Ps]).contiguous() if tiled else P
     scale = dev(np.array(scales, np.float16).view(np.int16))
-    desc = pq.DecodeDesc(B, K, N, r, E if r else 1, top_k if r else 1, L, alpha)
+    desc = pq.DecodeDesc(B, K, N, r, E if r else 1, top_k if r else 1, L,
+                         pq.PQ_PACKED_TILED64 if tiled else pq.PQ_PACKED_ROWMAJOR, alpha)
     ws = pq.decode_workspace(desc)
     X = dev(c["X"], True)
     A = dev(c["A"], True) if r else None
@@ -38,13 +40,13 @@ def run_decode(c, top_k, alpha, beta):
     Wr = dev(c["Wr"], True) if r else None
     Y = torch.empty((L, B, N), dtype=torch.bfloat16, device="cuda")
     acc = torch.empty((L, B, N), dtype=torch.int32, device="cuda")
-    pq.decode_gemv(desc, X, P, scale, Y, ws, A=A, B=Bm, Wr=Wr, acc_out=acc)
+    pq.decode_gemv(desc, X, Pin, scale, Y, ws, A=A, B=Bm, Wr=Wr, acc_out=acc)
     torch.cuda.synchronize()
     return Y.float().cpu().numpy(), acc.cpu().numpy(), P.cpu().numpy().view(np.uint32), mls
 
 
-def check_decode(c, top_k=2, alpha=2.0, beta=0.2):
-    Y, acc, P, mls = run_decode(c, top_k, alpha, beta)
+def check_decode(c, top_k=2, alpha=2.0, beta=0.2, tiled=False):
+    Y, acc, P, mls = run_decode(c, top_k, alpha, beta, tiled)
     r = c["hp_rank"]
     worst = 0.0
     for l in range(c["n_layers"]):
@@ -62,9 +64,11 @@ def check_decode(c, top_k=2, alpha=2.0, beta=0.2):
 
 @pytest.mark.parametrize("L,B,K,N,E,r,k", [(1, 1, 256, 136, 4, 16, 2), (2, 1, 4096, 1000, 8, 64, 2), (1, 1, 128, 64, 1, 0, 1),
                                            (3, 1, 640, 328, 8, 8, 1), (1, 1, 8192, 260, 4, 24, 3)])
-def test_decode_gemv_batch1(L, B, K, N, E, r, k):
-    print(f"decode B=1: L={L} K={K} N={N} E={E} r={r} k={k}", flush=True)
-    check_decode(wl.decode_case(40 + K + N, B, d_in=K, d_out=N, n_experts=E, hp_rank=r, n_layers=L), top_k=k)
+@pytest.mark.parametrize("tiled", [False, True])
+def test_decode_gemv_batch1(L, B, K, N, E, r, k, tiled):
+    print(f"decode B=1: L={L} K={K} N={N} E={E} r={r} k={k} tiled={tiled}", flush=True)
+    check_decode(wl.decode_case(40 + K + N, B, d_in=K, d_out=N, n_experts=E, hp_rank=r, n_layers=L), top_k=k,
+                 tiled=tiled)
 
 
 @pytest.mark.parametrize("L,B,K,N,E,r,k", [(1, 3, 512, 200, 4, 32, 2), (2, 8, 1024, 1028, 8, 64, 2), (1, 16, 512, 64, 2, 32, 1),
@@ -78,7 +82,7 @@ def test_decode_small_batch(L, B, K, N, E, r, k):
 def test_decode_config4_full_size(B):
     """4096 -> 11008, E=8 top-2 experts of rank 64 (the bench shape), two layers."""
     print(f"decode config 4, B={B}", flush=True)
-    check_decode(wl.decode_case(4, B, n_layers=2), top_k=2)
+    check_decode(wl.decode_case(4, B, n_layers=2), top_k=2, tiled=(B == 1))
 
 
 def test_decode_alpha_zero_and_beta_edge():
