@@ -125,6 +125,32 @@ int pq_linear_bwd(const pq_linear_desc* desc, const void* dY, const void* X, con
                   void* dX, float* dW, float* dhpA, float* dhpB, float* dWr, float* dalpha_dbeta,
                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* The decoupled FFN (Sec. 3.2 FFN equation; Sec. 3.3):
+ *     Y = beta * FFN_1bit(X) + alpha * sum_j gate_j(X) * FFN_e_j(X)
+ * FFN_1bit: U = L_up(Q(X)), G = L_gate(Q(X)) (pure 1-bit linears, Sec. 3.1), Hd = silu(G) * U,
+ * Y1 = L_down(Q(Hd)); U and G are stored in bf16, Hd is formed in fp32 and re-quantised per token.
+ * FFN_e: gated bf16 expert of hidden width r, Down_e (silu(Gate_e x) * Up_e x); the router of
+ * pq_router_topk picks top_k experts per token; tokens are permuted by expert (stable), the experts
+ * run as grouped GEMMs and the results are combined in token order.
+ *   X [T][d] bf16;  W_up, W_gate [F][d], W_down [d][F] bf16 latent weights;
+ *   Up, Gate [E][r][d], Down [E][d][r], Wr [E][d] bf16;  Y [T][d] bf16 out.
+ *   Backward (STE as in pq_linear_bwd): dX [T][d] bf16; dW_up, dW_gate [F][d], dW_down [d][F], dUp,
+ *   dGate [E][r][d], dDown [E][d][r], dWr [E][d] fp32; dalpha_dbeta [2] fp32.
+ * bf16 I/O only; d and F multiples of 32, r a multiple of 8, E <= 64. */
+typedef struct pq_ffn_desc {
+  int32_t tokens, d_model, d_ffn, hp_rank, n_experts, top_k, io_dtype;
+  float alpha, beta;
+} pq_ffn_desc;
+size_t pq_ffn_ctx_bytes(const pq_ffn_desc* desc);
+size_t pq_ffn_workspace_bytes(const pq_ffn_desc* desc);
+int pq_ffn_fwd(const pq_ffn_desc* desc, const void* X, const void* W_up, const void* W_gate, const void* W_down,
+               const void* Up, const void* Gate, const void* Down, const void* Wr, void* Y, void* ctx,
+               size_t ctx_bytes, void* workspace, size_t workspace_bytes, void* stream);
+int pq_ffn_bwd(const pq_ffn_desc* desc, const void* dY, const void* X, const void* Up, const void* Gate,
+               const void* Down, const void* Wr, const void* ctx, size_t ctx_bytes, void* dX, float* dW_up,
+               float* dW_gate, float* dW_down, float* dUp, float* dGate, float* dDown, float* dWr,
+               float* dalpha_dbeta, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Inference on packed weights for small token batches (App. A): the decode product
  *     y[l][b][n] = (s_l / gamma_lb) * sum_k q[l][b][k] * S_l[n][k]
  *                  + alpha * sum_j gate[l][b][j] * B_le (A_le x_lb),   e = idx[l][b][j]

@@ -23,7 +23,8 @@ EXPORTS = [
     "pq_version", "pq_last_error_string", "pq_quant_act", "pq_pack_workspace_bytes", "pq_pack_sign",
     "pq_router_topk", "pq_onebit_acc", "pq_linear_ctx_bytes", "pq_linear_workspace_bytes",
     "pq_linear_fwd", "pq_linear_bwd", "pq_prof_enable", "pq_prof_count", "pq_prof_label", "pq_prof_read",
-    "pq_prof_reset", "pq_decode_workspace_bytes", "pq_decode_gemv", "pq_pack_tiled64_bytes", "pq_pack_retile64",
+    "pq_prof_reset", "pq_decode_workspace_bytes", "pq_decode_gemv", "pq_pack_tiled64_bytes", "pq_pack_retile64", "pq_ffn_ctx_bytes", "pq_ffn_workspace_bytes",
+    "pq_ffn_fwd", "pq_ffn_bwd",
 ]
 
 
@@ -37,6 +38,12 @@ class DecodeDesc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("d_in", C.c_int32), ("d_out", C.c_int32), ("hp_rank", C.c_int32),
                 ("n_experts", C.c_int32), ("top_k", C.c_int32), ("n_layers", C.c_int32),
                 ("packed_layout", C.c_int32), ("alpha", C.c_float)]
+
+
+class FFNDesc(C.Structure):
+    _fields_ = [("tokens", C.c_int32), ("d_model", C.c_int32), ("d_ffn", C.c_int32), ("hp_rank", C.c_int32),
+                ("n_experts", C.c_int32), ("top_k", C.c_int32), ("io_dtype", C.c_int32), ("alpha", C.c_float),
+                ("beta", C.c_float)]
 
 
 class PQError(RuntimeError):
@@ -56,7 +63,8 @@ def lib():
         L.pq_last_error_string.restype = C.c_char_p
         L.pq_prof_label.restype = C.c_char_p
         for name in ("pq_pack_workspace_bytes", "pq_linear_ctx_bytes", "pq_linear_workspace_bytes",
-                     "pq_decode_workspace_bytes", "pq_pack_tiled64_bytes"):
+                     "pq_decode_workspace_bytes", "pq_pack_tiled64_bytes", "pq_ffn_ctx_bytes",
+                     "pq_ffn_workspace_bytes"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -202,3 +210,26 @@ def pack_retile64(P, K):
     T = torch.empty((n // 4,), dtype=torch.int32, device=P.device)
     _check(lib().pq_pack_retile64(_p(P), N, K, _p(T), _stream()))
     return T
+
+
+class FFNBuffers:
+    def __init__(self, desc, device="cuda"):
+        nctx = lib().pq_ffn_ctx_bytes(C.byref(desc))
+        nws = lib().pq_ffn_workspace_bytes(C.byref(desc))
+        if nctx == 0 or nws == 0:
+            raise PQError(f"bad FFN descriptor: {lib().pq_last_error_string().decode()}")
+        self.ctx = _bytes(nctx, device)
+        self.ws = _bytes(nws, device)
+
+
+def ffn_fwd(desc, X, W_up, W_gate, W_down, Up, Gate, Down, Wr, Y, bufs):
+    _check(lib().pq_ffn_fwd(C.byref(desc), _p(X), _p(W_up), _p(W_gate), _p(W_down), _p(Up), _p(Gate), _p(Down), _p(Wr),
+                            _p(Y), _p(bufs.ctx), C.c_size_t(bufs.ctx.numel()), _p(bufs.ws), C.c_size_t(bufs.ws.numel()),
+                            _stream()))
+    return Y
+
+
+def ffn_bwd(desc, dY, X, Up, Gate, Down, Wr, bufs, dX, dW_up, dW_gate, dW_down, dUp, dGate, dDown, dWr, d_ab):
+    _check(lib().pq_ffn_bwd(C.byref(desc), _p(dY), _p(X), _p(Up), _p(Gate), _p(Down), _p(Wr), _p(bufs.ctx),
+                            C.c_size_t(bufs.ctx.numel()), _p(dX), _p(dW_up), _p(dW_gate), _p(dW_down), _p(dUp),
+                            _p(dGate), _p(dDown), _p(dWr), _p(d_ab), _p(bufs.ws), C.c_size_t(bufs.ws.numel()), _stream()))

@@ -30,20 +30,20 @@ std::vector<prof_sample*> g_prof_samples;
 const char* const g_prof_names[PQP_COUNT] = {
     "quant_act", "wstats_partial", "pack_sign", "router", "reduce_partials",
     "gemm_onebit_fwd", "gemm_hp_H", "gemm_hp_Y", "gemm_dH", "gemm_dX", "gemm_dX_hp",
-    "gemm_dW", "gemm_dB", "gemm_dA", "gemm_other", "decode_prep", "decode_h", "decode_main"};
+    "gemm_dW", "gemm_dB", "gemm_dA", "gemm_other", "decode_prep", "decode_h", "decode_main", "moe_route", "moe_elementwise", "swiglu", "gemm_expert"};
 }  // namespace
 
 pq_prof_scope::pq_prof_scope(int label_, hipStream_t s_) : label(label_), s(s_), slot(nullptr) {
   if (!g_prof_on) return;
   prof_sample* ps = new prof_sample{nullptr, nullptr, label_, false};
   if (hipEventCreate(&ps->a) != hipSuccess || hipEventCreate(&ps->b) != hipSuccess) { delete ps; return; }
-  hipEventRecord(ps->a, s);
+  (void)hipEventRecord(ps->a, s);
   slot = ps;
 }
 pq_prof_scope::~pq_prof_scope() {
   if (!slot) return;
   prof_sample* ps = (prof_sample*)slot;
-  hipEventRecord(ps->b, s);
+  (void)hipEventRecord(ps->b, s);
   ps->closed = true;
   std::lock_guard<std::mutex> g(g_prof_mu);
   g_prof_samples.push_back(ps);
@@ -68,7 +68,7 @@ extern "C" int pq_prof_read(int label, double* total_ms, int* launches) {
 }
 extern "C" int pq_prof_reset(void) {
   std::lock_guard<std::mutex> g(g_prof_mu);
-  for (prof_sample* ps : g_prof_samples) { hipEventDestroy(ps->a); hipEventDestroy(ps->b); delete ps; }
+  for (prof_sample* ps : g_prof_samples) { (void)hipEventDestroy(ps->a); (void)hipEventDestroy(ps->b); delete ps; }
   g_prof_samples.clear();
   return PQ_OK;
 }

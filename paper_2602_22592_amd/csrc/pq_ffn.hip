@@ -1,0 +1,313 @@
+// The decoupled FFN (Sec. 3.2 FFN equation, Sec. 3.3):
+//     Y = beta * FFN_1bit(X) + alpha * sum_j gate_j * FFN_e_j(X)
+// FFN_1bit: three pure 1-bit linears around a gated unit, hidden state re-quantised before the down
+// projection; FFN_e: routed bf16 experts of hidden width r (permute -> grouped GEMMs -> combine).
+// This file sequences the kernels; all arithmetic lives in pq_gemm.hip / pq_quant.hip / pq_moe.hip.
+#include <string.h>
+#include "pq_internal.h"
+
+namespace {
+
+#define PQ_REQUIRE(cond, code, ...) \
+  do { if (!(cond)) return pq_set_error(code, __VA_ARGS__); } while (0)
+
+inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+
+struct cursor {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    size_t o = off;
+    off = pq_align_up(off + (bytes ? bytes : 1), 256);
+    return o;
+  }
+};
+
+struct ffn_layout {
+  // ctx
+  size_t ml_up, ml_gate, ml_down, P_up, Pt_up, P_gate, Pt_gate, P_down, Pt_down, Xq, gx, Xt, U, G, Hq, gh, Ht;
+  size_t idx, gate, probs, counts, offsets, perm, inv, Xp, ue, ge, a, Ys, ctx_total;
+  // workspace
+  size_t stat, red_a, red_b, splitk, dHd, dU, dG, dYp, rd, da, du, dg, as, dXs, dlogit, dwr, ws_total;
+  int n_red_a, n_red_b;
+};
+
+ffn_layout make_layout(const pq_ffn_desc& d) {
+  ffn_layout L;
+  memset(&L, 0, sizeof(L));
+  const size_t T = d.tokens, D = d.d_model, F = d.d_ffn, r = d.hp_rank, E = d.n_experts, S = T * (size_t)d.top_k;
+  cursor c;
+  L.ml_up = c.take(8); L.ml_gate = c.take(8); L.ml_down = c.take(8);
+  L.P_up = c.take(F * D / 8); L.Pt_up = c.take(F * D / 8);
+  L.P_gate = c.take(F * D / 8); L.Pt_gate = c.take(F * D / 8);
+  L.P_down = c.take(F * D / 8); L.Pt_down = c.take(F * D / 8);
+  L.Xq = c.take(T * D); L.gx = c.take(T * 4); L.Xt = c.take(T * D * 2);
+  L.U = c.take(T * F * 2); L.G = c.take(T * F * 2);
+  L.Hq = c.take(T * F); L.gh = c.take(T * 4); L.Ht = c.take(T * F * 2);
+  L.idx = c.take(S * 4); L.gate = c.take(S * 4); L.probs = c.take(T * E * 4);
+  L.counts = c.take(E * 4); L.offsets = c.take((E + 1) * 4); L.perm = c.take(S * 4); L.inv = c.take(S * 4);
+  L.Xp = c.take(S * D * 2); L.ue = c.take(S * r * 2); L.ge = c.take(S * r * 2); L.a = c.take(S * r * 2);
+  L.Ys = c.take(S * D * 2);
+  L.ctx_total = c.off;
+  cursor w;
+  L.stat = w.take(2 * sizeof(double) * 1024);
+  L.n_red_a = pq_rowdot_blocks((int)S);
+  L.n_red_b = pq_plan_gemm(0, (int)D, (int)F, (int)T).red_blocks;      // dW_down GEMM
+  L.red_a = w.take(sizeof(double) * (size_t)L.n_red_a);
+  L.red_b = w.take(sizeof(double) * (size_t)L.n_red_b);
+  size_t sk = 0;
+  const int Ti = d.tokens, Di = d.d_model, Fi = d.d_ffn;
+  const int shapes[4][3] = {{Di, Fi, Ti}, {Ti, Fi, Di}, {Ti, Di, Fi}, {Fi, Di, Ti}};
+  for (const auto& sh : shapes) {
+    if (sh[0] <= 0 || sh[1] <= 0) continue;
+    const size_t b = pq_plan_gemm(0, sh[0], sh[1], sh[2]).ws_bytes;
+    if (b > sk) sk = b;
+  }
+  L.splitk = w.take(sk);
+  L.dHd = w.take(T * F * 2); L.dU = w.take(T * F * 2); L.dG = w.take(T * F * 2);
+  L.dYp = w.take(S * D * 2); L.rd = w.take(S * 4);
+  L.da = w.take(S * r * 2); L.du = w.take(S * r * 2); L.dg = w.take(S * r * 2); L.as = w.take(S * r * 2);
+  L.dXs = w.take(S * D * 2); L.dlogit = w.take(T * E * 4);
+  L.dwr = w.take(pq_dwr_scratch_bytes((int)T, (int)D, (int)E));
+  L.ws_total = w.off;
+  return L;
+}
+
+int check_ffn(const pq_ffn_desc* d) {
+  PQ_REQUIRE(d != nullptr, PQ_ERR_BAD_ARG, "desc is NULL");
+  PQ_REQUIRE(d->tokens >= 0 && d->d_model > 0 && d->d_ffn > 0 && d->hp_rank > 0, PQ_ERR_BAD_ARG, "bad dimension");
+  PQ_REQUIRE(d->io_dtype == PQ_BF16, PQ_ERR_DTYPE, "the FFN path runs on bf16 I/O only");
+  PQ_REQUIRE(d->d_model % 32 == 0 && d->d_ffn % 32 == 0, PQ_ERR_SHAPE, "d_model=%d and d_ffn=%d must be multiples of 32",
+             d->d_model, d->d_ffn);
+  PQ_REQUIRE(d->hp_rank % 8 == 0, PQ_ERR_SHAPE, "hp_rank=%d must be a multiple of 8", d->hp_rank);
+  PQ_REQUIRE(d->n_experts >= 1 && d->n_experts <= 64, PQ_ERR_BAD_ARG, "n_experts=%d must be in 1..64", d->n_experts);
+  PQ_REQUIRE(d->top_k >= 1 && d->top_k <= d->n_experts, PQ_ERR_BAD_ARG, "top_k=%d must be in 1..n_experts", d->top_k);
+  return PQ_OK;
+}
+
+pq_epilogue epi0() {
+  pq_epilogue e;
+  memset(&e, 0, sizeof(e));
+  e.scale = 1.0f;
+  return e;
+}
+
+int pack_weight(const void* W, int N, int K, char* cx, size_t offP, size_t offPt, size_t offml, double* part, hipStream_t s) {
+  const size_t n = (size_t)N * K;
+  const int nb = pq_stats_blocks(n);
+  if (int e = pq_launch_wstats_partial(W, PQ_BF16, n, part, nb, s)) return e;
+  return pq_launch_pack(W, PQ_BF16, N, K, part, nb, (uint32_t*)(cx + offP), (uint32_t*)(cx + offPt), (float*)(cx + offml), s);
+}
+
+}  // namespace
+
+extern "C" size_t pq_ffn_ctx_bytes(const pq_ffn_desc* d) {
+  if (check_ffn(d) != PQ_OK) return 0;
+  return make_layout(*d).ctx_total;
+}
+extern "C" size_t pq_ffn_workspace_bytes(const pq_ffn_desc* d) {
+  if (check_ffn(d) != PQ_OK) return 0;
+  return make_layout(*d).ws_total;
+}
+
+extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up, const void* W_gate, const void* W_down,
+                          const void* Up, const void* Gate, const void* Down, const void* Wr, void* Y, void* ctx,
+                          size_t ctx_bytes, void* workspace, size_t workspace_bytes, void* stream) {
+  if (int e = check_ffn(d)) return e;
+  const ffn_layout L = make_layout(*d);
+  PQ_REQUIRE(X && W_up && W_gate && W_down && Up && Gate && Down && Wr && Y && ctx && workspace, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(aligned16(X) && aligned16(W_up) && aligned16(W_gate) && aligned16(W_down) && aligned16(Up) && aligned16(Gate) &&
+                 aligned16(Down) && aligned16(Wr) && aligned16(Y) && aligned16(ctx) && aligned16(workspace),
+             PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
+  PQ_REQUIRE(ctx_bytes >= L.ctx_total, PQ_ERR_WORKSPACE, "ctx too small: %zu < %zu", ctx_bytes, L.ctx_total);
+  PQ_REQUIRE(workspace_bytes >= L.ws_total, PQ_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, L.ws_total);
+  hipStream_t s = (hipStream_t)stream;
+  char* cx = (char*)ctx;
+  char* ws = (char*)workspace;
+  const int T = d->tokens, D = d->d_model, F = d->d_ffn, r = d->hp_rank, E = d->n_experts, k = d->top_k, S = T * k;
+  double* part = (double*)(ws + L.stat);
+  void* sk = ws + L.splitk;
+
+  if (int e = pack_weight(W_up, F, D, cx, L.P_up, L.Pt_up, L.ml_up, part, s)) return e;
+  if (int e = pack_weight(W_gate, F, D, cx, L.P_gate, L.Pt_gate, L.ml_gate, part, s)) return e;
+  if (int e = pack_weight(W_down, D, F, cx, L.P_down, L.Pt_down, L.ml_down, part, s)) return e;
+  if (T == 0)  // no tokens: leave empty expert segments behind so that a backward call is well defined
+    return pq_launch_route((const int*)(cx + L.idx), 0, E, (int*)(cx + L.counts), (int*)(cx + L.offsets), (int*)(cx + L.perm),
+                           (int*)(cx + L.inv), s);
+
+  int8_t* Xq = (int8_t*)(cx + L.Xq);
+  float* gx = (float*)(cx + L.gx);
+  if (int e = pq_launch_quant_act(X, PQ_BF16, T, D, Xq, gx, (uint16_t*)(cx + L.Xt), s)) return e;
+  {  // U and G: pure 1-bit linears (no feature scale of their own)
+    pq_operand A{Xq, D, PQ_SRC_KC8, nullptr};
+    pq_operand Bu{cx + L.P_up, D / 8, PQ_SRC_BITS8, nullptr};
+    pq_epilogue e = epi0();
+    e.C = cx + L.U; e.ldc = F; e.out_kind = PQ_OUT_BF16; e.dev_scale = (const float*)(cx + L.ml_up) + 1; e.row_div = gx;
+    if (int err = pq_launch_gemm(0, T, F, D, A, Bu, e, s, PQP_GEMM_ONEBIT, sk)) return err;
+    pq_operand Bg{cx + L.P_gate, D / 8, PQ_SRC_BITS8, nullptr};
+    e.C = cx + L.G; e.dev_scale = (const float*)(cx + L.ml_gate) + 1;
+    if (int err = pq_launch_gemm(0, T, F, D, A, Bg, e, s, PQP_GEMM_ONEBIT, sk)) return err;
+  }
+  int8_t* Hq = (int8_t*)(cx + L.Hq);
+  float* gh = (float*)(cx + L.gh);
+  if (int e = pq_launch_swiglu_quant(cx + L.U, cx + L.G, T, F, Hq, gh, cx + L.Ht, s)) return e;
+  {  // Y = beta * (lambda_d / gamma_h) * acc
+    pq_operand A{Hq, F, PQ_SRC_KC8, nullptr};
+    pq_operand B{cx + L.P_down, F / 8, PQ_SRC_BITS8, nullptr};
+    pq_epilogue e = epi0();
+    e.C = Y; e.ldc = D; e.out_kind = PQ_OUT_BF16; e.scale = d->beta; e.dev_scale = (const float*)(cx + L.ml_down) + 1; e.row_div = gh;
+    if (int err = pq_launch_gemm(0, T, D, F, A, B, e, s, PQP_GEMM_ONEBIT, sk)) return err;
+  }
+  // routed experts: router -> stable permutation by expert -> gather -> grouped GEMMs -> combine
+  int* idx = (int*)(cx + L.idx);
+  float* gate = (float*)(cx + L.gate);
+  if (int e = pq_launch_router(X, Wr, PQ_BF16, T, D, E, k, idx, gate, (float*)(cx + L.probs), s)) return e;
+  int* offsets = (int*)(cx + L.offsets);
+  int* perm = (int*)(cx + L.perm);
+  int* inv = (int*)(cx + L.inv);
+  if (int e = pq_launch_route(idx, S, E, (int*)(cx + L.counts), offsets, perm, inv, s)) return e;
+  if (int e = pq_launch_gather_rows(X, perm, k, S, D, cx + L.Xp, s)) return e;
+  pq_gemm_group g1{offsets, E, 1, 0, 0, S};
+  {
+    pq_operand A{cx + L.Xp, D, PQ_SRC_KC16, nullptr};
+    pq_operand B{Up, D, PQ_SRC_KC16, nullptr};
+    pq_epilogue e = epi0();
+    e.C = cx + L.ue; e.ldc = r; e.out_kind = PQ_OUT_BF16;
+    g1.b_stride = (long)r * D;
+    if (int err = pq_launch_gemm(0, S, r, D, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+    pq_operand Bg{Gate, D, PQ_SRC_KC16, nullptr};
+    e.C = cx + L.ge;
+    if (int err = pq_launch_gemm(0, S, r, D, A, Bg, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+  }
+  if (int e = pq_launch_expert_act(cx + L.ue, cx + L.ge, (size_t)S * r, cx + L.a, s)) return e;
+  {
+    pq_operand A{cx + L.a, r, PQ_SRC_KC16, nullptr};
+    pq_operand B{Down, r, PQ_SRC_KC16, nullptr};
+    pq_epilogue e = epi0();
+    e.C = cx + L.Ys; e.ldc = D; e.out_kind = PQ_OUT_BF16;
+    g1.b_stride = (long)D * r;
+    if (int err = pq_launch_gemm(0, S, D, r, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+  }
+  return pq_launch_combine_fwd(Y, cx + L.Ys, inv, gate, d->alpha, T, k, D, s);
+}
+
+extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, const void* Up, const void* Gate,
+                          const void* Down, const void* Wr, const void* ctx, size_t ctx_bytes, void* dX, float* dW_up,
+                          float* dW_gate, float* dW_down, float* dUp, float* dGate, float* dDown, float* dWr,
+                          float* dalpha_dbeta, void* workspace, size_t workspace_bytes, void* stream) {
+  if (int e = check_ffn(d)) return e;
+  const ffn_layout L = make_layout(*d);
+  PQ_REQUIRE(dY && X && Up && Gate && Down && Wr && ctx && dX && dW_up && dW_gate && dW_down && dUp && dGate && dDown && dWr &&
+                 dalpha_dbeta && workspace, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(aligned16(dY) && aligned16(X) && aligned16(Up) && aligned16(Gate) && aligned16(Down) && aligned16(Wr) &&
+                 aligned16(ctx) && aligned16(dX) && aligned16(dW_up) && aligned16(dW_gate) && aligned16(dW_down) &&
+                 aligned16(dUp) && aligned16(dGate) && aligned16(dDown) && aligned16(workspace),
+             PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
+  PQ_REQUIRE(ctx_bytes >= L.ctx_total, PQ_ERR_WORKSPACE, "ctx too small: %zu < %zu", ctx_bytes, L.ctx_total);
+  PQ_REQUIRE(workspace_bytes >= L.ws_total, PQ_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, L.ws_total);
+  hipStream_t s = (hipStream_t)stream;
+  const char* cx = (const char*)ctx;
+  char* ws = (char*)workspace;
+  const int T = d->tokens, D = d->d_model, F = d->d_ffn, r = d->hp_rank, E = d->n_experts, k = d->top_k, S = T * k;
+  void* sk = ws + L.splitk;
+  const float* ml_up = (const float*)(cx + L.ml_up);
+  const float* ml_gate = (const float*)(cx + L.ml_gate);
+  const float* ml_down = (const float*)(cx + L.ml_down);
+  double* red_a = (double*)(ws + L.red_a);
+  double* red_b = (double*)(ws + L.red_b);
+
+  {  // dW_down = beta * dY^T Ht ;  d beta = lambda_d * sum S_d .* (dY^T Ht)
+    pq_operand A{dY, D, PQ_SRC_KS16, nullptr};
+    pq_operand B{cx + L.Ht, F, PQ_SRC_KS16, nullptr};
+    pq_epilogue e = epi0();
+    e.C = dW_down; e.ldc = F; e.out_kind = PQ_OUT_F32; e.scale = d->beta;
+    e.sign_bytes = (const uint8_t*)(cx + L.P_down); e.ld_sign = F / 8; e.partials = red_b;
+    if (int err = pq_launch_gemm(0, D, F, T, A, B, e, s, PQP_GEMM_DW, sk)) return err;
+    if (int err = pq_launch_reduce_partials(red_b, L.n_red_b, 1.0f, ml_down + 1, dalpha_dbeta + 1, s)) return err;
+  }
+  if (T > 0) {
+    {  // dHd = beta * lambda_d * dY S_d
+      pq_operand A{dY, D, PQ_SRC_KC16, nullptr};
+      pq_operand B{cx + L.Pt_down, D / 8, PQ_SRC_BITS16, nullptr};
+      pq_epilogue e = epi0();
+      e.C = ws + L.dHd; e.ldc = F; e.out_kind = PQ_OUT_BF16; e.scale = d->beta; e.dev_scale = ml_down + 1;
+      if (int err = pq_launch_gemm(0, T, F, D, A, B, e, s, PQP_GEMM_DX, sk)) return err;
+    }
+    if (int err = pq_launch_swiglu_bwd(ws + L.dHd, cx + L.U, cx + L.G, (size_t)T * F, ws + L.dU, ws + L.dG, s)) return err;
+    {  // dX = lambda_u dU S_u + lambda_g dG S_g
+      pq_operand A{ws + L.dU, F, PQ_SRC_KC16, nullptr};
+      pq_operand B{cx + L.Pt_up, F / 8, PQ_SRC_BITS16, nullptr};
+      pq_epilogue e = epi0();
+      e.C = dX; e.ldc = D; e.out_kind = PQ_OUT_BF16; e.dev_scale = ml_up + 1;
+      if (int err = pq_launch_gemm(0, T, D, F, A, B, e, s, PQP_GEMM_DX, sk)) return err;
+      pq_operand A2{ws + L.dG, F, PQ_SRC_KC16, nullptr};
+      pq_operand B2{cx + L.Pt_gate, F / 8, PQ_SRC_BITS16, nullptr};
+      e.accumulate = 1; e.dev_scale = ml_gate + 1;
+      if (int err = pq_launch_gemm(0, T, D, F, A2, B2, e, s, PQP_GEMM_DX, sk)) return err;
+    }
+  }
+  {  // dW_up = dU^T Xt, dW_gate = dG^T Xt
+    pq_operand B{cx + L.Xt, D, PQ_SRC_KS16, nullptr};
+    pq_epilogue e = epi0();
+    e.ldc = D; e.out_kind = PQ_OUT_F32;
+    pq_operand A{ws + L.dU, F, PQ_SRC_KS16, nullptr};
+    e.C = dW_up;
+    if (int err = pq_launch_gemm(0, F, D, T, A, B, e, s, PQP_GEMM_DW, sk)) return err;
+    pq_operand A2{ws + L.dG, F, PQ_SRC_KS16, nullptr};
+    e.C = dW_gate;
+    if (int err = pq_launch_gemm(0, F, D, T, A2, B, e, s, PQP_GEMM_DW, sk)) return err;
+  }
+  // experts
+  const int* idx = (const int*)(cx + L.idx);
+  const float* gate = (const float*)(cx + L.gate);
+  const int* offsets = (const int*)(cx + L.offsets);
+  const int* perm = (const int*)(cx + L.perm);
+  const int* inv = (const int*)(cx + L.inv);
+  float* rd = (float*)(ws + L.rd);
+  if (int e = pq_launch_gather_rows(dY, perm, k, S, D, ws + L.dYp, s)) return e;
+  if (int e = pq_launch_rowdot(ws + L.dYp, cx + L.Ys, perm, gate, S, D, rd, red_a, s)) return e;
+  if (int e = pq_launch_reduce_partials(red_a, S > 0 ? L.n_red_a : 0, 1.0f, nullptr, dalpha_dbeta, s)) return e;
+  pq_gemm_group g1{offsets, E, 1, 0, 0, S};
+  pq_gemm_group g2{offsets, E, 2, 0, 0, S};
+  if (S > 0) {  // da = dYp Down_e  (scaled by alpha*gate inside the activation backward)
+    pq_operand A{ws + L.dYp, D, PQ_SRC_KC16, nullptr};
+    pq_operand B{Down, r, PQ_SRC_KS16, nullptr};
+    pq_epilogue e = epi0();
+    e.C = ws + L.da; e.ldc = r; e.out_kind = PQ_OUT_BF16;
+    g1.b_stride = (long)D * r;
+    if (int err = pq_launch_gemm(0, S, r, D, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+  }
+  if (int e = pq_launch_expert_act_bwd(ws + L.da, cx + L.ue, cx + L.ge, cx + L.a, perm, gate, d->alpha, S, r, ws + L.du, ws + L.dg,
+                                       ws + L.as, s)) return e;
+  {  // per-expert weight gradients: contraction over the expert's slots
+    pq_operand A{ws + L.dYp, D, PQ_SRC_KS16, nullptr};
+    pq_operand B{ws + L.as, r, PQ_SRC_KS16, nullptr};
+    pq_epilogue e = epi0();
+    e.C = dDown; e.ldc = r; e.out_kind = PQ_OUT_F32;
+    g2.c_stride = (long)D * r;
+    if (int err = pq_launch_gemm(0, D, r, S, A, B, e, s, PQP_GEMM_EXPERT, sk, &g2)) return err;
+    pq_operand Bx{cx + L.Xp, D, PQ_SRC_KS16, nullptr};
+    pq_operand Au{ws + L.du, r, PQ_SRC_KS16, nullptr};
+    e.C = dUp; e.ldc = D;
+    g2.c_stride = (long)r * D;
+    if (int err = pq_launch_gemm(0, r, D, S, Au, Bx, e, s, PQP_GEMM_EXPERT, sk, &g2)) return err;
+    pq_operand Ag{ws + L.dg, r, PQ_SRC_KS16, nullptr};
+    e.C = dGate;
+    if (int err = pq_launch_gemm(0, r, D, S, Ag, Bx, e, s, PQP_GEMM_EXPERT, sk, &g2)) return err;
+  }
+  if (S > 0) {  // dXs = du Up_e + dg Gate_e  (slot order)
+    pq_operand A{ws + L.du, r, PQ_SRC_KC16, nullptr};
+    pq_operand B{Up, D, PQ_SRC_KS16, nullptr};
+    pq_epilogue e = epi0();
+    e.C = ws + L.dXs; e.ldc = D; e.out_kind = PQ_OUT_BF16;
+    g1.b_stride = (long)r * D;
+    if (int err = pq_launch_gemm(0, S, D, r, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+    pq_operand A2{ws + L.dg, r, PQ_SRC_KC16, nullptr};
+    pq_operand B2{Gate, D, PQ_SRC_KS16, nullptr};
+    e.accumulate = 1;
+    if (int err = pq_launch_gemm(0, S, D, r, A2, B2, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+  }
+  float* dlogit = (float*)(ws + L.dlogit);
+  if (int e = pq_launch_router_bwd(rd, inv, idx, (const float*)(cx + L.probs), d->alpha, T, k, E, dlogit, s)) return e;
+  if (int e = pq_launch_dwr(dlogit, X, T, D, E, (float*)(ws + L.dwr), dWr, s)) return e;
+  return pq_launch_combine_bwd(dX, ws + L.dXs, inv, dlogit, Wr, T, k, D, E, s);
+}

@@ -297,7 +297,7 @@ template <int BM, int BN, int WGM, int WGN, bool INT8, int AK, int BKIND>
 __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N, int K, pq_operand A,
                                                                      pq_operand B, pq_epilogue epi,
                                                                      int nbn, int total_tiles, int kchunk,
-                                                                     float* splitk_part) {
+                                                                     float* splitk_part, pq_gemm_group grp) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -313,9 +313,22 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
   int pid = blockIdx.x;
   if ((total_tiles & 7) == 0) pid = (pid & 7) * (total_tiles >> 3) + (pid >> 3);
   const int bm = pid / nbn, bn = pid % nbn;
-  const int m0 = bm * BM, n0 = bn * BN;
-  const int kb = blockIdx.y * kchunk;
-  const int ke = min(K, kb + kchunk);
+  int m0 = bm * BM;
+  const int n0 = bn * BN;
+  int kb = blockIdx.y * kchunk;
+  int ke = min(K, kb + kchunk);
+  if (grp.mode == 1) {          // rows of group z: [offsets[z], offsets[z+1])
+    const int z = blockIdx.z;
+    m0 += grp.offsets[z];
+    M = grp.offsets[z + 1];
+    if (m0 >= M) return;        // uniform for the workgroup
+    B.p = (const char*)B.p + (size_t)z * grp.b_stride * (BKIND == PQ_SRC_KC8 ? 1 : 2);
+  } else if (grp.mode == 2) {   // contraction range of group z, own output slab
+    const int z = blockIdx.z;
+    kb = grp.offsets[z];
+    ke = grp.offsets[z + 1];
+    epi.C = (char*)epi.C + (size_t)z * grp.c_stride * (epi.out_kind == PQ_OUT_BF16 ? 2 : 4);
+  }
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
@@ -486,21 +499,22 @@ __global__ __launch_bounds__(256) void ref_gemm_kernel(int M, int N, int K, pq_o
 
 template <int BM, int BN, int WGM, int WGN, bool INT8, int AK, int BKIND>
 int launch_mfma(const pq_gemm_plan& pl, int M, int N, int K, const pq_operand& A, const pq_operand& B,
-                const pq_epilogue& epi, hipStream_t s, float* part) {
-  const int nbm = (M + BM - 1) / BM, nbn = (N + BN - 1) / BN;
+                const pq_epilogue& epi, hipStream_t s, float* part, const pq_gemm_group& grp) {
+  const int Mrows = grp.mode == 1 ? grp.max_rows : M;
+  const int nbm = (Mrows + BM - 1) / BM, nbn = (N + BN - 1) / BN;
   const int tiles = nbm * nbn;
-  dim3 grid(tiles, pl.splits), block(WGM * WGN * 64);
+  dim3 grid(tiles, pl.splits, grp.mode ? grp.n_groups : 1), block(WGM * WGN * 64);
   mfma_gemm_kernel<BM, BN, WGM, WGN, INT8, AK, BKIND><<<grid, block, 0, s>>>(M, N, K, A, B, epi, nbn, tiles, pl.kchunk,
-                                                                               pl.splits > 1 ? part : nullptr);
+                                                                               pl.splits > 1 ? part : nullptr, grp);
   PQ_CHECK_LAUNCH("mfma_gemm_kernel");
   return PQ_OK;
 }
 
 template <bool INT8, int AK, int BKIND>
 int launch_mfma_cfg(const pq_gemm_plan& pl, int M, int N, int K, const pq_operand& A, const pq_operand& B,
-                    const pq_epilogue& epi, hipStream_t s, float* part) {
-  if (pl.bm == 256) return launch_mfma<256, 256, 2, 4, INT8, AK, BKIND>(pl, M, N, K, A, B, epi, s, part);
-  return launch_mfma<128, 128, 2, 2, INT8, AK, BKIND>(pl, M, N, K, A, B, epi, s, part);
+                    const pq_epilogue& epi, hipStream_t s, float* part, const pq_gemm_group& grp) {
+  if (pl.bm == 256) return launch_mfma<256, 256, 2, 4, INT8, AK, BKIND>(pl, M, N, K, A, B, epi, s, part, grp);
+  return launch_mfma<128, 128, 2, 2, INT8, AK, BKIND>(pl, M, N, K, A, B, epi, s, part, grp);
 }
 
 }  // namespace
@@ -536,8 +550,13 @@ pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8) {
 }
 
 int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const pq_operand& B,
-                   const pq_epilogue& epi, hipStream_t s, int prof_label, void* splitk_ws) {
+                   const pq_epilogue& epi, hipStream_t s, int prof_label, void* splitk_ws,
+                   const pq_gemm_group* group) {
   if (M <= 0 || N <= 0) return PQ_OK;
+  pq_gemm_group grp;
+  memset(&grp, 0, sizeof(grp));
+  if (group) grp = *group;
+  if (grp.mode && engine == 1) return pq_set_error(PQ_ERR_DTYPE, "grouped GEMMs run on the MFMA engine only (bf16 I/O)");
   pq_prof_scope prof(prof_label, s);
   if (engine == 1) {
     dim3 grid((N + 15) / 16, (M + 15) / 16), block(256);
@@ -547,15 +566,20 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
   }
   const int ak = A.kind, bk = B.kind;
   const bool int8 = (ak == PQ_SRC_KC8);
-  const pq_gemm_plan pl = pq_plan_gemm(0, M, N, K, int8);
+  pq_gemm_plan pl = pq_plan_gemm(0, M, N, K, int8);
+  if (grp.mode) {               // groups already give parallelism; no contraction split
+    pl.splits = 1;
+    pl.kchunk = K > 0 ? K : 1;
+    pl.bm = pl.bn = 128;
+  }
   if (pl.splits > 1 && !splitk_ws) return pq_set_error(PQ_ERR_WORKSPACE, "split contraction needs scratch");
   float* part = (float*)splitk_ws;
   int rc;
-  if (ak == PQ_SRC_KC8 && bk == PQ_SRC_BITS8) rc = launch_mfma_cfg<true, PQ_SRC_KC8, PQ_SRC_BITS8>(pl, M, N, K, A, B, epi, s, part);
-  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KC16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KC16>(pl, M, N, K, A, B, epi, s, part);
-  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KS16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part);
-  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_BITS16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_BITS16>(pl, M, N, K, A, B, epi, s, part);
-  else if (ak == PQ_SRC_KS16 && bk == PQ_SRC_KS16) rc = launch_mfma_cfg<false, PQ_SRC_KS16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part);
+  if (ak == PQ_SRC_KC8 && bk == PQ_SRC_BITS8) rc = launch_mfma_cfg<true, PQ_SRC_KC8, PQ_SRC_BITS8>(pl, M, N, K, A, B, epi, s, part, grp);
+  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KC16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KC16>(pl, M, N, K, A, B, epi, s, part, grp);
+  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KS16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part, grp);
+  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_BITS16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_BITS16>(pl, M, N, K, A, B, epi, s, part, grp);
+  else if (ak == PQ_SRC_KS16 && bk == PQ_SRC_KS16) rc = launch_mfma_cfg<false, PQ_SRC_KS16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part, grp);
   else return pq_set_error(PQ_ERR_BAD_ARG, "no MFMA kernel for operand kinds (%d, %d)", ak, bk);
   if (rc != PQ_OK) return rc;
   if (pl.splits > 1) {

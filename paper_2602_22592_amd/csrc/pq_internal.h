@@ -6,7 +6,7 @@
 enum pq_prof_id {
   PQP_QUANT = 0, PQP_WSTATS, PQP_PACK, PQP_ROUTER, PQP_REDUCE,
   PQP_GEMM_ONEBIT, PQP_GEMM_HP_H, PQP_GEMM_HP_Y, PQP_GEMM_DH, PQP_GEMM_DX, PQP_GEMM_DX_HP,
-  PQP_GEMM_DW, PQP_GEMM_DB, PQP_GEMM_DA, PQP_GEMM_OTHER, PQP_DECODE_PREP, PQP_DECODE_H, PQP_DECODE_MAIN, PQP_COUNT
+  PQP_GEMM_DW, PQP_GEMM_DB, PQP_GEMM_DA, PQP_GEMM_OTHER, PQP_DECODE_PREP, PQP_DECODE_H, PQP_DECODE_MAIN, PQP_MOE_ROUTE, PQP_MOE_ELEMENTWISE, PQP_SWIGLU, PQP_GEMM_EXPERT, PQP_COUNT
 };
 struct pq_prof_scope {   // records an event pair around the launches made while it is alive
   int label; hipStream_t s; void* slot;
@@ -80,6 +80,20 @@ struct pq_epilogue {
 
 // C[M][N] (+)= epilogue( sum_k A(m,k) * B(n,k) ).  `engine` 0 = MFMA (bf16 or int8 operands),
 // 1 = reference precision (fp64 accumulate, any operand kind).
+// Grouped execution over expert segments (Sec. 3.3): `offsets` [n_groups+1] is a device array of
+// slot positions.  mode 1: rows [offsets[e], offsets[e+1]) of A and C belong to group e and use
+// B + e*b_stride (elements of B's type) -- the per-expert GEMMs of the forward pass;  mode 2: the
+// contraction index runs over [offsets[e], offsets[e+1]) and the result goes to C + e*c_stride
+// (elements of C's type) -- the per-expert weight gradients.  max_rows bounds a segment (launch size).
+struct pq_gemm_group {
+  const int* offsets;
+  int n_groups;
+  int mode;          // 0 = not grouped
+  long b_stride;
+  long c_stride;
+  int max_rows;
+};
+
 struct pq_gemm_plan {
   int bm, bn;        // tile
   int splits;        // contraction splits (1 = none)
@@ -90,7 +104,7 @@ struct pq_gemm_plan {
 pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8 = false);
 int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const pq_operand& B,
                    const pq_epilogue& epi, hipStream_t s, int prof_label = PQP_GEMM_OTHER,
-                   void* splitk_ws = nullptr);
+                   void* splitk_ws = nullptr, const pq_gemm_group* group = nullptr);
 
 // ---- pq_decode.hip ------------------------------------------------------------------------
 size_t pq_decode_ws_layout(const pq_decode_desc& d, size_t* off);
@@ -98,3 +112,22 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
                      const void* hpA, const void* hpB, const void* Wr, void* Y, int32_t* acc_out, void* workspace,
                      hipStream_t s);
 int pq_launch_retile64(const uint32_t* packed, int N, int K, uint32_t* tiled, hipStream_t s);
+
+// ---- pq_moe.hip ---------------------------------------------------------------------------
+int pq_launch_route(const int* idx, int S, int E, int* counts, int* offsets, int* perm, int* inv, hipStream_t s);
+int pq_launch_gather_rows(const void* src, const int* perm, int k, int S, int d, void* dst, hipStream_t s);
+int pq_launch_swiglu_quant(const void* U, const void* G, int T, int F, int8_t* Hq, float* gamma, void* Ht, hipStream_t s);
+int pq_launch_swiglu_bwd(const void* dHd, const void* U, const void* G, size_t n, void* dU, void* dG, hipStream_t s);
+int pq_launch_expert_act(const void* ue, const void* ge, size_t n, void* a, hipStream_t s);
+int pq_launch_expert_act_bwd(const void* da, const void* ue, const void* ge, const void* a, const int* perm, const float* gate,
+                             float alpha, int S, int r, void* du, void* dg, void* as, hipStream_t s);
+int pq_rowdot_blocks(int S);
+int pq_launch_rowdot(const void* A, const void* B, const int* perm, const float* gate, int S, int d, float* rd, double* partial,
+                     hipStream_t s);
+int pq_launch_combine_fwd(void* Y, const void* Ys, const int* inv, const float* gate, float alpha, int T, int k, int d, hipStream_t s);
+int pq_launch_router_bwd(const float* rd, const int* inv, const int* idx, const float* probs, float alpha, int T, int k, int E,
+                         float* dlogit, hipStream_t s);
+size_t pq_dwr_scratch_bytes(int T, int d, int E);
+int pq_launch_dwr(const float* dlogit, const void* X, int T, int d, int E, float* part, float* dWr, hipStream_t s);
+int pq_launch_combine_bwd(void* dX, const void* dXs, const int* inv, const float* dlogit, const void* Wr, int T, int k, int d, int E,
+                          hipStream_t s);

@@ -1,0 +1,438 @@
+// Routing bookkeeping and element-wise kernels of the decoupled FFN (Sec. 3.2, 3.3): expert
+// histogram and stable permutation, row gather, the gated unit with fused AbsMax re-quantisation,
+// expert activation forward/backward, gate/alpha reductions, router backward, scatter-combine.
+// All tensors here are bf16 unless noted; every reduction has a fixed order.
+#include "pq_internal.h"
+
+namespace {
+
+__device__ __forceinline__ void unpack8(const uint4& u, float* f) {
+  f[0] = __uint_as_float(u.x << 16); f[1] = __uint_as_float(u.x & 0xFFFF0000u);
+  f[2] = __uint_as_float(u.y << 16); f[3] = __uint_as_float(u.y & 0xFFFF0000u);
+  f[4] = __uint_as_float(u.z << 16); f[5] = __uint_as_float(u.z & 0xFFFF0000u);
+  f[6] = __uint_as_float(u.w << 16); f[7] = __uint_as_float(u.w & 0xFFFF0000u);
+}
+__device__ __forceinline__ uint4 pack8(const float* f) {
+  return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+}
+__device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + expf(-x)); }
+__device__ __forceinline__ float siluf_(float x) { return x * sigmoidf_(x); }
+__device__ __forceinline__ float dsiluf_(float x) {
+  const float s = sigmoidf_(x);
+  return s * (1.0f + x * (1.0f - s));
+}
+
+// ---- routing: one wavefront per expert ------------------------------------------------------
+__global__ __launch_bounds__(256) void route_count_kernel(const int* __restrict__ idx, int S, int E, int* __restrict__ counts) {
+  const int e = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (e >= E) return;
+  int cnt = 0;
+  for (int s0 = 0; s0 < S; s0 += 64) {
+    const int s = s0 + lane;
+    cnt += __builtin_popcountll(__ballot(s < S && idx[s] == e));
+  }
+  if (lane == 0) counts[e] = cnt;
+}
+
+// Stable counting sort of the slots (slot = token * k + j) by expert: perm[pos] = slot, inv[slot] = pos.
+__global__ __launch_bounds__(256) void route_build_kernel(const int* __restrict__ idx, const int* __restrict__ counts, int S,
+                                                          int E, int* __restrict__ offsets, int* __restrict__ perm,
+                                                          int* __restrict__ inv) {
+  const int e = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (e >= E) return;
+  int running = 0;
+  for (int i = 0; i < e; ++i) running += counts[i];
+  if (lane == 0) {
+    offsets[e] = running;
+    if (e == E - 1) offsets[E] = running + counts[e];
+  }
+  for (int s0 = 0; s0 < S; s0 += 64) {
+    const int s = s0 + lane;
+    const bool match = s < S && idx[s] == e;
+    const unsigned long long m = __ballot(match);
+    if (match) {
+      const int pos = running + __builtin_popcountll(m & ((1ull << lane) - 1ull));
+      perm[pos] = s;
+      inv[s] = pos;
+    }
+    running += __builtin_popcountll(m);
+  }
+}
+
+// dst[pos][:] = src[perm[pos] / k][:]   (rows of d bf16, d % 8 == 0), one wavefront per row
+__global__ __launch_bounds__(256) void gather_rows_kernel(const uint16_t* __restrict__ src, const int* __restrict__ perm, int k,
+                                                          int S, int d, uint16_t* __restrict__ dst) {
+  const int pos = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (pos >= S) return;
+  const int t = perm[pos] / k;
+  const uint4* s4 = reinterpret_cast<const uint4*>(src + (size_t)t * d);
+  uint4* d4 = reinterpret_cast<uint4*>(dst + (size_t)pos * d);
+  for (int c = lane; c < d / 8; c += 64) d4[c] = s4[c];
+}
+
+// ---- the gated unit with fused AbsMax re-quantisation (one wavefront per token) -------------
+//   Hd = silu(G) * U in fp32; gamma_h = 128 / max(|Hd|, 1e-5); Hq = codes; Ht = bf16(Hq / gamma_h)
+template <int NV>
+__global__ __launch_bounds__(256) void swiglu_quant_kernel(const uint16_t* __restrict__ U, const uint16_t* __restrict__ G,
+                                                           int T, int F, int8_t* __restrict__ Hq, float* __restrict__ gamma,
+                                                           uint16_t* __restrict__ Ht) {
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (t >= T) return;
+  const uint4* u4 = reinterpret_cast<const uint4*>(U + (size_t)t * F);
+  const uint4* g4 = reinterpret_cast<const uint4*>(G + (size_t)t * F);
+  const int nvec = F / 8;
+  float hd[NV > 0 ? NV : 1][8];
+  float amax = 0.0f;
+  auto eval = [&](int c, float* h) {
+    float uf[8], gf[8];
+    unpack8(u4[c], uf);
+    unpack8(g4[c], gf);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) h[j] = siluf_(gf[j]) * uf[j];
+  };
+  if constexpr (NV > 0) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = i * 64 + lane;
+      if (c < nvec) {
+        eval(c, hd[i]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(hd[i][j]));
+      }
+    }
+  } else {
+    for (int c = lane; c < nvec; c += 64) {
+      float h[8];
+      eval(c, h);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(h[j]));
+    }
+  }
+  amax = wave_max(amax);
+  const float g = 128.0f / fmaxf(amax, 1e-5f);
+  if (lane == 0) gamma[t] = g;
+  auto emit = [&](int c, const float* h) {
+    int q[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) q[j] = (int)fminf(fmaxf(rintf(__fmul_rn(h[j], g)), -128.0f), 127.0f);
+    const uint32_t w0 = (uint32_t)(q[0] & 0xFF) | ((uint32_t)(q[1] & 0xFF) << 8) | ((uint32_t)(q[2] & 0xFF) << 16) | ((uint32_t)(q[3] & 0xFF) << 24);
+    const uint32_t w1 = (uint32_t)(q[4] & 0xFF) | ((uint32_t)(q[5] & 0xFF) << 8) | ((uint32_t)(q[6] & 0xFF) << 16) | ((uint32_t)(q[7] & 0xFF) << 24);
+    *reinterpret_cast<uint2*>(Hq + (size_t)t * F + (size_t)c * 8) = make_uint2(w0, w1);
+    float o[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = (float)q[j] / g;
+    *reinterpret_cast<uint4*>(Ht + (size_t)t * F + (size_t)c * 8) = pack8(o);
+  };
+  if constexpr (NV > 0) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = i * 64 + lane;
+      if (c < nvec) emit(c, hd[i]);
+    }
+  } else {
+    for (int c = lane; c < nvec; c += 64) {
+      float h[8];
+      eval(c, h);
+      emit(c, h);
+    }
+  }
+}
+
+// dU = dHd * silu(G), dG = dHd * U * silu'(G)   (element-wise over T*F, 8 per thread)
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const uint16_t* __restrict__ dHd, const uint16_t* __restrict__ U,
+                                                         const uint16_t* __restrict__ G, size_t nvec, uint16_t* __restrict__ dU,
+                                                         uint16_t* __restrict__ dG) {
+  for (size_t c = (size_t)blockIdx.x * 256 + threadIdx.x; c < nvec; c += (size_t)gridDim.x * 256) {
+    float dh[8], uf[8], gf[8], du[8], dg[8];
+    unpack8(reinterpret_cast<const uint4*>(dHd)[c], dh);
+    unpack8(reinterpret_cast<const uint4*>(U)[c], uf);
+    unpack8(reinterpret_cast<const uint4*>(G)[c], gf);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      du[j] = dh[j] * siluf_(gf[j]);
+      dg[j] = dh[j] * uf[j] * dsiluf_(gf[j]);
+    }
+    reinterpret_cast<uint4*>(dU)[c] = pack8(du);
+    reinterpret_cast<uint4*>(dG)[c] = pack8(dg);
+  }
+}
+
+// ---- expert activation ----------------------------------------------------------------------
+// a = silu(ge) * ue  over S*r elements (slot order)
+__global__ __launch_bounds__(256) void expert_act_kernel(const uint16_t* __restrict__ ue, const uint16_t* __restrict__ ge,
+                                                         size_t nvec, uint16_t* __restrict__ a) {
+  const size_t c = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (c >= nvec) return;
+  float uf[8], gf[8], o[8];
+  unpack8(reinterpret_cast<const uint4*>(ue)[c], uf);
+  unpack8(reinterpret_cast<const uint4*>(ge)[c], gf);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) o[j] = siluf_(gf[j]) * uf[j];
+  reinterpret_cast<uint4*>(a)[c] = pack8(o);
+}
+
+// with s = alpha * gate[slot]:  du = s da silu(ge), dg = s da ue silu'(ge), as = s a   (r % 8 == 0)
+__global__ __launch_bounds__(256) void expert_act_bwd_kernel(const uint16_t* __restrict__ da, const uint16_t* __restrict__ ue,
+                                                             const uint16_t* __restrict__ ge, const uint16_t* __restrict__ a,
+                                                             const int* __restrict__ perm, const float* __restrict__ gate,
+                                                             float alpha, int r, size_t nvec, uint16_t* __restrict__ du,
+                                                             uint16_t* __restrict__ dg, uint16_t* __restrict__ as) {
+  const size_t c = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (c >= nvec) return;
+  const int pos = (int)(c / (size_t)(r / 8));
+  const float sc = alpha * gate[perm[pos]];
+  float d[8], uf[8], gf[8], af[8], o1[8], o2[8], o3[8];
+  unpack8(reinterpret_cast<const uint4*>(da)[c], d);
+  unpack8(reinterpret_cast<const uint4*>(ue)[c], uf);
+  unpack8(reinterpret_cast<const uint4*>(ge)[c], gf);
+  unpack8(reinterpret_cast<const uint4*>(a)[c], af);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float dj = sc * d[j];           // upstream of the expert output is alpha * gate * dY
+    o1[j] = dj * siluf_(gf[j]);
+    o2[j] = dj * uf[j] * dsiluf_(gf[j]);
+    o3[j] = sc * af[j];
+  }
+  reinterpret_cast<uint4*>(du)[c] = pack8(o1);
+  reinterpret_cast<uint4*>(dg)[c] = pack8(o2);
+  reinterpret_cast<uint4*>(as)[c] = pack8(o3);
+}
+
+// rd[pos] = <A[pos,:], B[pos,:]> (fp32), partial[block] = sum gate[perm[pos]] * rd[pos]  (for d alpha)
+__global__ __launch_bounds__(256) void rowdot_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ Bm,
+                                                     const int* __restrict__ perm, const float* __restrict__ gate, int S, int d,
+                                                     float* __restrict__ rd, double* __restrict__ partial) {
+  __shared__ double red[4];
+  const int pos = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  double contrib = 0.0;
+  if (pos < S) {
+    const uint4* a4 = reinterpret_cast<const uint4*>(A + (size_t)pos * d);
+    const uint4* b4 = reinterpret_cast<const uint4*>(Bm + (size_t)pos * d);
+    float acc = 0.0f;
+    for (int c = lane; c < d / 8; c += 64) {
+      float x[8], y[8];
+      unpack8(a4[c], x);
+      unpack8(b4[c], y);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc += x[j] * y[j];
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) {
+      rd[pos] = acc;
+      contrib = (double)gate[perm[pos]] * (double)acc;
+    }
+  }
+  const double t = block_sum_d<256>(contrib, red);
+  if (threadIdx.x == 0) partial[blockIdx.x] = t;
+}
+
+// Y[t,:] += alpha * sum_j gate[t,j] * Ys[inv[t*k+j], :]   (one wavefront per token)
+__global__ __launch_bounds__(256) void combine_fwd_kernel(uint16_t* __restrict__ Y, const uint16_t* __restrict__ Ys,
+                                                          const int* __restrict__ inv, const float* __restrict__ gate, float alpha,
+                                                          int T, int k, int d) {
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (t >= T) return;
+  uint4* y4 = reinterpret_cast<uint4*>(Y + (size_t)t * d);
+  for (int c = lane; c < d / 8; c += 64) {
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int j = 0; j < k; ++j) {
+      const float gt = gate[t * k + j];
+      float v[8];
+      unpack8(reinterpret_cast<const uint4*>(Ys + (size_t)inv[t * k + j] * d)[c], v);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += gt * v[i];
+    }
+    float y[8];
+    unpack8(y4[c], y);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) y[i] += alpha * acc[i];
+    y4[c] = pack8(y);
+  }
+}
+
+// dlogit[t,e] = sum_j dgate[t,j] * p[idx_j] * (1[e == idx_j] - p[e]),  dgate[t,j] = alpha * rd[inv[t*k+j]]
+__global__ __launch_bounds__(256) void router_bwd_kernel(const float* __restrict__ rd, const int* __restrict__ inv,
+                                                         const int* __restrict__ idx, const float* __restrict__ probs, float alpha,
+                                                         int T, int k, int E, float* __restrict__ dlogit) {
+  const int i = blockIdx.x * 256 + threadIdx.x;   // t * E + e
+  if (i >= T * E) return;
+  const int t = i / E, e = i % E;
+  const float pe = probs[i];
+  float acc = 0.0f;
+  for (int j = 0; j < k; ++j) {
+    const int ej = idx[t * k + j];
+    const float dgt = alpha * rd[inv[t * k + j]];
+    acc += dgt * probs[t * E + ej] * ((e == ej ? 1.0f : 0.0f) - pe);
+  }
+  dlogit[i] = acc;
+}
+
+// dWr partials: part[tc][e][c] = sum_{t in chunk tc} dlogit[t,e] * X[t,c]   (chunks of 256 tokens)
+__global__ __launch_bounds__(256) void dwr_partial_kernel(const float* __restrict__ dlogit, const uint16_t* __restrict__ X, int T,
+                                                          int d, int E, float* __restrict__ part) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  const int t0 = blockIdx.y * 256, t1 = min(T, t0 + 256);
+  if (c >= d) return;
+  for (int e0 = 0; e0 < E; e0 += 8) {
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int t = t0; t < t1; ++t) {
+      const float x = bf16_to_f32(X[(size_t)t * d + c]);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (e0 + u < E) acc[u] += dlogit[(size_t)t * E + e0 + u] * x;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (e0 + u < E) part[((size_t)blockIdx.y * E + e0 + u) * d + c] = acc[u];
+  }
+}
+__global__ __launch_bounds__(256) void dwr_final_kernel(const float* __restrict__ part, int nchunks, int n, float* __restrict__ dWr) {
+  const int i = blockIdx.x * 256 + threadIdx.x;   // e * d + c
+  if (i >= n) return;
+  float acc = 0.0f;
+  for (int tc = 0; tc < nchunks; ++tc) acc += part[(size_t)tc * n + i];
+  dWr[i] = acc;
+}
+
+// dX[t,:] += sum_j dXs[inv[t*k+j], :] + sum_e dlogit[t,e] * Wr[e,:]
+__global__ __launch_bounds__(256) void combine_bwd_kernel(uint16_t* __restrict__ dX, const uint16_t* __restrict__ dXs,
+                                                          const int* __restrict__ inv, const float* __restrict__ dlogit,
+                                                          const uint16_t* __restrict__ Wr, int T, int k, int d, int E) {
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (t >= T) return;
+  uint4* x4 = reinterpret_cast<uint4*>(dX + (size_t)t * d);
+  for (int c = lane; c < d / 8; c += 64) {
+    float acc[8];
+    unpack8(x4[c], acc);
+    for (int j = 0; j < k; ++j) {
+      float v[8];
+      unpack8(reinterpret_cast<const uint4*>(dXs + (size_t)inv[t * k + j] * d)[c], v);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += v[i];
+    }
+    for (int e = 0; e < E; ++e) {
+      const float dl = dlogit[(size_t)t * E + e];
+      float w[8];
+      unpack8(reinterpret_cast<const uint4*>(Wr + (size_t)e * d)[c], w);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += dl * w[i];
+    }
+    x4[c] = pack8(acc);
+  }
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+int pq_launch_route(const int* idx, int S, int E, int* counts, int* offsets, int* perm, int* inv, hipStream_t s) {
+  pq_prof_scope prof(PQP_MOE_ROUTE, s);
+  route_count_kernel<<<(E + 3) / 4, 256, 0, s>>>(idx, S, E, counts);
+  PQ_CHECK_LAUNCH("route_count_kernel");
+  route_build_kernel<<<(E + 3) / 4, 256, 0, s>>>(idx, counts, S, E, offsets, perm, inv);
+  PQ_CHECK_LAUNCH("route_build_kernel");
+  return PQ_OK;
+}
+
+int pq_launch_gather_rows(const void* src, const int* perm, int k, int S, int d, void* dst, hipStream_t s) {
+  if (S == 0) return PQ_OK;
+  pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
+  gather_rows_kernel<<<(S + 3) / 4, 256, 0, s>>>((const uint16_t*)src, perm, k, S, d, (uint16_t*)dst);
+  PQ_CHECK_LAUNCH("gather_rows_kernel");
+  return PQ_OK;
+}
+
+int pq_launch_swiglu_quant(const void* U, const void* G, int T, int F, int8_t* Hq, float* gamma, void* Ht, hipStream_t s) {
+  if (T == 0) return PQ_OK;
+  pq_prof_scope prof(PQP_SWIGLU, s);
+  const int per_lane = (F / 8 + 63) / 64;
+  dim3 grid((T + 3) / 4), block(256);
+  const uint16_t* u = (const uint16_t*)U;
+  const uint16_t* g = (const uint16_t*)G;
+  if (per_lane <= 4) swiglu_quant_kernel<4><<<grid, block, 0, s>>>(u, g, T, F, Hq, gamma, (uint16_t*)Ht);
+  else if (per_lane <= 12) swiglu_quant_kernel<12><<<grid, block, 0, s>>>(u, g, T, F, Hq, gamma, (uint16_t*)Ht);
+  else swiglu_quant_kernel<0><<<grid, block, 0, s>>>(u, g, T, F, Hq, gamma, (uint16_t*)Ht);
+  PQ_CHECK_LAUNCH("swiglu_quant_kernel");
+  return PQ_OK;
+}
+
+int pq_launch_swiglu_bwd(const void* dHd, const void* U, const void* G, size_t n, void* dU, void* dG, hipStream_t s) {
+  if (n == 0) return PQ_OK;
+  pq_prof_scope prof(PQP_SWIGLU, s);
+  const size_t nvec = n / 8;
+  size_t blocks = (nvec + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  swiglu_bwd_kernel<<<(unsigned)blocks, 256, 0, s>>>((const uint16_t*)dHd, (const uint16_t*)U, (const uint16_t*)G, nvec,
+                                                    (uint16_t*)dU, (uint16_t*)dG);
+  PQ_CHECK_LAUNCH("swiglu_bwd_kernel");
+  return PQ_OK;
+}
+
+int pq_launch_expert_act(const void* ue, const void* ge, size_t n, void* a, hipStream_t s) {
+  if (n == 0) return PQ_OK;
+  pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
+  expert_act_kernel<<<(unsigned)((n / 8 + 255) / 256), 256, 0, s>>>((const uint16_t*)ue, (const uint16_t*)ge, n / 8, (uint16_t*)a);
+  PQ_CHECK_LAUNCH("expert_act_kernel");
+  return PQ_OK;
+}
+
+int pq_launch_expert_act_bwd(const void* da, const void* ue, const void* ge, const void* a, const int* perm, const float* gate,
+                             float alpha, int S, int r, void* du, void* dg, void* as, hipStream_t s) {
+  if (S == 0) return PQ_OK;
+  pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
+  const size_t nvec = (size_t)S * r / 8;
+  expert_act_bwd_kernel<<<(unsigned)((nvec + 255) / 256), 256, 0, s>>>((const uint16_t*)da, (const uint16_t*)ue, (const uint16_t*)ge,
+                                                                      (const uint16_t*)a, perm, gate, alpha, r, nvec, (uint16_t*)du,
+                                                                      (uint16_t*)dg, (uint16_t*)as);
+  PQ_CHECK_LAUNCH("expert_act_bwd_kernel");
+  return PQ_OK;
+}
+
+int pq_rowdot_blocks(int S) { return (S + 3) / 4; }
+int pq_launch_rowdot(const void* A, const void* B, const int* perm, const float* gate, int S, int d, float* rd, double* partial,
+                     hipStream_t s) {
+  if (S == 0) return PQ_OK;
+  pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
+  rowdot_kernel<<<(S + 3) / 4, 256, 0, s>>>((const uint16_t*)A, (const uint16_t*)B, perm, gate, S, d, rd, partial);
+  PQ_CHECK_LAUNCH("rowdot_kernel");
+  return PQ_OK;
+}
+
+int pq_launch_combine_fwd(void* Y, const void* Ys, const int* inv, const float* gate, float alpha, int T, int k, int d, hipStream_t s) {
+  if (T == 0) return PQ_OK;
+  pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
+  combine_fwd_kernel<<<(T + 3) / 4, 256, 0, s>>>((uint16_t*)Y, (const uint16_t*)Ys, inv, gate, alpha, T, k, d);
+  PQ_CHECK_LAUNCH("combine_fwd_kernel");
+  return PQ_OK;
+}
+
+int pq_launch_router_bwd(const float* rd, const int* inv, const int* idx, const float* probs, float alpha, int T, int k, int E,
+                         float* dlogit, hipStream_t s) {
+  if (T == 0) return PQ_OK;
+  pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
+  router_bwd_kernel<<<(T * E + 255) / 256, 256, 0, s>>>(rd, inv, idx, probs, alpha, T, k, E, dlogit);
+  PQ_CHECK_LAUNCH("router_bwd_kernel");
+  return PQ_OK;
+}
+
+size_t pq_dwr_scratch_bytes(int T, int d, int E) { return (size_t)((T + 255) / 256) * E * d * sizeof(float); }
+int pq_launch_dwr(const float* dlogit, const void* X, int T, int d, int E, float* part, float* dWr, hipStream_t s) {
+  pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
+  const int nchunks = (T + 255) / 256;
+  if (nchunks > 0) {
+    dim3 grid((d + 255) / 256, nchunks);
+    dwr_partial_kernel<<<grid, 256, 0, s>>>(dlogit, (const uint16_t*)X, T, d, E, part);
+    PQ_CHECK_LAUNCH("dwr_partial_kernel");
+  }
+  dwr_final_kernel<<<(E * d + 255) / 256, 256, 0, s>>>(part, nchunks, E * d, dWr);
+  PQ_CHECK_LAUNCH("dwr_final_kernel");
+  return PQ_OK;
+}
+
+int pq_launch_combine_bwd(void* dX, const void* dXs, const int* inv, const float* dlogit, const void* Wr, int T, int k, int d, int E,
+                          hipStream_t s) {
+  if (T == 0) return PQ_OK;
+  pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
+  combine_bwd_kernel<<<(T + 3) / 4, 256, 0, s>>>((uint16_t*)dX, (const uint16_t*)dXs, inv, dlogit, (const uint16_t*)Wr, T, k, d, E);
+  PQ_CHECK_LAUNCH("combine_bwd_kernel");
+  return PQ_OK;
+}

@@ -1,0 +1,76 @@
+"""Parity of the decoupled FFN (1-bit up/gate/down + routed bf16 experts; Sec. 3.2, 3.3) against the
+CPU oracle: outputs and gradients within 2e-2 (max-norm relative, bf16 I/O)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pquant_oracle as po
+from paper_2602_22592_amd import binding as pq
+from paper_2602_22592_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda().to(torch.bfloat16)
+
+
+def relerr(a, b):
+    a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
+    return float(np.abs(a - b).max() / max(np.abs(b).max(), 1e-30))
+
+
+def run_ffn(c, top_k, alpha, beta):
+    T, D, F, E, r = c["tokens"], c["d_model"], c["d_ffn"], c["n_experts"], c["hp_rank"]
+    desc = pq.FFNDesc(T, D, F, r, E, top_k, pq.PQ_BF16, alpha, beta)
+    bufs = pq.FFNBuffers(desc)
+    t = {k: dev(c[k]) for k in ("X", "dY", "W_up", "W_gate", "W_down", "Up", "Gate", "Down", "Wr")}
+    f32 = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
+    Y = torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
+    out = dict(dW_up=f32(F, D), dW_gate=f32(F, D), dW_down=f32(D, F), dUp=f32(E, r, D), dGate=f32(E, r, D),
+               dDown=f32(E, D, r), dWr=f32(E, D), dab=f32(2))
+    pq.ffn_fwd(desc, t["X"], t["W_up"], t["W_gate"], t["W_down"], t["Up"], t["Gate"], t["Down"], t["Wr"], Y, bufs)
+    pq.ffn_bwd(desc, t["dY"], t["X"], t["Up"], t["Gate"], t["Down"], t["Wr"], bufs, dX, out["dW_up"], out["dW_gate"],
+               out["dW_down"], out["dUp"], out["dGate"], out["dDown"], out["dWr"], out["dab"])
+    torch.cuda.synchronize()
+    res = {k: v.cpu().numpy() for k, v in out.items()}
+    res["Y"] = Y.float().cpu().numpy(); res["dX"] = dX.float().cpu().numpy()
+    return res
+
+
+def check_ffn(c, top_k=1, alpha=2.0, beta=0.2):
+    got = run_ffn(c, top_k, alpha, beta)
+    f = po.ffn_fwd(c["X"], c["W_up"], c["W_gate"], c["W_down"], c["Up"], c["Gate"], c["Down"], c["Wr"], alpha, beta,
+                   top_k=top_k, bf16=True)
+    g = po.ffn_bwd(c["dY"], c["X"], c["Up"], c["Gate"], c["Down"], c["Wr"], alpha, beta, f)
+    errs = {"Y": relerr(got["Y"], f["Y"])}
+    for k in ("dX", "dW_up", "dW_gate", "dW_down", "dUp", "dGate", "dDown", "dWr"):
+        errs[k] = relerr(got[k], g[k])
+    dY = c["dY"].astype(np.float64)
+    sb = max(abs(g["dbeta"]), np.sqrt(((dY * f["Y1"]) ** 2).sum()), 1e-30)
+    sa = max(abs(g["dalpha"]), np.sqrt(((dY * f["Yhp"]) ** 2).sum()), 1e-30)
+    errs["dbeta"] = abs(got["dab"][1] - g["dbeta"]) / sb
+    errs["dalpha"] = abs(got["dab"][0] - g["dalpha"]) / sa
+    print("  errors: " + ", ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
+    for k, v in errs.items():
+        assert v <= TOL, f"{k}: {v} > {TOL}"
+
+
+@pytest.mark.parametrize("T,D,F,E,r,k", [(200, 96, 160, 4, 8, 1), (200, 96, 160, 4, 8, 2), (700, 256, 544, 8, 32, 1),
+                                         (130, 64, 64, 2, 16, 2), (1, 32, 32, 8, 8, 1)])
+def test_ffn_small(T, D, F, E, r, k):
+    print(f"ffn T={T} d={D} F={F} E={E} r={r} k={k}", flush=True)
+    check_ffn(wl.ffn_case(80 + T + k, T, D, F, E, r), top_k=k)
+
+
+def test_ffn_scale_edge_cases():
+    c = wl.ffn_case(90, 150, 64, 96, 4, 8)
+    check_ffn(c, alpha=0.0, beta=0.7)
+    check_ffn(c, alpha=1.5, beta=0.0)
+
+
+def test_ffn_config3_reduced_tokens():
+    print("ffn config 3 shape at T=384 (d=2048, F=5504, E=8, r=32, top-1)", flush=True)
+    check_ffn(wl.config3(tokens=384), top_k=1)
