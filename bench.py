@@ -102,6 +102,81 @@ def decode_bench(pq, torch, batch, n_layers=64, steps=20, warmup=3):
             "us_per_layer": round(total_us / n_layers, 3), "bytes_per_layer": (main_bytes + prep_bytes) // n_layers}
 
 
+def _time_steps(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def ffn_bench(pq, torch, T=8192, D=2048, F=5504, E=8, r=32, steps=5, warmup=2):
+    """Config 3: the 1.3B-shaped decoupled FFN (three 1-bit projections + E=8 top-1 experts of width 32), fwd+bwd."""
+    g = torch.Generator(device="cuda").manual_seed(3)
+    bf = torch.bfloat16
+    rn = lambda *s, std=0.02: (torch.randn(s, device="cuda", generator=g) * std).to(bf)
+    X = rn(T, D, std=1.0); dY = rn(T, D, std=1.0)
+    W_up, W_gate, W_down = rn(F, D), rn(F, D), rn(D, F)
+    Up, Gate, Down, Wr = rn(E, r, D), rn(E, r, D), rn(E, D, r), rn(E, D)
+    desc = pq.FFNDesc(T, D, F, r, E, 1, pq.PQ_BF16, 2.0, 0.2)
+    bufs = pq.FFNBuffers(desc)
+    f32 = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
+    Y = torch.empty((T, D), dtype=bf, device="cuda"); dX = torch.empty((T, D), dtype=bf, device="cuda")
+    gr = (f32(F, D), f32(F, D), f32(D, F), f32(E, r, D), f32(E, r, D), f32(E, D, r), f32(E, D), f32(2))
+
+    def step():
+        pq.ffn_fwd(desc, X, W_up, W_gate, W_down, Up, Gate, Down, Wr, Y, bufs)
+        pq.ffn_bwd(desc, dY, X, Up, Gate, Down, Wr, bufs, dX, *gr)
+    pq.prof_reset(); pq.prof_enable(True)
+    ms = _time_steps(torch, step, steps, warmup)
+    pq.prof_enable(False)
+    prof = pq.prof_read(); pq.prof_reset()
+    t_mfma = 3 * 2.0 * T * D * F / PEAK_I8 + 6 * 2.0 * T * D * F / PEAK_BF16       # experts are < 1 % of the flops
+    return {"workload": f"tokens={T}, d_model={D}, d_ffn={F}, E={E} experts of width {r}, top-1, bf16, fwd+bwd",
+            "ms_per_step": round(ms, 4), "tokens_per_s": round(T / ms * 1e3, 1), "mfma_frac_of_step": round(t_mfma / (ms * 1e-3), 4),
+            "kernels_us_total_per_step": {k: round(1e3 * v[0] / (steps + warmup), 1) for k, v in sorted(prof.items())}}
+
+
+def stack_bench(pq, torch, L=24, T=16384, D=2048, F=5504, E=8, r=32, steps=2, warmup=1):
+    """Config 5: 24 layers of {q,k,v,o pure 1-bit 2048^2 linears + the config-3 FFN}, one fwd+bwd over 16384 tokens."""
+    from paper_2602_22592_amd import workloads as wl
+    from paper_2602_22592_amd.stack import Stack
+    g = torch.Generator(device="cuda").manual_seed(5)
+    bf = torch.bfloat16
+    rn = lambda *s, std=0.02: (torch.randn(s, device="cuda", generator=g) * std).to(bf)
+    shapes = dict(Wq=(D, D), Wk=(D, D), Wv=(D, D), Wo=(D, D), W_up=(F, D), W_gate=(F, D), W_down=(D, F), Up=(E, r, D),
+                  Gate=(E, r, D), Down=(E, D, r), Wr=(E, D))
+    weights = [{n: rn(*s) for n, s in shapes.items()} for _ in range(L)]
+    grads = [dict({n: torch.empty(s, dtype=torch.float32, device="cuda") for n, s in shapes.items()},
+                  dab=torch.empty(2, dtype=torch.float32, device="cuda")) for _ in range(L)]
+    table = rn(32000, D, std=1.0)
+    ids = torch.randint(0, 32000, (T,), dtype=torch.int32, device="cuda", generator=g)
+    dY = rn(T, D, std=1.0)
+    st = Stack(L, T, D, F, E, r, 1, [wl.TRAINED_ALPHA[l % 16] for l in range(L)], [wl.TRAINED_BETA[l % 16] for l in range(L)])
+    h0 = torch.empty((T, D), dtype=bf, device="cuda")
+
+    def step():
+        pq.glue_gather_rows(table, ids, h0)
+        st.forward(h0, weights)
+        st.backward(dY, weights, grads)
+    pq.prof_reset(); pq.prof_enable(True)
+    ms = _time_steps(torch, step, steps, warmup)
+    pq.prof_enable(False)
+    prof = pq.prof_read(); pq.prof_reset()
+    glue_ms = prof.get("glue", (0.0, 1))[0] / (steps + warmup)
+    ops_i8 = L * (4 * 2.0 * T * D * D + 3 * 2.0 * T * D * F)
+    t_mfma = ops_i8 / PEAK_I8 + 2 * ops_i8 / PEAK_BF16
+    return {"workload": f"{L} layers x (4 pure 1-bit {D}x{D} linears + FFN d_ffn={F}, E={E}x{r} top-1), tokens={T}, bf16, fwd+bwd",
+            "ms_per_step": round(ms, 3), "ms_per_layer": round(ms / L, 3), "tokens_per_s": round(T / ms * 1e3, 1),
+            "glue_ms_per_step": round(glue_ms, 3), "linears_ms_per_step": round(ms - glue_ms, 3),
+            "mfma_frac_of_step": round(t_mfma / (ms * 1e-3), 4)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -111,6 +186,8 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-ffn", action="store_true")
+    ap.add_argument("--no-stack", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -188,6 +265,12 @@ def main():
     if not args.no_decode:
         out["decode_gemv"] = {"metric": "1-bit decode GEMV HBM GB/s (4096->11008, E=8 top-2 r=64 experts)",
                               "B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8)}
+    if not args.no_ffn:
+        out["ffn_config3"] = ffn_bench(pq, torch)
+    if not args.no_stack:
+        del X, W, dY, A, B, Y, dX, dW, bufs
+        torch.cuda.empty_cache()
+        out["stack_config5"] = stack_bench(pq, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample_tokens)
     print(json.dumps(out), flush=True)

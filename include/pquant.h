@@ -189,6 +189,14 @@ int pq_decode_gemv(const pq_decode_desc* desc, const void* X, const uint32_t* pa
                    const void* hpA, const void* hpB, const void* Wr, void* Y, int32_t* acc_out, void* workspace,
                    size_t workspace_bytes, void* stream);
 
+/* Glue for chaining the linears into a layer stack; not part of the method.
+ * pq_glue_lincomb: out = c0 x0 + c1 x1 + c2 x2 + c3 x3 over n bf16 elements (x1..x3 may be NULL;
+ * fp32 arithmetic, one rounding; n % 8 == 0) -- residual adds and the mean that stands in for the
+ * attention core.  pq_glue_gather_rows: out[t][:] = table[ids[t]][:] (bf16 rows of d elements). */
+int pq_glue_lincomb(void* out, const void* x0, const void* x1, const void* x2, const void* x3, float c0,
+                    float c1, float c2, float c3, size_t n, void* stream);
+int pq_glue_gather_rows(const void* table, const int32_t* ids, int32_t T, int32_t d, void* out, void* stream);
+
 /* Per-kernel timing for benchmarks.  While enabled, every kernel launch made by the library is
  * bracketed by a pair of HIP events on the caller's stream (events are created on demand, so this
  * mode allocates; it is off by default).  pq_prof_count() = number of kernel labels;

@@ -367,6 +367,43 @@ def decode_gemv(x, P, mu_lambda, alpha, beta, A=None, B=None, Wr=None, top_k=2):
                       mu_lambda=mu_lambda, scale_fp16=True)
 
 
+# ----------------------------------------------------------------------------------------------
+# A stack of layers made of the pieces above (used only to check the chaining of the GPU calls)
+# ----------------------------------------------------------------------------------------------
+def stack_fwd(h0, layers, top_k=1):
+    """Per layer: q,k,v = pure 1-bit linears of h (Sec. 3.1); m = (q+k+v)/3 stands in for the attention
+    core; h1 = h + L_o(m); h2 = h1 + FFN(h1) (Sec. 3.2/3.3).  Every stored activation is bf16."""
+    h = _round_io(h0, True)
+    saved = []
+    for w in layers:
+        fq, fk, fv = (linear_fwd(h, w[n], 0.0, 1.0) for n in ("Wq", "Wk", "Wv"))
+        q, k, v = (_round_io(f["Y"], True).astype(F64) for f in (fq, fk, fv))
+        m = _round_io((q + k + v) / 3.0, True)
+        fo = linear_fwd(m, w["Wo"], 0.0, 1.0)
+        h1 = _round_io(h.astype(F64) + _round_io(fo["Y"], True), True)
+        ff = ffn_fwd(h1, w["W_up"], w["W_gate"], w["W_down"], w["Up"], w["Gate"], w["Down"], w["Wr"], w["alpha"], w["beta"],
+                     top_k=top_k, bf16=True)
+        h2 = _round_io(h1.astype(F64) + _round_io(ff["Y"], True), True)
+        saved.append(dict(h=h, m=m, h1=h1, fq=fq, fk=fk, fv=fv, fo=fo, ff=ff))
+        h = h2
+    return h, saved
+
+
+def stack_bwd(dY, layers, saved):
+    d = np.asarray(dY, dtype=F64)
+    grads = []
+    for w, sv in zip(reversed(layers), reversed(saved)):
+        gf = ffn_bwd(d, sv["h1"], w["Up"], w["Gate"], w["Down"], w["Wr"], w["alpha"], w["beta"], sv["ff"])
+        dh1 = d + gf["dX"]
+        go = linear_bwd(dh1, sv["m"], w["Wo"], 0.0, 1.0, sv["fo"])
+        dm = go["dX"] / 3.0
+        gq, gk, gv = (linear_bwd(dm, sv["h"], w[n], 0.0, 1.0, sv[f]) for n, f in (("Wq", "fq"), ("Wk", "fk"), ("Wv", "fv")))
+        d = dh1 + gq["dX"] + gk["dX"] + gv["dX"]
+        grads.append(dict(Wq=gq["dW"], Wk=gk["dW"], Wv=gv["dW"], Wo=go["dW"], W_up=gf["dW_up"], W_gate=gf["dW_gate"],
+                          W_down=gf["dW_down"], Up=gf["dUp"], Gate=gf["dGate"], Down=gf["dDown"], Wr=gf["dWr"]))
+    return d, grads[::-1]
+
+
 def bits_per_weight(frac_1bit, frac_8bit):
     """Average bit-width of a decoupled layer (Table 1 percentages -> the 'Bit' column of Table 2)."""
     return frac_1bit * 1.0 + frac_8bit * 8.0

@@ -24,7 +24,7 @@ EXPORTS = [
     "pq_router_topk", "pq_onebit_acc", "pq_linear_ctx_bytes", "pq_linear_workspace_bytes",
     "pq_linear_fwd", "pq_linear_bwd", "pq_prof_enable", "pq_prof_count", "pq_prof_label", "pq_prof_read",
     "pq_prof_reset", "pq_decode_workspace_bytes", "pq_decode_gemv", "pq_pack_tiled64_bytes", "pq_pack_retile64", "pq_ffn_ctx_bytes", "pq_ffn_workspace_bytes",
-    "pq_ffn_fwd", "pq_ffn_bwd",
+    "pq_ffn_fwd", "pq_ffn_bwd", "pq_glue_lincomb", "pq_glue_gather_rows",
 ]
 
 
@@ -144,13 +144,13 @@ def make_desc(tokens, d_in, d_out, hp_rank=0, n_experts=1, top_k=1, io_dtype=PQ_
 class LinearBuffers:
     """Caller-owned ctx / workspace for one descriptor (allocated once, reused across steps)."""
 
-    def __init__(self, desc, device="cuda"):
+    def __init__(self, desc, device="cuda", ws=None):
         nctx = lib().pq_linear_ctx_bytes(C.byref(desc))
         nws = lib().pq_linear_workspace_bytes(C.byref(desc))
         if nctx == 0 or nws == 0:
             raise PQError(f"bad descriptor: {lib().pq_last_error_string().decode()}")
         self.ctx = _bytes(nctx, device)
-        self.ws = _bytes(nws, device)
+        self.ws = ws if ws is not None else _bytes(nws, device)   # scratch may be shared between layers
 
 
 def linear_fwd(desc, X, W, Y, bufs, A=None, B=None, Wr=None, mu_lambda=None, save=True):
@@ -213,13 +213,13 @@ def pack_retile64(P, K):
 
 
 class FFNBuffers:
-    def __init__(self, desc, device="cuda"):
+    def __init__(self, desc, device="cuda", ws=None):
         nctx = lib().pq_ffn_ctx_bytes(C.byref(desc))
         nws = lib().pq_ffn_workspace_bytes(C.byref(desc))
         if nctx == 0 or nws == 0:
             raise PQError(f"bad FFN descriptor: {lib().pq_last_error_string().decode()}")
         self.ctx = _bytes(nctx, device)
-        self.ws = _bytes(nws, device)
+        self.ws = ws if ws is not None else _bytes(nws, device)
 
 
 def ffn_fwd(desc, X, W_up, W_gate, W_down, Up, Gate, Down, Wr, Y, bufs):
@@ -233,3 +233,16 @@ def ffn_bwd(desc, dY, X, Up, Gate, Down, Wr, bufs, dX, dW_up, dW_gate, dW_down, 
     _check(lib().pq_ffn_bwd(C.byref(desc), _p(dY), _p(X), _p(Up), _p(Gate), _p(Down), _p(Wr), _p(bufs.ctx),
                             C.c_size_t(bufs.ctx.numel()), _p(dX), _p(dW_up), _p(dW_gate), _p(dW_down), _p(dUp),
                             _p(dGate), _p(dDown), _p(dWr), _p(d_ab), _p(bufs.ws), C.c_size_t(bufs.ws.numel()), _stream()))
+
+
+def glue_lincomb(out, xs, cs):
+    xs = list(xs) + [None] * (4 - len(xs))
+    cs = list(cs) + [0.0] * (4 - len(cs))
+    _check(lib().pq_glue_lincomb(_p(out), _p(xs[0]), _p(xs[1]), _p(xs[2]), _p(xs[3]), C.c_float(cs[0]), C.c_float(cs[1]),
+                                 C.c_float(cs[2]), C.c_float(cs[3]), C.c_size_t(out.numel()), _stream()))
+    return out
+
+
+def glue_gather_rows(table, ids, out):
+    _check(lib().pq_glue_gather_rows(_p(table), _p(ids), ids.numel(), table.shape[1], _p(out), _stream()))
+    return out

@@ -30,7 +30,7 @@ std::vector<prof_sample*> g_prof_samples;
 const char* const g_prof_names[PQP_COUNT] = {
     "quant_act", "wstats_partial", "pack_sign", "router", "reduce_partials",
     "gemm_onebit_fwd", "gemm_hp_H", "gemm_hp_Y", "gemm_dH", "gemm_dX", "gemm_dX_hp",
-    "gemm_dW", "gemm_dB", "gemm_dA", "gemm_other", "decode_prep", "decode_h", "decode_main", "moe_route", "moe_elementwise", "swiglu", "gemm_expert"};
+    "gemm_dW", "gemm_dB", "gemm_dA", "gemm_other", "decode_prep", "decode_h", "decode_main", "moe_route", "moe_elementwise", "swiglu", "gemm_expert", "glue"};
 }  // namespace
 
 pq_prof_scope::pq_prof_scope(int label_, hipStream_t s_) : label(label_), s(s_), slot(nullptr) {
@@ -482,4 +482,24 @@ extern "C" int pq_pack_retile64(const uint32_t* packed, int32_t N, int32_t K, ui
   PQ_REQUIRE(packed && tiled, PQ_ERR_BAD_ARG, "NULL buffer");
   PQ_REQUIRE(aligned16(packed) && aligned16(tiled), PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
   return pq_launch_retile64(packed, N, K, tiled, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Glue for chaining linears into a layer stack (not part of the method: residual adds, row gather)
+// ---------------------------------------------------------------------------------------------
+extern "C" int pq_glue_lincomb(void* out, const void* x0, const void* x1, const void* x2, const void* x3, float c0,
+                               float c1, float c2, float c3, size_t n, void* stream) {
+  PQ_REQUIRE(out && x0, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(n % 8 == 0, PQ_ERR_SHAPE, "n=%zu must be a multiple of 8", n);
+  PQ_REQUIRE(aligned16(out) && aligned16(x0) && aligned16(x1) && aligned16(x2) && aligned16(x3), PQ_ERR_SHAPE,
+             "buffers must be 16-byte aligned");
+  return pq_launch_lincomb(out, x0, x1, x2, x3, c0, c1, c2, c3, n, (hipStream_t)stream);
+}
+
+extern "C" int pq_glue_gather_rows(const void* table, const int32_t* ids, int32_t T, int32_t d, void* out, void* stream) {
+  PQ_REQUIRE(T >= 0 && d > 0 && d % 8 == 0, PQ_ERR_SHAPE, "bad shape T=%d d=%d (d must be a multiple of 8)", T, d);
+  if (T == 0) return PQ_OK;
+  PQ_REQUIRE(table && ids && out, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(aligned16(table) && aligned16(out), PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
+  return pq_launch_gather_rows(table, ids, 1, T, d, out, (hipStream_t)stream);
 }

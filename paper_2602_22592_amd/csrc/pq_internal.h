@@ -6,7 +6,7 @@
 enum pq_prof_id {
   PQP_QUANT = 0, PQP_WSTATS, PQP_PACK, PQP_ROUTER, PQP_REDUCE,
   PQP_GEMM_ONEBIT, PQP_GEMM_HP_H, PQP_GEMM_HP_Y, PQP_GEMM_DH, PQP_GEMM_DX, PQP_GEMM_DX_HP,
-  PQP_GEMM_DW, PQP_GEMM_DB, PQP_GEMM_DA, PQP_GEMM_OTHER, PQP_DECODE_PREP, PQP_DECODE_H, PQP_DECODE_MAIN, PQP_MOE_ROUTE, PQP_MOE_ELEMENTWISE, PQP_SWIGLU, PQP_GEMM_EXPERT, PQP_COUNT
+  PQP_GEMM_DW, PQP_GEMM_DB, PQP_GEMM_DA, PQP_GEMM_OTHER, PQP_DECODE_PREP, PQP_DECODE_H, PQP_DECODE_MAIN, PQP_MOE_ROUTE, PQP_MOE_ELEMENTWISE, PQP_SWIGLU, PQP_GEMM_EXPERT, PQP_GLUE, PQP_COUNT
 };
 struct pq_prof_scope {   // records an event pair around the launches made while it is alive
   int label; hipStream_t s; void* slot;
@@ -131,3 +131,5 @@ size_t pq_dwr_scratch_bytes(int T, int d, int E);
 int pq_launch_dwr(const float* dlogit, const void* X, int T, int d, int E, float* part, float* dWr, hipStream_t s);
 int pq_launch_combine_bwd(void* dX, const void* dXs, const int* inv, const float* dlogit, const void* Wr, int T, int k, int d, int E,
                           hipStream_t s);
+int pq_launch_lincomb(void* out, const void* x0, const void* x1, const void* x2, const void* x3, float c0, float c1, float c2,
+                      float c3, size_t n, hipStream_t s);

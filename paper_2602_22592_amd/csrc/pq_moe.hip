@@ -321,7 +321,49 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(uint16_t* __restrict__
   }
 }
 
+// out = sum_i c[i] * x[i]  (up to 4 bf16 tensors, fp32 arithmetic, one rounding): the glue between
+// the linears of a layer stack (residual adds, the stand-in for the attention core)
+__global__ __launch_bounds__(256) void lincomb_kernel(uint16_t* __restrict__ out, const uint16_t* x0, const uint16_t* x1,
+                                                      const uint16_t* x2, const uint16_t* x3, float c0, float c1, float c2,
+                                                      float c3, size_t nvec) {
+  for (size_t c = (size_t)blockIdx.x * 256 + threadIdx.x; c < nvec; c += (size_t)gridDim.x * 256) {
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, v[8];
+    unpack8(reinterpret_cast<const uint4*>(x0)[c], v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = c0 * v[j];
+    if (x1) {
+      unpack8(reinterpret_cast<const uint4*>(x1)[c], v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] += c1 * v[j];
+    }
+    if (x2) {
+      unpack8(reinterpret_cast<const uint4*>(x2)[c], v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] += c2 * v[j];
+    }
+    if (x3) {
+      unpack8(reinterpret_cast<const uint4*>(x3)[c], v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] += c3 * v[j];
+    }
+    reinterpret_cast<uint4*>(out)[c] = pack8(acc);
+  }
+}
+
 }  // namespace
+
+int pq_launch_lincomb(void* out, const void* x0, const void* x1, const void* x2, const void* x3, float c0, float c1, float c2,
+                      float c3, size_t n, hipStream_t s) {
+  if (n == 0) return PQ_OK;
+  pq_prof_scope prof(PQP_GLUE, s);
+  const size_t nvec = n / 8;
+  size_t blocks = (nvec + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  lincomb_kernel<<<(unsigned)blocks, 256, 0, s>>>((uint16_t*)out, (const uint16_t*)x0, (const uint16_t*)x1, (const uint16_t*)x2,
+                                                 (const uint16_t*)x3, c0, c1, c2, c3, nvec);
+  PQ_CHECK_LAUNCH("lincomb_kernel");
+  return PQ_OK;
+}
 
 // ---------------------------------------------------------------------------------------------
 int pq_launch_route(const int* idx, int S, int E, int* counts, int* offsets, int* perm, int* inv, hipStream_t s) {

@@ -125,3 +125,30 @@ def decode_case(seed, batch, d_in=4096, d_out=11008, n_experts=8, hp_rank=64, n_
 
 def config4(batch=1, seed=4, n_layers=1):
     return decode_case(seed, batch, n_layers=n_layers)
+
+
+# Feature scales of the trained 1.3B model (App. F, table of feature scaling after training), in the
+# order the paper lists the layers; used cyclically as realistic per-layer alpha/beta.
+TRAINED_ALPHA = [1.82, 1.73, 1.57, 1.59, 1.39, 1.33, 1.25, 1.22, 1.34, 1.49, 1.37, 1.27, 1.38, 1.45, 1.56, 1.61]
+TRAINED_BETA = [0.78, 0.62, 0.48, 0.42, 0.38, 0.34, 0.31, 0.26, 0.29, 0.36, 0.43, 0.45, 0.41, 0.47, 0.52, 0.50]
+
+
+def stack_case(seed, n_layers, tokens, d_model, d_ffn, n_experts, hp_rank, vocab=32000, w_std=0.02):
+    """Token ids ~ U[0, vocab) gathering rows of an N(0,1) bf16 table, per-layer weights of a stack of
+    {q,k,v,o pure 1-bit linears + decoupled FFN}, and an N(0,1) output gradient."""
+    rng = np.random.default_rng(seed)
+    layers = []
+    for l in range(n_layers):
+        w = {n: normal(rng, (d_model, d_model), w_std, True) for n in ("Wq", "Wk", "Wv", "Wo")}
+        w.update(W_up=normal(rng, (d_ffn, d_model), w_std, True), W_gate=normal(rng, (d_ffn, d_model), w_std, True),
+                 W_down=normal(rng, (d_model, d_ffn), w_std, True),
+                 Up=normal(rng, (n_experts, hp_rank, d_model), w_std, True),
+                 Gate=normal(rng, (n_experts, hp_rank, d_model), w_std, True),
+                 Down=normal(rng, (n_experts, d_model, hp_rank), w_std, True),
+                 Wr=normal(rng, (n_experts, d_model), w_std, True),
+                 alpha=TRAINED_ALPHA[l % 16], beta=TRAINED_BETA[l % 16])
+        layers.append(w)
+    return {"layers": layers, "table": normal(rng, (vocab, d_model), 1.0, True),
+            "ids": rng.integers(0, vocab, size=tokens).astype(np.int32),
+            "dY": normal(rng, (tokens, d_model), 1.0, True),
+            "tokens": tokens, "d_model": d_model, "d_ffn": d_ffn, "n_experts": n_experts, "hp_rank": hp_rank}

@@ -1,0 +1,50 @@
+"""The layer stack (q,k,v,o pure 1-bit linears + decoupled FFN per layer) chained on the GPU against
+the same chain of oracle calls, at 2 layers and T=256 (bf16; 2e-2 max-norm relative)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pquant_oracle as po
+from paper_2602_22592_amd import binding as pq
+from paper_2602_22592_amd import workloads as wl
+from paper_2602_22592_amd.stack import Stack
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda().to(torch.bfloat16)
+
+
+def relerr(a, b):
+    a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
+    return float(np.abs(a - b).max() / max(np.abs(b).max(), 1e-30))
+
+
+@pytest.mark.parametrize("L,T,D,F,E,r", [(2, 256, 128, 352, 8, 32), (3, 100, 64, 96, 4, 8)])
+def test_stack_two_layers(L, T, D, F, E, r):
+    print(f"stack L={L} T={T} d={D} F={F} E={E} r={r}", flush=True)
+    c = wl.stack_case(7, L, T, D, F, E, r, vocab=1000)
+    names = ("Wq", "Wk", "Wv", "Wo", "W_up", "W_gate", "W_down", "Up", "Gate", "Down", "Wr")
+    weights = [{n: dev(w[n]) for n in names} for w in c["layers"]]
+    grads = [dict({n: torch.empty(w[n].shape, dtype=torch.float32, device="cuda") for n in names},
+                  dab=torch.empty(2, dtype=torch.float32, device="cuda")) for w in c["layers"]]
+    st = Stack(L, T, D, F, E, r, 1, [w["alpha"] for w in c["layers"]], [w["beta"] for w in c["layers"]])
+    h0 = torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
+    pq.glue_gather_rows(dev(c["table"]), torch.from_numpy(c["ids"]).cuda(), h0)
+    out = st.forward(h0, weights)
+    d0 = st.backward(dev(c["dY"]), weights, grads)
+    torch.cuda.synchronize()
+
+    h0_ref = c["table"][c["ids"]]
+    assert np.array_equal(h0.float().cpu().numpy(), h0_ref)
+    y_ref, saved = po.stack_fwd(h0_ref, c["layers"], top_k=1)
+    d_ref, g_ref = po.stack_bwd(c["dY"], c["layers"], saved)
+    errs = {"out": relerr(out.float().cpu().numpy(), y_ref), "dh0": relerr(d0.float().cpu().numpy(), d_ref)}
+    for l in (0, L - 1):
+        for n in ("Wq", "Wo", "W_up", "W_down", "Up", "Down", "Wr"):
+            errs[f"{n}[{l}]"] = relerr(grads[l][n].cpu().numpy(), g_ref[l][n])
+    print("  errors: " + ", ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
+    # routing decisions of later layers may flip on near-ties once bf16-level differences have propagated;
+    # the bar below holds when they agree, which they do for these seeds
+    assert max(errs.values()) <= 2e-2, errs
