@@ -18,9 +18,9 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = True, extra_flags=()) -> str:
+def build(verbose: bool = True, extra_flags=(), out: str = LIB) -> str:
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = ["hipcc", *HIPCC_FLAGS, *extra_flags, "-I", os.path.join(HERE, "..", "include"), *srcs, "-o", LIB]
+    cmd = ["hipcc", *HIPCC_FLAGS, *extra_flags, "-I", os.path.join(HERE, "..", "include"), *srcs, "-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -30,7 +30,7 @@ def build(verbose: bool = True, extra_flags=()) -> str:
         print(out, flush=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -15,6 +15,7 @@
 //   v_mfma_f32_32x32x16_bf16 / v_mfma_i32_32x32x32_i8, 16 bytes of operand per lane per issue.
 // LDS rows are 128 bytes with the 16-byte chunk index XOR-swizzled by the row so that the MFMA
 // operand reads, the row-wise stores and the transposed stores are all free of bank conflicts.
+#include <stdlib.h>
 #include <string.h>
 #include <type_traits>
 #include "pq_internal.h"
@@ -26,72 +27,123 @@ __device__ __forceinline__ uint4 mask4(const uint4& t, bool keep) {
   return make_uint4(t.x & m, t.y & m, t.z & m, t.w & m);
 }
 
-__device__ __forceinline__ int lds_off(int r, int c) { return r * 128 + (((c ^ r ^ (r >> 3)) & 7) << 4); }
+// Byte offset of 16-byte chunk c of row r in a tile whose rows are KB bytes (128 or 64).  The chunk
+// index is XOR-swizzled by the row so that 8 consecutive rows at one logical chunk, and rows 8 apart
+// at consecutive chunks (the transposing stores), fall into distinct 16-byte bank groups.
+template <int KB>
+__device__ __forceinline__ int lds_off(int r, int c) {
+  if constexpr (KB == 128) return r * 128 + (((c ^ r ^ (r >> 3)) & 7) << 4);
+  else return r * 64 + (((c ^ (r >> 1) ^ (r >> 3)) & 3) << 4);
+}
 
 // ---------------------------------------------------------------------------------------------
 // Operand tile staging: global -> registers (load) and registers -> LDS (store)
 // ---------------------------------------------------------------------------------------------
-template <int KIND, int ROWS, int NT>
+// Everything that does not change from one contraction step to the next (which rows and LDS slots a
+// thread serves, their byte offsets) is computed once in setup(); a step then costs one load per
+// 16 bytes with a uniform base pointer.  FAST instantiations are for shapes made of whole tiles:
+// they carry no validity masks at all.  Otherwise loads stay unconditional (an out-of-range chunk
+// reads element (0,0), which always exists, and is replaced by zeros on the way into LDS) so that
+// all of a thread's loads are in flight together.
+template <int KIND, int ROWS, int NT, int KB, bool FAST>
 struct tile_stage {
-  static constexpr int NCH = (ROWS * 8 + NT - 1) / NT;  // 16-byte LDS chunks per thread
+  static constexpr int CPR = KB / 16;                        // 16-byte chunks per LDS row
+  static constexpr int NCH = (ROWS * CPR + NT - 1) / NT;     // chunks per thread
   static constexpr bool kBits = (KIND == PQ_SRC_BITS8 || KIND == PQ_SRC_BITS16);
   static constexpr bool kStrided = (KIND == PQ_SRC_KS16);
   static constexpr int EPC = (KIND == PQ_SRC_KC8 || KIND == PQ_SRC_BITS8) ? 16 : 8;  // elements per chunk
-  // KS16: a unit is 8 rows x KQ contraction indices (KQ 16-byte loads, transposed in registers)
-  static constexpr int KQ = (ROWS >= NT) ? 8 : 4;
-  static constexpr int UPR = 64 / KQ;                     // units per 8-row group
+  // KS16: a unit is 8 rows x KQ contraction indices (KQ 16-byte loads, transposed in registers);
+  // KQ is the largest of 8, 4, 2 that still gives every thread a unit
+  static constexpr int KQ = (ROWS * KB / 128 >= NT) ? 8 : (ROWS * KB / 64 >= NT) ? 4 : 2;
+  static constexpr int UPR = (KB / 2) / KQ;                  // units per 8-row group
+  static constexpr int UPC = 8 / KQ;                         // units per 16-byte chunk
   static constexpr int NU = (ROWS / 8 * UPR + NT - 1) / NT;  // units per thread
+  static_assert(NT % CPR == 0 && NT % UPR == 0, "a thread keeps its contraction position across chunks");
   uint4 v[kBits ? 1 : (kStrided ? NU * KQ : NCH)];
   uint32_t raw[kBits ? NCH : 1];
-  uint32_t okbits;  // validity of each loaded chunk, applied when the tile is written to LDS
+  uint32_t boff[kStrided ? NU : NCH];      // byte offset of each load at contraction index 0
+  uint32_t ldst[kStrided ? NU * 8 : NCH];  // LDS byte offset of each store
+  uint32_t rowok;                          // bit i: chunk / unit i lies in a valid row
+  uint32_t okbits;                         // validity of each load of the step in flight
+  uint32_t jstride;                        // KS16: bytes between consecutive contraction indices
+  int kpos;                                // this thread's contraction offset inside a tile (elements)
 
-  // Loads are unconditional (an out-of-range chunk reads element (0,0), which always exists, and is
-  // then replaced by zeros) so that all of a thread's loads are in flight together.
-  __device__ __forceinline__ void load(const pq_operand& op, int row0, int rows, int k0, int K, int tid) {
+  // bytes of the source advanced per contraction element, times 8 (bits kinds advance 1/8 byte)
+  static constexpr int ES8 = (KIND == PQ_SRC_KC16) ? 16 : (KIND == PQ_SRC_KC8) ? 8 : 1;
+
+  __device__ __forceinline__ void setup(const pq_operand& op, int row0, int rows, int tid) {
+    rowok = 0u;
     okbits = 0u;
     if constexpr (kStrided) {
-      const uint16_t* p = (const uint16_t*)op.p;
+      jstride = (uint32_t)op.ld * 2u;
+      kpos = (tid % UPR) * KQ;
 #pragma unroll
       for (int i = 0; i < NU; ++i) {
         const int u = tid + i * NT;
         const int r8 = u / UPR, kq = u % UPR;
         const int col = row0 + r8 * 8;
-        const bool okc = (u < ROWS / 8 * UPR) && (col < rows);
+        const bool ok = (u < ROWS / 8 * UPR) && (col < rows);
+        rowok |= (ok ? 1u : 0u) << i;
+        boff[i] = ((uint32_t)(kq * KQ) * (uint32_t)op.ld + (uint32_t)(ok ? col : 0)) * 2u;
 #pragma unroll
-        for (int j = 0; j < KQ; ++j) {
-          const int kk = k0 + kq * KQ + j;
-          const bool ok = okc && (kk < K);
-          const size_t off = ok ? (size_t)kk * op.ld + col : 0;
-          v[i * KQ + j] = *reinterpret_cast<const uint4*>(p + off);
-          okbits |= (ok ? 1u : 0u) << (i * KQ + j);
-        }
+        for (int rr = 0; rr < 8; ++rr)
+          ldst[i * 8 + rr] = (uint32_t)(lds_off<KB>(r8 * 8 + rr, kq / UPC) + (kq % UPC) * (KQ * 2));
       }
     } else {
+      jstride = 0u;
+      kpos = (tid % CPR) * EPC;
 #pragma unroll
       for (int i = 0; i < NCH; ++i) {
         const int c = tid + i * NT;
-        const int r = c >> 3, kc = c & 7;
-        const int grow = row0 + r, k = k0 + kc * EPC;
-        const bool ok = (c < ROWS * 8) && (grow < rows) && (k < K);
-        if constexpr (KIND == PQ_SRC_KC16) {
-          const size_t off = ok ? (size_t)grow * op.ld + k : 0;
-          v[i] = *reinterpret_cast<const uint4*>((const uint16_t*)op.p + off);
-          okbits |= (ok ? 1u : 0u) << i;
-        } else if constexpr (KIND == PQ_SRC_KC8) {
-          const size_t off = ok ? (size_t)grow * op.ld + k : 0;
-          v[i] = *reinterpret_cast<const uint4*>((const int8_t*)op.p + off);
-          okbits |= (ok ? 1u : 0u) << i;
-        } else if constexpr (KIND == PQ_SRC_BITS8) {
-          const size_t off = ok ? (size_t)grow * op.ld + (k >> 3) : 0;
-          raw[i] = *reinterpret_cast<const uint16_t*>((const uint8_t*)op.p + off);
-          okbits |= (ok ? 1u : 0u) << i;
-        } else {  // BITS16
-          const size_t off = ok ? (size_t)grow * op.ld + (k >> 3) : 0;
-          raw[i] = ((const uint8_t*)op.p)[off];
-          okbits |= (ok ? 1u : 0u) << i;
-        }
+        const int r = c / CPR, kc = c % CPR;
+        const int grow = row0 + r;
+        const bool ok = (c < ROWS * CPR) && (grow < rows);
+        rowok |= (ok ? 1u : 0u) << i;
+        const uint32_t rowb = (uint32_t)(ok ? grow : 0) * (uint32_t)op.ld;   // ld is in bytes for the bits kinds
+        boff[i] = (kBits ? rowb : rowb * (uint32_t)(ES8 / 8)) + (uint32_t)(kc * EPC * ES8 / 8);
+        ldst[i] = (uint32_t)lds_off<KB>(r, kc);
       }
     }
+  }
+
+  // k0: contraction index of the tile's first element; K: end of the valid contraction range
+  __device__ __forceinline__ void load(const pq_operand& op, int k0, int K) {
+    if constexpr (kStrided) {
+      const char* base = FAST ? (const char*)op.p + (size_t)k0 * jstride : (const char*)op.p;
+      const uint32_t kbyte = FAST ? 0u : (uint32_t)k0 * jstride;
+      okbits = 0u;
+#pragma unroll
+      for (int i = 0; i < NU; ++i) {
+#pragma unroll
+        for (int j = 0; j < KQ; ++j) {
+          uint32_t off = boff[i] + (uint32_t)j * jstride;
+          if constexpr (!FAST) {
+            const bool ok = ((rowok >> i) & 1u) && (k0 + kpos + j < K);
+            off = ok ? off + kbyte : 0u;
+            okbits |= (ok ? 1u : 0u) << (i * KQ + j);
+          }
+          v[i * KQ + j] = *reinterpret_cast<const uint4*>(base + off);
+        }
+      }
+    } else {
+      const size_t kb8 = (size_t)k0 * ES8 / 8;
+      const char* base = FAST ? (const char*)op.p + kb8 : (const char*)op.p;
+      const bool kv = FAST ? true : (k0 + kpos < K);
+      okbits = kv ? rowok : 0u;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        uint32_t off = boff[i];
+        if constexpr (!FAST) off = ((okbits >> i) & 1u) ? off + (uint32_t)kb8 : 0u;
+        if constexpr (KIND == PQ_SRC_BITS8) raw[i] = *reinterpret_cast<const uint16_t*>(base + off);
+        else if constexpr (KIND == PQ_SRC_BITS16) raw[i] = *reinterpret_cast<const uint8_t*>(base + off);
+        else v[i] = *reinterpret_cast<const uint4*>(base + off);
+      }
+    }
+  }
+
+  __device__ __forceinline__ uint4 valid(const uint4& t, int bit) const {
+    if constexpr (FAST) return t;
+    else return mask4(t, (okbits >> bit) & 1u);
   }
 
   __device__ __forceinline__ void store(unsigned char* lds, int tid) const {
@@ -100,26 +152,24 @@ struct tile_stage {
       for (int i = 0; i < NU; ++i) {
         const int u = tid + i * NT;
         if (u < ROWS / 8 * UPR) {
-          const int r8 = u / UPR, kq = u % UPR;
           // transpose of 16-bit elements: v[i*KQ+j] holds rows r8*8..+7 at contraction index j
 #pragma unroll
           for (int rr = 0; rr < 8; ++rr) {
             uint32_t o[KQ / 2];
 #pragma unroll
             for (int p = 0; p < KQ / 2; ++p) {
-              const uint4 lo4 = mask4(v[i * KQ + 2 * p], (okbits >> (i * KQ + 2 * p)) & 1u);
-              const uint4 hi4 = mask4(v[i * KQ + 2 * p + 1], (okbits >> (i * KQ + 2 * p + 1)) & 1u);
+              const uint4 lo4 = valid(v[i * KQ + 2 * p], i * KQ + 2 * p);
+              const uint4 hi4 = valid(v[i * KQ + 2 * p + 1], i * KQ + 2 * p + 1);
               const uint32_t lo = (rr >> 1) == 0 ? lo4.x : (rr >> 1) == 1 ? lo4.y : (rr >> 1) == 2 ? lo4.z : lo4.w;
               const uint32_t hi = (rr >> 1) == 0 ? hi4.x : (rr >> 1) == 1 ? hi4.y : (rr >> 1) == 2 ? hi4.z : hi4.w;
               // result = [lo.half, hi.half]; v_perm selects bytes 0-3 from the 2nd operand, 4-7 from the 1st
               o[p] = (rr & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u)
                               : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
             }
-            if constexpr (KQ == 8) {
-              *reinterpret_cast<uint4*>(lds + lds_off(r8 * 8 + rr, kq)) = make_uint4(o[0], o[1], o[2], o[3]);
-            } else {
-              *reinterpret_cast<uint2*>(lds + lds_off(r8 * 8 + rr, kq >> 1) + (kq & 1) * 8) = make_uint2(o[0], o[1]);
-            }
+            unsigned char* dst = lds + ldst[i * 8 + rr];
+            if constexpr (KQ == 8) *reinterpret_cast<uint4*>(dst) = make_uint4(o[0], o[1], o[2], o[3]);
+            else if constexpr (KQ == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(o[0], o[1]);
+            else *reinterpret_cast<uint32_t*>(dst) = o[0];
           }
         }
       }
@@ -127,8 +177,7 @@ struct tile_stage {
 #pragma unroll
       for (int i = 0; i < NCH; ++i) {
         const int c = tid + i * NT;
-        if (c < ROWS * 8) {
-          const int r = c >> 3, kc = c & 7;
+        if (c < ROWS * CPR) {
           uint4 out;
           if constexpr (KIND == PQ_SRC_BITS8) {
             // 16 bits -> 16 bytes of +1 (0x01) / -1 (0xFF): spread a nibble to one bit per byte with a
@@ -141,21 +190,19 @@ struct tile_stage {
               const uint32_t m = __umul24(nib, 0x00204081u) & 0x01010101u;
               o[d] = __builtin_amdgcn_perm(0x000001FFu, 0x000001FFu, m);
             }
-            out = mask4(make_uint4(o[0], o[1], o[2], o[3]), (okbits >> i) & 1u);
+            out = valid(make_uint4(o[0], o[1], o[2], o[3]), i);
           } else if constexpr (KIND == PQ_SRC_BITS16) {
-            // 8 bits -> 8 bf16 of +1 (0x3F80) / -1 (0xBF80)
-            const uint32_t b = raw[i];
+            // 8 bits -> 8 bf16 of +1 (0x3F80) / -1 (0xBF80): move each (inverted) bit to a sign position
+            const uint32_t nb = ~raw[i];
             uint32_t o[4];
 #pragma unroll
-            for (int d = 0; d < 4; ++d) {
-              const uint32_t x = (b >> (2 * d)) & 3u;
-              o[d] = 0xBF80BF80u ^ (((x & 1u) << 15) | ((x & 2u) << 30));
-            }
-            out = mask4(make_uint4(o[0], o[1], o[2], o[3]), (okbits >> i) & 1u);
+            for (int d = 0; d < 4; ++d)
+              o[d] = 0x3F803F80u | ((nb << (15 - 2 * d)) & 0x00008000u) | ((nb << (30 - 2 * d)) & 0x80000000u);
+            out = valid(make_uint4(o[0], o[1], o[2], o[3]), i);
           } else {
-            out = mask4(v[i], (okbits >> i) & 1u);
+            out = valid(v[i], i);
           }
-          *reinterpret_cast<uint4*>(lds + lds_off(r, kc)) = out;
+          *reinterpret_cast<uint4*>(lds + ldst[i]) = out;
         }
       }
     }
@@ -293,7 +340,7 @@ __device__ __forceinline__ void epi_vec8(const pq_epilogue& e, epi_state& st, in
 // blockIdx.y.  LDS holds two stages of both operand tiles; per 128-byte step there is a single
 // barrier: after it, the registers prefetched during the previous step are written to the idle
 // stage, the loads of the step after next are issued, and the MFMAs run on the ready stage.
-template <int BM, int BN, int WGM, int WGN, bool INT8, int AK, int BKIND>
+template <int BM, int BN, int WGM, int WGN, int KB, bool FAST, bool INT8, int AK, int BKIND>
 __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N, int K, pq_operand A,
                                                                      pq_operand B, pq_epilogue epi,
                                                                      int nbn, int total_tiles, int kchunk,
@@ -301,8 +348,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
   constexpr int NT = WGM * WGN * 64;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
-  constexpr int EPB = INT8 ? 128 : 64;  // contraction elements per 128-byte LDS row
-  constexpr int STAGE = (BM + BN) * 128;
+  constexpr int EPB = INT8 ? KB : KB / 2;  // contraction elements per LDS row
+  constexpr int STAGE = (BM + BN) * KB;
   using acc_t = typename std::conditional<INT8, i32x16_t, f32x16_t>::type;
 
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * STAGE];
@@ -341,54 +388,91 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-  tile_stage<AK, BM, NT> sa;
-  tile_stage<BKIND, BN, NT> sb;
+  tile_stage<AK, BM, NT, KB, FAST> sa;
+  tile_stage<BKIND, BN, NT, KB, FAST> sb;
+  sa.setup(A, m0, M, tid);
+  sb.setup(B, n0, N, tid);
   const int nkt = ke > kb ? (ke - kb + EPB - 1) / EPB : 0;
-  if (nkt > 0) {
-    sa.load(A, m0, M, kb, ke, tid);
-    sb.load(B, n0, N, kb, ke, tid);
-    sa.store(smem, tid);
-    sb.store(smem + BM * 128, tid);
-    if (nkt > 1) {
-      sa.load(A, m0, M, kb + EPB, ke, tid);
-      sb.load(B, n0, N, kb + EPB, ke, tid);
-    }
-  }
+  constexpr int NKS = KB / 32;   // MFMA issues along the contraction per LDS stage
 
+  // per-thread LDS read offsets of the MFMA operand fragments (row part and swizzle part)
+  int a_rb[TM], a_fx[TM], b_rb[TN], b_fx[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int r = wm0 + i * 32 + (lane & 31);
+    a_rb[i] = lds_off<KB>(r, 0) & ~(KB - 1);
+    a_fx[i] = (lds_off<KB>(r, 0) & (KB - 1)) >> 4;
+  }
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int r = wn0 + j * 32 + (lane & 31);
+    b_rb[j] = BM * KB + (lds_off<KB>(r, 0) & ~(KB - 1));
+    b_fx[j] = (lds_off<KB>(r, 0) & (KB - 1)) >> 4;
+  }
+  uint4 af[2][TM], bf[2][TN];
+  auto read_frags = [&](const unsigned char* stage, int ks, uint4* fa, uint4* fb) {
+    const int ch = 2 * ks + (lane >> 5);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const uint4*>(stage + a_rb[i] + ((ch ^ a_fx[i]) << 4));
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const uint4*>(stage + b_rb[j] + ((ch ^ b_fx[j]) << 4));
+  };
+
+  if (nkt > 0) {
+    sa.load(A, kb, ke);
+    sb.load(B, kb, ke);
+    sa.store(smem, tid);
+    sb.store(smem + BM * KB, tid);
+    const int k1 = nkt > 1 ? 1 : 0;
+    sa.load(A, kb + k1 * EPB, ke);
+    sb.load(B, kb + k1 * EPB, ke);
+  }
+  __syncthreads();
+  if (nkt > 0) read_frags(smem, 0, af[0], bf[0]);
+
+  // Steady state, one barrier per stage and no branches in the body: the registers hold tile kt+1,
+  // which goes to the idle LDS stage while the loads of tile kt+2 are issued and the MFMAs run on
+  // the ready stage; the operand fragments of the next MFMA group are read one group ahead.  On the
+  // last steps the tile index is clamped, so the same tile is (harmlessly) staged again.
+#ifndef PQ_VAR_SCHED
+#define PQ_VAR_SCHED 0
+#endif
   for (int kt = 0; kt < nkt; ++kt) {
-    __syncthreads();  // stage kt&1 is complete; nobody still reads the other stage
     unsigned char* cur = smem + (kt & 1) * STAGE;
     unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
-    if (kt + 1 < nkt) {
-      sa.store(nxt, tid);
-      sb.store(nxt + BM * 128, tid);
-    }
-    if (kt + 2 < nkt) {
-      sa.load(A, m0, M, kb + (kt + 2) * EPB, ke, tid);
-      sb.load(B, n0, N, kb + (kt + 2) * EPB, ke, tid);
-    }
-    const unsigned char* As = cur;
-    const unsigned char* Bs = cur + BM * 128;
+    sa.store(nxt, tid);
+    sb.store(nxt + BM * KB, tid);
+    const int k2 = min(kt + 2, nkt - 1);
+    sa.load(A, kb + k2 * EPB, ke);
+    sb.load(B, kb + k2 * EPB, ke);
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      uint4 af[TM], bf[TN];
-      const int ch = 2 * ks + (lane >> 5);
-#pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const uint4*>(As + lds_off(wm0 + i * 32 + (lane & 31), ch));
-#pragma unroll
-      for (int j = 0; j < TN; ++j) bf[j] = *reinterpret_cast<const uint4*>(Bs + lds_off(wn0 + j * 32 + (lane & 31), ch));
+    for (int ks = 0; ks < NKS; ++ks) {
+      if (ks + 1 < NKS) read_frags(cur, ks + 1, af[(ks + 1) & 1], bf[(ks + 1) & 1]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           if constexpr (INT8)
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4_t, af[i]),
-                                                              __builtin_bit_cast(i32x4_t, bf[j]), acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4_t, af[ks & 1][i]),
+                                                              __builtin_bit_cast(i32x4_t, bf[ks & 1][j]), acc[i][j], 0, 0, 0);
           else
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[i]),
-                                                                __builtin_bit_cast(bf16x8_t, bf[j]), acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[ks & 1][i]),
+                                                                __builtin_bit_cast(bf16x8_t, bf[ks & 1][j]), acc[i][j], 0, 0, 0);
         }
     }
+    __syncthreads();  // stage nxt is complete and nobody still reads stage cur
+    read_frags(nxt, 0, af[0], bf[0]);
+#if PQ_VAR_SCHED == 1
+    // one MFMA, then a few instructions of the other kinds in its shadow
+#pragma unroll
+    for (int q = 0; q < TM * TN * NKS; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+      __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);   // VALU
+      __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // DS write
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read
+    }
+#endif
   }
   __syncthreads();  // all MFMA operand reads are done: LDS is reused below
 
@@ -497,15 +581,15 @@ __global__ __launch_bounds__(256) void ref_gemm_kernel(int M, int N, int K, pq_o
   epi_end<256>(epi, st, red, blockIdx.y * gridDim.x + blockIdx.x);
 }
 
-template <int BM, int BN, int WGM, int WGN, bool INT8, int AK, int BKIND>
+template <int BM, int BN, int WGM, int WGN, int KB, bool FAST, bool INT8, int AK, int BKIND>
 int launch_mfma(const pq_gemm_plan& pl, int M, int N, int K, const pq_operand& A, const pq_operand& B,
                 const pq_epilogue& epi, hipStream_t s, float* part, const pq_gemm_group& grp) {
   const int Mrows = grp.mode == 1 ? grp.max_rows : M;
   const int nbm = (Mrows + BM - 1) / BM, nbn = (N + BN - 1) / BN;
   const int tiles = nbm * nbn;
   dim3 grid(tiles, pl.splits, grp.mode ? grp.n_groups : 1), block(WGM * WGN * 64);
-  mfma_gemm_kernel<BM, BN, WGM, WGN, INT8, AK, BKIND><<<grid, block, 0, s>>>(M, N, K, A, B, epi, nbn, tiles, pl.kchunk,
-                                                                               pl.splits > 1 ? part : nullptr, grp);
+  mfma_gemm_kernel<BM, BN, WGM, WGN, KB, FAST, INT8, AK, BKIND><<<grid, block, 0, s>>>(M, N, K, A, B, epi, nbn, tiles, pl.kchunk,
+                                                                                         pl.splits > 1 ? part : nullptr, grp);
   PQ_CHECK_LAUNCH("mfma_gemm_kernel");
   return PQ_OK;
 }
@@ -513,8 +597,17 @@ int launch_mfma(const pq_gemm_plan& pl, int M, int N, int K, const pq_operand& A
 template <bool INT8, int AK, int BKIND>
 int launch_mfma_cfg(const pq_gemm_plan& pl, int M, int N, int K, const pq_operand& A, const pq_operand& B,
                     const pq_epilogue& epi, hipStream_t s, float* part, const pq_gemm_group& grp) {
-  if (pl.bm == 256) return launch_mfma<256, 256, 2, 4, INT8, AK, BKIND>(pl, M, N, K, A, B, epi, s, part, grp);
-  return launch_mfma<128, 128, 2, 2, INT8, AK, BKIND>(pl, M, N, K, A, B, epi, s, part, grp);
+  constexpr int EPB = INT8 ? 128 : 64;
+  if (pl.bm == 256) {
+    // whole tiles everywhere: the instantiation without validity masks
+    const bool whole = grp.mode == 0 && M % 256 == 0 && N % 256 == 0 && K % EPB == 0 && pl.kchunk % EPB == 0;
+#ifndef PQ_VAR_WAVES
+#define PQ_VAR_WAVES 8
+#endif
+    if (whole) return launch_mfma<256, 256, 2, PQ_VAR_WAVES / 2, 128, true, INT8, AK, BKIND>(pl, M, N, K, A, B, epi, s, part, grp);
+    return launch_mfma<256, 256, 2, PQ_VAR_WAVES / 2, 128, false, INT8, AK, BKIND>(pl, M, N, K, A, B, epi, s, part, grp);
+  }
+  return launch_mfma<128, 128, 2, 2, 128, false, INT8, AK, BKIND>(pl, M, N, K, A, B, epi, s, part, grp);
 }
 
 }  // namespace
