@@ -296,30 +296,39 @@ extern "C" int pq_linear_fwd(const pq_linear_desc* d, const void* X, const void*
   uint16_t* Xt = (ctx && bf16) ? (uint16_t*)(cx + L.Xt) : nullptr;
   if (int e = pq_launch_quant_act(X, d->io_dtype, T, K, Xq, gamma, Xt, s)) return e;
 
-  {  // 1-bit branch: Y = fl32(fl32(beta*lambda)/gamma_t) * acc
+  // bf16 I/O with a live hp branch: the rank-r product H B^T is accumulated into the 1-bit GEMM's tile
+  const bool fuse_hp = bf16 && r > 0 && d->alpha != 0.0f && pq_plan_gemm(0, T, N, K, true).splits == 1;
+  void* H = r > 0 ? (ctx ? (void*)(cx + L.H) : (void*)(ws + L.w_H)) : nullptr;
+  if (r > 0) {  // H = X A^T
+    pq_operand A{X, K, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
+    pq_operand B{hpA, K, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
+    pq_epilogue e = epi_zero();
+    e.C = H; e.ldc = r; e.out_kind = ok;
+    if (int err = pq_launch_gemm(engine, T, r, K, A, B, e, s, PQP_GEMM_HP_H, sk_ws)) return err;
+  }
+  {  // 1-bit branch: Y = fl32(fl32(beta*lambda)/gamma_t) * acc   [+ alpha * H B^T when fused]
     pq_operand A{Xq, K, PQ_SRC_KC8, nullptr};
     pq_operand B{P, K / 8, PQ_SRC_BITS8, nullptr};
     pq_epilogue e = epi_zero();
     e.C = Y; e.ldc = N; e.out_kind = ok;
-    e.scale = d->beta; e.dev_scale = mulam + 1; e.row_div = gamma;
-    if (int err = pq_launch_gemm(0, T, N, K, A, B, e, s, PQP_GEMM_ONEBIT, sk_ws)) return err;
+    if (fuse_hp) {   // Y = alpha * ( (beta*lambda/alpha/gamma_t) * acc + H B^T )
+      pq_phase2 p2;
+      p2.A2 = pq_operand{H, r, PQ_SRC_KC16, nullptr};
+      p2.B2 = pq_operand{hpB, r, PQ_SRC_KC16, nullptr};
+      p2.K2 = r; p2.scale1 = d->beta / d->alpha; p2.dev_scale1 = mulam + 1; p2.row_div1 = gamma;
+      e.scale = d->alpha;
+      if (int err = pq_launch_gemm(0, T, N, K, A, B, e, s, PQP_GEMM_ONEBIT, sk_ws, nullptr, &p2)) return err;
+    } else {
+      e.scale = d->beta; e.dev_scale = mulam + 1; e.row_div = gamma;
+      if (int err = pq_launch_gemm(0, T, N, K, A, B, e, s, PQP_GEMM_ONEBIT, sk_ws)) return err;
+    }
   }
-  if (r > 0) {
-    void* H = ctx ? (void*)(cx + L.H) : (void*)(ws + L.w_H);
-    {  // H = X A^T
-      pq_operand A{X, K, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
-      pq_operand B{hpA, K, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
-      pq_epilogue e = epi_zero();
-      e.C = H; e.ldc = r; e.out_kind = ok;
-      if (int err = pq_launch_gemm(engine, T, r, K, A, B, e, s, PQP_GEMM_HP_H, sk_ws)) return err;
-    }
-    {  // Y += alpha * H B^T
-      pq_operand A{H, r, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
-      pq_operand B{hpB, r, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
-      pq_epilogue e = epi_zero();
-      e.C = Y; e.ldc = N; e.out_kind = ok; e.accumulate = 1; e.scale = d->alpha;
-      if (int err = pq_launch_gemm(engine, T, N, r, A, B, e, s, PQP_GEMM_HP_Y, sk_ws)) return err;
-    }
+  if (r > 0 && !fuse_hp && d->alpha != 0.0f) {  // Y += alpha * H B^T
+    pq_operand A{H, r, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
+    pq_operand B{hpB, r, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
+    pq_epilogue e = epi_zero();
+    e.C = Y; e.ldc = N; e.out_kind = ok; e.accumulate = 1; e.scale = d->alpha;
+    if (int err = pq_launch_gemm(engine, T, N, r, A, B, e, s, PQP_GEMM_HP_Y, sk_ws)) return err;
   }
   return PQ_OK;
 }
@@ -367,18 +376,28 @@ extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void
   }
   if (int err = pq_launch_reduce_partials(red_a, (T > 0 && r > 0) ? L.n_red_a : 0, 1.0f, nullptr, dalpha_dbeta, s)) return err;
 
-  if (T > 0) {  // dX = beta*lambda * dY S  (+ dH A)
+  if (T > 0) {  // dX = beta*lambda * dY S  (+ dH A, fused into the same tile for bf16 I/O)
     pq_operand A{dY, N, KC, nullptr};
     pq_operand B{cx + L.Pt, N / 8, bf16 ? PQ_SRC_BITS16 : PQ_SRC_BITSF, nullptr};
     pq_epilogue e = epi_zero();
-    e.C = dX; e.ldc = K; e.out_kind = ok; e.scale = d->beta; e.dev_scale = mulam + 1;
-    if (int err = pq_launch_gemm(engine, T, K, N, A, B, e, s, PQP_GEMM_DX, sk_ws)) return err;
-    if (r > 0) {
-      pq_operand A2{dH, r, KC, nullptr};
-      pq_operand B2{hpA, K, KS, nullptr};
-      pq_epilogue e2 = epi_zero();
-      e2.C = dX; e2.ldc = K; e2.out_kind = ok; e2.accumulate = 1;
-      if (int err = pq_launch_gemm(engine, T, K, r, A2, B2, e2, s, PQP_GEMM_DX_HP, sk_ws)) return err;
+    e.C = dX; e.ldc = K; e.out_kind = ok;
+    const bool fuse = bf16 && r > 0 && pq_plan_gemm(0, T, K, N).splits == 1;
+    if (fuse) {
+      pq_phase2 p2;
+      p2.A2 = pq_operand{dH, r, PQ_SRC_KC16, nullptr};
+      p2.B2 = pq_operand{hpA, K, PQ_SRC_KS16, nullptr};
+      p2.K2 = r; p2.scale1 = d->beta; p2.dev_scale1 = mulam + 1; p2.row_div1 = nullptr;
+      if (int err = pq_launch_gemm(0, T, K, N, A, B, e, s, PQP_GEMM_DX, sk_ws, nullptr, &p2)) return err;
+    } else {
+      e.scale = d->beta; e.dev_scale = mulam + 1;
+      if (int err = pq_launch_gemm(engine, T, K, N, A, B, e, s, PQP_GEMM_DX, sk_ws)) return err;
+      if (r > 0) {
+        pq_operand A2{dH, r, KC, nullptr};
+        pq_operand B2{hpA, K, KS, nullptr};
+        pq_epilogue e2 = epi_zero();
+        e2.C = dX; e2.ldc = K; e2.out_kind = ok; e2.accumulate = 1;
+        if (int err = pq_launch_gemm(engine, T, K, r, A2, B2, e2, s, PQP_GEMM_DX_HP, sk_ws)) return err;
+      }
     }
   }
   {  // dW = beta * (dY/gamma)^T q  [masked];  d beta = lambda * sum S .* (dY/gamma)^T q

@@ -340,11 +340,12 @@ __device__ __forceinline__ void epi_vec8(const pq_epilogue& e, epi_state& st, in
 // blockIdx.y.  LDS holds two stages of both operand tiles; per 128-byte step there is a single
 // barrier: after it, the registers prefetched during the previous step are written to the idle
 // stage, the loads of the step after next are issued, and the MFMAs run on the ready stage.
-template <int BM, int BN, int WGM, int WGN, int KB, bool FAST, bool INT8, int AK, int BKIND>
+template <int BM, int BN, int WGM, int WGN, int KB, bool FAST, bool INT8, int AK, int BKIND, int AK2 = -1, int BK2 = -1>
 __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N, int K, pq_operand A,
                                                                      pq_operand B, pq_epilogue epi,
                                                                      int nbn, int total_tiles, int kchunk,
-                                                                     float* splitk_part, pq_gemm_group grp) {
+                                                                     float* splitk_part, pq_gemm_group grp,
+                                                                     pq_phase2 ph2) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -476,6 +477,50 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
   }
   __syncthreads();  // all MFMA operand reads are done: LDS is reused below
 
+  // Optional second contraction (rank-r branch): rescale the first accumulator, then run a short
+  // un-pipelined bf16 loop over K2 into the same tile.
+  constexpr bool PH2 = (AK2 >= 0);
+  constexpr bool ACC_INT = INT8 && !PH2;
+  f32x16_t accf[PH2 ? TM : 1][PH2 ? TN : 1];
+  if constexpr (PH2) {
+    const float sc1 = ph2.dev_scale1 ? __fmul_rn(ph2.scale1, *ph2.dev_scale1) : ph2.scale1;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = m0 + wm0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        float sr = sc1;
+        if (ph2.row_div1) sr = sc1 / ph2.row_div1[m < M ? m : M - 1];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const auto e1 = acc[i][j][v];
+          accf[i][j][v] = (float)e1 * sr;
+        }
+      }
+    tile_stage<AK2, BM, NT, KB, FAST> sa2;
+    tile_stage<BK2, BN, NT, KB, FAST> sb2;
+    sa2.setup(ph2.A2, m0, M, tid);
+    sb2.setup(ph2.B2, n0, N, tid);
+    for (int k2 = 0; k2 < ph2.K2; k2 += KB / 2) {
+      sa2.load(ph2.A2, k2, ph2.K2);
+      sb2.load(ph2.B2, k2, ph2.K2);
+      sa2.store(smem, tid);
+      sb2.store(smem + BM * KB, tid);
+      __syncthreads();
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        read_frags(smem, ks, af[0], bf[0]);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            accf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[0][i]),
+                                                                 __builtin_bit_cast(bf16x8_t, bf[0][j]), accf[i][j], 0, 0, 0);
+      }
+      __syncthreads();
+    }
+  }
+
   // Epilogue: each wavefront passes its 32x32 accumulator blocks through a private LDS patch
   // (row stride 36 words: conflict-free both ways) so that a lane ends up with 8 consecutive
   // columns of one row and global loads/stores are 16 bytes wide.  With a split contraction the
@@ -491,8 +536,14 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int rr = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        const auto elem = acc[i][j][v];  // copy out first: a vector element is not a bit_cast-able lvalue
-        stg[rr * 36 + (lane & 31)] = __builtin_bit_cast(uint32_t, elem);
+        // copy the element out first: a vector element is not a bit_cast-able lvalue
+        if constexpr (PH2) {
+          const float elem = accf[i][j][v];
+          stg[rr * 36 + (lane & 31)] = __builtin_bit_cast(uint32_t, elem);
+        } else {
+          const auto elem = acc[i][j][v];
+          stg[rr * 36 + (lane & 31)] = __builtin_bit_cast(uint32_t, elem);
+        }
       }
       // wave-private patch: order this wave's LDS writes before its reads (other lanes' data)
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -508,7 +559,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
             *reinterpret_cast<uint4*>(slab + (size_t)m * N + n) = r0;
             *reinterpret_cast<uint4*>(slab + (size_t)m * N + n + 4) = r1;
           } else {
-            epi_vec8<INT8>(epi, st, m, n, r0, r1);
+            epi_vec8<ACC_INT>(epi, st, m, n, r0, r1);
           }
         }
       }
@@ -581,33 +632,31 @@ __global__ __launch_bounds__(256) void ref_gemm_kernel(int M, int N, int K, pq_o
   epi_end<256>(epi, st, red, blockIdx.y * gridDim.x + blockIdx.x);
 }
 
-template <int BM, int BN, int WGM, int WGN, int KB, bool FAST, bool INT8, int AK, int BKIND>
+template <int BM, int BN, int WGM, int WGN, int KB, bool FAST, bool INT8, int AK, int BKIND, int AK2 = -1, int BK2 = -1>
 int launch_mfma(const pq_gemm_plan& pl, int M, int N, int K, const pq_operand& A, const pq_operand& B,
-                const pq_epilogue& epi, hipStream_t s, float* part, const pq_gemm_group& grp) {
+                const pq_epilogue& epi, hipStream_t s, float* part, const pq_gemm_group& grp, const pq_phase2& ph2) {
   const int Mrows = grp.mode == 1 ? grp.max_rows : M;
   const int nbm = (Mrows + BM - 1) / BM, nbn = (N + BN - 1) / BN;
   const int tiles = nbm * nbn;
   dim3 grid(tiles, pl.splits, grp.mode ? grp.n_groups : 1), block(WGM * WGN * 64);
-  mfma_gemm_kernel<BM, BN, WGM, WGN, KB, FAST, INT8, AK, BKIND><<<grid, block, 0, s>>>(M, N, K, A, B, epi, nbn, tiles, pl.kchunk,
-                                                                                         pl.splits > 1 ? part : nullptr, grp);
+  mfma_gemm_kernel<BM, BN, WGM, WGN, KB, FAST, INT8, AK, BKIND, AK2, BK2><<<grid, block, 0, s>>>(
+      M, N, K, A, B, epi, nbn, tiles, pl.kchunk, pl.splits > 1 ? part : nullptr, grp, ph2);
   PQ_CHECK_LAUNCH("mfma_gemm_kernel");
   return PQ_OK;
 }
 
-template <bool INT8, int AK, int BKIND>
+template <bool INT8, int AK, int BKIND, int AK2 = -1, int BK2 = -1>
 int launch_mfma_cfg(const pq_gemm_plan& pl, int M, int N, int K, const pq_operand& A, const pq_operand& B,
-                    const pq_epilogue& epi, hipStream_t s, float* part, const pq_gemm_group& grp) {
+                    const pq_epilogue& epi, hipStream_t s, float* part, const pq_gemm_group& grp, const pq_phase2& ph2) {
   constexpr int EPB = INT8 ? 128 : 64;
   if (pl.bm == 256) {
     // whole tiles everywhere: the instantiation without validity masks
-    const bool whole = grp.mode == 0 && M % 256 == 0 && N % 256 == 0 && K % EPB == 0 && pl.kchunk % EPB == 0;
-#ifndef PQ_VAR_WAVES
-#define PQ_VAR_WAVES 8
-#endif
-    if (whole) return launch_mfma<256, 256, 2, PQ_VAR_WAVES / 2, 128, true, INT8, AK, BKIND>(pl, M, N, K, A, B, epi, s, part, grp);
-    return launch_mfma<256, 256, 2, PQ_VAR_WAVES / 2, 128, false, INT8, AK, BKIND>(pl, M, N, K, A, B, epi, s, part, grp);
+    const bool whole = grp.mode == 0 && M % 256 == 0 && N % 256 == 0 && K % EPB == 0 && pl.kchunk % EPB == 0 &&
+                       ph2.K2 % 64 == 0;
+    if (whole) return launch_mfma<256, 256, 2, 4, 128, true, INT8, AK, BKIND, AK2, BK2>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+    return launch_mfma<256, 256, 2, 4, 128, false, INT8, AK, BKIND, AK2, BK2>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
   }
-  return launch_mfma<128, 128, 2, 2, 128, false, INT8, AK, BKIND>(pl, M, N, K, A, B, epi, s, part, grp);
+  return launch_mfma<128, 128, 2, 2, 128, false, INT8, AK, BKIND, AK2, BK2>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
 }
 
 }  // namespace
@@ -644,11 +693,15 @@ pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8) {
 
 int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const pq_operand& B,
                    const pq_epilogue& epi, hipStream_t s, int prof_label, void* splitk_ws,
-                   const pq_gemm_group* group) {
+                   const pq_gemm_group* group, const pq_phase2* phase2) {
   if (M <= 0 || N <= 0) return PQ_OK;
   pq_gemm_group grp;
   memset(&grp, 0, sizeof(grp));
   if (group) grp = *group;
+  pq_phase2 ph2;
+  memset(&ph2, 0, sizeof(ph2));
+  if (phase2) ph2 = *phase2;
+  if (ph2.K2 > 0 && (engine == 1 || grp.mode)) return pq_set_error(PQ_ERR_BAD_ARG, "a fused second contraction needs the plain MFMA engine");
   if (grp.mode && engine == 1) return pq_set_error(PQ_ERR_DTYPE, "grouped GEMMs run on the MFMA engine only (bf16 I/O)");
   pq_prof_scope prof(prof_label, s);
   if (engine == 1) {
@@ -668,11 +721,19 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
   if (pl.splits > 1 && !splitk_ws) return pq_set_error(PQ_ERR_WORKSPACE, "split contraction needs scratch");
   float* part = (float*)splitk_ws;
   int rc;
-  if (ak == PQ_SRC_KC8 && bk == PQ_SRC_BITS8) rc = launch_mfma_cfg<true, PQ_SRC_KC8, PQ_SRC_BITS8>(pl, M, N, K, A, B, epi, s, part, grp);
-  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KC16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KC16>(pl, M, N, K, A, B, epi, s, part, grp);
-  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KS16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part, grp);
-  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_BITS16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_BITS16>(pl, M, N, K, A, B, epi, s, part, grp);
-  else if (ak == PQ_SRC_KS16 && bk == PQ_SRC_KS16) rc = launch_mfma_cfg<false, PQ_SRC_KS16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part, grp);
+  if (ph2.K2 > 0) {
+    if (pl.splits > 1) return pq_set_error(PQ_ERR_BAD_ARG, "a fused second contraction cannot be combined with a split contraction");
+    if (ak == PQ_SRC_KC8 && bk == PQ_SRC_BITS8 && ph2.A2.kind == PQ_SRC_KC16 && ph2.B2.kind == PQ_SRC_KC16)
+      return launch_mfma_cfg<true, PQ_SRC_KC8, PQ_SRC_BITS8, PQ_SRC_KC16, PQ_SRC_KC16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+    if (ak == PQ_SRC_KC16 && bk == PQ_SRC_BITS16 && ph2.A2.kind == PQ_SRC_KC16 && ph2.B2.kind == PQ_SRC_KS16)
+      return launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_BITS16, PQ_SRC_KC16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+    return pq_set_error(PQ_ERR_BAD_ARG, "no fused MFMA kernel for these operand kinds");
+  }
+  if (ak == PQ_SRC_KC8 && bk == PQ_SRC_BITS8) rc = launch_mfma_cfg<true, PQ_SRC_KC8, PQ_SRC_BITS8>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KC16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KC16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KS16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_BITS16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_BITS16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+  else if (ak == PQ_SRC_KS16 && bk == PQ_SRC_KS16) rc = launch_mfma_cfg<false, PQ_SRC_KS16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
   else return pq_set_error(PQ_ERR_BAD_ARG, "no MFMA kernel for operand kinds (%d, %d)", ak, bk);
   if (rc != PQ_OK) return rc;
   if (pl.splits > 1) {

@@ -78,6 +78,18 @@ struct pq_epilogue {
   float tau;
 };
 
+// Optional second contraction accumulated into the same output tile (the rank-r branch fused into
+// the 1-bit GEMM): after the main contraction acc1, the accumulator becomes
+//     acc = (scale1 * [*dev_scale1] / [row_div1[m]]) * acc1 + sum_{k<K2} A2(m,k) * B2(n,k)
+// and the epilogue then applies its own scale.  bf16 operands (KC16 x KC16 or KC16 x KS16).
+struct pq_phase2 {
+  pq_operand A2, B2;
+  int K2;                    // 0 = no second contraction
+  float scale1;
+  const float* dev_scale1;
+  const float* row_div1;
+};
+
 // C[M][N] (+)= epilogue( sum_k A(m,k) * B(n,k) ).  `engine` 0 = MFMA (bf16 or int8 operands),
 // 1 = reference precision (fp64 accumulate, any operand kind).
 // Grouped execution over expert segments (Sec. 3.3): `offsets` [n_groups+1] is a device array of
@@ -104,7 +116,8 @@ struct pq_gemm_plan {
 pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8 = false);
 int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const pq_operand& B,
                    const pq_epilogue& epi, hipStream_t s, int prof_label = PQP_GEMM_OTHER,
-                   void* splitk_ws = nullptr, const pq_gemm_group* group = nullptr);
+                   void* splitk_ws = nullptr, const pq_gemm_group* group = nullptr,
+                   const pq_phase2* phase2 = nullptr);
 
 // ---- pq_decode.hip ------------------------------------------------------------------------
 size_t pq_decode_ws_layout(const pq_decode_desc& d, size_t* off);
