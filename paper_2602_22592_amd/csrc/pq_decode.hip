@@ -21,6 +21,14 @@
 
 namespace {
 
+// streaming 16-byte load: the packed weights are read exactly once, keep them out of the way of the
+// small tensors that are re-read (bit planes, expert hidden states)
+__device__ __forceinline__ uint4 nt_load16(const uint4* p) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 __device__ __forceinline__ float fp16_bits_to_f32(uint16_t h) {
   _Float16 x = __builtin_bit_cast(_Float16, h);
   return (float)x;
@@ -291,75 +299,104 @@ __global__ __launch_bounds__(256) void decode_gemv_b1_kernel(gemv_params p) {
 // needed, and a lane needs only its weight words and 8 counters in VGPRs, so many waves are
 // resident and many loads are in flight.  The 4 wavefronts of a workgroup split the columns.
 // ------------------------------------------------------------------------------------------
+template <int GPB>   // row groups (of 64 rows) per workgroup: all their loads are issued before the popcounts start
 __global__ __launch_bounds__(256) void decode_gemv_tiled_kernel(gemv_params p) {
-  __shared__ int s_dot[4][64];
-  __shared__ float s_yh[4][64];
-  const int layer = blockIdx.y, grp = blockIdx.x;
+  __shared__ int s_dot[GPB][4][64];
+  __shared__ float s_yh[GPB][64];
+  const int layer = blockIdx.y;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nw = p.K / 32, nq = nw / 4;
   const int G = (p.N + 63) / 64;
-  const uint4* __restrict__ Pg = reinterpret_cast<const uint4*>(p.P) + ((size_t)layer * G + grp) * nq * 64;
   const uint32_t* __restrict__ planes = p.planes + (size_t)layer * 8 * nw;
-  const int row = grp * 64 + lane;
-  const bool okr = row < p.N;
 
-  int a[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int q0 = 0; q0 < nq; q0 += 32) {
-    uint4 w[8];
+  int a[GPB][8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int q = q0 + 4 * i + wave;
-      w[i] = (q < nq) ? Pg[(size_t)q * 64 + lane] : make_uint4(0, 0, 0, 0);
+  for (int g = 0; g < GPB; ++g)
+#pragma unroll
+    for (int pp = 0; pp < 8; ++pp) a[g][pp] = 0;
+  for (int q0 = 0; q0 < nq; q0 += 32) {
+    uint4 w[GPB][8];
+#pragma unroll
+    for (int g = 0; g < GPB; ++g) {
+      const int grp = blockIdx.x * GPB + g;
+      const uint4* __restrict__ Pg = reinterpret_cast<const uint4*>(p.P) + ((size_t)layer * G + (grp < G ? grp : 0)) * nq * 64;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int q = q0 + 4 * i + wave;
+        w[g][i] = (q < nq && grp < G) ? nt_load16(&Pg[(size_t)q * 64 + lane]) : make_uint4(0, 0, 0, 0);
+      }
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int q = q0 + 4 * i + wave;
       if (q < nq) {                                   // wave-uniform
-        const uint32_t ww[4] = {w[i].x, w[i].y, w[i].z, w[i].w};
 #pragma unroll
         for (int pp = 0; pp < 8; ++pp) {
           const uint32_t* pl = planes + (size_t)pp * nw + 4 * q;   // uniform address: scalar loads
+          const uint32_t p0 = pl[0], p1 = pl[1], p2 = pl[2], p3 = pl[3];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) a[pp] += __builtin_popcount(ww[j] & pl[j]);
+          for (int g = 0; g < GPB; ++g)
+            a[g][pp] += __builtin_popcount(w[g][i].x & p0) + __builtin_popcount(w[g][i].y & p1) +
+                        __builtin_popcount(w[g][i].z & p2) + __builtin_popcount(w[g][i].w & p3);
         }
       }
     }
   }
-  int d = 0;
-#pragma unroll
-  for (int pp = 0; pp < 7; ++pp) d += a[pp] << pp;
-  d -= a[7] << 7;
 
-  float yh = 0.0f;
-  if (p.r > 0) {
-    for (int j = 0; j < p.topk; ++j) {
-      const int e = p.idx[layer * p.topk + j];
-      const float gt = p.gate[layer * p.topk + j];
-      const uint16_t* brow = p.hpB + (((size_t)layer * p.E + e) * p.N + (okr ? row : 0)) * p.r;
-      const float* __restrict__ hh = p.h + ((size_t)layer * p.topk + j) * p.r;
-      float part = 0.0f;
-      for (int c = wave; c < p.r / 8; c += 4) {       // the 4 wavefronts split the expert's rank
-        const uint4 b = *reinterpret_cast<const uint4*>(brow + c * 8);
-        const float* h8 = hh + c * 8;                 // uniform
-        part += __uint_as_float(b.x << 16) * h8[0] + __uint_as_float(b.x & 0xFFFF0000u) * h8[1];
-        part += __uint_as_float(b.y << 16) * h8[2] + __uint_as_float(b.y & 0xFFFF0000u) * h8[3];
-        part += __uint_as_float(b.z << 16) * h8[4] + __uint_as_float(b.z & 0xFFFF0000u) * h8[5];
-        part += __uint_as_float(b.w << 16) * h8[6] + __uint_as_float(b.w & 0xFFFF0000u) * h8[7];
+#pragma unroll
+  for (int g = 0; g < GPB; ++g) {
+    const int grp = blockIdx.x * GPB + g;
+    int d = 0;
+#pragma unroll
+    for (int pp = 0; pp < 7; ++pp) d += a[g][pp] << pp;
+    d -= a[g][7] << 7;
+    s_dot[g][wave][lane] = d;
+    // experts: wavefront w covers rows 16 w .. 16 w + 15 of the group, 8 lanes per row (one 16-byte chunk
+    // of the expert's rank each), so a load instruction reads 8 whole 128-byte rows
+    if (p.r > 0) {
+      const int sub = lane & 7, rl = lane >> 3;
+#pragma unroll
+      for (int it = 0; it < 2; ++it) {
+        const int lrow = 16 * wave + 8 * it + rl;
+        const int erow = grp * 64 + lrow;
+        const bool oke = erow < p.N;
+        float yh = 0.0f;
+        for (int j = 0; j < p.topk; ++j) {
+          const int e = p.idx[layer * p.topk + j];
+          const float gt = p.gate[layer * p.topk + j];
+          const uint16_t* brow = p.hpB + (((size_t)layer * p.E + e) * p.N + (oke ? erow : 0)) * p.r;
+          const float* hh = p.h + ((size_t)layer * p.topk + j) * p.r;
+          float part = 0.0f;
+          for (int c = sub; c < p.r / 8; c += 8) {
+            const uint4 b = nt_load16(reinterpret_cast<const uint4*>(brow + c * 8));
+            const float4 h0 = *reinterpret_cast<const float4*>(hh + c * 8);
+            const float4 h1 = *reinterpret_cast<const float4*>(hh + c * 8 + 4);
+            part += __uint_as_float(b.x << 16) * h0.x + __uint_as_float(b.x & 0xFFFF0000u) * h0.y;
+            part += __uint_as_float(b.y << 16) * h0.z + __uint_as_float(b.y & 0xFFFF0000u) * h0.w;
+            part += __uint_as_float(b.z << 16) * h1.x + __uint_as_float(b.z & 0xFFFF0000u) * h1.y;
+            part += __uint_as_float(b.w << 16) * h1.z + __uint_as_float(b.w & 0xFFFF0000u) * h1.w;
+          }
+          yh += gt * part;
+        }
+#pragma unroll
+        for (int o = 4; o > 0; o >>= 1) yh += __shfl_xor(yh, o, 64);
+        if (sub == 0) s_yh[g][lrow] = yh;
       }
-      yh += gt * part;
     }
   }
-  s_dot[wave][lane] = d;
-  s_yh[wave][lane] = yh;
   __syncthreads();
-  if (wave == 0 && okr) {
-    const int dd = s_dot[0][lane] + s_dot[1][lane] + s_dot[2][lane] + s_dot[3][lane];
-    const float yy = (s_yh[0][lane] + s_yh[1][lane]) + (s_yh[2][lane] + s_yh[3][lane]);
-    const int acc = 2 * dd - p.rowsum[layer];
-    if (p.acc_out) p.acc_out[(size_t)layer * p.N + row] = acc;
-    const float sc = fp16_bits_to_f32(p.scale[layer]) / p.gamma[layer];
-    p.Y[(size_t)layer * p.N + row] = f32_to_bf16(__fmul_rn(sc, (float)acc) + p.alpha * yy);
+  if (wave < GPB) {
+    const int g = wave;
+    const int row = (blockIdx.x * GPB + g) * 64 + lane;
+    if (row < p.N) {
+      const int dd = s_dot[g][0][lane] + s_dot[g][1][lane] + s_dot[g][2][lane] + s_dot[g][3][lane];
+      const float yy = p.r > 0 ? s_yh[g][lane] : 0.0f;
+      const int acc = 2 * dd - p.rowsum[layer];
+      if (p.acc_out) p.acc_out[(size_t)layer * p.N + row] = acc;
+      const float sc = fp16_bits_to_f32(p.scale[layer]) / p.gamma[layer];
+      p.Y[(size_t)layer * p.N + row] = f32_to_bf16(__fmul_rn(sc, (float)acc) + p.alpha * yy);
+    }
   }
 }
 
@@ -566,8 +603,11 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
     gemv_params p{packed, scale_fp16, planes, rowsum, gamma, (const uint16_t*)hpB, idx, gate, h, (uint16_t*)Y, acc_out,
                   N, K, d.n_experts, r, d.top_k, d.alpha};
     if (d.packed_layout == PQ_PACKED_TILED64) {
-      dim3 grid((N + 63) / 64, L);
-      decode_gemv_tiled_kernel<<<grid, 256, 0, s>>>(p);
+#ifndef PQ_GEMV_GPB
+#define PQ_GEMV_GPB 1
+#endif
+      dim3 grid(((N + 63) / 64 + PQ_GEMV_GPB - 1) / PQ_GEMV_GPB, L);
+      decode_gemv_tiled_kernel<PQ_GEMV_GPB><<<grid, 256, 0, s>>>(p);
       PQ_CHECK_LAUNCH("decode_gemv_tiled_kernel");
     } else {
       dim3 grid((N + GEMV_ROWS_PER_BLOCK - 1) / GEMV_ROWS_PER_BLOCK, L);
