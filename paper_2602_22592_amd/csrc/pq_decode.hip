@@ -18,6 +18,7 @@
 // Several independent layers (weight sets) can be processed by one launch (grid.y), which is how
 // the bench keeps the working set larger than the Infinity Cache.
 #include "pq_internal.h"
+#include <type_traits>
 
 namespace {
 
@@ -87,7 +88,11 @@ __global__ __launch_bounds__(256) void decode_prep_kernel(const uint16_t* __rest
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
       const unsigned long long m = __ballot(((uint32_t)q >> p) & 1u);
-      if (lane < 2) planes[((size_t)tok * 8 + p) * (K / 32) + (k0 >> 5) + lane] = (uint32_t)(m >> (32 * lane));
+      // plane words are grouped per 128 columns: [token][K/128][plane][4 words]
+      if (lane < 2) {
+        const int wd = (k0 >> 5) + lane;
+        planes[(((size_t)tok * (K / 128) + (wd >> 2)) * 8 + p) * 4 + (wd & 3)] = (uint32_t)(m >> (32 * lane));
+      }
     }
   }
 #pragma unroll
@@ -179,7 +184,7 @@ constexpr int GEMV_ROWS_PER_BLOCK = 4 * GEMV_ROWS_PER_WAVE;
 struct gemv_params {
   const uint32_t* P;      // [L][N][K/32]
   const uint16_t* scale;  // [L] fp16 bits
-  const uint32_t* planes; // [L][8][K/32]
+  const uint32_t* planes; // [L][K/128][8][4]: the 8 planes of 128 columns are 128 contiguous bytes
   const int* rowsum;      // [L]
   const float* gamma;     // [L]
   const uint16_t* hpB;    // [L][E][N][r] bf16
@@ -213,7 +218,7 @@ __global__ __launch_bounds__(256) void decode_gemv_b1_kernel(gemv_params p) {
       const int w0 = wc + 32 * i + 4 * sub;
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
-        const uint4 v = (w0 < nw) ? *reinterpret_cast<const uint4*>(planes + (size_t)q * nw + w0) : make_uint4(0, 0, 0, 0);
+        const uint4 v = (w0 < nw) ? *reinterpret_cast<const uint4*>(planes + ((size_t)(w0 >> 2) * 8 + q) * 4) : make_uint4(0, 0, 0, 0);
         pl[i][q][0] = v.x; pl[i][q][1] = v.y; pl[i][q][2] = v.z; pl[i][q][3] = v.w;
       }
     }
@@ -315,34 +320,55 @@ __global__ __launch_bounds__(256) void decode_gemv_tiled_kernel(gemv_params p) {
   for (int g = 0; g < GPB; ++g)
 #pragma unroll
     for (int pp = 0; pp < 8; ++pp) a[g][pp] = 0;
-  for (int q0 = 0; q0 < nq; q0 += 32) {
+  // 32 chunks of 128 columns per pass, 8 per wavefront.  Whole passes run without any condition, so the
+  // loads stay in flight while the wait counter releases one chunk at a time; the ragged last pass
+  // clamps its addresses and skips the chunks beyond the row.
+  auto pass = [&](const int q0, auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
     uint4 w[GPB][8];
 #pragma unroll
     for (int g = 0; g < GPB; ++g) {
       const int grp = blockIdx.x * GPB + g;
-      const uint4* __restrict__ Pg = reinterpret_cast<const uint4*>(p.P) + ((size_t)layer * G + (grp < G ? grp : 0)) * nq * 64;
+      const uint4* __restrict__ Pg = reinterpret_cast<const uint4*>(p.P) + ((size_t)layer * G + (grp < G ? grp : G - 1)) * nq * 64;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int q = q0 + 4 * i + wave;
-        w[g][i] = (q < nq && grp < G) ? nt_load16(&Pg[(size_t)q * 64 + lane]) : make_uint4(0, 0, 0, 0);
+        w[g][i] = nt_load16(&Pg[(size_t)((FULL || q < nq) ? q : nq - 1) * 64 + lane]);
       }
+    }
+    // the 32 plane words of chunk i+1 are requested (scalar loads, uniform address) before the
+    // popcounts of chunk i start
+    uint32_t pc[32], pn[32];
+    {
+      const int q = q0 + wave;
+      const uint32_t* pl = planes + (size_t)((FULL || q < nq) ? q : 0) * 32;
+#pragma unroll
+      for (int t = 0; t < 32; ++t) pc[t] = pl[t];
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int q = q0 + 4 * i + wave;
-      if (q < nq) {                                   // wave-uniform
+      if (i + 1 < 8) {
+        const int qn = q0 + 4 * (i + 1) + wave;
+        const uint32_t* pl = planes + (size_t)((FULL || qn < nq) ? qn : 0) * 32;
 #pragma unroll
-        for (int pp = 0; pp < 8; ++pp) {
-          const uint32_t* pl = planes + (size_t)pp * nw + 4 * q;   // uniform address: scalar loads
-          const uint32_t p0 = pl[0], p1 = pl[1], p2 = pl[2], p3 = pl[3];
+        for (int t = 0; t < 32; ++t) pn[t] = pl[t];
+      }
+      const int q = q0 + 4 * i + wave;
+      if (FULL || q < nq) {                            // wave-uniform
+#pragma unroll
+        for (int pp = 0; pp < 8; ++pp)
 #pragma unroll
           for (int g = 0; g < GPB; ++g)
-            a[g][pp] += __builtin_popcount(w[g][i].x & p0) + __builtin_popcount(w[g][i].y & p1) +
-                        __builtin_popcount(w[g][i].z & p2) + __builtin_popcount(w[g][i].w & p3);
-        }
+            a[g][pp] += __builtin_popcount(w[g][i].x & pc[4 * pp]) + __builtin_popcount(w[g][i].y & pc[4 * pp + 1]) +
+                        __builtin_popcount(w[g][i].z & pc[4 * pp + 2]) + __builtin_popcount(w[g][i].w & pc[4 * pp + 3]);
       }
+#pragma unroll
+      for (int t = 0; t < 32; ++t) pc[t] = pn[t];
     }
-  }
+  };
+  int q0 = 0;
+  for (; q0 + 32 <= nq; q0 += 32) pass(q0, std::true_type{});
+  if (q0 < nq) pass(q0, std::false_type{});
 
 #pragma unroll
   for (int g = 0; g < GPB; ++g) {
