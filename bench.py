@@ -69,7 +69,7 @@ def decode_bench(pq, torch, batch, n_layers=64, steps=20, warmup=3):
     Wr = (torch.randn((n_layers, E, K), device="cuda", generator=g) * 0.02).to(bf)
     scale = torch.from_numpy(np.full(n_layers, np.float16(0.2 * 0.016)).view(np.int16)).cuda()
     Y = torch.empty((n_layers, batch, N), dtype=bf, device="cuda")
-    tiled = batch == 1        # batch 1 streams the row-interleaved packing (re-tiled offline)
+    tiled = True              # the decode kernels stream the row-interleaved packing (re-tiled offline)
     if tiled:
         P = torch.stack([pq.pack_retile64(P[l], K) for l in range(n_layers)]).contiguous()
     desc = pq.DecodeDesc(batch, K, N, r, E, k, n_layers, pq.PQ_PACKED_TILED64 if tiled else pq.PQ_PACKED_ROWMAJOR, 2.0)
@@ -94,7 +94,7 @@ def decode_bench(pq, torch, batch, n_layers=64, steps=20, warmup=3):
     # algorithmic bytes of the main kernel per layer: packed bits + the selected experts' B rows + x, y
     n_sel = k if batch == 1 else min(E, batch * k)          # upper bound on distinct experts per layer
     main_bytes = n_layers * (N * K // 8 + n_sel * N * r * 2 + batch * (K + 2 * N))
-    prep_bytes = n_layers * (batch * (2 * K + k * r * K * 2) + E * K * 2)
+    prep_bytes = n_layers * (batch * 2 * K + n_sel * r * K * 2 + E * K * 2)     # x, the selected experts' A, router
     return {"batch": batch, "layers_per_launch": n_layers, "main_kernel_us": round(main_us, 2),
             "prep_kernel_us": round(prep_us, 2), "h_kernel_us": round(h_us, 2), "launch_us": round(total_us, 2),
             "main_kernel_GBps": round(main_bytes / main_us / 1e3, 1), "main_kernel_frac_hbm": round(main_bytes / main_us / 1e3 / 8000.0, 4),

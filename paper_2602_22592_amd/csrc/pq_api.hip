@@ -442,25 +442,30 @@ int check_decode(const pq_decode_desc* d) {
   PQ_REQUIRE(d->d_in > 0 && d->d_out > 0 && d->hp_rank >= 0 && d->n_layers >= 1, PQ_ERR_BAD_ARG, "bad dimension");
   PQ_REQUIRE(d->d_out % 4 == 0, PQ_ERR_SHAPE, "d_out=%d must be a multiple of 4", d->d_out);
   PQ_REQUIRE(d->d_in <= 16384, PQ_ERR_SHAPE, "d_in=%d exceeds 16384 (one token's activations are staged in LDS)", d->d_in);
-  PQ_REQUIRE(d->packed_layout == PQ_PACKED_ROWMAJOR || (d->packed_layout == PQ_PACKED_TILED64 && d->batch == 1),
-             PQ_ERR_BAD_ARG, "packed_layout=%d is not valid for batch=%d", d->packed_layout, d->batch);
+  PQ_REQUIRE(d->packed_layout == PQ_PACKED_ROWMAJOR || d->packed_layout == PQ_PACKED_TILED64, PQ_ERR_BAD_ARG,
+             "packed_layout=%d is not a known layout", d->packed_layout);
+  const bool tiled = d->packed_layout == PQ_PACKED_TILED64;
   if (d->batch == 1) {
     PQ_REQUIRE(d->d_in % 128 == 0, PQ_ERR_SHAPE, "d_in=%d must be a multiple of 128", d->d_in);
     PQ_REQUIRE(d->hp_rank % 8 == 0, PQ_ERR_SHAPE, "hp_rank=%d must be a multiple of 8", d->hp_rank);
   } else {
-    PQ_REQUIRE(d->d_in % 512 == 0, PQ_ERR_SHAPE, "batch > 1 needs d_in=%d to be a multiple of 512", d->d_in);
+    if (tiled) PQ_REQUIRE(d->d_in % 128 == 0, PQ_ERR_SHAPE, "d_in=%d must be a multiple of 128", d->d_in);
+    else PQ_REQUIRE(d->d_in % 512 == 0, PQ_ERR_SHAPE, "batch > 1 on the row-major packing needs d_in=%d to be a multiple of 512", d->d_in);
     PQ_REQUIRE(d->hp_rank % 32 == 0, PQ_ERR_SHAPE, "batch > 1 needs hp_rank=%d to be a multiple of 32", d->hp_rank);
   }
   if (d->hp_rank > 0) {
     PQ_REQUIRE(d->n_experts >= 1 && d->n_experts <= 64, PQ_ERR_BAD_ARG, "n_experts=%d must be in 1..64", d->n_experts);
     PQ_REQUIRE(d->top_k >= 1 && d->top_k <= d->n_experts, PQ_ERR_BAD_ARG, "top_k=%d must be in 1..n_experts", d->top_k);
-    if (d->batch > 1) {
-      PQ_REQUIRE((d->n_experts * d->hp_rank) % 64 == 0, PQ_ERR_SHAPE, "batch > 1 needs n_experts*hp_rank %% 64 == 0");
-      PQ_REQUIRE(16 * (size_t)d->d_in + 32 * (size_t)d->n_experts * d->hp_rank <= 160 * 1024, PQ_ERR_SHAPE,
-                 "activations and expert hidden states do not fit the 160 KiB LDS");
-    }
-  } else {
-    PQ_REQUIRE(d->batch == 1 || 16 * (size_t)d->d_in <= 160 * 1024, PQ_ERR_SHAPE, "activations do not fit the 160 KiB LDS");
+    if (d->batch > 1) PQ_REQUIRE((d->n_experts * d->hp_rank) % 64 == 0, PQ_ERR_SHAPE, "batch > 1 needs n_experts*hp_rank %% 64 == 0");
+  }
+  if (d->batch > 1) {
+    // LDS of the small-batch kernels: 8 or 16 token rows of codes and expert hidden states; on the
+    // row-interleaved packing the hidden states share their space with 8 KiB of per-wavefront patches
+    const size_t toks = d->batch <= 8 ? 8 : 16;
+    const size_t er = d->hp_rank > 0 ? (size_t)d->n_experts * d->hp_rank : 0;
+    const size_t hm = 2 * toks * er;
+    PQ_REQUIRE(toks * (size_t)d->d_in + ((tiled && hm < 8192) ? 8192 : hm) <= 160 * 1024, PQ_ERR_SHAPE,
+               "activations and expert hidden states do not fit the 160 KiB LDS");
   }
   return PQ_OK;
 }

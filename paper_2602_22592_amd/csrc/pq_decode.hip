@@ -11,8 +11,8 @@
 //             2 VALU ops per (word, plane) with the popcount's built-in accumulate, no multiplies,
 //             and sum_k q S = 2 * (that) - sum_k q.  Eight lanes share a row; the planes a lane
 //             needs stay in registers for all of its rows.
-//   batch >1  int8 MFMA (v_mfma_i32_16x16x64_i8): the weight bits are expanded to {0,1} bytes in
-//             registers (3 VALU ops per 4 weights) once for all tokens, the activations sit in
+//   batch >1  int8 MFMA (v_mfma_i32_16x16x64_i8): the weight bits are expanded to {0,-128} bytes in
+//             registers (2 VALU ops per 4 weights) once for all tokens, the activations sit in
 //             LDS; the same 2*dot - rowsum identity restores the +/-1 product.  Experts run as a
 //             dense-masked bf16 MFMA over the experts that some token of the batch selected.
 // Several independent layers (weight sets) can be processed by one launch (grid.y), which is how
@@ -83,7 +83,9 @@ __global__ __launch_bounds__(256) void decode_prep_kernel(const uint16_t* __rest
     const float y = __fmul_rn(xs[k0 + lane], g);
     const float r = fminf(fmaxf(rintf(y), -128.0f), 127.0f);
     const int q = (int)r;
-    xq[(size_t)tok * K + k0 + lane] = (int8_t)q;
+    // code order inside a 32-column group follows the byte order the small-batch MFMA kernel derives
+    // from a weight word: column 8 b + t sits at byte 4 (7 - t) + b
+    xq[(size_t)tok * K + k0 + (lane & 32) + 4 * (7 - (lane & 7)) + ((lane & 31) >> 3)] = (int8_t)q;
     isum += q;
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
@@ -336,34 +338,45 @@ __global__ __launch_bounds__(256) void decode_gemv_tiled_kernel(gemv_params p) {
         w[g][i] = nt_load16(&Pg[(size_t)((FULL || q < nq) ? q : nq - 1) * 64 + lane]);
       }
     }
-    // the 32 plane words of chunk i+1 are requested (scalar loads, uniform address) before the
+    // full passes request the 32 plane words of chunk i+1 (scalar loads, uniform address) before the
     // popcounts of chunk i start
-    uint32_t pc[32], pn[32];
-    {
-      const int q = q0 + wave;
-      const uint32_t* pl = planes + (size_t)((FULL || q < nq) ? q : 0) * 32;
+    if constexpr (FULL) {
+      uint32_t pc[32], pn[32];
+      {
+        const uint32_t* pl = planes + (size_t)(q0 + wave) * 32;
 #pragma unroll
-      for (int t = 0; t < 32; ++t) pc[t] = pl[t];
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      if (i + 1 < 8) {
-        const int qn = q0 + 4 * (i + 1) + wave;
-        const uint32_t* pl = planes + (size_t)((FULL || qn < nq) ? qn : 0) * 32;
-#pragma unroll
-        for (int t = 0; t < 32; ++t) pn[t] = pl[t];
+        for (int t = 0; t < 32; ++t) pc[t] = pl[t];
       }
-      const int q = q0 + 4 * i + wave;
-      if (FULL || q < nq) {                            // wave-uniform
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (i + 1 < 8) {
+          const uint32_t* pl = planes + (size_t)(q0 + 4 * (i + 1) + wave) * 32;
+#pragma unroll
+          for (int t = 0; t < 32; ++t) pn[t] = pl[t];
+        }
 #pragma unroll
         for (int pp = 0; pp < 8; ++pp)
 #pragma unroll
           for (int g = 0; g < GPB; ++g)
             a[g][pp] += __builtin_popcount(w[g][i].x & pc[4 * pp]) + __builtin_popcount(w[g][i].y & pc[4 * pp + 1]) +
                         __builtin_popcount(w[g][i].z & pc[4 * pp + 2]) + __builtin_popcount(w[g][i].w & pc[4 * pp + 3]);
-      }
 #pragma unroll
-      for (int t = 0; t < 32; ++t) pc[t] = pn[t];
+        for (int t = 0; t < 32; ++t) pc[t] = pn[t];
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int q = q0 + 4 * i + wave;
+        if (q < nq) {                                  // wave-uniform
+          const uint32_t* pl = planes + (size_t)q * 32;
+#pragma unroll
+          for (int pp = 0; pp < 8; ++pp)
+#pragma unroll
+            for (int g = 0; g < GPB; ++g)
+              a[g][pp] += __builtin_popcount(w[g][i].x & pl[4 * pp]) + __builtin_popcount(w[g][i].y & pl[4 * pp + 1]) +
+                          __builtin_popcount(w[g][i].z & pl[4 * pp + 2]) + __builtin_popcount(w[g][i].w & pl[4 * pp + 3]);
+        }
+      }
     }
   };
   int q0 = 0;
@@ -462,28 +475,32 @@ constexpr int G16_RT = 4;                           // 16-row MFMA tiles per wav
 constexpr int G16_ROWS_PER_WAVE = 16 * G16_RT;
 constexpr int G16_ROWS_PER_BLOCK = 4 * G16_ROWS_PER_WAVE;
 
-__device__ __forceinline__ uint32_t expand01(uint32_t nib) { return __umul24(nib, 0x00204081u) & 0x01010101u; }
-
-__global__ __launch_bounds__(256) void decode_gemm16_kernel(gemm16_params p) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char dsm[];
-  // dsm: xq [16][K] int8 (16-byte chunk c of token j stored at chunk c ^ (j & 7)), then Hm [16][E*r] bf16
-  const int layer = blockIdx.y;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+// Stages the batch's INT8 codes and the gate-weighted expert hidden states into LDS and returns the mask
+// of experts that some token selected.  xs: [TOKS][K] int8, 16-byte chunk c of token j at chunk c ^ (j & 7);
+// hm: [TOKS][E*r] bf16 (zero where a token did not select the expert), same chunk swizzle.
+template <int TOKS>
+__device__ __forceinline__ unsigned long long g16_stage_inputs(const gemm16_params& p, int layer, unsigned char* xs,
+                                                               uint16_t* hm) {
+  const int tid = threadIdx.x;
   const int K = p.K, Er = p.E * p.r;
-  unsigned char* xs = dsm;
-  uint16_t* hm = reinterpret_cast<uint16_t*>(dsm + 16 * (size_t)K);
   const int kch = K / 16;
-  for (int c = tid; c < 16 * kch; c += 256) {
+  for (int c = tid; c < TOKS * kch; c += 256) {
     const int j = c / kch, cc = c % kch;
     uint4 v = make_uint4(0, 0, 0, 0);
     if (j < p.B) v = *reinterpret_cast<const uint4*>(p.xq + ((size_t)layer * p.B + j) * K + cc * 16);
     *reinterpret_cast<uint4*>(xs + (size_t)j * K + ((cc ^ (j & 7)) << 4)) = v;
   }
-  for (int c = tid; c < 16 * Er / 8; c += 256) reinterpret_cast<uint4*>(hm)[c] = make_uint4(0, 0, 0, 0);
+  for (int c = tid; c < TOKS * Er / 8; c += 256) reinterpret_cast<uint4*>(hm)[c] = make_uint4(0, 0, 0, 0);
   __syncthreads();
   unsigned long long used = 0ull;
   if (p.r > 0) {
-    for (int s = 0; s < p.B * p.topk; ++s) used |= 1ull << p.idx[(size_t)layer * p.B * p.topk + s];
+    // every wavefront builds the mask of selected experts: lane s reads slot s, a ballot per expert bit
+    const int nslot = p.B * p.topk;                  // <= 16 * 64
+    for (int s0 = 0; s0 < nslot; s0 += 64) {
+      const int s = s0 + (tid & 63);
+      const int e = s < nslot ? p.idx[(size_t)layer * nslot + s] : -1;
+      for (int ee = 0; ee < p.E; ++ee) used |= (__ballot(e == ee) != 0ull) ? (1ull << ee) : 0ull;
+    }
     for (int c = tid; c < p.B * p.topk * p.r; c += 256) {
       const int rr = c % p.r, s = c / p.r, j = s / p.topk;
       const int e = p.idx[(size_t)layer * p.B * p.topk + s];
@@ -493,86 +510,288 @@ __global__ __launch_bounds__(256) void decode_gemm16_kernel(gemm16_params p) {
     }
   }
   __syncthreads();
+  return used;
+}
+
+// TOKS = token rows kept in LDS (8 or 16).  With at most 8 tokens the MFMA's columns 8..15 re-read the
+// rows of columns 0..7 (their results are never stored), which halves the LDS footprint and doubles the
+// resident workgroups per CU.
+template <int TOKS>
+__global__ __launch_bounds__(256) void decode_gemm16_kernel(gemm16_params p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char dsm[];
+  // dsm: xq [TOKS][K] int8 (16-byte chunk c of token j stored at chunk c ^ (j & 7)), then Hm [TOKS][E*r] bf16
+  const int layer = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int K = p.K, Er = p.E * p.r;
+  unsigned char* xs = dsm;
+  uint16_t* hm = reinterpret_cast<uint16_t*>(dsm + TOKS * (size_t)K);
+  const unsigned long long used = g16_stage_inputs<TOKS>(p, layer, xs, hm);
 
   const int i = lane & 15, g = lane >> 4;
+  const int il = i & (TOKS - 1);                     // LDS row read for MFMA column i
   const int row0 = blockIdx.x * G16_ROWS_PER_BLOCK + wave * G16_ROWS_PER_WAVE;
   if (row0 >= p.N) return;
   const int nw = K / 32;
   const uint32_t* P = p.P + (size_t)layer * p.N * nw;
 
-  i32x4_t acc[G16_RT];
-  f32x4_t accf[G16_RT];
+  // A wavefront walks its 64 rows as four 16-row MFMA tiles.  One step covers 4096 columns of a tile:
+  // 16 whole rows of 512 bytes = 8 KB of contiguous packed weights, fetched by eight 16-byte loads per
+  // lane (lane (i, g) takes bytes 64 j + 16 g of row i), so every DRAM page is visited once.  The loads
+  // of the next step are issued before the MFMAs of the current one.
+  //
+  // Weight bytes for the MFMA are {0, -128}: (x << s) & 0x80808080 puts bit 8 b + 7 - s of the word x
+  // into the sign position of byte b, one AND (plus one shift) per four weights.  The accumulator then
+  // holds -128 * sum_k [S=+1] q_k; the INT8 codes in LDS are stored in the matching byte order.  Rows
+  // past N read row 0 and are never stored.
+  constexpr uint32_t SIGNS = 0x80808080u;
+  const int ncb = (K + 4095) / 4096;                 // K is a multiple of 512
+  const int nsteps = G16_RT * ncb;
+  uint4 wn[8];
+  auto issue = [&](const int u) {
+    const int t = u / ncb, cb = u - t * ncb;
+    const int row = row0 + 16 * t + i;
+    const uint32_t* pr = P + (size_t)(row < p.N ? row : 0) * nw + 4 * g + cb * 128;
+    const int nj = min(8, (K - 4096 * cb) / 512);
 #pragma unroll
+    for (int j = 0; j < 8; ++j) wn[j] = nt_load16(reinterpret_cast<const uint4*>(pr + (j < nj ? j : 0) * 16));
+  };
+  issue(0);
+  const int nhf = p.r / 32;
+
   for (int t = 0; t < G16_RT; ++t) {
-    acc[t] = i32x4_t{0, 0, 0, 0};
-    accf[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  }
-  // 512 columns per step: lane (i, g) holds words 4g..4g+3 of the step for row 16 t + i; MFMA issue s
-  // consumes bits [16 s, 16 s + 16) of that 128-bit group, i.e. columns 512 c + 128 g + 16 s + [0,16),
-  // and the activation fragment is read from the same columns.
-  for (int c = 0; c < K / 512; ++c) {
-    uint4 w[G16_RT];
+    if (row0 + 16 * t >= p.N) break;                 // wave-uniform
+    i32x4_t acc0 = i32x4_t{0, 0, 0, 0}, acc1 = i32x4_t{0, 0, 0, 0};
+    for (int cb = 0; cb < ncb; ++cb) {
+      uint4 w[8];
 #pragma unroll
-    for (int t = 0; t < G16_RT; ++t) {
-      const int row = row0 + 16 * t + i;
-      const bool ok = row < p.N;
-      const uint4 v = *reinterpret_cast<const uint4*>(P + (size_t)(ok ? row : 0) * nw + c * 16 + 4 * g);
-      const uint32_t m = ok ? 0xFFFFFFFFu : 0u;
-      w[t] = make_uint4(v.x & m, v.y & m, v.z & m, v.w & m);
-    }
+      for (int j = 0; j < 8; ++j) w[j] = wn[j];
+      const int u = t * ncb + cb;
+      if (u + 1 < nsteps) issue(u + 1);
+      const int nj = min(8, (K - 4096 * cb) / 512);
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const int chunk = 32 * c + 8 * g + s;
-      const uint4 act = *reinterpret_cast<const uint4*>(xs + (size_t)i * K + ((chunk ^ (i & 7)) << 4));
+      for (int j = 0; j < 8; ++j) {
+        if (j < nj) {                                // block-uniform
 #pragma unroll
-      for (int t = 0; t < G16_RT; ++t) {
-        const uint32_t word = (s >> 1) == 0 ? w[t].x : (s >> 1) == 1 ? w[t].y : (s >> 1) == 2 ? w[t].z : w[t].w;
-        const uint32_t bits = (s & 1) ? (word >> 16) : (word & 0xFFFFu);
-        const uint4 ex = make_uint4(expand01(bits & 0xFu), expand01((bits >> 4) & 0xFu), expand01((bits >> 8) & 0xFu),
-                                    expand01((bits >> 12) & 0xFu));
-        acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4_t, ex), __builtin_bit_cast(i32x4_t, act),
-                                                       acc[t], 0, 0, 0);
+          for (int ww = 0; ww < 4; ++ww) {
+            const int chunk = 256 * cb + 32 * j + 8 * g + 2 * ww;
+            const uint4 act0 = *reinterpret_cast<const uint4*>(xs + (size_t)il * K + ((chunk ^ (il & 7)) << 4));
+            const uint4 act1 = *reinterpret_cast<const uint4*>(xs + (size_t)il * K + (((chunk + 1) ^ (il & 7)) << 4));
+            const uint32_t x = ww == 0 ? w[j].x : ww == 1 ? w[j].y : ww == 2 ? w[j].z : w[j].w;
+            const uint4 e0 = make_uint4(x & SIGNS, (x << 1) & SIGNS, (x << 2) & SIGNS, (x << 3) & SIGNS);
+            const uint4 e1 = make_uint4((x << 4) & SIGNS, (x << 5) & SIGNS, (x << 6) & SIGNS, (x << 7) & SIGNS);
+            acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4_t, e0), __builtin_bit_cast(i32x4_t, act0),
+                                                         acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4_t, e1), __builtin_bit_cast(i32x4_t, act1),
+                                                         acc1, 0, 0, 0);
+          }
+        }
       }
     }
+    // experts selected by at least one token of the batch: dense-masked bf16 MFMA, 32 columns of r per
+    // issue; the rows of up to four experts are requested together
+    f32x4_t accf = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    if (p.r > 0) {
+      const int row = row0 + 16 * t + i;
+      const size_t roff = (size_t)(row < p.N ? row : 0) * p.r + 8 * g;
+      for (int hf = 0; hf < nhf; hf += 2) {
+        const bool two = hf + 1 < nhf;
+        for (int e0 = 0; e0 < p.E; e0 += 4) {
+          if (!((used >> e0) & 0xFull)) continue;
+          uint4 a0[4], a1[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int e = (e0 + q < p.E && ((used >> (e0 + q)) & 1ull)) ? e0 + q : -1;
+            const uint16_t* br = p.hpB + ((size_t)layer * p.E + (e < 0 ? 0 : e)) * p.N * p.r + roff + 32 * hf;
+            if (e >= 0) {                            // block-uniform
+              a0[q] = nt_load16(reinterpret_cast<const uint4*>(br));
+              a1[q] = nt_load16(reinterpret_cast<const uint4*>(br + (two ? 32 : 0)));
+            } else {
+              a0[q] = make_uint4(0, 0, 0, 0);
+              a1[q] = make_uint4(0, 0, 0, 0);
+            }
+          }
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int e = e0 + q;
+            if (e < p.E && ((used >> e) & 1ull)) {
+              const int col = e * p.r + 32 * hf + 8 * g;
+              const uint4 b0 = *reinterpret_cast<const uint4*>(hm + (size_t)il * Er + (((col >> 3) ^ (il & 7)) << 3));
+              accf = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a0[q]), __builtin_bit_cast(bf16x8_t, b0),
+                                                             accf, 0, 0, 0);
+              if (two) {
+                const uint4 b1 = *reinterpret_cast<const uint4*>(hm + (size_t)il * Er + ((((col + 32) >> 3) ^ (il & 7)) << 3));
+                accf = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a1[q]), __builtin_bit_cast(bf16x8_t, b1),
+                                                               accf, 0, 0, 0);
+              }
+            }
+          }
+        }
+      }
+    }
+    // D[row 4 g + v][token i]
+    const int j = i;
+    const int n0 = row0 + 16 * t + 4 * g;
+    if (j < p.B && n0 < p.N) {                        // N % 4 == 0: a group of four rows is all in or all out
+      const float sc = fp16_bits_to_f32(p.scale[layer]) / p.gamma[layer * p.B + j];
+      const int rs = p.rowsum[layer * p.B + j];
+      float y[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int a = -((acc0[v] + acc1[v]) >> 6) - rs;   // 2 * (-acc / 128) - rowsum, acc is a multiple of 128
+        if (p.acc_out) p.acc_out[((size_t)layer * p.B + j) * p.N + n0 + v] = a;
+        y[v] = __fmul_rn(sc, (float)a) + p.alpha * accf[v];
+      }
+      *reinterpret_cast<uint2*>(p.Y + ((size_t)layer * p.B + j) * p.N + n0) =
+          make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+    }
   }
-  // experts selected by at least one token of the batch: dense-masked bf16 MFMA, 32 columns of r per issue
-  if (p.r > 0) {
+}
+
+// The same product on the row-interleaved packing.  A wavefront owns one group of 64 rows, whose packed
+// bits are one contiguous run of K * 8 bytes: each load instruction reads 1 KB of consecutive memory
+// (lane = row, 128 columns).  The MFMA wants lane (i, g) to hold row 16 t + i instead, so each 1 KB chunk
+// makes a round trip through a wave-private LDS patch: written as loaded, read back one word per tile
+// (word g of row 16 t + i, bank-conflict free).  Results leave through the same patch so that a token's
+// 64 outputs are stored as one 128-byte run.
+template <int TOKS>
+__global__ __launch_bounds__(256, 4) void decode_gemm16_tiled_kernel(gemm16_params p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char dsm[];
+  // dsm: xq [TOKS][K] int8, then a region that first holds Hm [TOKS][E*r] bf16 (expert phase) and afterwards
+  // the four 2 KB wave-private patches (1-bit phase and output staging); it is max(8 KB, Hm) long
+  const int layer = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int K = p.K, Er = p.E * p.r;
+  unsigned char* xs = dsm;
+  uint16_t* hm = reinterpret_cast<uint16_t*>(dsm + TOKS * (size_t)K);
+  uint32_t* patch = reinterpret_cast<uint32_t*>(dsm + TOKS * (size_t)K) + wave * 512;
+  const int i = lane & 15, g = lane >> 4;
+  const int il = i & (TOKS - 1);
+  const int G = (p.N + 63) / 64;
+  const int grp = blockIdx.x * 4 + wave;
+  const int nq = K / 128;
+  const uint4* __restrict__ Pg = reinterpret_cast<const uint4*>(p.P) + ((size_t)layer * G + (grp < G ? grp : G - 1)) * nq * 64 + lane;
+  constexpr uint32_t SIGNS = 0x80808080u;             // weight bytes {0, -128}, see decode_gemm16_kernel
+
+  i32x4_t acc[4][2];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) acc[t][0] = acc[t][1] = i32x4_t{0, 0, 0, 0};
+
+  // Eight chunks (8 KB per wavefront) are in flight at any time: as soon as a chunk has been written to the
+  // patch its registers receive the chunk eight positions ahead.
+  uint4 w[8];
+#pragma unroll
+  for (int jj = 0; jj < 8; ++jj) w[jj] = nt_load16(Pg + (size_t)(jj < nq ? jj : nq - 1) * 64);
+  const unsigned long long used = g16_stage_inputs<TOKS>(p, layer, xs, hm);   // overlaps the first loads
+  const bool active = grp < G;                        // idle wavefronts of the last workgroup still meet the barrier
+
+  // experts selected by at least one token of the batch (dense-masked bf16 MFMA, 32 columns of r per issue)
+  f32x4_t accf[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) accf[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  if (p.r > 0 && active) {
+    const int nhf = p.r / 32;
+    size_t roff[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int row = grp * 64 + 16 * t + i;
+      roff[t] = (size_t)(row < p.N ? row : 0) * p.r + 8 * g;
+    }
     for (int e = 0; e < p.E; ++e) {
       if (!((used >> e) & 1ull)) continue;
-      for (int hf = 0; hf < p.r / 32; ++hf) {
-        const int col = e * p.r + 32 * hf + 8 * g;
-        const uint4 bfrag = *reinterpret_cast<const uint4*>(hm + (size_t)i * Er + (((col >> 3) ^ (i & 7)) << 3));
+      const uint16_t* Be = p.hpB + ((size_t)layer * p.E + e) * p.N * p.r;
+      for (int hf = 0; hf < nhf; hf += 2) {
+        const bool two = hf + 1 < nhf;
+        uint4 a0[4], a1[4];
 #pragma unroll
-        for (int t = 0; t < G16_RT; ++t) {
-          const int row = row0 + 16 * t + i;
-          const bool ok = row < p.N;
-          const uint4 v = *reinterpret_cast<const uint4*>(p.hpB + (((size_t)layer * p.E + e) * p.N + (ok ? row : 0)) * p.r + 32 * hf + 8 * g);
-          const uint32_t m = ok ? 0xFFFFFFFFu : 0u;
-          const uint4 afrag = make_uint4(v.x & m, v.y & m, v.z & m, v.w & m);
-          accf[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, afrag), __builtin_bit_cast(bf16x8_t, bfrag),
+        for (int t = 0; t < 4; ++t) {
+          a0[t] = nt_load16(reinterpret_cast<const uint4*>(Be + roff[t] + 32 * hf));
+          a1[t] = nt_load16(reinterpret_cast<const uint4*>(Be + roff[t] + 32 * hf + (two ? 32 : 0)));
+        }
+        const int col = e * p.r + 32 * hf + 8 * g;
+        const uint4 b0 = *reinterpret_cast<const uint4*>(hm + (size_t)il * Er + (((col >> 3) ^ (il & 7)) << 3));
+        const uint4 b1 = *reinterpret_cast<const uint4*>(hm + (size_t)il * Er + ((((col + (two ? 32 : 0)) >> 3) ^ (il & 7)) << 3));
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          accf[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a0[t]), __builtin_bit_cast(bf16x8_t, b0),
                                                             accf[t], 0, 0, 0);
+          if (two)
+            accf[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a1[t]), __builtin_bit_cast(bf16x8_t, b1),
+                                                              accf[t], 0, 0, 0);
         }
       }
     }
   }
-  // D[row 4 g + v][token i]
-  const int j = i;
-  if (j < p.B) {
-    const float sc = fp16_bits_to_f32(p.scale[layer]) / p.gamma[layer * p.B + j];
-    const int rs = p.rowsum[layer * p.B + j];
+
+  __syncthreads();                                    // Hm is dead: its LDS becomes the patches
+
+  // Passes of 8 chunks; whole passes carry no condition (one basic block: the accumulators stay put and
+  // the MFMAs of one chunk overlap the LDS round trip of the next), the ragged last pass checks each chunk.
+  auto pass = [&](const int q0, auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
-    for (int t = 0; t < G16_RT; ++t) {
-      const int n0 = row0 + 16 * t + 4 * g;
-      if (n0 < p.N) {                                // N % 4 == 0: a group of four rows is all in or all out
-        float y[4];
+    for (int jj = 0; jj < 8; ++jj) {
+      if (FULL || q0 + jj < nq) {                     // block-uniform
+        uint32_t* buf = patch + (jj & 1) * 256;
+        *reinterpret_cast<uint4*>(buf + 4 * lane) = w[jj];
+        const int qn = q0 + 8 + jj;
+        w[jj] = nt_load16(Pg + (size_t)(qn < nq ? qn : nq - 1) * 64);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const int chunk = 8 * (q0 + jj) + 2 * g;      // 16-column chunk of the activation row
+        const uint4 act0 = *reinterpret_cast<const uint4*>(xs + (size_t)il * K + ((chunk ^ (il & 7)) << 4));
+        const uint4 act1 = *reinterpret_cast<const uint4*>(xs + (size_t)il * K + (((chunk + 1) ^ (il & 7)) << 4));
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int a = 2 * acc[t][v] - rs;
-          if (p.acc_out) p.acc_out[((size_t)layer * p.B + j) * p.N + n0 + v] = a;
-          y[v] = __fmul_rn(sc, (float)a) + p.alpha * accf[t][v];
+        for (int t = 0; t < 4; ++t) {
+          const uint32_t x = buf[(16 * t + i) * 4 + g];
+          const uint4 e0 = make_uint4(x & SIGNS, (x << 1) & SIGNS, (x << 2) & SIGNS, (x << 3) & SIGNS);
+          const uint4 e1 = make_uint4((x << 4) & SIGNS, (x << 5) & SIGNS, (x << 6) & SIGNS, (x << 7) & SIGNS);
+          acc[t][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4_t, e0), __builtin_bit_cast(i32x4_t, act0),
+                                                            acc[t][0], 0, 0, 0);
+          acc[t][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4_t, e1), __builtin_bit_cast(i32x4_t, act1),
+                                                            acc[t][1], 0, 0, 0);
         }
-        *reinterpret_cast<uint2*>(p.Y + ((size_t)layer * p.B + j) * p.N + n0) =
-            make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+      }
+    }
+  };
+  if (!active) return;                                // no workgroup barrier below
+  int q0 = 0;
+  for (; q0 + 8 <= nq; q0 += 8) pass(q0, std::true_type{});
+  if (q0 < nq) pass(q0, std::false_type{});
+
+  // D[row 4 g + v][token i] -> patch as [token][64 rows] bf16, then 128-byte runs per token
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  uint16_t* stage = reinterpret_cast<uint16_t*>(patch);
+  if (i < p.B) {
+    const float sc = fp16_bits_to_f32(p.scale[layer]) / p.gamma[layer * p.B + i];
+    const int rs = p.rowsum[layer * p.B + i];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      float y[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int a = -((acc[t][0][v] + acc[t][1][v]) >> 6) - rs;   // 2 * (-acc / 128) - rowsum
+        const int n = grp * 64 + 16 * t + 4 * g + v;
+        if (p.acc_out && n < p.N) p.acc_out[((size_t)layer * p.B + i) * p.N + n] = a;
+        y[v] = __fmul_rn(sc, (float)a) + p.alpha * accf[t][v];
+      }
+      *reinterpret_cast<uint2*>(stage + i * 64 + 16 * t + 4 * g) = make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  const int piece = lane & 7;
+  const int n0 = grp * 64 + 8 * piece;
+  const bool vec_ok = (p.N % 8 == 0);
+  for (int jb = 0; jb < p.B; jb += 8) {
+    const int j = jb + (lane >> 3);
+    if (j < p.B && n0 < p.N) {
+      uint16_t* dst = p.Y + ((size_t)layer * p.B + j) * p.N + n0;
+      const uint16_t* src = stage + j * 64 + 8 * piece;
+      if (vec_ok) {                                   // N % 8 == 0: the 8 rows are all inside and 16-byte aligned
+        *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+      } else {
+        for (int v = 0; v < 8 && n0 + v < p.N; ++v) dst[v] = src[v];
       }
     }
   }
@@ -643,14 +862,27 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
   } else {
     gemm16_params p{packed, scale_fp16, xq, rowsum, gamma, (const uint16_t*)hpB, idx, gate, h, (uint16_t*)Y, acc_out,
                     B, N, K, d.n_experts, r, d.top_k, d.alpha};
-    const size_t lds = 16 * (size_t)K + 32 * (size_t)d.n_experts * r;
+    const int toks = B <= 8 ? 8 : 16;
+    const bool tiled = d.packed_layout == PQ_PACKED_TILED64;
+    const size_t hm_bytes = 2 * (size_t)toks * d.n_experts * r;
+    const size_t lds = (size_t)toks * K + (tiled ? (hm_bytes > 8192 ? hm_bytes : 8192) : hm_bytes);
     static bool attr_set = false;
     if (!attr_set) {
-      PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+      PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+      PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+      PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+      PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
       attr_set = true;
     }
-    dim3 grid((N + G16_ROWS_PER_BLOCK - 1) / G16_ROWS_PER_BLOCK, L);
-    decode_gemm16_kernel<<<grid, 256, lds, s>>>(p);
+    if (tiled) {
+      dim3 grid(((N + 63) / 64 + 3) / 4, L);
+      if (toks == 8) decode_gemm16_tiled_kernel<8><<<grid, 256, lds, s>>>(p);
+      else decode_gemm16_tiled_kernel<16><<<grid, 256, lds, s>>>(p);
+    } else {
+      dim3 grid((N + G16_ROWS_PER_BLOCK - 1) / G16_ROWS_PER_BLOCK, L);
+      if (toks == 8) decode_gemm16_kernel<8><<<grid, 256, lds, s>>>(p);
+      else decode_gemm16_kernel<16><<<grid, 256, lds, s>>>(p);
+    }
     PQ_CHECK_LAUNCH("decode_gemm16_kernel");
   }
   return PQ_OK;

@@ -73,16 +73,26 @@ def test_decode_gemv_batch1(L, B, K, N, E, r, k, tiled):
 
 @pytest.mark.parametrize("L,B,K,N,E,r,k", [(1, 3, 512, 200, 4, 32, 2), (2, 8, 1024, 1028, 8, 64, 2), (1, 16, 512, 64, 2, 32, 1),
                                            (1, 2, 4096, 300, 1, 0, 1), (1, 5, 1536, 520, 8, 32, 3)])
-def test_decode_small_batch(L, B, K, N, E, r, k):
-    print(f"decode B={B}: L={L} K={K} N={N} E={E} r={r} k={k}", flush=True)
-    check_decode(wl.decode_case(50 + K + N + B, B, d_in=K, d_out=N, n_experts=E, hp_rank=r, n_layers=L), top_k=k)
+@pytest.mark.parametrize("tiled", [False, True])
+def test_decode_small_batch(L, B, K, N, E, r, k, tiled):
+    print(f"decode B={B}: L={L} K={K} N={N} E={E} r={r} k={k} tiled={tiled}", flush=True)
+    check_decode(wl.decode_case(50 + K + N + B, B, d_in=K, d_out=N, n_experts=E, hp_rank=r, n_layers=L), top_k=k,
+                 tiled=tiled)
 
 
-@pytest.mark.parametrize("B", [1, 8])
-def test_decode_config4_full_size(B):
+@pytest.mark.parametrize("L,B,K,N,E,r,k", [(1, 4, 640, 132, 4, 32, 2), (2, 9, 1408, 260, 2, 64, 1)])
+def test_decode_small_batch_tiled_ragged_k(L, B, K, N, E, r, k):
+    """Row-interleaved packing takes any d_in that is a multiple of 128 (here not of 512) and a ragged last group."""
+    print(f"decode tiled B={B}: L={L} K={K} N={N} E={E} r={r} k={k}", flush=True)
+    check_decode(wl.decode_case(70 + K + N + B, B, d_in=K, d_out=N, n_experts=E, hp_rank=r, n_layers=L), top_k=k,
+                 tiled=True)
+
+
+@pytest.mark.parametrize("B,tiled", [(1, True), (8, True), (8, False)])
+def test_decode_config4_full_size(B, tiled):
     """4096 -> 11008, E=8 top-2 experts of rank 64 (the bench shape), two layers."""
-    print(f"decode config 4, B={B}", flush=True)
-    check_decode(wl.decode_case(4, B, n_layers=2), top_k=2, tiled=(B == 1))
+    print(f"decode config 4, B={B} tiled={tiled}", flush=True)
+    check_decode(wl.decode_case(4, B, n_layers=2), top_k=2, tiled=tiled)
 
 
 def test_decode_alpha_zero_and_beta_edge():
