@@ -89,7 +89,7 @@ def decode_bench(pq, torch, batch, n_layers=64, steps=20, warmup=3):
     prof = pq.prof_read(); pq.prof_reset()
     main_us = 1e3 * prof["decode_main"][0] / prof["decode_main"][1]
     prep_us = 1e3 * prof["decode_prep"][0] / prof["decode_prep"][1]
-    h_us = 1e3 * prof["decode_h"][0] / prof["decode_h"][1]
+    h_us = 1e3 * prof["decode_h"][0] / prof["decode_h"][1] if "decode_h" in prof else 0.0   # batch 1: fused into prep
     total_us = 1e3 * e0.elapsed_time(e1) / steps
     # algorithmic bytes of the main kernel per layer: packed bits + the selected experts' B rows + x, y
     n_sel = k if batch == 1 else min(E, batch * k)          # upper bound on distinct experts per layer

@@ -36,24 +36,24 @@ __device__ __forceinline__ float fp16_bits_to_f32(uint16_t h) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Prep: one workgroup per (layer, token): quantise, bit planes, row sum, router.
+// Prep: quantise (Sec. 3.1), bit planes, row sum, router (Sec. 3.3).  The steps are device functions shared
+// by two kernels: one workgroup per (layer, token) doing all of them (any batch), and for batch 1 a fused
+// kernel that also produces the expert hidden states so that a decode call is two launches.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void decode_prep_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wr,
-                                                          int B, int K, int E, int topk, int8_t* __restrict__ xq,
-                                                          uint32_t* __restrict__ planes, int* __restrict__ rowsum,
-                                                          float* __restrict__ gamma, int* __restrict__ idx,
-                                                          float* __restrict__ gate) {
-  extern __shared__ __attribute__((aligned(16))) float xs[];   // the token's activations as fp32 [K]
-  __shared__ float s_red[4];
-  __shared__ double s_dred[4][8];
-  __shared__ float s_gamma;
-  __shared__ int s_isum[4];
-  __shared__ double s_logit[64];
-  const int tok = blockIdx.x;            // layer * B + b
-  const int layer = tok / B;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const uint4* x4 = reinterpret_cast<const uint4*>(X + (size_t)tok * K);
+struct prep_shared {
+  float red[4];
+  double dred[4][8];
+  float gamma;
+  int isum[4];
+  double logit[64];
+  double expo[64];
+  int sel[64];
+};
 
+// x -> fp32 in LDS; returns this thread's partial absmax
+__device__ __forceinline__ float prep_load_x(const uint16_t* __restrict__ X, size_t tok, int K, float* xs) {
+  const int tid = threadIdx.x;
+  const uint4* x4 = reinterpret_cast<const uint4*>(X + tok * K);
   float amax = 0.0f;
   for (int c = tid; c < K / 8; c += 256) {
     const uint4 u = x4[c];
@@ -65,27 +65,34 @@ __global__ __launch_bounds__(256) void decode_prep_kernel(const uint16_t* __rest
     *reinterpret_cast<float4*>(xs + 8 * c) = make_float4(f[0], f[1], f[2], f[3]);
     *reinterpret_cast<float4*>(xs + 8 * c + 4) = make_float4(f[4], f[5], f[6], f[7]);
   }
+  return amax;
+}
+
+// INT8 codes, bit planes, row sum and gamma of one token (all threads of the workgroup; xs is complete)
+__device__ __forceinline__ void prep_quantise(float amax, size_t tok, int K, const float* xs, prep_shared& sh,
+                                              int8_t* __restrict__ xq, uint32_t* __restrict__ planes,
+                                              int* __restrict__ rowsum, float* __restrict__ gamma) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   amax = wave_max(amax);
-  if (lane == 0) s_red[wave] = amax;
+  if (lane == 0) sh.red[wave] = amax;
   __syncthreads();
   if (tid == 0) {
-    const float a = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+    const float a = fmaxf(fmaxf(sh.red[0], sh.red[1]), fmaxf(sh.red[2], sh.red[3]));
     const float g = 128.0f / fmaxf(a, 1e-5f);
-    s_gamma = g;
+    sh.gamma = g;
     gamma[tok] = g;
   }
   __syncthreads();
-  const float g = s_gamma;
-
-  // codes, bit planes and the row sum: lane <-> column, a wave-wide ballot per bit plane yields two words
+  const float g = sh.gamma;
+  // lane <-> column, a wave-wide ballot per bit plane yields two words
   int isum = 0;
   for (int k0 = wave * 64; k0 < K; k0 += 256) {
     const float y = __fmul_rn(xs[k0 + lane], g);
     const float r = fminf(fmaxf(rintf(y), -128.0f), 127.0f);
     const int q = (int)r;
-    // code order inside a 32-column group follows the byte order the small-batch MFMA kernel derives
+    // code order inside a 32-column group follows the byte order the small-batch MFMA kernels derive
     // from a weight word: column 8 b + t sits at byte 4 (7 - t) + b
-    xq[(size_t)tok * K + k0 + (lane & 32) + 4 * (7 - (lane & 7)) + ((lane & 31) >> 3)] = (int8_t)q;
+    xq[tok * K + k0 + (lane & 32) + 4 * (7 - (lane & 7)) + ((lane & 31) >> 3)] = (int8_t)q;
     isum += q;
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
@@ -93,19 +100,24 @@ __global__ __launch_bounds__(256) void decode_prep_kernel(const uint16_t* __rest
       // plane words are grouped per 128 columns: [token][K/128][plane][4 words]
       if (lane < 2) {
         const int wd = (k0 >> 5) + lane;
-        planes[(((size_t)tok * (K / 128) + (wd >> 2)) * 8 + p) * 4 + (wd & 3)] = (uint32_t)(m >> (32 * lane));
+        planes[((tok * (K / 128) + (wd >> 2)) * 8 + p) * 4 + (wd & 3)] = (uint32_t)(m >> (32 * lane));
       }
     }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) isum += __shfl_xor(isum, o, 64);
-  if (lane == 0) s_isum[wave] = isum;
+  if (lane == 0) sh.isum[wave] = isum;
   __syncthreads();
-  if (tid == 0) rowsum[tok] = s_isum[0] + s_isum[1] + s_isum[2] + s_isum[3];
+  if (tid == 0) rowsum[tok] = sh.isum[0] + sh.isum[1] + sh.isum[2] + sh.isum[3];
+}
 
-  if (E <= 0) return;
-  // router: fp64 logits rounded once to fp32, top-k on logits (ties to the lower index), softmax gates;
-  // eight experts per pass over x
+// Router of one token: fp64 logits rounded once to fp32, top-k on logits (ties to the lower index), softmax
+// gates over all experts; eight experts per pass over x.  Leaves the selection in sh.sel (valid after the
+// closing barrier); when idx is not null it also computes the gates and writes both out.
+__device__ __forceinline__ void prep_router(const uint16_t* __restrict__ Wr, int layer, size_t tok, int K, int E, int topk,
+                                            const float* xs, prep_shared& sh, int* __restrict__ idx,
+                                            float* __restrict__ gate) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int e0 = 0; e0 < E; e0 += 8) {
     double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int c = tid; c < K / 8; c += 256) {
@@ -125,26 +137,102 @@ __global__ __launch_bounds__(256) void decode_prep_kernel(const uint16_t* __rest
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const double t = wave_sum_d(acc[u]);
-      if (lane == 0) s_dred[wave][u] = t;
+      if (lane == 0) sh.dred[wave][u] = t;
     }
     __syncthreads();
     if (tid < 8 && e0 + tid < E)
-      s_logit[e0 + tid] = (double)(float)(s_dred[0][tid] + s_dred[1][tid] + s_dred[2][tid] + s_dred[3][tid]);
+      sh.logit[e0 + tid] = (double)(float)(sh.dred[0][tid] + sh.dred[1][tid] + sh.dred[2][tid] + sh.dred[3][tid]);
+  }
+  __syncthreads();
+  // softmax terms in parallel (one expert per thread), summed in index order by thread 0
+  const bool need_gate = idx != nullptr;
+  if (need_gate && tid < E) {
+    double mx = -1e300;
+    for (int e = 0; e < E; ++e) mx = fmax(mx, sh.logit[e]);
+    sh.expo[tid] = exp(sh.logit[tid] - mx);
   }
   __syncthreads();
   if (tid == 0) {
-    double mx = -1e300, den = 0.0;
-    for (int e = 0; e < E; ++e) mx = fmax(mx, s_logit[e]);
-    for (int e = 0; e < E; ++e) den += exp(s_logit[e] - mx);
+    double den = 0.0;
+    if (need_gate)
+      for (int e = 0; e < E; ++e) den += sh.expo[e];
     unsigned long long taken = 0ull;
     for (int j = 0; j < topk; ++j) {
       int best = -1;
       for (int e = 0; e < E; ++e)
-        if (!((taken >> e) & 1ull) && (best < 0 || s_logit[e] > s_logit[best])) best = e;
+        if (!((taken >> e) & 1ull) && (best < 0 || sh.logit[e] > sh.logit[best])) best = e;
       taken |= 1ull << best;
-      idx[(size_t)tok * topk + j] = best;
-      gate[(size_t)tok * topk + j] = (float)(exp(s_logit[best] - mx) / den);
+      sh.sel[j] = best;
+      if (need_gate) {
+        idx[tok * topk + j] = best;
+        gate[tok * topk + j] = (float)(sh.expo[best] / den);
+      }
     }
+  }
+  __syncthreads();
+}
+
+__global__ __launch_bounds__(256) void decode_prep_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wr,
+                                                          int B, int K, int E, int topk, int8_t* __restrict__ xq,
+                                                          uint32_t* __restrict__ planes, int* __restrict__ rowsum,
+                                                          float* __restrict__ gamma, int* __restrict__ idx,
+                                                          float* __restrict__ gate) {
+  extern __shared__ __attribute__((aligned(16))) float xs[];   // the token's activations as fp32 [K]
+  __shared__ prep_shared sh;
+  const size_t tok = blockIdx.x;         // layer * B + b
+  const int layer = (int)(tok / B);
+  const float amax = prep_load_x(X, tok, K, xs);
+  prep_quantise(amax, tok, K, xs, sh, xq, planes, rowsum, gamma);
+  if (E > 0) prep_router(Wr, layer, tok, K, E, topk, xs, sh, idx, gate);
+}
+
+// Batch 1 with experts: workgroup 0 of a layer quantises the token; each of the other workgroups repeats the
+// (cheap) router for itself and computes PREP_H_ROWS rows of the selected experts' hidden state
+// h = A_e x (bf16 inputs, fp32 accumulate), two rows per wavefront.
+constexpr int PREP_H_ROWS = 8;
+
+__global__ __launch_bounds__(256) void decode_prep_h_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wr,
+                                                            const uint16_t* __restrict__ hpA, int K, int E, int r, int topk,
+                                                            int parts, int8_t* __restrict__ xq, uint32_t* __restrict__ planes,
+                                                            int* __restrict__ rowsum, float* __restrict__ gamma,
+                                                            int* __restrict__ idx, float* __restrict__ gate,
+                                                            float* __restrict__ h) {
+  extern __shared__ __attribute__((aligned(16))) float xs[];
+  __shared__ prep_shared sh;
+  const int layer = blockIdx.x / parts, part = blockIdx.x - layer * parts;
+  const size_t tok = layer;
+  const float amax = prep_load_x(X, tok, K, xs);
+  if (part == 0) {
+    prep_quantise(amax, tok, K, xs, sh, xq, planes, rowsum, gamma);
+    return;
+  }
+  __syncthreads();                                    // xs complete
+  prep_router(Wr, layer, tok, K, E, topk, xs, sh, part == 1 ? idx : nullptr, gate);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int o0 = (part - 1) * PREP_H_ROWS + 2 * wave;  // row of the [topk][r] hidden state
+  if (o0 >= topk * r) return;
+  const bool two = o0 + 1 < topk * r;
+  const int o1 = two ? o0 + 1 : o0;
+  const uint4* a0 = reinterpret_cast<const uint4*>(hpA + (((size_t)layer * E + sh.sel[o0 / r]) * r + o0 % r) * K);
+  const uint4* a1 = reinterpret_cast<const uint4*>(hpA + (((size_t)layer * E + sh.sel[o1 / r]) * r + o1 % r) * K);
+  float s0 = 0.0f, s1 = 0.0f;
+  for (int c = lane; c < K / 8; c += 64) {
+    const uint4 u = nt_load16(a0 + c), v = nt_load16(a1 + c);
+    const float4 xa = *reinterpret_cast<const float4*>(xs + 8 * c), xb = *reinterpret_cast<const float4*>(xs + 8 * c + 4);
+    s0 += __uint_as_float(u.x << 16) * xa.x + __uint_as_float(u.x & 0xFFFF0000u) * xa.y;
+    s0 += __uint_as_float(u.y << 16) * xa.z + __uint_as_float(u.y & 0xFFFF0000u) * xa.w;
+    s0 += __uint_as_float(u.z << 16) * xb.x + __uint_as_float(u.z & 0xFFFF0000u) * xb.y;
+    s0 += __uint_as_float(u.w << 16) * xb.z + __uint_as_float(u.w & 0xFFFF0000u) * xb.w;
+    s1 += __uint_as_float(v.x << 16) * xa.x + __uint_as_float(v.x & 0xFFFF0000u) * xa.y;
+    s1 += __uint_as_float(v.y << 16) * xa.z + __uint_as_float(v.y & 0xFFFF0000u) * xa.w;
+    s1 += __uint_as_float(v.z << 16) * xb.x + __uint_as_float(v.z & 0xFFFF0000u) * xb.y;
+    s1 += __uint_as_float(v.w << 16) * xb.z + __uint_as_float(v.w & 0xFFFF0000u) * xb.w;
+  }
+  s0 = wave_sum(s0);
+  s1 = wave_sum(s1);
+  if (lane == 0) {
+    h[(size_t)layer * topk * r + o0] = s0;
+    if (two) h[(size_t)layer * topk * r + o1] = s1;
   }
 }
 
@@ -828,14 +916,21 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
   float* gate = (float*)(ws + off[5]);
   float* h = (float*)(ws + off[6]);
   const int L = d.n_layers, B = d.batch, K = d.d_in, N = d.d_out, r = d.hp_rank, E = r > 0 ? d.n_experts : 0;
-  {
+  if (B == 1 && r > 0) {
     pq_prof_scope prof(PQP_DECODE_PREP, s);
-    decode_prep_kernel<<<L * B, 256, (size_t)K * sizeof(float), s>>>((const uint16_t*)X, (const uint16_t*)Wr, B, K, E, d.top_k, xq, planes, rowsum,
-                                            gamma, idx, gate);
-    PQ_CHECK_LAUNCH("decode_prep_kernel");
-  }
-  if (r > 0) {
+    const int parts = 1 + (d.top_k * r + PREP_H_ROWS - 1) / PREP_H_ROWS;
+    decode_prep_h_kernel<<<L * parts, 256, (size_t)K * sizeof(float), s>>>((const uint16_t*)X, (const uint16_t*)Wr, (const uint16_t*)hpA,
+                                                                          K, E, r, d.top_k, parts, xq, planes, rowsum, gamma, idx,
+                                                                          gate, h);
+    PQ_CHECK_LAUNCH("decode_prep_h_kernel");
+  } else {
     {
+      pq_prof_scope prof(PQP_DECODE_PREP, s);
+      decode_prep_kernel<<<L * B, 256, (size_t)K * sizeof(float), s>>>((const uint16_t*)X, (const uint16_t*)Wr, B, K, E, d.top_k, xq,
+                                                                      planes, rowsum, gamma, idx, gate);
+      PQ_CHECK_LAUNCH("decode_prep_kernel");
+    }
+    if (r > 0) {
       pq_prof_scope prof(PQP_DECODE_H, s);
       const int total = L * B * d.top_k * r;
       decode_h_kernel<<<(total + 3) / 4, 256, 0, s>>>((const uint16_t*)X, (const uint16_t*)hpA, idx, B, K, d.n_experts, r,
