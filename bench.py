@@ -185,6 +185,8 @@ def main():
     ap.add_argument("--tokens", type=int, default=8192)
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a 256 MiB copy kernel of known size (scale for rocprofv3 --pmc byte counters)")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-ffn", action="store_true")
     ap.add_argument("--no-stack", action="store_true")
@@ -262,6 +264,19 @@ def main():
         "roofline": roofline,
         "kernels_us": {k: round(v["avg_us"], 2) for k, v in sorted(kernels.items())},
     }
+    if args.calibrate:
+        # a plain copy of known size through the library's row-gather kernel (identity indices), so that a
+        # rocprofv3 --pmc run of this command carries its own scale for FETCH_SIZE / WRITE_SIZE
+        rows, cols = 65536, 2048
+        src = torch.randn((rows, cols), device="cuda").to(bf)
+        dst = torch.empty_like(src)
+        ids = torch.arange(rows, dtype=torch.int32, device="cuda")
+        for _ in range(3):
+            pq.glue_gather_rows(src, ids, dst)
+        torch.cuda.synchronize()
+        out["calibration_copy"] = {"kernel": "gather_rows_kernel", "read_bytes": rows * cols * 2 + rows * 4,
+                                   "write_bytes": rows * cols * 2}
+        del src, dst, ids
     if not args.no_decode:
         out["decode_gemv"] = {"metric": "1-bit decode GEMV HBM GB/s (4096->11008, E=8 top-2 r=64 experts)",
                               "B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8)}
