@@ -106,16 +106,20 @@ struct tile_stage {
     }
   }
 
-  // k0: contraction index of the tile's first element; K: end of the valid contraction range
-  __device__ __forceinline__ void load(const pq_operand& op, int k0, int K) {
+  // k0: contraction index of the tile's first element; K: end of the valid contraction range.  The loads of
+  // a step can be issued in `np` pieces (piece = 0..np-1, both compile-time constants after unrolling) so
+  // that the caller can spread them between its MFMA groups.
+  __device__ __forceinline__ void load(const pq_operand& op, int k0, int K, int piece = 0, int np = 1) {
     if constexpr (kStrided) {
+      constexpr int NL = NU * KQ;
       const char* base = FAST ? (const char*)op.p + (size_t)k0 * jstride : (const char*)op.p;
       const uint32_t kbyte = FAST ? 0u : (uint32_t)k0 * jstride;
-      okbits = 0u;
+      if (piece == 0) okbits = 0u;
 #pragma unroll
       for (int i = 0; i < NU; ++i) {
 #pragma unroll
         for (int j = 0; j < KQ; ++j) {
+          if (((i * KQ + j) * np) / NL != piece) continue;
           uint32_t off = boff[i] + (uint32_t)j * jstride;
           if constexpr (!FAST) {
             const bool ok = ((rowok >> i) & 1u) && (k0 + kpos + j < K);
@@ -132,6 +136,7 @@ struct tile_stage {
       okbits = kv ? rowok : 0u;
 #pragma unroll
       for (int i = 0; i < NCH; ++i) {
+        if ((i * np) / NCH != piece) continue;
         uint32_t off = boff[i];
         if constexpr (!FAST) off = ((okbits >> i) & 1u) ? off + (uint32_t)kb8 : 0u;
         if constexpr (KIND == PQ_SRC_BITS8) raw[i] = *reinterpret_cast<const uint16_t*>(base + off);
@@ -333,6 +338,75 @@ __device__ __forceinline__ void epi_vec8(const pq_epilogue& e, epi_state& st, in
   }
 }
 
+#ifdef PQ_VAR_TRACE
+__device__ unsigned long long pq_trace[8 * 16 * 8];
+#define PQ_TS(ph) if (trace_on && kt < 16) { const unsigned long long ts_ = __builtin_amdgcn_s_memtime(); if (lane == 0) pq_trace[(wave * 16 + kt) * 8 + ph] = ts_; }
+#else
+#define PQ_TS(ph)
+#endif
+// ---------------------------------------------------------------------------------------------
+// Streaming main loop (DTL instantiations): operands go from global memory straight into LDS
+// (global_load_lds_dwordx4, no staging registers, no ds_write), and the contraction step is a fixed
+// instruction order written as volatile asm statements: the fragment reads of MFMA group g+1 are issued
+// before the MFMAs of group g, and the single barrier of a step sits before its last MFMA group, so the
+// loads of the step after next and the first fragment reads of the next stage are issued under that
+// group's MFMAs.  The compiler allocates the registers; the order of the statements is kept as written.
+//   * contraction-contiguous operands (KC16, KC8): LDS tile [row][128 B], 16-byte chunks swizzled as
+//     lds_off<128>; the swizzle is applied on the global side (lane l of a load instruction lands at LDS
+//     byte 16 l of its 1 KB block, so it fetches the chunk that belongs there).
+//   * contraction-strided operands (KS16): the tile stays as it is in memory, [64 contraction rows][512 B],
+//     chunk c of row t stored at chunk c ^ 4 (t & 3); MFMA operands come from ds_read_b64_tr_b16, which
+//     hands lane i of a 16-lane group element (i % 4) of the 8-byte row addressed by lane 4 e + i / 4,
+//     e = 0..3: with lane j addressing (t = j / 4, 4 columns at 4 (j % 4)) lane i receives four consecutive
+//     t of column i.
+//   * packed-bit B operands keep the register path (load, expand, ds_write) one stage ahead.
+// A wait on asm-issued reads names the registers it releases ("+v"), which orders their uses after it.
+// ---------------------------------------------------------------------------------------------
+typedef int pq_i32x2 __attribute__((ext_vector_type(2)));
+#define PQ_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define PQ_DS_READ128(dst, addr, off) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off) : "memory")
+#define PQ_DS_READ_TR(dst, addr, off) asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off) : "memory")
+#define PQ_MFMA_BF16(acc, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b))
+#define PQ_MFMA_I8(acc, a, b) asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b))
+
+// One fragment set of a 128x64 wavefront tile: four A and two B operands of 16 bytes per lane.  Operands
+// read with ds_read_b128 are whole (q), transposing reads deliver 8-byte halves (h) that the register
+// allocator places next to each other.
+template <bool ATR, bool BTR>
+struct pq_frag_set {
+  i32x4_t qa[ATR ? 1 : 4], qb[BTR ? 1 : 2];
+  pq_i32x2 ha[ATR ? 8 : 1], hb[BTR ? 4 : 1];
+  static constexpr int NREADS = (ATR ? 8 : 4) + (BTR ? 4 : 2);
+  __device__ __forceinline__ i32x4_t A(int i) const {
+    if constexpr (ATR) return i32x4_t{ha[2 * i][0], ha[2 * i][1], ha[2 * i + 1][0], ha[2 * i + 1][1]};
+    else return qa[i];
+  }
+  __device__ __forceinline__ i32x4_t B(int j) const {
+    if constexpr (BTR) return i32x4_t{hb[2 * j][0], hb[2 * j][1], hb[2 * j + 1][0], hb[2 * j + 1][1]};
+    else return qb[j];
+  }
+  // waits until at most N_OUT LDS operations are outstanding; naming the registers orders their uses after it
+  template <int N_OUT>
+  __device__ __forceinline__ void wait() {
+    if constexpr (!ATR && !BTR)
+      asm volatile("s_waitcnt lgkmcnt(%6)" : "+v"(qa[0]), "+v"(qa[1]), "+v"(qa[2]), "+v"(qa[3]), "+v"(qb[0]), "+v"(qb[1]) : "n"(N_OUT));
+    else if constexpr (ATR && BTR)
+      asm volatile("s_waitcnt lgkmcnt(%12)"
+                   : "+v"(ha[0]), "+v"(ha[1]), "+v"(ha[2]), "+v"(ha[3]), "+v"(ha[4]), "+v"(ha[5]), "+v"(ha[6]), "+v"(ha[7]),
+                     "+v"(hb[0]), "+v"(hb[1]), "+v"(hb[2]), "+v"(hb[3])
+                   : "n"(N_OUT));
+    else if constexpr (ATR && !BTR)
+      asm volatile("s_waitcnt lgkmcnt(%10)"
+                   : "+v"(ha[0]), "+v"(ha[1]), "+v"(ha[2]), "+v"(ha[3]), "+v"(ha[4]), "+v"(ha[5]), "+v"(ha[6]), "+v"(ha[7]),
+                     "+v"(qb[0]), "+v"(qb[1])
+                   : "n"(N_OUT));
+    else
+      asm volatile("s_waitcnt lgkmcnt(%8)"
+                   : "+v"(qa[0]), "+v"(qa[1]), "+v"(qa[2]), "+v"(qa[3]), "+v"(hb[0]), "+v"(hb[1]), "+v"(hb[2]), "+v"(hb[3])
+                   : "n"(N_OUT));
+  }
+};
+
 // ---------------------------------------------------------------------------------------------
 // MFMA engine
 // ---------------------------------------------------------------------------------------------
@@ -340,7 +414,7 @@ __device__ __forceinline__ void epi_vec8(const pq_epilogue& e, epi_state& st, in
 // blockIdx.y.  LDS holds two stages of both operand tiles; per 128-byte step there is a single
 // barrier: after it, the registers prefetched during the previous step are written to the idle
 // stage, the loads of the step after next are issued, and the MFMAs run on the ready stage.
-template <int BM, int BN, int WGM, int WGN, int KB, bool FAST, bool INT8, int AK, int BKIND, int AK2 = -1, int BK2 = -1>
+template <int BM, int BN, int WGM, int WGN, int KB, bool FAST, bool INT8, int AK, int BKIND, int AK2 = -1, int BK2 = -1, bool DTL = false>
 __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N, int K, pq_operand A,
                                                                      pq_operand B, pq_epilogue epi,
                                                                      int nbn, int total_tiles, int kchunk,
@@ -358,12 +432,23 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
 
   // XCD-aware tile order: consecutive workgroups go to different XCDs, so give each XCD a
   // contiguous range of tiles (its L2 then sees the same A row-panel for a run of tiles).
-  int pid = blockIdx.x;
-  if ((total_tiles & 7) == 0) pid = (pid & 7) * (total_tiles >> 3) + (pid >> 3);
+  // Work items are ordered (contraction split, tile row, tile column) and XCD c takes the c-th eighth of
+  // that order: with a split contraction an XCD then works on one split and a band of tile rows, so the
+  // operand panels it streams are shared by its workgroups instead of being fetched by every XCD.
+  int pid = blockIdx.x, split = blockIdx.y;
+  {
+    const int nb = total_tiles * (int)gridDim.y;
+    if ((nb & 7) == 0) {
+      const int lin = blockIdx.x + total_tiles * blockIdx.y;
+      const int w = (lin & 7) * (nb >> 3) + (lin >> 3);
+      split = w / total_tiles;
+      pid = w - split * total_tiles;
+    }
+  }
   const int bm = pid / nbn, bn = pid % nbn;
   int m0 = bm * BM;
   const int n0 = bn * BN;
-  int kb = blockIdx.y * kchunk;
+  int kb = split * kchunk;
   int ke = min(K, kb + kchunk);
   if (grp.mode == 1) {          // rows of group z: [offsets[z], offsets[z+1])
     const int z = blockIdx.z;
@@ -419,61 +504,248 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
     for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const uint4*>(stage + b_rb[j] + ((ch ^ b_fx[j]) << 4));
   };
 
-  if (nkt > 0) {
-    sa.load(A, kb, ke);
-    sb.load(B, kb, ke);
-    sa.store(smem, tid);
-    sb.store(smem + BM * KB, tid);
-    const int k1 = nkt > 1 ? 1 : 0;
-    sa.load(A, kb + k1 * EPB, ke);
-    sb.load(B, kb + k1 * EPB, ke);
-  }
-  __syncthreads();
-  if (nkt > 0) read_frags(smem, 0, af[0], bf[0]);
+  if constexpr (DTL) {
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the kernel's signature (LDS address-space casts are device-only)
+    static_assert(BM == 256 && BN == 256 && WGM == 2 && WGN == 4 && KB == 128, "streaming loop: 256x256 tile on 8 wavefronts");
+    constexpr bool ATR = (AK == PQ_SRC_KS16), BTR = (BKIND == PQ_SRC_KS16);
+    constexpr bool BREG = (BKIND == PQ_SRC_BITS8 || BKIND == PQ_SRC_BITS16);   // B through registers (bit expansion)
+    constexpr int IPW = BREG ? 4 : 8;                 // direct-load instructions per wavefront and stage
+    constexpr int AES = (AK == PQ_SRC_KC8) ? 1 : 2, BES = (BKIND == PQ_SRC_KC8) ? 1 : 2;
+    const int wv = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t lds0 = (uint32_t)(size_t)smem;
 
-  // Steady state, one barrier per stage and no branches in the body: the registers hold tile kt+1,
-  // which goes to the idle LDS stage while the loads of tile kt+2 are issued and the MFMAs run on
-  // the ready stage; the operand fragments of the next MFMA group are read one group ahead.  On the
-  // last steps the tile index is clamped, so the same tile is (harmlessly) staged again.
+    // ---- direct loads: instruction block qi of an operand is 1 KB of its LDS tile --------------------
+    const bool opB = !BREG && wv >= 4;                // wave-uniform
+    const int q0 = BREG ? wv * 4 : (wv & 3) * 8;
+    const char* src[IPW];
+    size_t adv;                                       // source bytes per contraction step
+    {
+      auto kc_src = [&](const pq_operand& op, int row0, int rows, int es, int qi) {
+        const int r = qi * 8 + (lane >> 3), pc = lane & 7;
+        const int c = pc ^ ((r ^ (r >> 3)) & 7);      // logical chunk stored at physical chunk pc of row r
+        const int grow = min(row0 + r, rows - 1);      // rows past the end re-read the last row (never stored)
+        return (const char*)op.p + ((size_t)grow * op.ld + kb) * es + c * 16;
+      };
+      auto ks_src = [&](const pq_operand& op, int col0, int cols, int qi) {
+        const int t = qi * 2 + (lane >> 5), pc = lane & 31;
+        const int c = pc ^ (4 * (t & 3));
+        int col = col0 + c * 8;
+        if (col + 8 > cols) col = col0;                // columns past the end: any valid chunk
+        return (const char*)op.p + ((size_t)(kb + t) * op.ld + col) * 2;
+      };
+#pragma unroll
+      for (int i = 0; i < IPW; ++i) {
+        if (opB) {
+          if constexpr (BTR) src[i] = ks_src(B, n0, N, q0 + i);
+          else src[i] = kc_src(B, n0, N, BES, q0 + i);
+        } else {
+          if constexpr (ATR) src[i] = ks_src(A, m0, M, q0 + i);
+          else src[i] = kc_src(A, m0, M, AES, q0 + i);
+        }
+      }
+      if (opB) adv = BTR ? (size_t)64 * B.ld * 2 : (size_t)128;
+      else adv = ATR ? (size_t)64 * A.ld * 2 : (size_t)128;
+    }
+    auto issue = [&](int kt, int stage) {
+      unsigned char* base = smem + stage * STAGE + (opB ? BM * KB : 0) + q0 * 1024;
+#pragma unroll
+      for (int i = 0; i < IPW; ++i)
+        __builtin_amdgcn_global_load_lds(src[i] + (size_t)kt * adv, PQ_LDS_PTR(base + i * 1024), 16, 0, 0);
+    };
+
+    // ---- fragment read addresses (stage 0) ------------------------------------------------------------
+    const int h = lane >> 5;
+    uint32_t adA[ATR ? 4 : 8], adB[BTR ? 2 : 8];
+    if constexpr (ATR) {
+      const int tl = 8 * h + ((lane & 15) >> 2), cl = 16 * ((lane >> 4) & 1) + 4 * (lane & 3), sw = 4 * ((lane & 15) >> 2);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int col = wm0 + 32 * i + cl;
+        adA[i] = lds0 + tl * 512 + (((col >> 3) ^ sw) << 4) + (col & 7) * 2;
+      }
+    } else {
+#pragma unroll
+      for (int pp = 0; pp < 2; ++pp)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) adA[pp * 4 + ks] = lds0 + a_rb[pp] + (((2 * ks + h) ^ a_fx[pp]) << 4);
+    }
+    if constexpr (BTR) {
+      const int tl = 8 * h + ((lane & 15) >> 2), cl = 16 * ((lane >> 4) & 1) + 4 * (lane & 3), sw = 4 * ((lane & 15) >> 2);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = wn0 + 32 * j + cl;
+        adB[j] = lds0 + BM * KB + tl * 512 + (((col >> 3) ^ sw) << 4) + (col & 7) * 2;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) adB[j * 4 + ks] = lds0 + b_rb[j] + (((2 * ks + h) ^ b_fx[j]) << 4);
+    }
+    using fset = pq_frag_set<ATR, BTR>;
+    fset F0, F1;
+    auto read_set = [&](fset& F, auto ks_c, uint32_t so) {
+      constexpr int ks = decltype(ks_c)::value;
+      if constexpr (ATR) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint32_t pa = adA[i] + so;
+          PQ_DS_READ_TR(F.ha[2 * i], pa, ks * 8192);
+          PQ_DS_READ_TR(F.ha[2 * i + 1], pa, ks * 8192 + 2048);
+        }
+      } else {
+        const uint32_t p0 = adA[ks] + so, p1 = adA[4 + ks] + so;
+        PQ_DS_READ128(F.qa[0], p0, 0);
+        PQ_DS_READ128(F.qa[1], p1, 0);
+        PQ_DS_READ128(F.qa[2], p0, 8192);
+        PQ_DS_READ128(F.qa[3], p1, 8192);
+      }
+      if constexpr (BTR) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const uint32_t pb = adB[j] + so;
+          PQ_DS_READ_TR(F.hb[2 * j], pb, ks * 8192);
+          PQ_DS_READ_TR(F.hb[2 * j + 1], pb, ks * 8192 + 2048);
+        }
+      } else {
+        const uint32_t pb0 = adB[ks] + so, pb1 = adB[4 + ks] + so;
+        PQ_DS_READ128(F.qb[0], pb0, 0);
+        PQ_DS_READ128(F.qb[1], pb1, 0);
+      }
+    };
+    auto mfma_set = [&](const fset& F) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const i32x4_t fa = F.A(i);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const i32x4_t fb = F.B(j);
+          if constexpr (INT8) PQ_MFMA_I8(acc[i][j], fa, fb);
+          else PQ_MFMA_BF16(acc[i][j], fa, fb);
+        }
+      }
+    };
+    using c0 = std::integral_constant<int, 0>;
+    using c1 = std::integral_constant<int, 1>;
+    using c2 = std::integral_constant<int, 2>;
+    using c3 = std::integral_constant<int, 3>;
+    constexpr int NR = fset::NREADS;
+    constexpr int NLB = BREG ? tile_stage<BKIND, BN, NT, KB, FAST>::NCH : 0;   // register-path loads issued per step
+
+    if (nkt > 0) {
+      issue(0, 0);
+      if constexpr (BREG) {
+        sb.load(B, kb, ke);
+        sb.store(smem + BM * KB, tid);
+        sb.load(B, kb + (nkt > 1 ? 1 : 0) * EPB, ke);
+      }
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NLB) : "memory");
+      asm volatile("s_barrier" ::: "memory");
+      if (nkt > 1) issue(1, 1);
+      read_set(F0, c0{}, 0u);
+    }
+    for (int kt = 0; kt < nkt; ++kt) {
+      const uint32_t so = (kt & 1) ? (uint32_t)STAGE : 0u, sn = (kt & 1) ? 0u : (uint32_t)STAGE;
+      if constexpr (BREG) {                           // tile kt+1 of B goes to the idle stage, tile kt+2 into registers
+        sb.store(smem + sn + BM * KB, tid);
+        sb.load(B, kb + min(kt + 2, nkt - 1) * EPB, ke);
+      }
+      read_set(F1, c1{}, so);
+      F0.template wait<NR>();
+      mfma_set(F0);
+      read_set(F0, c2{}, so);
+      F1.template wait<NR>();
+      mfma_set(F1);
+      read_set(F1, c3{}, so);
+      F0.template wait<NR>();
+      mfma_set(F0);
+      F1.template wait<0>();                          // every LDS access of this step is complete
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NLB) : "memory");   // the direct loads of the next stage have landed
+      asm volatile("s_barrier" ::: "memory");
+      if (kt + 2 < nkt) issue(kt + 2, kt & 1);
+      if (kt + 1 < nkt) read_set(F0, c0{}, sn);
+      mfma_set(F1);
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#endif
+  } else {
+  if (nkt > 0) {
+      sa.load(A, kb, ke);
+      sb.load(B, kb, ke);
+      sa.store(smem, tid);
+      sb.store(smem + BM * KB, tid);
+      const int k1 = nkt > 1 ? 1 : 0;
+      sa.load(A, kb + k1 * EPB, ke);
+      sb.load(B, kb + k1 * EPB, ke);
+    }
+    __syncthreads();
+    if (nkt > 0) read_frags(smem, 0, af[0], bf[0]);
+  
+    // Steady state, one barrier per stage and no branches in the body: the registers hold tile kt+1,
+    // which goes to the idle LDS stage while the loads of tile kt+2 are issued and the MFMAs run on
+    // the ready stage; the operand fragments of the next MFMA group are read one group ahead.  On the
+    // last steps the tile index is clamped, so the same tile is (harmlessly) staged again.
 #ifndef PQ_VAR_SCHED
 #define PQ_VAR_SCHED 0
 #endif
-  for (int kt = 0; kt < nkt; ++kt) {
-    unsigned char* cur = smem + (kt & 1) * STAGE;
-    unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
-    sa.store(nxt, tid);
-    sb.store(nxt + BM * KB, tid);
-    const int k2 = min(kt + 2, nkt - 1);
-    sa.load(A, kb + k2 * EPB, ke);
-    sb.load(B, kb + k2 * EPB, ke);
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      if (ks + 1 < NKS) read_frags(cur, ks + 1, af[(ks + 1) & 1], bf[(ks + 1) & 1]);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          if constexpr (INT8)
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4_t, af[ks & 1][i]),
-                                                              __builtin_bit_cast(i32x4_t, bf[ks & 1][j]), acc[i][j], 0, 0, 0);
-          else
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[ks & 1][i]),
-                                                                __builtin_bit_cast(bf16x8_t, bf[ks & 1][j]), acc[i][j], 0, 0, 0);
-        }
-    }
-    __syncthreads();  // stage nxt is complete and nobody still reads stage cur
-    read_frags(nxt, 0, af[0], bf[0]);
-#if PQ_VAR_SCHED == 1
-    // one MFMA, then a few instructions of the other kinds in its shadow
-#pragma unroll
-    for (int q = 0; q < TM * TN * NKS; ++q) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
-      __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);   // VALU
-      __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // DS write
-      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read
-    }
+#ifndef PQ_VAR_SPREAD
+#define PQ_VAR_SPREAD 0
 #endif
+#ifdef PQ_VAR_TRACE
+    const bool trace_on = blockIdx.x == 8 && blockIdx.y == 0 && blockIdx.z == 0 && NT == 512 && nkt >= 16;
+#endif
+    for (int kt = 0; kt < nkt; ++kt) {
+      unsigned char* cur = smem + (kt & 1) * STAGE;
+      unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
+      PQ_TS(0)
+      sa.store(nxt, tid);
+      PQ_TS(4)
+      sb.store(nxt + BM * KB, tid);
+      PQ_TS(5)
+      const int k2 = min(kt + 2, nkt - 1);
+#if !PQ_VAR_SPREAD
+      sa.load(A, kb + k2 * EPB, ke);
+      sb.load(B, kb + k2 * EPB, ke);
+#endif
+      PQ_TS(1)
+  #pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        if (ks + 1 < NKS) read_frags(cur, ks + 1, af[(ks + 1) & 1], bf[(ks + 1) & 1]);
+#if PQ_VAR_SPREAD
+        // a quarter of the step's global loads per MFMA group: a stalled load issue then costs this
+        // wavefront one group while the other wavefront of the SIMD keeps the matrix pipe busy
+        sa.load(A, kb + k2 * EPB, ke, ks, NKS);
+        sb.load(B, kb + k2 * EPB, ke, ks, NKS);
+        __builtin_amdgcn_sched_barrier(0);
+#endif
+  #pragma unroll
+        for (int i = 0; i < TM; ++i)
+  #pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            if constexpr (INT8)
+              acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4_t, af[ks & 1][i]),
+                                                                __builtin_bit_cast(i32x4_t, bf[ks & 1][j]), acc[i][j], 0, 0, 0);
+            else
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[ks & 1][i]),
+                                                                  __builtin_bit_cast(bf16x8_t, bf[ks & 1][j]), acc[i][j], 0, 0, 0);
+          }
+      }
+      PQ_TS(2)
+      __syncthreads();  // stage nxt is complete and nobody still reads stage cur
+      PQ_TS(3)
+      read_frags(nxt, 0, af[0], bf[0]);
+#if PQ_VAR_SCHED == 1
+      // one MFMA, then a few instructions of the other kinds in its shadow
+  #pragma unroll
+      for (int q = 0; q < TM * TN * NKS; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);   // VALU
+        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // DS write
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read
+      }
+#endif
+    }
   }
   __syncthreads();  // all MFMA operand reads are done: LDS is reused below
 
@@ -527,7 +799,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
   // raw fp32 accumulators go to this split's slab instead; splitk_reduce_kernel finishes the job.
   epi_state st;
   epi_begin(epi, st);
-  float* slab = splitk_part ? splitk_part + (size_t)blockIdx.y * M * N : nullptr;
+  float* slab = splitk_part ? splitk_part + (size_t)split * M * N : nullptr;
   uint32_t* stg = reinterpret_cast<uint32_t*>(smem) + wave * (32 * 36);
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -632,18 +904,22 @@ __global__ __launch_bounds__(256) void ref_gemm_kernel(int M, int N, int K, pq_o
   epi_end<256>(epi, st, red, blockIdx.y * gridDim.x + blockIdx.x);
 }
 
-template <int BM, int BN, int WGM, int WGN, int KB, bool FAST, bool INT8, int AK, int BKIND, int AK2 = -1, int BK2 = -1>
+template <int BM, int BN, int WGM, int WGN, int KB, bool FAST, bool INT8, int AK, int BKIND, int AK2 = -1, int BK2 = -1, bool DTL = false>
 int launch_mfma(const pq_gemm_plan& pl, int M, int N, int K, const pq_operand& A, const pq_operand& B,
                 const pq_epilogue& epi, hipStream_t s, float* part, const pq_gemm_group& grp, const pq_phase2& ph2) {
   const int Mrows = grp.mode == 1 ? grp.max_rows : M;
   const int nbm = (Mrows + BM - 1) / BM, nbn = (N + BN - 1) / BN;
   const int tiles = nbm * nbn;
   dim3 grid(tiles, pl.splits, grp.mode ? grp.n_groups : 1), block(WGM * WGN * 64);
-  mfma_gemm_kernel<BM, BN, WGM, WGN, KB, FAST, INT8, AK, BKIND, AK2, BK2><<<grid, block, 0, s>>>(
+  mfma_gemm_kernel<BM, BN, WGM, WGN, KB, FAST, INT8, AK, BKIND, AK2, BK2, DTL><<<grid, block, 0, s>>>(
       M, N, K, A, B, epi, nbn, tiles, pl.kchunk, pl.splits > 1 ? part : nullptr, grp, ph2);
   PQ_CHECK_LAUNCH("mfma_gemm_kernel");
   return PQ_OK;
 }
+
+#ifndef PQ_VAR_DTL
+#define PQ_VAR_DTL 1
+#endif
 
 template <bool INT8, int AK, int BKIND, int AK2 = -1, int BK2 = -1>
 int launch_mfma_cfg(const pq_gemm_plan& pl, int M, int N, int K, const pq_operand& A, const pq_operand& B,
@@ -653,6 +929,21 @@ int launch_mfma_cfg(const pq_gemm_plan& pl, int M, int N, int K, const pq_operan
     // whole tiles everywhere: the instantiation without validity masks
     const bool whole = grp.mode == 0 && M % 256 == 0 && N % 256 == 0 && K % EPB == 0 && pl.kchunk % EPB == 0 &&
                        ph2.K2 % 64 == 0;
+    // Streaming main loop: plain tiles (no expert segments), whole contraction steps in every split, rows of
+    // both operands 16-byte aligned.  Ragged M or N are fine there (edge rows are clamped, never stored).
+    constexpr bool kinds_ok = (AK == PQ_SRC_KC16 || AK == PQ_SRC_KS16 || AK == PQ_SRC_KC8) &&
+                              (BKIND == PQ_SRC_KC16 || BKIND == PQ_SRC_KS16 || BKIND == PQ_SRC_BITS8 || BKIND == PQ_SRC_BITS16);
+    if constexpr (kinds_ok) {
+      const long aes = AK == PQ_SRC_KC8 ? 1 : 2;
+      const bool a_ok = (A.ld * aes) % 16 == 0 && ((uintptr_t)A.p % 16) == 0 && (AK != PQ_SRC_KS16 || M % 8 == 0);
+      const bool b_ok = (BKIND == PQ_SRC_BITS8 || BKIND == PQ_SRC_BITS16) ||
+                        ((B.ld * 2) % 16 == 0 && ((uintptr_t)B.p % 16) == 0 && (BKIND != PQ_SRC_KS16 || N % 8 == 0));
+      const bool stream = PQ_VAR_DTL && grp.mode == 0 && K % EPB == 0 && pl.kchunk % EPB == 0 && a_ok && b_ok && M >= 1 && N >= 1;
+      if (stream) {
+        if (whole) return launch_mfma<256, 256, 2, 4, 128, true, INT8, AK, BKIND, AK2, BK2, true>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+        return launch_mfma<256, 256, 2, 4, 128, false, INT8, AK, BKIND, AK2, BK2, true>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+      }
+    }
     if (whole) return launch_mfma<256, 256, 2, 4, 128, true, INT8, AK, BKIND, AK2, BK2>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
     return launch_mfma<256, 256, 2, 4, 128, false, INT8, AK, BKIND, AK2, BK2>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
   }
@@ -690,6 +981,12 @@ pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8) {
   pl.ws_bytes = pl.splits > 1 ? (size_t)pl.splits * M * N * sizeof(float) : 0;
   return pl;
 }
+
+#ifdef PQ_VAR_TRACE
+extern "C" int pq_trace_read(unsigned long long* out) {
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(pq_trace), sizeof(unsigned long long) * 8 * 16 * 8);
+}
+#endif
 
 int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const pq_operand& B,
                    const pq_epilogue& epi, hipStream_t s, int prof_label, void* splitk_ws,

@@ -267,23 +267,54 @@ __global__ __launch_bounds__(256) void router_bwd_kernel(const float* __restrict
   dlogit[i] = acc;
 }
 
-// dWr partials: part[tc][e][c] = sum_{t in chunk tc} dlogit[t,e] * X[t,c]   (chunks of 256 tokens)
+// dWr partials: part[tc][e][c] = sum_{t in chunk tc} dlogit[t,e] * X[t,c]   (chunks of 256 tokens).
+// A workgroup covers 256 columns of one chunk: thread = (token subgroup sg, column group cg); it walks the
+// 32 tokens t0 + sg, t0 + sg + 8, ... with 16-byte loads of 8 columns, then the 8 subgroups are summed in LDS
+// in a fixed order.
 __global__ __launch_bounds__(256) void dwr_partial_kernel(const float* __restrict__ dlogit, const uint16_t* __restrict__ X, int T,
                                                           int d, int E, float* __restrict__ part) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
+  __shared__ float red[8][4][8][32];                 // [subgroup][expert % 4][column % 8][column group]
+  const int tid = threadIdx.x, cg = tid & 31, sg = tid >> 5;
+  const int c0 = blockIdx.x * 256 + cg * 8;
   const int t0 = blockIdx.y * 256, t1 = min(T, t0 + 256);
-  if (c >= d) return;
+  const bool okc = c0 < d;                            // d % 8 == 0
   for (int e0 = 0; e0 < E; e0 += 8) {
-    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int t = t0; t < t1; ++t) {
-      const float x = bf16_to_f32(X[(size_t)t * d + c]);
-#pragma unroll
-      for (int u = 0; u < 8; ++u)
-        if (e0 + u < E) acc[u] += dlogit[(size_t)t * E + e0 + u] * x;
-    }
+    float acc[8][8];
 #pragma unroll
     for (int u = 0; u < 8; ++u)
-      if (e0 + u < E) part[((size_t)blockIdx.y * E + e0 + u) * d + c] = acc[u];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[u][j] = 0.0f;
+    if (okc) {
+#pragma unroll 4
+      for (int t = t0 + sg; t < t1; t += 8) {
+        float x[8];
+        unpack8(*reinterpret_cast<const uint4*>(X + (size_t)t * d + c0), x);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const float g = (e0 + u < E) ? dlogit[(size_t)t * E + e0 + u] : 0.0f;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) acc[u][j] += g * x[j];
+        }
+      }
+    }
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {           // four experts per round through LDS
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) red[sg][u][j][cg] = acc[4 * half + u][j];
+      __syncthreads();
+      for (int o = tid; o < 4 * 256; o += 256) {
+        const int u = o >> 8, c = o & 255, e = e0 + 4 * half + u;
+        if (e < E && blockIdx.x * 256 + c < d) {
+          float v = 0.0f;
+#pragma unroll
+          for (int q = 0; q < 8; ++q) v += red[q][u][c & 7][c >> 3];
+          part[((size_t)blockIdx.y * E + e) * d + blockIdx.x * 256 + c] = v;
+        }
+      }
+      __syncthreads();
+    }
   }
 }
 __global__ __launch_bounds__(256) void dwr_final_kernel(const float* __restrict__ part, int nchunks, int n, float* __restrict__ dWr) {
