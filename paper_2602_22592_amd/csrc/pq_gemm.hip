@@ -151,7 +151,8 @@ struct tile_stage {
     else return mask4(t, (okbits >> bit) & 1u);
   }
 
-  __device__ __forceinline__ void store(unsigned char* lds, int tid) const {
+  // np > 1: only the chunks of piece `piece` (contraction-contiguous and bit kinds)
+  __device__ __forceinline__ void store(unsigned char* lds, int tid, int piece = 0, int np = 1) const {
     if constexpr (kStrided) {
 #pragma unroll
       for (int i = 0; i < NU; ++i) {
@@ -181,6 +182,7 @@ struct tile_stage {
     } else {
 #pragma unroll
       for (int i = 0; i < NCH; ++i) {
+        if ((i * np) / NCH != piece) continue;
         const int c = tid + i * NT;
         if (c < ROWS * CPR) {
           uint4 out;
@@ -338,12 +340,6 @@ __device__ __forceinline__ void epi_vec8(const pq_epilogue& e, epi_state& st, in
   }
 }
 
-#ifdef PQ_VAR_TRACE
-__device__ unsigned long long pq_trace[8 * 16 * 8];
-#define PQ_TS(ph) if (trace_on && kt < 16) { const unsigned long long ts_ = __builtin_amdgcn_s_memtime(); if (lane == 0) pq_trace[(wave * 16 + kt) * 8 + ph] = ts_; }
-#else
-#define PQ_TS(ph)
-#endif
 // ---------------------------------------------------------------------------------------------
 // Streaming main loop (DTL instantiations): operands go from global memory straight into LDS
 // (global_load_lds_dwordx4, no staging registers, no ds_write), and the contraction step is a fixed
@@ -646,19 +642,22 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
     }
     for (int kt = 0; kt < nkt; ++kt) {
       const uint32_t so = (kt & 1) ? (uint32_t)STAGE : 0u, sn = (kt & 1) ? 0u : (uint32_t)STAGE;
-      if constexpr (BREG) {                           // tile kt+1 of B goes to the idle stage, tile kt+2 into registers
-        sb.store(smem + sn + BM * KB, tid);
-        sb.load(B, kb + min(kt + 2, nkt - 1) * EPB, ke);
-      }
+      // Register path of B (packed bits): tile kt+1 is expanded into the idle stage in two halves placed
+      // behind the first two MFMA groups, tile kt+2 is requested behind the third, so that this work runs
+      // under MFMAs instead of in a phase of its own.
+
       read_set(F1, c1{}, so);
       F0.template wait<NR>();
       mfma_set(F0);
+      if constexpr (BREG) sb.store(smem + sn + BM * KB, tid, 0, 2);
       read_set(F0, c2{}, so);
       F1.template wait<NR>();
       mfma_set(F1);
+      if constexpr (BREG) sb.store(smem + sn + BM * KB, tid, 1, 2);
       read_set(F1, c3{}, so);
       F0.template wait<NR>();
       mfma_set(F0);
+      if constexpr (BREG) sb.load(B, kb + min(kt + 2, nkt - 1) * EPB, ke);
       F1.template wait<0>();                          // every LDS access of this step is complete
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NLB) : "memory");   // the direct loads of the next stage have landed
       asm volatile("s_barrier" ::: "memory");
@@ -680,47 +679,25 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
     }
     __syncthreads();
     if (nkt > 0) read_frags(smem, 0, af[0], bf[0]);
-  
+
     // Steady state, one barrier per stage and no branches in the body: the registers hold tile kt+1,
     // which goes to the idle LDS stage while the loads of tile kt+2 are issued and the MFMAs run on
     // the ready stage; the operand fragments of the next MFMA group are read one group ahead.  On the
     // last steps the tile index is clamped, so the same tile is (harmlessly) staged again.
-#ifndef PQ_VAR_SCHED
-#define PQ_VAR_SCHED 0
-#endif
-#ifndef PQ_VAR_SPREAD
-#define PQ_VAR_SPREAD 0
-#endif
-#ifdef PQ_VAR_TRACE
-    const bool trace_on = blockIdx.x == 8 && blockIdx.y == 0 && blockIdx.z == 0 && NT == 512 && nkt >= 16;
-#endif
     for (int kt = 0; kt < nkt; ++kt) {
       unsigned char* cur = smem + (kt & 1) * STAGE;
       unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
-      PQ_TS(0)
       sa.store(nxt, tid);
-      PQ_TS(4)
       sb.store(nxt + BM * KB, tid);
-      PQ_TS(5)
       const int k2 = min(kt + 2, nkt - 1);
-#if !PQ_VAR_SPREAD
       sa.load(A, kb + k2 * EPB, ke);
       sb.load(B, kb + k2 * EPB, ke);
-#endif
-      PQ_TS(1)
-  #pragma unroll
+#pragma unroll
       for (int ks = 0; ks < NKS; ++ks) {
         if (ks + 1 < NKS) read_frags(cur, ks + 1, af[(ks + 1) & 1], bf[(ks + 1) & 1]);
-#if PQ_VAR_SPREAD
-        // a quarter of the step's global loads per MFMA group: a stalled load issue then costs this
-        // wavefront one group while the other wavefront of the SIMD keeps the matrix pipe busy
-        sa.load(A, kb + k2 * EPB, ke, ks, NKS);
-        sb.load(B, kb + k2 * EPB, ke, ks, NKS);
-        __builtin_amdgcn_sched_barrier(0);
-#endif
-  #pragma unroll
+#pragma unroll
         for (int i = 0; i < TM; ++i)
-  #pragma unroll
+#pragma unroll
           for (int j = 0; j < TN; ++j) {
             if constexpr (INT8)
               acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4_t, af[ks & 1][i]),
@@ -730,21 +707,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
                                                                   __builtin_bit_cast(bf16x8_t, bf[ks & 1][j]), acc[i][j], 0, 0, 0);
           }
       }
-      PQ_TS(2)
       __syncthreads();  // stage nxt is complete and nobody still reads stage cur
-      PQ_TS(3)
       read_frags(nxt, 0, af[0], bf[0]);
-#if PQ_VAR_SCHED == 1
-      // one MFMA, then a few instructions of the other kinds in its shadow
-  #pragma unroll
-      for (int q = 0; q < TM * TN * NKS; ++q) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
-        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);   // VALU
-        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // DS write
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read
-      }
-#endif
     }
   }
   __syncthreads();  // all MFMA operand reads are done: LDS is reused below
@@ -917,10 +881,6 @@ int launch_mfma(const pq_gemm_plan& pl, int M, int N, int K, const pq_operand& A
   return PQ_OK;
 }
 
-#ifndef PQ_VAR_DTL
-#define PQ_VAR_DTL 1
-#endif
-
 template <bool INT8, int AK, int BKIND, int AK2 = -1, int BK2 = -1>
 int launch_mfma_cfg(const pq_gemm_plan& pl, int M, int N, int K, const pq_operand& A, const pq_operand& B,
                     const pq_epilogue& epi, hipStream_t s, float* part, const pq_gemm_group& grp, const pq_phase2& ph2) {
@@ -938,7 +898,7 @@ int launch_mfma_cfg(const pq_gemm_plan& pl, int M, int N, int K, const pq_operan
       const bool a_ok = (A.ld * aes) % 16 == 0 && ((uintptr_t)A.p % 16) == 0 && (AK != PQ_SRC_KS16 || M % 8 == 0);
       const bool b_ok = (BKIND == PQ_SRC_BITS8 || BKIND == PQ_SRC_BITS16) ||
                         ((B.ld * 2) % 16 == 0 && ((uintptr_t)B.p % 16) == 0 && (BKIND != PQ_SRC_KS16 || N % 8 == 0));
-      const bool stream = PQ_VAR_DTL && grp.mode == 0 && K % EPB == 0 && pl.kchunk % EPB == 0 && a_ok && b_ok && M >= 1 && N >= 1;
+      const bool stream = grp.mode == 0 && K % EPB == 0 && pl.kchunk % EPB == 0 && a_ok && b_ok && M >= 1 && N >= 1;
       if (stream) {
         if (whole) return launch_mfma<256, 256, 2, 4, 128, true, INT8, AK, BKIND, AK2, BK2, true>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
         return launch_mfma<256, 256, 2, 4, 128, false, INT8, AK, BKIND, AK2, BK2, true>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
@@ -982,11 +942,6 @@ pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8) {
   return pl;
 }
 
-#ifdef PQ_VAR_TRACE
-extern "C" int pq_trace_read(unsigned long long* out) {
-  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(pq_trace), sizeof(unsigned long long) * 8 * 16 * 8);
-}
-#endif
 
 int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const pq_operand& B,
                    const pq_epilogue& epi, hipStream_t s, int prof_label, void* splitk_ws,
