@@ -62,6 +62,8 @@ ffn_layout make_layout(const pq_ffn_desc& d) {
     const size_t b = pq_plan_gemm(0, sh[0], sh[1], sh[2]).ws_bytes;
     if (b > sk) sk = b;
   }
+  // the expert up/gate projections and their input gradients split the contraction up to 8 ways: [8][S][r] fp32
+  if (8 * S * r * sizeof(float) > sk) sk = 8 * S * r * sizeof(float);
   L.splitk = w.take(sk);
   L.dHd = w.take(T * F * 2); L.dU = w.take(T * F * 2); L.dG = w.take(T * F * 2);
   L.dYp = w.take(S * D * 2); L.rd = w.take(S * 4);

@@ -446,11 +446,17 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
   const int n0 = bn * BN;
   int kb = split * kchunk;
   int ke = min(K, kb + kchunk);
-  if (grp.mode == 1) {          // rows of group z: [offsets[z], offsets[z+1])
-    const int z = blockIdx.z;
-    m0 += grp.offsets[z];
+  const int Mtot = M;           // rows of C (a split's slab has Mtot rows)
+  if (grp.mode == 1) {          // rows of group z: [offsets[z], offsets[z+1]); row tiles are numbered group after group
+    int t = bm, z = 0;
+    for (; z < grp.n_groups; ++z) {
+      const int nt = (grp.offsets[z + 1] - grp.offsets[z] + BM - 1) / BM;
+      if (t < nt) break;
+      t -= nt;
+    }
+    if (z == grp.n_groups) return;   // uniform for the workgroup: the launch covers the worst-case tile count
+    m0 = grp.offsets[z] + t * BM;
     M = grp.offsets[z + 1];
-    if (m0 >= M) return;        // uniform for the workgroup
     B.p = (const char*)B.p + (size_t)z * grp.b_stride * (BKIND == PQ_SRC_KC8 ? 1 : 2);
   } else if (grp.mode == 2) {   // contraction range of group z, own output slab
     const int z = blockIdx.z;
@@ -763,7 +769,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
   // raw fp32 accumulators go to this split's slab instead; splitk_reduce_kernel finishes the job.
   epi_state st;
   epi_begin(epi, st);
-  float* slab = splitk_part ? splitk_part + (size_t)split * M * N : nullptr;
+  float* slab = splitk_part ? splitk_part + (size_t)split * Mtot * N : nullptr;
   uint32_t* stg = reinterpret_cast<uint32_t*>(smem) + wave * (32 * 36);
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -871,10 +877,11 @@ __global__ __launch_bounds__(256) void ref_gemm_kernel(int M, int N, int K, pq_o
 template <int BM, int BN, int WGM, int WGN, int KB, bool FAST, bool INT8, int AK, int BKIND, int AK2 = -1, int BK2 = -1, bool DTL = false>
 int launch_mfma(const pq_gemm_plan& pl, int M, int N, int K, const pq_operand& A, const pq_operand& B,
                 const pq_epilogue& epi, hipStream_t s, float* part, const pq_gemm_group& grp, const pq_phase2& ph2) {
-  const int Mrows = grp.mode == 1 ? grp.max_rows : M;
-  const int nbm = (Mrows + BM - 1) / BM, nbn = (N + BN - 1) / BN;
+  // grouped rows: every group may end in a partial tile, so at most ceil(rows / BM) + n_groups row tiles exist
+  const int nbm = grp.mode == 1 ? (grp.max_rows + BM - 1) / BM + grp.n_groups : (M + BM - 1) / BM;
+  const int nbn = (N + BN - 1) / BN;
   const int tiles = nbm * nbn;
-  dim3 grid(tiles, pl.splits, grp.mode ? grp.n_groups : 1), block(WGM * WGN * 64);
+  dim3 grid(tiles, pl.splits, grp.mode == 2 ? grp.n_groups : 1), block(WGM * WGN * 64);
   mfma_gemm_kernel<BM, BN, WGM, WGN, KB, FAST, INT8, AK, BKIND, AK2, BK2, DTL><<<grid, block, 0, s>>>(
       M, N, K, A, B, epi, nbn, tiles, pl.kchunk, pl.splits > 1 ? part : nullptr, grp, ph2);
   PQ_CHECK_LAUNCH("mfma_gemm_kernel");
@@ -965,10 +972,25 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
   const int ak = A.kind, bk = B.kind;
   const bool int8 = (ak == PQ_SRC_KC8);
   pq_gemm_plan pl = pq_plan_gemm(0, M, N, K, int8);
-  if (grp.mode) {               // groups already give parallelism; no contraction split
+  if (grp.mode) {
     pl.splits = 1;
     pl.kchunk = K > 0 ? K : 1;
     pl.bm = pl.bn = 128;
+    // row groups with a narrow output and a long contraction (expert up/gate projections, their input
+    // gradients): too few tiles to fill the chip, so the contraction is split as for plain GEMMs
+    if (grp.mode == 1 && N <= 128 && K >= 1024 && splitk_ws) {
+      const long tiles = (long)((grp.max_rows + 127) / 128 + grp.n_groups) * ((N + 127) / 128);
+      long want = tiles > 0 ? 256 / tiles : 1;
+      if (want > 8) want = 8;
+      if (want > 1) {
+        long chunk = (K + want - 1) / want;
+        chunk = (chunk + 255) / 256 * 256;
+        pl.kchunk = (int)chunk;
+        pl.splits = (int)((K + chunk - 1) / chunk);
+        pl.red_blocks = (int)(((size_t)M * (N / 8) + 255) / 256);
+        pl.ws_bytes = (size_t)pl.splits * M * N * sizeof(float);
+      }
+    }
   }
   if (pl.splits > 1 && !splitk_ws) return pq_set_error(PQ_ERR_WORKSPACE, "split contraction needs scratch");
   float* part = (float*)splitk_ws;
