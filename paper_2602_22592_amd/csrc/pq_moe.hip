@@ -22,40 +22,58 @@ __device__ __forceinline__ float dsiluf_(float x) {
   return s * (1.0f + x * (1.0f - s));
 }
 
-// ---- routing: one wavefront per expert ------------------------------------------------------
-__global__ __launch_bounds__(256) void route_count_kernel(const int* __restrict__ idx, int S, int E, int* __restrict__ counts) {
-  const int e = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (e >= E) return;
-  int cnt = 0;
-  for (int s0 = 0; s0 < S; s0 += 64) {
-    const int s = s0 + lane;
-    cnt += __builtin_popcountll(__ballot(s < S && idx[s] == e));
+// Stable counting sort of the slots (slot = token * k + j) by expert: perm[pos] = slot, inv[slot] = pos,
+// offsets[e] = first position of expert e.  One workgroup of 16 wavefronts.  The expert ids (< 64) are first
+// copied into LDS as bytes (LDS_IDS; otherwise every scan re-reads them from global memory); a wavefront owns
+// the experts e = w, w + 16, ...: it counts them, the counts are scanned, then it assigns positions in slot
+// order (rank inside a batch of 64 slots by ballot prefix).
+template <bool LDS_IDS>
+__global__ __launch_bounds__(1024) void route_kernel(const int* __restrict__ idx, int S, int E, int* __restrict__ counts,
+                                                     int* __restrict__ offsets, int* __restrict__ perm,
+                                                     int* __restrict__ inv) {
+  extern __shared__ unsigned char s_ids[];
+  __shared__ int s_cnt[64], s_off[65];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if constexpr (LDS_IDS) {
+    for (int s = threadIdx.x; s < S; s += 1024) s_ids[s] = (unsigned char)idx[s];
+    __syncthreads();
   }
-  if (lane == 0) counts[e] = cnt;
-}
-
-// Stable counting sort of the slots (slot = token * k + j) by expert: perm[pos] = slot, inv[slot] = pos.
-__global__ __launch_bounds__(256) void route_build_kernel(const int* __restrict__ idx, const int* __restrict__ counts, int S,
-                                                          int E, int* __restrict__ offsets, int* __restrict__ perm,
-                                                          int* __restrict__ inv) {
-  const int e = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (e >= E) return;
-  int running = 0;
-  for (int i = 0; i < e; ++i) running += counts[i];
-  if (lane == 0) {
-    offsets[e] = running;
-    if (e == E - 1) offsets[E] = running + counts[e];
+  auto id_at = [&](int s) -> int {
+    if (s >= S) return -1;
+    if constexpr (LDS_IDS) return s_ids[s];
+    else return idx[s];
+  };
+  for (int e = wave; e < E; e += 16) {
+    int cnt = 0;
+    for (int s0 = 0; s0 < S; s0 += 64) cnt += __builtin_popcountll(__ballot(id_at(s0 + lane) == e));
+    if (lane == 0) s_cnt[e] = cnt;
   }
-  for (int s0 = 0; s0 < S; s0 += 64) {
-    const int s = s0 + lane;
-    const bool match = s < S && idx[s] == e;
-    const unsigned long long m = __ballot(match);
-    if (match) {
-      const int pos = running + __builtin_popcountll(m & ((1ull << lane) - 1ull));
-      perm[pos] = s;
-      inv[s] = pos;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int e = 0; e < E; ++e) {
+      s_off[e] = run;
+      offsets[e] = run;
+      counts[e] = s_cnt[e];
+      run += s_cnt[e];
     }
-    running += __builtin_popcountll(m);
+    s_off[E] = run;
+    offsets[E] = run;
+  }
+  __syncthreads();
+  for (int e = wave; e < E; e += 16) {
+    int running = s_off[e];
+    for (int s0 = 0; s0 < S; s0 += 64) {
+      const int s = s0 + lane;
+      const bool match = id_at(s) == e;
+      const unsigned long long m = __ballot(match);
+      if (match) {
+        const int pos = running + __builtin_popcountll(m & ((1ull << lane) - 1ull));
+        perm[pos] = s;
+        inv[s] = pos;
+      }
+      running += __builtin_popcountll(m);
+    }
   }
 }
 
@@ -399,10 +417,17 @@ int pq_launch_lincomb(void* out, const void* x0, const void* x1, const void* x2,
 // ---------------------------------------------------------------------------------------------
 int pq_launch_route(const int* idx, int S, int E, int* counts, int* offsets, int* perm, int* inv, hipStream_t s) {
   pq_prof_scope prof(PQP_MOE_ROUTE, s);
-  route_count_kernel<<<(E + 3) / 4, 256, 0, s>>>(idx, S, E, counts);
-  PQ_CHECK_LAUNCH("route_count_kernel");
-  route_build_kernel<<<(E + 3) / 4, 256, 0, s>>>(idx, counts, S, E, offsets, perm, inv);
-  PQ_CHECK_LAUNCH("route_build_kernel");
+  if (S <= 96 * 1024) {
+    static bool attr_set = false;
+    if (!attr_set) {
+      PQ_CHECK_HIP(hipFuncSetAttribute((const void*)route_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
+      attr_set = true;
+    }
+    route_kernel<true><<<1, 1024, (size_t)((S + 15) / 16 * 16), s>>>(idx, S, E, counts, offsets, perm, inv);
+  } else {
+    route_kernel<false><<<1, 1024, 0, s>>>(idx, S, E, counts, offsets, perm, inv);
+  }
+  PQ_CHECK_LAUNCH("route_kernel");
   return PQ_OK;
 }
 
