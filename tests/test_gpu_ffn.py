@@ -74,3 +74,22 @@ def test_ffn_scale_edge_cases():
 def test_ffn_config3_reduced_tokens():
     print("ffn config 3 shape at T=384 (d=2048, F=5504, E=8, r=32, top-1)", flush=True)
     check_ffn(wl.config3(tokens=384), top_k=1)
+
+
+def test_ffn_config3_full_size_sampled_tokens():
+    """Config 3 at its full size (T=8192) in the launch configuration the bench times.  Every step of the
+    path is per token except the sums behind the weight gradients, so the oracle run on a sample of the
+    tokens must reproduce the GPU's Y and dX rows of those tokens."""
+    print("ffn config 3, full size, 48 sampled tokens", flush=True)
+    c = wl.config3()
+    got = run_ffn(c, 1, 2.0, 0.2)
+    rows = np.random.default_rng(33).choice(c["tokens"], size=48, replace=False)
+    rows.sort()
+    f = po.ffn_fwd(c["X"][rows], c["W_up"], c["W_gate"], c["W_down"], c["Up"], c["Gate"], c["Down"], c["Wr"], 2.0, 0.2,
+                   top_k=1, bf16=True)
+    g = po.ffn_bwd(c["dY"][rows], c["X"][rows], c["Up"], c["Gate"], c["Down"], c["Wr"], 2.0, 0.2, f)
+    ey, ex = relerr(got["Y"][rows], f["Y"]), relerr(got["dX"][rows], g["dX"])
+    print(f"  errors on the sampled rows: Y={ey:.2e} dX={ex:.2e}", flush=True)
+    assert ey <= TOL and ex <= TOL
+    for k in ("dW_up", "dW_gate", "dW_down", "dUp", "dGate", "dDown", "dWr", "dab"):
+        assert np.isfinite(got[k]).all(), k

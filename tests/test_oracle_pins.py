@@ -423,3 +423,64 @@ def test_workload_generators_are_seeded_and_bf16_exact():
         wl.bf16_bits(c[k])                                            # asserts representability
     col_energy = (a["X"].astype(np.float64) ** 2).mean(axis=0)
     assert (col_energy > 30).sum() == 4                               # the four x10 outlier channels
+
+
+# ---------------------------------------------------------------------------------------------------
+# Layer stack (config 5): wiring pins.  The pieces (linear, FFN) are pinned above; these cases fix the
+# residual connections, the q/k/v average and the order of the backward chain.
+# ---------------------------------------------------------------------------------------------------
+def _tiny_stack(seed, n_layers=2, tokens=12, d=32, f=64, e=2, r=8):
+    return wl.stack_case(seed, n_layers, tokens, d, f, e, r, vocab=50)
+
+
+def test_stack_is_the_identity_when_the_output_projections_vanish():
+    """An all-zero latent matrix has lambda = 0, so its 1-bit linear returns exactly 0.  With W_o = W_down = 0 and
+    alpha = 0 both residual branches add nothing: the stack must hand its (bf16) input through unchanged, and the
+    backward pass must hand the upstream gradient through unchanged."""
+    c = _tiny_stack(5)
+    for w in c["layers"]:
+        w["Wo"] = np.zeros_like(w["Wo"]); w["W_down"] = np.zeros_like(w["W_down"]); w["alpha"] = 0.0
+    h0 = c["table"][c["ids"]]
+    out, saved = po.stack_fwd(h0, c["layers"])
+    np.testing.assert_array_equal(np.asarray(out, np.float64), wl.bf16_round(h0).astype(np.float64))
+    dY = c["dY"]
+    d0, grads = po.stack_bwd(dY, c["layers"], saved)
+    np.testing.assert_allclose(np.asarray(d0, np.float64), dY.astype(np.float64), rtol=0, atol=0)
+    # W_o = 0 still receives a gradient (it depends on dY and the codes of m, not on lambda)
+    assert np.abs(grads[0]["Wo"]).max() > 0
+
+
+def test_stack_averages_q_k_v():
+    """With W_q = W_k = W_v the stand-in for the attention core is (3 q) / 3 = q exactly, so the first half of a layer
+    must equal h + L_o(L_q(h)) built by hand from the pinned linear."""
+    c = _tiny_stack(6, n_layers=1)
+    w = c["layers"][0]
+    w["Wk"] = w["Wq"].copy(); w["Wv"] = w["Wq"].copy()
+    h0 = wl.bf16_round(c["table"][c["ids"]])
+    _, saved = po.stack_fwd(h0, c["layers"])
+    q = wl.bf16_round(po.linear_fwd(h0, w["Wq"], 0.0, 1.0)["Y"].astype(np.float32))
+    o = wl.bf16_round(po.linear_fwd(q, w["Wo"], 0.0, 1.0)["Y"].astype(np.float32))
+    h1 = wl.bf16_round((h0.astype(np.float64) + o).astype(np.float32))
+    np.testing.assert_array_equal(np.asarray(saved[0]["m"], np.float32), q)
+    np.testing.assert_array_equal(np.asarray(saved[0]["h1"], np.float32), h1)
+
+
+def test_stack_backward_is_linear_in_the_upstream_gradient():
+    """The STE backward is a linear map of dY.  Scaling by 2 commutes with every rounding (exact), a sum of two
+    upstream gradients gives the sum of the results up to the bf16 roundings of the stored gradients."""
+    c = _tiny_stack(7)
+    h0 = c["table"][c["ids"]]
+    _, saved = po.stack_fwd(h0, c["layers"])
+    rng = np.random.default_rng(70)
+    dA = wl.bf16_round(rng.standard_normal(c["dY"].shape).astype(np.float32))
+    dB = wl.bf16_round(rng.standard_normal(c["dY"].shape).astype(np.float32))
+    xa, ga = po.stack_bwd(dA, c["layers"], saved)
+    x2, g2 = po.stack_bwd(2.0 * dA, c["layers"], saved)
+    np.testing.assert_array_equal(np.asarray(x2, np.float64), 2.0 * np.asarray(xa, np.float64))
+    np.testing.assert_array_equal(np.asarray(g2[0]["Wq"], np.float64), 2.0 * np.asarray(ga[0]["Wq"], np.float64))
+    xb, gb = po.stack_bwd(dB, c["layers"], saved)
+    xs, gs = po.stack_bwd(dA + dB, c["layers"], saved)
+    ref = np.asarray(xa, np.float64) + np.asarray(xb, np.float64)
+    assert np.abs(np.asarray(xs, np.float64) - ref).max() <= 2e-2 * np.abs(ref).max()
+    refw = np.asarray(ga[1]["W_up"], np.float64) + np.asarray(gb[1]["W_up"], np.float64)
+    assert np.abs(np.asarray(gs[1]["W_up"], np.float64) - refw).max() <= 2e-2 * np.abs(refw).max()
