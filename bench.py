@@ -7,8 +7,10 @@ gradients): weight statistics, binarise+pack, activation quantiser, int8 MFMA GE
 and the backward GEMMs with the alpha/beta reductions.  Inputs are synthetic, seeded, and already
 resident in HBM when the timed region starts.
 
-Prints ONE JSON line (see the keys below).  `roofline` is for the dominant kernel, its duration
-measured with HIP events recorded by the library around each launch inside the timed region;
+Prints ONE JSON line (see the keys below).  `value` comes from a timed region of exactly `--steps` steps
+between synchronisations.  `roofline` is for the dominant kernel: its duration is measured with HIP events
+recorded by the library around each launch, on the launch stream, in a second pass over the same steps
+(the events open gaps between launches, so they stay out of the region that is timed as a whole);
 `cpu_baseline` is the NumPy oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -75,22 +77,16 @@ def decode_bench(pq, torch, batch, n_layers=64, steps=20, warmup=3):
     desc = pq.DecodeDesc(batch, K, N, r, E, k, n_layers, pq.PQ_PACKED_TILED64 if tiled else pq.PQ_PACKED_ROWMAJOR, 2.0)
     ws = pq.decode_workspace(desc)
     run = lambda: pq.decode_gemv(desc, X, P, scale, Y, ws, A=A, B=Bm, Wr=Wr)
-    for _ in range(warmup):
-        run()
-    torch.cuda.synchronize()
-    pq.prof_reset(); pq.prof_enable(True)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
+    total_us = 1e3 * _time_steps(torch, run, steps, warmup)        # whole calls, no per-launch events
+    pq.prof_reset(); pq.prof_enable(True)                          # second pass: per-kernel durations
     for _ in range(steps):
         run()
-    e1.record()
     torch.cuda.synchronize()
     pq.prof_enable(False)
     prof = pq.prof_read(); pq.prof_reset()
     main_us = 1e3 * prof["decode_main"][0] / prof["decode_main"][1]
     prep_us = 1e3 * prof["decode_prep"][0] / prof["decode_prep"][1]
     h_us = 1e3 * prof["decode_h"][0] / prof["decode_h"][1] if "decode_h" in prof else 0.0   # batch 1: fused into prep
-    total_us = 1e3 * e0.elapsed_time(e1) / steps
     # algorithmic bytes of the main kernel per layer: packed bits + the selected experts' B rows + x, y
     n_sel = k if batch == 1 else min(E, batch * k)          # upper bound on distinct experts per layer
     main_bytes = n_layers * (N * K // 8 + n_sel * N * r * 2 + batch * (K + 2 * N))
@@ -115,6 +111,19 @@ def _time_steps(torch, fn, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
+def _profile_steps(pq, torch, fn, steps):
+    """A separate pass with the library's per-launch HIP events on (they cost launch gaps, so the pass that is
+    timed as a whole runs without them).  Returns {label: (total ms, launches)}."""
+    torch.cuda.synchronize()
+    pq.prof_reset(); pq.prof_enable(True)
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    pq.prof_enable(False)
+    prof = pq.prof_read(); pq.prof_reset()
+    return prof
+
+
 def ffn_bench(pq, torch, T=8192, D=2048, F=5504, E=8, r=32, steps=5, warmup=2):
     """Config 3: the 1.3B-shaped decoupled FFN (three 1-bit projections + E=8 top-1 experts of width 32), fwd+bwd."""
     g = torch.Generator(device="cuda").manual_seed(3)
@@ -132,14 +141,12 @@ def ffn_bench(pq, torch, T=8192, D=2048, F=5504, E=8, r=32, steps=5, warmup=2):
     def step():
         pq.ffn_fwd(desc, X, W_up, W_gate, W_down, Up, Gate, Down, Wr, Y, bufs)
         pq.ffn_bwd(desc, dY, X, Up, Gate, Down, Wr, bufs, dX, *gr)
-    pq.prof_reset(); pq.prof_enable(True)
     ms = _time_steps(torch, step, steps, warmup)
-    pq.prof_enable(False)
-    prof = pq.prof_read(); pq.prof_reset()
+    prof = _profile_steps(pq, torch, step, steps)
     t_mfma = 3 * 2.0 * T * D * F / PEAK_I8 + 6 * 2.0 * T * D * F / PEAK_BF16       # experts are < 1 % of the flops
     return {"workload": f"tokens={T}, d_model={D}, d_ffn={F}, E={E} experts of width {r}, top-1, bf16, fwd+bwd",
             "ms_per_step": round(ms, 4), "tokens_per_s": round(T / ms * 1e3, 1), "mfma_frac_of_step": round(t_mfma / (ms * 1e-3), 4),
-            "kernels_us_total_per_step": {k: round(1e3 * v[0] / (steps + warmup), 1) for k, v in sorted(prof.items())}}
+            "kernels_us_total_per_step": {k: round(1e3 * v[0] / steps, 1) for k, v in sorted(prof.items())}}
 
 
 def stack_bench(pq, torch, L=24, T=16384, D=2048, F=5504, E=8, r=32, steps=2, warmup=1):
@@ -164,11 +171,9 @@ def stack_bench(pq, torch, L=24, T=16384, D=2048, F=5504, E=8, r=32, steps=2, wa
         pq.glue_gather_rows(table, ids, h0)
         st.forward(h0, weights)
         st.backward(dY, weights, grads)
-    pq.prof_reset(); pq.prof_enable(True)
     ms = _time_steps(torch, step, steps, warmup)
-    pq.prof_enable(False)
-    prof = pq.prof_read(); pq.prof_reset()
-    glue_ms = prof.get("glue", (0.0, 1))[0] / (steps + warmup)
+    prof = _profile_steps(pq, torch, step, 1)
+    glue_ms = prof.get("glue", (0.0, 1))[0]
     ops_i8 = L * (4 * 2.0 * T * D * D + 3 * 2.0 * T * D * F)
     t_mfma = ops_i8 / PEAK_I8 + 2 * ops_i8 / PEAK_BF16
     return {"workload": f"{L} layers x (4 pure 1-bit {D}x{D} linears + FFN d_ffn={F}, E={E}x{r} top-1), tokens={T}, bf16, fwd+bwd",
@@ -224,22 +229,11 @@ def main():
         pq.linear_fwd(desc, X, W, Y, bufs, A=A, B=B)
         pq.linear_bwd(desc, dY, X, W, bufs, dX, dW, dab, A=A, B=B, dA=dA, dB=dB)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    pq.prof_reset()
-    pq.prof_enable(True)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(args.steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
-    pq.prof_enable(False)
-    ms_per_step = e0.elapsed_time(e1) / args.steps
-    prof = pq.prof_read()
-    pq.prof_reset()
+    # timed region: warm-up, then exactly `steps` steps between synchronisations, no per-launch events
+    ms_per_step = _time_steps(torch, step, args.steps, args.warmup)
+    # per-kernel durations: the same `steps` steps again with the library's HIP events around every launch (on the
+    # launch stream); those events open gaps between launches, which is why they stay out of the timed region
+    prof = _profile_steps(pq, torch, step, args.steps)
 
     kernels = {k: {"avg_us": 1e3 * ms / n, "launches": n} for k, (ms, n) in prof.items()}
     fl = gemm_flops(T, K, N, r)
