@@ -29,6 +29,11 @@ sys.path.insert(0, ROOT)
 PEAK_BF16 = 2.5e15      # dense MFMA bf16, FLOP/s
 PEAK_I8 = 5.0e15        # dense MFMA int8, OP/s
 
+# Measured HBM bytes per launch at the default workload (profiles/linear_fwd_bwd_config2_hbm_traffic.md):
+# (FETCH_SIZE KiB x 1.986 + WRITE_SIZE KiB x 1.000) x 1024
+TRAFFIC_BYTES = {"gemm_dW": int((49350 * 1.986 + 65730) * 1024), "gemm_dX": int((21860 * 1.986 + 32900) * 1024),
+                 "gemm_onebit_fwd": int((13680 * 1.986 + 32900) * 1024)}
+
 
 def gemm_flops(T, K, N, r):
     """Algorithmic flops of one launch of each GEMM label (2 * M * N * K each)."""
@@ -241,8 +246,12 @@ def main():
     is_i8 = dom == "gemm_onebit_fwd"
     achieved = fl[dom] / (kernels[dom]["avg_us"] * 1e-6) / 1e12
     peak = (PEAK_I8 if is_i8 else PEAK_BF16) / 1e12
+    # HBM traffic of that kernel per launch: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch) scaled by what
+    # the same counters read for a 256 MiB copy of known size (`--calibrate`), see profiles/; keyed by GEMM label
+    # at the default workload, null for anything that was not profiled
+    traffic = TRAFFIC_BYTES.get(dom) if (T, K, N, r) == (8192, 2048, 2048, 128) else None
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": peak,
-                "unit": "TOP/s" if is_i8 else "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
+                "unit": "TOP/s" if is_i8 else "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": traffic,
                 "avg_us": round(kernels[dom]["avg_us"], 2)}
     # whole-step MFMA utilisation: int8 ops at the int8 peak + bf16 flops at the bf16 peak
     t_mfma = fl["gemm_onebit_fwd"] / PEAK_I8 + sum(v for k, v in fl.items() if k != "gemm_onebit_fwd") / PEAK_BF16

@@ -30,7 +30,7 @@ std::vector<prof_sample*> g_prof_samples;
 const char* const g_prof_names[PQP_COUNT] = {
     "quant_act", "wstats_partial", "pack_sign", "router", "reduce_partials",
     "gemm_onebit_fwd", "gemm_hp_H", "gemm_hp_Y", "gemm_dH", "gemm_dX", "gemm_dX_hp",
-    "gemm_dW", "gemm_dB", "gemm_dA", "gemm_other", "decode_prep", "decode_h", "decode_main", "moe_route", "moe_elementwise", "swiglu", "gemm_expert", "glue"};
+    "gemm_dW", "gemm_dB", "gemm_dA", "gemm_other", "decode_prep", "decode_h", "decode_main", "moe_route", "moe_elementwise", "swiglu", "gemm_expert", "glue", "splitk_reduce"};
 }  // namespace
 
 pq_prof_scope::pq_prof_scope(int label_, hipStream_t s_) : label(label_), s(s_), slot(nullptr) {

@@ -962,8 +962,8 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
   if (phase2) ph2 = *phase2;
   if (ph2.K2 > 0 && (engine == 1 || grp.mode)) return pq_set_error(PQ_ERR_BAD_ARG, "a fused second contraction needs the plain MFMA engine");
   if (grp.mode && engine == 1) return pq_set_error(PQ_ERR_DTYPE, "grouped GEMMs run on the MFMA engine only (bf16 I/O)");
-  pq_prof_scope prof(prof_label, s);
   if (engine == 1) {
+    pq_prof_scope prof(prof_label, s);
     dim3 grid((N + 15) / 16, (M + 15) / 16), block(256);
     ref_gemm_kernel<<<grid, block, 0, s>>>(M, N, K, A, B, epi);
     PQ_CHECK_LAUNCH("ref_gemm_kernel");
@@ -995,22 +995,26 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
   if (pl.splits > 1 && !splitk_ws) return pq_set_error(PQ_ERR_WORKSPACE, "split contraction needs scratch");
   float* part = (float*)splitk_ws;
   int rc;
-  if (ph2.K2 > 0) {
-    if (pl.splits > 1) return pq_set_error(PQ_ERR_BAD_ARG, "a fused second contraction cannot be combined with a split contraction");
-    if (ak == PQ_SRC_KC8 && bk == PQ_SRC_BITS8 && ph2.A2.kind == PQ_SRC_KC16 && ph2.B2.kind == PQ_SRC_KC16)
-      return launch_mfma_cfg<true, PQ_SRC_KC8, PQ_SRC_BITS8, PQ_SRC_KC16, PQ_SRC_KC16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
-    if (ak == PQ_SRC_KC16 && bk == PQ_SRC_BITS16 && ph2.A2.kind == PQ_SRC_KC16 && ph2.B2.kind == PQ_SRC_KS16)
-      return launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_BITS16, PQ_SRC_KC16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
-    return pq_set_error(PQ_ERR_BAD_ARG, "no fused MFMA kernel for these operand kinds");
+  {
+    pq_prof_scope prof(prof_label, s);   // the MFMA kernel alone; a split's reduction is timed under its own label
+    if (ph2.K2 > 0) {
+      if (pl.splits > 1) return pq_set_error(PQ_ERR_BAD_ARG, "a fused second contraction cannot be combined with a split contraction");
+      if (ak == PQ_SRC_KC8 && bk == PQ_SRC_BITS8 && ph2.A2.kind == PQ_SRC_KC16 && ph2.B2.kind == PQ_SRC_KC16)
+        return launch_mfma_cfg<true, PQ_SRC_KC8, PQ_SRC_BITS8, PQ_SRC_KC16, PQ_SRC_KC16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+      if (ak == PQ_SRC_KC16 && bk == PQ_SRC_BITS16 && ph2.A2.kind == PQ_SRC_KC16 && ph2.B2.kind == PQ_SRC_KS16)
+        return launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_BITS16, PQ_SRC_KC16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+      return pq_set_error(PQ_ERR_BAD_ARG, "no fused MFMA kernel for these operand kinds");
+    }
+    if (ak == PQ_SRC_KC8 && bk == PQ_SRC_BITS8) rc = launch_mfma_cfg<true, PQ_SRC_KC8, PQ_SRC_BITS8>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+    else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KC16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KC16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+    else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KS16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+    else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_BITS16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_BITS16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+    else if (ak == PQ_SRC_KS16 && bk == PQ_SRC_KS16) rc = launch_mfma_cfg<false, PQ_SRC_KS16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+    else return pq_set_error(PQ_ERR_BAD_ARG, "no MFMA kernel for operand kinds (%d, %d)", ak, bk);
   }
-  if (ak == PQ_SRC_KC8 && bk == PQ_SRC_BITS8) rc = launch_mfma_cfg<true, PQ_SRC_KC8, PQ_SRC_BITS8>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
-  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KC16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KC16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
-  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KS16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
-  else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_BITS16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_BITS16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
-  else if (ak == PQ_SRC_KS16 && bk == PQ_SRC_KS16) rc = launch_mfma_cfg<false, PQ_SRC_KS16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
-  else return pq_set_error(PQ_ERR_BAD_ARG, "no MFMA kernel for operand kinds (%d, %d)", ak, bk);
   if (rc != PQ_OK) return rc;
   if (pl.splits > 1) {
+    pq_prof_scope prof(PQP_SPLITK_REDUCE, s);
     splitk_reduce_kernel<<<pl.red_blocks, 256, 0, s>>>(M, N, pl.splits, part, epi);
     PQ_CHECK_LAUNCH("splitk_reduce_kernel");
   }

@@ -6,7 +6,7 @@
 enum pq_prof_id {
   PQP_QUANT = 0, PQP_WSTATS, PQP_PACK, PQP_ROUTER, PQP_REDUCE,
   PQP_GEMM_ONEBIT, PQP_GEMM_HP_H, PQP_GEMM_HP_Y, PQP_GEMM_DH, PQP_GEMM_DX, PQP_GEMM_DX_HP,
-  PQP_GEMM_DW, PQP_GEMM_DB, PQP_GEMM_DA, PQP_GEMM_OTHER, PQP_DECODE_PREP, PQP_DECODE_H, PQP_DECODE_MAIN, PQP_MOE_ROUTE, PQP_MOE_ELEMENTWISE, PQP_SWIGLU, PQP_GEMM_EXPERT, PQP_GLUE, PQP_COUNT
+  PQP_GEMM_DW, PQP_GEMM_DB, PQP_GEMM_DA, PQP_GEMM_OTHER, PQP_DECODE_PREP, PQP_DECODE_H, PQP_DECODE_MAIN, PQP_MOE_ROUTE, PQP_MOE_ELEMENTWISE, PQP_SWIGLU, PQP_GEMM_EXPERT, PQP_GLUE, PQP_SPLITK_REDUCE, PQP_COUNT
 };
 struct pq_prof_scope {   // records an event pair around the launches made while it is alive
   int label; hipStream_t s; void* slot;
