@@ -161,11 +161,13 @@ int pq_ffn_bwd(const pq_ffn_desc* desc, const void* dY, const void* X, const voi
  *   scale_fp16 [L]: the bits of fp16(beta * lambda), the single stored scale of a packed layer;
  *   hpA [L][E][r][K], hpB [L][E][N][r], Wr [L][E][K] bf16 (all NULL when hp_rank == 0);
  *   Y [L][B][N] bf16 out;  acc_out [L][B][N] int32 out or NULL (the exact accumulators, for tests).
- * Limits: 1 <= B <= 16; K % 128 == 0 (B == 1) or K % 512 == 0 (B > 1); N % 4 == 0; r % 8 == 0
- * (B == 1) or r % 32 == 0 and (E r) % 64 == 0 (B > 1); 16 K + 32 E r <= 160 KiB for B > 1. */
+ * Limits: 1 <= B <= 16; K % 128 == 0 (K % 512 == 0 for B > 1 on the row-major packing); N % 4 == 0;
+ * r % 8 == 0 (B == 1) or r % 32 == 0 and (E r) % 64 == 0 (B > 1); for B > 1 the codes and expert
+ * hidden states of 8 (B <= 8) or 16 token rows must fit the LDS: rows * (K + 2 E r) <= 160 KiB
+ * (row-interleaved packing: rows * K + max(8 KiB, 2 rows E r)).  Violations return PQ_ERR_SHAPE. */
 typedef enum pq_packed_layout {
   PQ_PACKED_ROWMAJOR = 0, /* [N][K/32], as written by pq_pack_sign */
-  PQ_PACKED_TILED64 = 1   /* [ceil(N/64)][K/128][64][4]: rows interleaved by 64 (pq_pack_retile64); batch 1 only */
+  PQ_PACKED_TILED64 = 1   /* [ceil(N/64)][K/128][64][4]: rows interleaved by 64 (pq_pack_retile64); any batch, the fast layout */
 } pq_packed_layout;
 typedef struct pq_decode_desc {
   int32_t batch;     /* B, tokens per layer */
@@ -179,10 +181,10 @@ typedef struct pq_decode_desc {
   float alpha;
 } pq_decode_desc;
 size_t pq_decode_workspace_bytes(const pq_decode_desc* desc);
-/* Offline re-tiling for batch-1 decode: packed [N][K/32] -> tiled, pq_pack_tiled64_bytes(N, K) bytes, word
+/* Offline re-tiling for decode: packed [N][K/32] -> tiled, pq_pack_tiled64_bytes(N, K) bytes, word
  * (row, w) stored at (((row/64) * (K/128) + w/4) * 64 + row%64) * 4 + w%4, rows padded with zeros to a
- * multiple of 64.  In this order a wavefront reads 1 KiB of contiguous memory per load and every
- * lane owns one output row.  K % 128 == 0. */
+ * multiple of 64.  In this order a wavefront reads 1 KiB of contiguous memory per load and a group of
+ * 64 rows is one contiguous run of 8 K bytes.  K % 128 == 0. */
 size_t pq_pack_tiled64_bytes(int32_t N, int32_t K);
 int pq_pack_retile64(const uint32_t* packed, int32_t N, int32_t K, uint32_t* tiled, void* stream);
 int pq_decode_gemv(const pq_decode_desc* desc, const void* X, const uint32_t* packed, const uint16_t* scale_fp16,
