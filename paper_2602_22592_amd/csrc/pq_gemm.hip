@@ -355,15 +355,37 @@ __device__ __forceinline__ void epi_vec8(const pq_epilogue& e, epi_state& st, in
 //     hands lane i of a 16-lane group element (i % 4) of the 8-byte row addressed by lane 4 e + i / 4,
 //     e = 0..3: with lane j addressing (t = j / 4, 4 columns at 4 (j % 4)) lane i receives four consecutive
 //     t of column i.
-//   * packed-bit B operands keep the register path (load, expand, ds_write) one stage ahead.
+//   * packed-bit B operands stay packed in LDS (direct 4-byte loads) and are expanded to MFMA operands in
+//     registers; the small stage this gives allows a ring of four stages instead of two.
 // A wait on asm-issued reads names the registers it releases ("+v"), which orders their uses after it.
 // ---------------------------------------------------------------------------------------------
 typedef int pq_i32x2 __attribute__((ext_vector_type(2)));
 #define PQ_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define PQ_DS_READ128(dst, addr, off) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off) : "memory")
+#define PQ_DS_READ64(dst, addr, off) asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off) : "memory")
 #define PQ_DS_READ_TR(dst, addr, off) asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off) : "memory")
 #define PQ_MFMA_BF16(acc, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b))
 #define PQ_MFMA_I8(acc, a, b) asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b))
+
+// MFMA operand of +/-1 values from packed bits (bit i set = +1, clear = -1, Eq. 4): 8 bits -> 8 bf16 (bits
+// above the eighth are ignored), 16 bits -> 16 int8.
+__device__ __forceinline__ i32x4_t pq_bits_to_bf16(uint32_t b) {
+  const uint32_t nb = ~b;
+  i32x4_t o;
+#pragma unroll
+  for (int d = 0; d < 4; ++d)
+    o[d] = (int)(0x3F803F80u | ((nb << (15 - 2 * d)) & 0x00008000u) | ((nb << (30 - 2 * d)) & 0x80000000u));
+  return o;
+}
+__device__ __forceinline__ i32x4_t pq_bits_to_i8(uint32_t b) {
+  i32x4_t o;
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const uint32_t m = __umul24((b >> (4 * d)) & 0xFu, 0x00204081u) & 0x01010101u;
+    o[d] = (int)__builtin_amdgcn_perm(0x000001FFu, 0x000001FFu, m);
+  }
+  return o;
+}
 
 // One fragment set of a 128x64 wavefront tile: four A and two B operands of 16 bytes per lane.  Operands
 // read with ds_read_b128 are whole (q), transposing reads deliver 8-byte halves (h) that the register
@@ -423,7 +445,11 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
   constexpr int STAGE = (BM + BN) * KB;
   using acc_t = typename std::conditional<INT8, i32x16_t, f32x16_t>::type;
 
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * STAGE];
+  // Streaming instantiations with a packed-bit B operand keep that operand as bits in LDS (three buffers of
+  // 32 bytes per row), which leaves room for a ring of four stages of the A operand.
+  constexpr bool BBITS = DTL && (BKIND == PQ_SRC_BITS8 || BKIND == PQ_SRC_BITS16);
+  constexpr int SMEM_BYTES = BBITS ? 4 * BM * KB + 3 * BN * 32 : 2 * STAGE;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
   __shared__ double red[NT / 64];
 
   // XCD-aware tile order: consecutive workgroups go to different XCDs, so give each XCD a
@@ -510,8 +536,13 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the kernel's signature (LDS address-space casts are device-only)
     static_assert(BM == 256 && BN == 256 && WGM == 2 && WGN == 4 && KB == 128, "streaming loop: 256x256 tile on 8 wavefronts");
     constexpr bool ATR = (AK == PQ_SRC_KS16), BTR = (BKIND == PQ_SRC_KS16);
-    constexpr bool BREG = (BKIND == PQ_SRC_BITS8 || BKIND == PQ_SRC_BITS16);   // B through registers (bit expansion)
-    constexpr int IPW = BREG ? 4 : 8;                 // direct-load instructions per wavefront and stage
+    constexpr bool BREG = BBITS;                      // B stays packed in LDS and is expanded per fragment
+    constexpr int IPW = BREG ? 4 : 8;                 // 16-byte direct-load instructions per wavefront and stage
+    constexpr int NSTAGE = BREG ? 4 : 2;              // depth of the LDS ring
+    constexpr int STG = BREG ? BM * KB : STAGE;       // bytes per ring stage
+    constexpr int RB = INT8 ? 16 : 8;                 // bytes of packed bits per B row and step
+    constexpr int CH = 32 / RB;                       // steps covered by a 32-byte chunk of a packed row
+    constexpr int BITS0 = NSTAGE * BM * KB;           // LDS offset of the three chunk buffers [256 rows][32 B]
     constexpr int AES = (AK == PQ_SRC_KC8) ? 1 : 2, BES = (BKIND == PQ_SRC_KC8) ? 1 : 2;
     const int wv = __builtin_amdgcn_readfirstlane(wave);
     const uint32_t lds0 = (uint32_t)(size_t)smem;
@@ -549,10 +580,17 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
       else adv = ATR ? (size_t)64 * A.ld * 2 : (size_t)128;
     }
     auto issue = [&](int kt, int stage) {
-      unsigned char* base = smem + stage * STAGE + (opB ? BM * KB : 0) + q0 * 1024;
+      unsigned char* base = smem + stage * STG + (opB ? BM * KB : 0) + q0 * 1024;
 #pragma unroll
       for (int i = 0; i < IPW; ++i)
         __builtin_amdgcn_global_load_lds(src[i] + (size_t)kt * adv, PQ_LDS_PTR(base + i * 1024), 16, 0, 0);
+    };
+    // Packed bits of B: a row's bits are fetched 32 bytes (CH steps) at a time, two lanes per row, so a chunk
+    // (256 rows, 8 KB) is one 16-byte load instruction per wavefront every CH steps.
+    auto issue_bits = [&](int chunk, int buf) {
+      const int row = min(n0 + wv * 32 + (lane >> 1), N - 1);
+      const char* g = (const char*)B.p + (size_t)row * B.ld + (kb >> 3) + chunk * 32 + (lane & 1) * 16;
+      __builtin_amdgcn_global_load_lds(g, PQ_LDS_PTR(smem + BITS0 + buf * (BN * 32) + wv * 1024), 16, 0, 0);
     };
 
     // ---- fragment read addresses (stage 0) ------------------------------------------------------------
@@ -584,6 +622,160 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) adB[j * 4 + ks] = lds0 + b_rb[j] + (((2 * ks + h) ^ b_fx[j]) << 4);
     }
+    if constexpr (BREG) {
+      // ---- ring of four stages: A streams as above, B stays packed ------------------------------------
+      // A step's bits of a B row (8 or 16 bytes) are read once per wavefront tile column; the operand of
+      // contraction sub-step s+1 is expanded from them in registers while the MFMAs of sub-step s issue,
+      // one 4-byte piece behind each MFMA (the two wavefronts of a SIMD run in step, so a block of
+      // expansion instructions ahead of a block of MFMAs would leave the matrix pipe idle for its length).
+      // Every wavefront issues IPW direct loads of A per step, whatever the step (steps and chunks past the end
+      // re-load the last one into a place nobody reads), plus one load of bits, ahead of them, in the first
+      // step of a chunk.  At the barrier of step t at most 2 IPW loads stay in flight, which leaves A up to
+      // step t + 1 and the bits issued up to step t - 2 in LDS (when a load of bits is among the last 2 IPW,
+      // the wait merely covers one more load of A).  Chunk c is issued in the first step of chunk c - 2 and
+      // goes to buffer c mod 3, whose previous content (chunk c - 3) was last read one barrier earlier.
+      static_assert(!ATR, "packed B goes with a contraction-contiguous A");
+      using bits_t = typename std::conditional<INT8, i32x4_t, pq_i32x2>::type;
+      struct aset {
+        i32x4_t q[4];
+        __device__ __forceinline__ void wait4() { asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(q[0]), "+v"(q[1]), "+v"(q[2]), "+v"(q[3])); }
+        __device__ __forceinline__ void wait0() { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(q[0]), "+v"(q[1]), "+v"(q[2]), "+v"(q[3])); }
+      };
+      struct bfrag { int e[8]; };                      // two operands of four dwords
+      aset G0, G1;
+      bits_t bq0, bq1;
+      const uint32_t adQ0 = lds0 + BITS0 + (wn0 + (lane & 31)) * 32, adQ1 = adQ0 + 32 * 32;
+      const uint32_t sh = INT8 ? 16u * h : 8u * h;
+      // constants of the expansion kept in registers (three-operand encodings take no literals)
+      uint32_t kM = INT8 ? 0x000001FFu : 0x80008000u, kC = 0x3F803F80u;
+      asm volatile("" : "+v"(kM), "+v"(kC));
+      auto read_a = [&](aset& G, auto ks_c, uint32_t so) {
+        constexpr int ks = decltype(ks_c)::value;
+        const uint32_t p0 = adA[ks] + so, p1 = adA[4 + ks] + so;
+        PQ_DS_READ128(G.q[0], p0, 0);
+        PQ_DS_READ128(G.q[1], p1, 0);
+        PQ_DS_READ128(G.q[2], p0, 8192);
+        PQ_DS_READ128(G.q[3], p1, 8192);
+      };
+      auto read_bits = [&](uint32_t so) {
+        const uint32_t p0 = adQ0 + so, p1 = adQ1 + so;
+        if constexpr (INT8) { PQ_DS_READ128(bq0, p0, 0); PQ_DS_READ128(bq1, p1, 0); }
+        else { PQ_DS_READ64(bq0, p0, 0); PQ_DS_READ64(bq1, p1, 0); }
+      };
+      // bits of sub-step ks in the form the piecewise expansion takes: int8: the 16 bits; bf16: the 8
+      // inverted bits at positions 0..7 and again at 15..22, so that one shift by 15 - 2d puts bits 2d
+      // and 2d + 1 on the two sign positions of dword d
+      auto prep = [&](const bits_t& q, auto ks_c) -> uint32_t {
+        constexpr int ks = decltype(ks_c)::value;
+        if constexpr (INT8) return (uint32_t)q[ks] >> sh;
+        else {
+          const uint32_t nb = ((((uint32_t)q[ks >> 1] >> (16 * (ks & 1))) >> sh) & 0xFFu) ^ 0xFFu;
+          return nb | (nb << 15);
+        }
+      };
+      // dword d of an operand: bf16: sign bits from the prepared word over the pattern (1.0, 1.0);
+      // int8: nibble d -> one bit per byte (24-bit multiply) -> bytes 0x01 / 0xFF (byte permute)
+#define PQ_EXPAND(dst, y, d)                                                                                     \
+  do {                                                                                                           \
+    if constexpr (INT8)                                                                                          \
+      asm volatile("v_bfe_u32 %0, %1, %2, 4\n\tv_mul_u32_u24 %0, 0x204081, %0\n\tv_and_b32 %0, 0x1010101, %0\n\t" \
+                   "v_perm_b32 %0, %3, %3, %0"                                                                    \
+                   : "=&v"(dst)                                                                                  \
+                   : "v"(y), "n"(4 * (d)), "v"(kM));                                                             \
+    else                                                                                                         \
+      asm volatile("v_lshlrev_b32 %0, %2, %1\n\tv_and_or_b32 %0, %0, %3, %4"                                      \
+                   : "=&v"(dst)                                                                                  \
+                   : "v"(y), "n"(15 - 2 * (d)), "v"(kM), "v"(kC));                                               \
+  } while (0)
+#define PQ_MFMA_AB(i, j, G, f0, f1)                                                          \
+  do {                                                                                       \
+    if constexpr (INT8) PQ_MFMA_I8(acc[i][j], G.q[i], (j) ? f1 : f0);                        \
+    else PQ_MFMA_BF16(acc[i][j], G.q[i], (j) ? f1 : f0);                                     \
+  } while (0)
+      // MFMAs of one sub-step; FROM: the first MFMA that is followed by expansion pieces (0 = all eight)
+      auto mfma_x = [&](const aset& G, const bfrag& cur, bfrag& nxt, uint32_t y0, uint32_t y1, auto from_c) {
+        constexpr int FROM = decltype(from_c)::value;
+        const i32x4_t f0 = {cur.e[0], cur.e[1], cur.e[2], cur.e[3]}, f1 = {cur.e[4], cur.e[5], cur.e[6], cur.e[7]};
+        if constexpr (FROM == 0) {
+          PQ_MFMA_AB(0, 0, G, f0, f1); PQ_EXPAND(nxt.e[0], y0, 0);
+          PQ_MFMA_AB(0, 1, G, f0, f1); PQ_EXPAND(nxt.e[1], y0, 1);
+          PQ_MFMA_AB(1, 0, G, f0, f1); PQ_EXPAND(nxt.e[2], y0, 2);
+          PQ_MFMA_AB(1, 1, G, f0, f1); PQ_EXPAND(nxt.e[3], y0, 3);
+          PQ_MFMA_AB(2, 0, G, f0, f1); PQ_EXPAND(nxt.e[4], y1, 0);
+          PQ_MFMA_AB(2, 1, G, f0, f1); PQ_EXPAND(nxt.e[5], y1, 1);
+          PQ_MFMA_AB(3, 0, G, f0, f1); PQ_EXPAND(nxt.e[6], y1, 2);
+          PQ_MFMA_AB(3, 1, G, f0, f1); PQ_EXPAND(nxt.e[7], y1, 3);
+        } else {
+          PQ_MFMA_AB(1, 0, G, f0, f1); PQ_EXPAND(nxt.e[0], y0, 0); PQ_EXPAND(nxt.e[1], y0, 1);
+          PQ_MFMA_AB(1, 1, G, f0, f1); PQ_EXPAND(nxt.e[2], y0, 2);
+          PQ_MFMA_AB(2, 0, G, f0, f1); PQ_EXPAND(nxt.e[3], y0, 3); PQ_EXPAND(nxt.e[4], y1, 0);
+          PQ_MFMA_AB(2, 1, G, f0, f1); PQ_EXPAND(nxt.e[5], y1, 1);
+          PQ_MFMA_AB(3, 0, G, f0, f1); PQ_EXPAND(nxt.e[6], y1, 2);
+          PQ_MFMA_AB(3, 1, G, f0, f1); PQ_EXPAND(nxt.e[7], y1, 3);
+        }
+      };
+      using c0 = std::integral_constant<int, 0>;
+      using c1 = std::integral_constant<int, 1>;
+      using c2 = std::integral_constant<int, 2>;
+      using c3 = std::integral_constant<int, 3>;
+      bfrag fc, fn;
+      const int nch = nkt / CH;                         // whole chunks (the launcher checks the contraction range)
+      if (nkt > 0) {
+        issue_bits(0, 0);
+        issue_bits(min(1, nch - 1), 1);
+#pragma unroll
+        for (int s = 0; s < NSTAGE; ++s) issue(min(s, nkt - 1), s);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 1) * IPW) : "memory");
+        asm volatile("s_barrier" ::: "memory");
+        read_bits(0u);
+        read_a(G0, c0{}, 0u);
+        asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(bq0), "+v"(bq1));
+        const uint32_t y0 = prep(bq0, c0{}), y1 = prep(bq1, c0{});
+        PQ_EXPAND(fc.e[0], y0, 0); PQ_EXPAND(fc.e[1], y0, 1); PQ_EXPAND(fc.e[2], y0, 2); PQ_EXPAND(fc.e[3], y0, 3);
+        PQ_EXPAND(fc.e[4], y1, 0); PQ_EXPAND(fc.e[5], y1, 1); PQ_EXPAND(fc.e[6], y1, 2); PQ_EXPAND(fc.e[7], y1, 3);
+      }
+      uint32_t so = 0u;
+      int st = 0;
+      int part = 0, buf = 0, chunk = 0;                 // position of the current step in the packed operand
+      for (int kt = 0; kt < nkt; ++kt) {
+        const int stn = (st + 1) & (NSTAGE - 1);
+        const uint32_t sn = (uint32_t)stn * STG;
+        const bool wrap = (part == CH - 1);
+        const int partn = wrap ? 0 : part + 1;
+        const int bufn = wrap ? (buf == 2 ? 0 : buf + 1) : buf;
+        read_a(G1, c1{}, so);
+        G0.wait4();
+        mfma_x(G0, fc, fn, prep(bq0, c1{}), prep(bq1, c1{}), c0{});
+        read_a(G0, c2{}, so);
+        G1.wait4();
+        mfma_x(G1, fn, fc, prep(bq0, c2{}), prep(bq1, c2{}), c0{});
+        read_a(G1, c3{}, so);
+        G0.wait4();
+        mfma_x(G0, fc, fn, prep(bq0, c3{}), prep(bq1, c3{}), c0{});
+        G1.wait0();                                     // every LDS read of this step is complete
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * IPW) : "memory");
+        asm volatile("s_barrier" ::: "memory");
+        if (part == 0) issue_bits(min(chunk + 2, nch - 1), buf == 0 ? 2 : buf - 1);   // (buf + 2) mod 3
+        issue(min(kt + NSTAGE, nkt - 1), st);           // refill the stage just read
+        read_bits((uint32_t)(bufn * (BN * 32) + partn * RB));   // past the last step: a place nobody uses
+        read_a(G0, c0{}, sn);
+        {
+          const i32x4_t f0 = {fn.e[0], fn.e[1], fn.e[2], fn.e[3]}, f1 = {fn.e[4], fn.e[5], fn.e[6], fn.e[7]};
+          PQ_MFMA_AB(0, 0, G1, f0, f1);
+          PQ_MFMA_AB(0, 1, G1, f0, f1);
+        }
+        asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(bq0), "+v"(bq1));   // the bits were requested ahead of G0's reads
+        mfma_x(G1, fn, fc, prep(bq0, c0{}), prep(bq1, c0{}), c1{});
+        st = stn;
+        so = sn;
+        part = partn;
+        buf = bufn;
+        chunk += wrap ? 1 : 0;
+      }
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#undef PQ_EXPAND
+#undef PQ_MFMA_AB
+    } else {
     using fset = pq_frag_set<ATR, BTR>;
     fset F0, F1;
     auto read_set = [&](fset& F, auto ks_c, uint32_t so) {
@@ -632,46 +824,34 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
     using c2 = std::integral_constant<int, 2>;
     using c3 = std::integral_constant<int, 3>;
     constexpr int NR = fset::NREADS;
-    constexpr int NLB = BREG ? tile_stage<BKIND, BN, NT, KB, FAST>::NCH : 0;   // register-path loads issued per step
 
     if (nkt > 0) {
       issue(0, 0);
-      if constexpr (BREG) {
-        sb.load(B, kb, ke);
-        sb.store(smem + BM * KB, tid);
-        sb.load(B, kb + (nkt > 1 ? 1 : 0) * EPB, ke);
-      }
-      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NLB) : "memory");
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       asm volatile("s_barrier" ::: "memory");
       if (nkt > 1) issue(1, 1);
       read_set(F0, c0{}, 0u);
     }
     for (int kt = 0; kt < nkt; ++kt) {
       const uint32_t so = (kt & 1) ? (uint32_t)STAGE : 0u, sn = (kt & 1) ? 0u : (uint32_t)STAGE;
-      // Register path of B (packed bits): tile kt+1 is expanded into the idle stage in two halves placed
-      // behind the first two MFMA groups, tile kt+2 is requested behind the third, so that this work runs
-      // under MFMAs instead of in a phase of its own.
-
       read_set(F1, c1{}, so);
       F0.template wait<NR>();
       mfma_set(F0);
-      if constexpr (BREG) sb.store(smem + sn + BM * KB, tid, 0, 2);
       read_set(F0, c2{}, so);
       F1.template wait<NR>();
       mfma_set(F1);
-      if constexpr (BREG) sb.store(smem + sn + BM * KB, tid, 1, 2);
       read_set(F1, c3{}, so);
       F0.template wait<NR>();
       mfma_set(F0);
-      if constexpr (BREG) sb.load(B, kb + min(kt + 2, nkt - 1) * EPB, ke);
       F1.template wait<0>();                          // every LDS access of this step is complete
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NLB) : "memory");   // the direct loads of the next stage have landed
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the direct loads of the next stage have landed
       asm volatile("s_barrier" ::: "memory");
       if (kt + 2 < nkt) issue(kt + 2, kt & 1);
       if (kt + 1 < nkt) read_set(F0, c0{}, sn);
       mfma_set(F1);
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    }
 #endif
   } else {
   if (nkt > 0) {
@@ -903,7 +1083,9 @@ int launch_mfma_cfg(const pq_gemm_plan& pl, int M, int N, int K, const pq_operan
     if constexpr (kinds_ok) {
       const long aes = AK == PQ_SRC_KC8 ? 1 : 2;
       const bool a_ok = (A.ld * aes) % 16 == 0 && ((uintptr_t)A.p % 16) == 0 && (AK != PQ_SRC_KS16 || M % 8 == 0);
-      const bool b_ok = (BKIND == PQ_SRC_BITS8 || BKIND == PQ_SRC_BITS16) ||
+      // packed rows are fetched 32 bytes (256 contraction indices) at a time
+      constexpr bool b_bits = (BKIND == PQ_SRC_BITS8 || BKIND == PQ_SRC_BITS16);
+      const bool b_ok = b_bits ? (K % 256 == 0 && pl.kchunk % 256 == 0 && B.ld % 16 == 0 && ((uintptr_t)B.p % 16) == 0) :
                         ((B.ld * 2) % 16 == 0 && ((uintptr_t)B.p % 16) == 0 && (BKIND != PQ_SRC_KS16 || N % 8 == 0));
       const bool stream = grp.mode == 0 && K % EPB == 0 && pl.kchunk % EPB == 0 && a_ok && b_ok && M >= 1 && N >= 1;
       if (stream) {
