@@ -55,15 +55,25 @@ __device__ __forceinline__ float prep_load_x(const uint16_t* __restrict__ X, siz
   const int tid = threadIdx.x;
   const uint4* x4 = reinterpret_cast<const uint4*>(X + tok * K);
   float amax = 0.0f;
-  for (int c = tid; c < K / 8; c += 256) {
-    const uint4 u = x4[c];
-    const float f[8] = {__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u), __uint_as_float(u.y << 16),
-                        __uint_as_float(u.y & 0xFFFF0000u), __uint_as_float(u.z << 16), __uint_as_float(u.z & 0xFFFF0000u),
-                        __uint_as_float(u.w << 16), __uint_as_float(u.w & 0xFFFF0000u)};
+  // four loads in flight per thread (a load behind a loop-carried wait costs a memory latency each)
+  for (int cb = tid; cb < K / 8; cb += 1024) {
+    uint4 u4[4];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(f[j]));
-    *reinterpret_cast<float4*>(xs + 8 * c) = make_float4(f[0], f[1], f[2], f[3]);
-    *reinterpret_cast<float4*>(xs + 8 * c + 4) = make_float4(f[4], f[5], f[6], f[7]);
+    for (int i = 0; i < 4; ++i) u4[i] = x4[min(cb + 256 * i, K / 8 - 1)];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = cb + 256 * i;
+      if (c < K / 8) {
+        const uint4 u = u4[i];
+        const float f[8] = {__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u), __uint_as_float(u.y << 16),
+                            __uint_as_float(u.y & 0xFFFF0000u), __uint_as_float(u.z << 16), __uint_as_float(u.z & 0xFFFF0000u),
+                            __uint_as_float(u.w << 16), __uint_as_float(u.w & 0xFFFF0000u)};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(f[j]));
+        *reinterpret_cast<float4*>(xs + 8 * c) = make_float4(f[0], f[1], f[2], f[3]);
+        *reinterpret_cast<float4*>(xs + 8 * c + 4) = make_float4(f[4], f[5], f[6], f[7]);
+      }
+    }
   }
   return amax;
 }
@@ -121,16 +131,18 @@ __device__ __forceinline__ void prep_router(const uint16_t* __restrict__ Wr, int
   for (int e0 = 0; e0 < E; e0 += 8) {
     double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int c = tid; c < K / 8; c += 256) {
+      // the eight rows are requested together; experts past the end re-read the last one (their sums are dropped)
+      uint4 wv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) wv[u] = reinterpret_cast<const uint4*>(Wr + ((size_t)layer * E + min(e0 + u, E - 1)) * K)[c];
       const float4 xa = *reinterpret_cast<const float4*>(xs + 8 * c), xb = *reinterpret_cast<const float4*>(xs + 8 * c + 4);
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        if (e0 + u < E) {
-          const uint4 w = reinterpret_cast<const uint4*>(Wr + ((size_t)layer * E + e0 + u) * K)[c];
-          acc[u] += (double)xa.x * (double)__uint_as_float(w.x << 16) + (double)xa.y * (double)__uint_as_float(w.x & 0xFFFF0000u);
-          acc[u] += (double)xa.z * (double)__uint_as_float(w.y << 16) + (double)xa.w * (double)__uint_as_float(w.y & 0xFFFF0000u);
-          acc[u] += (double)xb.x * (double)__uint_as_float(w.z << 16) + (double)xb.y * (double)__uint_as_float(w.z & 0xFFFF0000u);
-          acc[u] += (double)xb.z * (double)__uint_as_float(w.w << 16) + (double)xb.w * (double)__uint_as_float(w.w & 0xFFFF0000u);
-        }
+        const uint4 w = wv[u];
+        acc[u] += (double)xa.x * (double)__uint_as_float(w.x << 16) + (double)xa.y * (double)__uint_as_float(w.x & 0xFFFF0000u);
+        acc[u] += (double)xa.z * (double)__uint_as_float(w.y << 16) + (double)xa.w * (double)__uint_as_float(w.y & 0xFFFF0000u);
+        acc[u] += (double)xb.x * (double)__uint_as_float(w.z << 16) + (double)xb.y * (double)__uint_as_float(w.z & 0xFFFF0000u);
+        acc[u] += (double)xb.z * (double)__uint_as_float(w.w << 16) + (double)xb.w * (double)__uint_as_float(w.w & 0xFFFF0000u);
       }
     }
     __syncthreads();
@@ -179,17 +191,27 @@ __global__ __launch_bounds__(256) void decode_prep_kernel(const uint16_t* __rest
                                                           float* __restrict__ gate) {
   extern __shared__ __attribute__((aligned(16))) float xs[];   // the token's activations as fp32 [K]
   __shared__ prep_shared sh;
-  const size_t tok = blockIdx.x;         // layer * B + b
+  // two workgroups per token when there is a router: one quantises, the other routes (independent work
+  // that would otherwise run back to back inside one workgroup)
+  const bool split = E > 0;
+  const size_t tok = split ? blockIdx.x >> 1 : blockIdx.x;   // layer * B + b
   const int layer = (int)(tok / B);
   const float amax = prep_load_x(X, tok, K, xs);
-  prep_quantise(amax, tok, K, xs, sh, xq, planes, rowsum, gamma);
-  if (E > 0) prep_router(Wr, layer, tok, K, E, topk, xs, sh, idx, gate);
+  if (!split || (blockIdx.x & 1) == 0) {
+    prep_quantise(amax, tok, K, xs, sh, xq, planes, rowsum, gamma);
+  } else {
+    __syncthreads();                                  // xs complete
+    prep_router(Wr, layer, tok, K, E, topk, xs, sh, idx, gate);
+  }
 }
 
 // Batch 1 with experts: workgroup 0 of a layer quantises the token; each of the other workgroups repeats the
 // (cheap) router for itself and computes PREP_H_ROWS rows of the selected experts' hidden state
 // h = A_e x (bf16 inputs, fp32 accumulate), two rows per wavefront.
-constexpr int PREP_H_ROWS = 8;
+#ifndef PQ_PREP_H_ROWS
+#define PQ_PREP_H_ROWS 16
+#endif
+constexpr int PREP_H_ROWS = PQ_PREP_H_ROWS;   // rows per workgroup: few enough workgroups that the repeated router stays cheap
 
 __global__ __launch_bounds__(256) void decode_prep_h_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wr,
                                                             const uint16_t* __restrict__ hpA, int K, int E, int r, int topk,
@@ -199,7 +221,20 @@ __global__ __launch_bounds__(256) void decode_prep_h_kernel(const uint16_t* __re
                                                             float* __restrict__ h) {
   extern __shared__ __attribute__((aligned(16))) float xs[];
   __shared__ prep_shared sh;
-  const int layer = blockIdx.x / parts, part = blockIdx.x - layer * parts;
+  // Consecutive workgroups go to different XCDs (each with its own L2): number them so that all parts of a
+  // layer land on one XCD and its router matrix and activations are fetched from memory once.
+  int layer, part;
+  {
+    const int L = (int)gridDim.x / parts, b = blockIdx.x;
+    if ((L & 7) == 0) {
+      const int g = b / (8 * parts), rem = b - g * (8 * parts);
+      layer = 8 * g + (rem & 7);
+      part = rem >> 3;
+    } else {
+      layer = b / parts;
+      part = b - layer * parts;
+    }
+  }
   const size_t tok = layer;
   const float amax = prep_load_x(X, tok, K, xs);
   if (part == 0) {
@@ -209,30 +244,44 @@ __global__ __launch_bounds__(256) void decode_prep_h_kernel(const uint16_t* __re
   __syncthreads();                                    // xs complete
   prep_router(Wr, layer, tok, K, E, topk, xs, sh, part == 1 ? idx : nullptr, gate);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int o0 = (part - 1) * PREP_H_ROWS + 2 * wave;  // row of the [topk][r] hidden state
-  if (o0 >= topk * r) return;
-  const bool two = o0 + 1 < topk * r;
-  const int o1 = two ? o0 + 1 : o0;
-  const uint4* a0 = reinterpret_cast<const uint4*>(hpA + (((size_t)layer * E + sh.sel[o0 / r]) * r + o0 % r) * K);
-  const uint4* a1 = reinterpret_cast<const uint4*>(hpA + (((size_t)layer * E + sh.sel[o1 / r]) * r + o1 % r) * K);
-  float s0 = 0.0f, s1 = 0.0f;
-  for (int c = lane; c < K / 8; c += 64) {
-    const uint4 u = nt_load16(a0 + c), v = nt_load16(a1 + c);
-    const float4 xa = *reinterpret_cast<const float4*>(xs + 8 * c), xb = *reinterpret_cast<const float4*>(xs + 8 * c + 4);
-    s0 += __uint_as_float(u.x << 16) * xa.x + __uint_as_float(u.x & 0xFFFF0000u) * xa.y;
-    s0 += __uint_as_float(u.y << 16) * xa.z + __uint_as_float(u.y & 0xFFFF0000u) * xa.w;
-    s0 += __uint_as_float(u.z << 16) * xb.x + __uint_as_float(u.z & 0xFFFF0000u) * xb.y;
-    s0 += __uint_as_float(u.w << 16) * xb.z + __uint_as_float(u.w & 0xFFFF0000u) * xb.w;
-    s1 += __uint_as_float(v.x << 16) * xa.x + __uint_as_float(v.x & 0xFFFF0000u) * xa.y;
-    s1 += __uint_as_float(v.y << 16) * xa.z + __uint_as_float(v.y & 0xFFFF0000u) * xa.w;
-    s1 += __uint_as_float(v.z << 16) * xb.x + __uint_as_float(v.z & 0xFFFF0000u) * xb.y;
-    s1 += __uint_as_float(v.w << 16) * xb.z + __uint_as_float(v.w & 0xFFFF0000u) * xb.w;
-  }
-  s0 = wave_sum(s0);
-  s1 = wave_sum(s1);
-  if (lane == 0) {
-    h[(size_t)layer * topk * r + o0] = s0;
-    if (two) h[(size_t)layer * topk * r + o1] = s1;
+  const int oend = min(part * PREP_H_ROWS, topk * r);
+  for (int o0 = (part - 1) * PREP_H_ROWS + 2 * wave; o0 < oend; o0 += 8) {   // rows of the [topk][r] hidden state
+    const bool two = o0 + 1 < oend;
+    const int o1 = two ? o0 + 1 : o0;
+    const uint4* a0 = reinterpret_cast<const uint4*>(hpA + (((size_t)layer * E + sh.sel[o0 / r]) * r + o0 % r) * K);
+    const uint4* a1 = reinterpret_cast<const uint4*>(hpA + (((size_t)layer * E + sh.sel[o1 / r]) * r + o1 % r) * K);
+    float s0 = 0.0f, s1 = 0.0f;
+    for (int cb = lane; cb < K / 8; cb += 256) {       // eight loads in flight per lane
+      uint4 ua[4], va[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int cc = min(cb + 64 * i, K / 8 - 1);
+        ua[i] = nt_load16(a0 + cc);
+        va[i] = nt_load16(a1 + cc);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int c = cb + 64 * i;
+        if (c < K / 8) {
+          const uint4 u = ua[i], v = va[i];
+          const float4 xa = *reinterpret_cast<const float4*>(xs + 8 * c), xb = *reinterpret_cast<const float4*>(xs + 8 * c + 4);
+          s0 += __uint_as_float(u.x << 16) * xa.x + __uint_as_float(u.x & 0xFFFF0000u) * xa.y;
+          s0 += __uint_as_float(u.y << 16) * xa.z + __uint_as_float(u.y & 0xFFFF0000u) * xa.w;
+          s0 += __uint_as_float(u.z << 16) * xb.x + __uint_as_float(u.z & 0xFFFF0000u) * xb.y;
+          s0 += __uint_as_float(u.w << 16) * xb.z + __uint_as_float(u.w & 0xFFFF0000u) * xb.w;
+          s1 += __uint_as_float(v.x << 16) * xa.x + __uint_as_float(v.x & 0xFFFF0000u) * xa.y;
+          s1 += __uint_as_float(v.y << 16) * xa.z + __uint_as_float(v.y & 0xFFFF0000u) * xa.w;
+          s1 += __uint_as_float(v.z << 16) * xb.x + __uint_as_float(v.z & 0xFFFF0000u) * xb.y;
+          s1 += __uint_as_float(v.w << 16) * xb.z + __uint_as_float(v.w & 0xFFFF0000u) * xb.w;
+        }
+      }
+    }
+    s0 = wave_sum(s0);
+    s1 = wave_sum(s1);
+    if (lane == 0) {
+      h[(size_t)layer * topk * r + o0] = s0;
+      if (two) h[(size_t)layer * topk * r + o1] = s1;
+    }
   }
 }
 
@@ -251,12 +300,24 @@ __global__ __launch_bounds__(256) void decode_h_kernel(const uint16_t* __restric
   const uint4* a4 = reinterpret_cast<const uint4*>(hpA + (((size_t)layer * E + e) * r + rr) * K);
   const uint4* x4 = reinterpret_cast<const uint4*>(X + (size_t)tok * K);
   float acc = 0.0f;
-  for (int c = lane; c < K / 8; c += 64) {
-    const uint4 a = a4[c], x = x4[c];
-    acc += __uint_as_float(a.x << 16) * __uint_as_float(x.x << 16) + __uint_as_float(a.x & 0xFFFF0000u) * __uint_as_float(x.x & 0xFFFF0000u);
-    acc += __uint_as_float(a.y << 16) * __uint_as_float(x.y << 16) + __uint_as_float(a.y & 0xFFFF0000u) * __uint_as_float(x.y & 0xFFFF0000u);
-    acc += __uint_as_float(a.z << 16) * __uint_as_float(x.z << 16) + __uint_as_float(a.z & 0xFFFF0000u) * __uint_as_float(x.z & 0xFFFF0000u);
-    acc += __uint_as_float(a.w << 16) * __uint_as_float(x.w << 16) + __uint_as_float(a.w & 0xFFFF0000u) * __uint_as_float(x.w & 0xFFFF0000u);
+  for (int cb = lane; cb < K / 8; cb += 512) {         // sixteen loads in flight per lane
+    uint4 av[8], xv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int cc = min(cb + 64 * i, K / 8 - 1);
+      av[i] = a4[cc];
+      xv[i] = x4[cc];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (cb + 64 * i < K / 8) {
+        const uint4 a = av[i], x = xv[i];
+        acc += __uint_as_float(a.x << 16) * __uint_as_float(x.x << 16) + __uint_as_float(a.x & 0xFFFF0000u) * __uint_as_float(x.x & 0xFFFF0000u);
+        acc += __uint_as_float(a.y << 16) * __uint_as_float(x.y << 16) + __uint_as_float(a.y & 0xFFFF0000u) * __uint_as_float(x.y & 0xFFFF0000u);
+        acc += __uint_as_float(a.z << 16) * __uint_as_float(x.z << 16) + __uint_as_float(a.z & 0xFFFF0000u) * __uint_as_float(x.z & 0xFFFF0000u);
+        acc += __uint_as_float(a.w << 16) * __uint_as_float(x.w << 16) + __uint_as_float(a.w & 0xFFFF0000u) * __uint_as_float(x.w & 0xFFFF0000u);
+      }
+    }
   }
   acc = wave_sum(acc);
   if (lane == 0) h[o] = acc;
@@ -926,7 +987,7 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
   } else {
     {
       pq_prof_scope prof(PQP_DECODE_PREP, s);
-      decode_prep_kernel<<<L * B, 256, (size_t)K * sizeof(float), s>>>((const uint16_t*)X, (const uint16_t*)Wr, B, K, E, d.top_k, xq,
+      decode_prep_kernel<<<L * B * (E > 0 ? 2 : 1), 256, (size_t)K * sizeof(float), s>>>((const uint16_t*)X, (const uint16_t*)Wr, B, K, E, d.top_k, xq,
                                                                       planes, rowsum, gamma, idx, gate);
       PQ_CHECK_LAUNCH("decode_prep_kernel");
     }
