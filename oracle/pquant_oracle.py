@@ -21,6 +21,8 @@ Readings taken where the paper is silent or garbled (each also listed in the des
   * router: logits on raw X, top-k on logits (ties -> lower index), gates = softmax over all experts,
     not renormalised.
   * STE: identity through Sign and Q; mu, lambda, gamma carry no gradient.
+  * the normalisation in front of the quantiser is RMSNorm with a per-channel gain g and an eps inside the
+    square root (App. B names RMSNorm, Sec. 3.1 prints LayerNorm; neither gives gain or eps).
 """
 from __future__ import annotations
 
@@ -402,6 +404,50 @@ def stack_bwd(dY, layers, saved):
         grads.append(dict(Wq=gq["dW"], Wk=gk["dW"], Wv=gv["dW"], Wo=go["dW"], W_up=gf["dW_up"], W_gate=gf["dW_gate"],
                           W_down=gf["dW_down"], Up=gf["dUp"], Gate=gf["dGate"], Down=gf["dDown"], Wr=gf["dWr"]))
     return d, grads[::-1]
+
+
+# ----------------------------------------------------------------------------------------------
+# Sec. 3.1 (Y = (lambda/gamma) W Q(Norm(X))), App. A (RMSNorm merged with activation quantisation),
+# App. B (RMSNorm in front of the quantiser): normalisation fused with the AbsMax quantiser
+# ----------------------------------------------------------------------------------------------
+def rmsnorm(X, g, eps):
+    """x_hat[t, k] = x[t, k] * rstd[t] * g[k], rstd[t] = (mean_k x[t, k]^2 + eps)^(-1/2).
+    The mean of squares and rstd are formed in fp64 and rstd is rounded once to fp32; the two products
+    are fp32, (x * rstd) first."""
+    X32 = np.asarray(X, dtype=F32)
+    g32 = np.asarray(g, dtype=F32)
+    ms = np.mean(X32.astype(F64) ** 2, axis=1)
+    rstd = (1.0 / np.sqrt(ms + F64(eps))).astype(F32)
+    xn = ((X32 * rstd[:, None]).astype(F32) * g32[None, :]).astype(F32)
+    return xn, rstd
+
+
+def rmsnorm_quant_fwd(X, g, eps, bf16=False):
+    """Q(Norm(X)) in one pass: the normalised activations are rounded to their storage format (what
+    the high-precision branch and the backward read), and the AbsMax quantiser of Sec. 3.1 acts on
+    those stored values.  Returns x_hat (stored), q, gamma, rstd and x_tilde = q / gamma."""
+    xn, rstd = rmsnorm(X, g, eps)
+    xn = _round_io(xn, bf16)
+    q, gamma = quant_act(xn)
+    xt = (q.astype(F32) / gamma[:, None]).astype(F32)
+    return dict(Xn=xn, q=q, gamma=gamma, rstd=rstd, Xt=xt)
+
+
+def rmsnorm_bwd(dXn, X, g, rstd):
+    """Backward of rmsnorm for an upstream gradient dXn w.r.t. x_hat (the quantiser is passed straight
+    through, App. B.1).  With u = x * rstd:  dg[k] = sum_t dXn[t, k] u[t, k];
+    dx[t, :] = rstd[t] * (g * dXn[t, :] - u[t, :] * mean_k(g[k] dXn[t, k] u[t, k])).  fp64 throughout,
+    rstd as stored by the forward (fp32)."""
+    d = np.asarray(dXn, dtype=F64)
+    x = np.asarray(X, dtype=F64)
+    g64 = np.asarray(g, dtype=F64)
+    s = np.asarray(rstd, dtype=F64)[:, None]
+    u = x * s
+    dg = np.sum(d * u, axis=0)
+    gd = d * g64[None, :]
+    c = np.mean(gd * u, axis=1, keepdims=True)
+    dx = s * (gd - u * c)
+    return dx, dg
 
 
 def bits_per_weight(frac_1bit, frac_8bit):

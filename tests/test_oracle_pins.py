@@ -484,3 +484,108 @@ def test_stack_backward_is_linear_in_the_upstream_gradient():
     assert np.abs(np.asarray(xs, np.float64) - ref).max() <= 2e-2 * np.abs(ref).max()
     refw = np.asarray(ga[1]["W_up"], np.float64) + np.asarray(gb[1]["W_up"], np.float64)
     assert np.abs(np.asarray(gs[1]["W_up"], np.float64) - refw).max() <= 2e-2 * np.abs(refw).max()
+
+
+# ------------------------------------------------------------------------------------------------
+# Normalisation fused with the quantiser (Sec. 3.1 Q(Norm(X)); App. A; App. B)
+# ------------------------------------------------------------------------------------------------
+def test_rmsnorm_hand_cases():
+    # x = (3, 4): mean square 12.5, so x_hat = (3, 4) / sqrt(12.5) times the gain
+    xn, rstd = po.rmsnorm(np.array([[3.0, 4.0]], np.float32), np.array([1.0, 2.0], np.float32), 0.0)
+    assert abs(float(rstd[0]) - 1.0 / math.sqrt(12.5)) < 1e-7
+    assert np.allclose(xn[0], [3.0 / math.sqrt(12.5), 8.0 / math.sqrt(12.5)], rtol=3e-7, atol=0)
+    # a constant row normalises to the sign of the constant times the gain
+    g = np.array([0.5, -1.0, 2.0, 4.0], np.float32)
+    xn, _ = po.rmsnorm(np.full((1, 4), -7.0, np.float32), g, 0.0)
+    assert np.allclose(xn[0], -g, rtol=3e-7, atol=0)
+    # eps dominates a zero row: the output is zero and rstd = eps^(-1/2)
+    xn, rstd = po.rmsnorm(np.zeros((1, 8), np.float32), np.ones(8, np.float32), 1e-6)
+    assert np.all(xn == 0) and abs(float(rstd[0]) - 1000.0) < 1e-3
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_rmsnorm_invariants(seed):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((9, 96)).astype(np.float32)
+    X[:, 5] *= 30.0
+    ones = np.ones(96, np.float32)
+    xn, rstd = po.rmsnorm(X, ones, 0.0)
+    # unit mean square per token
+    assert np.allclose(np.mean(xn.astype(np.float64) ** 2, axis=1), 1.0, rtol=2e-6)
+    # scaling a token by a power of two changes nothing, bit for bit (every operation scales exactly)
+    xn4, rstd4 = po.rmsnorm(X * np.float32(4.0), ones, 0.0)
+    assert np.array_equal(xn4, xn) and np.array_equal(rstd4 * np.float32(4.0), rstd)
+    # any positive scale leaves the result unchanged up to rounding
+    xn3, _ = po.rmsnorm(X * np.float32(3.0), ones, 0.0)
+    assert np.allclose(xn3, xn, rtol=1e-6, atol=1e-7)
+    # the gain multiplies channel-wise
+    g = rng.standard_normal(96).astype(np.float32)
+    xg, _ = po.rmsnorm(X, g, 0.0)
+    assert np.allclose(xg, xn * g[None, :], rtol=2e-7, atol=0)
+
+
+def test_rmsnorm_quant_is_the_quantiser_of_the_stored_normalised_rows():
+    rng = np.random.default_rng(3)
+    X = rng.standard_normal((17, 64)).astype(np.float32) * 5.0
+    g = (1.0 + 0.1 * rng.standard_normal(64)).astype(np.float32)
+    for bf16 in (False, True):
+        f = po.rmsnorm_quant_fwd(X, g, 1e-6, bf16=bf16)
+        # codes: brute force from the definition of Q on the stored x_hat, element by element
+        for t in range(X.shape[0]):
+            row = f["Xn"][t]
+            gam = np.float32(128.0) / max(np.float32(np.max(np.abs(row))), np.float32(1e-5))
+            assert gam == f["gamma"][t]
+            for k in range(X.shape[1]):
+                code = int(min(127, max(-128, np.rint(np.float32(row[k] * gam)))))
+                assert code == int(f["q"][t, k])
+        # every token reaches the top code: |q| hits 127 or 128-clamped
+        assert np.all(np.max(np.abs(f["q"].astype(np.int32)), axis=1) >= 127)
+        # de-quantised activations stay within half a step of the stored ones (a full step where +absmax,
+        # which maps to 128, was clamped to 127)
+        step = 1.0 / f["gamma"][:, None].astype(np.float64)
+        assert np.all(np.abs(f["Xt"].astype(np.float64) - f["Xn"]) <= step * (0.5 + 0.5 * (f["q"] == 127)) * (1 + 1e-6))
+        if bf16:   # stored rows are bf16 values
+            import torch
+            t32 = torch.from_numpy(f["Xn"])
+            assert torch.equal(t32.to(torch.bfloat16).to(torch.float32), t32)
+
+
+def test_rmsnorm_backward_by_finite_differences_and_orthogonality():
+    rng = np.random.default_rng(11)
+    T, K = 4, 12
+    X = rng.standard_normal((T, K))
+    g = 1.0 + 0.2 * rng.standard_normal(K)
+    C = rng.standard_normal((T, K))            # L = sum(C * x_hat)
+    eps = 1e-3
+
+    def loss(Xv, gv):
+        # fp64 evaluation of the forward definition through the oracle itself would round to fp32;
+        # central differences need fp64, so the loss is the forward oracle applied to fp32-exact inputs
+        # scaled up: use the identity x_hat(X) computed in fp64 from the printed formula
+        ms = np.mean(Xv ** 2, axis=1, keepdims=True)
+        return float(np.sum(C * (Xv / np.sqrt(ms + eps) * gv[None, :])))
+
+    # the fp64 formula above and the oracle forward agree to fp32 rounding (ties the two together)
+    xn, rstd = po.rmsnorm(X.astype(np.float32), g.astype(np.float32), eps)
+    X32, g32 = X.astype(np.float32).astype(np.float64), g.astype(np.float32).astype(np.float64)
+    ms = np.mean(X32 ** 2, axis=1, keepdims=True)
+    assert np.allclose(xn, X32 / np.sqrt(ms + eps) * g32[None, :], rtol=3e-7, atol=1e-7)
+    dx, dg = po.rmsnorm_bwd(C, X32, g32, (1.0 / np.sqrt(ms[:, 0] + eps)))
+    h = 1e-6
+    for (t, k) in [(0, 0), (1, 5), (3, 11), (2, 7)]:
+        Xp, Xm = X32.copy(), X32.copy()
+        Xp[t, k] += h
+        Xm[t, k] -= h
+        assert abs((loss(Xp, g32) - loss(Xm, g32)) / (2 * h) - dx[t, k]) < 1e-7
+    for k in (0, 4, 11):
+        gp, gm = g32.copy(), g32.copy()
+        gp[k] += h
+        gm[k] -= h
+        assert abs((loss(X32, gp) - loss(X32, gm)) / (2 * h) - dg[k]) < 1e-7
+    # without eps x_hat does not depend on the length of x, so the gradient is orthogonal to x
+    ms0 = np.mean(X32 ** 2, axis=1)
+    dx0, _ = po.rmsnorm_bwd(C, X32, g32, 1.0 / np.sqrt(ms0))
+    assert np.all(np.abs(np.sum(dx0 * X32, axis=1)) < 1e-12)
+    # linear in the upstream gradient
+    dx2, dg2 = po.rmsnorm_bwd(2.0 * C, X32, g32, 1.0 / np.sqrt(ms[:, 0] + eps))
+    assert np.allclose(dx2, 2.0 * dx, rtol=1e-14) and np.allclose(dg2, 2.0 * dg, rtol=1e-14)
