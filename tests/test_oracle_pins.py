@@ -543,7 +543,7 @@ def test_rmsnorm_quant_is_the_quantiser_of_the_stored_normalised_rows():
         # de-quantised activations stay within half a step of the stored ones (a full step where +absmax,
         # which maps to 128, was clamped to 127)
         step = 1.0 / f["gamma"][:, None].astype(np.float64)
-        assert np.all(np.abs(f["Xt"].astype(np.float64) - f["Xn"]) <= step * (0.5 + 0.5 * (f["q"] == 127)) * (1 + 1e-6))
+        assert np.all(np.abs(f["Xt"].astype(np.float64) - f["Xn"]) <= step * (0.5 + 0.5 * (f["q"] == 127) + 1e-4))
         if bf16:   # stored rows are bf16 values
             import torch
             t32 = torch.from_numpy(f["Xn"])
