@@ -129,6 +129,51 @@ def _profile_steps(pq, torch, fn, steps):
     return prof
 
 
+def norm_quant_bench(pq, torch, T=8192, K=2048, sets=4, steps=40, warmup=8):
+    """RMSNorm fused with the AbsMax quantiser at the config-2 activation shape (bf16), forward (all outputs)
+    and backward, against HBM bandwidth.  The calls rotate over `sets` buffer sets so that the working set
+    (sets x 112 MB forward) is larger than the 256 MB last-level cache.  Algorithmic bytes per element:
+    forward 2 (x) + 2 (x_hat) + 1 (codes) + 2 (q / gamma) = 7; backward 2 (dx_hat) + 2 (x) + 2 (dx) = 6."""
+    g = torch.Generator(device="cuda").manual_seed(6)
+    bf = torch.bfloat16
+    Xs = [torch.randn((T, K), device="cuda", generator=g).to(bf) for _ in range(sets)]
+    dXs = [torch.randn((T, K), device="cuda", generator=g).to(bf) for _ in range(sets)]
+    gain = (1.0 + 0.1 * torch.randn((K,), device="cuda", generator=g)).to(bf)
+    outs = [dict(Xn=torch.empty_like(Xs[0]), Xq=torch.empty((T, K), dtype=torch.int8, device="cuda"),
+                 gamma=torch.empty((T,), dtype=torch.float32, device="cuda"), Xt=torch.empty_like(Xs[0]),
+                 rstd=torch.empty((T,), dtype=torch.float32, device="cuda"), dX=torch.empty_like(Xs[0]),
+                 dg=torch.empty((K,), dtype=torch.float32, device="cuda")) for _ in range(sets)]
+    ws = torch.empty(pq.lib().pq_rmsnorm_bwd_workspace_bytes(T, K), dtype=torch.uint8, device="cuda")
+    it = [0]
+
+    def fwd():
+        i = it[0] % sets; it[0] += 1
+        o = outs[i]
+        pq.rmsnorm_quant_fwd_into(Xs[i], gain, 1e-6, o["Xn"], o["Xq"], o["gamma"], o["Xt"], o["rstd"])
+
+    def bwd():
+        i = it[0] % sets; it[0] += 1
+        o = outs[i]
+        pq.rmsnorm_bwd_into(dXs[i], Xs[i], gain, o["rstd"], o["dX"], o["dg"], ws)
+
+    def unfused():
+        i = it[0] % sets; it[0] += 1
+        o = outs[i]
+        pq.quant_act_into(Xs[i], o["Xq"], o["gamma"])
+
+    for _ in range(sets):
+        fwd()
+    ms_f = _time_steps(torch, fwd, steps, warmup)
+    ms_b = _time_steps(torch, bwd, steps, warmup)
+    ms_q = _time_steps(torch, unfused, steps, warmup)
+    n = T * K
+    fb, bb, qb = 7 * n + 8 * T, 6 * n + 4 * T + 4 * K, 3 * n + 4 * T
+    return {"workload": "tokens=%d, d=%d, bf16; buffers rotate over %d sets" % (T, K, sets),
+            "fwd_us": round(ms_f * 1e3, 2), "fwd_GBps": round(fb / ms_f / 1e6, 1), "fwd_frac_hbm": round(fb / ms_f / 1e6 / 8000.0, 4),
+            "bwd_us": round(ms_b * 1e3, 2), "bwd_GBps": round(bb / ms_b / 1e6, 1), "bwd_frac_hbm": round(bb / ms_b / 1e6 / 8000.0, 4),
+            "plain_quantiser_us": round(ms_q * 1e3, 2), "plain_quantiser_GBps": round(qb / ms_q / 1e6, 1)}
+
+
 def ffn_bench(pq, torch, T=8192, D=2048, F=5504, E=8, r=32, steps=5, warmup=2):
     """Config 3: the 1.3B-shaped decoupled FFN (three 1-bit projections + E=8 top-1 experts of width 32), fwd+bwd."""
     g = torch.Generator(device="cuda").manual_seed(3)
@@ -200,6 +245,7 @@ def main():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-ffn", action="store_true")
     ap.add_argument("--no-stack", action="store_true")
+    ap.add_argument("--no-norm", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -283,6 +329,8 @@ def main():
     if not args.no_decode:
         out["decode_gemv"] = {"metric": "1-bit decode GEMV HBM GB/s (4096->11008, E=8 top-2 r=64 experts)",
                               "B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8)}
+    if not args.no_norm:
+        out["rmsnorm_quant"] = norm_quant_bench(pq, torch)
     if not args.no_ffn:
         out["ffn_config3"] = ffn_bench(pq, torch)
     if not args.no_stack:

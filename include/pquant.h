@@ -67,6 +67,28 @@ const char* pq_last_error_string(void); /* host string, valid until the thread's
 int pq_quant_act(const void* X, int32_t dtype, int32_t T, int32_t K, int8_t* Xq, float* gamma,
                  void* stream);
 
+/* RMSNorm fused with the activation quantiser (Sec. 3.1: Y = (lambda/gamma) W Q(Norm(X)); App. A: the
+ * normalisation and the quantiser are both element-wise per token and merge; App. B: RMSNorm).  Per token t:
+ *     rstd_t = (mean_k x_tk^2 + eps)^(-1/2)   (mean and rstd in fp64, rstd rounded once to fp32),
+ *     xhat_tk = fl32(fl32(x_tk * rstd_t) * g_k), rounded to `dtype` (the stored normalised activation),
+ *     gamma_t, q_tk = the quantiser of pq_quant_act applied to the stored xhat.
+ *   X [T][K], gain [K] of `dtype`;  Xq [T][K] int8 out, gamma [T] fp32 out;
+ *   Xn [T][K] of `dtype` out or NULL (xhat: input of the high-precision branch and of the backward);
+ *   Xt [T][K] bf16 out or NULL (q / gamma, what the STE weight gradient multiplies with);
+ *   rstd [T] fp32 out or NULL.
+ * K % 32 == 0 and K <= 8192 (bf16) / 4096 (fp32): a token's row is read from memory once. */
+int pq_rmsnorm_quant_fwd(const void* X, const void* gain, int32_t dtype, int32_t T, int32_t K, float eps, void* Xn,
+                         int8_t* Xq, float* gamma, void* Xt, float* rstd, void* stream);
+/* Backward of the normalisation for an upstream gradient dXn with respect to xhat (the quantiser itself is
+ * differentiated as identity, App. B.1).  With u = x * rstd:
+ *     dX_tk = rstd_t * (g_k dXn_tk - u_tk * mean_j(g_j dXn_tj u_tj)),    dgain_k = sum_t dXn_tk u_tk.
+ *   dXn, X [T][K], gain [K] of `dtype`; rstd [T] fp32 as written by the forward; dX [T][K] of `dtype` out;
+ *   dgain [K] fp32 out (two-stage reduction in a fixed order).  K <= 4096 (bf16) / 2048 (fp32).
+ * workspace: at least pq_rmsnorm_bwd_workspace_bytes(T, K) bytes of scratch. */
+size_t pq_rmsnorm_bwd_workspace_bytes(int32_t T, int32_t K);
+int pq_rmsnorm_bwd(const void* dXn, const void* X, const void* gain, const float* rstd, int32_t dtype, int32_t T,
+                   int32_t K, void* dX, float* dgain, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Weight statistics + binariser + packer (Sec. 3.1 eqs. for W^INT1, mu, lambda; App. A packing).
  * mu and lambda are fp64 sums divided in fp64 and rounded once to fp32; bit = [W >= mu] (so W == mu
  * maps to +1).  packed [N][K/32] uint32: bit j of word w <-> column 32 w + j, 1 <-> +1 (the same byte

@@ -25,6 +25,7 @@ EXPORTS = [
     "pq_linear_fwd", "pq_linear_bwd", "pq_prof_enable", "pq_prof_count", "pq_prof_label", "pq_prof_read",
     "pq_prof_reset", "pq_decode_workspace_bytes", "pq_decode_gemv", "pq_pack_tiled64_bytes", "pq_pack_retile64", "pq_ffn_ctx_bytes", "pq_ffn_workspace_bytes",
     "pq_ffn_fwd", "pq_ffn_bwd", "pq_glue_lincomb", "pq_glue_gather_rows",
+    "pq_rmsnorm_quant_fwd", "pq_rmsnorm_bwd_workspace_bytes", "pq_rmsnorm_bwd",
 ]
 
 
@@ -64,7 +65,7 @@ def lib():
         L.pq_prof_label.restype = C.c_char_p
         for name in ("pq_pack_workspace_bytes", "pq_linear_ctx_bytes", "pq_linear_workspace_bytes",
                      "pq_decode_workspace_bytes", "pq_pack_tiled64_bytes", "pq_ffn_ctx_bytes",
-                     "pq_ffn_workspace_bytes"):
+                     "pq_ffn_workspace_bytes", "pq_rmsnorm_bwd_workspace_bytes"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -105,6 +106,49 @@ def quant_act(X):
     gamma = torch.empty((T,), dtype=torch.float32, device=X.device)
     _check(lib().pq_quant_act(_p(X), _dt(X), T, K, _p(Xq), _p(gamma), _stream()))
     return Xq, gamma
+
+
+def quant_act_into(X, Xq, gamma):
+    T, K = X.shape
+    _check(lib().pq_quant_act(_p(X), _dt(X), T, K, _p(Xq), _p(gamma), _stream()))
+
+
+def rmsnorm_quant_fwd_into(X, gain, eps, Xn, Xq, gamma, Xt, rstd):
+    """Same call as rmsnorm_quant_fwd, writing into buffers the caller holds (any of Xn, Xt, rstd may be None)."""
+    T, K = X.shape
+    _check(lib().pq_rmsnorm_quant_fwd(_p(X), _p(gain), _dt(X), T, K, C.c_float(eps), _p(Xn), _p(Xq), _p(gamma), _p(Xt),
+                                      _p(rstd), _stream()))
+
+
+def rmsnorm_bwd_into(dXn, X, gain, rstd, dX, dgain, ws):
+    T, K = X.shape
+    _check(lib().pq_rmsnorm_bwd(_p(dXn), _p(X), _p(gain), _p(rstd), _dt(X), T, K, _p(dX), _p(dgain), _p(ws),
+                                C.c_size_t(ws.numel()), _stream()))
+
+
+def rmsnorm_quant_fwd(X, gain, eps, want_xn=True, want_xt=True, want_rstd=True):
+    """Returns (Xn, Xq, gamma, Xt, rstd); entries not asked for are None."""
+    T, K = X.shape
+    Xq = torch.empty((T, K), dtype=torch.int8, device=X.device)
+    gamma = torch.empty((T,), dtype=torch.float32, device=X.device)
+    Xn = torch.empty_like(X) if want_xn else None
+    Xt = torch.empty((T, K), dtype=torch.bfloat16, device=X.device) if want_xt else None
+    rstd = torch.empty((T,), dtype=torch.float32, device=X.device) if want_rstd else None
+    _check(lib().pq_rmsnorm_quant_fwd(_p(X), _p(gain), _dt(X), T, K, C.c_float(eps), _p(Xn), _p(Xq), _p(gamma), _p(Xt),
+                                      _p(rstd), _stream()))
+    return Xn, Xq, gamma, Xt, rstd
+
+
+def rmsnorm_bwd(dXn, X, gain, rstd, ws=None):
+    """Returns (dX, dgain)."""
+    T, K = X.shape
+    dX = torch.empty_like(X)
+    dgain = torch.empty((K,), dtype=torch.float32, device=X.device)
+    if ws is None:
+        ws = _bytes(lib().pq_rmsnorm_bwd_workspace_bytes(T, K), X.device)
+    _check(lib().pq_rmsnorm_bwd(_p(dXn), _p(X), _p(gain), _p(rstd), _dt(X), T, K, _p(dX), _p(dgain), _p(ws),
+                                C.c_size_t(ws.numel()), _stream()))
+    return dX, dgain
 
 
 def pack_sign(W, transposed=False):

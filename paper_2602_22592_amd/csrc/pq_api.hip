@@ -30,7 +30,7 @@ std::vector<prof_sample*> g_prof_samples;
 const char* const g_prof_names[PQP_COUNT] = {
     "quant_act", "wstats_partial", "pack_sign", "router", "reduce_partials",
     "gemm_onebit_fwd", "gemm_hp_H", "gemm_hp_Y", "gemm_dH", "gemm_dX", "gemm_dX_hp",
-    "gemm_dW", "gemm_dB", "gemm_dA", "gemm_other", "decode_prep", "decode_h", "decode_main", "moe_route", "moe_elementwise", "swiglu", "gemm_expert", "glue", "splitk_reduce"};
+    "gemm_dW", "gemm_dB", "gemm_dA", "gemm_other", "decode_prep", "decode_h", "decode_main", "moe_route", "moe_elementwise", "swiglu", "gemm_expert", "glue", "splitk_reduce", "rmsnorm_quant", "rmsnorm_bwd"};
 }  // namespace
 
 pq_prof_scope::pq_prof_scope(int label_, hipStream_t s_) : label(label_), s(s_), slot(nullptr) {
@@ -184,6 +184,40 @@ extern "C" int pq_quant_act(const void* X, int32_t dtype, int32_t T, int32_t K, 
   PQ_REQUIRE(X && Xq && gamma, PQ_ERR_BAD_ARG, "NULL buffer");
   PQ_REQUIRE(aligned16(X) && aligned16(Xq), PQ_ERR_SHAPE, "X and Xq must be 16-byte aligned");
   return pq_launch_quant_act(X, dtype, T, K, Xq, gamma, nullptr, (hipStream_t)stream);
+}
+
+extern "C" int pq_rmsnorm_quant_fwd(const void* X, const void* gain, int32_t dtype, int32_t T, int32_t K, float eps, void* Xn,
+                                    int8_t* Xq, float* gamma, void* Xt, float* rstd, void* stream) {
+  if (int e = check_dtype(dtype)) return e;
+  PQ_REQUIRE(T >= 0 && K > 0, PQ_ERR_BAD_ARG, "bad size T=%d K=%d", T, K);
+  PQ_REQUIRE(K % 32 == 0, PQ_ERR_SHAPE, "K=%d must be a multiple of 32", K);
+  PQ_REQUIRE(eps >= 0.0f, PQ_ERR_BAD_ARG, "eps must not be negative");
+  PQ_REQUIRE(K <= (dtype == PQ_F32 ? 4096 : 8192), PQ_ERR_SHAPE, "K=%d exceeds the row length this call keeps in registers", K);
+  if (T == 0) return PQ_OK;
+  PQ_REQUIRE(X && gain && Xq && gamma, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(aligned16(X) && aligned16(gain) && aligned16(Xq) && aligned16(Xn) && aligned16(Xt), PQ_ERR_SHAPE,
+             "buffers must be 16-byte aligned");
+  return pq_launch_rmsnorm_quant(X, gain, dtype, T, K, eps, Xn, Xq, gamma, (uint16_t*)Xt, rstd, (hipStream_t)stream);
+}
+
+extern "C" size_t pq_rmsnorm_bwd_workspace_bytes(int32_t T, int32_t K) {
+  if (T < 0 || K <= 0) return 0;
+  return pq_rmsnorm_bwd_scratch_bytes(T, K) + 256;
+}
+
+extern "C" int pq_rmsnorm_bwd(const void* dXn, const void* X, const void* gain, const float* rstd, int32_t dtype, int32_t T,
+                              int32_t K, void* dX, float* dgain, void* workspace, size_t workspace_bytes, void* stream) {
+  if (int e = check_dtype(dtype)) return e;
+  PQ_REQUIRE(T >= 0 && K > 0, PQ_ERR_BAD_ARG, "bad size T=%d K=%d", T, K);
+  PQ_REQUIRE(K % 32 == 0, PQ_ERR_SHAPE, "K=%d must be a multiple of 32", K);
+  PQ_REQUIRE(K <= (dtype == PQ_F32 ? 2048 : 4096), PQ_ERR_SHAPE, "K=%d exceeds the row length this call keeps in registers", K);
+  PQ_REQUIRE(dgain && gain, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(T == 0 || (dXn && X && rstd && dX), PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(aligned16(dXn) && aligned16(X) && aligned16(gain) && aligned16(dX), PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
+  PQ_REQUIRE(workspace_bytes >= pq_rmsnorm_bwd_workspace_bytes(T, K), PQ_ERR_WORKSPACE, "workspace too small");
+  PQ_REQUIRE(T == 0 || workspace, PQ_ERR_BAD_ARG, "NULL workspace");
+  float* part = (float*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
+  return pq_launch_rmsnorm_bwd(dXn, X, gain, rstd, dtype, T, K, dX, dgain, part, (hipStream_t)stream);
 }
 
 extern "C" size_t pq_pack_workspace_bytes(int32_t N, int32_t K) {

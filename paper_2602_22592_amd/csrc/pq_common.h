@@ -25,6 +25,23 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
 
+// Stores with an optional non-temporal hint, for results that are written once and not re-read before they
+// would have left the caches anyway.  Measured on a stream of fresh buffers the hint raises the write rate by
+// about 40 %; inside a training step, where the next kernel re-reads a result out of the last-level cache,
+// plain stores are the better choice, so the hint is a per-call-site decision.
+typedef uint32_t pq_u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t pq_u32x2_t __attribute__((ext_vector_type(2)));
+template <bool NT>
+__device__ __forceinline__ void pq_st16(void* p, const uint4& v) {
+  if constexpr (NT) __builtin_nontemporal_store(pq_u32x4_t{v.x, v.y, v.z, v.w}, reinterpret_cast<pq_u32x4_t*>(p));
+  else *reinterpret_cast<uint4*>(p) = v;
+}
+template <bool NT>
+__device__ __forceinline__ void pq_st8(void* p, const uint2& v) {
+  if constexpr (NT) __builtin_nontemporal_store(pq_u32x2_t{v.x, v.y}, reinterpret_cast<pq_u32x2_t*>(p));
+  else *reinterpret_cast<uint2*>(p) = v;
+}
+
 template <typename T> struct io_traits;
 template <> struct io_traits<float> {
   static __device__ __forceinline__ float load(const float* p, size_t i) { return p[i]; }

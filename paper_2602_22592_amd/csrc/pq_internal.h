@@ -6,7 +6,7 @@
 enum pq_prof_id {
   PQP_QUANT = 0, PQP_WSTATS, PQP_PACK, PQP_ROUTER, PQP_REDUCE,
   PQP_GEMM_ONEBIT, PQP_GEMM_HP_H, PQP_GEMM_HP_Y, PQP_GEMM_DH, PQP_GEMM_DX, PQP_GEMM_DX_HP,
-  PQP_GEMM_DW, PQP_GEMM_DB, PQP_GEMM_DA, PQP_GEMM_OTHER, PQP_DECODE_PREP, PQP_DECODE_H, PQP_DECODE_MAIN, PQP_MOE_ROUTE, PQP_MOE_ELEMENTWISE, PQP_SWIGLU, PQP_GEMM_EXPERT, PQP_GLUE, PQP_SPLITK_REDUCE, PQP_COUNT
+  PQP_GEMM_DW, PQP_GEMM_DB, PQP_GEMM_DA, PQP_GEMM_OTHER, PQP_DECODE_PREP, PQP_DECODE_H, PQP_DECODE_MAIN, PQP_MOE_ROUTE, PQP_MOE_ELEMENTWISE, PQP_SWIGLU, PQP_GEMM_EXPERT, PQP_GLUE, PQP_SPLITK_REDUCE, PQP_NORM_QUANT, PQP_NORM_BWD, PQP_COUNT
 };
 struct pq_prof_scope {   // records an event pair around the launches made while it is alive
   int label; hipStream_t s; void* slot;
@@ -19,6 +19,14 @@ struct pq_prof_scope {   // records an event pair around the launches made while
 // activation that the STE backward multiplies with.
 int pq_launch_quant_act(const void* X, int dtype, int T, int K, int8_t* Xq, float* gamma,
                         uint16_t* Xt, hipStream_t s);
+// RMSNorm fused with the quantiser: Xn (optional, I/O type) receives the stored normalised activations,
+// Xt (optional, bf16) q/gamma, rstd (optional) the per-token reciprocal RMS.  Rows of up to 16*64 16-byte
+// vectors (8 for the backward).
+int pq_launch_rmsnorm_quant(const void* X, const void* gain, int dtype, int T, int K, float eps, void* Xn, int8_t* Xq,
+                            float* gamma, uint16_t* Xt, float* rstd, hipStream_t s);
+size_t pq_rmsnorm_bwd_scratch_bytes(int T, int K);
+int pq_launch_rmsnorm_bwd(const void* dXn, const void* X, const void* gain, const float* rstd, int dtype, int T, int K, void* dX,
+                          float* dgain, float* part, hipStream_t s);
 // Weight statistics, stage 1: per-block fp64 partial sums {sum W, sum |W|}.
 int pq_stats_blocks(size_t n_elems);
 int pq_launch_wstats_partial(const void* W, int dtype, size_t n_elems, double* partials, int nblocks,

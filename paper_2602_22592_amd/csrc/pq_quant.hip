@@ -32,7 +32,7 @@ __device__ __forceinline__ int quant_code(float x, float g) {
   return (int)r;
 }
 
-template <typename T>
+template <typename T, bool NT = false>
 __device__ __forceinline__ void quant_store(const uint4& u, float g, int8_t* qrow, uint16_t* xtrow,
                                             int c) {
   constexpr int V = vec16<T>::V;
@@ -47,7 +47,7 @@ __device__ __forceinline__ void quant_store(const uint4& u, float g, int8_t* qro
     w[j] = (uint32_t)(q[4 * j] & 0xFF) | ((uint32_t)(q[4 * j + 1] & 0xFF) << 8) |
            ((uint32_t)(q[4 * j + 2] & 0xFF) << 16) | ((uint32_t)(q[4 * j + 3] & 0xFF) << 24);
   if constexpr (V == 8) {
-    *reinterpret_cast<uint2*>(qrow + (size_t)c * 8) = make_uint2(w[0], w[1]);
+    pq_st8<NT>(qrow + (size_t)c * 8, make_uint2(w[0], w[1]));
   } else {
     *reinterpret_cast<uint32_t*>(qrow + (size_t)c * 4) = w[0];
   }
@@ -57,9 +57,9 @@ __device__ __forceinline__ void quant_store(const uint4& u, float g, int8_t* qro
     for (int j = 0; j < V / 2; ++j)
       o[j] = pack_bf16x2((float)q[2 * j] / g, (float)q[2 * j + 1] / g);
     if constexpr (V == 8) {
-      *reinterpret_cast<uint4*>(xtrow + (size_t)c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+      pq_st16<NT>(xtrow + (size_t)c * 8, make_uint4(o[0], o[1], o[2], o[3]));
     } else {
-      *reinterpret_cast<uint2*>(xtrow + (size_t)c * 4) = make_uint2(o[0], o[1]);
+      pq_st8<NT>(xtrow + (size_t)c * 4, make_uint2(o[0], o[1]));
     }
   }
 }
@@ -134,6 +134,283 @@ int pq_launch_quant_act(const void* X, int dtype, int T, int K, int8_t* Xq, floa
   pq_prof_scope prof(PQP_QUANT, s);
   if (dtype == PQ_F32) return launch_quant_t<float>((const float*)X, T, K, Xq, gamma, Xt, s);
   return launch_quant_t<uint16_t>((const uint16_t*)X, T, K, Xq, gamma, Xt, s);
+}
+
+// ------------------------------------------------------------------------------------------
+// RMSNorm fused with the AbsMax quantiser (Sec. 3.1: Q(Norm(X)); App. A: both are element-wise per token
+// and merge; App. B: RMSNorm).  One wavefront per token, the row stays in registers between the three
+// steps: sum of squares (fp64, so that rstd does not depend on the order of the sum beyond its last fp64
+// bit), x_hat = fl(fl(x rstd) g) rounded to the I/O type, then the quantiser of the stored x_hat.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ uint4 pack_io(const float* f);
+template <>
+__device__ __forceinline__ uint4 pack_io<float>(const float* f) {
+  return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+}
+template <>
+__device__ __forceinline__ uint4 pack_io<uint16_t>(const float* f) {
+  return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+}
+
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void rmsnorm_quant_kernel(const T* __restrict__ X, const T* __restrict__ gain, int Tn, int K,
+                                                            float eps, T* __restrict__ Xn, int8_t* __restrict__ Xq,
+                                                            float* __restrict__ gamma, uint16_t* __restrict__ Xt,
+                                                            float* __restrict__ rstd_out) {
+  constexpr int V = vec16<T>::V;
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= Tn) return;
+  const uint4* xr = reinterpret_cast<const uint4*>(X + (size_t)row * K);
+  const uint4* gr = reinterpret_cast<const uint4*>(gain);
+  const int nvec = K / V;
+  uint4 cache[NV];
+  double ss = 0.0;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = i * 64 + lane;
+    if (c < nvec) {
+      cache[i] = xr[c];
+      float f[V];
+      vec16<T>::unpack(cache[i], f);
+#pragma unroll
+      for (int j = 0; j < V; ++j) ss += (double)f[j] * (double)f[j];
+    }
+  }
+  ss = wave_sum_d(ss);
+  const float r = (float)(1.0 / sqrt(ss / (double)K + (double)eps));
+  float amax = 0.0f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = i * 64 + lane;
+    if (c < nvec) {
+      float f[V], g[V];
+      vec16<T>::unpack(cache[i], f);
+      vec16<T>::unpack(gr[c], g);
+#pragma unroll
+      for (int j = 0; j < V; ++j) f[j] = __fmul_rn(__fmul_rn(f[j], r), g[j]);
+      cache[i] = pack_io<T>(f);                      // the stored x_hat; everything below reads it back
+      vec16<T>::unpack(cache[i], f);
+#pragma unroll
+      for (int j = 0; j < V; ++j) amax = fmaxf(amax, fabsf(f[j]));
+      if (Xn) pq_st16<true>(reinterpret_cast<uint4*>(Xn + (size_t)row * K) + c, cache[i]);
+    }
+  }
+  amax = wave_max(amax);
+  const float g = 128.0f / fmaxf(amax, 1e-5f);
+  if (lane == 0) {
+    gamma[row] = g;
+    if (rstd_out) rstd_out[row] = r;
+  }
+  int8_t* qrow = Xq + (size_t)row * K;
+  uint16_t* xtrow = Xt ? Xt + (size_t)row * K : nullptr;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = i * 64 + lane;
+    if (c < nvec) quant_store<T, true>(cache[i], g, qrow, xtrow, c);
+  }
+}
+
+template <typename T>
+static int launch_rmsnorm_quant_t(const T* X, const T* gain, int Tn, int K, float eps, T* Xn, int8_t* Xq, float* gamma,
+                                  uint16_t* Xt, float* rstd, hipStream_t s) {
+  constexpr int V = vec16<T>::V;
+  const int per_lane = (K / V + 63) / 64;
+  dim3 grid((Tn + 3) / 4), block(256);
+  if (per_lane <= 4) rmsnorm_quant_kernel<T, 4><<<grid, block, 0, s>>>(X, gain, Tn, K, eps, Xn, Xq, gamma, Xt, rstd);
+  else if (per_lane <= 8) rmsnorm_quant_kernel<T, 8><<<grid, block, 0, s>>>(X, gain, Tn, K, eps, Xn, Xq, gamma, Xt, rstd);
+  else if (per_lane <= 16) rmsnorm_quant_kernel<T, 16><<<grid, block, 0, s>>>(X, gain, Tn, K, eps, Xn, Xq, gamma, Xt, rstd);
+  else return pq_set_error(PQ_ERR_SHAPE, "row of %d elements does not fit the register cache of the fused normalising quantiser", K);
+  PQ_CHECK_LAUNCH("rmsnorm_quant_kernel");
+  return PQ_OK;
+}
+
+int pq_launch_rmsnorm_quant(const void* X, const void* gain, int dtype, int T, int K, float eps, void* Xn, int8_t* Xq,
+                            float* gamma, uint16_t* Xt, float* rstd, hipStream_t s) {
+  if (T == 0) return PQ_OK;
+  pq_prof_scope prof(PQP_NORM_QUANT, s);
+  if (dtype == PQ_F32)
+    return launch_rmsnorm_quant_t<float>((const float*)X, (const float*)gain, T, K, eps, (float*)Xn, Xq, gamma, Xt, rstd, s);
+  return launch_rmsnorm_quant_t<uint16_t>((const uint16_t*)X, (const uint16_t*)gain, T, K, eps, (uint16_t*)Xn, Xq, gamma, Xt, rstd, s);
+}
+
+// Backward of the normalisation (the quantiser is passed straight through, App. B.1): with u = x rstd,
+//   dx = rstd (g dxn - u mean_k(g dxn u)),   dg[k] = sum_t dxn[t][k] u[t][k].
+// A wavefront walks NORM_BWD_TPW tokens and keeps its share of dg in registers; the four wavefronts of a
+// workgroup add their shares through LDS into one partial row, and a second kernel adds the partial rows in a
+// fixed order (fp64), so the result is the same on every run.
+constexpr int NORM_BWD_TPW = 4;                    // tokens per wavefront
+constexpr int NORM_BWD_TPB = 4 * NORM_BWD_TPW;     // tokens per workgroup = per partial row of dgain
+
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ dXn, const T* __restrict__ X,
+                                                          const T* __restrict__ gain, const float* __restrict__ rstd, int Tn,
+                                                          int K, T* __restrict__ dX, float* __restrict__ part) {
+  constexpr int V = vec16<T>::V;
+  extern __shared__ __attribute__((aligned(16))) float dsh[];   // [3][K]: the dgain shares of wavefronts 1..3
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t0 = blockIdx.x * NORM_BWD_TPB + wave * NORM_BWD_TPW;
+  const int nvec = K / V;
+  const uint4* gr = reinterpret_cast<const uint4*>(gain);
+  uint4 gp[NV];
+  float dga[NV][V];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    gp[i] = gr[min(i * 64 + lane, nvec - 1)];
+#pragma unroll
+    for (int j = 0; j < V; ++j) dga[i][j] = 0.0f;
+  }
+  const int t1 = min(t0 + NORM_BWD_TPW, Tn);
+  for (int t = t0; t < t1; t += 2) {                  // two tokens per pass: sixteen row loads in flight
+    const bool two = t + 1 < t1;
+    const int tb = two ? t + 1 : t;
+    uint4 dc[2][NV], xc[2][NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = min(i * 64 + lane, nvec - 1);
+      dc[0][i] = reinterpret_cast<const uint4*>(dXn + (size_t)t * K)[c];
+      xc[0][i] = reinterpret_cast<const uint4*>(X + (size_t)t * K)[c];
+      dc[1][i] = reinterpret_cast<const uint4*>(dXn + (size_t)tb * K)[c];
+      xc[1][i] = reinterpret_cast<const uint4*>(X + (size_t)tb * K)[c];
+    }
+    const float s2[2] = {rstd[t], rstd[tb]};
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      if (q == 1 && !two) break;
+      const float s = s2[q];
+      double dot = 0.0;
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        if (i * 64 + lane < nvec) {
+          float d[V], x[V], g[V];
+          vec16<T>::unpack(dc[q][i], d);
+          vec16<T>::unpack(xc[q][i], x);
+          vec16<T>::unpack(gp[i], g);
+#pragma unroll
+          for (int j = 0; j < V; ++j) {
+            const float u = __fmul_rn(x[j], s);
+            dot += (double)__fmul_rn(g[j], d[j]) * (double)u;
+            dga[i][j] = __fadd_rn(dga[i][j], __fmul_rn(d[j], u));
+          }
+        }
+      }
+      const float cm = (float)(wave_sum_d(dot) / (double)K);
+      T* orow = dX + (size_t)(q ? tb : t) * K;
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int c = i * 64 + lane;
+        if (c < nvec) {
+          float d[V], x[V], g[V], o[V];
+          vec16<T>::unpack(dc[q][i], d);
+          vec16<T>::unpack(xc[q][i], x);
+          vec16<T>::unpack(gp[i], g);
+#pragma unroll
+          for (int j = 0; j < V; ++j) {
+            const float u = __fmul_rn(x[j], s);
+            o[j] = __fmul_rn(s, __fsub_rn(__fmul_rn(g[j], d[j]), __fmul_rn(u, cm)));
+          }
+          pq_st16<true>(reinterpret_cast<uint4*>(orow) + c, pack_io<T>(o));
+        }
+      }
+    }
+  }
+  // the four wavefronts' shares are added in wavefront order and leave as one partial row
+  if (wave > 0) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = i * 64 + lane;
+      if (c < nvec) {
+#pragma unroll
+        for (int j = 0; j < V; j += 4)
+          *reinterpret_cast<float4*>(dsh + (size_t)(wave - 1) * K + (size_t)c * V + j) =
+              make_float4(dga[i][j], dga[i][j + 1], dga[i][j + 2], dga[i][j + 3]);
+      }
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    float* prow = part + (size_t)blockIdx.x * K;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = i * 64 + lane;
+      if (c < nvec) {
+#pragma unroll
+        for (int j = 0; j < V; j += 4) {
+          float4 a = make_float4(dga[i][j], dga[i][j + 1], dga[i][j + 2], dga[i][j + 3]);
+#pragma unroll
+          for (int w = 0; w < 3; ++w) {
+            const float4 b = *reinterpret_cast<const float4*>(dsh + (size_t)w * K + (size_t)c * V + j);
+            a.x = __fadd_rn(a.x, b.x); a.y = __fadd_rn(a.y, b.y); a.z = __fadd_rn(a.z, b.z); a.w = __fadd_rn(a.w, b.w);
+          }
+          *reinterpret_cast<float4*>(prow + (size_t)c * V + j) = a;
+        }
+      }
+    }
+  }
+}
+
+// 8 columns x 32 row slices per workgroup: slice r adds rows r, r + 32, ... (sixteen independent loads in
+// flight), the slices are then added in slice order.
+__global__ __launch_bounds__(256) void rmsnorm_dgain_kernel(const float* __restrict__ part, int nrows, int K, float* __restrict__ dgain) {
+  __shared__ double red[32][9];
+  const int col = threadIdx.x & 7, slice = threadIdx.x >> 3;
+  const int k = blockIdx.x * 8 + col;
+  double a = 0.0;
+  if (k < K) {
+    int w = slice;
+    for (; w + 15 * 32 < nrows; w += 16 * 32) {
+      float v[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] = part[(size_t)(w + 32 * i) * K + k];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) a += (double)v[i];
+    }
+    for (; w < nrows; w += 32) a += (double)part[(size_t)w * K + k];
+  }
+  red[slice][col] = a;
+  __syncthreads();
+  if (slice == 0 && k < K) {
+    double t = 0.0;
+#pragma unroll
+    for (int r = 0; r < 32; ++r) t += red[r][col];
+    dgain[k] = (float)t;
+  }
+}
+
+size_t pq_rmsnorm_bwd_scratch_bytes(int T, int K) {
+  return (size_t)((T + NORM_BWD_TPB - 1) / NORM_BWD_TPB) * K * sizeof(float);
+}
+
+template <typename T>
+static int launch_rmsnorm_bwd_t(const T* dXn, const T* X, const T* gain, const float* rstd, int Tn, int K, T* dX, float* part,
+                                hipStream_t s) {
+  constexpr int V = vec16<T>::V;
+  const int per_lane = (K / V + 63) / 64;
+  dim3 grid((Tn + NORM_BWD_TPB - 1) / NORM_BWD_TPB), block(256);
+  const size_t lds = (size_t)3 * K * sizeof(float);
+  if (per_lane <= 4) rmsnorm_bwd_kernel<T, 4><<<grid, block, lds, s>>>(dXn, X, gain, rstd, Tn, K, dX, part);
+  else if (per_lane <= 8) rmsnorm_bwd_kernel<T, 8><<<grid, block, lds, s>>>(dXn, X, gain, rstd, Tn, K, dX, part);
+  else return pq_set_error(PQ_ERR_SHAPE, "row of %d elements does not fit the register cache of the normalisation backward", K);
+  PQ_CHECK_LAUNCH("rmsnorm_bwd_kernel");
+  return PQ_OK;
+}
+
+int pq_launch_rmsnorm_bwd(const void* dXn, const void* X, const void* gain, const float* rstd, int dtype, int T, int K, void* dX,
+                          float* dgain, float* part, hipStream_t s) {
+  if (T > 0) {
+    pq_prof_scope prof(PQP_NORM_BWD, s);
+    int e;
+    if (dtype == PQ_F32)
+      e = launch_rmsnorm_bwd_t<float>((const float*)dXn, (const float*)X, (const float*)gain, rstd, T, K, (float*)dX, part, s);
+    else
+      e = launch_rmsnorm_bwd_t<uint16_t>((const uint16_t*)dXn, (const uint16_t*)X, (const uint16_t*)gain, rstd, T, K, (uint16_t*)dX, part, s);
+    if (e) return e;
+  }
+  pq_prof_scope prof(PQP_NORM_BWD, s);
+  rmsnorm_dgain_kernel<<<(K + 7) / 8, 256, 0, s>>>(part, (T + NORM_BWD_TPB - 1) / NORM_BWD_TPB, K, dgain);
+  PQ_CHECK_LAUNCH("rmsnorm_dgain_kernel");
+  return PQ_OK;
 }
 
 // ------------------------------------------------------------------------------------------
