@@ -147,6 +147,24 @@ int pq_linear_bwd(const pq_linear_desc* desc, const void* dY, const void* X, con
                   void* dX, float* dW, float* dhpA, float* dhpB, float* dWr, float* dalpha_dbeta,
                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* The decoupled linear with its normalisation in front (Sec. 3.1 prints Y = (lambda/gamma) W Q(Norm(X)); App. B
+ * names RMSNorm): pq_linear_fwd / pq_linear_bwd applied to xhat = RMSNorm(X) * gain, with the normalisation fused
+ * into the activation quantiser (pq_rmsnorm_quant_fwd writes the codes into ctx; X is read from memory once) and the
+ * normalisation backward (pq_rmsnorm_bwd) chained behind the linear's dX.  The high-precision branch reads xhat.
+ *   X [T][K], gain [K] io_dtype; eps >= 0; W latent weights (PQ_W_MASTER); the other arguments as in pq_linear_fwd.
+ *   Backward: dX [T][K] io_dtype is the gradient with respect to X; dgain [K] fp32.
+ *   ctx / workspace: pq_linear_norm_ctx_bytes() / pq_linear_norm_workspace_bytes() bytes (ctx is required).
+ *   d_in <= 8192 (bf16) / 4096 (fp32) for the forward, 4096 / 2048 for the backward. */
+size_t pq_linear_norm_ctx_bytes(const pq_linear_desc* desc);
+size_t pq_linear_norm_workspace_bytes(const pq_linear_desc* desc);
+int pq_linear_norm_fwd(const pq_linear_desc* desc, const void* X, const void* gain, float eps, const void* W,
+                       const void* hpA, const void* hpB, const void* Wr, void* Y, void* ctx, size_t ctx_bytes,
+                       void* workspace, size_t workspace_bytes, void* stream);
+int pq_linear_norm_bwd(const pq_linear_desc* desc, const void* dY, const void* X, const void* gain, const void* W,
+                       const void* hpA, const void* hpB, const void* Wr, const void* ctx, size_t ctx_bytes, void* dX,
+                       float* dgain, float* dW, float* dhpA, float* dhpB, float* dWr, float* dalpha_dbeta,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
 /* The decoupled FFN (Sec. 3.2 FFN equation; Sec. 3.3):
  *     Y = beta * FFN_1bit(X) + alpha * sum_j gate_j(X) * FFN_e_j(X)
  * FFN_1bit: U = L_up(Q(X)), G = L_gate(Q(X)) (pure 1-bit linears, Sec. 3.1), Hd = silu(G) * U,

@@ -26,6 +26,7 @@ EXPORTS = [
     "pq_prof_reset", "pq_decode_workspace_bytes", "pq_decode_gemv", "pq_pack_tiled64_bytes", "pq_pack_retile64", "pq_ffn_ctx_bytes", "pq_ffn_workspace_bytes",
     "pq_ffn_fwd", "pq_ffn_bwd", "pq_glue_lincomb", "pq_glue_gather_rows",
     "pq_rmsnorm_quant_fwd", "pq_rmsnorm_bwd_workspace_bytes", "pq_rmsnorm_bwd",
+    "pq_linear_norm_ctx_bytes", "pq_linear_norm_workspace_bytes", "pq_linear_norm_fwd", "pq_linear_norm_bwd",
 ]
 
 
@@ -65,7 +66,8 @@ def lib():
         L.pq_prof_label.restype = C.c_char_p
         for name in ("pq_pack_workspace_bytes", "pq_linear_ctx_bytes", "pq_linear_workspace_bytes",
                      "pq_decode_workspace_bytes", "pq_pack_tiled64_bytes", "pq_ffn_ctx_bytes",
-                     "pq_ffn_workspace_bytes", "pq_rmsnorm_bwd_workspace_bytes"):
+                     "pq_ffn_workspace_bytes", "pq_rmsnorm_bwd_workspace_bytes", "pq_linear_norm_ctx_bytes",
+                     "pq_linear_norm_workspace_bytes"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -210,6 +212,32 @@ def linear_bwd(desc, dY, X, W, bufs, dX, dW, d_ab, A=None, B=None, Wr=None, dA=N
                                _p(bufs.ctx), C.c_size_t(bufs.ctx.numel()), _p(dX), _p(dW), _p(dA), _p(dB),
                                _p(dWr), _p(d_ab), _p(bufs.ws), C.c_size_t(bufs.ws.numel()), _stream()))
     return dX, dW, d_ab
+
+
+class LinearNormBuffers:
+    """ctx / workspace of the linear with its normalisation in front."""
+
+    def __init__(self, desc, device="cuda"):
+        nctx = lib().pq_linear_norm_ctx_bytes(C.byref(desc))
+        nws = lib().pq_linear_norm_workspace_bytes(C.byref(desc))
+        if nctx == 0 or nws == 0:
+            raise PQError(f"bad descriptor: {lib().pq_last_error_string().decode()}")
+        self.ctx = _bytes(nctx, device)
+        self.ws = _bytes(nws, device)
+
+
+def linear_norm_fwd(desc, X, gain, eps, W, Y, bufs, A=None, B=None, Wr=None):
+    _check(lib().pq_linear_norm_fwd(C.byref(desc), _p(X), _p(gain), C.c_float(eps), _p(W), _p(A), _p(B), _p(Wr), _p(Y),
+                                    _p(bufs.ctx), C.c_size_t(bufs.ctx.numel()), _p(bufs.ws), C.c_size_t(bufs.ws.numel()),
+                                    _stream()))
+    return Y
+
+
+def linear_norm_bwd(desc, dY, X, gain, W, bufs, dX, dgain, dW, d_ab, A=None, B=None, Wr=None, dA=None, dB=None, dWr=None):
+    _check(lib().pq_linear_norm_bwd(C.byref(desc), _p(dY), _p(X), _p(gain), _p(W), _p(A), _p(B), _p(Wr), _p(bufs.ctx),
+                                    C.c_size_t(bufs.ctx.numel()), _p(dX), _p(dgain), _p(dW), _p(dA), _p(dB), _p(dWr), _p(d_ab),
+                                    _p(bufs.ws), C.c_size_t(bufs.ws.numel()), _stream()))
+    return dX, dgain, dW, d_ab
 
 
 def prof_enable(on=True):

@@ -284,9 +284,11 @@ extern "C" size_t pq_linear_workspace_bytes(const pq_linear_desc* d) {
 // ---------------------------------------------------------------------------------------------
 // Forward: [stats -> pack] -> quantise -> int8 MFMA GEMM with de-quantising epilogue -> hp branch
 // ---------------------------------------------------------------------------------------------
-extern "C" int pq_linear_fwd(const pq_linear_desc* d, const void* X, const void* W_or_packed,
-                             const float* mu_lambda, const void* hpA, const void* hpB, const void* Wr, void* Y,
-                             void* ctx, size_t ctx_bytes, void* workspace, size_t workspace_bytes, void* stream) {
+// prequant: the quantised activations (codes, gamma, q/gamma) are already in ctx and X is what the
+// high-precision branch reads (the normalising entry point runs the fused quantiser first)
+static int linear_fwd_impl(const pq_linear_desc* d, const void* X, const void* W_or_packed,
+                           const float* mu_lambda, const void* hpA, const void* hpB, const void* Wr, void* Y,
+                           void* ctx, size_t ctx_bytes, void* workspace, size_t workspace_bytes, void* stream, bool prequant) {
   (void)Wr;
   if (int e = check_desc(d, false)) return e;
   const lin_layout L = make_layout(*d);
@@ -328,7 +330,8 @@ extern "C" int pq_linear_fwd(const pq_linear_desc* d, const void* X, const void*
   int8_t* Xq = (int8_t*)(ctx ? cx + L.Xq : ws + L.w_Xq);
   float* gamma = (float*)(ctx ? cx + L.gamma : ws + L.w_gamma);
   uint16_t* Xt = (ctx && bf16) ? (uint16_t*)(cx + L.Xt) : nullptr;
-  if (int e = pq_launch_quant_act(X, d->io_dtype, T, K, Xq, gamma, Xt, s)) return e;
+  if (!prequant)
+    if (int e = pq_launch_quant_act(X, d->io_dtype, T, K, Xq, gamma, Xt, s)) return e;
 
   // bf16 I/O with a live hp branch: the rank-r product H B^T is accumulated into the 1-bit GEMM's tile
   const bool fuse_hp = bf16 && r > 0 && d->alpha != 0.0f && pq_plan_gemm(0, T, N, K, true).splits == 1;
@@ -365,6 +368,12 @@ extern "C" int pq_linear_fwd(const pq_linear_desc* d, const void* X, const void*
     if (int err = pq_launch_gemm(engine, T, N, r, A, B, e, s, PQP_GEMM_HP_Y, sk_ws)) return err;
   }
   return PQ_OK;
+}
+
+extern "C" int pq_linear_fwd(const pq_linear_desc* d, const void* X, const void* W_or_packed,
+                             const float* mu_lambda, const void* hpA, const void* hpB, const void* Wr, void* Y,
+                             void* ctx, size_t ctx_bytes, void* workspace, size_t workspace_bytes, void* stream) {
+  return linear_fwd_impl(d, X, W_or_packed, mu_lambda, hpA, hpB, Wr, Y, ctx, ctx_bytes, workspace, workspace_bytes, stream, false);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -464,6 +473,88 @@ extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void
     }
   }
   return PQ_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// The linear with its normalisation (Sec. 3.1: Y = (lambda/gamma) W Q(Norm(X))): the fused normalising
+// quantiser writes codes, gamma and q/gamma straight into the linear's ctx, the high-precision branch reads
+// the stored normalised activations, and the backward chains the linear's dX into the normalisation backward.
+// ctx = [linear ctx][x_hat T*K][rstd T]; workspace = [linear workspace][d x_hat T*K][dgain partial rows].
+// ---------------------------------------------------------------------------------------------
+namespace {
+struct norm_layout { size_t Xn, rstd, ctx_total, dXn, part, ws_total; };
+norm_layout make_norm_layout(const pq_linear_desc& d, const lin_layout& L) {
+  norm_layout n;
+  const size_t T = d.tokens, K = d.d_in, es = esize(d.io_dtype);
+  cursor c; c.off = pq_align_up(L.ctx_total, 256);
+  n.Xn = c.take(T * K * es);
+  n.rstd = c.take(T * sizeof(float));
+  n.ctx_total = c.off;
+  cursor w; w.off = pq_align_up(L.ws_total, 256);
+  n.dXn = w.take(T * K * es);
+  n.part = w.take(pq_rmsnorm_bwd_scratch_bytes(d.tokens, d.d_in) + 256);
+  n.ws_total = w.off;
+  return n;
+}
+int check_norm(const pq_linear_desc* d, bool bwd) {
+  const int lim = d->io_dtype == PQ_F32 ? (bwd ? 2048 : 4096) : (bwd ? 4096 : 8192);
+  PQ_REQUIRE(d->d_in <= lim, PQ_ERR_SHAPE, "d_in=%d exceeds the row length the fused normalisation keeps in registers (%d)", d->d_in, lim);
+  return PQ_OK;
+}
+}  // namespace
+
+extern "C" size_t pq_linear_norm_ctx_bytes(const pq_linear_desc* d) {
+  if (check_desc(d, false) != PQ_OK) return 0;
+  return make_norm_layout(*d, make_layout(*d)).ctx_total;
+}
+extern "C" size_t pq_linear_norm_workspace_bytes(const pq_linear_desc* d) {
+  if (check_desc(d, false) != PQ_OK) return 0;
+  return make_norm_layout(*d, make_layout(*d)).ws_total;
+}
+
+extern "C" int pq_linear_norm_fwd(const pq_linear_desc* d, const void* X, const void* gain, float eps, const void* W,
+                                  const void* hpA, const void* hpB, const void* Wr, void* Y, void* ctx, size_t ctx_bytes,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (int e = check_desc(d, false)) return e;
+  if (int e = check_norm(d, false)) return e;
+  PQ_REQUIRE(d->w_kind == PQ_W_MASTER, PQ_ERR_BAD_ARG, "the normalising entry point takes latent weights");
+  PQ_REQUIRE(X && gain && ctx && workspace, PQ_ERR_BAD_ARG, "NULL buffer (X, gain, ctx or workspace)");
+  PQ_REQUIRE(eps >= 0.0f, PQ_ERR_BAD_ARG, "eps must not be negative");
+  PQ_REQUIRE(aligned16(X) && aligned16(gain) && aligned16(ctx), PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
+  const lin_layout L = make_layout(*d);
+  const norm_layout NL = make_norm_layout(*d, L);
+  PQ_REQUIRE(ctx_bytes >= NL.ctx_total, PQ_ERR_WORKSPACE, "ctx too small: %zu < %zu", ctx_bytes, NL.ctx_total);
+  PQ_REQUIRE(workspace_bytes >= NL.ws_total, PQ_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, NL.ws_total);
+  char* cx = (char*)ctx;
+  const bool bf16 = d->io_dtype == PQ_BF16;
+  void* Xn = cx + NL.Xn;
+  if (int e = pq_launch_rmsnorm_quant(X, gain, d->io_dtype, d->tokens, d->d_in, eps, Xn, (int8_t*)(cx + L.Xq), (float*)(cx + L.gamma),
+                                      bf16 ? (uint16_t*)(cx + L.Xt) : nullptr, (float*)(cx + NL.rstd), (hipStream_t)stream))
+    return e;
+  return linear_fwd_impl(d, Xn, W, nullptr, hpA, hpB, Wr, Y, ctx, L.ctx_total, workspace, L.ws_total, stream, true);
+}
+
+extern "C" int pq_linear_norm_bwd(const pq_linear_desc* d, const void* dY, const void* X, const void* gain, const void* W,
+                                  const void* hpA, const void* hpB, const void* Wr, const void* ctx, size_t ctx_bytes, void* dX,
+                                  float* dgain, float* dW, float* dhpA, float* dhpB, float* dWr, float* dalpha_dbeta,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (int e = check_desc(d, true)) return e;
+  if (int e = check_norm(d, true)) return e;
+  PQ_REQUIRE(X && gain && ctx && dX && dgain && workspace, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(aligned16(X) && aligned16(gain) && aligned16(dX) && aligned16(workspace), PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
+  const lin_layout L = make_layout(*d);
+  const norm_layout NL = make_norm_layout(*d, L);
+  PQ_REQUIRE(ctx_bytes >= NL.ctx_total, PQ_ERR_WORKSPACE, "ctx too small: %zu < %zu", ctx_bytes, NL.ctx_total);
+  PQ_REQUIRE(workspace_bytes >= NL.ws_total, PQ_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, NL.ws_total);
+  const char* cx = (const char*)ctx;
+  char* ws = (char*)workspace;
+  void* dXn = ws + NL.dXn;
+  if (int e = pq_linear_bwd(d, dY, cx + NL.Xn, W, hpA, hpB, Wr, ctx, L.ctx_total, dXn, dW, dhpA, dhpB, dWr, dalpha_dbeta, workspace,
+                            L.ws_total, stream))
+    return e;
+  float* part = (float*)(((uintptr_t)(ws + NL.part) + 255) & ~(uintptr_t)255);
+  return pq_launch_rmsnorm_bwd(dXn, X, gain, (const float*)(cx + NL.rstd), d->io_dtype, d->tokens, d->d_in, dX, dgain, part,
+                               (hipStream_t)stream);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -110,3 +110,68 @@ def test_rmsnorm_full_size_sampled_tokens():
     dx_ref, dg_ref = po.rmsnorm_bwd(dXn, X, g, rstd_all)
     assert relerr(host(dX)[rows], dx_ref[rows]) <= 2e-2
     assert relerr(host(dg), dg_ref) <= 1e-5
+
+
+# ---------------------------------------------------------------------------- the linear with its normalisation
+def _run_linear_norm(c, gain, eps, bf16, alpha, beta):
+    T, K, N, r = c["tokens"], c["d_in"], c["d_out"], c["hp_rank"]
+    desc = pq.make_desc(T, K, N, hp_rank=r, io_dtype=pq.PQ_BF16 if bf16 else pq.PQ_F32, alpha=alpha, beta=beta)
+    bufs = pq.LinearNormBuffers(desc)
+    X, W, dY, g = dev(c["X"], bf16), dev(c["W"], bf16), dev(c["dY"], bf16), dev(gain, bf16)
+    A = dev(c["A"], bf16) if r else None
+    B = dev(c["B"], bf16) if r else None
+    io = torch.bfloat16 if bf16 else torch.float32
+    Y = torch.empty((T, N), dtype=io, device="cuda")
+    dX = torch.empty((T, K), dtype=io, device="cuda")
+    dg = torch.empty((K,), dtype=torch.float32, device="cuda")
+    dW = torch.empty((N, K), dtype=torch.float32, device="cuda")
+    dA = torch.empty((r, K), dtype=torch.float32, device="cuda") if r else None
+    dB = torch.empty((N, r), dtype=torch.float32, device="cuda") if r else None
+    dab = torch.empty((2,), dtype=torch.float32, device="cuda")
+    pq.linear_norm_fwd(desc, X, g, eps, W, Y, bufs, A=A, B=B)
+    pq.linear_norm_bwd(desc, dY, X, g, W, bufs, dX, dg, dW, dab, A=A, B=B, dA=dA, dB=dB)
+    torch.cuda.synchronize()
+    out = dict(Y=host(Y), dX=host(dX), dg=host(dg), dW=host(dW), dab=host(dab))
+    if r:
+        out.update(dA=host(dA), dB=host(dB))
+    return out
+
+
+def _oracle_linear_norm(c, gain, eps, bf16, alpha, beta):
+    r = c["hp_rank"]
+    kw = dict(A=c["A"], B=c["B"]) if r else {}
+    f = po.rmsnorm_quant_fwd(c["X"], gain, eps, bf16=bf16)
+    fw = po.linear_fwd(f["Xn"], c["W"], alpha, beta, **kw)
+    gr = po.linear_bwd(c["dY"], f["Xn"], c["W"], alpha, beta, fw, **kw)
+    dXn = po._round_io(gr["dX"], bf16)                     # the library hands dX of the linear over in the I/O type
+    dx, dg = po.rmsnorm_bwd(dXn, c["X"], gain, f["rstd"])
+    dY = c["dY"].astype(np.float64)           # natural scales of the two scalar gradients (root-sum-square of their terms)
+    sb = max(abs(gr["dbeta"]), np.sqrt(((dY * fw["Y1_nobeta"]) ** 2).sum()))
+    sa = max(abs(gr["dalpha"]), np.sqrt(((dY * fw["Yhp"]) ** 2).sum()), 1e-30)
+    out = dict(Y=fw["Y"], dX=dx, dg=dg, dW=gr["dW"], dab=np.array([gr["dalpha"], gr["dbeta"]]), dab_scale=np.array([sa, sb]))
+    if r:
+        out.update(dA=gr["dA"], dB=gr["dB"])
+    return out
+
+
+@pytest.mark.parametrize("T,K,N,r,bf16", [(64, 256, 256, 16, False), (333, 544, 416, 24, True), (70, 96, 64, 0, True),
+                                         (300, 2048, 512, 0, False), (513, 1024, 768, 64, True)])
+def test_linear_norm_parity(T, K, N, r, bf16):
+    say(f"linear with normalisation T={T} K={K} N={N} r={r} bf16={bf16}")
+    c = wl.linear_case(1200 + T + r, T, K, N, hp_rank=r, bf16=bf16, outlier_frac=0.02, outlier_scale=10.0)
+    # un-normalised inputs: rows of very different length
+    scale = np.exp2(np.random.default_rng(T).integers(-3, 4, size=(T, 1))).astype(np.float32)
+    c["X"] = (c["X"] * scale).astype(np.float32)
+    rng = np.random.default_rng(77)
+    gain = wl.normal(rng, (K,), 0.1, False) + np.float32(1.0)
+    if bf16:
+        gain = torch.from_numpy(gain).to(torch.bfloat16).float().numpy()
+    got = _run_linear_norm(c, gain, 1e-6, bf16, 2.0, 0.2)
+    ref = _oracle_linear_norm(c, gain, 1e-6, bf16, 2.0, 0.2)
+    tol = TOL[bf16]
+    for k in ref:
+        if k == "dab_scale":
+            continue
+        e = float(np.max(np.abs(got[k] - ref[k]) / ref["dab_scale"])) if k == "dab" else relerr(got[k], ref[k])
+        say(f"  {k}: {e:.2e}")
+        assert e <= tol, k
