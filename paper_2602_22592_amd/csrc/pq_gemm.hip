@@ -587,9 +587,14 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
     };
     // Packed bits of B: a row's bits are fetched 32 bytes (CH steps) at a time, two lanes per row, so a chunk
     // (256 rows, 8 KB) is one 16-byte load instruction per wavefront every CH steps.
+    // The last chunk of a contraction range may be half a chunk (ranges are whole multiples of 128 indices):
+    // its missing half re-reads the start of the range into a place no step uses.
+    const int range_bytes = (ke - kb) >> 3;
     auto issue_bits = [&](int chunk, int buf) {
       const int row = min(n0 + wv * 32 + (lane >> 1), N - 1);
-      const char* g = (const char*)B.p + (size_t)row * B.ld + (kb >> 3) + chunk * 32 + (lane & 1) * 16;
+      int off = chunk * 32 + (lane & 1) * 16;
+      if (off + 16 > range_bytes) off = 0;
+      const char* g = (const char*)B.p + (size_t)row * B.ld + (kb >> 3) + off;
       __builtin_amdgcn_global_load_lds(g, PQ_LDS_PTR(smem + BITS0 + buf * (BN * 32) + wv * 1024), 16, 0, 0);
     };
 
@@ -719,7 +724,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
       using c2 = std::integral_constant<int, 2>;
       using c3 = std::integral_constant<int, 3>;
       bfrag fc, fn;
-      const int nch = nkt / CH;                         // whole chunks (the launcher checks the contraction range)
+      const int nch = (nkt + CH - 1) / CH;              // the last chunk may be half used
       if (nkt > 0) {
         issue_bits(0, 0);
         issue_bits(min(1, nch - 1), 1);
@@ -1083,9 +1088,10 @@ int launch_mfma_cfg(const pq_gemm_plan& pl, int M, int N, int K, const pq_operan
     if constexpr (kinds_ok) {
       const long aes = AK == PQ_SRC_KC8 ? 1 : 2;
       const bool a_ok = (A.ld * aes) % 16 == 0 && ((uintptr_t)A.p % 16) == 0 && (AK != PQ_SRC_KS16 || M % 8 == 0);
-      // packed rows are fetched 32 bytes (256 contraction indices) at a time
+      // packed rows are fetched in 16-byte halves of 32-byte chunks: ranges of whole multiples of 128 contraction
+      // indices, a split's range starting on a chunk
       constexpr bool b_bits = (BKIND == PQ_SRC_BITS8 || BKIND == PQ_SRC_BITS16);
-      const bool b_ok = b_bits ? (K % 256 == 0 && pl.kchunk % 256 == 0 && B.ld % 16 == 0 && ((uintptr_t)B.p % 16) == 0) :
+      const bool b_ok = b_bits ? (K % 128 == 0 && (pl.splits == 1 || pl.kchunk % 256 == 0) && B.ld % 16 == 0 && ((uintptr_t)B.p % 16) == 0) :
                         ((B.ld * 2) % 16 == 0 && ((uintptr_t)B.p % 16) == 0 && (BKIND != PQ_SRC_KS16 || N % 8 == 0));
       const bool stream = grp.mode == 0 && K % EPB == 0 && pl.kchunk % EPB == 0 && a_ok && b_ok && M >= 1 && N >= 1;
       if (stream) {
