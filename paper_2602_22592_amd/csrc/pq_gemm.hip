@@ -355,8 +355,9 @@ __device__ __forceinline__ void epi_vec8(const pq_epilogue& e, epi_state& st, in
 //     hands lane i of a 16-lane group element (i % 4) of the 8-byte row addressed by lane 4 e + i / 4,
 //     e = 0..3: with lane j addressing (t = j / 4, 4 columns at 4 (j % 4)) lane i receives four consecutive
 //     t of column i.
-//   * packed-bit B operands stay packed in LDS (direct 4-byte loads) and are expanded to MFMA operands in
-//     registers; the small stage this gives allows a ring of four stages instead of two.
+//   * packed-bit B operands stay packed in LDS (32-byte chunks of a row, one 16-byte direct load per
+//     wavefront and chunk, three chunk buffers) and are expanded to MFMA operands in registers, one dword
+//     behind each MFMA; with B that small the A operand gets a ring of four stages instead of two.
 // A wait on asm-issued reads names the registers it releases ("+v"), which orders their uses after it.
 // ---------------------------------------------------------------------------------------------
 typedef int pq_i32x2 __attribute__((ext_vector_type(2)));
@@ -429,9 +430,10 @@ struct pq_frag_set {
 // MFMA engine
 // ---------------------------------------------------------------------------------------------
 // One workgroup computes a BM x BN tile over the contraction range [z*kchunk, (z+1)*kchunk), z =
-// blockIdx.y.  LDS holds two stages of both operand tiles; per 128-byte step there is a single
-// barrier: after it, the registers prefetched during the previous step are written to the idle
-// stage, the loads of the step after next are issued, and the MFMAs run on the ready stage.
+// blockIdx.y.  Register-staged instantiations (DTL = false): LDS holds two stages of both operand tiles;
+// per 128-byte step there is a single barrier: after it, the registers prefetched during the previous
+// step are written to the idle stage, the loads of the step after next are issued, and the MFMAs run on
+// the ready stage.  Streaming instantiations (DTL = true) are described above.
 template <int BM, int BN, int WGM, int WGN, int KB, bool FAST, bool INT8, int AK, int BKIND, int AK2 = -1, int BK2 = -1, bool DTL = false>
 __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N, int K, pq_operand A,
                                                                      pq_operand B, pq_epilogue epi,
