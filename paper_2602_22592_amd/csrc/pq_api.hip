@@ -417,7 +417,6 @@ extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void
     e.dot_comp = H; e.ld_comp = r; e.comp_kind = ok; e.partials = red_a;
     if (int err = pq_launch_gemm(engine, T, r, N, A, B, e, s, PQP_GEMM_DH, sk_ws)) return err;
   }
-  if (int err = pq_launch_reduce_partials(red_a, (T > 0 && r > 0) ? L.n_red_a : 0, 1.0f, nullptr, dalpha_dbeta, s)) return err;
 
   if (T > 0) {  // dX = beta*lambda * dY S  (+ dH A, fused into the same tile for bf16 I/O)
     pq_operand A{dY, N, KC, nullptr};
@@ -454,7 +453,9 @@ extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void
       e.maskW = W; e.mask_kind = ok; e.mu_dev = mulam; e.tau = d->ste_tau;
     }
     if (int err = pq_launch_gemm(engine, N, K, T, A, B, e, s, PQP_GEMM_DW, sk_ws)) return err;
-    if (int err = pq_launch_reduce_partials(red_b, L.n_red_b, 1.0f, mulam + 1, dalpha_dbeta + 1, s)) return err;
+    // d alpha and d beta: both fixed-order sums of per-workgroup partials, one launch
+    if (int err = pq_launch_reduce_partials2(red_a, (T > 0 && r > 0) ? L.n_red_a : 0, 1.0f, nullptr, dalpha_dbeta, red_b, L.n_red_b, 1.0f,
+                                             mulam + 1, dalpha_dbeta + 1, s)) return err;
   }
   if (r > 0) {
     {  // dB = alpha * dY^T H

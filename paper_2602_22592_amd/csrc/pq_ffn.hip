@@ -224,7 +224,6 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
     e.C = dW_down; e.ldc = F; e.out_kind = PQ_OUT_F32; e.scale = d->beta;
     e.sign_bytes = (const uint8_t*)(cx + L.P_down); e.ld_sign = F / 8; e.partials = red_b;
     if (int err = pq_launch_gemm(0, D, F, T, A, B, e, s, PQP_GEMM_DW, sk)) return err;
-    if (int err = pq_launch_reduce_partials(red_b, L.n_red_b, 1.0f, ml_down + 1, dalpha_dbeta + 1, s)) return err;
   }
   if (T > 0) {
     {  // dHd = beta * lambda_d * dY S_d
@@ -267,7 +266,9 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
   float* rd = (float*)(ws + L.rd);
   if (int e = pq_launch_gather_rows(dY, perm, k, S, D, ws + L.dYp, s)) return e;
   if (int e = pq_launch_rowdot(ws + L.dYp, cx + L.Ys, perm, gate, S, D, rd, red_a, s)) return e;
-  if (int e = pq_launch_reduce_partials(red_a, S > 0 ? L.n_red_a : 0, 1.0f, nullptr, dalpha_dbeta, s)) return e;
+  // d alpha (row dots above) and d beta (partials of the dW_down GEMM): one launch for both fixed-order sums
+  if (int e = pq_launch_reduce_partials2(red_a, S > 0 ? L.n_red_a : 0, 1.0f, nullptr, dalpha_dbeta, red_b, L.n_red_b, 1.0f, ml_down + 1,
+                                         dalpha_dbeta + 1, s)) return e;
   pq_gemm_group g1{offsets, E, 1, 0, 0, S};
   pq_gemm_group g2{offsets, E, 2, 0, 0, S};
   if (S > 0) {  // da = dYp Down_e  (scaled by alpha*gate inside the activation backward)

@@ -40,6 +40,8 @@ int pq_launch_router(const void* X, const void* Wr, int dtype, int T, int K, int
 // out[0] = factor * sum(partials[0..n)) (+ optionally factor2 read from device: *dev_factor)
 int pq_launch_reduce_partials(const double* partials, int n, float factor, const float* dev_factor,
                               float* out, hipStream_t s);
+int pq_launch_reduce_partials2(const double* pa, int na, float fa, const float* dfa, float* oa, const double* pb, int nb, float fb,
+                               const float* dfb, float* ob, hipStream_t s);
 
 // ---- pq_gemm.hip --------------------------------------------------------------------------
 enum pq_src_kind {

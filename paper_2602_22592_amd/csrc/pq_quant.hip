@@ -645,24 +645,35 @@ int pq_launch_router(const void* X, const void* Wr, int dtype, int T, int K, int
 // ------------------------------------------------------------------------------------------
 // Fixed-order final reduction of per-block partial sums.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const double* __restrict__ partials, int n,
-                                                              float factor, const float* dev_factor,
-                                                              float* __restrict__ out) {
+struct reduce_job { const double* partials; int n; float factor; const float* dev_factor; float* out; };
+
+__global__ __launch_bounds__(256) void reduce_partials_kernel(reduce_job j0, reduce_job j1) {   // one workgroup per job
   __shared__ double red[4];
+  const reduce_job j = blockIdx.x == 0 ? j0 : j1;
   double s = 0.0;
-  for (int i = threadIdx.x; i < n; i += 256) s += partials[i];
+  for (int i = threadIdx.x; i < j.n; i += 256) s += j.partials[i];
   double t = block_sum_d<256>(s, red);
   if (threadIdx.x == 0) {
-    double f = (double)factor;
-    if (dev_factor) f *= (double)(*dev_factor);
-    out[0] = (float)(t * f);
+    double f = (double)j.factor;
+    if (j.dev_factor) f *= (double)(*j.dev_factor);
+    j.out[0] = (float)(t * f);
   }
 }
 
 int pq_launch_reduce_partials(const double* partials, int n, float factor, const float* dev_factor,
                               float* out, hipStream_t s) {
   pq_prof_scope prof(PQP_REDUCE, s);
-  reduce_partials_kernel<<<1, 256, 0, s>>>(partials, n, factor, dev_factor, out);
+  const reduce_job j{partials, n, factor, dev_factor, out};
+  reduce_partials_kernel<<<1, 256, 0, s>>>(j, j);
+  PQ_CHECK_LAUNCH("reduce_partials_kernel");
+  return PQ_OK;
+}
+
+// two independent reductions in one launch
+int pq_launch_reduce_partials2(const double* pa, int na, float fa, const float* dfa, float* oa, const double* pb, int nb, float fb,
+                               const float* dfb, float* ob, hipStream_t s) {
+  pq_prof_scope prof(PQP_REDUCE, s);
+  reduce_partials_kernel<<<2, 256, 0, s>>>(reduce_job{pa, na, fa, dfa, oa}, reduce_job{pb, nb, fb, dfb, ob});
   PQ_CHECK_LAUNCH("reduce_partials_kernel");
   return PQ_OK;
 }
