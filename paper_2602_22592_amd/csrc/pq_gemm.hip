@@ -906,12 +906,23 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
   }
   __syncthreads();  // all MFMA operand reads are done: LDS is reused below
 
-  // Optional second contraction (rank-r branch): rescale the first accumulator, then run a short
-  // un-pipelined bf16 loop over K2 into the same tile.
+  // Optional second contraction (rank-r branch): rescale the first accumulator, then run a short bf16 loop
+  // over K2 into the same tile.  The first operand tiles are requested before the rescale arithmetic and the
+  // tiles of step s+1 before the MFMAs of step s (two LDS stages), so the memory latencies overlap with work
+  // instead of standing in a row.
   constexpr bool PH2 = (AK2 >= 0);
   constexpr bool ACC_INT = INT8 && !PH2;
   f32x16_t accf[PH2 ? TM : 1][PH2 ? TN : 1];
   if constexpr (PH2) {
+    constexpr int KS2 = KB / 2;                      // contraction elements per step
+    tile_stage<AK2, BM, NT, KB, FAST> sa2;
+    tile_stage<BK2, BN, NT, KB, FAST> sb2;
+    sa2.setup(ph2.A2, m0, M, tid);
+    sb2.setup(ph2.B2, n0, N, tid);
+    if (ph2.K2 > 0) {
+      sa2.load(ph2.A2, 0, ph2.K2);
+      sb2.load(ph2.B2, 0, ph2.K2);
+    }
     const float sc1 = ph2.dev_scale1 ? __fmul_rn(ph2.scale1, *ph2.dev_scale1) : ph2.scale1;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -926,19 +937,18 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
           accf[i][j][v] = (float)e1 * sr;
         }
       }
-    tile_stage<AK2, BM, NT, KB, FAST> sa2;
-    tile_stage<BK2, BN, NT, KB, FAST> sb2;
-    sa2.setup(ph2.A2, m0, M, tid);
-    sb2.setup(ph2.B2, n0, N, tid);
-    for (int k2 = 0; k2 < ph2.K2; k2 += KB / 2) {
-      sa2.load(ph2.A2, k2, ph2.K2);
-      sb2.load(ph2.B2, k2, ph2.K2);
-      sa2.store(smem, tid);
-      sb2.store(smem + BM * KB, tid);
-      __syncthreads();
+    int st2 = 0;
+    for (int k2 = 0; k2 < ph2.K2; k2 += KS2) {
+      unsigned char* stage = smem + st2 * STAGE;
+      sa2.store(stage, tid);
+      sb2.store(stage + BM * KB, tid);
+      const int kn = (k2 + KS2 < ph2.K2) ? k2 + KS2 : k2;   // the last step re-requests itself (harmless, never stored)
+      sa2.load(ph2.A2, kn, ph2.K2);
+      sb2.load(ph2.B2, kn, ph2.K2);
+      __syncthreads();                               // this stage is complete; the other one is free again
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) {
-        read_frags(smem, ks, af[0], bf[0]);
+        read_frags(stage, ks, af[0], bf[0]);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -946,8 +956,9 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
             accf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[0][i]),
                                                                  __builtin_bit_cast(bf16x8_t, bf[0][j]), accf[i][j], 0, 0, 0);
       }
-      __syncthreads();
+      st2 ^= 1;
     }
+    __syncthreads();
   }
 
   // Epilogue: each wavefront passes its 32x32 accumulator blocks through a private LDS patch
