@@ -111,12 +111,11 @@ __global__ __launch_bounds__(256) void swiglu_quant_kernel(const uint16_t* __res
   if constexpr (NV > 0) {
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      const int c = i * 64 + lane;
-      if (c < nvec) {
-        eval(c, hd[i]);
+      // unconditional (lanes past the end repeat the last vector, which cannot change the maximum): loads under
+      // a branch would each get a wait of their own
+      eval(min(i * 64 + lane, nvec - 1), hd[i]);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(hd[i][j]));
-      }
+      for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(hd[i][j]));
     }
   } else {
     for (int c = lane; c < nvec; c += 64) {

@@ -78,16 +78,16 @@ __global__ __launch_bounds__(256) void quant_act_kernel(const T* __restrict__ X,
   float amax = 0.0f;
   uint4 cache[NV > 0 ? NV : 1];
   if constexpr (NV > 0) {
+    // unconditional loads (lanes past the end re-read the last vector, which cannot change the maximum): a load
+    // under a branch gets a wait of its own and the row would arrive one memory latency per vector
+#pragma unroll
+    for (int i = 0; i < NV; ++i) cache[i] = xr[min(i * 64 + lane, nvec - 1)];
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      int c = i * 64 + lane;
-      if (c < nvec) {
-        cache[i] = xr[c];
-        float f[V];
-        vec16<T>::unpack(cache[i], f);
+      float f[V];
+      vec16<T>::unpack(cache[i], f);
 #pragma unroll
-        for (int j = 0; j < V; ++j) amax = fmaxf(amax, fabsf(f[j]));
-      }
+      for (int j = 0; j < V; ++j) amax = fmaxf(amax, fabsf(f[j]));
     }
   } else {
     for (int c = lane; c < nvec; c += 64) {
@@ -165,13 +165,18 @@ __global__ __launch_bounds__(256) void rmsnorm_quant_kernel(const T* __restrict_
   const uint4* xr = reinterpret_cast<const uint4*>(X + (size_t)row * K);
   const uint4* gr = reinterpret_cast<const uint4*>(gain);
   const int nvec = K / V;
-  uint4 cache[NV];
+  uint4 cache[NV], gc[NV];
   double ss = 0.0;
+  // unconditional loads (clamped index) so that all of them are in flight together
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    const int c = i * 64 + lane;
-    if (c < nvec) {
-      cache[i] = xr[c];
+    const int cc = min(i * 64 + lane, nvec - 1);
+    cache[i] = xr[cc];
+    gc[i] = gr[cc];
+  }
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    if (i * 64 + lane < nvec) {
       float f[V];
       vec16<T>::unpack(cache[i], f);
 #pragma unroll
@@ -187,7 +192,7 @@ __global__ __launch_bounds__(256) void rmsnorm_quant_kernel(const T* __restrict_
     if (c < nvec) {
       float f[V], g[V];
       vec16<T>::unpack(cache[i], f);
-      vec16<T>::unpack(gr[c], g);
+      vec16<T>::unpack(gc[i], g);
 #pragma unroll
       for (int j = 0; j < V; ++j) f[j] = __fmul_rn(__fmul_rn(f[j], r), g[j]);
       cache[i] = pack_io<T>(f);                      // the stored x_hat; everything below reads it back
