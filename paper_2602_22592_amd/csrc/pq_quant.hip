@@ -578,16 +578,23 @@ __global__ __launch_bounds__(256) void router_kernel(const T* __restrict__ X, co
   double acc[EMAX];
 #pragma unroll
   for (int e = 0; e < EMAX; ++e) acc[e] = 0.0;
+  // Router rows are requested unconditionally, eight at a time (rows past E repeat the last one and their sums
+  // are never used): a load under a branch gets a wait of its own, which made this loop a chain of latencies.
   for (int c = lane; c < nvec; c += 64) {
     float xf[V];
-    vec16<T>::unpack(xr[c], xf);
+    const uint4 xv = xr[c];
 #pragma unroll
-    for (int e = 0; e < EMAX; ++e) {
-      if (e < E) {
+    for (int e0 = 0; e0 < EMAX; e0 += 8) {
+      uint4 wv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) wv[u] = reinterpret_cast<const uint4*>(Wr + (size_t)min(e0 + u, E - 1) * K)[c];
+      if (e0 == 0) vec16<T>::unpack(xv, xf);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
         float wf[V];
-        vec16<T>::unpack(reinterpret_cast<const uint4*>(Wr + (size_t)e * K)[c], wf);
+        vec16<T>::unpack(wv[u], wf);
 #pragma unroll
-        for (int j = 0; j < V; ++j) acc[e] += (double)xf[j] * (double)wf[j];
+        for (int j = 0; j < V; ++j) acc[e0 + u] += (double)xf[j] * (double)wf[j];
       }
     }
   }
