@@ -285,8 +285,9 @@ __device__ __forceinline__ void load_io8(const void* p, int kind, size_t i, floa
 }
 
 template <bool INT8>
+// row_scale: sc0 / row_div[m] when the caller has it at hand (NaN = not given, it is formed here)
 __device__ __forceinline__ void epi_vec8(const pq_epilogue& e, epi_state& st, int m, int n, const uint4& r0,
-                                         const uint4& r1) {
+                                         const uint4& r1, float row_scale = __builtin_nanf("")) {
   const size_t ci = (size_t)m * e.ldc + n;
   if (e.out_kind == PQ_OUT_I32) {
     *reinterpret_cast<uint4*>((int*)e.C + ci) = r0;
@@ -313,7 +314,7 @@ __device__ __forceinline__ void epi_vec8(const pq_epilogue& e, epi_state& st, in
     for (int j = 0; j < 8; ++j) st.psum += ((byte >> j) & 1u) ? (double)acc[j] : -(double)acc[j];
   }
   float sc = st.sc0;
-  if (e.row_div) sc = sc / e.row_div[m];
+  if (e.row_div) sc = (row_scale == row_scale) ? row_scale : sc / e.row_div[m];
   float val[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) val[j] = __fmul_rn(sc, acc[j]);
@@ -426,6 +427,16 @@ struct pq_frag_set {
   }
 };
 
+#ifdef PQ_VAR_TIMELINE
+__device__ unsigned long long pq_dbg_ts[2048 * 8];
+#define PQ_TL(i) do { if (BKIND == PQ_VAR_TIMELINE && DTL && threadIdx.x == 0) pq_dbg_ts[(blockIdx.x + gridDim.x * blockIdx.y) * 8 + (i)] = wall_clock64(); } while (0)
+extern "C" int pq_debug_read_timeline(unsigned long long* host, int n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(pq_dbg_ts), sizeof(unsigned long long) * n);
+}
+#else
+#define PQ_TL(i) do { } while (0)
+#endif
+
 // ---------------------------------------------------------------------------------------------
 // MFMA engine
 // ---------------------------------------------------------------------------------------------
@@ -440,6 +451,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
                                                                      int nbn, int total_tiles, int kchunk,
                                                                      float* splitk_part, pq_gemm_group grp,
                                                                      pq_phase2 ph2) {
+  PQ_TL(0);
   constexpr int NT = WGM * WGN * 64;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -453,6 +465,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
   constexpr int SMEM_BYTES = BBITS ? 4 * BM * KB + 3 * BN * 32 : 2 * STAGE;
   __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
   __shared__ double red[NT / 64];
+  __shared__ float rowscale[BM];                     // per-row scale of the tile (one division per row, not per element)
 
   // XCD-aware tile order: consecutive workgroups go to different XCDs, so give each XCD a
   // contiguous range of tiles (its L2 then sees the same A row-panel for a run of tiles).
@@ -734,6 +747,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
         for (int s = 0; s < NSTAGE; ++s) issue(min(s, nkt - 1), s);
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 1) * IPW) : "memory");
         asm volatile("s_barrier" ::: "memory");
+        PQ_TL(1);
         read_bits(0u);
         read_a(G0, c0{}, 0u);
         asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(bq0), "+v"(bq1));
@@ -904,6 +918,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
       read_frags(nxt, 0, af[0], bf[0]);
     }
   }
+  PQ_TL(2);
   __syncthreads();  // all MFMA operand reads are done: LDS is reused below
 
   // Optional second contraction (rank-r branch): rescale the first accumulator, then run a short bf16 loop
@@ -924,13 +939,16 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
       sb2.load(ph2.B2, 0, ph2.K2);
     }
     const float sc1 = ph2.dev_scale1 ? __fmul_rn(ph2.scale1, *ph2.dev_scale1) : ph2.scale1;
+    if (ph2.row_div1) {                              // uniform: one divisor load and one division per row of the tile
+      for (int r = tid; r < BM; r += NT) rowscale[r] = sc1 / ph2.row_div1[min(m0 + r, M - 1)];
+      __syncthreads();
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        float sr = sc1;
-        if (ph2.row_div1) sr = sc1 / ph2.row_div1[m < M ? m : M - 1];
+        const int rl = wm0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const float sr = ph2.row_div1 ? rowscale[rl] : sc1;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           const auto e1 = acc[i][j][v];
@@ -961,6 +979,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
     __syncthreads();
   }
 
+  PQ_TL(3);
   // Epilogue: each wavefront passes its 32x32 accumulator blocks through a private LDS patch
   // (row stride 36 words: conflict-free both ways) so that a lane ends up with 8 consecutive
   // columns of one row and global loads/stores are 16 bytes wide.  With a split contraction the
@@ -968,6 +987,11 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
   epi_state st;
   epi_begin(epi, st);
   float* slab = splitk_part ? splitk_part + (size_t)split * Mtot * N : nullptr;
+  const bool row_scaled = !slab && epi.row_div != nullptr;   // uniform
+  if (row_scaled) {
+    for (int r = tid; r < BM; r += NT) rowscale[r] = st.sc0 / epi.row_div[min(m0 + r, M - 1)];
+    __syncthreads();
+  }
   uint32_t* stg = reinterpret_cast<uint32_t*>(smem) + wave * (32 * 36);
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -999,7 +1023,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
             *reinterpret_cast<uint4*>(slab + (size_t)m * N + n) = r0;
             *reinterpret_cast<uint4*>(slab + (size_t)m * N + n + 4) = r1;
           } else {
-            epi_vec8<ACC_INT>(epi, st, m, n, r0, r1);
+            epi_vec8<ACC_INT>(epi, st, m, n, r0, r1, row_scaled ? rowscale[m - m0] : __builtin_nanf(""));
           }
         }
       }
@@ -1007,6 +1031,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
       __builtin_amdgcn_wave_barrier();
     }
   if (!slab) epi_end<NT>(epi, st, red, blockIdx.x);
+  PQ_TL(4);
 }
 
 // Second stage of a split contraction: sum the slabs in index order (deterministic), then apply
