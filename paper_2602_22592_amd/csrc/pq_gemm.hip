@@ -427,16 +427,6 @@ struct pq_frag_set {
   }
 };
 
-#ifdef PQ_VAR_TIMELINE
-__device__ unsigned long long pq_dbg_ts[2048 * 8];
-#define PQ_TL(i) do { if (BKIND == PQ_VAR_TIMELINE && DTL && threadIdx.x == 0) pq_dbg_ts[(blockIdx.x + gridDim.x * blockIdx.y) * 8 + (i)] = wall_clock64(); } while (0)
-extern "C" int pq_debug_read_timeline(unsigned long long* host, int n) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(pq_dbg_ts), sizeof(unsigned long long) * n);
-}
-#else
-#define PQ_TL(i) do { } while (0)
-#endif
-
 // ---------------------------------------------------------------------------------------------
 // MFMA engine
 // ---------------------------------------------------------------------------------------------
@@ -451,7 +441,6 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
                                                                      int nbn, int total_tiles, int kchunk,
                                                                      float* splitk_part, pq_gemm_group grp,
                                                                      pq_phase2 ph2) {
-  PQ_TL(0);
   constexpr int NT = WGM * WGN * 64;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -747,7 +736,6 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
         for (int s = 0; s < NSTAGE; ++s) issue(min(s, nkt - 1), s);
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 1) * IPW) : "memory");
         asm volatile("s_barrier" ::: "memory");
-        PQ_TL(1);
         read_bits(0u);
         read_a(G0, c0{}, 0u);
         asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(bq0), "+v"(bq1));
@@ -918,7 +906,6 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
       read_frags(nxt, 0, af[0], bf[0]);
     }
   }
-  PQ_TL(2);
   __syncthreads();  // all MFMA operand reads are done: LDS is reused below
 
   // Optional second contraction (rank-r branch): rescale the first accumulator, then run a short bf16 loop
@@ -978,8 +965,6 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
     }
     __syncthreads();
   }
-
-  PQ_TL(3);
   // Epilogue: each wavefront passes its 32x32 accumulator blocks through a private LDS patch
   // (row stride 36 words: conflict-free both ways) so that a lane ends up with 8 consecutive
   // columns of one row and global loads/stores are 16 bytes wide.  With a split contraction the
@@ -1031,7 +1016,6 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
       __builtin_amdgcn_wave_barrier();
     }
   if (!slab) epi_end<NT>(epi, st, red, blockIdx.x);
-  PQ_TL(4);
 }
 
 // Second stage of a split contraction: sum the slabs in index order (deterministic), then apply
