@@ -17,7 +17,8 @@ Readings taken where the paper is silent or garbled (each also listed in the des
   * lambda is the mean of |W| on the raw (un-centred) weights, as printed.
   * RoundClip bounds: gamma = 128/absmax, round half to even, clamp to [-128, 127].
   * one gamma per token (row of X); a zero row uses max(absmax, 1e-5).
-  * the high-precision branch reads the raw X (not Q(X)) and keeps 16-bit weights (Sec. 4.6 FP16 variant).
+  * the high-precision branch reads the raw X (not Q(X)) and keeps 16-bit weights (Sec. 4.6 FP16 variant);
+    its INT8 form (Sec. 3.2) quantises the rows of both factors and the hidden state like activations.
   * router: logits on raw X, top-k on logits (ties -> lower index), gates = softmax over all experts,
     not renormalised.
   * STE: identity through Sign and Q; mu, lambda, gamma carry no gradient.
@@ -448,6 +449,48 @@ def rmsnorm_bwd(dXn, X, g, rstd):
     c = np.mean(gd * u, axis=1, keepdims=True)
     dx = s * (gd - u * c)
     return dx, dg
+
+
+# ----------------------------------------------------------------------------------------------
+# Sec. 3.2: the high-precision branch in its INT8 form ("8-bit weights are quantized identically to 8-bit
+# activations"), for the two-factor branch B (A x) of a single linear
+# ----------------------------------------------------------------------------------------------
+def _dequant_scale(acc, g_row, g_col):
+    """fl32(fl32(fl32(1 / g_row) * fl32(acc)) / g_col): the order in which the library removes the two scales
+    from an integer accumulator (row scale as one reciprocal per row, column scale by division)."""
+    s = (F32(1.0) / g_row.astype(F32)).astype(F32)
+    v = (s[:, None] * acc.astype(F32)).astype(F32)
+    return (v / g_col.astype(F32)[None, :]).astype(F32)
+
+
+def hp_int8_fwd(X, A, B, bf16=False, q_gamma=None):
+    """Y_hp = B~ Q(A~ Q(x)) with every factor on the INT8 grid of Sec. 3.1: x per token, the rows of A [r, n]
+    and of B [m, r] per row (their output channel), and the hidden state per token again.  Both products are
+    exact integer accumulations; the hidden state is stored in the I/O type before it is re-quantised.
+    `q_gamma` passes in codes and gamma of X that the caller already has (the 1-bit branch's)."""
+    q_x, g_x = quant_act(X) if q_gamma is None else q_gamma
+    q_a, g_a = quant_act(np.asarray(A, dtype=F32))
+    q_b, g_b = quant_act(np.asarray(B, dtype=F32))
+    acc1 = q_x.astype(np.int64) @ q_a.astype(np.int64).T
+    H = _round_io(_dequant_scale(acc1, g_x, g_a), bf16)
+    q_h, g_h = quant_act(H)
+    acc2 = q_h.astype(np.int64) @ q_b.astype(np.int64).T
+    Yhp = _dequant_scale(acc2, g_h, g_b)
+    return dict(q_x=q_x, g_x=g_x, q_a=q_a, g_a=g_a, q_b=q_b, g_b=g_b, acc1=acc1, H=H, q_h=q_h, g_h=g_h, acc2=acc2,
+                Yhp=Yhp)
+
+
+def hp_int8_bwd(dYhp, fwd):
+    """STE backward of hp_int8_fwd (App. B.1): every quantiser is differentiated as identity, so each product
+    is differentiated with the de-quantised factors it actually multiplied: with X~ = q_x / g_x, A~, B~, H~
+    likewise,  dH = dY B~,  dB = dY^T H~,  dA = dH^T X~,  dX = dH A~.  fp64."""
+    d = np.asarray(dYhp, dtype=F64)
+    Xt = fwd["q_x"].astype(F64) / fwd["g_x"].astype(F64)[:, None]
+    At = fwd["q_a"].astype(F64) / fwd["g_a"].astype(F64)[:, None]
+    Bt = fwd["q_b"].astype(F64) / fwd["g_b"].astype(F64)[:, None]
+    Ht = fwd["q_h"].astype(F64) / fwd["g_h"].astype(F64)[:, None]
+    dH = d @ Bt
+    return dict(dH=dH, dB=d.T @ Ht, dA=dH.T @ Xt, dX=dH @ At)
 
 
 def bits_per_weight(frac_1bit, frac_8bit):

@@ -589,3 +589,87 @@ def test_rmsnorm_backward_by_finite_differences_and_orthogonality():
     # linear in the upstream gradient
     dx2, dg2 = po.rmsnorm_bwd(2.0 * C, X32, g32, 1.0 / np.sqrt(ms[:, 0] + eps))
     assert np.allclose(dx2, 2.0 * dx, rtol=1e-14) and np.allclose(dg2, 2.0 * dg, rtol=1e-14)
+
+
+# ------------------------------------------------------------------------------------------------
+# INT8 form of the high-precision branch (Sec. 3.2)
+# ------------------------------------------------------------------------------------------------
+def test_hp_int8_integer_grid_inputs_give_the_exact_product():
+    """Rows that already sit on the INT8 grid with gamma = 1 (most negative entry -128) are their own codes,
+    so the first product must be the exact integer matrix product, entry by entry (Python integers)."""
+    rng = np.random.default_rng(5)
+    T, n, r, m = 5, 32, 8, 6
+    X = rng.integers(-100, 100, size=(T, n)).astype(np.float32); X[:, 0] = -128
+    A = rng.integers(-100, 100, size=(r, n)).astype(np.float32); A[:, 1] = -128
+    B = rng.integers(-100, 100, size=(m, r)).astype(np.float32); B[:, 2] = -128
+    f = po.hp_int8_fwd(X, A, B)
+    assert np.all(f["g_x"] == 1.0) and np.all(f["g_a"] == 1.0) and np.all(f["g_b"] == 1.0)
+    assert np.array_equal(f["q_x"], X.astype(np.int8)) and np.array_equal(f["q_a"], A.astype(np.int8))
+    for t in range(T):
+        for j in range(r):
+            assert int(f["acc1"][t, j]) == sum(int(X[t, k]) * int(A[j, k]) for k in range(n))
+            assert float(f["H"][t, j]) == float(f["acc1"][t, j])          # below 2^24: exact in fp32
+    for t in range(T):
+        for i in range(m):
+            assert int(f["acc2"][t, i]) == sum(int(f["q_h"][t, j]) * int(f["q_b"][i, j]) for j in range(r))
+    # the hidden state is re-quantised per token: its codes reach 127 or -128 in every row
+    assert np.all(np.max(np.abs(f["q_h"].astype(np.int32)), axis=1) >= 127)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_hp_int8_stays_within_the_quantisation_error_of_the_float_branch(bf16):
+    rng = np.random.default_rng(9)
+    T, n, r, m = 48, 256, 32, 64
+    X = wl.activations(rng, T, n, bf16=bf16)
+    A = wl.normal(rng, (r, n), 0.02, bf16)
+    B = wl.normal(rng, (m, r), 0.02, bf16)
+    f = po.hp_int8_fwd(X, A, B, bf16=bf16)
+    ref = (X.astype(np.float64) @ A.astype(np.float64).T) @ B.astype(np.float64).T
+    # three INT8 grids with uniform rounding error of 1/256 of each row maximum, averaged over 256- and 32-term sums
+    err = np.abs(f["Yhp"] - ref).max() / np.abs(ref).max()
+    assert err < 0.05
+    # codes and gammas of X are the quantiser's; passing them in changes nothing
+    q, g = po.quant_act(X)
+    f2 = po.hp_int8_fwd(X, A, B, bf16=bf16, q_gamma=(q, g))
+    assert np.array_equal(f2["Yhp"], f["Yhp"])
+    # scaling a row of A by a power of two scales its gamma and leaves codes and result bits unchanged otherwise
+    A2 = A.copy(); A2[3] *= 4.0
+    f3 = po.hp_int8_fwd(X, A2, B, bf16=False)
+    f1 = po.hp_int8_fwd(X, A, B, bf16=False)
+    assert np.array_equal(f3["q_a"], f1["q_a"]) and f3["g_a"][3] * 4.0 == f1["g_a"][3]
+    assert np.array_equal(f3["H"][:, 3], (f1["H"][:, 3] * np.float32(4.0)))
+
+
+def test_hp_int8_backward_is_the_gradient_of_the_dequantised_bilinear_form():
+    """STE: with the codes frozen, Y = (X~ A~^T -> H~) B~^T is bilinear in (H~, B~) and (X~, A~); the backward
+    must equal the derivatives of <C, H' B'^T> and <dH, X' A'^T> at the de-quantised points (central
+    differences are exact for bilinear forms up to rounding)."""
+    rng = np.random.default_rng(13)
+    T, n, r, m = 6, 32, 8, 5
+    X = rng.standard_normal((T, n)).astype(np.float32)
+    A = (0.1 * rng.standard_normal((r, n))).astype(np.float32)
+    B = (0.1 * rng.standard_normal((m, r))).astype(np.float32)
+    C = rng.standard_normal((T, m))
+    f = po.hp_int8_fwd(X, A, B)
+    g = po.hp_int8_bwd(C, f)
+    Xt = f["q_x"].astype(np.float64) / f["g_x"].astype(np.float64)[:, None]
+    At = f["q_a"].astype(np.float64) / f["g_a"].astype(np.float64)[:, None]
+    Bt = f["q_b"].astype(np.float64) / f["g_b"].astype(np.float64)[:, None]
+    Ht = f["q_h"].astype(np.float64) / f["g_h"].astype(np.float64)[:, None]
+    h = 1e-3
+    L2 = lambda Hm, Bm: float(np.sum(C * (Hm @ Bm.T)))
+    L1 = lambda Xm, Am: float(np.sum(g["dH"] * (Xm @ Am.T)))
+    for (i, j) in [(0, 0), (4, 7), (2, 3)]:
+        E = np.zeros_like(Bt); E[i, j] = h
+        assert abs((L2(Ht, Bt + E) - L2(Ht, Bt - E)) / (2 * h) - g["dB"][i, j]) < 1e-9
+    for (t, j) in [(0, 0), (5, 7)]:
+        E = np.zeros_like(Ht); E[t, j] = h
+        assert abs((L2(Ht + E, Bt) - L2(Ht - E, Bt)) / (2 * h) - g["dH"][t, j]) < 1e-9
+    for (j, k) in [(0, 0), (7, 31), (3, 10)]:
+        E = np.zeros_like(At); E[j, k] = h
+        assert abs((L1(Xt, At + E) - L1(Xt, At - E)) / (2 * h) - g["dA"][j, k]) < 1e-9
+    for (t, k) in [(0, 0), (5, 31)]:
+        E = np.zeros_like(Xt); E[t, k] = h
+        assert abs((L1(Xt + E, At) - L1(Xt - E, At)) / (2 * h) - g["dX"][t, k]) < 1e-9
+    # the de-quantised hidden state is within half a step of the stored one
+    assert np.all(np.abs(Ht - f["H"]) <= (0.5 + 0.5 * (f["q_h"] == 127) + 1e-4) / f["g_h"].astype(np.float64)[:, None])
