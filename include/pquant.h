@@ -165,6 +165,27 @@ int pq_linear_norm_bwd(const pq_linear_desc* desc, const void* dY, const void* X
                        float* dgain, float* dW, float* dhpA, float* dhpB, float* dWr, float* dalpha_dbeta,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* INT8 form of the two-factor high-precision branch (Sec. 3.2: the 8-bit weights are quantised identically to
+ * the 8-bit activations; Sec. 3.1 quantiser).  With Q the AbsMax INT8 quantiser of pq_quant_act applied per row:
+ *     (q_a, g_a) = Q(A),  (q_b, g_b) = Q(B),   acc1 = q_x q_a^T (exact int32),
+ *     H = fl32(fl32(fl32(1/g_x[t]) * fl32(acc1)) / g_a[j]) rounded to bf16,  (q_h, g_h) = Q(H),
+ *     acc2 = q_h q_b^T (exact int32),   Y (+)= fl32(fl32(fl32(alpha/g_h[t]) * fl32(acc2)) / g_b[n]).
+ *   Xq [T][K] int8 and gamma_x [T] fp32: codes of X as written by pq_quant_act / pq_rmsnorm_quant_fwd (the 1-bit
+ *   branch's own, nothing is quantised twice);  A [r][K], B [N][r] bf16;  Y [T][N] bf16, overwritten or, with
+ *   accumulate != 0, added to (the 1-bit branch's output).  ctx receives what the backward needs.
+ * Backward (STE, App. B.1: every quantiser is the identity): with X~ = q_x/g_x (Xt [T][K] bf16 as written by the
+ * quantiser), A~, B~, H~ likewise:  dH = alpha dY B~,  dB = alpha dY^T H~,  dA = dH^T X~,  dX (+)= dH A~.
+ *   dY [T][N] bf16;  dX [T][K] bf16 (overwritten, or added to with accumulate_dX != 0);  dA [r][K], dB [N][r] fp32.
+ * bf16 only; K, N and r multiples of 32.  ctx / workspace sizes from the two queries. */
+size_t pq_hp_int8_ctx_bytes(int32_t T, int32_t K, int32_t N, int32_t r);
+size_t pq_hp_int8_workspace_bytes(int32_t T, int32_t K, int32_t N, int32_t r);
+int pq_hp_int8_fwd(const int8_t* Xq, const float* gamma_x, const void* A, const void* B, int32_t dtype, int32_t T,
+                   int32_t K, int32_t N, int32_t r, float alpha, void* Y, int32_t accumulate, void* ctx,
+                   size_t ctx_bytes, void* workspace, size_t workspace_bytes, void* stream);
+int pq_hp_int8_bwd(const void* dY, const void* Xt, int32_t dtype, int32_t T, int32_t K, int32_t N, int32_t r,
+                   float alpha, const void* ctx, size_t ctx_bytes, void* dX, int32_t accumulate_dX, float* dA, float* dB,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
 /* The decoupled FFN (Sec. 3.2 FFN equation; Sec. 3.3):
  *     Y = beta * FFN_1bit(X) + alpha * sum_j gate_j(X) * FFN_e_j(X)
  * FFN_1bit: U = L_up(Q(X)), G = L_gate(Q(X)) (pure 1-bit linears, Sec. 3.1), Hd = silu(G) * U,

@@ -27,6 +27,7 @@ EXPORTS = [
     "pq_ffn_fwd", "pq_ffn_bwd", "pq_glue_lincomb", "pq_glue_gather_rows",
     "pq_rmsnorm_quant_fwd", "pq_rmsnorm_bwd_workspace_bytes", "pq_rmsnorm_bwd",
     "pq_linear_norm_ctx_bytes", "pq_linear_norm_workspace_bytes", "pq_linear_norm_fwd", "pq_linear_norm_bwd",
+    "pq_hp_int8_ctx_bytes", "pq_hp_int8_workspace_bytes", "pq_hp_int8_fwd", "pq_hp_int8_bwd",
 ]
 
 
@@ -67,7 +68,7 @@ def lib():
         for name in ("pq_pack_workspace_bytes", "pq_linear_ctx_bytes", "pq_linear_workspace_bytes",
                      "pq_decode_workspace_bytes", "pq_pack_tiled64_bytes", "pq_ffn_ctx_bytes",
                      "pq_ffn_workspace_bytes", "pq_rmsnorm_bwd_workspace_bytes", "pq_linear_norm_ctx_bytes",
-                     "pq_linear_norm_workspace_bytes"):
+                     "pq_linear_norm_workspace_bytes", "pq_hp_int8_ctx_bytes", "pq_hp_int8_workspace_bytes"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -238,6 +239,44 @@ def linear_norm_bwd(desc, dY, X, gain, W, bufs, dX, dgain, dW, d_ab, A=None, B=N
                                     C.c_size_t(bufs.ctx.numel()), _p(dX), _p(dgain), _p(dW), _p(dA), _p(dB), _p(dWr), _p(d_ab),
                                     _p(bufs.ws), C.c_size_t(bufs.ws.numel()), _stream()))
     return dX, dgain, dW, d_ab
+
+
+class HpInt8Buffers:
+    """ctx and workspace of the INT8 high-precision branch, with views of what the forward saved."""
+
+    def __init__(self, T, K, N, r, device="cuda"):
+        self.shape = (T, K, N, r)
+        self.ctx = _bytes(lib().pq_hp_int8_ctx_bytes(T, K, N, r), device)
+        self.ws = _bytes(lib().pq_hp_int8_workspace_bytes(T, K, N, r), device)
+
+    def views(self):
+        """(q_a, g_a, q_b, g_b, H, q_h, g_h) as tensors over ctx (same order and 256-byte rounding as the library)."""
+        T, K, N, r = self.shape
+        off = 0
+
+        def take(nbytes, dtype, shape):
+            nonlocal off
+            v = self.ctx[off:off + nbytes].view(dtype).view(shape)
+            off += (nbytes + 255) // 256 * 256
+            return v
+        q_a = take(r * K, torch.int8, (r, K)); g_a = take(r * 4, torch.float32, (r,)); take(r * K * 2, torch.bfloat16, (r, K))
+        q_b = take(N * r, torch.int8, (N, r)); g_b = take(N * 4, torch.float32, (N,)); take(N * r * 2, torch.bfloat16, (N, r))
+        H = take(T * r * 2, torch.bfloat16, (T, r)); q_h = take(T * r, torch.int8, (T, r)); g_h = take(T * 4, torch.float32, (T,))
+        return q_a, g_a, q_b, g_b, H, q_h, g_h
+
+
+def hp_int8_fwd(Xq, gamma_x, A, B, alpha, Y, bufs, accumulate=False):
+    T, K, N, r = bufs.shape
+    _check(lib().pq_hp_int8_fwd(_p(Xq), _p(gamma_x), _p(A), _p(B), _dt(A), T, K, N, r, C.c_float(alpha), _p(Y),
+                                int(accumulate), _p(bufs.ctx), C.c_size_t(bufs.ctx.numel()), _p(bufs.ws),
+                                C.c_size_t(bufs.ws.numel()), _stream()))
+
+
+def hp_int8_bwd(dY, Xt, alpha, bufs, dX, dA, dB, accumulate_dX=False):
+    T, K, N, r = bufs.shape
+    _check(lib().pq_hp_int8_bwd(_p(dY), _p(Xt), _dt(dY), T, K, N, r, C.c_float(alpha), _p(bufs.ctx),
+                                C.c_size_t(bufs.ctx.numel()), _p(dX), int(accumulate_dX), _p(dA), _p(dB), _p(bufs.ws),
+                                C.c_size_t(bufs.ws.numel()), _stream()))
 
 
 def prof_enable(on=True):

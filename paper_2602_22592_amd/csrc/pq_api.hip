@@ -559,6 +559,138 @@ extern "C" int pq_linear_norm_bwd(const pq_linear_desc* d, const void* dY, const
 }
 
 // ---------------------------------------------------------------------------------------------
+// INT8 form of the two-factor high-precision branch (Sec. 3.2): rows of A and B and the hidden state are
+// quantised like activations; both products run on the int8 MFMA path with exact int32 accumulation and a
+// de-quantising epilogue (row scale as a reciprocal per row, column scale by division).  The backward is the
+// STE one: bf16 GEMMs on the de-quantised factors saved by the forward.
+// ctx: [Aq r*K][gA r][At r*K bf16][Bq N*r][gB N][Bt N*r bf16][H T*r bf16][Hq T*r][gH T][Ht T*r bf16]
+// workspace: [dH T*r bf16][split-contraction slabs]
+// ---------------------------------------------------------------------------------------------
+namespace {
+struct hp8_layout { size_t Aq, gA, At, Bq, gB, Bt, H, Hq, gH, Ht, ctx_total, dH, splitk, ws_total; };
+hp8_layout make_hp8_layout(int T, int K, int N, int r) {
+  hp8_layout L;
+  const size_t t = T, k = K, n = N, rr = r;
+  cursor c;
+  L.Aq = c.take(rr * k); L.gA = c.take(rr * sizeof(float)); L.At = c.take(rr * k * 2);
+  L.Bq = c.take(n * rr); L.gB = c.take(n * sizeof(float)); L.Bt = c.take(n * rr * 2);
+  L.H = c.take(t * rr * 2); L.Hq = c.take(t * rr); L.gH = c.take(t * sizeof(float)); L.Ht = c.take(t * rr * 2);
+  L.ctx_total = c.off;
+  cursor w;
+  L.dH = w.take(t * rr * 2);
+  size_t sk = 0;
+  const int shapes[4][3] = {{T, r, N}, {N, r, T}, {r, K, T}, {T, K, r}};
+  for (const auto& sh : shapes) {
+    if (sh[0] <= 0 || sh[1] <= 0) continue;
+    const size_t b = pq_plan_gemm(0, sh[0], sh[1], sh[2]).ws_bytes;
+    if (b > sk) sk = b;
+  }
+  L.splitk = w.take(sk);
+  L.ws_total = w.off;
+  return L;
+}
+int check_hp8(int dtype, int T, int K, int N, int r) {
+  PQ_REQUIRE(dtype == PQ_BF16, PQ_ERR_DTYPE, "the INT8 high-precision branch takes bf16 tensors");
+  PQ_REQUIRE(T >= 0 && K > 0 && N > 0 && r > 0, PQ_ERR_BAD_ARG, "bad size T=%d K=%d N=%d r=%d", T, K, N, r);
+  PQ_REQUIRE(K % 32 == 0 && N % 32 == 0 && r % 32 == 0, PQ_ERR_SHAPE, "K=%d, N=%d and r=%d must be multiples of 32", K, N, r);
+  return PQ_OK;
+}
+}  // namespace
+
+extern "C" size_t pq_hp_int8_ctx_bytes(int32_t T, int32_t K, int32_t N, int32_t r) {
+  if (check_hp8(PQ_BF16, T, K, N, r) != PQ_OK) return 0;
+  return make_hp8_layout(T, K, N, r).ctx_total;
+}
+extern "C" size_t pq_hp_int8_workspace_bytes(int32_t T, int32_t K, int32_t N, int32_t r) {
+  if (check_hp8(PQ_BF16, T, K, N, r) != PQ_OK) return 0;
+  return make_hp8_layout(T, K, N, r).ws_total;
+}
+
+extern "C" int pq_hp_int8_fwd(const int8_t* Xq, const float* gamma_x, const void* A, const void* B, int32_t dtype, int32_t T,
+                              int32_t K, int32_t N, int32_t r, float alpha, void* Y, int32_t accumulate, void* ctx,
+                              size_t ctx_bytes, void* workspace, size_t workspace_bytes, void* stream) {
+  if (int e = check_hp8(dtype, T, K, N, r)) return e;
+  const hp8_layout L = make_hp8_layout(T, K, N, r);
+  PQ_REQUIRE(A && B && ctx && workspace, PQ_ERR_BAD_ARG, "NULL buffer (A, B, ctx or workspace)");
+  PQ_REQUIRE(T == 0 || (Xq && gamma_x && Y), PQ_ERR_BAD_ARG, "NULL buffer (Xq, gamma_x or Y)");
+  PQ_REQUIRE(aligned16(Xq) && aligned16(A) && aligned16(B) && aligned16(Y) && aligned16(ctx) && aligned16(workspace), PQ_ERR_SHAPE,
+             "buffers must be 16-byte aligned");
+  PQ_REQUIRE(ctx_bytes >= L.ctx_total, PQ_ERR_WORKSPACE, "ctx too small: %zu < %zu", ctx_bytes, L.ctx_total);
+  PQ_REQUIRE(workspace_bytes >= L.ws_total, PQ_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, L.ws_total);
+  hipStream_t s = (hipStream_t)stream;
+  char* cx = (char*)ctx;
+  void* sk = (char*)workspace + L.splitk;
+  // weight side: rows of A and B on the activation grid (codes, gamma, bf16 de-quantised copy for the backward)
+  if (int e = pq_launch_quant_act(A, dtype, r, K, (int8_t*)(cx + L.Aq), (float*)(cx + L.gA), (uint16_t*)(cx + L.At), s)) return e;
+  if (int e = pq_launch_quant_act(B, dtype, N, r, (int8_t*)(cx + L.Bq), (float*)(cx + L.gB), (uint16_t*)(cx + L.Bt), s)) return e;
+  if (T == 0) return PQ_OK;
+  {  // H = (q_x q_a^T) / (gamma_x gamma_a)
+    pq_operand a{Xq, K, PQ_SRC_KC8, nullptr};
+    pq_operand b{cx + L.Aq, K, PQ_SRC_KC8, nullptr};
+    pq_epilogue e = epi_zero();
+    e.C = cx + L.H; e.ldc = r; e.out_kind = PQ_OUT_BF16; e.row_div = gamma_x; e.col_div = (const float*)(cx + L.gA);
+    if (int err = pq_launch_gemm(0, T, r, K, a, b, e, s, PQP_GEMM_HP_H, sk)) return err;
+  }
+  if (int e = pq_launch_quant_act(cx + L.H, dtype, T, r, (int8_t*)(cx + L.Hq), (float*)(cx + L.gH), (uint16_t*)(cx + L.Ht), s)) return e;
+  {  // Y (+)= alpha * (q_h q_b^T) / (gamma_h gamma_b)
+    pq_operand a{cx + L.Hq, r, PQ_SRC_KC8, nullptr};
+    pq_operand b{cx + L.Bq, r, PQ_SRC_KC8, nullptr};
+    pq_epilogue e = epi_zero();
+    e.C = Y; e.ldc = N; e.out_kind = PQ_OUT_BF16; e.accumulate = accumulate ? 1 : 0; e.scale = alpha;
+    e.row_div = (const float*)(cx + L.gH); e.col_div = (const float*)(cx + L.gB);
+    if (int err = pq_launch_gemm(0, T, N, r, a, b, e, s, PQP_GEMM_HP_Y, sk)) return err;
+  }
+  return PQ_OK;
+}
+
+extern "C" int pq_hp_int8_bwd(const void* dY, const void* Xt, int32_t dtype, int32_t T, int32_t K, int32_t N, int32_t r,
+                              float alpha, const void* ctx, size_t ctx_bytes, void* dX, int32_t accumulate_dX, float* dA, float* dB,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  if (int e = check_hp8(dtype, T, K, N, r)) return e;
+  const hp8_layout L = make_hp8_layout(T, K, N, r);
+  PQ_REQUIRE(ctx && dA && dB && workspace, PQ_ERR_BAD_ARG, "NULL buffer (ctx, dA, dB or workspace)");
+  PQ_REQUIRE(T == 0 || (dY && Xt && dX), PQ_ERR_BAD_ARG, "NULL buffer (dY, Xt or dX)");
+  PQ_REQUIRE(aligned16(dY) && aligned16(Xt) && aligned16(ctx) && aligned16(dX) && aligned16(dA) && aligned16(dB) && aligned16(workspace),
+             PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
+  PQ_REQUIRE(ctx_bytes >= L.ctx_total, PQ_ERR_WORKSPACE, "ctx too small: %zu < %zu", ctx_bytes, L.ctx_total);
+  PQ_REQUIRE(workspace_bytes >= L.ws_total, PQ_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, L.ws_total);
+  hipStream_t s = (hipStream_t)stream;
+  const char* cx = (const char*)ctx;
+  char* ws = (char*)workspace;
+  void* sk = ws + L.splitk;
+  void* dH = ws + L.dH;
+  if (T > 0) {  // dH = alpha * dY B~
+    pq_operand a{dY, N, PQ_SRC_KC16, nullptr};
+    pq_operand b{cx + L.Bt, r, PQ_SRC_KS16, nullptr};
+    pq_epilogue e = epi_zero();
+    e.C = dH; e.ldc = r; e.out_kind = PQ_OUT_BF16; e.scale = alpha;
+    if (int err = pq_launch_gemm(0, T, r, N, a, b, e, s, PQP_GEMM_DH, sk)) return err;
+  }
+  {  // dB = alpha * dY^T H~
+    pq_operand a{dY, N, PQ_SRC_KS16, nullptr};
+    pq_operand b{cx + L.Ht, r, PQ_SRC_KS16, nullptr};
+    pq_epilogue e = epi_zero();
+    e.C = dB; e.ldc = r; e.out_kind = PQ_OUT_F32; e.scale = alpha;
+    if (int err = pq_launch_gemm(0, N, r, T, a, b, e, s, PQP_GEMM_DB, sk)) return err;
+  }
+  {  // dA = dH^T X~   (dH already carries alpha)
+    pq_operand a{dH, r, PQ_SRC_KS16, nullptr};
+    pq_operand b{Xt, K, PQ_SRC_KS16, nullptr};
+    pq_epilogue e = epi_zero();
+    e.C = dA; e.ldc = K; e.out_kind = PQ_OUT_F32;
+    if (int err = pq_launch_gemm(0, r, K, T, a, b, e, s, PQP_GEMM_DA, sk)) return err;
+  }
+  if (T > 0) {  // dX (+)= dH A~
+    pq_operand a{dH, r, PQ_SRC_KC16, nullptr};
+    pq_operand b{cx + L.At, K, PQ_SRC_KS16, nullptr};
+    pq_epilogue e = epi_zero();
+    e.C = dX; e.ldc = K; e.out_kind = PQ_OUT_BF16; e.accumulate = accumulate_dX ? 1 : 0;
+    if (int err = pq_launch_gemm(0, T, K, r, a, b, e, s, PQP_GEMM_DX_HP, sk)) return err;
+  }
+  return PQ_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Decode on packed weights
 // ---------------------------------------------------------------------------------------------
 namespace {

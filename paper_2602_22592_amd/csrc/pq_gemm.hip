@@ -251,6 +251,7 @@ __device__ __forceinline__ void epi_elem(const pq_epilogue& e, epi_state& st, in
   float sc = st.sc0;
   if (e.row_div) sc = sc / e.row_div[m];
   AccT val = (AccT)sc * acc;
+  if (e.col_div) val = val / (AccT)e.col_div[n];
   if (e.maskW) {
     const double w = (double)load_io(e.maskW, e.mask_kind, ci);
     if (fabs(w - (double)st.mu) > (double)e.tau) val = (AccT)0;
@@ -318,6 +319,12 @@ __device__ __forceinline__ void epi_vec8(const pq_epilogue& e, epi_state& st, in
   float val[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) val[j] = __fmul_rn(sc, acc[j]);
+  if (e.col_div) {
+    const float4 c0 = *reinterpret_cast<const float4*>(e.col_div + n), c1 = *reinterpret_cast<const float4*>(e.col_div + n + 4);
+    const float cd[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) val[j] = val[j] / cd[j];
+  }
   if (e.maskW) {
     float w[8];
     load_io8(e.maskW, e.mask_kind, ci, w);
@@ -1216,6 +1223,7 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
       return pq_set_error(PQ_ERR_BAD_ARG, "no fused MFMA kernel for these operand kinds");
     }
     if (ak == PQ_SRC_KC8 && bk == PQ_SRC_BITS8) rc = launch_mfma_cfg<true, PQ_SRC_KC8, PQ_SRC_BITS8>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
+    else if (ak == PQ_SRC_KC8 && bk == PQ_SRC_KC8) rc = launch_mfma_cfg<true, PQ_SRC_KC8, PQ_SRC_KC8>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
     else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KC16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KC16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
     else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_KS16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_KS16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
     else if (ak == PQ_SRC_KC16 && bk == PQ_SRC_BITS16) rc = launch_mfma_cfg<false, PQ_SRC_KC16, PQ_SRC_BITS16>(pl, M, N, K, A, B, epi, s, part, grp, ph2);

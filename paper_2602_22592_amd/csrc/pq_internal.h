@@ -74,6 +74,7 @@ struct pq_epilogue {
   float scale;                // value = scale * acc, or (scale / row_div[m]) * acc
   const float* dev_scale;     // optional device scalar multiplied into `scale` first (fp32 product)
   const float* row_div;       // optional per-row divisor (gamma_t)
+  const float* col_div;       // optional per-column divisor applied after the row scale: value / col_div[n]
   // optional fixed-order partial reductions, one double per block:
   const void* dot_comp;       // sum_{m,n} comp[m][n] * acc   (comp of the io dtype)
   long ld_comp;
