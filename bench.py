@@ -173,6 +173,34 @@ def norm_quant_bench(pq, torch, T=8192, K=2048, sets=4, steps=40, warmup=8):
             "plain_quantiser_us": round(ms_q * 1e3, 2), "plain_quantiser_GBps": round(qb / ms_q / 1e6, 1)}
 
 
+def hp_int8_bench(pq, torch, T=8192, K=2048, N=2048, r=128, steps=20, warmup=5):
+    """INT8 form of the high-precision branch at the config-2 shape: forward (weight-row quantisers, two int8
+    GEMMs with the de-quantising epilogue, hidden-state quantiser) and STE backward (four bf16 GEMMs)."""
+    g = torch.Generator(device="cuda").manual_seed(8)
+    bf = torch.bfloat16
+    X = torch.randn((T, K), device="cuda", generator=g).to(bf)
+    A = (0.02 * torch.randn((r, K), device="cuda", generator=g)).to(bf)
+    B = (0.02 * torch.randn((N, r), device="cuda", generator=g)).to(bf)
+    dY = torch.randn((T, N), device="cuda", generator=g).to(bf)
+    gain = torch.ones((K,), dtype=bf, device="cuda")
+    _, Xq, gx, Xt, _ = pq.rmsnorm_quant_fwd(X, gain, 1e-6, want_xn=False, want_rstd=False)
+    bufs = pq.HpInt8Buffers(T, K, N, r)
+    Y = torch.zeros((T, N), dtype=bf, device="cuda")
+    dX = torch.empty((T, K), dtype=bf, device="cuda")
+    dA = torch.empty((r, K), dtype=torch.float32, device="cuda")
+    dB = torch.empty((N, r), dtype=torch.float32, device="cuda")
+    fwd = lambda: pq.hp_int8_fwd(Xq, gx, A, B, 1.0, Y, bufs)
+    bwd = lambda: pq.hp_int8_bwd(dY, Xt, 1.0, bufs, dX, dA, dB)
+    ms_f = _time_steps(torch, fwd, steps, warmup)
+    ms_b = _time_steps(torch, bwd, steps, warmup)
+    prof = _profile_steps(pq, torch, lambda: (fwd(), bwd()), steps)
+    ops_f = 2.0 * T * r * (K + N)
+    return {"workload": "tokens=%d, d_in=%d, d_out=%d, r=%d, bf16 I/O" % (T, K, N, r),
+            "fwd_us": round(ms_f * 1e3, 2), "fwd_int8_TOPs": round(ops_f / ms_f / 1e9, 1),
+            "bwd_us": round(ms_b * 1e3, 2), "bwd_bf16_TFLOPs": round(2.0 * ops_f / ms_b / 1e9, 1),
+            "kernels_us": {k: round(1e3 * ms / n, 2) for k, (ms, n) in sorted(prof.items())}}
+
+
 def ffn_bench(pq, torch, T=8192, D=2048, F=5504, E=8, r=32, steps=5, warmup=2):
     """Config 3: the 1.3B-shaped decoupled FFN (three 1-bit projections + E=8 top-1 experts of width 32), fwd+bwd."""
     g = torch.Generator(device="cuda").manual_seed(3)
@@ -245,6 +273,7 @@ def main():
     ap.add_argument("--no-ffn", action="store_true")
     ap.add_argument("--no-stack", action="store_true")
     ap.add_argument("--no-norm", action="store_true")
+    ap.add_argument("--no-hp8", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -330,6 +359,8 @@ def main():
                               "B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8)}
     if not args.no_norm:
         out["rmsnorm_quant"] = norm_quant_bench(pq, torch)
+    if not args.no_hp8:
+        out["hp_int8_branch"] = hp_int8_bench(pq, torch)
     if not args.no_ffn:
         out["ffn_config3"] = ffn_bench(pq, torch)
     if not args.no_stack:

@@ -493,6 +493,30 @@ def hp_int8_bwd(dYhp, fwd):
     return dict(dH=dH, dB=d.T @ Ht, dA=dH.T @ Xt, dX=dH @ At)
 
 
+def decode_gemv_int8(x, P, mu_lambda, alpha, beta, A, B, Wr, top_k=2):
+    """decode_gemv with the routed experts in their INT8 form (Sec. 3.2: 8-bit weights quantised like the
+    8-bit activations; Sec. 3.3 routing; App. A inference scales): the 1-bit branch and the router are those of
+    decode_gemv (the router reads the unquantised x), every selected expert is hp_int8_fwd on the token's own
+    codes with a bf16 hidden state, and Y = Y1 + alpha * sum_j gate_j Y_e_j.  A [E, r, n], B [E, m, r]."""
+    X32 = np.asarray(x, dtype=F32)
+    base = linear_fwd(X32, None, 0.0, beta, packed=P, mu_lambda=mu_lambda, scale_fp16=True)
+    idx, gate, p, logits = router_topk(X32, Wr, top_k)
+    T = X32.shape[0]
+    E, r = np.asarray(A).shape[0], np.asarray(A).shape[1]
+    m = np.asarray(B).shape[1]
+    Hs = np.zeros((T, top_k, r), F32)
+    Ys = np.zeros((T, top_k, m), F32)
+    for t in range(T):
+        for j in range(top_k):
+            e = int(idx[t, j])
+            f = hp_int8_fwd(None, A[e], B[e], bf16=True, q_gamma=(base["q"][t:t + 1], base["gamma"][t:t + 1]))
+            Hs[t, j] = f["H"][0]
+            Ys[t, j] = f["Yhp"][0]
+    Yhp = (gate.astype(F64)[:, :, None] * Ys.astype(F64)).sum(axis=1)
+    return dict(acc=base["acc"], gamma=base["gamma"], Y1=base["Y1"], idx=idx, gate=gate, Hs=Hs, Ys=Ys, Yhp=Yhp,
+                Y=base["Y1"].astype(F64) + F64(alpha) * Yhp)
+
+
 def bits_per_weight(frac_1bit, frac_8bit):
     """Average bit-width of a decoupled layer (Table 1 percentages -> the 'Bit' column of Table 2)."""
     return frac_1bit * 1.0 + frac_8bit * 8.0

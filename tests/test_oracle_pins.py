@@ -673,3 +673,45 @@ def test_hp_int8_backward_is_the_gradient_of_the_dequantised_bilinear_form():
         assert abs((L1(Xt + E, At) - L1(Xt - E, At)) / (2 * h) - g["dX"][t, k]) < 1e-9
     # the de-quantised hidden state is within half a step of the stored one
     assert np.all(np.abs(Ht - f["H"]) <= (0.5 + 0.5 * (f["q_h"] == 127) + 1e-4) / f["g_h"].astype(np.float64)[:, None])
+
+
+def test_decode_int8_experts_reduce_to_the_dense_int8_branch_and_track_the_float_experts():
+    """One expert and top-1: the softmax gate over a single logit is exactly 1, so the routed INT8 decode must be
+    the 1-bit product plus alpha times the dense INT8 branch, bit for bit.  With several experts the result stays
+    within the INT8 quantisation error of the bf16-expert decode (same routing, same 1-bit branch)."""
+    rng = np.random.default_rng(21)
+    T, n, m, r, E = 3, 256, 64, 32, 4
+    x = wl.activations(rng, T, n, bf16=True)
+    W = wl.normal(rng, (m, n), 0.02, True)
+    A = wl.normal(rng, (E, r, n), 0.02, True)
+    B = wl.normal(rng, (E, m, r), 0.02, True)
+    Wr = wl.normal(rng, (E, n), 0.05, True)
+    mu, lam = po.weight_stats(W)
+    P = po.pack_sign(po.binarise(W, mu))
+    alpha, beta = 0.7, 0.9
+    one = po.decode_gemv_int8(x, P, (mu, lam), alpha, beta, A[:1], B[:1], Wr[:1], top_k=1)
+    assert np.all(one["gate"] == 1.0) and np.all(one["idx"] == 0)
+    dense = po.hp_int8_fwd(x, A[0], B[0], bf16=True)
+    plain = po.decode_gemv(x, P, (mu, lam), 0.0, beta)
+    assert np.array_equal(one["acc"], plain["acc"])
+    assert np.array_equal(one["Y"], plain["Y1"].astype(np.float64) + alpha * dense["Yhp"].astype(np.float64))
+    assert np.array_equal(one["Hs"][:, 0], dense["H"])
+    # several experts against the float experts
+    f8 = po.decode_gemv_int8(x, P, (mu, lam), alpha, beta, A, B, Wr, top_k=2)
+    ff = po.decode_gemv(x, P, (mu, lam), alpha, beta, A=A, B=B, Wr=Wr, top_k=2)
+    assert np.array_equal(f8["idx"], ff["idx"]) and np.array_equal(f8["gate"], ff["gate"])
+    assert np.abs(f8["Yhp"] - ff["Yhp"]).max() / np.abs(ff["Yhp"]).max() < 0.05
+    # brute force of one output element from the stored codes (Python integers and one division chain)
+    t, j, i = 1, 1, 5
+    e = int(f8["idx"][t, j])
+    qa, ga = po.quant_act(A[e]); qb, gb = po.quant_act(B[e]); qx, gx = po.quant_act(x)
+    h = np.zeros(r, np.float32)
+    for jj in range(r):
+        a1 = sum(int(qx[t, k]) * int(qa[jj, k]) for k in range(n))
+        h[jj] = np.float32(np.float32(np.float32(1.0) / gx[t]) * np.float32(a1)) / ga[jj]
+    h = po._round_io(h, True)
+    assert np.array_equal(h, f8["Hs"][t, j])
+    qh, gh = po.quant_act(h[None, :])
+    a2 = sum(int(qh[0, jj]) * int(qb[i, jj]) for jj in range(r))
+    y = np.float32(np.float32(np.float32(1.0) / gh[0]) * np.float32(a2)) / gb[i]
+    assert y == f8["Ys"][t, j, i]
