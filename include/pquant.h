@@ -252,6 +252,21 @@ int pq_decode_gemv(const pq_decode_desc* desc, const void* X, const uint32_t* pa
                    const void* hpA, const void* hpB, const void* Wr, void* Y, int32_t* acc_out, void* workspace,
                    size_t workspace_bytes, void* stream);
 
+/* pq_decode_gemv with the routed experts in their INT8 form (Sec. 3.2: the 8-bit weights are quantised like the
+ * 8-bit activations; Sec. 3.3; App. A).  Offline, every row of A_le and B_le goes through pq_quant_act:
+ *   hpA_q [L][E][r][K] int8 with gamma_A [L][E][r],  hpB_q [L][E][N][r] int8 with gamma_B [L][E][N].
+ * Per token and selected expert e (q, gamma_x: the token's codes of the 1-bit branch; the router reads x itself):
+ *     H_i  = bf16(fl32(fl32(1/gamma_x) * sum_k q_k A_q[e][i][k]) / gamma_A[e][i]),   (q_h, gamma_h) = Q(H),
+ *     Y_en = fl32(fl32(1/gamma_h) * sum_i q_h,i B_q[e][n][i]) / gamma_B[e][n],
+ * both sums exact int32, and y = 1-bit product + alpha * sum_j gate_j Y_e_j as in pq_decode_gemv.  The expert
+ * weights are read as 1 byte per entry instead of 2.  The workspace is that of pq_decode_gemv; after the call
+ * its hidden-state section holds H ([L][top_k][r] fp32 values of the bf16 roundings, for tests).
+ * Limits: batch == 1; r % 32 == 0; top_k <= 8 and top_k * r <= 2048; K % 128 == 0 and K <= 13056. */
+int pq_decode_gemv_int8(const pq_decode_desc* desc, const void* X, const uint32_t* packed, const uint16_t* scale_fp16,
+                        const int8_t* hpA_q, const float* gamma_A, const int8_t* hpB_q, const float* gamma_B,
+                        const void* Wr, void* Y, int32_t* acc_out, void* workspace, size_t workspace_bytes,
+                        void* stream);
+
 /* Glue for chaining the linears into a layer stack; not part of the method.
  * pq_glue_lincomb: out = c0 x0 + c1 x1 + c2 x2 + c3 x3 over n bf16 elements (x1..x3 may be NULL;
  * fp32 arithmetic, one rounding; n % 8 == 0) -- residual adds and the mean that stands in for the

@@ -27,7 +27,7 @@ EXPORTS = [
     "pq_ffn_fwd", "pq_ffn_bwd", "pq_glue_lincomb", "pq_glue_gather_rows",
     "pq_rmsnorm_quant_fwd", "pq_rmsnorm_bwd_workspace_bytes", "pq_rmsnorm_bwd",
     "pq_linear_norm_ctx_bytes", "pq_linear_norm_workspace_bytes", "pq_linear_norm_fwd", "pq_linear_norm_bwd",
-    "pq_hp_int8_ctx_bytes", "pq_hp_int8_workspace_bytes", "pq_hp_int8_fwd", "pq_hp_int8_bwd",
+    "pq_hp_int8_ctx_bytes", "pq_hp_int8_workspace_bytes", "pq_hp_int8_fwd", "pq_hp_int8_bwd", "pq_decode_gemv_int8",
 ]
 
 
@@ -310,6 +310,30 @@ def decode_gemv(desc, X, packed, scale_fp16, Y, ws, A=None, B=None, Wr=None, acc
     _check(lib().pq_decode_gemv(C.byref(desc), _p(X), _p(packed), _p(scale_fp16), _p(A), _p(B), _p(Wr), _p(Y),
                                 _p(acc_out), _p(ws), C.c_size_t(ws.numel()), _stream()))
     return Y
+
+
+def quant_rows(W):
+    """AbsMax INT8 codes and gammas of the rows of the last axis of a bf16 / fp32 tensor (the activation quantiser
+    applied to weight rows): returns (codes of W's shape, gammas of W's shape without the last axis)."""
+    K = W.shape[-1]
+    q, g = quant_act(W.reshape(-1, K).contiguous())
+    return q.view(W.shape), g.view(W.shape[:-1])
+
+
+def decode_gemv_int8(desc, X, packed, scale_fp16, Y, ws, Aq, gA, Bq, gB, Wr, acc_out=None):
+    _check(lib().pq_decode_gemv_int8(C.byref(desc), _p(X), _p(packed), _p(scale_fp16), _p(Aq), _p(gA), _p(Bq), _p(gB),
+                                     _p(Wr), _p(Y), _p(acc_out), _p(ws), C.c_size_t(ws.numel()), _stream()))
+    return Y
+
+
+def decode_ws_hidden(desc, ws):
+    """The expert hidden states [L][B][top_k][r] (fp32) inside a decode workspace (same section order and 256-byte
+    rounding as the library: codes, bit planes, row sums, gammas, indices, gates, hidden states)."""
+    L, B, K, k, r = desc.n_layers, desc.batch, desc.d_in, desc.top_k, desc.hp_rank
+    off = 0
+    for nbytes in (L * B * K, L * B * 8 * (K // 32) * 4, L * B * 4, L * B * 4, L * B * k * 4, L * B * k * 4):
+        off = (off + nbytes + 255) // 256 * 256
+    return ws[off:off + L * B * k * r * 4].view(torch.float32).view(L, B, k, r)
 
 
 def pack_retile64(P, K):

@@ -753,6 +753,25 @@ extern "C" int pq_decode_gemv(const pq_decode_desc* d, const void* X, const uint
   return pq_launch_decode(dd, X, packed, scale_fp16, hpA, hpB, Wr, Y, acc_out, workspace, (hipStream_t)stream);
 }
 
+extern "C" int pq_decode_gemv_int8(const pq_decode_desc* d, const void* X, const uint32_t* packed, const uint16_t* scale_fp16,
+                                   const int8_t* hpA_q, const float* gamma_A, const int8_t* hpB_q, const float* gamma_B,
+                                   const void* Wr, void* Y, int32_t* acc_out, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+  if (int e = check_decode(d)) return e;
+  PQ_REQUIRE(d->batch == 1, PQ_ERR_SHAPE, "INT8 experts are implemented for batch 1 (batch=%d)", d->batch);
+  PQ_REQUIRE(d->hp_rank > 0 && d->hp_rank % 32 == 0, PQ_ERR_SHAPE, "hp_rank=%d must be a positive multiple of 32", d->hp_rank);
+  PQ_REQUIRE(d->top_k <= 8 && d->top_k * d->hp_rank <= 2048, PQ_ERR_SHAPE, "top_k=%d (at most 8) times hp_rank=%d exceeds 2048",
+             d->top_k, d->hp_rank);
+  PQ_REQUIRE((size_t)d->d_in * 5 <= 64 * 1024, PQ_ERR_SHAPE, "d_in=%d exceeds 13056 (activations and their codes are staged in LDS)", d->d_in);
+  PQ_REQUIRE(X && packed && scale_fp16 && Y && workspace && hpA_q && gamma_A && hpB_q && gamma_B && Wr, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(aligned16(X) && aligned16(packed) && aligned16(Y) && aligned16(workspace) && aligned16(hpA_q) && aligned16(hpB_q) &&
+                 aligned16(Wr) && aligned16(acc_out), PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
+  size_t off[7];
+  const size_t need = pq_decode_ws_layout(*d, off);
+  PQ_REQUIRE(workspace_bytes >= need, PQ_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, need);
+  return pq_launch_decode(*d, X, packed, scale_fp16, hpA_q, hpB_q, Wr, Y, acc_out, workspace, (hipStream_t)stream, gamma_A, gamma_B);
+}
+
 extern "C" size_t pq_pack_tiled64_bytes(int32_t N, int32_t K) {
   if (N <= 0 || K <= 0 || K % 128 != 0) return 0;
   return (size_t)((N + 63) / 64) * 64 * (K / 32) * sizeof(uint32_t);

@@ -213,14 +213,27 @@ __global__ __launch_bounds__(256) void decode_prep_kernel(const uint16_t* __rest
 #endif
 constexpr int PREP_H_ROWS = PQ_PREP_H_ROWS;   // rows per workgroup: few enough workgroups that the repeated router stays cheap
 
+// I8 (Sec. 3.2, experts on the INT8 grid): hpA holds INT8 codes [L][E][r][K] with one gamma per row in gA; the
+// hidden state is the exact integer product of the token's codes with a row, de-quantised as
+// fl32(fl32(1/gamma_x) * acc) / gamma_a and rounded to bf16 (stored as fp32).  The token's codes (natural column
+// order) sit in LDS behind its fp32 activations.
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+template <bool I8>
 __global__ __launch_bounds__(256) void decode_prep_h_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wr,
-                                                            const uint16_t* __restrict__ hpA, int K, int E, int r, int topk,
+                                                            const void* __restrict__ hpA_, const float* __restrict__ gA,
+                                                            int K, int E, int r, int topk,
                                                             int parts, int8_t* __restrict__ xq, uint32_t* __restrict__ planes,
                                                             int* __restrict__ rowsum, float* __restrict__ gamma,
                                                             int* __restrict__ idx, float* __restrict__ gate,
                                                             float* __restrict__ h) {
   extern __shared__ __attribute__((aligned(16))) float xs[];
   __shared__ prep_shared sh;
+  const uint16_t* __restrict__ hpA = (const uint16_t*)hpA_;
   // Consecutive workgroups go to different XCDs (each with its own L2): number them so that all parts of a
   // layer land on one XCD and its router matrix and activations are fetched from memory once.
   int layer, part;
@@ -241,10 +254,73 @@ __global__ __launch_bounds__(256) void decode_prep_h_kernel(const uint16_t* __re
     prep_quantise(amax, tok, K, xs, sh, xq, planes, rowsum, gamma);
     return;
   }
-  __syncthreads();                                    // xs complete
-  prep_router(Wr, layer, tok, K, E, topk, xs, sh, part == 1 ? idx : nullptr, gate);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float gx = 0.0f;
+  if constexpr (I8) {                                 // the quantiser's gamma, as prep_quantise forms it
+    const float wm = wave_max(amax);
+    if (lane == 0) sh.red[wave] = wm;
+  }
+  __syncthreads();                                    // xs complete
+  if constexpr (I8) gx = 128.0f / fmaxf(fmaxf(fmaxf(sh.red[0], sh.red[1]), fmaxf(sh.red[2], sh.red[3])), 1e-5f);
+  prep_router(Wr, layer, tok, K, E, topk, xs, sh, part == 1 ? idx : nullptr, gate);
   const int oend = min(part * PREP_H_ROWS, topk * r);
+  if constexpr (I8) {
+    uint32_t* xc = reinterpret_cast<uint32_t*>(xs + K);          // K code bytes
+    for (int c = threadIdx.x; c < K / 4; c += 256) {
+      const float4 v = *reinterpret_cast<const float4*>(xs + 4 * c);
+      const float f[4] = {v.x, v.y, v.z, v.w};
+      uint32_t w = 0u;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int q = (int)fminf(fmaxf(rintf(__fmul_rn(f[j], gx)), -128.0f), 127.0f);
+        w |= (uint32_t)(q & 0xFF) << (8 * j);
+      }
+      xc[c] = w;
+    }
+    __syncthreads();
+    const int8_t* __restrict__ A8 = (const int8_t*)hpA_;
+    const float sx = 1.0f / gx;
+    for (int o0 = (part - 1) * PREP_H_ROWS + 2 * wave; o0 < oend; o0 += 8) {
+      const bool two = o0 + 1 < oend;
+      const int o1 = two ? o0 + 1 : o0;
+      const size_t row0 = ((size_t)layer * E + sh.sel[o0 / r]) * r + o0 % r;
+      const size_t row1 = ((size_t)layer * E + sh.sel[o1 / r]) * r + o1 % r;
+      const uint4* a0 = reinterpret_cast<const uint4*>(A8 + row0 * K);
+      const uint4* a1 = reinterpret_cast<const uint4*>(A8 + row1 * K);
+      int s0 = 0, s1 = 0;
+      for (int cb = lane; cb < K / 16; cb += 256) {     // eight loads in flight per lane
+        uint4 ua[4], va[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int cc = min(cb + 64 * i, K / 16 - 1);
+          ua[i] = nt_load16(a0 + cc);
+          va[i] = nt_load16(a1 + cc);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int c = cb + 64 * i;
+          if (c < K / 16) {
+            const uint4 q = *reinterpret_cast<const uint4*>(xc + 4 * c);
+            s0 = __builtin_amdgcn_sdot4((int)ua[i].x, (int)q.x, s0, false);
+            s0 = __builtin_amdgcn_sdot4((int)ua[i].y, (int)q.y, s0, false);
+            s0 = __builtin_amdgcn_sdot4((int)ua[i].z, (int)q.z, s0, false);
+            s0 = __builtin_amdgcn_sdot4((int)ua[i].w, (int)q.w, s0, false);
+            s1 = __builtin_amdgcn_sdot4((int)va[i].x, (int)q.x, s1, false);
+            s1 = __builtin_amdgcn_sdot4((int)va[i].y, (int)q.y, s1, false);
+            s1 = __builtin_amdgcn_sdot4((int)va[i].z, (int)q.z, s1, false);
+            s1 = __builtin_amdgcn_sdot4((int)va[i].w, (int)q.w, s1, false);
+          }
+        }
+      }
+      s0 = wave_sum_i(s0);
+      s1 = wave_sum_i(s1);
+      if (lane == 0) {
+        h[(size_t)layer * topk * r + o0] = bf16_to_f32(f32_to_bf16(__fmul_rn(sx, (float)s0) / gA[row0]));
+        if (two) h[(size_t)layer * topk * r + o1] = bf16_to_f32(f32_to_bf16(__fmul_rn(sx, (float)s1) / gA[row1]));
+      }
+    }
+    return;
+  }
   for (int o0 = (part - 1) * PREP_H_ROWS + 2 * wave; o0 < oend; o0 += 8) {   // rows of the [topk][r] hidden state
     const bool two = o0 + 1 < oend;
     const int o1 = two ? o0 + 1 : o0;
@@ -346,8 +422,58 @@ struct gemv_params {
   int* acc_out;           // [L][N] or null
   int N, K, E, r, topk;
   float alpha;
+  const float* gB;        // INT8 experts: [L][E][N] gammas of the rows of hpB (then hpB is int8 [L][E][N][r])
 };
 
+// INT8 experts: the hidden state of every selected expert (bf16 values held as fp32) is put on the INT8 grid
+// again (Sec. 3.1 quantiser, one gamma per token and expert) by each wavefront for itself: codes to a
+// wave-private LDS patch qh[topk][r/4] (4 codes per word), gammas to gh[topk].  topk <= 8, topk * r <= 2048.
+constexpr int I8_MAX_TOPK = 8, I8_MAX_CODE_WORDS = 512;
+__device__ __forceinline__ void expert_codes_wave(const float* __restrict__ hh, int topk, int r, uint32_t* qh, float* gh) {
+  const int lane = threadIdx.x & 63;
+  for (int j = 0; j < topk; ++j) {
+    const float* hj = hh + (size_t)j * r;
+    float amax = 0.0f;
+    for (int d = lane; d < r / 4; d += 64) {
+      const float4 v = *reinterpret_cast<const float4*>(hj + 4 * d);
+      amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+    }
+    amax = wave_max(amax);
+    const float g = 128.0f / fmaxf(amax, 1e-5f);
+    for (int d = lane; d < r / 4; d += 64) {
+      const float4 v = *reinterpret_cast<const float4*>(hj + 4 * d);
+      const float f[4] = {v.x, v.y, v.z, v.w};
+      uint32_t w = 0u;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int q = (int)fminf(fmaxf(rintf(__fmul_rn(f[t], g)), -128.0f), 127.0f);
+        w |= (uint32_t)(q & 0xFF) << (8 * t);
+      }
+      qh[j * (r / 4) + d] = w;
+    }
+    if (lane == 0) gh[j] = g;
+  }
+  // wave-private patch: order this wave's LDS writes before its reads of other lanes' words
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+// One row of one selected expert against the token's hidden-state codes: this lane's share (16-byte chunks
+// sub, sub + 8, ... of the row's r codes) of the exact integer product
+__device__ __forceinline__ int expert_dot_i8(const int8_t* __restrict__ brow, const uint32_t* qhj, int r, int sub) {
+  int part = 0;
+  for (int c = sub; c < r / 16; c += 8) {
+    const uint4 b = nt_load16(reinterpret_cast<const uint4*>(brow + c * 16));
+    const uint4 q = *reinterpret_cast<const uint4*>(qhj + 4 * c);
+    part = __builtin_amdgcn_sdot4((int)b.x, (int)q.x, part, false);
+    part = __builtin_amdgcn_sdot4((int)b.y, (int)q.y, part, false);
+    part = __builtin_amdgcn_sdot4((int)b.z, (int)q.z, part, false);
+    part = __builtin_amdgcn_sdot4((int)b.w, (int)q.w, part, false);
+  }
+  return part;
+}
+
+template <bool I8>
 __global__ __launch_bounds__(256) void decode_gemv_b1_kernel(gemv_params p) {
   const int layer = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -408,12 +534,27 @@ __global__ __launch_bounds__(256) void decode_gemv_b1_kernel(gemv_params p) {
   const float gam = p.gamma[layer];
   const float sc = fp16_bits_to_f32(p.scale[layer]) / gam;
   const int rs = p.rowsum[layer];
+  __shared__ __attribute__((aligned(16))) uint32_t s_qh[I8 ? 4 : 1][I8 ? I8_MAX_CODE_WORDS : 4];
+  __shared__ float s_gh[I8 ? 4 : 1][I8_MAX_TOPK];
+  if constexpr (I8) expert_codes_wave(p.h + (size_t)layer * p.topk * p.r, p.topk, p.r, s_qh[wave], s_gh[wave]);
 #pragma unroll
   for (int it = 0; it < GEMV_ITERS; ++it) {
     const int row = row_base + it * 8 + rl;
     const bool okr = row < p.N;
     float yh = 0.0f;
-    if (p.r > 0) {
+    if constexpr (I8) {
+      const int8_t* B8 = (const int8_t*)p.hpB;
+      for (int j = 0; j < p.topk; ++j) {
+        const int e = p.idx[layer * p.topk + j];
+        const float gt = p.gate[layer * p.topk + j];
+        const size_t brow = ((size_t)layer * p.E + e) * p.N + (okr ? row : 0);
+        int part = expert_dot_i8(B8 + brow * p.r, s_qh[wave] + j * (p.r / 4), p.r, sub);
+#pragma unroll
+        for (int o = 4; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+        const float ys = __fmul_rn(1.0f / s_gh[wave][j], (float)part) / p.gB[brow];
+        yh += gt * ys;                                 // the same value in all 8 lanes of the row
+      }
+    } else if (p.r > 0) {
       for (int j = 0; j < p.topk; ++j) {
         const int e = p.idx[layer * p.topk + j];
         const float gt = p.gate[layer * p.topk + j];
@@ -436,7 +577,7 @@ __global__ __launch_bounds__(256) void decode_gemv_b1_kernel(gemv_params p) {
 #pragma unroll
     for (int o = 4; o > 0; o >>= 1) {
       d += __shfl_xor(d, o, 64);
-      yh += __shfl_xor(yh, o, 64);
+      if constexpr (!I8) yh += __shfl_xor(yh, o, 64);
     }
     if (sub == 0 && okr) {
       const int acc = 2 * d - rs;
@@ -455,10 +596,12 @@ __global__ __launch_bounds__(256) void decode_gemv_b1_kernel(gemv_params p) {
 // needed, and a lane needs only its weight words and 8 counters in VGPRs, so many waves are
 // resident and many loads are in flight.  The 4 wavefronts of a workgroup split the columns.
 // ------------------------------------------------------------------------------------------
-template <int GPB>   // row groups (of 64 rows) per workgroup: all their loads are issued before the popcounts start
+template <int GPB, bool I8>   // row groups (of 64 rows) per workgroup: all their loads are issued before the popcounts start
 __global__ __launch_bounds__(256) void decode_gemv_tiled_kernel(gemv_params p) {
   __shared__ int s_dot[GPB][4][64];
   __shared__ float s_yh[GPB][64];
+  __shared__ __attribute__((aligned(16))) uint32_t s_qh[I8 ? 4 : 1][I8 ? I8_MAX_CODE_WORDS : 4];
+  __shared__ float s_gh[I8 ? 4 : 1][I8_MAX_TOPK];
   const int layer = blockIdx.y;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -531,6 +674,7 @@ __global__ __launch_bounds__(256) void decode_gemv_tiled_kernel(gemv_params p) {
   int q0 = 0;
   for (; q0 + 32 <= nq; q0 += 32) pass(q0, std::true_type{});
   if (q0 < nq) pass(q0, std::false_type{});
+  if constexpr (I8) expert_codes_wave(p.h + (size_t)layer * p.topk * p.r, p.topk, p.r, s_qh[wave], s_gh[wave]);
 
 #pragma unroll
   for (int g = 0; g < GPB; ++g) {
@@ -550,6 +694,21 @@ __global__ __launch_bounds__(256) void decode_gemv_tiled_kernel(gemv_params p) {
         const int erow = grp * 64 + lrow;
         const bool oke = erow < p.N;
         float yh = 0.0f;
+        if constexpr (I8) {
+          const int8_t* B8 = (const int8_t*)p.hpB;
+          for (int j = 0; j < p.topk; ++j) {
+            const int e = p.idx[layer * p.topk + j];
+            const float gt = p.gate[layer * p.topk + j];
+            const size_t brow = ((size_t)layer * p.E + e) * p.N + (oke ? erow : 0);
+            int part = expert_dot_i8(B8 + brow * p.r, s_qh[wave] + j * (p.r / 4), p.r, sub);
+#pragma unroll
+            for (int o = 4; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+            const float ys = __fmul_rn(1.0f / s_gh[wave][j], (float)part) / p.gB[brow];
+            yh += gt * ys;                             // the same value in all 8 lanes of the row
+          }
+          if (sub == 0) s_yh[g][lrow] = yh;
+          continue;
+        }
         for (int j = 0; j < p.topk; ++j) {
           const int e = p.idx[layer * p.topk + j];
           const float gt = p.gate[layer * p.topk + j];
@@ -965,7 +1124,8 @@ size_t pq_decode_ws_layout(const pq_decode_desc& d, size_t* off /* [7]: xq plane
 
 int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* packed, const uint16_t* scale_fp16,
                      const void* hpA, const void* hpB, const void* Wr, void* Y, int32_t* acc_out, void* workspace,
-                     hipStream_t s) {
+                     hipStream_t s, const float* gA, const float* gB) {
+  const bool i8 = gA != nullptr;                      // INT8 experts (batch 1 only; the caller has checked the limits)
   size_t off[7];
   pq_decode_ws_layout(d, off);
   char* ws = (char*)workspace;
@@ -980,9 +1140,13 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
   if (B == 1 && r > 0) {
     pq_prof_scope prof(PQP_DECODE_PREP, s);
     const int parts = 1 + (d.top_k * r + PREP_H_ROWS - 1) / PREP_H_ROWS;
-    decode_prep_h_kernel<<<L * parts, 256, (size_t)K * sizeof(float), s>>>((const uint16_t*)X, (const uint16_t*)Wr, (const uint16_t*)hpA,
-                                                                          K, E, r, d.top_k, parts, xq, planes, rowsum, gamma, idx,
-                                                                          gate, h);
+    if (i8)
+      decode_prep_h_kernel<true><<<L * parts, 256, (size_t)K * 5, s>>>((const uint16_t*)X, (const uint16_t*)Wr, hpA, gA, K, E, r, d.top_k,
+                                                                      parts, xq, planes, rowsum, gamma, idx, gate, h);
+    else
+      decode_prep_h_kernel<false><<<L * parts, 256, (size_t)K * sizeof(float), s>>>((const uint16_t*)X, (const uint16_t*)Wr, hpA, nullptr,
+                                                                                   K, E, r, d.top_k, parts, xq, planes, rowsum, gamma,
+                                                                                   idx, gate, h);
     PQ_CHECK_LAUNCH("decode_prep_h_kernel");
   } else {
     {
@@ -1002,17 +1166,19 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
   pq_prof_scope prof(PQP_DECODE_MAIN, s);
   if (B == 1) {
     gemv_params p{packed, scale_fp16, planes, rowsum, gamma, (const uint16_t*)hpB, idx, gate, h, (uint16_t*)Y, acc_out,
-                  N, K, d.n_experts, r, d.top_k, d.alpha};
+                  N, K, d.n_experts, r, d.top_k, d.alpha, gB};
     if (d.packed_layout == PQ_PACKED_TILED64) {
 #ifndef PQ_GEMV_GPB
 #define PQ_GEMV_GPB 1
 #endif
       dim3 grid(((N + 63) / 64 + PQ_GEMV_GPB - 1) / PQ_GEMV_GPB, L);
-      decode_gemv_tiled_kernel<PQ_GEMV_GPB><<<grid, 256, 0, s>>>(p);
+      if (i8) decode_gemv_tiled_kernel<PQ_GEMV_GPB, true><<<grid, 256, 0, s>>>(p);
+      else decode_gemv_tiled_kernel<PQ_GEMV_GPB, false><<<grid, 256, 0, s>>>(p);
       PQ_CHECK_LAUNCH("decode_gemv_tiled_kernel");
     } else {
       dim3 grid((N + GEMV_ROWS_PER_BLOCK - 1) / GEMV_ROWS_PER_BLOCK, L);
-      decode_gemv_b1_kernel<<<grid, 256, 0, s>>>(p);
+      if (i8) decode_gemv_b1_kernel<true><<<grid, 256, 0, s>>>(p);
+      else decode_gemv_b1_kernel<false><<<grid, 256, 0, s>>>(p);
       PQ_CHECK_LAUNCH("decode_gemv_b1_kernel");
     }
   } else {

@@ -134,7 +134,7 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
 size_t pq_decode_ws_layout(const pq_decode_desc& d, size_t* off);
 int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* packed, const uint16_t* scale_fp16,
                      const void* hpA, const void* hpB, const void* Wr, void* Y, int32_t* acc_out, void* workspace,
-                     hipStream_t s);
+                     hipStream_t s, const float* gA = nullptr, const float* gB = nullptr);
 int pq_launch_retile64(const uint32_t* packed, int N, int K, uint32_t* tiled, hipStream_t s);
 
 // ---- pq_moe.hip ---------------------------------------------------------------------------

@@ -99,3 +99,65 @@ def test_decode_alpha_zero_and_beta_edge():
     c = wl.decode_case(60, 1, d_in=512, d_out=256, n_experts=4, hp_rank=16, n_layers=1)
     check_decode(c, alpha=0.0, beta=0.7)
     check_decode(c, alpha=1.5, beta=0.0)
+
+
+# ------------------------------------------------------------------------------------------------
+# Experts in their INT8 form (Sec. 3.2): accumulators and the bf16 hidden state bit-exact, outputs within 2e-2
+# ------------------------------------------------------------------------------------------------
+def check_decode_int8(c, top_k=2, alpha=2.0, beta=0.2, tiled=False):
+    L, B, K, N, E, r = c["n_layers"], c["batch"], c["d_in"], c["d_out"], c["n_experts"], c["hp_rank"]
+    Ps, scales, mls = [], [], []
+    for l in range(L):
+        P, _, ml = pq.pack_sign(dev(c["W"][l], True))
+        Ps.append(P); mls.append(ml.cpu().numpy())
+        scales.append(np.float16(np.float32(beta) * mls[-1][1]))
+    Pin = torch.stack([pq.pack_retile64(p_, K) for p_ in Ps]).contiguous() if tiled else torch.stack(Ps).contiguous()
+    scale = dev(np.array(scales, np.float16).view(np.int16))
+    desc = pq.DecodeDesc(B, K, N, r, E, top_k, L, pq.PQ_PACKED_TILED64 if tiled else pq.PQ_PACKED_ROWMAJOR, alpha)
+    ws = pq.decode_workspace(desc)
+    Aq, gA = pq.quant_rows(dev(c["A"], True))            # offline: weight rows through the activation quantiser
+    Bq, gB = pq.quant_rows(dev(c["B"], True))
+    Y = torch.empty((L, B, N), dtype=torch.bfloat16, device="cuda")
+    acc = torch.empty((L, B, N), dtype=torch.int32, device="cuda")
+    pq.decode_gemv_int8(desc, dev(c["X"], True), Pin, scale, Y, ws, Aq, gA, Bq, gB, dev(c["Wr"], True), acc_out=acc)
+    torch.cuda.synchronize()
+    H = pq.decode_ws_hidden(desc, ws).cpu().numpy()
+    Y = Y.float().cpu().numpy(); acc = acc.cpu().numpy()
+    worst = 0.0
+    for l in range(L):
+        mu, lam = po.weight_stats(c["W"][l])
+        Pref = po.pack_sign(po.binarise(c["W"][l], mu))
+        f = po.decode_gemv_int8(c["X"][l], Pref, (mu, lam), alpha, beta, c["A"][l], c["B"][l], c["Wr"][l], top_k=top_k)
+        qa, ga = po.quant_act(c["A"][l].reshape(E * r, K))
+        assert np.array_equal(Aq[l].cpu().numpy().reshape(E * r, K), qa) and np.array_equal(gA[l].cpu().numpy().reshape(-1), ga)
+        assert np.array_equal(acc[l].astype(np.int64), f["acc"]), f"layer {l}: int32 accumulators differ"
+        assert np.array_equal(H[l], f["Hs"]), f"layer {l}: expert hidden states differ"
+        worst = max(worst, relerr(Y[l], f["Y"]))
+    print(f"  INT8-expert decode max-norm relative error {worst:.2e}", flush=True)
+    assert worst <= 2e-2
+
+
+@pytest.mark.parametrize("L,K,N,E,r,k", [(1, 256, 136, 4, 32, 2), (2, 4096, 1000, 8, 64, 2), (3, 640, 328, 8, 32, 1),
+                                         (1, 8192, 260, 4, 96, 3), (1, 128, 64, 1, 32, 1)])
+@pytest.mark.parametrize("tiled", [False, True])
+def test_decode_int8_experts_batch1(L, K, N, E, r, k, tiled):
+    print(f"decode INT8 experts: L={L} K={K} N={N} E={E} r={r} k={k} tiled={tiled}", flush=True)
+    check_decode_int8(wl.decode_case(80 + K + N, 1, d_in=K, d_out=N, n_experts=E, hp_rank=r, n_layers=L), top_k=k,
+                      tiled=tiled)
+
+
+def test_decode_int8_experts_config4_full_size():
+    print("decode INT8 experts, config 4 shape, two layers", flush=True)
+    check_decode_int8(wl.decode_case(4, 1, n_layers=2), top_k=2, tiled=True)
+
+
+def test_decode_int8_experts_alone_and_limits():
+    """beta = 0 leaves only the expert term, so the whole output tests the INT8 branch; unsupported shapes are errors."""
+    c = wl.decode_case(61, 1, d_in=512, d_out=256, n_experts=4, hp_rank=32, n_layers=1)
+    check_decode_int8(c, alpha=1.5, beta=0.0)
+    desc = pq.DecodeDesc(2, 512, 256, 32, 4, 2, 1, pq.PQ_PACKED_TILED64, 1.0)
+    ws = pq.decode_workspace(desc)
+    z8 = torch.zeros(16, dtype=torch.int8, device="cuda")
+    zf = torch.zeros(16, dtype=torch.float32, device="cuda")
+    with pytest.raises(pq.PQError):                      # batch 2
+        pq.decode_gemv_int8(desc, z8, z8, z8, z8, ws, z8, zf, z8, zf, z8)
