@@ -62,8 +62,8 @@ def cpu_baseline(sample_tokens):
             "sample": f"first {sample_tokens} tokens of the workload, fwd+bwd, {dt:.1f} s"}
 
 
-def decode_bench(pq, torch, batch, n_layers=64, steps=20, warmup=3):
-    """Packed-1-bit decode product, 4096 -> 11008 with E=8 top-2 rank-64 bf16 experts, over
+def decode_bench(pq, torch, batch, n_layers=64, steps=20, warmup=3, int8_experts=False):
+    """Packed-1-bit decode product, 4096 -> 11008 with E=8 top-2 rank-64 experts (bf16, or their INT8 form), over
     `n_layers` distinct weight sets per launch (361 MB of bits: larger than the Infinity Cache)."""
     K, N, E, r, k = 4096, 11008, 8, 64, 2
     g = torch.Generator(device="cuda").manual_seed(4)
@@ -81,6 +81,13 @@ def decode_bench(pq, torch, batch, n_layers=64, steps=20, warmup=3):
     desc = pq.DecodeDesc(batch, K, N, r, E, k, n_layers, pq.PQ_PACKED_TILED64 if tiled else pq.PQ_PACKED_ROWMAJOR, 2.0)
     ws = pq.decode_workspace(desc)
     run = lambda: pq.decode_gemv(desc, X, P, scale, Y, ws, A=A, B=Bm, Wr=Wr)
+    eb = 2                                                  # bytes per expert weight
+    if int8_experts:
+        Aq, gA = pq.quant_rows(A)
+        Bq, gB = pq.quant_rows(Bm)
+        del A, Bm
+        run = lambda: pq.decode_gemv_int8(desc, X, P, scale, Y, ws, Aq, gA, Bq, gB, Wr)
+        eb = 1
     total_us = 1e3 * _time_steps(torch, run, steps, warmup)        # whole calls, no per-launch events
     pq.prof_reset(); pq.prof_enable(True)                          # second pass: per-kernel durations
     for _ in range(steps):
@@ -93,9 +100,9 @@ def decode_bench(pq, torch, batch, n_layers=64, steps=20, warmup=3):
     h_us = 1e3 * prof["decode_h"][0] / prof["decode_h"][1] if "decode_h" in prof else 0.0   # batch 1: fused into prep
     # algorithmic bytes of the main kernel per layer: packed bits + the selected experts' B rows + x, y
     n_sel = k if batch == 1 else min(E, batch * k)          # upper bound on distinct experts per layer
-    main_bytes = n_layers * (N * K // 8 + n_sel * N * r * 2 + batch * (K + 2 * N))
-    prep_bytes = n_layers * (batch * 2 * K + n_sel * r * K * 2 + E * K * 2)     # x, the selected experts' A, router
-    return {"batch": batch, "layers_per_launch": n_layers, "main_kernel_us": round(main_us, 2),
+    main_bytes = n_layers * (N * K // 8 + n_sel * N * (r * eb + (4 if int8_experts else 0)) + batch * (K + 2 * N))
+    prep_bytes = n_layers * (batch * 2 * K + n_sel * r * K * eb + E * K * 2)    # x, the selected experts' A, router
+    return {"batch": batch, "experts": "int8" if int8_experts else "bf16", "layers_per_launch": n_layers, "main_kernel_us": round(main_us, 2),
             "prep_kernel_us": round(prep_us, 2), "h_kernel_us": round(h_us, 2), "launch_us": round(total_us, 2),
             "main_kernel_GBps": round(main_bytes / main_us / 1e3, 1), "main_kernel_frac_hbm": round(main_bytes / main_us / 1e3 / 8000.0, 4),
             "whole_call_GBps": round((main_bytes + prep_bytes) / total_us / 1e3, 1),
@@ -356,7 +363,8 @@ def main():
         del src, dst, ids
     if not args.no_decode:
         out["decode_gemv"] = {"metric": "1-bit decode GEMV HBM GB/s (4096->11008, E=8 top-2 r=64 experts)",
-                              "B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8)}
+                              "B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8),
+                              "B1_int8_experts": decode_bench(pq, torch, 1, int8_experts=True)}
     if not args.no_norm:
         out["rmsnorm_quant"] = norm_quant_bench(pq, torch)
     if not args.no_hp8:

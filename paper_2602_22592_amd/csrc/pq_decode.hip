@@ -674,7 +674,6 @@ __global__ __launch_bounds__(256) void decode_gemv_tiled_kernel(gemv_params p) {
   int q0 = 0;
   for (; q0 + 32 <= nq; q0 += 32) pass(q0, std::true_type{});
   if (q0 < nq) pass(q0, std::false_type{});
-  if constexpr (I8) expert_codes_wave(p.h + (size_t)layer * p.topk * p.r, p.topk, p.r, s_qh[wave], s_gh[wave]);
 
 #pragma unroll
   for (int g = 0; g < GPB; ++g) {
@@ -695,16 +694,48 @@ __global__ __launch_bounds__(256) void decode_gemv_tiled_kernel(gemv_params p) {
         const bool oke = erow < p.N;
         float yh = 0.0f;
         if constexpr (I8) {
+          // The first 16-byte chunk of the row for the first PF selected experts and the rows' gammas are requested
+          // together (slots past top_k repeat the last one: no branch around a load); the hidden-state codes are
+          // formed while they are on their way.
+          constexpr int PF = 4;
           const int8_t* B8 = (const int8_t*)p.hpB;
-          for (int j = 0; j < p.topk; ++j) {
-            const int e = p.idx[layer * p.topk + j];
-            const float gt = p.gate[layer * p.topk + j];
-            const size_t brow = ((size_t)layer * p.E + e) * p.N + (oke ? erow : 0);
-            int part = expert_dot_i8(B8 + brow * p.r, s_qh[wave] + j * (p.r / 4), p.r, sub);
+          const int nch = p.r / 16;
+          uint4 bq[PF];
+          float gbv[PF];
+          size_t browi[PF];
+#pragma unroll
+          for (int j = 0; j < PF; ++j) {
+            const int e = p.idx[layer * p.topk + min(j, p.topk - 1)];
+            browi[j] = ((size_t)layer * p.E + e) * p.N + (oke ? erow : 0);
+            bq[j] = nt_load16(reinterpret_cast<const uint4*>(B8 + browi[j] * p.r + (sub < nch ? sub : 0) * 16));
+            gbv[j] = p.gB[browi[j]];
+          }
+          if (g == 0 && it == 0) expert_codes_wave(p.h + (size_t)layer * p.topk * p.r, p.topk, p.r, s_qh[wave], s_gh[wave]);
+#pragma unroll
+          for (int j = 0; j < PF; ++j)
+            if (j < p.topk) {
+              const uint32_t* qhj = s_qh[wave] + j * (p.r / 4);
+              int part = 0;
+              if (sub < nch) {
+                const uint4 q = *reinterpret_cast<const uint4*>(qhj + 4 * sub);
+                part = __builtin_amdgcn_sdot4((int)bq[j].x, (int)q.x, part, false);
+                part = __builtin_amdgcn_sdot4((int)bq[j].y, (int)q.y, part, false);
+                part = __builtin_amdgcn_sdot4((int)bq[j].z, (int)q.z, part, false);
+                part = __builtin_amdgcn_sdot4((int)bq[j].w, (int)q.w, part, false);
+                part += expert_dot_i8(B8 + browi[j] * p.r, qhj, p.r, sub + 8);
+              }
+#pragma unroll
+              for (int o = 4; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+              const float ys = __fmul_rn(1.0f / s_gh[wave][j], (float)part) / gbv[j];
+              yh += p.gate[layer * p.topk + j] * ys;   // the same value in all 8 lanes of the row
+            }
+          for (int j = PF; j < p.topk; ++j) {
+            const size_t br = ((size_t)layer * p.E + p.idx[layer * p.topk + j]) * p.N + (oke ? erow : 0);
+            int part = expert_dot_i8(B8 + br * p.r, s_qh[wave] + j * (p.r / 4), p.r, sub);
 #pragma unroll
             for (int o = 4; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
-            const float ys = __fmul_rn(1.0f / s_gh[wave][j], (float)part) / p.gB[brow];
-            yh += gt * ys;                             // the same value in all 8 lanes of the row
+            const float ys = __fmul_rn(1.0f / s_gh[wave][j], (float)part) / p.gB[br];
+            yh += p.gate[layer * p.topk + j] * ys;
           }
           if (sub == 0) s_yh[g][lrow] = yh;
           continue;
