@@ -373,8 +373,11 @@ typedef int pq_i32x2 __attribute__((ext_vector_type(2)));
 #define PQ_DS_READ128(dst, addr, off) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off) : "memory")
 #define PQ_DS_READ64(dst, addr, off) asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off) : "memory")
 #define PQ_DS_READ_TR(dst, addr, off) asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off) : "memory")
-#define PQ_MFMA_BF16(acc, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b))
-#define PQ_MFMA_I8(acc, a, b) asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b))
+// The B fragment is passed as the first MFMA operand: the accumulator block is then the transpose of the usual
+// one, lane l holds output row (l & 31) and register v holds column 8 (v >> 2) + 4 (l >> 5) + (v & 3), i.e. runs of
+// four consecutive columns of one row, which the epilogue turns into 16-byte stores without going through LDS.
+#define PQ_MFMA_BF16(acc, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %2, %1, %0" : "+v"(acc) : "v"(a), "v"(b))
+#define PQ_MFMA_I8(acc, a, b) asm volatile("v_mfma_i32_32x32x32_i8 %0, %2, %1, %0" : "+v"(acc) : "v"(a), "v"(b))
 
 // MFMA operand of +/-1 values from packed bits (bit i set = +1, clear = -1, Eq. 4): 8 bits -> 8 bf16 (bits
 // above the eighth are ignored), 16 bits -> 16 int8.
@@ -902,11 +905,11 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
 #pragma unroll
           for (int j = 0; j < TN; ++j) {
             if constexpr (INT8)
-              acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4_t, af[ks & 1][i]),
-                                                                __builtin_bit_cast(i32x4_t, bf[ks & 1][j]), acc[i][j], 0, 0, 0);
+              acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4_t, bf[ks & 1][j]),
+                                                                __builtin_bit_cast(i32x4_t, af[ks & 1][i]), acc[i][j], 0, 0, 0);
             else
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[ks & 1][i]),
-                                                                  __builtin_bit_cast(bf16x8_t, bf[ks & 1][j]), acc[i][j], 0, 0, 0);
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, bf[ks & 1][j]),
+                                                                  __builtin_bit_cast(bf16x8_t, af[ks & 1][i]), acc[i][j], 0, 0, 0);
           }
       }
       __syncthreads();  // stage nxt is complete and nobody still reads stage cur
@@ -938,17 +941,16 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
       __syncthreads();
     }
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+      const float sr = ph2.row_div1 ? rowscale[wm0 + i * 32 + (lane & 31)] : sc1;   // a lane holds one row of a block
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int rl = wm0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        const float sr = ph2.row_div1 ? rowscale[rl] : sc1;
+      for (int v = 0; v < 16; ++v)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           const auto e1 = acc[i][j][v];
           accf[i][j][v] = (float)e1 * sr;
         }
-      }
+    }
     int st2 = 0;
     for (int k2 = 0; k2 < ph2.K2; k2 += KS2) {
       unsigned char* stage = smem + st2 * STAGE;
@@ -965,17 +967,19 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
-            accf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[0][i]),
-                                                                 __builtin_bit_cast(bf16x8_t, bf[0][j]), accf[i][j], 0, 0, 0);
+            accf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, bf[0][j]),
+                                                                 __builtin_bit_cast(bf16x8_t, af[0][i]), accf[i][j], 0, 0, 0);
       }
       st2 ^= 1;
     }
     __syncthreads();
   }
-  // Epilogue: each wavefront passes its 32x32 accumulator blocks through a private LDS patch
-  // (row stride 36 words: conflict-free both ways) so that a lane ends up with 8 consecutive
-  // columns of one row and global loads/stores are 16 bytes wide.  With a split contraction the
-  // raw fp32 accumulators go to this split's slab instead; splitk_reduce_kernel finishes the job.
+  // Epilogue: in a 32x32 accumulator block lane l holds row (l & 31) and, per group g = v >> 2, the four columns
+  // 8 g + 4 (l >> 5) + (0..3).  One half-wave exchange per register (v_permlane32_swap: the upper half of the first
+  // operand against the lower half of the second) gives the lower lanes the eight columns of the even groups and
+  // the upper lanes those of the odd groups, so every lane stores 8 consecutive columns of its row at a time
+  // (two neighbouring lanes = 16 consecutive columns) and nothing passes through LDS.  With a split contraction
+  // the raw fp32 accumulators go to this split's slab instead; splitk_reduce_kernel finishes the job.
   epi_state st;
   epi_begin(epi, st);
   float* slab = splitk_part ? splitk_part + (size_t)split * Mtot * N : nullptr;
@@ -984,44 +988,44 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
     for (int r = tid; r < BM; r += NT) rowscale[r] = st.sc0 / epi.row_div[min(m0 + r, M - 1)];
     __syncthreads();
   }
-  uint32_t* stg = reinterpret_cast<uint32_t*>(smem) + wave * (32 * 36);
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TM; ++i) {
+    const int m = m0 + wm0 + i * 32 + (lane & 31);
+    const float rs = row_scaled ? rowscale[m - m0] : __builtin_nanf("");
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int rr = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        // copy the element out first: a vector element is not a bit_cast-able lvalue
-        if constexpr (PH2) {
-          const float elem = accf[i][j][v];
-          stg[rr * 36 + (lane & 31)] = __builtin_bit_cast(uint32_t, elem);
-        } else {
-          const auto elem = acc[i][j][v];
-          stg[rr * 36 + (lane & 31)] = __builtin_bit_cast(uint32_t, elem);
-        }
-      }
-      // wave-private patch: order this wave's LDS writes before its reads (other lanes' data)
-      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-      __builtin_amdgcn_wave_barrier();
+      for (int pr = 0; pr < 2; ++pr) {
+        uint32_t x[4], y[4];
 #pragma unroll
-      for (int pass = 0; pass < 2; ++pass) {
-        const int rr = pass * 16 + (lane >> 2), c0 = (lane & 3) * 8;
-        const int m = m0 + wm0 + i * 32 + rr, n = n0 + wn0 + j * 32 + c0;
-        const uint4 r0 = *reinterpret_cast<const uint4*>(stg + rr * 36 + c0);
-        const uint4 r1 = *reinterpret_cast<const uint4*>(stg + rr * 36 + c0 + 4);
+        for (int t = 0; t < 4; ++t) {
+          uint32_t lo, hi;
+          // copy the elements out first: a vector element is not a bit_cast-able lvalue
+          if constexpr (PH2) {
+            const float e0 = accf[i][j][8 * pr + t], e1 = accf[i][j][8 * pr + 4 + t];
+            lo = __builtin_bit_cast(uint32_t, e0); hi = __builtin_bit_cast(uint32_t, e1);
+          } else {
+            const auto e0 = acc[i][j][8 * pr + t];
+            const auto e1 = acc[i][j][8 * pr + 4 + t];
+            lo = __builtin_bit_cast(uint32_t, e0); hi = __builtin_bit_cast(uint32_t, e1);
+          }
+          const auto sw = __builtin_amdgcn_permlane32_swap(lo, hi, false, false);
+          x[t] = sw[0];
+          y[t] = sw[1];
+        }
+        const int n = n0 + wn0 + j * 32 + 8 * (2 * pr + (lane >> 5));
+        const uint4 r0 = make_uint4(x[0], x[1], x[2], x[3]), r1 = make_uint4(y[0], y[1], y[2], y[3]);
         if (m < M && n < N) {
           if (slab) {
             *reinterpret_cast<uint4*>(slab + (size_t)m * N + n) = r0;
             *reinterpret_cast<uint4*>(slab + (size_t)m * N + n + 4) = r1;
           } else {
-            epi_vec8<ACC_INT>(epi, st, m, n, r0, r1, row_scaled ? rowscale[m - m0] : __builtin_nanf(""));
+            epi_vec8<ACC_INT>(epi, st, m, n, r0, r1, rs);
           }
         }
       }
-      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-      __builtin_amdgcn_wave_barrier();
     }
+  }
   if (!slab) epi_end<NT>(epi, st, red, blockIdx.x);
 }
 
