@@ -1042,12 +1042,22 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(int M, int N, int sp
     const int m = (int)(idx / n8), n = (int)(idx % n8) * 8;
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
     const size_t slab = (size_t)M * N;
-    for (int z = 0; z < splits; ++z) {
-      const float* p = part + z * slab + (size_t)m * N + n;
-      const float4 x = *reinterpret_cast<const float4*>(p);
-      const float4 y = *reinterpret_cast<const float4*>(p + 4);
-      a.x += x.x; a.y += x.y; a.z += x.z; a.w += x.w;
-      b.x += y.x; b.y += y.y; b.z += y.z; b.w += y.w;
+    // four slabs are requested together (slabs past the end repeat the last one and are dropped): a load behind
+    // a loop-carried wait would cost one memory latency per slab; the sums still run in slab order
+    for (int z = 0; z < splits; z += 4) {
+      float4 x[4], y[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float* p = part + (size_t)min(z + u, splits - 1) * slab + (size_t)m * N + n;
+        x[u] = *reinterpret_cast<const float4*>(p);
+        y[u] = *reinterpret_cast<const float4*>(p + 4);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (z + u < splits) {
+          a.x += x[u].x; a.y += x[u].y; a.z += x[u].z; a.w += x[u].w;
+          b.x += y[u].x; b.y += y[u].y; b.z += y[u].z; b.w += y[u].w;
+        }
     }
     const uint4 r0 = make_uint4(__float_as_uint(a.x), __float_as_uint(a.y), __float_as_uint(a.z), __float_as_uint(a.w));
     const uint4 r1 = make_uint4(__float_as_uint(b.x), __float_as_uint(b.y), __float_as_uint(b.z), __float_as_uint(b.w));
