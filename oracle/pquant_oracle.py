@@ -517,6 +517,43 @@ def decode_gemv_int8(x, P, mu_lambda, alpha, beta, A, B, Wr, top_k=2):
                 Y=base["Y1"].astype(F64) + F64(alpha) * Yhp)
 
 
+def decode_ffn(x, P_up, P_gate, P_down, lam_up, lam_gate, lam_down, Up, Gate, Down, Wr, alpha, beta, top_k=2):
+    """The decoupled FFN at inference on packed weights (Sec. 3.2 FFN equation, Sec. 3.3, App. A): the forward of
+    ffn_fwd with the weight side read from packed bits and every layer's scalars folded into one fp16 scale
+    (lambda_up, lambda_gate, beta * lambda_down).  x is quantised once for the up and the gate projection; U and
+    G are stored in bf16; Hd = silu(G) * U is quantised from fp32; the routed experts are gated FFNs of hidden
+    width r evaluated on the unquantised x:  Y = Y1 + alpha * sum_j gate_j Down_e (silu(Gate_e x) * (Up_e x))."""
+    X32 = np.asarray(x, dtype=F32)
+    X64 = X32.astype(F64)
+    T, d = X32.shape
+    f = np.asarray(P_up).shape[0]
+    q, gamma = quant_act(X32)
+    acc_u = onebit_acc(q, unpack_sign(np.asarray(P_up, dtype=np.uint32), d))
+    acc_g = onebit_acc(q, unpack_sign(np.asarray(P_gate, dtype=np.uint32), d))
+    su = (F32(np.float16(F32(lam_up))) / gamma).astype(F32)
+    sg = (F32(np.float16(F32(lam_gate))) / gamma).astype(F32)
+    U = _round_io((su[:, None] * acc_u.astype(F32)).astype(F32), True)
+    G = _round_io((sg[:, None] * acc_g.astype(F32)).astype(F32), True)
+    Hd = (_silu(G.astype(F64)) * U.astype(F64)).astype(F32)
+    qh, gamma_h = quant_act(Hd)
+    acc_d = onebit_acc(qh, unpack_sign(np.asarray(P_down, dtype=np.uint32), f))
+    sd = (F32(np.float16(F32(F32(beta) * F32(lam_down)))) / gamma_h).astype(F32)
+    Y1 = (sd[:, None] * acc_d.astype(F32)).astype(F32)
+    idx, gate, p, logits = router_topk(X32, Wr, top_k)
+    Up64, Gate64, Down64 = (np.asarray(a, dtype=F64) for a in (Up, Gate, Down))
+    r = Up64.shape[1]
+    act = np.zeros((T, top_k, r), F64)
+    Ys = np.zeros((T, top_k, d), F64)
+    for t in range(T):
+        for j in range(top_k):
+            e = int(idx[t, j])
+            act[t, j] = _silu(Gate64[e] @ X64[t]) * (Up64[e] @ X64[t])
+            Ys[t, j] = Down64[e] @ act[t, j]
+    Yhp = (gate.astype(F64)[:, :, None] * Ys).sum(axis=1)
+    return dict(acc_u=acc_u, acc_g=acc_g, U=U, G=G, Hd=Hd, qh=qh, gamma_h=gamma_h, acc_d=acc_d, Y1=Y1, idx=idx,
+                gate=gate, act=act, Yhp=Yhp, Y=Y1.astype(F64) + F64(alpha) * Yhp)
+
+
 def bits_per_weight(frac_1bit, frac_8bit):
     """Average bit-width of a decoupled layer (Table 1 percentages -> the 'Bit' column of Table 2)."""
     return frac_1bit * 1.0 + frac_8bit * 8.0

@@ -715,3 +715,50 @@ def test_decode_int8_experts_reduce_to_the_dense_int8_branch_and_track_the_float
     a2 = sum(int(qh[0, jj]) * int(qb[i, jj]) for jj in range(r))
     y = np.float32(np.float32(np.float32(1.0) / gh[0]) * np.float32(a2)) / gb[i]
     assert y == f8["Ys"][t, j, i]
+
+
+def test_decode_ffn_agrees_with_the_training_forward_and_with_chained_decode_products():
+    """decode_ffn is ffn_fwd read from packed bits with fp16-folded scales.  With weights whose lambda and
+    beta * lambda are exactly representable in fp16 the two must agree to fp32 rounding; its three 1-bit products
+    are those of decode_gemv (a different code path through linear_fwd), bit for bit; one expert output is
+    recomputed with plain Python floats."""
+    rng = np.random.default_rng(31)
+    T, d, f, r, E = 3, 128, 256, 8, 4
+    x = wl.activations(rng, T, d, bf16=True)
+    def pm(shape, a):                                    # +/- a around a zero mean: mu = 0, lambda = a exactly
+        W = np.where(rng.random(shape) < 0.5, -a, a).astype(np.float32)
+        W.reshape(-1)[: W.size // 2] = a; W.reshape(-1)[W.size // 2:] = -a
+        return rng.permuted(W.reshape(-1)).reshape(shape)
+    Wu, Wg, Wd = pm((f, d), 0.03125), pm((f, d), 0.0625), pm((d, f), 0.015625)
+    Up = wl.normal(rng, (E, r, d), 0.05, True); Gate = wl.normal(rng, (E, r, d), 0.05, True)
+    Down = wl.normal(rng, (E, d, r), 0.05, True); Wr = wl.normal(rng, (E, d), 0.05, True)
+    alpha, beta = 1.5, 0.5
+    packs = []
+    for W in (Wu, Wg, Wd):
+        mu, lam = po.weight_stats(W)
+        assert mu == 0.0
+        packs.append((po.pack_sign(po.binarise(W, mu)), lam))
+    (Pu, lu), (Pg, lg), (Pd, ld) = packs
+    dec = po.decode_ffn(x, Pu, Pg, Pd, lu, lg, ld, Up, Gate, Down, Wr, alpha, beta, top_k=2)
+    trn = po.ffn_fwd(x, Wu, Wg, Wd, Up, Gate, Down, Wr, alpha, beta, top_k=2, bf16=True)
+    assert np.array_equal(dec["U"], trn["U"]) and np.array_equal(dec["G"], trn["G"])
+    assert np.array_equal(dec["qh"], trn["qh"]) and np.array_equal(dec["acc_d"], trn["acc_d"])
+    assert np.array_equal(dec["idx"], trn["idx"])
+    assert np.abs(dec["Y"] - trn["Y"]).max() <= 1e-6 * np.abs(trn["Y"]).max()
+    # the three products through decode_gemv
+    up = po.decode_gemv(x, Pu, (0.0, lu), 0.0, 1.0)
+    assert np.array_equal(up["acc"], dec["acc_u"]) and np.array_equal(po._round_io(up["Y1"], True), dec["U"])
+    dn = po.decode_gemv(dec["Hd"], Pd, (0.0, ld), 0.0, beta)
+    assert np.array_equal(dn["acc"], dec["acc_d"]) and np.array_equal(dn["Y1"], dec["Y1"])
+    # one expert output element by hand
+    t, j, i = 2, 1, 7
+    e = int(dec["idx"][t, j])
+    y = 0.0
+    for k in range(r):
+        u = sum(float(Up[e, k, c]) * float(x[t, c]) for c in range(d))
+        g = sum(float(Gate[e, k, c]) * float(x[t, c]) for c in range(d))
+        y += float(Down[e, i, k]) * (g / (1.0 + math.exp(-g))) * u
+    want = float(dec["Y1"][t, i]) + alpha * sum(
+        float(dec["gate"][t, jj]) * (y if jj == j else float((np.asarray(Down[int(dec["idx"][t, jj])], np.float64) @ dec["act"][t, jj])[i]))
+        for jj in range(2))
+    assert abs(want - dec["Y"][t, i]) <= 1e-9 * max(1.0, abs(want))
