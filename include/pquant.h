@@ -267,6 +267,34 @@ int pq_decode_gemv_int8(const pq_decode_desc* desc, const void* X, const uint32_
                         const void* Wr, void* Y, int32_t* acc_out, void* workspace, size_t workspace_bytes,
                         void* stream);
 
+/* The decoupled FFN at inference on packed weights, one token per layer (Sec. 3.2 FFN equation, Sec. 3.3,
+ * App. A: every scalar of a layer folded into one stored scale), for n_layers independent FFNs per call:
+ *     q, gamma = Q(x);  U = bf16((s_up/gamma) S_up q),  G = bf16((s_gate/gamma) S_gate q)   (x quantised once),
+ *     Hd = silu(G) * U (fp32),  q_h, gamma_h = Q(Hd),  Y1 = (s_down/gamma_h) S_down q_h,
+ *     Y = Y1 + alpha * sum_j gate_j Down_e (silu(Gate_e x) * (Up_e x)),  e = idx_j  (router and experts read x itself).
+ *   X [L][D] bf16;  packed_upgate [L][2]: the row-interleaved packing (pq_pack_retile64) of W_up then W_gate,
+ *   each pq_pack_tiled64_bytes(F, D) bytes;  scale_upgate [L][2]: fp16 bits of lambda_up, lambda_gate;
+ *   packed_down [L]: row-interleaved packing of W_down (pq_pack_tiled64_bytes(D, F) each);  scale_down [L]:
+ *   fp16 bits of beta * lambda_down;  UpGate [L][E][2r][D] bf16: the rows of Up_e followed by those of Gate_e;
+ *   Down [L][E][D][r], Wr [L][E][D] bf16;  Y [L][D] bf16 out;  acc_upgate [L][2][F] int32 out or NULL (the exact
+ *   accumulators of the up and gate products, for tests).
+ * Four launches: quantiser + router + expert hidden pairs; the 2 L up/gate products; gated unit + quantiser of
+ * Hd; the L down products with the experts' down projections.
+ * Limits: D % 128 == 0, F % 128 == 0, both <= 16384; r % 8 == 0, r > 0; 1 <= top_k <= E <= 64. */
+typedef struct pq_decode_ffn_desc {
+  int32_t d_model;   /* D */
+  int32_t d_ffn;     /* F */
+  int32_t hp_rank;   /* r: hidden width of an expert */
+  int32_t n_experts; /* E */
+  int32_t top_k;
+  int32_t n_layers;  /* L */
+  float alpha;
+} pq_decode_ffn_desc;
+size_t pq_decode_ffn_workspace_bytes(const pq_decode_ffn_desc* desc);
+int pq_decode_ffn(const pq_decode_ffn_desc* desc, const void* X, const uint32_t* packed_upgate, const uint16_t* scale_upgate,
+                  const uint32_t* packed_down, const uint16_t* scale_down, const void* UpGate, const void* Down,
+                  const void* Wr, void* Y, int32_t* acc_upgate, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Glue for chaining the linears into a layer stack; not part of the method.
  * pq_glue_lincomb: out = c0 x0 + c1 x1 + c2 x2 + c3 x3 over n bf16 elements (x1..x3 may be NULL;
  * fp32 arithmetic, one rounding; n % 8 == 0) -- residual adds and the mean that stands in for the

@@ -28,6 +28,7 @@ EXPORTS = [
     "pq_rmsnorm_quant_fwd", "pq_rmsnorm_bwd_workspace_bytes", "pq_rmsnorm_bwd",
     "pq_linear_norm_ctx_bytes", "pq_linear_norm_workspace_bytes", "pq_linear_norm_fwd", "pq_linear_norm_bwd",
     "pq_hp_int8_ctx_bytes", "pq_hp_int8_workspace_bytes", "pq_hp_int8_fwd", "pq_hp_int8_bwd", "pq_decode_gemv_int8",
+    "pq_decode_ffn_workspace_bytes", "pq_decode_ffn",
 ]
 
 
@@ -49,6 +50,11 @@ class FFNDesc(C.Structure):
                 ("beta", C.c_float)]
 
 
+class DecodeFFNDesc(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("d_ffn", C.c_int32), ("hp_rank", C.c_int32), ("n_experts", C.c_int32),
+                ("top_k", C.c_int32), ("n_layers", C.c_int32), ("alpha", C.c_float)]
+
+
 class PQError(RuntimeError):
     pass
 
@@ -68,7 +74,8 @@ def lib():
         for name in ("pq_pack_workspace_bytes", "pq_linear_ctx_bytes", "pq_linear_workspace_bytes",
                      "pq_decode_workspace_bytes", "pq_pack_tiled64_bytes", "pq_ffn_ctx_bytes",
                      "pq_ffn_workspace_bytes", "pq_rmsnorm_bwd_workspace_bytes", "pq_linear_norm_ctx_bytes",
-                     "pq_linear_norm_workspace_bytes", "pq_hp_int8_ctx_bytes", "pq_hp_int8_workspace_bytes"):
+                     "pq_linear_norm_workspace_bytes", "pq_hp_int8_ctx_bytes", "pq_hp_int8_workspace_bytes",
+                     "pq_decode_ffn_workspace_bytes"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -334,6 +341,19 @@ def decode_ws_hidden(desc, ws):
     for nbytes in (L * B * K, L * B * 8 * (K // 32) * 4, L * B * 4, L * B * 4, L * B * k * 4, L * B * k * 4):
         off = (off + nbytes + 255) // 256 * 256
     return ws[off:off + L * B * k * r * 4].view(torch.float32).view(L, B, k, r)
+
+
+def decode_ffn_workspace(desc, device="cuda"):
+    n = lib().pq_decode_ffn_workspace_bytes(C.byref(desc))
+    if n == 0:
+        raise PQError(f"bad decode FFN descriptor: {lib().pq_last_error_string().decode()}")
+    return _bytes(n, device)
+
+
+def decode_ffn(desc, X, packed_upgate, scale_upgate, packed_down, scale_down, UpGate, Down, Wr, Y, ws, acc_upgate=None):
+    _check(lib().pq_decode_ffn(C.byref(desc), _p(X), _p(packed_upgate), _p(scale_upgate), _p(packed_down), _p(scale_down),
+                               _p(UpGate), _p(Down), _p(Wr), _p(Y), _p(acc_upgate), _p(ws), C.c_size_t(ws.numel()), _stream()))
+    return Y
 
 
 def pack_retile64(P, K):

@@ -772,6 +772,57 @@ extern "C" int pq_decode_gemv_int8(const pq_decode_desc* d, const void* X, const
   return pq_launch_decode(*d, X, packed, scale_fp16, hpA_q, hpB_q, Wr, Y, acc_out, workspace, (hipStream_t)stream, gamma_A, gamma_B);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Decoupled FFN at inference: workspace = [decode workspace of the up/gate stage (rank 2r)][U and G, 2 L F bf16]
+// [decode workspace of the down stage]
+// ---------------------------------------------------------------------------------------------
+namespace {
+struct dffn_layout { size_t ws1, UG, ws2, total; };
+int check_dffn(const pq_decode_ffn_desc* d) {
+  PQ_REQUIRE(d != nullptr, PQ_ERR_BAD_ARG, "desc is NULL");
+  PQ_REQUIRE(d->d_model > 0 && d->d_ffn > 0 && d->hp_rank > 0 && d->n_layers >= 1, PQ_ERR_BAD_ARG, "bad dimension");
+  PQ_REQUIRE(d->d_model % 128 == 0 && d->d_ffn % 128 == 0, PQ_ERR_SHAPE, "d_model=%d and d_ffn=%d must be multiples of 128", d->d_model, d->d_ffn);
+  PQ_REQUIRE(d->d_model <= 16384 && d->d_ffn <= 16384, PQ_ERR_SHAPE, "d_model=%d / d_ffn=%d exceed 16384 (a token's activations are staged in LDS)", d->d_model, d->d_ffn);
+  PQ_REQUIRE(d->hp_rank % 8 == 0, PQ_ERR_SHAPE, "hp_rank=%d must be a multiple of 8", d->hp_rank);
+  PQ_REQUIRE(d->n_experts >= 1 && d->n_experts <= 64, PQ_ERR_BAD_ARG, "n_experts=%d must be in 1..64", d->n_experts);
+  PQ_REQUIRE(d->top_k >= 1 && d->top_k <= d->n_experts, PQ_ERR_BAD_ARG, "top_k=%d must be in 1..n_experts", d->top_k);
+  return PQ_OK;
+}
+dffn_layout make_dffn_layout(const pq_decode_ffn_desc& d) {
+  pq_decode_desc d1{1, d.d_model, d.d_ffn, 2 * d.hp_rank, d.n_experts, d.top_k, d.n_layers, PQ_PACKED_TILED64, d.alpha};
+  pq_decode_desc d2{1, d.d_ffn, d.d_model, d.hp_rank, d.n_experts, d.top_k, d.n_layers, PQ_PACKED_TILED64, d.alpha};
+  size_t off[7];
+  dffn_layout L;
+  cursor c;
+  L.ws1 = c.take(pq_decode_ws_layout(d1, off));
+  L.UG = c.take((size_t)2 * d.n_layers * d.d_ffn * 2);
+  L.ws2 = c.take(pq_decode_ws_layout(d2, off));
+  L.total = c.off;
+  return L;
+}
+}  // namespace
+
+extern "C" size_t pq_decode_ffn_workspace_bytes(const pq_decode_ffn_desc* d) {
+  if (check_dffn(d) != PQ_OK) return 0;
+  return make_dffn_layout(*d).total;
+}
+
+extern "C" int pq_decode_ffn(const pq_decode_ffn_desc* d, const void* X, const uint32_t* packed_upgate, const uint16_t* scale_upgate,
+                             const uint32_t* packed_down, const uint16_t* scale_down, const void* UpGate, const void* Down,
+                             const void* Wr, void* Y, int32_t* acc_upgate, void* workspace, size_t workspace_bytes, void* stream) {
+  if (int e = check_dffn(d)) return e;
+  PQ_REQUIRE(X && packed_upgate && scale_upgate && packed_down && scale_down && UpGate && Down && Wr && Y && workspace, PQ_ERR_BAD_ARG,
+             "NULL buffer");
+  PQ_REQUIRE(aligned16(X) && aligned16(packed_upgate) && aligned16(packed_down) && aligned16(UpGate) && aligned16(Down) && aligned16(Wr) &&
+                 aligned16(Y) && aligned16(acc_upgate) && aligned16(workspace), PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
+  const dffn_layout L = make_dffn_layout(*d);
+  PQ_REQUIRE(workspace_bytes >= L.total, PQ_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, L.total);
+  char* ws = (char*)workspace;
+  return pq_launch_decode_ffn(d->n_layers, d->d_model, d->d_ffn, d->hp_rank, d->n_experts, d->top_k, d->alpha, X, packed_upgate,
+                              scale_upgate, packed_down, scale_down, UpGate, Down, Wr, Y, acc_upgate, ws + L.UG, ws + L.ws1, ws + L.ws2,
+                              (hipStream_t)stream);
+}
+
 extern "C" size_t pq_pack_tiled64_bytes(int32_t N, int32_t K) {
   if (N <= 0 || K <= 0 || K % 128 != 0) return 0;
   return (size_t)((N + 63) / 64) * 64 * (K / 32) * sizeof(uint32_t);

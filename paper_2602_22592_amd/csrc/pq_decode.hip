@@ -423,6 +423,7 @@ struct gemv_params {
   int N, K, E, r, topk;
   float alpha;
   const float* gB;        // INT8 experts: [L][E][N] gammas of the rows of hpB (then hpB is int8 [L][E][N][r])
+  int xshare;             // > 1: that many consecutive weight sets read the same token (planes, row sum, gamma of set / xshare)
 };
 
 // INT8 experts: the hidden state of every selected expert (bf16 values held as fp32) is put on the INT8 grid
@@ -607,7 +608,8 @@ __global__ __launch_bounds__(256) void decode_gemv_tiled_kernel(gemv_params p) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nw = p.K / 32, nq = nw / 4;
   const int G = (p.N + 63) / 64;
-  const uint32_t* __restrict__ planes = p.planes + (size_t)layer * 8 * nw;
+  const int xl = p.xshare > 1 ? layer / p.xshare : layer;   // the token this weight set reads
+  const uint32_t* __restrict__ planes = p.planes + (size_t)xl * 8 * nw;
 
   int a[GPB][8];
 #pragma unroll
@@ -770,9 +772,9 @@ __global__ __launch_bounds__(256) void decode_gemv_tiled_kernel(gemv_params p) {
     if (row < p.N) {
       const int dd = s_dot[g][0][lane] + s_dot[g][1][lane] + s_dot[g][2][lane] + s_dot[g][3][lane];
       const float yy = p.r > 0 ? s_yh[g][lane] : 0.0f;
-      const int acc = 2 * dd - p.rowsum[layer];
+      const int acc = 2 * dd - p.rowsum[xl];
       if (p.acc_out) p.acc_out[(size_t)layer * p.N + row] = acc;
-      const float sc = fp16_bits_to_f32(p.scale[layer]) / p.gamma[layer];
+      const float sc = fp16_bits_to_f32(p.scale[layer]) / p.gamma[xl];
       p.Y[(size_t)layer * p.N + row] = f32_to_bf16(__fmul_rn(sc, (float)acc) + p.alpha * yy);
     }
   }
@@ -1136,7 +1138,106 @@ __global__ __launch_bounds__(256, 4) void decode_gemm16_tiled_kernel(gemm16_para
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Decoupled FFN at inference (Sec. 3.2 FFN equation; App. A), one token per layer: between the up/gate products
+// and the down product one workgroup per layer forms Hd = silu(G) * U from the stored bf16 U and G (fp32), puts
+// it on the INT8 grid (codes, bit planes, row sum, gamma: the input of the packed down product) and applies the
+// experts' gated unit a = silu(Gate_e x) * (Up_e x) to the hidden pairs the prep kernel left in hug [topk][2r].
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ float silu_f(float x) { return x / (1.0f + expf(-x)); }
+
+__global__ __launch_bounds__(256) void decode_ffn_mid_kernel(const uint16_t* __restrict__ UG, int F, int r, int topk,
+                                                             const float* __restrict__ hug, float* __restrict__ act,
+                                                             int8_t* __restrict__ xq, uint32_t* __restrict__ planes,
+                                                             int* __restrict__ rowsum, float* __restrict__ gamma) {
+  extern __shared__ __attribute__((aligned(16))) float xs[];   // Hd as fp32 [F]
+  __shared__ prep_shared sh;
+  const int layer = blockIdx.x, tid = threadIdx.x;
+  const uint4* u4 = reinterpret_cast<const uint4*>(UG + (size_t)(2 * layer) * F);
+  const uint4* g4 = reinterpret_cast<const uint4*>(UG + (size_t)(2 * layer + 1) * F);
+  float amax = 0.0f;
+  for (int cb = tid; cb < F / 8; cb += 1024) {        // eight loads in flight per thread
+    uint4 uu[4], gg[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int cc = min(cb + 256 * i, F / 8 - 1);
+      uu[i] = u4[cc];
+      gg[i] = g4[cc];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = cb + 256 * i;
+      if (c < F / 8) {
+        const uint32_t uw[4] = {uu[i].x, uu[i].y, uu[i].z, uu[i].w}, gw[4] = {gg[i].x, gg[i].y, gg[i].z, gg[i].w};
+        float hd[8];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          hd[2 * t] = silu_f(__uint_as_float(gw[t] << 16)) * __uint_as_float(uw[t] << 16);
+          hd[2 * t + 1] = silu_f(__uint_as_float(gw[t] & 0xFFFF0000u)) * __uint_as_float(uw[t] & 0xFFFF0000u);
+        }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) amax = fmaxf(amax, fabsf(hd[t]));
+        *reinterpret_cast<float4*>(xs + 8 * c) = make_float4(hd[0], hd[1], hd[2], hd[3]);
+        *reinterpret_cast<float4*>(xs + 8 * c + 4) = make_float4(hd[4], hd[5], hd[6], hd[7]);
+      }
+    }
+  }
+  for (int o = tid; o < topk * r; o += 256) {
+    const int j = o / r, i = o - j * r;
+    const float* hp = hug + ((size_t)layer * topk + j) * 2 * r;
+    act[(size_t)layer * topk * r + o] = silu_f(hp[r + i]) * hp[i];
+  }
+  __syncthreads();                                    // xs complete
+  prep_quantise(amax, (size_t)layer, F, xs, sh, xq, planes, rowsum, gamma);
+}
+
 }  // namespace
+
+int pq_launch_decode_ffn(int L, int D, int F, int r, int E, int topk, float alpha, const void* X, const uint32_t* packed_upgate,
+                         const uint16_t* scale_upgate, const uint32_t* packed_down, const uint16_t* scale_down,
+                         const void* UpGate, const void* Down, const void* Wr, void* Y, int32_t* acc_upgate, void* UG,
+                         void* ws1, void* ws2, hipStream_t s) {
+  pq_decode_desc d1{1, D, F, 2 * r, E, topk, L, PQ_PACKED_TILED64, alpha};
+  pq_decode_desc d2{1, F, D, r, E, topk, L, PQ_PACKED_TILED64, alpha};
+  size_t o1[7], o2[7];
+  pq_decode_ws_layout(d1, o1);
+  pq_decode_ws_layout(d2, o2);
+  char* w1 = (char*)ws1;
+  char* w2 = (char*)ws2;
+  int8_t* xq1 = (int8_t*)(w1 + o1[0]); uint32_t* pl1 = (uint32_t*)(w1 + o1[1]); int* rs1 = (int*)(w1 + o1[2]);
+  float* gm1 = (float*)(w1 + o1[3]); int* idx = (int*)(w1 + o1[4]); float* gate = (float*)(w1 + o1[5]); float* hug = (float*)(w1 + o1[6]);
+  int8_t* xq2 = (int8_t*)(w2 + o2[0]); uint32_t* pl2 = (uint32_t*)(w2 + o2[1]); int* rs2 = (int*)(w2 + o2[2]);
+  float* gm2 = (float*)(w2 + o2[3]); float* act = (float*)(w2 + o2[6]);
+  {  // quantiser of x, router, expert hidden pairs [Up_e x ; Gate_e x]
+    pq_prof_scope prof(PQP_DECODE_PREP, s);
+    const int parts = 1 + (topk * 2 * r + PREP_H_ROWS - 1) / PREP_H_ROWS;
+    decode_prep_h_kernel<false><<<L * parts, 256, (size_t)D * sizeof(float), s>>>((const uint16_t*)X, (const uint16_t*)Wr, UpGate, nullptr, D, E,
+                                                                                 2 * r, topk, parts, xq1, pl1, rs1, gm1, idx, gate, hug);
+    PQ_CHECK_LAUNCH("decode_prep_h_kernel");
+  }
+  {  // U and G: 2 L weight sets, each pair reading its layer's token once quantised
+    pq_prof_scope prof(PQP_DECODE_MAIN, s);
+    gemv_params p{packed_upgate, scale_upgate, pl1, rs1, gm1, nullptr, nullptr, nullptr, nullptr, (uint16_t*)UG, acc_upgate,
+                  F, D, E, 0, 0, alpha, nullptr, 2};
+    dim3 grid((F + 63) / 64, 2 * L);
+    decode_gemv_tiled_kernel<1, false><<<grid, 256, 0, s>>>(p);
+    PQ_CHECK_LAUNCH("decode_gemv_tiled_kernel");
+  }
+  {  // gated unit, quantiser of Hd, experts' gated unit
+    pq_prof_scope prof(PQP_DECODE_PREP, s);
+    decode_ffn_mid_kernel<<<L, 256, (size_t)F * sizeof(float), s>>>((const uint16_t*)UG, F, r, topk, hug, act, xq2, pl2, rs2, gm2);
+    PQ_CHECK_LAUNCH("decode_ffn_mid_kernel");
+  }
+  {  // down product + experts' down projections
+    pq_prof_scope prof(PQP_DECODE_MAIN, s);
+    gemv_params p{packed_down, scale_down, pl2, rs2, gm2, (const uint16_t*)Down, idx, gate, act, (uint16_t*)Y, nullptr,
+                  D, F, E, r, topk, alpha, nullptr, 1};
+    dim3 grid((D + 63) / 64, L);
+    decode_gemv_tiled_kernel<1, false><<<grid, 256, 0, s>>>(p);
+    PQ_CHECK_LAUNCH("decode_gemv_tiled_kernel");
+  }
+  return PQ_OK;
+}
 
 // ------------------------------------------------------------------------------------------
 size_t pq_decode_ws_layout(const pq_decode_desc& d, size_t* off /* [7]: xq planes rowsum gamma idx gate h */) {
