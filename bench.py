@@ -109,6 +109,35 @@ def decode_bench(pq, torch, batch, n_layers=64, steps=20, warmup=3, int8_experts
             "us_per_layer": round(total_us / n_layers, 3), "bytes_per_layer": (main_bytes + prep_bytes) // n_layers}
 
 
+def decode_ffn_bench(pq, torch, n_layers=32, steps=20, warmup=3):
+    """The decoupled FFN at inference, one token per layer: 4096 -> 11008 -> 4096 packed 1-bit matrices with E=8
+    top-2 experts of hidden width 64, `n_layers` distinct FFNs per call (541 MB of bits)."""
+    D, F, E, r, k = 4096, 11008, 8, 64, 2
+    g = torch.Generator(device="cuda").manual_seed(9)
+    bf = torch.bfloat16
+    rnd = lambda *s: torch.randint(-2**31, 2**31 - 1, s, dtype=torch.int32, device="cuda", generator=g)
+    Pug = rnd(n_layers, 2, ((F + 63) // 64) * 64 * (D // 32))     # random bits, already in the row-interleaved order
+    Pd = rnd(n_layers, ((D + 63) // 64) * 64 * (F // 32))
+    X = torch.randn((n_layers, D), device="cuda", generator=g).to(bf)
+    UpGate = (torch.randn((n_layers, E, 2 * r, D), device="cuda", generator=g) * 0.02).to(bf)
+    Down = (torch.randn((n_layers, E, D, r), device="cuda", generator=g) * 0.02).to(bf)
+    Wr = (torch.randn((n_layers, E, D), device="cuda", generator=g) * 0.02).to(bf)
+    sug = torch.from_numpy(np.full((n_layers, 2), np.float16(0.016)).view(np.int16)).cuda()
+    sd = torch.from_numpy(np.full(n_layers, np.float16(0.4 * 0.016)).view(np.int16)).cuda()
+    Y = torch.empty((n_layers, D), dtype=bf, device="cuda")
+    desc = pq.DecodeFFNDesc(D, F, r, E, k, n_layers, 1.5)
+    ws = pq.decode_ffn_workspace(desc)
+    run = lambda: pq.decode_ffn(desc, X, Pug, sug, Pd, sd, UpGate, Down, Wr, Y, ws)
+    total_us = 1e3 * _time_steps(torch, run, steps, warmup)
+    prof = _profile_steps(pq, torch, run, steps)
+    # algorithmic bytes per layer: three packed matrices, the selected experts (2r x D and D x r bf16), router, x, y
+    per_layer = 3 * D * F // 8 + k * (2 * r * D + D * r) * 2 + E * D * 2 + 4 * D
+    return {"layers_per_call": n_layers, "call_us": round(total_us, 2), "us_per_layer": round(total_us / n_layers, 3),
+            "bytes_per_layer": per_layer, "whole_call_GBps": round(per_layer * n_layers / total_us / 1e3, 1),
+            "frac_hbm": round(per_layer * n_layers / total_us / 1e3 / 8000.0, 4),
+            "kernels_us_total_per_call": {k_: round(1e3 * ms / steps, 2) for k_, (ms, n) in sorted(prof.items())}}
+
+
 def _time_steps(torch, fn, steps, warmup):
     for _ in range(warmup):
         fn()
@@ -365,6 +394,7 @@ def main():
         out["decode_gemv"] = {"metric": "1-bit decode GEMV HBM GB/s (4096->11008, E=8 top-2 r=64 experts)",
                               "B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8),
                               "B1_int8_experts": decode_bench(pq, torch, 1, int8_experts=True)}
+        out["decode_ffn"] = decode_ffn_bench(pq, torch)
     if not args.no_norm:
         out["rmsnorm_quant"] = norm_quant_bench(pq, torch)
     if not args.no_hp8:

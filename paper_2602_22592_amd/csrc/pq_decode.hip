@@ -79,9 +79,12 @@ __device__ __forceinline__ float prep_load_x(const uint16_t* __restrict__ X, siz
 }
 
 // INT8 codes, bit planes, row sum and gamma of one token (all threads of the workgroup; xs is complete)
+// (part, parts): several workgroups may share one token; each forms gamma and the row sum for itself (cheap) but
+// writes codes and bit planes only for every parts-th group of 256 columns, and part 0 writes gamma and the row sum.
 __device__ __forceinline__ void prep_quantise(float amax, size_t tok, int K, const float* xs, prep_shared& sh,
                                               int8_t* __restrict__ xq, uint32_t* __restrict__ planes,
-                                              int* __restrict__ rowsum, float* __restrict__ gamma) {
+                                              int* __restrict__ rowsum, float* __restrict__ gamma, int part = 0,
+                                              int parts = 1) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   amax = wave_max(amax);
   if (lane == 0) sh.red[wave] = amax;
@@ -90,7 +93,7 @@ __device__ __forceinline__ void prep_quantise(float amax, size_t tok, int K, con
     const float a = fmaxf(fmaxf(sh.red[0], sh.red[1]), fmaxf(sh.red[2], sh.red[3]));
     const float g = 128.0f / fmaxf(a, 1e-5f);
     sh.gamma = g;
-    gamma[tok] = g;
+    if (part == 0) gamma[tok] = g;
   }
   __syncthreads();
   const float g = sh.gamma;
@@ -100,10 +103,11 @@ __device__ __forceinline__ void prep_quantise(float amax, size_t tok, int K, con
     const float y = __fmul_rn(xs[k0 + lane], g);
     const float r = fminf(fmaxf(rintf(y), -128.0f), 127.0f);
     const int q = (int)r;
+    isum += q;
+    if (parts > 1 && (k0 >> 8) % parts != part) continue;     // uniform: another workgroup writes these 256 columns
     // code order inside a 32-column group follows the byte order the small-batch MFMA kernels derive
     // from a weight word: column 8 b + t sits at byte 4 (7 - t) + b
     xq[tok * K + k0 + (lane & 32) + 4 * (7 - (lane & 7)) + ((lane & 31) >> 3)] = (int8_t)q;
-    isum += q;
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
       const unsigned long long m = __ballot(((uint32_t)q >> p) & 1u);
@@ -118,7 +122,7 @@ __device__ __forceinline__ void prep_quantise(float amax, size_t tok, int K, con
   for (int o = 32; o > 0; o >>= 1) isum += __shfl_xor(isum, o, 64);
   if (lane == 0) sh.isum[wave] = isum;
   __syncthreads();
-  if (tid == 0) rowsum[tok] = sh.isum[0] + sh.isum[1] + sh.isum[2] + sh.isum[3];
+  if (tid == 0 && part == 0) rowsum[tok] = sh.isum[0] + sh.isum[1] + sh.isum[2] + sh.isum[3];
 }
 
 // Router of one token: fp64 logits rounded once to fp32, top-k on logits (ties to the lower index), softmax
@@ -1145,6 +1149,9 @@ __global__ __launch_bounds__(256, 4) void decode_gemm16_tiled_kernel(gemm16_para
 // experts' gated unit a = silu(Gate_e x) * (Up_e x) to the hidden pairs the prep kernel left in hug [topk][2r].
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + expf(-x)); }
+// Workgroups per layer: each forms all of Hd (its maximum decides gamma) but writes codes and planes for an
+// eighth of the columns, which is the expensive part of the quantiser.
+constexpr int FFN_MID_PARTS = 8;
 
 __global__ __launch_bounds__(256) void decode_ffn_mid_kernel(const uint16_t* __restrict__ UG, int F, int r, int topk,
                                                              const float* __restrict__ hug, float* __restrict__ act,
@@ -1152,7 +1159,7 @@ __global__ __launch_bounds__(256) void decode_ffn_mid_kernel(const uint16_t* __r
                                                              int* __restrict__ rowsum, float* __restrict__ gamma) {
   extern __shared__ __attribute__((aligned(16))) float xs[];   // Hd as fp32 [F]
   __shared__ prep_shared sh;
-  const int layer = blockIdx.x, tid = threadIdx.x;
+  const int layer = blockIdx.x / FFN_MID_PARTS, part = blockIdx.x % FFN_MID_PARTS, tid = threadIdx.x;
   const uint4* u4 = reinterpret_cast<const uint4*>(UG + (size_t)(2 * layer) * F);
   const uint4* g4 = reinterpret_cast<const uint4*>(UG + (size_t)(2 * layer + 1) * F);
   float amax = 0.0f;
@@ -1182,13 +1189,14 @@ __global__ __launch_bounds__(256) void decode_ffn_mid_kernel(const uint16_t* __r
       }
     }
   }
-  for (int o = tid; o < topk * r; o += 256) {
-    const int j = o / r, i = o - j * r;
-    const float* hp = hug + ((size_t)layer * topk + j) * 2 * r;
-    act[(size_t)layer * topk * r + o] = silu_f(hp[r + i]) * hp[i];
-  }
+  if (part == 0)
+    for (int o = tid; o < topk * r; o += 256) {
+      const int j = o / r, i = o - j * r;
+      const float* hp = hug + ((size_t)layer * topk + j) * 2 * r;
+      act[(size_t)layer * topk * r + o] = silu_f(hp[r + i]) * hp[i];
+    }
   __syncthreads();                                    // xs complete
-  prep_quantise(amax, (size_t)layer, F, xs, sh, xq, planes, rowsum, gamma);
+  prep_quantise(amax, (size_t)layer, F, xs, sh, xq, planes, rowsum, gamma, part, FFN_MID_PARTS);
 }
 
 }  // namespace
@@ -1224,8 +1232,8 @@ int pq_launch_decode_ffn(int L, int D, int F, int r, int E, int topk, float alph
     PQ_CHECK_LAUNCH("decode_gemv_tiled_kernel");
   }
   {  // gated unit, quantiser of Hd, experts' gated unit
-    pq_prof_scope prof(PQP_DECODE_PREP, s);
-    decode_ffn_mid_kernel<<<L, 256, (size_t)F * sizeof(float), s>>>((const uint16_t*)UG, F, r, topk, hug, act, xq2, pl2, rs2, gm2);
+    pq_prof_scope prof(PQP_SWIGLU, s);
+    decode_ffn_mid_kernel<<<L * FFN_MID_PARTS, 256, (size_t)F * sizeof(float), s>>>((const uint16_t*)UG, F, r, topk, hug, act, xq2, pl2, rs2, gm2);
     PQ_CHECK_LAUNCH("decode_ffn_mid_kernel");
   }
   {  // down product + experts' down projections
