@@ -931,10 +931,9 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
     tile_stage<BK2, BN, NT, KB, FAST> sb2;
     sa2.setup(ph2.A2, m0, M, tid);
     sb2.setup(ph2.B2, n0, N, tid);
-    if (ph2.K2 > 0) {
-      sa2.load(ph2.A2, 0, ph2.K2);
-      sb2.load(ph2.B2, 0, ph2.K2);
-    }
+    // the first A2 tile (activation-sized, far away) is requested before the rescale arithmetic, the first B2 tile
+    // (a small factor, cache-resident) after it: holding both across the rescale overflows the register file
+    if (ph2.K2 > 0) sa2.load(ph2.A2, 0, ph2.K2);
     const float sc1 = ph2.dev_scale1 ? __fmul_rn(ph2.scale1, *ph2.dev_scale1) : ph2.scale1;
     if (ph2.row_div1) {                              // uniform: one divisor load and one division per row of the tile
       for (int r = tid; r < BM; r += NT) rowscale[r] = sc1 / ph2.row_div1[min(m0 + r, M - 1)];
@@ -951,6 +950,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
           accf[i][j][v] = (float)e1 * sr;
         }
     }
+    if (ph2.K2 > 0) sb2.load(ph2.B2, 0, ph2.K2);
     int st2 = 0;
     for (int k2 = 0; k2 < ph2.K2; k2 += KS2) {
       unsigned char* stage = smem + st2 * STAGE;
