@@ -79,12 +79,53 @@ __device__ __forceinline__ float prep_load_x(const uint16_t* __restrict__ X, siz
 }
 
 // INT8 codes, bit planes, row sum and gamma of one token (all threads of the workgroup; xs is complete)
-// (part, parts): several workgroups may share one token; each forms gamma and the row sum for itself (cheap) but
-// writes codes and bit planes only for every parts-th group of 256 columns, and part 0 writes gamma and the row sum.
 __device__ __forceinline__ void prep_quantise(float amax, size_t tok, int K, const float* xs, prep_shared& sh,
                                               int8_t* __restrict__ xq, uint32_t* __restrict__ planes,
-                                              int* __restrict__ rowsum, float* __restrict__ gamma, int part = 0,
-                                              int parts = 1) {
+                                              int* __restrict__ rowsum, float* __restrict__ gamma) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  amax = wave_max(amax);
+  if (lane == 0) sh.red[wave] = amax;
+  __syncthreads();
+  if (tid == 0) {
+    const float a = fmaxf(fmaxf(sh.red[0], sh.red[1]), fmaxf(sh.red[2], sh.red[3]));
+    const float g = 128.0f / fmaxf(a, 1e-5f);
+    sh.gamma = g;
+    gamma[tok] = g;
+  }
+  __syncthreads();
+  const float g = sh.gamma;
+  // lane <-> column, a wave-wide ballot per bit plane yields two words
+  int isum = 0;
+  for (int k0 = wave * 64; k0 < K; k0 += 256) {
+    const float y = __fmul_rn(xs[k0 + lane], g);
+    const float r = fminf(fmaxf(rintf(y), -128.0f), 127.0f);
+    const int q = (int)r;
+    // code order inside a 32-column group follows the byte order the small-batch MFMA kernels derive
+    // from a weight word: column 8 b + t sits at byte 4 (7 - t) + b
+    xq[tok * K + k0 + (lane & 32) + 4 * (7 - (lane & 7)) + ((lane & 31) >> 3)] = (int8_t)q;
+    isum += q;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      const unsigned long long m = __ballot(((uint32_t)q >> p) & 1u);
+      // plane words are grouped per 128 columns: [token][K/128][plane][4 words]
+      if (lane < 2) {
+        const int wd = (k0 >> 5) + lane;
+        planes[((tok * (K / 128) + (wd >> 2)) * 8 + p) * 4 + (wd & 3)] = (uint32_t)(m >> (32 * lane));
+      }
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) isum += __shfl_xor(isum, o, 64);
+  if (lane == 0) sh.isum[wave] = isum;
+  __syncthreads();
+  if (tid == 0) rowsum[tok] = sh.isum[0] + sh.isum[1] + sh.isum[2] + sh.isum[3];
+}
+
+// (part, parts): several workgroups may share one token; each forms gamma and the row sum for itself (cheap) but
+// writes codes and bit planes only for every parts-th group of 256 columns, and part 0 writes gamma and the row sum.
+__device__ __forceinline__ void prep_quantise_slice(float amax, size_t tok, int K, const float* xs, prep_shared& sh,
+                                              int8_t* __restrict__ xq, uint32_t* __restrict__ planes,
+                                              int* __restrict__ rowsum, float* __restrict__ gamma, int part, int parts) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   amax = wave_max(amax);
   if (lane == 0) sh.red[wave] = amax;
@@ -1196,7 +1237,7 @@ __global__ __launch_bounds__(256) void decode_ffn_mid_kernel(const uint16_t* __r
       act[(size_t)layer * topk * r + o] = silu_f(hp[r + i]) * hp[i];
     }
   __syncthreads();                                    // xs complete
-  prep_quantise(amax, (size_t)layer, F, xs, sh, xq, planes, rowsum, gamma, part, FFN_MID_PARTS);
+  prep_quantise_slice(amax, (size_t)layer, F, xs, sh, xq, planes, rowsum, gamma, part, FFN_MID_PARTS);
 }
 
 }  // namespace
