@@ -393,7 +393,8 @@ def main():
     if not args.no_decode:
         out["decode_gemv"] = {"metric": "1-bit decode GEMV HBM GB/s (4096->11008, E=8 top-2 r=64 experts)",
                               "B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8),
-                              "B1_int8_experts": decode_bench(pq, torch, 1, int8_experts=True)}
+                              "B1_int8_experts": decode_bench(pq, torch, 1, int8_experts=True),
+                              "B8_int8_experts": decode_bench(pq, torch, 8, int8_experts=True)}
         out["decode_ffn"] = decode_ffn_bench(pq, torch)
     if not args.no_norm:
         out["rmsnorm_quant"] = norm_quant_bench(pq, torch)

@@ -261,7 +261,8 @@ int pq_decode_gemv(const pq_decode_desc* desc, const void* X, const uint32_t* pa
  * both sums exact int32, and y = 1-bit product + alpha * sum_j gate_j Y_e_j as in pq_decode_gemv.  The expert
  * weights are read as 1 byte per entry instead of 2.  The workspace is that of pq_decode_gemv; after the call
  * its hidden-state section holds H ([L][top_k][r] fp32 values of the bf16 roundings, for tests).
- * Limits: batch == 1; r % 32 == 0; top_k <= 8 and top_k * r <= 2048; K % 128 == 0 and K <= 13056. */
+ * Limits: r % 32 == 0.  batch == 1: top_k <= 8 and top_k * r <= 2048; K % 128 == 0 and K <= 13056.
+ * batch > 1: row-interleaved packing only, r % 64 == 0 and (E r) % 128 == 0, otherwise the limits of pq_decode_gemv. */
 int pq_decode_gemv_int8(const pq_decode_desc* desc, const void* X, const uint32_t* packed, const uint16_t* scale_fp16,
                         const int8_t* hpA_q, const float* gamma_A, const int8_t* hpB_q, const float* gamma_B,
                         const void* Wr, void* Y, int32_t* acc_out, void* workspace, size_t workspace_bytes,

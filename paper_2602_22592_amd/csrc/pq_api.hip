@@ -758,11 +758,17 @@ extern "C" int pq_decode_gemv_int8(const pq_decode_desc* d, const void* X, const
                                    const void* Wr, void* Y, int32_t* acc_out, void* workspace, size_t workspace_bytes,
                                    void* stream) {
   if (int e = check_decode(d)) return e;
-  PQ_REQUIRE(d->batch == 1, PQ_ERR_SHAPE, "INT8 experts are implemented for batch 1 (batch=%d)", d->batch);
   PQ_REQUIRE(d->hp_rank > 0 && d->hp_rank % 32 == 0, PQ_ERR_SHAPE, "hp_rank=%d must be a positive multiple of 32", d->hp_rank);
-  PQ_REQUIRE(d->top_k <= 8 && d->top_k * d->hp_rank <= 2048, PQ_ERR_SHAPE, "top_k=%d (at most 8) times hp_rank=%d exceeds 2048",
-             d->top_k, d->hp_rank);
-  PQ_REQUIRE((size_t)d->d_in * 5 <= 64 * 1024, PQ_ERR_SHAPE, "d_in=%d exceeds 13056 (activations and their codes are staged in LDS)", d->d_in);
+  if (d->batch == 1) {
+    PQ_REQUIRE(d->top_k <= 8 && d->top_k * d->hp_rank <= 2048, PQ_ERR_SHAPE, "top_k=%d (at most 8) times hp_rank=%d exceeds 2048",
+               d->top_k, d->hp_rank);
+    PQ_REQUIRE((size_t)d->d_in * 5 <= 64 * 1024, PQ_ERR_SHAPE, "d_in=%d exceeds 13056 (activations and their codes are staged in LDS)", d->d_in);
+  } else {
+    PQ_REQUIRE(d->packed_layout == PQ_PACKED_TILED64, PQ_ERR_SHAPE, "INT8 experts with batch > 1 need the row-interleaved packing");
+    PQ_REQUIRE(d->hp_rank % 64 == 0 && (d->n_experts * d->hp_rank) % 128 == 0, PQ_ERR_SHAPE,
+               "INT8 experts with batch > 1 need hp_rank=%d %% 64 == 0 and n_experts * hp_rank %% 128 == 0", d->hp_rank);
+    PQ_REQUIRE(d->d_out % 4 == 0, PQ_ERR_SHAPE, "d_out=%d must be a multiple of 4", d->d_out);
+  }
   PQ_REQUIRE(X && packed && scale_fp16 && Y && workspace && hpA_q && gamma_A && hpB_q && gamma_B && Wr, PQ_ERR_BAD_ARG, "NULL buffer");
   PQ_REQUIRE(aligned16(X) && aligned16(packed) && aligned16(Y) && aligned16(workspace) && aligned16(hpA_q) && aligned16(hpB_q) &&
                  aligned16(Wr) && aligned16(acc_out), PQ_ERR_SHAPE, "buffers must be 16-byte aligned");

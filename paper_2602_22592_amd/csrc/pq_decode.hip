@@ -30,6 +30,12 @@ __device__ __forceinline__ uint4 nt_load16(const uint4* p) {
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
 __device__ __forceinline__ float fp16_bits_to_f32(uint16_t h) {
   _Float16 x = __builtin_bit_cast(_Float16, h);
   return (float)x;
@@ -262,12 +268,6 @@ constexpr int PREP_H_ROWS = PQ_PREP_H_ROWS;   // rows per workgroup: few enough 
 // hidden state is the exact integer product of the token's codes with a row, de-quantised as
 // fl32(fl32(1/gamma_x) * acc) / gamma_a and rounded to bf16 (stored as fp32).  The token's codes (natural column
 // order) sit in LDS behind its fp32 activations.
-__device__ __forceinline__ int wave_sum_i(int v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
-}
-
 template <bool I8>
 __global__ __launch_bounds__(256) void decode_prep_h_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wr,
                                                             const void* __restrict__ hpA_, const float* __restrict__ gA,
@@ -409,6 +409,82 @@ __global__ __launch_bounds__(256) void decode_prep_h_kernel(const uint16_t* __re
 // ------------------------------------------------------------------------------------------
 // Expert hidden state: one wavefront per (layer, token, slot, r): h = A_e[r,:] . x   (bf16 in, fp32 out)
 // ------------------------------------------------------------------------------------------
+// INT8 experts: hpA holds INT8 codes with one gamma per row (gA).  One wavefront per (token, slot, group of 16
+// rows): the token's codes are formed once per 4096 columns from x and its gamma (the quantiser's arithmetic)
+// and kept in registers for the 16 rows; the products are exact integers, de-quantised as
+// fl32(fl32(1/gamma_x) * acc) / gamma_a and rounded to bf16 (held as fp32).  Columns past the end carry zero
+// codes and re-read the last chunk, so no load sits behind a branch.
+constexpr int H8_ROWS = 16;
+__global__ __launch_bounds__(256) void decode_h_int8_kernel(const uint16_t* __restrict__ X, const int8_t* __restrict__ A8,
+                                                            const float* __restrict__ gA, const float* __restrict__ gamma,
+                                                            const int* __restrict__ idx, int B, int K, int E, int r, int topk,
+                                                            int total, float* __restrict__ h) {
+  const int lane = threadIdx.x & 63;
+  const int o = blockIdx.x * 4 + (threadIdx.x >> 6);   // slot * (r / 16) + row group
+  if (o >= total) return;
+  const int ngrp = r / H8_ROWS;
+  const int slot = o / ngrp, rg = o - slot * ngrp;
+  const int tok = slot / topk, layer = tok / B;
+  const int e = idx[slot];
+  const size_t arow0 = ((size_t)layer * E + e) * r + (size_t)rg * H8_ROWS;
+  const uint4* x4 = reinterpret_cast<const uint4*>(X + (size_t)tok * K);
+  const float gx = gamma[tok];
+  const int nch = K / 16;
+  int acc[H8_ROWS];
+#pragma unroll
+  for (int rr = 0; rr < H8_ROWS; ++rr) acc[rr] = 0;
+  for (int c0 = 0; c0 < nch; c0 += 256) {
+    uint32_t xw[4][4];
+    int cc[4];
+    uint4 xv[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      cc[i] = min(c0 + lane + 64 * i, nch - 1);
+      xv[2 * i] = x4[2 * cc[i]];
+      xv[2 * i + 1] = x4[2 * cc[i] + 1];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const bool ok = c0 + lane + 64 * i < nch;
+      const uint32_t w8[8] = {xv[2 * i].x, xv[2 * i].y, xv[2 * i].z, xv[2 * i].w, xv[2 * i + 1].x, xv[2 * i + 1].y, xv[2 * i + 1].z, xv[2 * i + 1].w};
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {                    // four codes per word: columns 4 d .. 4 d + 3 of the chunk
+        const float f[4] = {__uint_as_float(w8[2 * d] << 16), __uint_as_float(w8[2 * d] & 0xFFFF0000u),
+                            __uint_as_float(w8[2 * d + 1] << 16), __uint_as_float(w8[2 * d + 1] & 0xFFFF0000u)};
+        uint32_t w = 0u;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int q = (int)fminf(fmaxf(rintf(__fmul_rn(f[t], gx)), -128.0f), 127.0f);
+          w |= (uint32_t)(q & 0xFF) << (8 * t);
+        }
+        xw[i][d] = ok ? w : 0u;
+      }
+    }
+#pragma unroll 4
+    for (int rr = 0; rr < H8_ROWS; ++rr) {
+      const uint4* a4 = reinterpret_cast<const uint4*>(A8 + (arow0 + rr) * K);
+      uint4 av[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) av[i] = nt_load16(a4 + cc[i]);
+      int a = acc[rr];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        a = __builtin_amdgcn_sdot4((int)av[i].x, (int)xw[i][0], a, false);
+        a = __builtin_amdgcn_sdot4((int)av[i].y, (int)xw[i][1], a, false);
+        a = __builtin_amdgcn_sdot4((int)av[i].z, (int)xw[i][2], a, false);
+        a = __builtin_amdgcn_sdot4((int)av[i].w, (int)xw[i][3], a, false);
+      }
+      acc[rr] = a;
+    }
+  }
+  const float sx = 1.0f / gx;
+#pragma unroll
+  for (int rr = 0; rr < H8_ROWS; ++rr) {
+    const int t = wave_sum_i(acc[rr]);
+    if (lane == 0) h[(size_t)slot * r + rg * H8_ROWS + rr] = bf16_to_f32(f32_to_bf16(__fmul_rn(sx, (float)t) / gA[arow0 + rr]));
+  }
+}
+
 __global__ __launch_bounds__(256) void decode_h_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ hpA,
                                                        const int* __restrict__ idx, int B, int K, int E, int r, int topk,
                                                        int total, float* __restrict__ h) {
@@ -855,6 +931,7 @@ struct gemm16_params {
   int* acc_out;           // [L][B][N] or null
   int B, N, K, E, r, topk;
   float alpha;
+  const float* gB;        // INT8 experts: [L][E][N] gammas of the rows of hpB (then hpB is int8 [L][E][N][r])
 };
 
 constexpr int G16_RT = 4;                           // 16-row MFMA tiles per wavefront
@@ -864,7 +941,10 @@ constexpr int G16_ROWS_PER_BLOCK = 4 * G16_ROWS_PER_WAVE;
 // Stages the batch's INT8 codes and the gate-weighted expert hidden states into LDS and returns the mask
 // of experts that some token selected.  xs: [TOKS][K] int8, 16-byte chunk c of token j at chunk c ^ (j & 7);
 // hm: [TOKS][E*r] bf16 (zero where a token did not select the expert), same chunk swizzle.
-template <int TOKS>
+// I8: hm holds INT8 codes instead ([TOKS][E*r] bytes, 16-byte chunk c of token j at chunk c ^ (j & 7)): every
+// selected (token, expert) hidden state is put on the INT8 grid with its own gamma (Sec. 3.1 quantiser), one
+// wavefront per slot; behind the codes sit 1/gamma_h and the gate per (token, expert), zero where not selected.
+template <int TOKS, bool I8 = false>
 __device__ __forceinline__ unsigned long long g16_stage_inputs(const gemm16_params& p, int layer, unsigned char* xs,
                                                                uint16_t* hm) {
   const int tid = threadIdx.x;
@@ -887,12 +967,39 @@ __device__ __forceinline__ unsigned long long g16_stage_inputs(const gemm16_para
       const int e = s < nslot ? p.idx[(size_t)layer * nslot + s] : -1;
       for (int ee = 0; ee < p.E; ++ee) used |= (__ballot(e == ee) != 0ull) ? (1ull << ee) : 0ull;
     }
+    if constexpr (I8) {
+      int8_t* hq = reinterpret_cast<int8_t*>(hm);
+      float* inv = reinterpret_cast<float*>(hq + (size_t)TOKS * Er);      // [TOKS][E] 1/gamma_h, then [TOKS][E] gates
+      float* gts = inv + TOKS * p.E;
+      for (int c = tid; c < 2 * TOKS * p.E; c += 256) inv[c] = 0.0f;
+      __syncthreads();
+      const int lane = tid & 63, wave = tid >> 6;
+      for (int s = wave; s < nslot; s += 4) {         // wave-uniform
+        const int j = s / p.topk;
+        const int e = p.idx[(size_t)layer * nslot + s];
+        const float* hs = p.h + ((size_t)layer * nslot + s) * p.r;
+        float amax = 0.0f;
+        for (int rr = lane; rr < p.r; rr += 64) amax = fmaxf(amax, fabsf(hs[rr]));
+        amax = wave_max(amax);
+        const float gh = 128.0f / fmaxf(amax, 1e-5f);
+        for (int rr = lane; rr < p.r; rr += 64) {
+          const int q = (int)fminf(fmaxf(rintf(__fmul_rn(hs[rr], gh)), -128.0f), 127.0f);
+          const int col = e * p.r + rr;
+          hq[(size_t)j * Er + ((((col >> 4) ^ (j & 7)) << 4) | (col & 15))] = (int8_t)q;
+        }
+        if (lane == 0) {
+          inv[j * p.E + e] = 1.0f / gh;
+          gts[j * p.E + e] = p.gate[(size_t)layer * nslot + s];
+        }
+      }
+    } else {
     for (int c = tid; c < p.B * p.topk * p.r; c += 256) {
       const int rr = c % p.r, s = c / p.r, j = s / p.topk;
       const int e = p.idx[(size_t)layer * p.B * p.topk + s];
       const float v = p.gate[(size_t)layer * p.B * p.topk + s] * p.h[((size_t)layer * p.B * p.topk + s) * p.r + rr];
       const int col = e * p.r + rr;                  // 16-byte chunk (col/8) stored at chunk ^ (j & 7)
       hm[(size_t)j * Er + ((((col >> 3) ^ (j & 7)) << 3) | (col & 7))] = f32_to_bf16(v);
+    }
     }
   }
   __syncthreads();
@@ -1039,7 +1146,7 @@ __global__ __launch_bounds__(256) void decode_gemm16_kernel(gemm16_params p) {
 // makes a round trip through a wave-private LDS patch: written as loaded, read back one word per tile
 // (word g of row 16 t + i, bank-conflict free).  Results leave through the same patch so that a token's
 // 64 outputs are stored as one 128-byte run.
-template <int TOKS>
+template <int TOKS, bool I8 = false>
 __global__ __launch_bounds__(256, 4) void decode_gemm16_tiled_kernel(gemm16_params p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char dsm[];
   // dsm: xq [TOKS][K] int8, then a region that first holds Hm [TOKS][E*r] bf16 (expert phase) and afterwards
@@ -1067,14 +1174,60 @@ __global__ __launch_bounds__(256, 4) void decode_gemm16_tiled_kernel(gemm16_para
   uint4 w[8];
 #pragma unroll
   for (int jj = 0; jj < 8; ++jj) w[jj] = nt_load16(Pg + (size_t)(jj < nq ? jj : nq - 1) * 64);
-  const unsigned long long used = g16_stage_inputs<TOKS>(p, layer, xs, hm);   // overlaps the first loads
+  const unsigned long long used = g16_stage_inputs<TOKS, I8>(p, layer, xs, hm);   // overlaps the first loads
   const bool active = grp < G;                        // idle wavefronts of the last workgroup still meet the barrier
 
   // experts selected by at least one token of the batch (dense-masked bf16 MFMA, 32 columns of r per issue)
   f32x4_t accf[4];
 #pragma unroll
   for (int t = 0; t < 4; ++t) accf[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  if (p.r > 0 && active) {
+  if constexpr (I8) {
+    // INT8 experts: per selected expert an exact int8 MFMA product (64 columns of r per issue, lane (i, g) holds
+    // bytes 16 g .. 16 g + 15 of row i resp. token i), then D[row 4 g + v][token i] is de-quantised with the
+    // token's 1/gamma_h and the row's gamma_B and added with the gate; scales of unselected pairs are zero.
+    if (active) {
+      const int8_t* hq = reinterpret_cast<const int8_t*>(hm);
+      const float* inv = reinterpret_cast<const float*>(hq + (size_t)TOKS * Er);
+      const float* gts = inv + TOKS * p.E;
+      const int nblk = p.r / 64;
+      size_t roff[4];
+      int rowg[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int row = grp * 64 + 16 * t + i;
+        roff[t] = (size_t)(row < p.N ? row : 0) * p.r + 16 * g;
+        const int r4 = grp * 64 + 16 * t + 4 * g;     // first of the four output rows this lane holds (N % 4 == 0)
+        rowg[t] = r4 < p.N ? r4 : 0;
+      }
+      for (int e = 0; e < p.E; ++e) {
+        if (!((used >> e) & 1ull)) continue;
+        const int8_t* Be = (const int8_t*)p.hpB + ((size_t)layer * p.E + e) * p.N * p.r;
+        i32x4_t ai[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) ai[t] = i32x4_t{0, 0, 0, 0};
+        for (int blk = 0; blk < nblk; ++blk) {
+          uint4 a[4];
+#pragma unroll
+          for (int t = 0; t < 4; ++t) a[t] = nt_load16(reinterpret_cast<const uint4*>(Be + roff[t] + 64 * blk));
+          const int chunk = (e * p.r + 64 * blk) / 16 + g;
+          const uint4 b = *reinterpret_cast<const uint4*>(hq + (size_t)il * Er + ((chunk ^ (il & 7)) << 4));
+#pragma unroll
+          for (int t = 0; t < 4; ++t)
+            ai[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4_t, a[t]), __builtin_bit_cast(i32x4_t, b), ai[t], 0, 0, 0);
+        }
+        const float ig = inv[il * p.E + e], gt = gts[il * p.E + e];
+        const float* gbe = p.gB + ((size_t)layer * p.E + e) * p.N;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const float4 gb = *reinterpret_cast<const float4*>(gbe + rowg[t]);
+          accf[t][0] += gt * (__fmul_rn(ig, (float)ai[t][0]) / gb.x);
+          accf[t][1] += gt * (__fmul_rn(ig, (float)ai[t][1]) / gb.y);
+          accf[t][2] += gt * (__fmul_rn(ig, (float)ai[t][2]) / gb.z);
+          accf[t][3] += gt * (__fmul_rn(ig, (float)ai[t][3]) / gb.w);
+        }
+      }
+    }
+  } else if (p.r > 0 && active) {
     const int nhf = p.r / 32;
     size_t roff[4];
 #pragma unroll
@@ -1339,8 +1492,12 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
     if (r > 0) {
       pq_prof_scope prof(PQP_DECODE_H, s);
       const int total = L * B * d.top_k * r;
-      decode_h_kernel<<<(total + 3) / 4, 256, 0, s>>>((const uint16_t*)X, (const uint16_t*)hpA, idx, B, K, d.n_experts, r,
-                                                     d.top_k, total, h);
+      if (i8) {
+        const int waves = L * B * d.top_k * (r / H8_ROWS);
+        decode_h_int8_kernel<<<(waves + 3) / 4, 256, 0, s>>>((const uint16_t*)X, (const int8_t*)hpA, gA, gamma, idx, B, K, d.n_experts, r,
+                                                           d.top_k, waves, h);
+      } else
+        decode_h_kernel<<<(total + 3) / 4, 256, 0, s>>>((const uint16_t*)X, (const uint16_t*)hpA, idx, B, K, d.n_experts, r, d.top_k, total, h);
       PQ_CHECK_LAUNCH("decode_h_kernel");
     }
   }
@@ -1364,7 +1521,7 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
     }
   } else {
     gemm16_params p{packed, scale_fp16, xq, rowsum, gamma, (const uint16_t*)hpB, idx, gate, h, (uint16_t*)Y, acc_out,
-                    B, N, K, d.n_experts, r, d.top_k, d.alpha};
+                    B, N, K, d.n_experts, r, d.top_k, d.alpha, gB};
     const int toks = B <= 8 ? 8 : 16;
     const bool tiled = d.packed_layout == PQ_PACKED_TILED64;
     const size_t hm_bytes = 2 * (size_t)toks * d.n_experts * r;
@@ -1375,13 +1532,21 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
       PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
       PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
       PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+      PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+      PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<16, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
       attr_set = true;
     }
     if (tiled) {
       dim3 grid(((N + 63) / 64 + 3) / 4, L);
-      if (toks == 8) decode_gemm16_tiled_kernel<8><<<grid, 256, lds, s>>>(p);
-      else decode_gemm16_tiled_kernel<16><<<grid, 256, lds, s>>>(p);
+      if (i8) {
+        if (toks == 8) decode_gemm16_tiled_kernel<8, true><<<grid, 256, lds, s>>>(p);
+        else decode_gemm16_tiled_kernel<16, true><<<grid, 256, lds, s>>>(p);
+      } else {
+        if (toks == 8) decode_gemm16_tiled_kernel<8><<<grid, 256, lds, s>>>(p);
+        else decode_gemm16_tiled_kernel<16><<<grid, 256, lds, s>>>(p);
+      }
     } else {
+      if (i8) return pq_set_error(PQ_ERR_SHAPE, "INT8 experts with batch > 1 need the row-interleaved packing");
       dim3 grid((N + G16_ROWS_PER_BLOCK - 1) / G16_ROWS_PER_BLOCK, L);
       if (toks == 8) decode_gemm16_kernel<8><<<grid, 256, lds, s>>>(p);
       else decode_gemm16_kernel<16><<<grid, 256, lds, s>>>(p);

@@ -155,9 +155,23 @@ def test_decode_int8_experts_alone_and_limits():
     """beta = 0 leaves only the expert term, so the whole output tests the INT8 branch; unsupported shapes are errors."""
     c = wl.decode_case(61, 1, d_in=512, d_out=256, n_experts=4, hp_rank=32, n_layers=1)
     check_decode_int8(c, alpha=1.5, beta=0.0)
-    desc = pq.DecodeDesc(2, 512, 256, 32, 4, 2, 1, pq.PQ_PACKED_TILED64, 1.0)
-    ws = pq.decode_workspace(desc)
     z8 = torch.zeros(16, dtype=torch.int8, device="cuda")
     zf = torch.zeros(16, dtype=torch.float32, device="cuda")
-    with pytest.raises(pq.PQError):                      # batch 2
-        pq.decode_gemv_int8(desc, z8, z8, z8, z8, ws, z8, zf, z8, zf, z8)
+    for desc in (pq.DecodeDesc(2, 512, 256, 32, 4, 2, 1, pq.PQ_PACKED_TILED64, 1.0),       # batch 2 with r % 64 != 0
+                 pq.DecodeDesc(2, 512, 256, 64, 4, 2, 1, pq.PQ_PACKED_ROWMAJOR, 1.0)):     # batch 2 on the row-major packing
+        ws = pq.decode_workspace(desc)
+        with pytest.raises(pq.PQError):
+            pq.decode_gemv_int8(desc, z8, z8, z8, z8, ws, z8, zf, z8, zf, z8)
+
+
+@pytest.mark.parametrize("L,B,K,N,E,r,k", [(1, 3, 512, 200, 4, 64, 2), (2, 8, 1024, 1028, 8, 64, 2), (1, 16, 512, 64, 2, 64, 1),
+                                           (1, 5, 1536, 520, 8, 128, 3), (1, 9, 640, 132, 4, 64, 2)])
+def test_decode_int8_experts_small_batch(L, B, K, N, E, r, k):
+    print(f"decode INT8 experts B={B}: L={L} K={K} N={N} E={E} r={r} k={k}", flush=True)
+    check_decode_int8(wl.decode_case(90 + K + N + B, B, d_in=K, d_out=N, n_experts=E, hp_rank=r, n_layers=L), top_k=k,
+                      tiled=True)
+
+
+def test_decode_int8_experts_config4_batch8():
+    print("decode INT8 experts, config 4 shape, batch 8, two layers", flush=True)
+    check_decode_int8(wl.decode_case(4, 8, n_layers=2), top_k=2, tiled=True)
