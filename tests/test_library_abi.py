@@ -68,3 +68,26 @@ def test_zero_token_calls_launch_nothing(lib):
     assert lib.pq_quant_act(fake, pq.PQ_BF16, 0, 64, fake, fake, None) == 0
     assert lib.pq_router_topk(fake, fake, pq.PQ_BF16, 0, 64, 8, 2, fake, fake, None, None) == 0
     assert lib.pq_onebit_acc(fake, fake, 0, 64, 64, fake, None) == 0
+
+
+def test_new_entry_points_validate_on_the_host(lib):
+    fake = C.c_void_p(0x1000)
+    big = C.c_size_t(1 << 40)
+    # INT8 high-precision branch: bf16 only, multiples of 32, buffers sized by the queries
+    lib.pq_hp_int8_ctx_bytes.restype = C.c_size_t
+    assert lib.pq_hp_int8_ctx_bytes(16, 64, 64, 32) > 0 and lib.pq_hp_int8_ctx_bytes(16, 64, 64, 24) == 0
+    assert lib.pq_hp_int8_fwd(fake, fake, fake, fake, pq.PQ_F32, 16, 64, 64, 32, C.c_float(1.0), fake, 0, fake, big, fake, big, None) == -3
+    assert lib.pq_hp_int8_fwd(fake, fake, fake, fake, pq.PQ_BF16, 16, 64, 64, 32, C.c_float(1.0), fake, 0, fake, C.c_size_t(8), fake, big,
+                              None) == -4
+    # decode with INT8 experts: rank multiple of 32; batch > 1 only on the row-interleaved packing with r % 64 == 0
+    d = pq.DecodeDesc(1, 256, 64, 16, 4, 2, 1, pq.PQ_PACKED_TILED64, 1.0)
+    assert lib.pq_decode_gemv_int8(C.byref(d), fake, fake, fake, fake, fake, fake, fake, fake, fake, None, fake, big, None) == -2
+    d = pq.DecodeDesc(4, 512, 64, 64, 4, 2, 1, pq.PQ_PACKED_ROWMAJOR, 1.0)
+    assert lib.pq_decode_gemv_int8(C.byref(d), fake, fake, fake, fake, fake, fake, fake, fake, fake, None, fake, big, None) == -2
+    # decode FFN: dimensions multiples of 128, a positive expert width
+    lib.pq_decode_ffn_workspace_bytes.restype = C.c_size_t
+    assert lib.pq_decode_ffn_workspace_bytes(C.byref(pq.DecodeFFNDesc(256, 384, 16, 4, 2, 2, 1.0))) > 0
+    assert lib.pq_decode_ffn_workspace_bytes(C.byref(pq.DecodeFFNDesc(256, 400, 16, 4, 2, 2, 1.0))) == 0
+    assert lib.pq_decode_ffn_workspace_bytes(C.byref(pq.DecodeFFNDesc(256, 384, 0, 4, 2, 2, 1.0))) == 0
+    df = pq.DecodeFFNDesc(256, 384, 16, 4, 2, 2, 1.0)
+    assert lib.pq_decode_ffn(C.byref(df), fake, fake, fake, fake, fake, fake, fake, fake, fake, None, fake, C.c_size_t(8), None) == -4
