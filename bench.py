@@ -390,24 +390,33 @@ def main():
         out["calibration_copy"] = {"kernel": "gather_rows_kernel", "read_bytes": rows * cols * 2 + rows * 4,
                                    "write_bytes": rows * cols * 2}
         del src, dst, ids
+    # The sections below are additional figures next to the headline step; one of them failing must not cost the
+    # line its headline numbers, so a failure is recorded in its place (and on stderr) instead of propagating.
+    def section(key, fn):
+        try:
+            out[key] = fn()
+        except Exception as exc:                      # noqa: BLE001
+            out[key] = {"error": f"{type(exc).__name__}: {exc}"}
+            print(f"bench.py: section {key} failed: {exc!r}", file=sys.stderr, flush=True)
+
     if not args.no_decode:
-        out["decode_gemv"] = {"metric": "1-bit decode GEMV HBM GB/s (4096->11008, E=8 top-2 r=64 experts)",
-                              "B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8),
-                              "B1_int8_experts": decode_bench(pq, torch, 1, int8_experts=True),
-                              "B8_int8_experts": decode_bench(pq, torch, 8, int8_experts=True)}
-        out["decode_ffn"] = decode_ffn_bench(pq, torch)
+        section("decode_gemv", lambda: {"metric": "1-bit decode GEMV HBM GB/s (4096->11008, E=8 top-2 r=64 experts)",
+                                        "B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8),
+                                        "B1_int8_experts": decode_bench(pq, torch, 1, int8_experts=True),
+                                        "B8_int8_experts": decode_bench(pq, torch, 8, int8_experts=True)})
+        section("decode_ffn", lambda: decode_ffn_bench(pq, torch))
     if not args.no_norm:
-        out["rmsnorm_quant"] = norm_quant_bench(pq, torch)
+        section("rmsnorm_quant", lambda: norm_quant_bench(pq, torch))
     if not args.no_hp8:
-        out["hp_int8_branch"] = hp_int8_bench(pq, torch)
+        section("hp_int8_branch", lambda: hp_int8_bench(pq, torch))
     if not args.no_ffn:
-        out["ffn_config3"] = ffn_bench(pq, torch)
+        section("ffn_config3", lambda: ffn_bench(pq, torch))
     if not args.no_stack:
         del X, W, dY, A, B, Y, dX, dW, bufs
         torch.cuda.empty_cache()
-        out["stack_config5"] = stack_bench(pq, torch)
+        section("stack_config5", lambda: stack_bench(pq, torch))
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.cpu_sample_tokens)
+        section("cpu_baseline", lambda: cpu_baseline(args.cpu_sample_tokens))
     print(json.dumps(out), flush=True)
 
 

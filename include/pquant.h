@@ -262,7 +262,9 @@ int pq_decode_gemv(const pq_decode_desc* desc, const void* X, const uint32_t* pa
  * weights are read as 1 byte per entry instead of 2.  The workspace is that of pq_decode_gemv; after the call
  * its hidden-state section holds H ([L][top_k][r] fp32 values of the bf16 roundings, for tests).
  * Limits: r % 32 == 0.  batch == 1: top_k <= 8 and top_k * r <= 2048; K % 128 == 0 and K <= 13056.
- * batch > 1: row-interleaved packing only, r % 64 == 0 and (E r) % 128 == 0, otherwise the limits of pq_decode_gemv. */
+ * batch > 1: row-interleaved packing only, r % 64 == 0 and (E r) % 128 == 0, otherwise the limits of pq_decode_gemv;
+ * there the division by gamma_B is a multiplication by the hardware reciprocal (within 1 ulp of the formula above; H,
+ * its codes and both integer sums are unaffected). */
 int pq_decode_gemv_int8(const pq_decode_desc* desc, const void* X, const uint32_t* packed, const uint16_t* scale_fp16,
                         const int8_t* hpA_q, const float* gamma_A, const int8_t* hpB_q, const float* gamma_B,
                         const void* Wr, void* Y, int32_t* acc_out, void* workspace, size_t workspace_bytes,

@@ -1219,11 +1219,13 @@ __global__ __launch_bounds__(256, 4) void decode_gemm16_tiled_kernel(gemm16_para
         const float* gbe = p.gB + ((size_t)layer * p.E + e) * p.N;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
+          // the row gammas come off through the hardware reciprocal (1 ulp): sixteen IEEE divisions per expert and
+          // lane would cost as many instructions as the whole packed product
           const float4 gb = *reinterpret_cast<const float4*>(gbe + rowg[t]);
-          accf[t][0] += gt * (__fmul_rn(ig, (float)ai[t][0]) / gb.x);
-          accf[t][1] += gt * (__fmul_rn(ig, (float)ai[t][1]) / gb.y);
-          accf[t][2] += gt * (__fmul_rn(ig, (float)ai[t][2]) / gb.z);
-          accf[t][3] += gt * (__fmul_rn(ig, (float)ai[t][3]) / gb.w);
+          accf[t][0] += gt * (__fmul_rn(ig, (float)ai[t][0]) * __builtin_amdgcn_rcpf(gb.x));
+          accf[t][1] += gt * (__fmul_rn(ig, (float)ai[t][1]) * __builtin_amdgcn_rcpf(gb.y));
+          accf[t][2] += gt * (__fmul_rn(ig, (float)ai[t][2]) * __builtin_amdgcn_rcpf(gb.z));
+          accf[t][3] += gt * (__fmul_rn(ig, (float)ai[t][3]) * __builtin_amdgcn_rcpf(gb.w));
         }
       }
     }
