@@ -409,24 +409,18 @@ __global__ __launch_bounds__(256) void decode_prep_h_kernel(const uint16_t* __re
 // ------------------------------------------------------------------------------------------
 // Expert hidden state: one wavefront per (layer, token, slot, r): h = A_e[r,:] . x   (bf16 in, fp32 out)
 // ------------------------------------------------------------------------------------------
-// INT8 experts: hpA holds INT8 codes with one gamma per row (gA).  One wavefront per (token, slot, group of 16
-// rows): the token's codes are formed once per 4096 columns from x and its gamma (the quantiser's arithmetic)
-// and kept in registers for the 16 rows; the products are exact integers, de-quantised as
+// INT8 experts: hpA holds INT8 codes with one gamma per row (gA).  One workgroup per (layer, expert, group of 16
+// rows); its four wavefronts share out the tokens of the layer that selected the expert (found by scanning the
+// layer's index list), so the 16 rows are fetched from memory once however many tokens use them.  Per token the
+// codes are formed once per 4096 columns from x and its gamma (the quantiser's arithmetic) and kept in
+// registers for the 16 rows; the products are exact integers, de-quantised as
 // fl32(fl32(1/gamma_x) * acc) / gamma_a and rounded to bf16 (held as fp32).  Columns past the end carry zero
 // codes and re-read the last chunk, so no load sits behind a branch.
 constexpr int H8_ROWS = 16;
-__global__ __launch_bounds__(256) void decode_h_int8_kernel(const uint16_t* __restrict__ X, const int8_t* __restrict__ A8,
-                                                            const float* __restrict__ gA, const float* __restrict__ gamma,
-                                                            const int* __restrict__ idx, int B, int K, int E, int r, int topk,
-                                                            int total, float* __restrict__ h) {
+__device__ __forceinline__ void h_int8_slot(const uint16_t* __restrict__ X, const int8_t* __restrict__ A8,
+                                            const float* __restrict__ gA, const float* __restrict__ gamma, int K, int r,
+                                            int slot, int tok, size_t arow0, int rg, float* __restrict__ h) {
   const int lane = threadIdx.x & 63;
-  const int o = blockIdx.x * 4 + (threadIdx.x >> 6);   // slot * (r / 16) + row group
-  if (o >= total) return;
-  const int ngrp = r / H8_ROWS;
-  const int slot = o / ngrp, rg = o - slot * ngrp;
-  const int tok = slot / topk, layer = tok / B;
-  const int e = idx[slot];
-  const size_t arow0 = ((size_t)layer * E + e) * r + (size_t)rg * H8_ROWS;
   const uint4* x4 = reinterpret_cast<const uint4*>(X + (size_t)tok * K);
   const float gx = gamma[tok];
   const int nch = K / 16;
@@ -465,7 +459,7 @@ __global__ __launch_bounds__(256) void decode_h_int8_kernel(const uint16_t* __re
       const uint4* a4 = reinterpret_cast<const uint4*>(A8 + (arow0 + rr) * K);
       uint4 av[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) av[i] = nt_load16(a4 + cc[i]);
+      for (int i = 0; i < 4; ++i) av[i] = a4[cc[i]];        // cached: the other wavefronts of the workgroup read the same rows
       int a = acc[rr];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -482,6 +476,25 @@ __global__ __launch_bounds__(256) void decode_h_int8_kernel(const uint16_t* __re
   for (int rr = 0; rr < H8_ROWS; ++rr) {
     const int t = wave_sum_i(acc[rr]);
     if (lane == 0) h[(size_t)slot * r + rg * H8_ROWS + rr] = bf16_to_f32(f32_to_bf16(__fmul_rn(sx, (float)t) / gA[arow0 + rr]));
+  }
+}
+
+__global__ __launch_bounds__(256) void decode_h_int8_kernel(const uint16_t* __restrict__ X, const int8_t* __restrict__ A8,
+                                                            const float* __restrict__ gA, const float* __restrict__ gamma,
+                                                            const int* __restrict__ idx, int B, int K, int E, int r, int topk,
+                                                            float* __restrict__ h) {
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int ngrp = r / H8_ROWS;
+  const int rg = blockIdx.x % ngrp, le = blockIdx.x / ngrp;    // le = layer * E + e
+  const int layer = le / E, e = le - layer * E;
+  const int nslot = B * topk;
+  const int* lidx = idx + (size_t)layer * nslot;
+  const size_t arow0 = (size_t)le * r + (size_t)rg * H8_ROWS;
+  int cnt = 0;
+  for (int sl = 0; sl < nslot; ++sl) {                // uniform scan: the cnt-th user of this expert goes to wave cnt % 4
+    if (lidx[sl] != e) continue;
+    if ((cnt & 3) == wave) h_int8_slot(X, A8, gA, gamma, K, r, layer * nslot + sl, layer * B + sl / topk, arow0, rg, h);
+    ++cnt;
   }
 }
 
@@ -1495,9 +1508,8 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
       pq_prof_scope prof(PQP_DECODE_H, s);
       const int total = L * B * d.top_k * r;
       if (i8) {
-        const int waves = L * B * d.top_k * (r / H8_ROWS);
-        decode_h_int8_kernel<<<(waves + 3) / 4, 256, 0, s>>>((const uint16_t*)X, (const int8_t*)hpA, gA, gamma, idx, B, K, d.n_experts, r,
-                                                           d.top_k, waves, h);
+        decode_h_int8_kernel<<<L * d.n_experts * (r / H8_ROWS), 256, 0, s>>>((const uint16_t*)X, (const int8_t*)hpA, gA, gamma, idx, B, K,
+                                                                           d.n_experts, r, d.top_k, h);
       } else
         decode_h_kernel<<<(total + 3) / 4, 256, 0, s>>>((const uint16_t*)X, (const uint16_t*)hpA, idx, B, K, d.n_experts, r, d.top_k, total, h);
       PQ_CHECK_LAUNCH("decode_h_kernel");
