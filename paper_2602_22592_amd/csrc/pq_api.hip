@@ -585,6 +585,10 @@ hp8_layout make_hp8_layout(int T, int K, int N, int r) {
     const size_t b = pq_plan_gemm(0, sh[0], sh[1], sh[2]).ws_bytes;
     if (b > sk) sk = b;
   }
+  if (T > 0) {   // the int8 H product splits its contraction (int32 slabs)
+    const size_t b = pq_plan_gemm(0, T, r, K, true, true).ws_bytes;
+    if (b > sk) sk = b;
+  }
   L.splitk = w.take(sk);
   L.ws_total = w.off;
   return L;
@@ -629,6 +633,7 @@ extern "C" int pq_hp_int8_fwd(const int8_t* Xq, const float* gamma_x, const void
     pq_operand b{cx + L.Aq, K, PQ_SRC_KC8, nullptr};
     pq_epilogue e = epi_zero();
     e.C = cx + L.H; e.ldc = r; e.out_kind = PQ_OUT_BF16; e.row_div = gamma_x; e.col_div = (const float*)(cx + L.gA);
+    e.split_int8 = 1;
     if (int err = pq_launch_gemm(0, T, r, K, a, b, e, s, PQP_GEMM_HP_H, sk)) return err;
   }
   if (int e = pq_launch_quant_act(cx + L.H, dtype, T, r, (int8_t*)(cx + L.Hq), (float*)(cx + L.gH), (uint16_t*)(cx + L.Ht), s)) return e;

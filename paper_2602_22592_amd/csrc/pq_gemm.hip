@@ -1031,6 +1031,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
 
 // Second stage of a split contraction: sum the slabs in index order (deterministic), then apply
 // the caller's epilogue.  One thread per 8 consecutive columns.
+// INT: the slabs hold int32 accumulators (int8 engine); their sum is exact.
+template <bool INT>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(int M, int N, int splits, const float* __restrict__ part,
                                                             pq_epilogue epi) {
   __shared__ double red[4];
@@ -1041,6 +1043,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(int M, int N, int sp
   if (idx < total) {
     const int m = (int)(idx / n8), n = (int)(idx % n8) * 8;
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+    int4 ia = make_int4(0, 0, 0, 0), ib = ia;
     const size_t slab = (size_t)M * N;
     // four slabs are requested together (slabs past the end repeat the last one and are dropped): a load behind
     // a loop-carried wait would cost one memory latency per slab; the sums still run in slab order
@@ -1055,13 +1058,23 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(int M, int N, int sp
 #pragma unroll
       for (int u = 0; u < 4; ++u)
         if (z + u < splits) {
-          a.x += x[u].x; a.y += x[u].y; a.z += x[u].z; a.w += x[u].w;
-          b.x += y[u].x; b.y += y[u].y; b.z += y[u].z; b.w += y[u].w;
+          if constexpr (INT) {
+            ia.x += __float_as_int(x[u].x); ia.y += __float_as_int(x[u].y); ia.z += __float_as_int(x[u].z); ia.w += __float_as_int(x[u].w);
+            ib.x += __float_as_int(y[u].x); ib.y += __float_as_int(y[u].y); ib.z += __float_as_int(y[u].z); ib.w += __float_as_int(y[u].w);
+          } else {
+            a.x += x[u].x; a.y += x[u].y; a.z += x[u].z; a.w += x[u].w;
+            b.x += y[u].x; b.y += y[u].y; b.z += y[u].z; b.w += y[u].w;
+          }
         }
     }
-    const uint4 r0 = make_uint4(__float_as_uint(a.x), __float_as_uint(a.y), __float_as_uint(a.z), __float_as_uint(a.w));
-    const uint4 r1 = make_uint4(__float_as_uint(b.x), __float_as_uint(b.y), __float_as_uint(b.z), __float_as_uint(b.w));
-    epi_vec8<false>(epi, st, m, n, r0, r1);
+    if constexpr (INT) {
+      epi_vec8<true>(epi, st, m, n, make_uint4((uint32_t)ia.x, (uint32_t)ia.y, (uint32_t)ia.z, (uint32_t)ia.w),
+                     make_uint4((uint32_t)ib.x, (uint32_t)ib.y, (uint32_t)ib.z, (uint32_t)ib.w));
+    } else {
+      const uint4 r0 = make_uint4(__float_as_uint(a.x), __float_as_uint(a.y), __float_as_uint(a.z), __float_as_uint(a.w));
+      const uint4 r1 = make_uint4(__float_as_uint(b.x), __float_as_uint(b.y), __float_as_uint(b.z), __float_as_uint(b.w));
+      epi_vec8<false>(epi, st, m, n, r0, r1);
+    }
   }
   epi_end<256>(epi, st, red, blockIdx.x);
 }
@@ -1153,7 +1166,7 @@ int launch_mfma_cfg(const pq_gemm_plan& pl, int M, int N, int K, const pq_operan
 // Tile shape and contraction split for one GEMM.  A 256x256 tile (8 wavefronts, 128x64 each) when
 // the output is large enough, else 128x128 (4 wavefronts); when the tiles alone cannot occupy the
 // 256 compute units the contraction is split and reduced in a second, fixed-order pass.
-pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8) {
+pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8, bool split_int8) {
   pq_gemm_plan pl;
   memset(&pl, 0, sizeof(pl));
   pl.splits = 1;
@@ -1167,7 +1180,7 @@ pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8) {
   pl.bm = pl.bn = big ? 256 : 128;
   const long tiles = (long)((M + pl.bm - 1) / pl.bm) * ((N + pl.bn - 1) / pl.bn);
   pl.kchunk = K > 0 ? K : 1;
-  if (!int8 && tiles > 0 && tiles <= 128 && K >= 512) {
+  if ((!int8 || split_int8) && tiles > 0 && tiles <= 128 && K >= 512) {
     long want = 256 / tiles;
     if (want > 16) want = 16;
     long chunk = (K + want - 1) / want;
@@ -1202,7 +1215,7 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
   }
   const int ak = A.kind, bk = B.kind;
   const bool int8 = (ak == PQ_SRC_KC8);
-  pq_gemm_plan pl = pq_plan_gemm(0, M, N, K, int8);
+  pq_gemm_plan pl = pq_plan_gemm(0, M, N, K, int8, epi.split_int8 != 0);
   if (grp.mode) {
     pl.splits = 1;
     pl.kchunk = K > 0 ? K : 1;
@@ -1247,7 +1260,8 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
   if (rc != PQ_OK) return rc;
   if (pl.splits > 1) {
     pq_prof_scope prof(PQP_SPLITK_REDUCE, s);
-    splitk_reduce_kernel<<<pl.red_blocks, 256, 0, s>>>(M, N, pl.splits, part, epi);
+    if (int8) splitk_reduce_kernel<true><<<pl.red_blocks, 256, 0, s>>>(M, N, pl.splits, part, epi);
+    else splitk_reduce_kernel<false><<<pl.red_blocks, 256, 0, s>>>(M, N, pl.splits, part, epi);
     PQ_CHECK_LAUNCH("splitk_reduce_kernel");
   }
   return PQ_OK;

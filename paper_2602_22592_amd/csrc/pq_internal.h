@@ -75,6 +75,8 @@ struct pq_epilogue {
   const float* dev_scale;     // optional device scalar multiplied into `scale` first (fp32 product)
   const float* row_div;       // optional per-row divisor (gamma_t)
   const float* col_div;       // optional per-column divisor applied after the row scale: value / col_div[n]
+  int split_int8;             // int8 GEMM: the contraction may be split (int32 slabs summed exactly); callers that set it
+                              // size their scratch with pq_plan_gemm(..., int8 = true, split_int8 = true)
   // optional fixed-order partial reductions, one double per block:
   const void* dot_comp;       // sum_{m,n} comp[m][n] * acc   (comp of the io dtype)
   long ld_comp;
@@ -124,7 +126,7 @@ struct pq_gemm_plan {
   int red_blocks;    // number of per-block partial sums written when a reduction is requested
   size_t ws_bytes;   // scratch for the split slabs
 };
-pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8 = false);
+pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8 = false, bool split_int8 = false);
 int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const pq_operand& B,
                    const pq_epilogue& epi, hipStream_t s, int prof_label = PQP_GEMM_OTHER,
                    void* splitk_ws = nullptr, const pq_gemm_group* group = nullptr,
