@@ -1410,10 +1410,25 @@ __global__ __launch_bounds__(256) void decode_ffn_mid_kernel(const uint16_t* __r
 
 }  // namespace
 
+// The per-token kernels stage one token as fp32 (plus its codes for INT8 experts) in dynamic LDS next to a small
+// static block: above 64 KB in total the launch needs the limit raised once per process.
+static int decode_raise_lds_limits() {
+  static bool done = false;
+  if (done) return PQ_OK;
+  const int lim = 96 * 1024;
+  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_prep_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lim));
+  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_prep_h_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, lim));
+  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_prep_h_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, lim));
+  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_ffn_mid_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lim));
+  done = true;
+  return PQ_OK;
+}
+
 int pq_launch_decode_ffn(int L, int D, int F, int r, int E, int topk, float alpha, const void* X, const uint32_t* packed_upgate,
                          const uint16_t* scale_upgate, const uint32_t* packed_down, const uint16_t* scale_down,
                          const void* UpGate, const void* Down, const void* Wr, void* Y, int32_t* acc_upgate, void* UG,
                          void* ws1, void* ws2, hipStream_t s) {
+  if (int e = decode_raise_lds_limits()) return e;
   pq_decode_desc d1{1, D, F, 2 * r, E, topk, L, PQ_PACKED_TILED64, alpha};
   pq_decode_desc d2{1, F, D, r, E, topk, L, PQ_PACKED_TILED64, alpha};
   size_t o1[7], o2[7];
@@ -1474,7 +1489,8 @@ size_t pq_decode_ws_layout(const pq_decode_desc& d, size_t* off /* [7]: xq plane
 int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* packed, const uint16_t* scale_fp16,
                      const void* hpA, const void* hpB, const void* Wr, void* Y, int32_t* acc_out, void* workspace,
                      hipStream_t s, const float* gA, const float* gB) {
-  const bool i8 = gA != nullptr;                      // INT8 experts (batch 1 only; the caller has checked the limits)
+  const bool i8 = gA != nullptr;                      // INT8 experts (the caller has checked the limits)
+  if (int e = decode_raise_lds_limits()) return e;
   size_t off[7];
   pq_decode_ws_layout(d, off);
   char* ws = (char*)workspace;

@@ -175,3 +175,11 @@ def test_decode_int8_experts_small_batch(L, B, K, N, E, r, k):
 def test_decode_int8_experts_config4_batch8():
     print("decode INT8 experts, config 4 shape, batch 8, two layers", flush=True)
     check_decode_int8(wl.decode_case(4, 8, n_layers=2), top_k=2, tiled=True)
+
+
+def test_decode_largest_d_in():
+    """d_in = 16384 (bf16 experts) and 13056 (INT8 experts): a token's staging area in LDS exceeds 64 KB."""
+    print("decode d_in = 16384", flush=True)
+    check_decode(wl.decode_case(95, 1, d_in=16384, d_out=72, n_experts=2, hp_rank=16, n_layers=1), top_k=1, tiled=True)
+    print("decode INT8 experts d_in = 13056", flush=True)
+    check_decode_int8(wl.decode_case(96, 1, d_in=13056, d_out=72, n_experts=2, hp_rank=32, n_layers=1), top_k=1, tiled=True)

@@ -92,3 +92,8 @@ def test_decode_ffn_expert_term_alone_and_limits():
         pq.decode_ffn_workspace(pq.DecodeFFNDesc(200, 256, 16, 4, 2, 1, 1.0))
     with pytest.raises(pq.PQError):
         pq.decode_ffn_workspace(pq.DecodeFFNDesc(256, 256, 0, 4, 2, 1, 1.0))
+
+
+def test_decode_ffn_largest_d_ffn():
+    print("decode FFN d_ffn = 16384", flush=True)
+    check(1, 128, 16384, 2, 8, 1)
