@@ -600,13 +600,16 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
         __builtin_amdgcn_global_load_lds(src[i] + (size_t)kt * adv, PQ_LDS_PTR(base + i * 1024), 16, 0, 0);
     };
     // Packed bits of B: a row's bits are fetched 32 bytes (CH steps) at a time, two lanes per row, so a chunk
-    // (256 rows, 8 KB) is one 16-byte load instruction per wavefront every CH steps.
+    // (256 rows, 8 KB) is one 16-byte load instruction per wavefront every CH steps.  Lanes 0..31 take the first
+    // 16 bytes of the wavefront's 32 rows and lanes 32..63 the second, so in LDS a block of 32 rows is
+    // [half][row][16 B]: the per-step reads (8 or 16 bytes of 32 consecutive rows) then walk consecutive
+    // 16-byte slots instead of a 32-byte row stride (rows 8 apart on the same banks).
     // The last chunk of a contraction range may be half a chunk (ranges are whole multiples of 128 indices):
     // its missing half re-reads the start of the range into a place no step uses.
     const int range_bytes = (ke - kb) >> 3;
     auto issue_bits = [&](int chunk, int buf) {
-      const int row = min(n0 + wv * 32 + (lane >> 1), N - 1);
-      int off = chunk * 32 + (lane & 1) * 16;
+      const int row = min(n0 + wv * 32 + (lane & 31), N - 1);
+      int off = chunk * 32 + (lane >> 5) * 16;
       if (off + 16 > range_bytes) off = 0;
       const char* g = (const char*)B.p + (size_t)row * B.ld + (kb >> 3) + off;
       __builtin_amdgcn_global_load_lds(g, PQ_LDS_PTR(smem + BITS0 + buf * (BN * 32) + wv * 1024), 16, 0, 0);
@@ -663,7 +666,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
       struct bfrag { int e[8]; };                      // two operands of four dwords
       aset G0, G1;
       bits_t bq0, bq1;
-      const uint32_t adQ0 = lds0 + BITS0 + (wn0 + (lane & 31)) * 32, adQ1 = adQ0 + 32 * 32;
+      const uint32_t adQ0 = lds0 + BITS0 + (wn0 / 32) * 1024 + (lane & 31) * 16, adQ1 = adQ0 + 1024;
       const uint32_t sh = INT8 ? 16u * h : 8u * h;
       // constants of the expansion kept in registers (three-operand encodings take no literals)
       uint32_t kM = INT8 ? 0x000001FFu : 0x80008000u, kC = 0x3F803F80u;
@@ -776,7 +779,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
         asm volatile("s_barrier" ::: "memory");
         if (part == 0) issue_bits(min(chunk + 2, nch - 1), buf == 0 ? 2 : buf - 1);   // (buf + 2) mod 3
         issue(min(kt + NSTAGE, nkt - 1), st);           // refill the stage just read
-        read_bits((uint32_t)(bufn * (BN * 32) + partn * RB));   // past the last step: a place nobody uses
+        read_bits((uint32_t)(bufn * (BN * 32) + ((partn * RB) >> 4) * 512 + ((partn * RB) & 15)));   // past the last step: a place nobody uses
         read_a(G0, c0{}, sn);
         {
           const i32x4_t f0 = {fn.e[0], fn.e[1], fn.e[2], fn.e[3]}, f1 = {fn.e[4], fn.e[5], fn.e[6], fn.e[7]};
