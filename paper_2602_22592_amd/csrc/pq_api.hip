@@ -99,7 +99,7 @@ struct lin_layout {
   // ctx (saved by forward for backward)
   size_t mulam, P, Pt, Xq, gamma, Xt, H, ctx_total;
   // workspace (scratch)
-  size_t stat_partials, red_a, red_b, dH, w_Xq, w_gamma, w_H, splitk, ws_total;
+  size_t stat_partials, red_a, red_b, dH, w_Xq, w_gamma, w_H, splitk, splitk2, ws_total;
   int n_red_a, n_red_b;
 };
 
@@ -146,6 +146,8 @@ lin_layout make_layout(const pq_linear_desc& d) {
   L.w_gamma = w.take(T * sizeof(float));
   L.w_H = w.take(T * r * es);
   L.splitk = w.take(sk);
+  // slabs of dA, which shares a launch with dB (whose slabs are in the region above)
+  L.splitk2 = w.take((ri > 0 && Ki > 0) ? pq_plan_gemm(engine, ri, Ki, Ti).ws_bytes : 0);
   L.ws_total = w.off;
   return L;
 }
@@ -457,7 +459,14 @@ extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void
     if (int err = pq_launch_reduce_partials2(red_a, (T > 0 && r > 0) ? L.n_red_a : 0, 1.0f, nullptr, dalpha_dbeta, red_b, L.n_red_b, 1.0f,
                                              mulam + 1, dalpha_dbeta + 1, s)) return err;
   }
-  if (r > 0) {
+  if (r > 0 && bf16 && T > 0) {
+    // dB = alpha * dY^T H and dA = dH^T X (dH already carries alpha): two narrow GEMMs over the same contraction,
+    // one launch when their plans agree
+    pq_operand A0{dY, N, PQ_SRC_KS16, nullptr}, B0{H, r, PQ_SRC_KS16, nullptr};
+    pq_operand A1{dH, r, PQ_SRC_KS16, nullptr}, B1{X, K, PQ_SRC_KS16, nullptr};
+    if (int err = pq_launch_gemm_pair_ks16(T, N, r, A0, B0, dhpB, r, d->alpha, r, K, A1, B1, dhpA, K, 1.0f, s, PQP_GEMM_DB, PQP_GEMM_DA,
+                                           sk_ws, ws + L.splitk2)) return err;
+  } else if (r > 0) {
     {  // dB = alpha * dY^T H
       pq_operand A{dY, N, KS, nullptr};
       pq_operand B{H, r, KS, nullptr};

@@ -471,6 +471,15 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
   // Work items are ordered (contraction split, tile row, tile column) and XCD c takes the c-th eighth of
   // that order: with a split contraction an XCD then works on one split and a band of tile rows, so the
   // operand panels it streams are shared by its workgroups instead of being fetched by every XCD.
+  // paired launches exist for the 128x128 kernel with contraction-strided operands only; elsewhere the test would
+  // only turn kernel arguments into run-time selections
+  if constexpr (BM == 128 && !DTL && AK == PQ_SRC_KS16 && BKIND == PQ_SRC_KS16 && AK2 < 0)
+  if (grp.mode == 3 && blockIdx.z == 1) {            // uniform: the second problem of a paired launch
+    A = grp.second.A; B = grp.second.B;
+    M = grp.second.M; N = grp.second.N; nbn = grp.second.nbn;
+    splitk_part = grp.second.part;
+    epi.C = grp.second.C; epi.ldc = grp.second.ldc; epi.scale = grp.second.scale;
+  }
   int pid = blockIdx.x, split = blockIdx.y;
   {
     const int nb = total_tiles * (int)gridDim.y;
@@ -1125,7 +1134,7 @@ int launch_mfma(const pq_gemm_plan& pl, int M, int N, int K, const pq_operand& A
   const int nbm = grp.mode == 1 ? (grp.max_rows + BM - 1) / BM + grp.n_groups : (M + BM - 1) / BM;
   const int nbn = (N + BN - 1) / BN;
   const int tiles = nbm * nbn;
-  dim3 grid(tiles, pl.splits, grp.mode == 2 ? grp.n_groups : 1), block(WGM * WGN * 64);
+  dim3 grid(tiles, pl.splits, grp.mode == 2 ? grp.n_groups : grp.mode == 3 ? 2 : 1), block(WGM * WGN * 64);
   mfma_gemm_kernel<BM, BN, WGM, WGN, KB, FAST, INT8, AK, BKIND, AK2, BK2, DTL><<<grid, block, 0, s>>>(
       M, N, K, A, B, epi, nbn, tiles, pl.kchunk, pl.splits > 1 ? part : nullptr, grp, ph2);
   PQ_CHECK_LAUNCH("mfma_gemm_kernel");
@@ -1196,6 +1205,45 @@ pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8, bool split
   return pl;
 }
 
+
+int pq_launch_gemm_pair_ks16(int K, int M0, int N0, const pq_operand& A0, const pq_operand& B0, float* C0, int ldc0, float scale0,
+                             int M1, int N1, const pq_operand& A1, const pq_operand& B1, float* C1, int ldc1, float scale1,
+                             hipStream_t s, int prof_label0, int prof_label1, void* splitk_ws0, void* splitk_ws1) {
+  pq_epilogue e0;
+  memset(&e0, 0, sizeof(e0));
+  e0.C = C0; e0.ldc = ldc0; e0.out_kind = PQ_OUT_F32; e0.scale = scale0;
+  pq_epilogue e1 = e0;
+  e1.C = C1; e1.ldc = ldc1; e1.scale = scale1;
+  const pq_gemm_plan p0 = pq_plan_gemm(0, M0, N0, K), p1 = pq_plan_gemm(0, M1, N1, K);
+  const int nbm0 = (M0 + 127) / 128, nbn0 = (N0 + 127) / 128, nbm1 = (M1 + 127) / 128, nbn1 = (N1 + 127) / 128;
+  const bool same = M0 > 0 && N0 > 0 && M1 > 0 && N1 > 0 && K > 0 && p0.bm == 128 && p1.bm == 128 && p0.splits == p1.splits &&
+                    p0.kchunk == p1.kchunk && nbm0 * nbn0 == nbm1 * nbn1 && A0.kind == PQ_SRC_KS16 && B0.kind == PQ_SRC_KS16 &&
+                    A1.kind == PQ_SRC_KS16 && B1.kind == PQ_SRC_KS16 && (p0.splits == 1 || (splitk_ws0 && splitk_ws1));
+  if (!same) {
+    if (int rc = pq_launch_gemm(0, M0, N0, K, A0, B0, e0, s, prof_label0, splitk_ws0)) return rc;
+    return pq_launch_gemm(0, M1, N1, K, A1, B1, e1, s, prof_label1, splitk_ws1);
+  }
+  pq_gemm_group grp;
+  memset(&grp, 0, sizeof(grp));
+  grp.mode = 3;
+  grp.second.A = A1; grp.second.B = B1; grp.second.C = C1; grp.second.ldc = ldc1; grp.second.scale = scale1;
+  grp.second.part = p0.splits > 1 ? (float*)splitk_ws1 : nullptr; grp.second.M = M1; grp.second.N = N1; grp.second.nbn = nbn1;
+  pq_phase2 ph2;
+  memset(&ph2, 0, sizeof(ph2));
+  {
+    pq_prof_scope prof(prof_label0, s);
+    if (int rc = launch_mfma<128, 128, 2, 2, 128, false, false, PQ_SRC_KS16, PQ_SRC_KS16>(p0, M0, N0, K, A0, B0, e0, s, (float*)splitk_ws0, grp, ph2))
+      return rc;
+  }
+  if (p0.splits > 1) {
+    pq_prof_scope prof(PQP_SPLITK_REDUCE, s);
+    splitk_reduce_kernel<false><<<p0.red_blocks, 256, 0, s>>>(M0, N0, p0.splits, (const float*)splitk_ws0, e0);
+    PQ_CHECK_LAUNCH("splitk_reduce_kernel");
+    splitk_reduce_kernel<false><<<p1.red_blocks, 256, 0, s>>>(M1, N1, p1.splits, (const float*)splitk_ws1, e1);
+    PQ_CHECK_LAUNCH("splitk_reduce_kernel");
+  }
+  return PQ_OK;
+}
 
 int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const pq_operand& B,
                    const pq_epilogue& epi, hipStream_t s, int prof_label, void* splitk_ws,

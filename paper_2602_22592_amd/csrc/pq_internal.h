@@ -110,6 +110,16 @@ struct pq_phase2 {
 // B + e*b_stride (elements of B's type) -- the per-expert GEMMs of the forward pass;  mode 2: the
 // contraction index runs over [offsets[e], offsets[e+1]) and the result goes to C + e*c_stride
 // (elements of C's type) -- the per-expert weight gradients.  max_rows bounds a segment (launch size).
+// mode 3: two independent GEMMs of the same operand kinds, tile shape, tile count and contraction in one launch;
+// workgroups with blockIdx.z == 1 work on `second` (plain epilogue: C = scale * acc, or raw slabs when split).
+struct pq_gemm_second {
+  pq_operand A, B;
+  void* C;
+  int ldc;
+  float scale;
+  float* part;       // split slabs of the second problem
+  int M, N, nbn;
+};
 struct pq_gemm_group {
   const int* offsets;
   int n_groups;
@@ -117,6 +127,7 @@ struct pq_gemm_group {
   long b_stride;
   long c_stride;
   int max_rows;
+  pq_gemm_second second;
 };
 
 struct pq_gemm_plan {
@@ -127,6 +138,12 @@ struct pq_gemm_plan {
   size_t ws_bytes;   // scratch for the split slabs
 };
 pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8 = false, bool split_int8 = false);
+// Two bf16 GEMMs with contraction-strided operands on both sides (the rank-r weight gradients dA and dB) in one
+// launch when their plans agree (same tile shape, tile count and contraction split), else one after the other.
+// Both have plain epilogues: C (fp32) = scale * acc.
+int pq_launch_gemm_pair_ks16(int K, int M0, int N0, const pq_operand& A0, const pq_operand& B0, float* C0, int ldc0, float scale0,
+                             int M1, int N1, const pq_operand& A1, const pq_operand& B1, float* C1, int ldc1, float scale1,
+                             hipStream_t s, int prof_label0, int prof_label1, void* splitk_ws0, void* splitk_ws1);
 int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const pq_operand& B,
                    const pq_epilogue& epi, hipStream_t s, int prof_label = PQP_GEMM_OTHER,
                    void* splitk_ws = nullptr, const pq_gemm_group* group = nullptr,
