@@ -1045,11 +1045,11 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
 // the caller's epilogue.  One thread per 8 consecutive columns.
 // INT: the slabs hold int32 accumulators (int8 engine); their sum is exact.
 template <bool INT>
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(int M, int N, int splits, const float* __restrict__ part,
-                                                            pq_epilogue epi) {
+__device__ __forceinline__ void splitk_reduce_body(int M, int N, int splits, const float* __restrict__ part, const pq_epilogue& epi,
+                                                   int block) {
   __shared__ double red[4];
   const size_t n8 = (size_t)N / 8, total = (size_t)M * n8;
-  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t idx = (size_t)block * 256 + threadIdx.x;
   epi_state st;
   epi_begin(epi, st);
   if (idx < total) {
@@ -1088,7 +1088,21 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(int M, int N, int sp
       epi_vec8<false>(epi, st, m, n, r0, r1);
     }
   }
-  epi_end<256>(epi, st, red, blockIdx.x);
+  epi_end<256>(epi, st, red, block);
+}
+
+template <bool INT>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(int M, int N, int splits, const float* __restrict__ part,
+                                                            pq_epilogue epi) {
+  splitk_reduce_body<INT>(M, N, splits, part, epi, blockIdx.x);
+}
+
+// The reductions of a paired launch in one launch: the first nblk0 workgroups finish problem 0, the rest problem 1.
+__global__ __launch_bounds__(256) void splitk_reduce_pair_kernel(int splits, int nblk0, int M0, int N0, const float* __restrict__ part0,
+                                                                 pq_epilogue epi0, int M1, int N1, const float* __restrict__ part1,
+                                                                 pq_epilogue epi1) {
+  if ((int)blockIdx.x < nblk0) splitk_reduce_body<false>(M0, N0, splits, part0, epi0, blockIdx.x);
+  else splitk_reduce_body<false>(M1, N1, splits, part1, epi1, blockIdx.x - nblk0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1237,10 +1251,9 @@ int pq_launch_gemm_pair_ks16(int K, int M0, int N0, const pq_operand& A0, const 
   }
   if (p0.splits > 1) {
     pq_prof_scope prof(PQP_SPLITK_REDUCE, s);
-    splitk_reduce_kernel<false><<<p0.red_blocks, 256, 0, s>>>(M0, N0, p0.splits, (const float*)splitk_ws0, e0);
-    PQ_CHECK_LAUNCH("splitk_reduce_kernel");
-    splitk_reduce_kernel<false><<<p1.red_blocks, 256, 0, s>>>(M1, N1, p1.splits, (const float*)splitk_ws1, e1);
-    PQ_CHECK_LAUNCH("splitk_reduce_kernel");
+    splitk_reduce_pair_kernel<<<p0.red_blocks + p1.red_blocks, 256, 0, s>>>(p0.splits, p0.red_blocks, M0, N0, (const float*)splitk_ws0, e0, M1,
+                                                                            N1, (const float*)splitk_ws1, e1);
+    PQ_CHECK_LAUNCH("splitk_reduce_pair_kernel");
   }
   return PQ_OK;
 }
