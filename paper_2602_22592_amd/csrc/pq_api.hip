@@ -311,13 +311,20 @@ static int linear_fwd_impl(const pq_linear_desc* d, const void* X, const void* W
   const int engine = bf16 ? 0 : 1;
   const int ok = out_kind_of(d->io_dtype);
 
+  int8_t* Xq = (int8_t*)(ctx ? cx + L.Xq : ws + L.w_Xq);
+  float* gamma = (float*)(ctx ? cx + L.gamma : ws + L.w_gamma);
+  uint16_t* Xt = (ctx && bf16) ? (uint16_t*)(cx + L.Xt) : nullptr;
+  bool quant_done = prequant;
   const uint32_t* P;
   const float* mulam;
   if (d->w_kind == PQ_W_MASTER) {
     const size_t n = (size_t)N * K;
     const int nb = pq_stats_blocks(n);
     double* part = (double*)(ws + L.stat_partials);
-    if (int e = pq_launch_wstats_partial(W_or_packed, d->io_dtype, n, part, nb, s)) return e;
+    if (bf16 && !prequant && T > 0) {   // the weight statistics and the activation quantiser share a launch
+      if (int e = pq_launch_wstats_quant(W_or_packed, n, part, nb, X, T, K, Xq, gamma, Xt, s)) return e;
+      quant_done = true;
+    } else if (int e = pq_launch_wstats_partial(W_or_packed, d->io_dtype, n, part, nb, s)) return e;
     uint32_t* Pt = (N % 32 == 0) ? (uint32_t*)(cx + L.Pt) : nullptr;
     if (int e = pq_launch_pack(W_or_packed, d->io_dtype, N, K, part, nb, (uint32_t*)(cx + L.P), Pt,
                                (float*)(cx + L.mulam), s)) return e;
@@ -329,10 +336,7 @@ static int linear_fwd_impl(const pq_linear_desc* d, const void* X, const void* W
   }
   if (T == 0) return PQ_OK;   // the weight side is still prepared, so a backward with no tokens is well defined
 
-  int8_t* Xq = (int8_t*)(ctx ? cx + L.Xq : ws + L.w_Xq);
-  float* gamma = (float*)(ctx ? cx + L.gamma : ws + L.w_gamma);
-  uint16_t* Xt = (ctx && bf16) ? (uint16_t*)(cx + L.Xt) : nullptr;
-  if (!prequant)
+  if (!quant_done)
     if (int e = pq_launch_quant_act(X, d->io_dtype, T, K, Xq, gamma, Xt, s)) return e;
 
   // bf16 I/O with a live hp branch: the rank-r product H B^T is accumulated into the 1-bit GEMM's tile

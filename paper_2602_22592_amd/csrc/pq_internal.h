@@ -29,6 +29,8 @@ int pq_launch_rmsnorm_bwd(const void* dXn, const void* X, const void* gain, cons
                           float* dgain, float* part, hipStream_t s);
 // Weight statistics, stage 1: per-block fp64 partial sums {sum W, sum |W|}.
 int pq_stats_blocks(size_t n_elems);
+int pq_launch_wstats_quant(const void* W, size_t n_elems, double* partials, int nblocks, const void* X, int T, int K,
+                           int8_t* Xq, float* gamma, uint16_t* Xt, hipStream_t s);
 int pq_launch_wstats_partial(const void* W, int dtype, size_t n_elems, double* partials, int nblocks,
                              hipStream_t s);
 // Stage 2 + binarise + pack (both orientations).  Every block re-reduces the partials in the

@@ -65,13 +65,11 @@ __device__ __forceinline__ void quant_store(const uint4& u, float g, int8_t* qro
 }
 
 template <typename T, int NV>
-__global__ __launch_bounds__(256) void quant_act_kernel(const T* __restrict__ X, int Tn, int K,
-                                                        int8_t* __restrict__ Xq,
-                                                        float* __restrict__ gamma,
-                                                        uint16_t* __restrict__ Xt) {
+__device__ __forceinline__ void quant_act_body(const T* __restrict__ X, int Tn, int K, int8_t* __restrict__ Xq,
+                                               float* __restrict__ gamma, uint16_t* __restrict__ Xt, int block) {
   constexpr int V = vec16<T>::V;
   const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int row = block * 4 + (threadIdx.x >> 6);
   if (row >= Tn) return;
   const uint4* xr = reinterpret_cast<const uint4*>(X + (size_t)row * K);
   const int nvec = K / V;
@@ -112,6 +110,14 @@ __global__ __launch_bounds__(256) void quant_act_kernel(const T* __restrict__ X,
   } else {
     for (int c = lane; c < nvec; c += 64) quant_store<T>(xr[c], g, qrow, xtrow, c);
   }
+}
+
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void quant_act_kernel(const T* __restrict__ X, int Tn, int K,
+                                                        int8_t* __restrict__ Xq,
+                                                        float* __restrict__ gamma,
+                                                        uint16_t* __restrict__ Xt) {
+  quant_act_body<T, NV>(X, Tn, K, Xq, gamma, Xt, blockIdx.x);
 }
 
 template <typename T>
@@ -422,13 +428,13 @@ int pq_launch_rmsnorm_bwd(const void* dXn, const void* X, const void* gain, cons
 // Weight statistics, stage 1: grid-stride fp64 sums of W and |W|, one pair per block.
 // ------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void wstats_partial_kernel(const T* __restrict__ W, size_t nvec,
-                                                             double* __restrict__ partials) {
+__device__ __forceinline__ void wstats_partial_body(const T* __restrict__ W, size_t nvec, double* __restrict__ partials, int block,
+                                                    int nblocks) {
   constexpr int V = vec16<T>::V;
   __shared__ double red[4];
   const uint4* w4 = reinterpret_cast<const uint4*>(W);
   double s = 0.0, a = 0.0;
-  for (size_t c = (size_t)blockIdx.x * 256 + threadIdx.x; c < nvec; c += (size_t)gridDim.x * 256) {
+  for (size_t c = (size_t)block * 256 + threadIdx.x; c < nvec; c += (size_t)nblocks * 256) {
     float f[V];
     vec16<T>::unpack(w4[c], f);
 #pragma unroll
@@ -440,9 +446,45 @@ __global__ __launch_bounds__(256) void wstats_partial_kernel(const T* __restrict
   double bs = block_sum_d<256>(s, red);
   double ba = block_sum_d<256>(a, red);
   if (threadIdx.x == 0) {
-    partials[2 * blockIdx.x] = bs;
-    partials[2 * blockIdx.x + 1] = ba;
+    partials[2 * block] = bs;
+    partials[2 * block + 1] = ba;
   }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void wstats_partial_kernel(const T* __restrict__ W, size_t nvec,
+                                                             double* __restrict__ partials) {
+  wstats_partial_body<T>(W, nvec, partials, blockIdx.x, gridDim.x);
+}
+
+// The first stage of the weight statistics and the activation quantiser of one forward call are independent and
+// each too short to fill its own launch well: one launch, the first nw workgroups take the weights.
+template <int NV>
+__global__ __launch_bounds__(256) void wstats_quant_kernel(const uint16_t* __restrict__ W, size_t nvec, double* __restrict__ partials,
+                                                           int nw, const uint16_t* __restrict__ X, int Tn, int K,
+                                                           int8_t* __restrict__ Xq, float* __restrict__ gamma,
+                                                           uint16_t* __restrict__ Xt) {
+  if ((int)blockIdx.x < nw) wstats_partial_body<uint16_t>(W, nvec, partials, blockIdx.x, nw);
+  else quant_act_body<uint16_t, NV>(X, Tn, K, Xq, gamma, Xt, blockIdx.x - nw);
+}
+
+// bf16 only; rows too long for the register-cached quantiser (more than 16 vectors per lane) take two launches
+int pq_launch_wstats_quant(const void* W, size_t n_elems, double* partials, int nblocks, const void* X, int T, int K,
+                           int8_t* Xq, float* gamma, uint16_t* Xt, hipStream_t s) {
+  const int per_lane = (K / 8 + 63) / 64;
+  if (T <= 0 || per_lane > 16) {
+    if (int e = pq_launch_wstats_partial(W, PQ_BF16, n_elems, partials, nblocks, s)) return e;
+    return pq_launch_quant_act(X, PQ_BF16, T, K, Xq, gamma, Xt, s);
+  }
+  pq_prof_scope prof(PQP_QUANT, s);
+  dim3 grid(nblocks + (T + 3) / 4), block(256);
+  const uint16_t* w = (const uint16_t*)W;
+  const uint16_t* x = (const uint16_t*)X;
+  if (per_lane <= 4) wstats_quant_kernel<4><<<grid, block, 0, s>>>(w, n_elems / 8, partials, nblocks, x, T, K, Xq, gamma, Xt);
+  else if (per_lane <= 8) wstats_quant_kernel<8><<<grid, block, 0, s>>>(w, n_elems / 8, partials, nblocks, x, T, K, Xq, gamma, Xt);
+  else wstats_quant_kernel<16><<<grid, block, 0, s>>>(w, n_elems / 8, partials, nblocks, x, T, K, Xq, gamma, Xt);
+  PQ_CHECK_LAUNCH("wstats_quant_kernel");
+  return PQ_OK;
 }
 
 int pq_stats_blocks(size_t n_elems) {
