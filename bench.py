@@ -40,7 +40,8 @@ def gemm_flops(T, K, N, r):
         "gemm_onebit_fwd": 2.0 * T * K * N,
         "gemm_hp_H": 2.0 * T * r * K, "gemm_hp_Y": 2.0 * T * N * r,
         "gemm_dH": 2.0 * T * r * N, "gemm_dX": 2.0 * T * K * N, "gemm_dX_hp": 2.0 * T * K * r,
-        "gemm_dW": 2.0 * T * K * N, "gemm_dB": 2.0 * T * N * r, "gemm_dA": 2.0 * T * r * K,
+        "gemm_dW": 2.0 * T * K * N,
+        "gemm_dB": 2.0 * T * N * r + 2.0 * T * r * K,      # dB and dA share one launch, timed under this label
     }
 
 
