@@ -459,18 +459,23 @@ extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void
       e.maskW = W; e.mask_kind = ok; e.mu_dev = mulam; e.tau = d->ste_tau;
     }
     if (int err = pq_launch_gemm(engine, N, K, T, A, B, e, s, PQP_GEMM_DW, sk_ws)) return err;
-    // d alpha and d beta: both fixed-order sums of per-workgroup partials, one launch
-    if (int err = pq_launch_reduce_partials2(red_a, (T > 0 && r > 0) ? L.n_red_a : 0, 1.0f, nullptr, dalpha_dbeta, red_b, L.n_red_b, 1.0f,
-                                             mulam + 1, dalpha_dbeta + 1, s)) return err;
   }
+  // d alpha and d beta: both fixed-order sums of per-workgroup partials
+  const pq_reduce_job jobs[2] = {{red_a, (T > 0 && r > 0) ? L.n_red_a : 0, 1.0f, nullptr, dalpha_dbeta},
+                                 {red_b, L.n_red_b, 1.0f, mulam + 1, dalpha_dbeta + 1}};
+  bool jobs_done = false;
   if (r > 0 && bf16 && T > 0) {
     // dB = alpha * dY^T H and dA = dH^T X (dH already carries alpha): two narrow GEMMs over the same contraction,
-    // one launch when their plans agree
+    // one launch when their plans agree; the two scalar reductions then ride along with their split reduction
     pq_operand A0{dY, N, PQ_SRC_KS16, nullptr}, B0{H, r, PQ_SRC_KS16, nullptr};
     pq_operand A1{dH, r, PQ_SRC_KS16, nullptr}, B1{X, K, PQ_SRC_KS16, nullptr};
     if (int err = pq_launch_gemm_pair_ks16(T, N, r, A0, B0, dhpB, r, d->alpha, r, K, A1, B1, dhpA, K, 1.0f, s, PQP_GEMM_DB, PQP_GEMM_DA,
-                                           sk_ws, ws + L.splitk2)) return err;
-  } else if (r > 0) {
+                                           sk_ws, ws + L.splitk2, jobs, &jobs_done)) return err;
+  }
+  if (!jobs_done)
+    if (int err = pq_launch_reduce_partials2(jobs[0].partials, jobs[0].n, 1.0f, nullptr, jobs[0].out, jobs[1].partials, jobs[1].n, 1.0f,
+                                             jobs[1].dev_factor, jobs[1].out, s)) return err;
+  if (r > 0 && !(bf16 && T > 0)) {
     {  // dB = alpha * dY^T H
       pq_operand A{dY, N, KS, nullptr};
       pq_operand B{H, r, KS, nullptr};

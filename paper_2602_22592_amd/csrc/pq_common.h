@@ -97,3 +97,18 @@ int pq_set_error(int code, const char* fmt, ...);
   } while (0)
 
 static inline size_t pq_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Fixed-order final reduction of per-block fp64 partial sums to one fp32 value: out = (sum partials) * factor [* *dev_factor].
+// One workgroup of 256 threads per job.
+struct pq_reduce_job { const double* partials; int n; float factor; const float* dev_factor; float* out; };
+__device__ __forceinline__ void pq_reduce_job_body(const pq_reduce_job& j) {
+  __shared__ double red[4];
+  double s = 0.0;
+  for (int i = threadIdx.x; i < j.n; i += 256) s += j.partials[i];
+  double t = block_sum_d<256>(s, red);
+  if (threadIdx.x == 0) {
+    double f = (double)j.factor;
+    if (j.dev_factor) f *= (double)(*j.dev_factor);
+    j.out[0] = (float)(t * f);
+  }
+}

@@ -1098,11 +1098,15 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(int M, int N, int sp
 }
 
 // The reductions of a paired launch in one launch: the first nblk0 workgroups finish problem 0, the rest problem 1.
-__global__ __launch_bounds__(256) void splitk_reduce_pair_kernel(int splits, int nblk0, int M0, int N0, const float* __restrict__ part0,
-                                                                 pq_epilogue epi0, int M1, int N1, const float* __restrict__ part1,
-                                                                 pq_epilogue epi1) {
-  if ((int)blockIdx.x < nblk0) splitk_reduce_body<false>(M0, N0, splits, part0, epi0, blockIdx.x);
-  else splitk_reduce_body<false>(M1, N1, splits, part1, epi1, blockIdx.x - nblk0);
+// Up to two scalar reductions of the same call (d alpha, d beta) ride along as the last workgroups of the grid.
+__global__ __launch_bounds__(256) void splitk_reduce_pair_kernel(int splits, int nblk0, int nblk1, int M0, int N0,
+                                                                 const float* __restrict__ part0, pq_epilogue epi0, int M1, int N1,
+                                                                 const float* __restrict__ part1, pq_epilogue epi1, pq_reduce_job j0,
+                                                                 pq_reduce_job j1) {
+  const int b = blockIdx.x;
+  if (b < nblk0) splitk_reduce_body<false>(M0, N0, splits, part0, epi0, b);
+  else if (b < nblk0 + nblk1) splitk_reduce_body<false>(M1, N1, splits, part1, epi1, b - nblk0);
+  else pq_reduce_job_body(b == nblk0 + nblk1 ? j0 : j1);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1222,7 +1226,9 @@ pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8, bool split
 
 int pq_launch_gemm_pair_ks16(int K, int M0, int N0, const pq_operand& A0, const pq_operand& B0, float* C0, int ldc0, float scale0,
                              int M1, int N1, const pq_operand& A1, const pq_operand& B1, float* C1, int ldc1, float scale1,
-                             hipStream_t s, int prof_label0, int prof_label1, void* splitk_ws0, void* splitk_ws1) {
+                             hipStream_t s, int prof_label0, int prof_label1, void* splitk_ws0, void* splitk_ws1,
+                             const pq_reduce_job* jobs, bool* jobs_done) {
+  if (jobs_done) *jobs_done = false;
   pq_epilogue e0;
   memset(&e0, 0, sizeof(e0));
   e0.C = C0; e0.ldc = ldc0; e0.out_kind = PQ_OUT_F32; e0.scale = scale0;
@@ -1251,9 +1257,14 @@ int pq_launch_gemm_pair_ks16(int K, int M0, int N0, const pq_operand& A0, const 
   }
   if (p0.splits > 1) {
     pq_prof_scope prof(PQP_SPLITK_REDUCE, s);
-    splitk_reduce_pair_kernel<<<p0.red_blocks + p1.red_blocks, 256, 0, s>>>(p0.splits, p0.red_blocks, M0, N0, (const float*)splitk_ws0, e0, M1,
-                                                                            N1, (const float*)splitk_ws1, e1);
+    pq_reduce_job none;
+    memset(&none, 0, sizeof(none));
+    const int extra = jobs ? 2 : 0;
+    splitk_reduce_pair_kernel<<<p0.red_blocks + p1.red_blocks + extra, 256, 0, s>>>(
+        p0.splits, p0.red_blocks, p1.red_blocks, M0, N0, (const float*)splitk_ws0, e0, M1, N1, (const float*)splitk_ws1, e1,
+        jobs ? jobs[0] : none, jobs ? jobs[1] : none);
     PQ_CHECK_LAUNCH("splitk_reduce_pair_kernel");
+    if (jobs && jobs_done) *jobs_done = true;
   }
   return PQ_OK;
 }

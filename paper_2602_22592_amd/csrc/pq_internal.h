@@ -145,7 +145,8 @@ pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8 = false, bo
 // Both have plain epilogues: C (fp32) = scale * acc.
 int pq_launch_gemm_pair_ks16(int K, int M0, int N0, const pq_operand& A0, const pq_operand& B0, float* C0, int ldc0, float scale0,
                              int M1, int N1, const pq_operand& A1, const pq_operand& B1, float* C1, int ldc1, float scale1,
-                             hipStream_t s, int prof_label0, int prof_label1, void* splitk_ws0, void* splitk_ws1);
+                             hipStream_t s, int prof_label0, int prof_label1, void* splitk_ws0, void* splitk_ws1,
+                             const pq_reduce_job* jobs = nullptr, bool* jobs_done = nullptr);   // jobs: two scalar reductions to ride along
 int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const pq_operand& B,
                    const pq_epilogue& epi, hipStream_t s, int prof_label = PQP_GEMM_OTHER,
                    void* splitk_ws = nullptr, const pq_gemm_group* group = nullptr,

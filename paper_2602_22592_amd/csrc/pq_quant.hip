@@ -699,19 +699,10 @@ int pq_launch_router(const void* X, const void* Wr, int dtype, int T, int K, int
 // ------------------------------------------------------------------------------------------
 // Fixed-order final reduction of per-block partial sums.
 // ------------------------------------------------------------------------------------------
-struct reduce_job { const double* partials; int n; float factor; const float* dev_factor; float* out; };
+typedef pq_reduce_job reduce_job;
 
 __global__ __launch_bounds__(256) void reduce_partials_kernel(reduce_job j0, reduce_job j1) {   // one workgroup per job
-  __shared__ double red[4];
-  const reduce_job j = blockIdx.x == 0 ? j0 : j1;
-  double s = 0.0;
-  for (int i = threadIdx.x; i < j.n; i += 256) s += j.partials[i];
-  double t = block_sum_d<256>(s, red);
-  if (threadIdx.x == 0) {
-    double f = (double)j.factor;
-    if (j.dev_factor) f *= (double)(*j.dev_factor);
-    j.out[0] = (float)(t * f);
-  }
+  pq_reduce_job_body(blockIdx.x == 0 ? j0 : j1);
 }
 
 int pq_launch_reduce_partials(const double* partials, int n, float factor, const float* dev_factor,
