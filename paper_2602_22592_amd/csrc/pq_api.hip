@@ -315,14 +315,34 @@ static int linear_fwd_impl(const pq_linear_desc* d, const void* X, const void* W
   float* gamma = (float*)(ctx ? cx + L.gamma : ws + L.w_gamma);
   uint16_t* Xt = (ctx && bf16) ? (uint16_t*)(cx + L.Xt) : nullptr;
   bool quant_done = prequant;
+  void* H = r > 0 ? (ctx ? (void*)(cx + L.H) : (void*)(ws + L.w_H)) : nullptr;
+  auto launch_H = [&](bool defer) -> int {   // H = X A^T
+    pq_operand A{X, K, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
+    pq_operand B{hpA, K, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
+    pq_epilogue e = epi_zero();
+    e.C = H; e.ldc = r; e.out_kind = ok; e.defer_reduce = defer ? 1 : 0;
+    return pq_launch_gemm(engine, T, r, K, A, B, e, s, PQP_GEMM_HP_H, sk_ws);
+  };
+  // The weight statistics' first stage and the activation quantiser share a launch (rows of up to 8192 elements stay
+  // in registers); when H = X A^T splits its contraction it goes first and the sum of its slabs rides along too.
+  const bool combo = d->w_kind == PQ_W_MASTER && bf16 && !prequant && T > 0 && K <= 8192;
+  bool H_done = false;
+  int H_splits = 0;
+  if (combo && r > 0) {
+    H_splits = pq_plan_gemm(0, T, r, K).splits;
+    if (int e = launch_H(H_splits > 1)) return e;
+    H_done = true;
+  }
   const uint32_t* P;
   const float* mulam;
   if (d->w_kind == PQ_W_MASTER) {
     const size_t n = (size_t)N * K;
     const int nb = pq_stats_blocks(n);
     double* part = (double*)(ws + L.stat_partials);
-    if (bf16 && !prequant && T > 0) {   // the weight statistics and the activation quantiser share a launch
-      if (int e = pq_launch_wstats_quant(W_or_packed, n, part, nb, X, T, K, Xq, gamma, Xt, s)) return e;
+    if (combo) {
+      const bool sum = H_done && H_splits > 1;
+      if (int e = pq_launch_wstats_quant(W_or_packed, n, part, nb, X, T, K, Xq, gamma, Xt, s, sum ? (const float*)sk_ws : nullptr, H_splits,
+                                         T, r, H, r)) return e;
       quant_done = true;
     } else if (int e = pq_launch_wstats_partial(W_or_packed, d->io_dtype, n, part, nb, s)) return e;
     uint32_t* Pt = (N % 32 == 0) ? (uint32_t*)(cx + L.Pt) : nullptr;
@@ -341,14 +361,8 @@ static int linear_fwd_impl(const pq_linear_desc* d, const void* X, const void* W
 
   // bf16 I/O with a live hp branch: the rank-r product H B^T is accumulated into the 1-bit GEMM's tile
   const bool fuse_hp = bf16 && r > 0 && d->alpha != 0.0f && pq_plan_gemm(0, T, N, K, true).splits == 1;
-  void* H = r > 0 ? (ctx ? (void*)(cx + L.H) : (void*)(ws + L.w_H)) : nullptr;
-  if (r > 0) {  // H = X A^T
-    pq_operand A{X, K, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
-    pq_operand B{hpA, K, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
-    pq_epilogue e = epi_zero();
-    e.C = H; e.ldc = r; e.out_kind = ok;
-    if (int err = pq_launch_gemm(engine, T, r, K, A, B, e, s, PQP_GEMM_HP_H, sk_ws)) return err;
-  }
+  if (r > 0 && !H_done)
+    if (int err = launch_H(false)) return err;
   {  // 1-bit branch: Y = fl32(fl32(beta*lambda)/gamma_t) * acc   [+ alpha * H B^T when fused]
     pq_operand A{Xq, K, PQ_SRC_KC8, nullptr};
     pq_operand B{P, K / 8, PQ_SRC_BITS8, nullptr};

@@ -98,6 +98,34 @@ int pq_set_error(int code, const char* fmt, ...);
 
 static inline size_t pq_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Sum of the fp32 slabs of a split contraction in slab order, rounded to bf16: C[m][n .. n+7] for the idx-th group of
+// eight columns (the plain epilogue C = acc of the GEMM engine's own reduction, bit for bit).
+__device__ __forceinline__ void pq_slab_sum_bf16_body(const float* __restrict__ part, int splits, int M, int N, uint16_t* __restrict__ C,
+                                                      int ldc, size_t idx) {
+  const size_t n8 = (size_t)N / 8, total = (size_t)M * n8;
+  if (idx >= total) return;
+  const int m = (int)(idx / n8), n = (int)(idx % n8) * 8;
+  const size_t slab = (size_t)M * N;
+  float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+  for (int z = 0; z < splits; z += 4) {
+    float4 x[4], y[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float* p = part + (size_t)min(z + u, splits - 1) * slab + (size_t)m * N + n;
+      x[u] = *reinterpret_cast<const float4*>(p);
+      y[u] = *reinterpret_cast<const float4*>(p + 4);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (z + u < splits) {
+        a.x += x[u].x; a.y += x[u].y; a.z += x[u].z; a.w += x[u].w;
+        b.x += y[u].x; b.y += y[u].y; b.z += y[u].z; b.w += y[u].w;
+      }
+  }
+  *reinterpret_cast<uint4*>(C + (size_t)m * ldc + n) =
+      make_uint4(pack_bf16x2(a.x, a.y), pack_bf16x2(a.z, a.w), pack_bf16x2(b.x, b.y), pack_bf16x2(b.z, b.w));
+}
+
 // Fixed-order final reduction of per-block fp64 partial sums to one fp32 value: out = (sum partials) * factor [* *dev_factor].
 // One workgroup of 256 threads per job.
 struct pq_reduce_job { const double* partials; int n; float factor; const float* dev_factor; float* out; };

@@ -1333,7 +1333,7 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
     else return pq_set_error(PQ_ERR_BAD_ARG, "no MFMA kernel for operand kinds (%d, %d)", ak, bk);
   }
   if (rc != PQ_OK) return rc;
-  if (pl.splits > 1) {
+  if (pl.splits > 1 && !epi.defer_reduce) {
     pq_prof_scope prof(PQP_SPLITK_REDUCE, s);
     if (int8) splitk_reduce_kernel<true><<<pl.red_blocks, 256, 0, s>>>(M, N, pl.splits, part, epi);
     else splitk_reduce_kernel<false><<<pl.red_blocks, 256, 0, s>>>(M, N, pl.splits, part, epi);

@@ -29,8 +29,11 @@ int pq_launch_rmsnorm_bwd(const void* dXn, const void* X, const void* gain, cons
                           float* dgain, float* part, hipStream_t s);
 // Weight statistics, stage 1: per-block fp64 partial sums {sum W, sum |W|}.
 int pq_stats_blocks(size_t n_elems);
+// slabs != nullptr: `splits` fp32 slabs [M][N] of a deferred split contraction are summed in slab order into the bf16
+// matrix C [M][ldc] by further workgroups of the same launch (N % 8 == 0)
 int pq_launch_wstats_quant(const void* W, size_t n_elems, double* partials, int nblocks, const void* X, int T, int K,
-                           int8_t* Xq, float* gamma, uint16_t* Xt, hipStream_t s);
+                           int8_t* Xq, float* gamma, uint16_t* Xt, hipStream_t s, const float* slabs = nullptr, int splits = 0,
+                           int M = 0, int N = 0, void* C = nullptr, int ldc = 0);
 int pq_launch_wstats_partial(const void* W, int dtype, size_t n_elems, double* partials, int nblocks,
                              hipStream_t s);
 // Stage 2 + binarise + pack (both orientations).  Every block re-reduces the partials in the
@@ -77,6 +80,8 @@ struct pq_epilogue {
   const float* dev_scale;     // optional device scalar multiplied into `scale` first (fp32 product)
   const float* row_div;       // optional per-row divisor (gamma_t)
   const float* col_div;       // optional per-column divisor applied after the row scale: value / col_div[n]
+  int defer_reduce;           // a split contraction leaves its fp32 slabs in the scratch and launches no reduction: the
+                              // caller sums them itself (plain epilogues only, see pq_slab_sum_bf16_body)
   int split_int8;             // int8 GEMM: the contraction may be split (int32 slabs summed exactly); callers that set it
                               // size their scratch with pq_plan_gemm(..., int8 = true, split_int8 = true)
   // optional fixed-order partial reductions, one double per block:

@@ -459,30 +459,34 @@ __global__ __launch_bounds__(256) void wstats_partial_kernel(const T* __restrict
 
 // The first stage of the weight statistics and the activation quantiser of one forward call are independent and
 // each too short to fill its own launch well: one launch, the first nw workgroups take the weights.
+struct slab_sum_job { const float* part; int splits, M, N; uint16_t* C; int ldc; };
 template <int NV>
 __global__ __launch_bounds__(256) void wstats_quant_kernel(const uint16_t* __restrict__ W, size_t nvec, double* __restrict__ partials,
                                                            int nw, const uint16_t* __restrict__ X, int Tn, int K,
                                                            int8_t* __restrict__ Xq, float* __restrict__ gamma,
-                                                           uint16_t* __restrict__ Xt) {
-  if ((int)blockIdx.x < nw) wstats_partial_body<uint16_t>(W, nvec, partials, blockIdx.x, nw);
-  else quant_act_body<uint16_t, NV>(X, Tn, K, Xq, gamma, Xt, blockIdx.x - nw);
+                                                           uint16_t* __restrict__ Xt, int nq, slab_sum_job sj) {
+  const int b = blockIdx.x;
+  if (b < nw) wstats_partial_body<uint16_t>(W, nvec, partials, b, nw);
+  else if (b < nw + nq) quant_act_body<uint16_t, NV>(X, Tn, K, Xq, gamma, Xt, b - nw);
+  else pq_slab_sum_bf16_body(sj.part, sj.splits, sj.M, sj.N, sj.C, sj.ldc, (size_t)(b - nw - nq) * 256 + threadIdx.x);
 }
 
 // bf16 only; rows too long for the register-cached quantiser (more than 16 vectors per lane) take two launches
 int pq_launch_wstats_quant(const void* W, size_t n_elems, double* partials, int nblocks, const void* X, int T, int K,
-                           int8_t* Xq, float* gamma, uint16_t* Xt, hipStream_t s) {
+                           int8_t* Xq, float* gamma, uint16_t* Xt, hipStream_t s, const float* slabs, int splits, int M, int N,
+                           void* C, int ldc) {
   const int per_lane = (K / 8 + 63) / 64;
-  if (T <= 0 || per_lane > 16) {
-    if (int e = pq_launch_wstats_partial(W, PQ_BF16, n_elems, partials, nblocks, s)) return e;
-    return pq_launch_quant_act(X, PQ_BF16, T, K, Xq, gamma, Xt, s);
-  }
+  if (T <= 0 || per_lane > 16) return pq_set_error(PQ_ERR_SHAPE, "combined statistics/quantiser launch: bad shape T=%d K=%d", T, K);
   pq_prof_scope prof(PQP_QUANT, s);
-  dim3 grid(nblocks + (T + 3) / 4), block(256);
+  const int nq = (T + 3) / 4;
+  const int ns = slabs ? (int)(((size_t)M * (N / 8) + 255) / 256) : 0;
+  dim3 grid(nblocks + nq + ns), block(256);
   const uint16_t* w = (const uint16_t*)W;
   const uint16_t* x = (const uint16_t*)X;
-  if (per_lane <= 4) wstats_quant_kernel<4><<<grid, block, 0, s>>>(w, n_elems / 8, partials, nblocks, x, T, K, Xq, gamma, Xt);
-  else if (per_lane <= 8) wstats_quant_kernel<8><<<grid, block, 0, s>>>(w, n_elems / 8, partials, nblocks, x, T, K, Xq, gamma, Xt);
-  else wstats_quant_kernel<16><<<grid, block, 0, s>>>(w, n_elems / 8, partials, nblocks, x, T, K, Xq, gamma, Xt);
+  const slab_sum_job sj{slabs, splits, M, N, (uint16_t*)C, ldc};
+  if (per_lane <= 4) wstats_quant_kernel<4><<<grid, block, 0, s>>>(w, n_elems / 8, partials, nblocks, x, T, K, Xq, gamma, Xt, nq, sj);
+  else if (per_lane <= 8) wstats_quant_kernel<8><<<grid, block, 0, s>>>(w, n_elems / 8, partials, nblocks, x, T, K, Xq, gamma, Xt, nq, sj);
+  else wstats_quant_kernel<16><<<grid, block, 0, s>>>(w, n_elems / 8, partials, nblocks, x, T, K, Xq, gamma, Xt, nq, sj);
   PQ_CHECK_LAUNCH("wstats_quant_kernel");
   return PQ_OK;
 }
