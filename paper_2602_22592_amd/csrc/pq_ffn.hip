@@ -129,16 +129,24 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
   double* part = (double*)(ws + L.stat);
   void* sk = ws + L.splitk;
 
-  if (int e = pack_weight(W_up, F, D, cx, L.P_up, L.Pt_up, L.ml_up, part, s)) return e;
+  int8_t* Xq = (int8_t*)(cx + L.Xq);
+  float* gx = (float*)(cx + L.gx);
+  const bool combo = T > 0 && D <= 8192;   // the quantiser of X shares the launch of W_up's statistics
+  if (combo) {
+    const size_t n = (size_t)F * D;
+    const int nb = pq_stats_blocks(n);
+    if (int e = pq_launch_wstats_quant(W_up, n, part, nb, X, T, D, Xq, gx, (uint16_t*)(cx + L.Xt), s)) return e;
+    if (int e = pq_launch_pack(W_up, PQ_BF16, F, D, part, nb, (uint32_t*)(cx + L.P_up), (uint32_t*)(cx + L.Pt_up),
+                               (float*)(cx + L.ml_up), s)) return e;
+  } else if (int e = pack_weight(W_up, F, D, cx, L.P_up, L.Pt_up, L.ml_up, part, s)) return e;
   if (int e = pack_weight(W_gate, F, D, cx, L.P_gate, L.Pt_gate, L.ml_gate, part, s)) return e;
   if (int e = pack_weight(W_down, D, F, cx, L.P_down, L.Pt_down, L.ml_down, part, s)) return e;
   if (T == 0)  // no tokens: leave empty expert segments behind so that a backward call is well defined
     return pq_launch_route((const int*)(cx + L.idx), 0, E, (int*)(cx + L.counts), (int*)(cx + L.offsets), (int*)(cx + L.perm),
                            (int*)(cx + L.inv), s);
 
-  int8_t* Xq = (int8_t*)(cx + L.Xq);
-  float* gx = (float*)(cx + L.gx);
-  if (int e = pq_launch_quant_act(X, PQ_BF16, T, D, Xq, gx, (uint16_t*)(cx + L.Xt), s)) return e;
+  if (!combo)
+    if (int e = pq_launch_quant_act(X, PQ_BF16, T, D, Xq, gx, (uint16_t*)(cx + L.Xt), s)) return e;
   {  // U and G: pure 1-bit linears (no feature scale of their own)
     pq_operand A{Xq, D, PQ_SRC_KC8, nullptr};
     pq_operand Bu{cx + L.P_up, D / 8, PQ_SRC_BITS8, nullptr};
