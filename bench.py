@@ -12,6 +12,9 @@ between synchronisations.  `roofline` is for the dominant kernel: its duration i
 recorded by the library around each launch, on the launch stream, in a second pass over the same steps
 (the events open gaps between launches, so they stay out of the region that is timed as a whole);
 `cpu_baseline` is the NumPy oracle timed on a bounded sample of the same workload.
+
+Defaults: 50 warm-up and 200 timed steps (0.1 s of GPU time).  Short runs measure the clock ramp of a GPU that
+has just been idle rather than the kernels: 5 + 20 steps read 8 % slower than the steady state on the same box.
 """
 from __future__ import annotations
 
@@ -63,7 +66,7 @@ def cpu_baseline(sample_tokens):
             "sample": f"first {sample_tokens} tokens of the workload, fwd+bwd, {dt:.1f} s"}
 
 
-def decode_bench(pq, torch, batch, n_layers=64, steps=20, warmup=3, int8_experts=False):
+def decode_bench(pq, torch, batch, n_layers=64, steps=100, warmup=20, int8_experts=False):
     """Packed-1-bit decode product, 4096 -> 11008 with E=8 top-2 rank-64 experts (bf16, or their INT8 form), over
     `n_layers` distinct weight sets per launch (361 MB of bits: larger than the Infinity Cache)."""
     K, N, E, r, k = 4096, 11008, 8, 64, 2
@@ -89,6 +92,7 @@ def decode_bench(pq, torch, batch, n_layers=64, steps=20, warmup=3, int8_experts
         del A, Bm
         run = lambda: pq.decode_gemv_int8(desc, X, P, scale, Y, ws, Aq, gA, Bq, gB, Wr)
         eb = 1
+    _warm(torch, run)
     total_us = 1e3 * _time_steps(torch, run, steps, warmup)        # whole calls, no per-launch events
     pq.prof_reset(); pq.prof_enable(True)                          # second pass: per-kernel durations
     for _ in range(steps):
@@ -110,7 +114,7 @@ def decode_bench(pq, torch, batch, n_layers=64, steps=20, warmup=3, int8_experts
             "us_per_layer": round(total_us / n_layers, 3), "bytes_per_layer": (main_bytes + prep_bytes) // n_layers}
 
 
-def decode_ffn_bench(pq, torch, n_layers=32, steps=20, warmup=3):
+def decode_ffn_bench(pq, torch, n_layers=32, steps=100, warmup=20):
     """The decoupled FFN at inference, one token per layer: 4096 -> 11008 -> 4096 packed 1-bit matrices with E=8
     top-2 experts of hidden width 64, `n_layers` distinct FFNs per call (541 MB of bits)."""
     D, F, E, r, k = 4096, 11008, 8, 64, 2
@@ -129,6 +133,7 @@ def decode_ffn_bench(pq, torch, n_layers=32, steps=20, warmup=3):
     desc = pq.DecodeFFNDesc(D, F, r, E, k, n_layers, 1.5)
     ws = pq.decode_ffn_workspace(desc)
     run = lambda: pq.decode_ffn(desc, X, Pug, sug, Pd, sd, UpGate, Down, Wr, Y, ws)
+    _warm(torch, run)
     total_us = 1e3 * _time_steps(torch, run, steps, warmup)
     prof = _profile_steps(pq, torch, run, steps)
     # algorithmic bytes per layer: three packed matrices, the selected experts (2r x D and D x r bf16), router, x, y
@@ -137,6 +142,16 @@ def decode_ffn_bench(pq, torch, n_layers=32, steps=20, warmup=3):
             "bytes_per_layer": per_layer, "whole_call_GBps": round(per_layer * n_layers / total_us / 1e3, 1),
             "frac_hbm": round(per_layer * n_layers / total_us / 1e3 / 8000.0, 4),
             "kernels_us_total_per_call": {k_: round(1e3 * ms / steps, 2) for k_, (ms, n) in sorted(prof.items())}}
+
+
+def _warm(torch, fn, seconds=0.2):
+    """Run fn back to back for `seconds` of wall time: the first measurement of a bandwidth-bound section in a process
+    otherwise reads 5-15 % slow (the first hundred milliseconds of a new access pattern)."""
+    t_end = time.time() + seconds
+    while time.time() < t_end:
+        for _ in range(50):
+            fn()
+        torch.cuda.synchronize()
 
 
 def _time_steps(torch, fn, steps, warmup):
@@ -165,7 +180,7 @@ def _profile_steps(pq, torch, fn, steps):
     return prof
 
 
-def norm_quant_bench(pq, torch, T=8192, K=2048, sets=4, steps=40, warmup=8):
+def norm_quant_bench(pq, torch, T=8192, K=2048, sets=4, steps=100, warmup=20):
     """RMSNorm fused with the AbsMax quantiser at the config-2 activation shape (bf16), forward (all outputs)
     and backward, against HBM bandwidth.  The calls rotate over `sets` buffer sets so that the working set
     (sets x 112 MB forward) is larger than the 256 MB last-level cache.  Algorithmic bytes per element:
@@ -210,7 +225,7 @@ def norm_quant_bench(pq, torch, T=8192, K=2048, sets=4, steps=40, warmup=8):
             "plain_quantiser_us": round(ms_q * 1e3, 2), "plain_quantiser_GBps": round(qb / ms_q / 1e6, 1)}
 
 
-def hp_int8_bench(pq, torch, T=8192, K=2048, N=2048, r=128, steps=20, warmup=5):
+def hp_int8_bench(pq, torch, T=8192, K=2048, N=2048, r=128, steps=100, warmup=20):
     """INT8 form of the high-precision branch at the config-2 shape: forward (weight-row quantisers, two int8
     GEMMs with the de-quantising epilogue, hidden-state quantiser) and STE backward (four bf16 GEMMs)."""
     g = torch.Generator(device="cuda").manual_seed(8)
@@ -238,7 +253,7 @@ def hp_int8_bench(pq, torch, T=8192, K=2048, N=2048, r=128, steps=20, warmup=5):
             "kernels_us": {k: round(1e3 * ms / n, 2) for k, (ms, n) in sorted(prof.items())}}
 
 
-def ffn_bench(pq, torch, T=8192, D=2048, F=5504, E=8, r=32, steps=5, warmup=2):
+def ffn_bench(pq, torch, T=8192, D=2048, F=5504, E=8, r=32, steps=20, warmup=5):
     """Config 3: the 1.3B-shaped decoupled FFN (three 1-bit projections + E=8 top-1 experts of width 32), fwd+bwd."""
     g = torch.Generator(device="cuda").manual_seed(3)
     bf = torch.bfloat16
@@ -299,8 +314,8 @@ def stack_bench(pq, torch, L=24, T=16384, D=2048, F=5504, E=8, r=32, steps=2, wa
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--tokens", type=int, default=8192)
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -326,6 +341,29 @@ def main():
     if not os.path.exists(pq.LIB_PATH):
         from paper_2602_22592_amd.build import build
         build(verbose=False)
+
+    # The sections next to the headline step; one of them failing must not cost the line its headline numbers, so a
+    # failure is recorded in its place (and on stderr) instead of propagating.
+    extra = {}
+
+    def section(key, fn):
+        try:
+            extra[key] = fn()
+        except Exception as exc:                      # noqa: BLE001
+            extra[key] = {"error": f"{type(exc).__name__}: {exc}"}
+            print(f"bench.py: section {key} failed: {exc!r}", file=sys.stderr, flush=True)
+
+    # The bandwidth-bound sections run first: straight after 0.15 s of back-to-back MFMA work the same kernels read
+    # 8-10 % slower (the chip's power management), which says nothing about them.
+    if not args.no_decode:
+        section("decode_gemv", lambda: {"metric": "1-bit decode GEMV HBM GB/s (4096->11008, E=8 top-2 r=64 experts)",
+                                        "B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8),
+                                        "B1_int8_experts": decode_bench(pq, torch, 1, int8_experts=True),
+                                        "B8_int8_experts": decode_bench(pq, torch, 8, int8_experts=True)})
+        section("decode_ffn", lambda: decode_ffn_bench(pq, torch))
+    if not args.no_norm:
+        section("rmsnorm_quant", lambda: norm_quant_bench(pq, torch))
+    torch.cuda.empty_cache()
 
     c = wl.config2(tokens=args.tokens)
     T, K, N, r = c["tokens"], c["d_in"], c["d_out"], c["hp_rank"]
@@ -391,23 +429,6 @@ def main():
         out["calibration_copy"] = {"kernel": "gather_rows_kernel", "read_bytes": rows * cols * 2 + rows * 4,
                                    "write_bytes": rows * cols * 2}
         del src, dst, ids
-    # The sections below are additional figures next to the headline step; one of them failing must not cost the
-    # line its headline numbers, so a failure is recorded in its place (and on stderr) instead of propagating.
-    def section(key, fn):
-        try:
-            out[key] = fn()
-        except Exception as exc:                      # noqa: BLE001
-            out[key] = {"error": f"{type(exc).__name__}: {exc}"}
-            print(f"bench.py: section {key} failed: {exc!r}", file=sys.stderr, flush=True)
-
-    if not args.no_decode:
-        section("decode_gemv", lambda: {"metric": "1-bit decode GEMV HBM GB/s (4096->11008, E=8 top-2 r=64 experts)",
-                                        "B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8),
-                                        "B1_int8_experts": decode_bench(pq, torch, 1, int8_experts=True),
-                                        "B8_int8_experts": decode_bench(pq, torch, 8, int8_experts=True)})
-        section("decode_ffn", lambda: decode_ffn_bench(pq, torch))
-    if not args.no_norm:
-        section("rmsnorm_quant", lambda: norm_quant_bench(pq, torch))
     if not args.no_hp8:
         section("hp_int8_branch", lambda: hp_int8_bench(pq, torch))
     if not args.no_ffn:
@@ -418,6 +439,7 @@ def main():
         section("stack_config5", lambda: stack_bench(pq, torch))
     if not args.no_cpu_baseline:
         section("cpu_baseline", lambda: cpu_baseline(args.cpu_sample_tokens))
+    out.update(extra)
     print(json.dumps(out), flush=True)
 
 
