@@ -160,7 +160,10 @@ def test_linear_config1_fp32():
 
 @pytest.mark.parametrize("T,K,N,r,bf16", [(333, 544, 416, 24, False), (333, 544, 416, 24, True),
                                          (70, 96, 64, 0, True), (70, 96, 64, 0, False),
-                                         (1, 64, 32, 8, True), (600, 1056, 1312, 136, True)])
+                                         (1, 64, 32, 8, True), (600, 1056, 1312, 136, True),
+                                         # rank 64 / 128 with ragged token and channel tiles: the streaming loop of the
+                                         # fused GEMMs with a second contraction of one and of two whole steps
+                                         (600, 1152, 1408, 64, True), (300, 640, 384, 128, True)])
 def test_linear_ragged_multi_tile(T, K, N, r, bf16):
     say(f"linear ragged T={T} K={K} N={N} r={r} bf16={bf16}")
     c = wl.linear_case(500 + T + r, T, K, N, hp_rank=r, bf16=bf16, outlier_frac=0.02, outlier_scale=10.0)
