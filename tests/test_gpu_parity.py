@@ -36,7 +36,8 @@ def say(msg):
 
 # ---------------------------------------------------------------------------- quantiser
 @pytest.mark.parametrize("T,K,bf16", [(64, 256, False), (300, 2048, True), (37, 5504, True), (9, 4096, False),
-                                     (5, 16384, True), (3, 32, True), (130, 4096, True), (0, 64, True)])
+                                     (5, 16384, True), (3, 32, True), (130, 4096, True), (0, 64, True),
+                                     (8192, 2048, True), (8192, 5504, True)])   # full sizes of configs 2 and 3
 def test_quant_act_bit_exact(T, K, bf16):
     say(f"quant_act T={T} K={K} bf16={bf16}")
     X = wl.activations(np.random.default_rng(100 + T), T, K, outlier_frac=0.01, outlier_scale=20.0, bf16=bf16)
@@ -52,7 +53,8 @@ def test_quant_act_bit_exact(T, K, bf16):
 
 # ---------------------------------------------------------------------------- binariser / packer
 @pytest.mark.parametrize("N,K,bf16,tr", [(256, 256, False, True), (2048, 2048, True, True), (72, 96, True, False),
-                                        (160, 544, False, True), (96, 5504, True, True), (32, 32, True, True)])
+                                        (160, 544, False, True), (96, 5504, True, True), (32, 32, True, True),
+                                        (5504, 2048, True, True), (11008, 4096, True, False)])   # configs 3 and 4
 def test_pack_sign_bit_exact(N, K, bf16, tr):
     say(f"pack_sign N={N} K={K} bf16={bf16} transposed={tr}")
     W = wl.normal(np.random.default_rng(200 + N), (N, K), 0.02, bf16)
@@ -90,9 +92,27 @@ def test_onebit_acc_int32_bit_exact(T, K, N):
     assert np.array_equal(host(acc).astype(np.int64), ref)
 
 
+def test_onebit_acc_full_size_sampled_rows():
+    """Config-2 size (8192 tokens, 2048 x 2048): every token's accumulator row depends on that token alone, so the
+    oracle recomputes sampled rows; the comparison is bit-exact."""
+    T, K, N = 8192, 2048, 2048
+    say(f"onebit_acc full size T={T} K={K} N={N}, sampled rows")
+    rng = np.random.default_rng(321)
+    q = rng.integers(-128, 128, size=(T, K)).astype(np.int8)
+    q[7] = -128                                       # the extreme accumulator magnitude 128 K stays below 2^24
+    S = np.where(rng.random((N, K)) < 0.5, 1, -1).astype(np.int8)
+    S[5] = -1
+    acc = pq.onebit_acc(dev(q), dev(po.pack_sign(S).view(np.int32)), N)
+    torch.cuda.synchronize()
+    rows = np.array([0, 7, 255, 256, 4095, 4096, 8190, 8191] + list(rng.choice(T, 24, replace=False)))
+    assert np.array_equal(host(acc)[rows].astype(np.int64), po.onebit_acc(q[rows], S))
+    assert host(acc)[7, 5] == 128 * K
+
+
 # ---------------------------------------------------------------------------- router
 @pytest.mark.parametrize("T,K,E,k,bf16", [(200, 256, 8, 1, True), (77, 2048, 8, 2, True), (50, 96, 4, 2, False),
-                                         (33, 64, 16, 3, True), (9, 64, 40, 2, False)])
+                                         (33, 64, 16, 3, True), (9, 64, 40, 2, False),
+                                         (8192, 2048, 8, 1, True), (4096, 4096, 8, 2, True)])   # config 3; config-4 widths
 def test_router_topk(T, K, E, k, bf16):
     say(f"router T={T} K={K} E={E} k={k} bf16={bf16}")
     rng = np.random.default_rng(400 + T)
