@@ -130,6 +130,7 @@ lin_layout make_layout(const pq_linear_desc& d) {
   L.stat_partials = w.take(2 * sizeof(double) * 1024);
   const int Ti = d.tokens, Ki = d.d_in, Ni = d.d_out, ri = d.hp_rank;
   L.n_red_a = r ? pq_plan_gemm(engine, Ti, ri, Ni).red_blocks : 0;       // dH GEMM
+  if (r && pq_skinny_blocks(Ti) > L.n_red_a) L.n_red_a = pq_skinny_blocks(Ti);   // room for the streaming rank-r kernel's partials
   L.n_red_b = pq_plan_gemm(engine, Ni, Ki, Ti).red_blocks;                // dW GEMM
   size_t sk = 0;
   const int shapes[8][3] = {{Ti, ri, Ki}, {Ti, Ni, ri}, {Ti, ri, Ni}, {Ti, Ki, Ni},
@@ -316,11 +317,21 @@ static int linear_fwd_impl(const pq_linear_desc* d, const void* X, const void* W
   uint16_t* Xt = (ctx && bf16) ? (uint16_t*)(cx + L.Xt) : nullptr;
   bool quant_done = prequant;
   void* H = r > 0 ? (ctx ? (void*)(cx + L.H) : (void*)(ws + L.w_H)) : nullptr;
-  auto launch_H = [&](bool defer) -> int {   // H = X A^T
+  // H = X A^T.  A rank of 128 over many tokens takes the streaming rank-r kernel (whole contraction per workgroup,
+  // nothing to reduce); other shapes go through the tile engine, which may split the contraction.
+  bool H_skinny = false;
+  if (r > 0 && bf16 && T > 0) {
+    pq_operand A{X, K, PQ_SRC_KC16, nullptr}, B{hpA, K, PQ_SRC_KC16, nullptr};
+    pq_epilogue e = epi_zero();
+    e.C = H; e.ldc = r; e.out_kind = ok;
+    H_skinny = pq_skinny_applies(T, r, K, A, B, e);
+  }
+  auto launch_H = [&](bool defer) -> int {
     pq_operand A{X, K, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
     pq_operand B{hpA, K, bf16 ? PQ_SRC_KC16 : PQ_SRC_KC32, nullptr};
     pq_epilogue e = epi_zero();
     e.C = H; e.ldc = r; e.out_kind = ok; e.defer_reduce = defer ? 1 : 0;
+    if (H_skinny) return pq_launch_skinny(T, K, A, B, e, s, PQP_GEMM_HP_H);
     return pq_launch_gemm(engine, T, r, K, A, B, e, s, PQP_GEMM_HP_H, sk_ws);
   };
   // The weight statistics' first stage and the activation quantiser share a launch (rows of up to 8192 elements stay
@@ -329,7 +340,7 @@ static int linear_fwd_impl(const pq_linear_desc* d, const void* X, const void* W
   bool H_done = false;
   int H_splits = 0;
   if (combo && r > 0) {
-    H_splits = pq_plan_gemm(0, T, r, K).splits;
+    H_splits = H_skinny ? 1 : pq_plan_gemm(0, T, r, K).splits;
     if (int e = launch_H(H_splits > 1)) return e;
     H_done = true;
   }
@@ -428,6 +439,7 @@ extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void
   void* dH = ws + L.dH;
   double* red_a = (double*)(ws + L.red_a);
   double* red_b = (double*)(ws + L.red_b);
+  int n_red_a = r > 0 ? pq_plan_gemm(engine, T, r, N).red_blocks : 0;   // partial sums of d alpha that the dH GEMM leaves
 
   if (T > 0 && r > 0) {  // dH = alpha * dY B ; d alpha = <H, dY B>
     pq_operand A{dY, N, KC, nullptr};
@@ -435,7 +447,10 @@ extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void
     pq_epilogue e = epi_zero();
     e.C = dH; e.ldc = r; e.out_kind = ok; e.scale = d->alpha;
     e.dot_comp = H; e.ld_comp = r; e.comp_kind = ok; e.partials = red_a;
-    if (int err = pq_launch_gemm(engine, T, r, N, A, B, e, s, PQP_GEMM_DH, sk_ws)) return err;
+    if (engine == 0 && pq_skinny_applies(T, r, N, A, B, e)) {   // many tokens at rank 128: nothing to split or reduce
+      n_red_a = pq_skinny_blocks(T);
+      if (int err = pq_launch_skinny(T, N, A, B, e, s, PQP_GEMM_DH)) return err;
+    } else if (int err = pq_launch_gemm(engine, T, r, N, A, B, e, s, PQP_GEMM_DH, sk_ws)) return err;
   }
 
   if (T > 0) {  // dX = beta*lambda * dY S  (+ dH A, fused into the same tile for bf16 I/O)
@@ -475,7 +490,7 @@ extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void
     if (int err = pq_launch_gemm(engine, N, K, T, A, B, e, s, PQP_GEMM_DW, sk_ws)) return err;
   }
   // d alpha and d beta: both fixed-order sums of per-workgroup partials
-  const pq_reduce_job jobs[2] = {{red_a, (T > 0 && r > 0) ? L.n_red_a : 0, 1.0f, nullptr, dalpha_dbeta},
+  const pq_reduce_job jobs[2] = {{red_a, (T > 0 && r > 0) ? n_red_a : 0, 1.0f, nullptr, dalpha_dbeta},
                                  {red_b, L.n_red_b, 1.0f, mulam + 1, dalpha_dbeta + 1}};
   bool jobs_done = false;
   if (r > 0 && bf16 && T > 0) {

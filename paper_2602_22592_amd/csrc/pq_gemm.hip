@@ -1193,6 +1193,220 @@ int launch_mfma_cfg(const pq_gemm_plan& pl, int M, int N, int K, const pq_operan
 
 }  // namespace
 
+// ---------------------------------------------------------------------------------------------
+// Rank-r products with a long row dimension: C[M][128] = scale * A[M][K] B^T, bf16, A with the contraction index
+// contiguous.  B is [128][K] (H = X A^T of the high-precision branch, Sec. 3.2) or, contraction-strided, [K][128]
+// (dH = alpha dY B of its backward), then with sum(comp * (A B^T)) as a side result (d alpha).
+// ---------------------------------------------------------------------------------------------
+// With 128 output columns the tile engine has one workgroup per CU and two loads in flight per thread, so it runs as
+// a chain of memory latencies, and it needs a split contraction with slabs to occupy the chip at all.  Here a
+// workgroup of four wavefronts owns 64 rows and the whole contraction: the operand tiles of a 64-element step
+// ([64][128 B] of A, chunks swizzled by row as in the tile engine, then 16 KB of B: [128][128 B] the same way, or
+// [64][256 B] as it lies in memory for the transposing LDS reads) go straight into a ring of six LDS stages, five
+// steps ahead of the MFMAs, so about 120 KB per CU are in flight and nothing is reduced afterwards.
+// Wavefront w computes rows 32 (w >> 1) and columns 64 (w & 1); one barrier per step.
+constexpr int SK_BM = 64, SK_BN = 128;
+[[maybe_unused]] constexpr int SK_NST = 6, SK_LPW = 6;               // ring stages; 1 KB load blocks per wavefront and stage
+[[maybe_unused]] constexpr int SK_STAGE = (SK_BM + SK_BN) * 128;     // 24 blocks of 1 KB
+static_assert(SK_STAGE == 4 * SK_LPW * 1024, "four wavefronts share a stage's blocks evenly");
+
+template <bool BTR>
+__global__ __launch_bounds__(256) void skinny_gemm_kernel(const uint16_t* __restrict__ A, long lda,
+                                                         const uint16_t* __restrict__ B, long ldb, int M, int K,
+                                                         uint16_t* __restrict__ C, long ldc, float scale,
+                                                         const uint16_t* __restrict__ comp, long ld_comp,
+                                                         double* __restrict__ partials) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __shared__ __attribute__((aligned(16))) unsigned char smem[SK_NST * SK_STAGE];
+  __shared__ double red[4];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int m0 = blockIdx.x * SK_BM;
+  const int nkt = K >> 6;
+  const uint32_t lds0 = (uint32_t)(size_t)smem;
+
+  // direct loads: lane l of a load lands at byte 16 l of its 1 KB block.  A, and a contraction-contiguous B: a block is
+  // 8 rows x 128 B and lane l fetches physical chunk l & 7 of row 8 b + (l >> 3).  Contraction-strided B: a block is
+  // 4 contraction rows x 256 B and lane l fetches physical chunk l & 15 of row 4 b + (l >> 4).
+  const char* src[SK_LPW];
+  size_t adv[SK_LPW];                                 // source bytes per contraction step
+#pragma unroll
+  for (int i = 0; i < SK_LPW; ++i) {
+    const int b = wv * SK_LPW + i;                    // 0..7: A, 8..23: B
+    if (BTR && b >= 8) {
+      const int t = (b - 8) * 4 + (lane >> 4), pc = lane & 15;
+      const int c = pc ^ (4 * (t & 3));
+      src[i] = (const char*)B + ((size_t)t * ldb + c * 8) * 2;
+      adv[i] = (size_t)64 * ldb * 2;
+    } else {
+      const int r = (b < 8 ? b : b - 8) * 8 + (lane >> 3), pc = lane & 7;
+      const int c = pc ^ ((r ^ (r >> 3)) & 7);
+      src[i] = b < 8 ? (const char*)A + ((size_t)min(m0 + r, M - 1) * lda) * 2 + c * 16   // rows past the end: the last row
+                     : (const char*)B + ((size_t)r * ldb) * 2 + c * 16;
+      adv[i] = 128;
+    }
+  }
+  auto issue = [&](int kt, int stage) {
+#pragma unroll
+    for (int i = 0; i < SK_LPW; ++i)
+      __builtin_amdgcn_global_load_lds(src[i] + (size_t)kt * adv[i], PQ_LDS_PTR(smem + stage * SK_STAGE + (wv * SK_LPW + i) * 1024),
+                                       16, 0, 0);
+  };
+
+  // fragment addresses in stage 0.  A (and a contraction-contiguous B): row l & 31 of the wavefront's block, logical
+  // chunk 2 ks + (l >> 5).  Contraction-strided B: the transposing read takes, per lane, the address of four
+  // consecutive columns in contraction row 8 (l >> 5) + ((l & 15) >> 2) (+ 4 for the second half of the operand).
+  const int h = lane >> 5;
+  uint32_t adA[4], adB[2][BTR ? 1 : 4];
+  {
+    const int ra = (wv >> 1) * 32 + (lane & 31);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) adA[ks] = lds0 + ra * 128 + ((((2 * ks + h) ^ ra ^ (ra >> 3)) & 7) << 4);
+    if constexpr (BTR) {
+      const int tl = 8 * h + ((lane & 15) >> 2), cl = 16 * ((lane >> 4) & 1) + 4 * (lane & 3), sw = 4 * ((lane & 15) >> 2);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = (wv & 1) * 64 + 32 * j + cl;
+        adB[j][0] = lds0 + SK_BM * 128 + tl * 256 + (((col >> 3) ^ sw) << 4) + (col & 7) * 2;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int rb = (wv & 1) * 64 + j * 32 + (lane & 31);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) adB[j][ks] = lds0 + SK_BM * 128 + rb * 128 + ((((2 * ks + h) ^ rb ^ (rb >> 3)) & 7) << 4);
+      }
+    }
+  }
+  f32x16_t acc[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+
+#pragma unroll
+  for (int st = 0; st < SK_NST - 1; ++st) issue(min(st, nkt - 1), st);   // steps past the end: the last one again, never read
+  int st = 0;
+  for (int kt = 0; kt < nkt; ++kt) {
+    // at most four later steps stay in flight: this step's tiles have landed (for this wavefront; the barrier makes
+    // it everybody's), and every wavefront is past its reads of the stage that is refilled next
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((SK_NST - 2) * SK_LPW) : "memory");
+    asm volatile("s_barrier" ::: "memory");
+    issue(min(kt + SK_NST - 1, nkt - 1), st == 0 ? SK_NST - 1 : st - 1);
+    const uint32_t so = (uint32_t)(st * SK_STAGE);
+    if constexpr (BTR) {
+      i32x4_t fa[4];
+      pq_i32x2 hb[2][4];                              // two sub-steps of B in flight: [parity][2 j + half]
+      const uint32_t p0 = adB[0][0] + so, p1 = adB[1][0] + so;
+#define PQ_SK_READ(ks)                                                                      \
+  do {                                                                                      \
+    PQ_DS_READ128(fa[ks], adA[ks] + so, 0);                                                 \
+    PQ_DS_READ_TR(hb[(ks) & 1][0], p0, (ks) * 4096);                                         \
+    PQ_DS_READ_TR(hb[(ks) & 1][1], p0, (ks) * 4096 + 1024);                                  \
+    PQ_DS_READ_TR(hb[(ks) & 1][2], p1, (ks) * 4096);                                         \
+    PQ_DS_READ_TR(hb[(ks) & 1][3], p1, (ks) * 4096 + 1024);                                  \
+  } while (0)
+#define PQ_SK_MFMA(ks, NOUT)                                                                                      \
+  do {                                                                                                            \
+    asm volatile("s_waitcnt lgkmcnt(%5)"                                                                          \
+                 : "+v"(fa[ks]), "+v"(hb[(ks) & 1][0]), "+v"(hb[(ks) & 1][1]), "+v"(hb[(ks) & 1][2]), "+v"(hb[(ks) & 1][3]) \
+                 : "n"(NOUT));                                                                                    \
+    const i32x4_t b0 = {hb[(ks) & 1][0][0], hb[(ks) & 1][0][1], hb[(ks) & 1][1][0], hb[(ks) & 1][1][1]};          \
+    const i32x4_t b1 = {hb[(ks) & 1][2][0], hb[(ks) & 1][2][1], hb[(ks) & 1][3][0], hb[(ks) & 1][3][1]};          \
+    PQ_MFMA_BF16(acc[0], fa[ks], b0);                                                                             \
+    PQ_MFMA_BF16(acc[1], fa[ks], b1);                                                                             \
+  } while (0)
+      PQ_SK_READ(0);
+      PQ_SK_READ(1);
+      PQ_SK_MFMA(0, 5);
+      PQ_SK_READ(2);
+      PQ_SK_MFMA(1, 5);
+      PQ_SK_READ(3);
+      PQ_SK_MFMA(2, 5);
+      PQ_SK_MFMA(3, 0);
+#undef PQ_SK_READ
+#undef PQ_SK_MFMA
+    } else {
+      i32x4_t fa[4], fb0[4], fb1[4];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        PQ_DS_READ128(fa[ks], adA[ks] + so, 0);
+        PQ_DS_READ128(fb0[ks], adB[0][ks] + so, 0);
+        PQ_DS_READ128(fb1[ks], adB[1][ks] + so, 0);
+      }
+      asm volatile("s_waitcnt lgkmcnt(9)" : "+v"(fa[0]), "+v"(fb0[0]), "+v"(fb1[0]));
+      PQ_MFMA_BF16(acc[0], fa[0], fb0[0]);
+      PQ_MFMA_BF16(acc[1], fa[0], fb1[0]);
+      asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(fa[1]), "+v"(fb0[1]), "+v"(fb1[1]));
+      PQ_MFMA_BF16(acc[0], fa[1], fb0[1]);
+      PQ_MFMA_BF16(acc[1], fa[1], fb1[1]);
+      asm volatile("s_waitcnt lgkmcnt(3)" : "+v"(fa[2]), "+v"(fb0[2]), "+v"(fb1[2]));
+      PQ_MFMA_BF16(acc[0], fa[2], fb0[2]);
+      PQ_MFMA_BF16(acc[1], fa[2], fb1[2]);
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(fa[3]), "+v"(fb0[3]), "+v"(fb1[3]));
+      PQ_MFMA_BF16(acc[0], fa[3], fb0[3]);
+      PQ_MFMA_BF16(acc[1], fa[3], fb1[3]);
+    }
+    st = st == SK_NST - 1 ? 0 : st + 1;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the redundant loads of the last steps are done before the workgroup ends
+
+  // the B fragment was the first MFMA operand: lane l holds row l & 31, register v column 8 (v >> 2) + 4 (l >> 5) + (v & 3)
+  const int m = m0 + (wv >> 1) * 32 + (lane & 31);
+  double psum = 0.0;
+  if (m < M) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n = (wv & 1) * 64 + j * 32 + 8 * g + 4 * h;
+        if (comp) {                                  // uniform
+          const uint2 u = *reinterpret_cast<const uint2*>(comp + (size_t)m * ld_comp + n);
+          psum += (double)__uint_as_float(u.x << 16) * (double)acc[j][4 * g];
+          psum += (double)__uint_as_float(u.x & 0xFFFF0000u) * (double)acc[j][4 * g + 1];
+          psum += (double)__uint_as_float(u.y << 16) * (double)acc[j][4 * g + 2];
+          psum += (double)__uint_as_float(u.y & 0xFFFF0000u) * (double)acc[j][4 * g + 3];
+        }
+        const float v0 = __fmul_rn(scale, acc[j][4 * g]), v1 = __fmul_rn(scale, acc[j][4 * g + 1]);
+        const float v2 = __fmul_rn(scale, acc[j][4 * g + 2]), v3 = __fmul_rn(scale, acc[j][4 * g + 3]);
+        *reinterpret_cast<uint2*>(C + (size_t)m * ldc + n) = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
+      }
+  }
+  if (partials) {                                    // uniform: one partial sum per workgroup, added in a fixed order
+    const double t = block_sum_d<256>(psum, red);
+    if (tid == 0) partials[blockIdx.x] = t;
+  }
+#endif
+}
+
+// Shapes, alignments and epilogues the kernel above takes: 128 columns, whole 64-element steps, a plain bf16 store,
+// optionally with the dot product against a bf16 matrix of the output's shape.
+bool pq_skinny_applies(int M, int N, int K, const pq_operand& A, const pq_operand& B, const pq_epilogue& e) {
+  const bool btr = B.kind == PQ_SRC_KS16;
+  return M >= 1024 && N == SK_BN && K >= 64 && K % 64 == 0 && A.kind == PQ_SRC_KC16 && (B.kind == PQ_SRC_KC16 || btr) && !A.kdiv &&
+         !B.kdiv && A.ld >= K && B.ld >= (btr ? N : K) && (A.ld * 2) % 16 == 0 && (B.ld * 2) % 16 == 0 && ((uintptr_t)A.p % 16) == 0 &&
+         ((uintptr_t)B.p % 16) == 0 && e.out_kind == PQ_OUT_BF16 && e.ldc >= N && (e.ldc * 2) % 8 == 0 && ((uintptr_t)e.C % 8) == 0 &&
+         !e.row_div && !e.col_div && !e.sign_bytes && !e.maskW && !e.accumulate && !e.dev_scale &&
+         (!e.dot_comp || (e.comp_kind == PQ_OUT_BF16 && e.partials && e.ld_comp >= N && (e.ld_comp * 2) % 8 == 0 &&
+                          ((uintptr_t)e.dot_comp % 8) == 0)) &&
+         (e.dot_comp || !e.partials);
+}
+
+int pq_skinny_blocks(int M) { return (M + SK_BM - 1) / SK_BM; }
+
+int pq_launch_skinny(int M, int K, const pq_operand& A, const pq_operand& B, const pq_epilogue& e, hipStream_t s, int prof_label) {
+  pq_prof_scope prof(prof_label, s);
+  const dim3 grid(pq_skinny_blocks(M)), block(256);
+  if (B.kind == PQ_SRC_KS16)
+    skinny_gemm_kernel<true><<<grid, block, 0, s>>>((const uint16_t*)A.p, A.ld, (const uint16_t*)B.p, B.ld, M, K, (uint16_t*)e.C, e.ldc,
+                                                    e.scale, (const uint16_t*)e.dot_comp, e.ld_comp, e.partials);
+  else
+    skinny_gemm_kernel<false><<<grid, block, 0, s>>>((const uint16_t*)A.p, A.ld, (const uint16_t*)B.p, B.ld, M, K, (uint16_t*)e.C, e.ldc,
+                                                     e.scale, (const uint16_t*)e.dot_comp, e.ld_comp, e.partials);
+  PQ_CHECK_LAUNCH("skinny_gemm_kernel");
+  return PQ_OK;
+}
+
 // Tile shape and contraction split for one GEMM.  A 256x256 tile (8 wavefronts, 128x64 each) when
 // the output is large enough, else 128x128 (4 wavefronts); when the tiles alone cannot occupy the
 // 256 compute units the contraction is split and reduced in a second, fixed-order pass.

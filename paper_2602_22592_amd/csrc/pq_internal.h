@@ -148,6 +148,15 @@ pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8 = false, bo
 // Two bf16 GEMMs with contraction-strided operands on both sides (the rank-r weight gradients dA and dB) in one
 // launch when their plans agree (same tile shape, tile count and contraction split), else one after the other.
 // Both have plain epilogues: C (fp32) = scale * acc.
+// C[M][128] = scale * A B^T for bf16 operands and many rows (the hidden state of the dense high-precision branch
+// and its gradient, Sec. 3.2): one workgroup per 64 rows runs the whole contraction through a six-stage ring of
+// direct-to-LDS loads, so nothing is split or reduced.  B is contraction-contiguous or contraction-strided; the
+// epilogue may carry dot_comp / partials (one partial sum per workgroup: pq_skinny_blocks(M) of them).
+// `applies` states the shapes, alignments and epilogues it takes.
+bool pq_skinny_applies(int M, int N, int K, const pq_operand& A, const pq_operand& B, const pq_epilogue& e);
+int pq_skinny_blocks(int M);
+int pq_launch_skinny(int M, int K, const pq_operand& A, const pq_operand& B, const pq_epilogue& e, hipStream_t s, int prof_label);
+
 int pq_launch_gemm_pair_ks16(int K, int M0, int N0, const pq_operand& A0, const pq_operand& B0, float* C0, int ldc0, float scale0,
                              int M1, int N1, const pq_operand& A1, const pq_operand& B1, float* C1, int ldc1, float scale1,
                              hipStream_t s, int prof_label0, int prof_label1, void* splitk_ws0, void* splitk_ws1,

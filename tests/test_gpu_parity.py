@@ -183,7 +183,9 @@ def test_linear_config1_fp32():
                                          (1, 64, 32, 8, True), (600, 1056, 1312, 136, True),
                                          # rank 64 / 128 with ragged token and channel tiles: the streaming loop of the
                                          # fused GEMMs with a second contraction of one and of two whole steps
-                                         (600, 1152, 1408, 64, True), (300, 640, 384, 128, True)])
+                                         (600, 1152, 1408, 64, True), (300, 640, 384, 128, True),
+                                         # many tokens at rank 128: the streaming rank-r kernel computes H (ragged last block)
+                                         (1100, 640, 384, 128, True), (1024, 64, 256, 128, True)])
 def test_linear_ragged_multi_tile(T, K, N, r, bf16):
     say(f"linear ragged T={T} K={K} N={N} r={r} bf16={bf16}")
     c = wl.linear_case(500 + T + r, T, K, N, hp_rank=r, bf16=bf16, outlier_frac=0.02, outlier_scale=10.0)
