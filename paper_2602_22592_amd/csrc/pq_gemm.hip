@@ -1200,166 +1200,184 @@ int launch_mfma_cfg(const pq_gemm_plan& pl, int M, int N, int K, const pq_operan
 // ---------------------------------------------------------------------------------------------
 // With 128 output columns the tile engine has one workgroup per CU and two loads in flight per thread, so it runs as
 // a chain of memory latencies, and it needs a split contraction with slabs to occupy the chip at all.  Here a
-// workgroup of four wavefronts owns 64 rows and the whole contraction: the operand tiles of a 64-element step
+// workgroup of four wavefronts owns 64 (or 32) rows and the whole contraction: the operand tiles of a 64-element step
 // ([64][128 B] of A, chunks swizzled by row as in the tile engine, then 16 KB of B: [128][128 B] the same way, or
 // [64][256 B] as it lies in memory for the transposing LDS reads) go straight into a ring of six LDS stages, five
-// steps ahead of the MFMAs, so about 120 KB per CU are in flight and nothing is reduced afterwards.
-// Wavefront w computes rows 32 (w >> 1) and columns 64 (w & 1); one barrier per step.
-constexpr int SK_BM = 64, SK_BN = 128;
-[[maybe_unused]] constexpr int SK_NST = 6, SK_LPW = 6;               // ring stages; 1 KB load blocks per wavefront and stage
-[[maybe_unused]] constexpr int SK_STAGE = (SK_BM + SK_BN) * 128;     // 24 blocks of 1 KB
-static_assert(SK_STAGE == 4 * SK_LPW * 1024, "four wavefronts share a stage's blocks evenly");
+// steps ahead of the MFMAs, so about 120 KB per CU are in flight and nothing is reduced afterwards; one barrier per step.
+constexpr int SK_BN = 128;
 
-template <bool BTR>
+// BM = 64: wavefront w computes rows 32 (w >> 1) and columns 64 (w & 1), six stages of 24 KB.  BM = 32: one row block,
+// wavefront w computes columns 32 w, seven stages of 20 KB (twice the workgroups for the same rows: B is streamed by
+// twice as many CUs, A by each of them half as long).
+template <bool BTR, int BM>
 __global__ __launch_bounds__(256) void skinny_gemm_kernel(const uint16_t* __restrict__ A, long lda,
                                                          const uint16_t* __restrict__ B, long ldb, int M, int K,
                                                          uint16_t* __restrict__ C, long ldc, float scale,
                                                          const uint16_t* __restrict__ comp, long ld_comp,
                                                          double* __restrict__ partials) {
 #if defined(__HIP_DEVICE_COMPILE__)
-  __shared__ __attribute__((aligned(16))) unsigned char smem[SK_NST * SK_STAGE];
+  static_assert(BM == 64 || BM == 32, "one or two 32-row blocks");
+  constexpr int NA = BM / 8;                          // 1 KB load blocks of A per stage; B has 16
+  constexpr int LPW = (NA + 16) / 4;                  // load blocks per wavefront and stage
+  constexpr int NST = BM == 64 ? 6 : 7;               // ring stages
+  constexpr int STAGE = (NA + 16) * 1024;
+  constexpr int NJ = BM == 64 ? 2 : 1;                // 32-column blocks per wavefront
+  static_assert((NA + 16) % 4 == 0 && NST * STAGE <= 150 * 1024, "even split of the loads; the ring fits LDS");
+  __shared__ __attribute__((aligned(16))) unsigned char smem[NST * STAGE];
   __shared__ double red[4];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int m0 = blockIdx.x * SK_BM;
+  const int m0 = blockIdx.x * BM;
+  const int wr0 = BM == 64 ? (wv >> 1) * 32 : 0;      // the wavefront's rows and columns inside the tile
+  const int wc0 = BM == 64 ? (wv & 1) * 64 : wv * 32;
   const int nkt = K >> 6;
   const uint32_t lds0 = (uint32_t)(size_t)smem;
 
   // direct loads: lane l of a load lands at byte 16 l of its 1 KB block.  A, and a contraction-contiguous B: a block is
   // 8 rows x 128 B and lane l fetches physical chunk l & 7 of row 8 b + (l >> 3).  Contraction-strided B: a block is
   // 4 contraction rows x 256 B and lane l fetches physical chunk l & 15 of row 4 b + (l >> 4).
-  const char* src[SK_LPW];
-  size_t adv[SK_LPW];                                 // source bytes per contraction step
+  const char* src[LPW];
+  size_t adv[LPW];                                    // source bytes per contraction step
 #pragma unroll
-  for (int i = 0; i < SK_LPW; ++i) {
-    const int b = wv * SK_LPW + i;                    // 0..7: A, 8..23: B
-    if (BTR && b >= 8) {
-      const int t = (b - 8) * 4 + (lane >> 4), pc = lane & 15;
+  for (int i = 0; i < LPW; ++i) {
+    const int b = wv * LPW + i;                       // 0..NA-1: A, then 16 blocks of B
+    if (BTR && b >= NA) {
+      const int t = (b - NA) * 4 + (lane >> 4), pc = lane & 15;
       const int c = pc ^ (4 * (t & 3));
       src[i] = (const char*)B + ((size_t)t * ldb + c * 8) * 2;
       adv[i] = (size_t)64 * ldb * 2;
     } else {
-      const int r = (b < 8 ? b : b - 8) * 8 + (lane >> 3), pc = lane & 7;
+      const int r = (b < NA ? b : b - NA) * 8 + (lane >> 3), pc = lane & 7;
       const int c = pc ^ ((r ^ (r >> 3)) & 7);
-      src[i] = b < 8 ? (const char*)A + ((size_t)min(m0 + r, M - 1) * lda) * 2 + c * 16   // rows past the end: the last row
-                     : (const char*)B + ((size_t)r * ldb) * 2 + c * 16;
+      src[i] = b < NA ? (const char*)A + ((size_t)min(m0 + r, M - 1) * lda) * 2 + c * 16   // rows past the end: the last row
+                      : (const char*)B + ((size_t)r * ldb) * 2 + c * 16;
       adv[i] = 128;
     }
   }
   auto issue = [&](int kt, int stage) {
 #pragma unroll
-    for (int i = 0; i < SK_LPW; ++i)
-      __builtin_amdgcn_global_load_lds(src[i] + (size_t)kt * adv[i], PQ_LDS_PTR(smem + stage * SK_STAGE + (wv * SK_LPW + i) * 1024),
-                                       16, 0, 0);
+    for (int i = 0; i < LPW; ++i)
+      __builtin_amdgcn_global_load_lds(src[i] + (size_t)kt * adv[i], PQ_LDS_PTR(smem + stage * STAGE + (wv * LPW + i) * 1024), 16, 0, 0);
   };
 
   // fragment addresses in stage 0.  A (and a contraction-contiguous B): row l & 31 of the wavefront's block, logical
   // chunk 2 ks + (l >> 5).  Contraction-strided B: the transposing read takes, per lane, the address of four
   // consecutive columns in contraction row 8 (l >> 5) + ((l & 15) >> 2) (+ 4 for the second half of the operand).
   const int h = lane >> 5;
-  uint32_t adA[4], adB[2][BTR ? 1 : 4];
+  uint32_t adA[4], adB[NJ][BTR ? 1 : 4];
   {
-    const int ra = (wv >> 1) * 32 + (lane & 31);
+    const int ra = wr0 + (lane & 31);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) adA[ks] = lds0 + ra * 128 + ((((2 * ks + h) ^ ra ^ (ra >> 3)) & 7) << 4);
     if constexpr (BTR) {
       const int tl = 8 * h + ((lane & 15) >> 2), cl = 16 * ((lane >> 4) & 1) + 4 * (lane & 3), sw = 4 * ((lane & 15) >> 2);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int col = (wv & 1) * 64 + 32 * j + cl;
-        adB[j][0] = lds0 + SK_BM * 128 + tl * 256 + (((col >> 3) ^ sw) << 4) + (col & 7) * 2;
+      for (int j = 0; j < NJ; ++j) {
+        const int col = wc0 + 32 * j + cl;
+        adB[j][0] = lds0 + NA * 1024 + tl * 256 + (((col >> 3) ^ sw) << 4) + (col & 7) * 2;
       }
     } else {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int rb = (wv & 1) * 64 + j * 32 + (lane & 31);
+      for (int j = 0; j < NJ; ++j) {
+        const int rb = wc0 + j * 32 + (lane & 31);
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) adB[j][ks] = lds0 + SK_BM * 128 + rb * 128 + ((((2 * ks + h) ^ rb ^ (rb >> 3)) & 7) << 4);
+        for (int ks = 0; ks < 4; ++ks) adB[j][ks] = lds0 + NA * 1024 + rb * 128 + ((((2 * ks + h) ^ rb ^ (rb >> 3)) & 7) << 4);
       }
     }
   }
-  f32x16_t acc[2];
+  f32x16_t acc[NJ];
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
+  for (int j = 0; j < NJ; ++j)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
 
 #pragma unroll
-  for (int st = 0; st < SK_NST - 1; ++st) issue(min(st, nkt - 1), st);   // steps past the end: the last one again, never read
+  for (int st = 0; st < NST - 1; ++st) issue(min(st, nkt - 1), st);   // steps past the end: the last one again, never read
   int st = 0;
   for (int kt = 0; kt < nkt; ++kt) {
-    // at most four later steps stay in flight: this step's tiles have landed (for this wavefront; the barrier makes
+    // all but the NST - 2 latest steps have landed: this step's tiles are there (for this wavefront; the barrier makes
     // it everybody's), and every wavefront is past its reads of the stage that is refilled next
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((SK_NST - 2) * SK_LPW) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NST - 2) * LPW) : "memory");
     asm volatile("s_barrier" ::: "memory");
-    issue(min(kt + SK_NST - 1, nkt - 1), st == 0 ? SK_NST - 1 : st - 1);
-    const uint32_t so = (uint32_t)(st * SK_STAGE);
+    issue(min(kt + NST - 1, nkt - 1), st == 0 ? NST - 1 : st - 1);
+    const uint32_t so = (uint32_t)(st * STAGE);
+    i32x4_t fa[4];
     if constexpr (BTR) {
-      i32x4_t fa[4];
-      pq_i32x2 hb[2][4];                              // two sub-steps of B in flight: [parity][2 j + half]
-      const uint32_t p0 = adB[0][0] + so, p1 = adB[1][0] + so;
+      constexpr int RPS = 1 + 2 * NJ;                 // LDS reads per sub-step
+      pq_i32x2 hb[2][2 * NJ];                         // two sub-steps of B in flight: [parity][2 j + half]
+      uint32_t pb[NJ];
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) pb[j] = adB[j][0] + so;
 #define PQ_SK_READ(ks)                                                                      \
   do {                                                                                      \
     PQ_DS_READ128(fa[ks], adA[ks] + so, 0);                                                 \
-    PQ_DS_READ_TR(hb[(ks) & 1][0], p0, (ks) * 4096);                                         \
-    PQ_DS_READ_TR(hb[(ks) & 1][1], p0, (ks) * 4096 + 1024);                                  \
-    PQ_DS_READ_TR(hb[(ks) & 1][2], p1, (ks) * 4096);                                         \
-    PQ_DS_READ_TR(hb[(ks) & 1][3], p1, (ks) * 4096 + 1024);                                  \
+    PQ_DS_READ_TR(hb[(ks) & 1][0], pb[0], (ks) * 4096);                                      \
+    PQ_DS_READ_TR(hb[(ks) & 1][1], pb[0], (ks) * 4096 + 1024);                               \
+    if constexpr (NJ == 2) {                                                                \
+      PQ_DS_READ_TR(hb[(ks) & 1][2 * (NJ - 1)], pb[NJ - 1], (ks) * 4096);                    \
+      PQ_DS_READ_TR(hb[(ks) & 1][2 * (NJ - 1) + 1], pb[NJ - 1], (ks) * 4096 + 1024);         \
+    }                                                                                       \
   } while (0)
 #define PQ_SK_MFMA(ks, NOUT)                                                                                      \
   do {                                                                                                            \
-    asm volatile("s_waitcnt lgkmcnt(%5)"                                                                          \
-                 : "+v"(fa[ks]), "+v"(hb[(ks) & 1][0]), "+v"(hb[(ks) & 1][1]), "+v"(hb[(ks) & 1][2]), "+v"(hb[(ks) & 1][3]) \
-                 : "n"(NOUT));                                                                                    \
-    const i32x4_t b0 = {hb[(ks) & 1][0][0], hb[(ks) & 1][0][1], hb[(ks) & 1][1][0], hb[(ks) & 1][1][1]};          \
-    const i32x4_t b1 = {hb[(ks) & 1][2][0], hb[(ks) & 1][2][1], hb[(ks) & 1][3][0], hb[(ks) & 1][3][1]};          \
-    PQ_MFMA_BF16(acc[0], fa[ks], b0);                                                                             \
-    PQ_MFMA_BF16(acc[1], fa[ks], b1);                                                                             \
+    if constexpr (NJ == 2)                                                                                        \
+      asm volatile("s_waitcnt lgkmcnt(%5)"                                                                        \
+                   : "+v"(fa[ks]), "+v"(hb[(ks) & 1][0]), "+v"(hb[(ks) & 1][1]), "+v"(hb[(ks) & 1][2 * (NJ - 1)]),  \
+                     "+v"(hb[(ks) & 1][2 * (NJ - 1) + 1])                                                         \
+                   : "n"(NOUT));                                                                                  \
+    else                                                                                                          \
+      asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(fa[ks]), "+v"(hb[(ks) & 1][0]), "+v"(hb[(ks) & 1][1]) : "n"(NOUT)); \
+    _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                                              \
+      const i32x4_t b = {hb[(ks) & 1][2 * j][0], hb[(ks) & 1][2 * j][1], hb[(ks) & 1][2 * j + 1][0], hb[(ks) & 1][2 * j + 1][1]}; \
+      PQ_MFMA_BF16(acc[j], fa[ks], b);                                                                            \
+    }                                                                                                             \
   } while (0)
       PQ_SK_READ(0);
       PQ_SK_READ(1);
-      PQ_SK_MFMA(0, 5);
+      PQ_SK_MFMA(0, RPS);
       PQ_SK_READ(2);
-      PQ_SK_MFMA(1, 5);
+      PQ_SK_MFMA(1, RPS);
       PQ_SK_READ(3);
-      PQ_SK_MFMA(2, 5);
+      PQ_SK_MFMA(2, RPS);
       PQ_SK_MFMA(3, 0);
 #undef PQ_SK_READ
 #undef PQ_SK_MFMA
     } else {
-      i32x4_t fa[4], fb0[4], fb1[4];
+      constexpr int RPS = 1 + NJ;
+      i32x4_t fb[NJ][4];
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         PQ_DS_READ128(fa[ks], adA[ks] + so, 0);
-        PQ_DS_READ128(fb0[ks], adB[0][ks] + so, 0);
-        PQ_DS_READ128(fb1[ks], adB[1][ks] + so, 0);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) PQ_DS_READ128(fb[j][ks], adB[j][ks] + so, 0);
       }
-      asm volatile("s_waitcnt lgkmcnt(9)" : "+v"(fa[0]), "+v"(fb0[0]), "+v"(fb1[0]));
-      PQ_MFMA_BF16(acc[0], fa[0], fb0[0]);
-      PQ_MFMA_BF16(acc[1], fa[0], fb1[0]);
-      asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(fa[1]), "+v"(fb0[1]), "+v"(fb1[1]));
-      PQ_MFMA_BF16(acc[0], fa[1], fb0[1]);
-      PQ_MFMA_BF16(acc[1], fa[1], fb1[1]);
-      asm volatile("s_waitcnt lgkmcnt(3)" : "+v"(fa[2]), "+v"(fb0[2]), "+v"(fb1[2]));
-      PQ_MFMA_BF16(acc[0], fa[2], fb0[2]);
-      PQ_MFMA_BF16(acc[1], fa[2], fb1[2]);
-      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(fa[3]), "+v"(fb0[3]), "+v"(fb1[3]));
-      PQ_MFMA_BF16(acc[0], fa[3], fb0[3]);
-      PQ_MFMA_BF16(acc[1], fa[3], fb1[3]);
+#define PQ_SK_MFMA(ks)                                                                                             \
+  do {                                                                                                             \
+    if constexpr (NJ == 2)                                                                                         \
+      asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(fa[ks]), "+v"(fb[0][ks]), "+v"(fb[NJ - 1][ks]) : "n"((3 - (ks)) * RPS)); \
+    else                                                                                                           \
+      asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(fa[ks]), "+v"(fb[0][ks]) : "n"((3 - (ks)) * RPS));              \
+    _Pragma("unroll") for (int j = 0; j < NJ; ++j) PQ_MFMA_BF16(acc[j], fa[ks], fb[j][ks]);                        \
+  } while (0)
+      PQ_SK_MFMA(0);
+      PQ_SK_MFMA(1);
+      PQ_SK_MFMA(2);
+      PQ_SK_MFMA(3);
+#undef PQ_SK_MFMA
     }
-    st = st == SK_NST - 1 ? 0 : st + 1;
+    st = st == NST - 1 ? 0 : st + 1;
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the redundant loads of the last steps are done before the workgroup ends
 
   // the B fragment was the first MFMA operand: lane l holds row l & 31, register v column 8 (v >> 2) + 4 (l >> 5) + (v & 3)
-  const int m = m0 + (wv >> 1) * 32 + (lane & 31);
+  const int m = m0 + wr0 + (lane & 31);
   double psum = 0.0;
   if (m < M) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int n = (wv & 1) * 64 + j * 32 + 8 * g + 4 * h;
+        const int n = wc0 + j * 32 + 8 * g + 4 * h;
         if (comp) {                                  // uniform
           const uint2 u = *reinterpret_cast<const uint2*>(comp + (size_t)m * ld_comp + n);
           psum += (double)__uint_as_float(u.x << 16) * (double)acc[j][4 * g];
@@ -1392,17 +1410,22 @@ bool pq_skinny_applies(int M, int N, int K, const pq_operand& A, const pq_operan
          (e.dot_comp || !e.partials);
 }
 
-int pq_skinny_blocks(int M) { return (M + SK_BM - 1) / SK_BM; }
+#ifndef PQ_SK_ROWS
+#define PQ_SK_ROWS 32
+#endif
+int pq_skinny_blocks(int M) { return (M + PQ_SK_ROWS - 1) / PQ_SK_ROWS; }
 
 int pq_launch_skinny(int M, int K, const pq_operand& A, const pq_operand& B, const pq_epilogue& e, hipStream_t s, int prof_label) {
   pq_prof_scope prof(prof_label, s);
   const dim3 grid(pq_skinny_blocks(M)), block(256);
   if (B.kind == PQ_SRC_KS16)
-    skinny_gemm_kernel<true><<<grid, block, 0, s>>>((const uint16_t*)A.p, A.ld, (const uint16_t*)B.p, B.ld, M, K, (uint16_t*)e.C, e.ldc,
-                                                    e.scale, (const uint16_t*)e.dot_comp, e.ld_comp, e.partials);
+    skinny_gemm_kernel<true, PQ_SK_ROWS><<<grid, block, 0, s>>>((const uint16_t*)A.p, A.ld, (const uint16_t*)B.p, B.ld, M, K,
+                                                                (uint16_t*)e.C, e.ldc, e.scale, (const uint16_t*)e.dot_comp, e.ld_comp,
+                                                                e.partials);
   else
-    skinny_gemm_kernel<false><<<grid, block, 0, s>>>((const uint16_t*)A.p, A.ld, (const uint16_t*)B.p, B.ld, M, K, (uint16_t*)e.C, e.ldc,
-                                                     e.scale, (const uint16_t*)e.dot_comp, e.ld_comp, e.partials);
+    skinny_gemm_kernel<false, PQ_SK_ROWS><<<grid, block, 0, s>>>((const uint16_t*)A.p, A.ld, (const uint16_t*)B.p, B.ld, M, K,
+                                                                 (uint16_t*)e.C, e.ldc, e.scale, (const uint16_t*)e.dot_comp, e.ld_comp,
+                                                                 e.partials);
   PQ_CHECK_LAUNCH("skinny_gemm_kernel");
   return PQ_OK;
 }
@@ -1495,6 +1518,10 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
   if (phase2) ph2 = *phase2;
   if (ph2.K2 > 0 && (engine == 1 || grp.mode)) return pq_set_error(PQ_ERR_BAD_ARG, "a fused second contraction needs the plain MFMA engine");
   if (grp.mode && engine == 1) return pq_set_error(PQ_ERR_DTYPE, "grouped GEMMs run on the MFMA engine only (bf16 I/O)");
+  // plain rank-128 products over many rows: the streaming kernel (callers that want per-block partial sums or the
+  // slabs of a split contraction choose it themselves, since it changes how many of those there are)
+  if (engine == 0 && !grp.mode && ph2.K2 == 0 && !epi.partials && !epi.defer_reduce && pq_skinny_applies(M, N, K, A, B, epi))
+    return pq_launch_skinny(M, K, A, B, epi, s, prof_label);
   if (engine == 1) {
     pq_prof_scope prof(prof_label, s);
     dim3 grid((N + 15) / 16, (M + 15) / 16), block(256);
