@@ -1397,6 +1397,146 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const uint16_t* __rest
 #endif
 }
 
+// The two weight gradients of the rank-128 branch, dB = alpha dY^T H and dA = dH^T X (Sec. 3.2, STE backward): the
+// contraction runs over the tokens and both operands are stored token-major.  Same ring as above with both tiles as
+// they lie in memory ([64 tokens][128 B] of the wide operand's 64 columns, [64 tokens][256 B] of the rank-128 one)
+// and transposing LDS reads for both.  A workgroup owns 64 columns of the wide operand and one of 4 to 16 token
+// ranges (blockIdx.y), and writes a 64 x 128 fp32 tile of that range's slab; blockIdx.z selects the problem.  For dA the wide
+// operand is X, so the tile is the transpose of the output's and is stored transposed (dA is [128][d_in]).
+struct skt_problem {
+  const uint16_t* W;   // wide operand [T][ldw], M columns used
+  long ldw;
+  const uint16_t* R;   // rank-128 operand [T][ldr]
+  long ldr;
+  int M;               // multiple of 64
+  int trans;           // 0: slab[split][M][128], 1: slab[split][128][M]
+  float* slab;
+};
+
+__global__ __launch_bounds__(256) void skinny_tn_pair_kernel(skt_problem p0, skt_problem p1, int tokens_per_split) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  constexpr int NST = 6, LPW = 6, STAGE = 24 * 1024;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[NST * STAGE];
+  const skt_problem& p = blockIdx.z ? p1 : p0;        // uniform
+  const int m0 = blockIdx.x * 64;
+  if (m0 >= p.M) return;                              // uniform, ahead of every barrier
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int split = blockIdx.y;
+  const size_t kb = (size_t)split * tokens_per_split;
+  const int nkt = tokens_per_split >> 6;
+  const uint32_t lds0 = (uint32_t)(size_t)smem;
+  const int wr0 = (wv >> 1) * 32, wc0 = (wv & 1) * 64;
+
+  // direct loads, lane l at byte 16 l of a 1 KB block.  Wide operand: a block is 8 tokens x 128 B, lane l fetches
+  // physical chunk l & 7 of token 8 b + (l >> 3); rank-128 operand: 4 tokens x 256 B, chunk l & 15 of token 4 b + (l >> 4).
+  // Chunks are XOR-swizzled by the token's two low bits so that the transposing reads spread over the banks.
+  const char* src[LPW];
+  size_t adv[LPW];
+#pragma unroll
+  for (int i = 0; i < LPW; ++i) {
+    const int b = wv * LPW + i;                       // 0..7: wide operand, 8..23: rank-128 operand
+    if (b < 8) {
+      const int t = b * 8 + (lane >> 3), pc = lane & 7;
+      const int c = pc ^ (2 * (t & 3));
+      src[i] = (const char*)p.W + ((kb + t) * p.ldw + m0 + c * 8) * 2;
+      adv[i] = (size_t)64 * p.ldw * 2;
+    } else {
+      const int t = (b - 8) * 4 + (lane >> 4), pc = lane & 15;
+      const int c = pc ^ (4 * (t & 3));
+      src[i] = (const char*)p.R + ((kb + t) * p.ldr + c * 8) * 2;
+      adv[i] = (size_t)64 * p.ldr * 2;
+    }
+  }
+  auto issue = [&](int kt, int stage) {
+#pragma unroll
+    for (int i = 0; i < LPW; ++i)
+      __builtin_amdgcn_global_load_lds(src[i] + (size_t)kt * adv[i], PQ_LDS_PTR(smem + stage * STAGE + (wv * LPW + i) * 1024), 16, 0, 0);
+  };
+
+  // transposing reads: per lane the address of four consecutive columns in token 8 (l >> 5) + ((l & 15) >> 2) of a
+  // 16-token sub-step (+ 4 tokens for the second half of the operand)
+  const int h = lane >> 5, q = (lane & 15) >> 2;
+  const int tl = 8 * h + q, cl = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  uint32_t adW, adR[2];
+  {
+    const int col = wr0 + cl;
+    adW = lds0 + tl * 128 + ((((col >> 3) ^ (2 * q)) & 7) << 4) + (col & 7) * 2;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int cr = wc0 + 32 * j + cl;
+      adR[j] = lds0 + 8 * 1024 + tl * 256 + (((cr >> 3) ^ (4 * q)) << 4) + (cr & 7) * 2;
+    }
+  }
+  f32x16_t acc[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+
+#pragma unroll
+  for (int st = 0; st < NST - 1; ++st) issue(min(st, nkt - 1), st);
+  int st = 0;
+  for (int kt = 0; kt < nkt; ++kt) {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NST - 2) * LPW) : "memory");
+    asm volatile("s_barrier" ::: "memory");
+    issue(min(kt + NST - 1, nkt - 1), st == 0 ? NST - 1 : st - 1);
+    const uint32_t so = (uint32_t)(st * STAGE);
+    const uint32_t pw = adW + so, pr0 = adR[0] + so, pr1 = adR[1] + so;
+    pq_i32x2 hw[2][2], hr[2][4];                      // two sub-steps in flight: [parity][...]
+#define PQ_SKT_READ(ks)                                                     \
+  do {                                                                      \
+    PQ_DS_READ_TR(hw[(ks) & 1][0], pw, (ks) * 2048);                         \
+    PQ_DS_READ_TR(hw[(ks) & 1][1], pw, (ks) * 2048 + 512);                   \
+    PQ_DS_READ_TR(hr[(ks) & 1][0], pr0, (ks) * 4096);                        \
+    PQ_DS_READ_TR(hr[(ks) & 1][1], pr0, (ks) * 4096 + 1024);                 \
+    PQ_DS_READ_TR(hr[(ks) & 1][2], pr1, (ks) * 4096);                        \
+    PQ_DS_READ_TR(hr[(ks) & 1][3], pr1, (ks) * 4096 + 1024);                 \
+  } while (0)
+#define PQ_SKT_MFMA(ks, NOUT)                                                                                    \
+  do {                                                                                                           \
+    asm volatile("s_waitcnt lgkmcnt(%6)"                                                                         \
+                 : "+v"(hw[(ks) & 1][0]), "+v"(hw[(ks) & 1][1]), "+v"(hr[(ks) & 1][0]), "+v"(hr[(ks) & 1][1]),   \
+                   "+v"(hr[(ks) & 1][2]), "+v"(hr[(ks) & 1][3])                                                  \
+                 : "n"(NOUT));                                                                                   \
+    const i32x4_t fw = {hw[(ks) & 1][0][0], hw[(ks) & 1][0][1], hw[(ks) & 1][1][0], hw[(ks) & 1][1][1]};         \
+    const i32x4_t f0 = {hr[(ks) & 1][0][0], hr[(ks) & 1][0][1], hr[(ks) & 1][1][0], hr[(ks) & 1][1][1]};         \
+    const i32x4_t f1 = {hr[(ks) & 1][2][0], hr[(ks) & 1][2][1], hr[(ks) & 1][3][0], hr[(ks) & 1][3][1]};         \
+    PQ_MFMA_BF16(acc[0], fw, f0);                                                                                \
+    PQ_MFMA_BF16(acc[1], fw, f1);                                                                                \
+  } while (0)
+    PQ_SKT_READ(0);
+    PQ_SKT_READ(1);
+    PQ_SKT_MFMA(0, 6);
+    PQ_SKT_READ(2);
+    PQ_SKT_MFMA(1, 6);
+    PQ_SKT_READ(3);
+    PQ_SKT_MFMA(2, 6);
+    PQ_SKT_MFMA(3, 0);
+#undef PQ_SKT_READ
+#undef PQ_SKT_MFMA
+    st = st == NST - 1 ? 0 : st + 1;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+  // lane l holds row l & 31 (a column of the wide operand), register v column 8 (v >> 2) + 4 (l >> 5) + (v & 3)
+  const int m = m0 + wr0 + (lane & 31);
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int n = wc0 + j * 32 + 8 * g + 4 * h;
+      if (p.trans) {                                  // uniform
+#pragma unroll
+        for (int e = 0; e < 4; ++e) p.slab[((size_t)split * SK_BN + n + e) * p.M + m] = acc[j][4 * g + e];
+      } else {
+        *reinterpret_cast<float4*>(p.slab + ((size_t)split * p.M + m) * SK_BN + n) =
+            make_float4(acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]);
+      }
+    }
+#endif
+}
+
 // Shapes, alignments and epilogues the kernel above takes: 128 columns, whole 64-element steps, a plain bf16 store,
 // optionally with the dot product against a bf16 matrix of the output's shape.
 bool pq_skinny_applies(int M, int N, int K, const pq_operand& A, const pq_operand& B, const pq_epilogue& e) {
@@ -1472,6 +1612,39 @@ int pq_launch_gemm_pair_ks16(int K, int M0, int N0, const pq_operand& A0, const 
   pq_epilogue e1 = e0;
   e1.C = C1; e1.ldc = ldc1; e1.scale = scale1;
   const pq_gemm_plan p0 = pq_plan_gemm(0, M0, N0, K), p1 = pq_plan_gemm(0, M1, N1, K);
+  {
+    // rank 128 over many tokens: the streaming pair kernel (problem 1 runs transposed).  Four token ranges when that
+    // already gives a workgroup per CU (fewer slabs to write and add), up to sixteen for small matrices, never
+    // shorter than 256 tokens
+    auto al = [](const pq_operand& o) { return o.kind == PQ_SRC_KS16 && !o.kdiv && (o.ld * 2) % 16 == 0 && ((uintptr_t)o.p % 16) == 0; };
+    int splits = 4;
+    while (splits < 16 && (M0 / 64 + N1 / 64) * splits < 256 && K % (splits * 2 * 64) == 0 && K / (splits * 2) >= 256) splits *= 2;
+    const size_t need0 = (size_t)splits * M0 * N0 * sizeof(float), need1 = (size_t)splits * M1 * N1 * sizeof(float);
+    const bool tn = N0 == SK_BN && M1 == SK_BN && M0 >= 64 && N1 >= 64 && M0 % 64 == 0 && N1 % 64 == 0 && K >= 2048 &&
+                    K % (splits * 64) == 0 && al(A0) && al(B0) && al(A1) && al(B1) && A0.ld >= M0 && B0.ld >= N0 && A1.ld >= M1 &&
+                    B1.ld >= N1 && splitk_ws0 && splitk_ws1 && p0.ws_bytes >= need0 && p1.ws_bytes >= need1 &&
+                    ((uintptr_t)splitk_ws0 % 16) == 0 && ((uintptr_t)splitk_ws1 % 16) == 0;
+    if (tn) {
+      skt_problem q0{(const uint16_t*)A0.p, A0.ld, (const uint16_t*)B0.p, B0.ld, M0, 0, (float*)splitk_ws0};
+      skt_problem q1{(const uint16_t*)B1.p, B1.ld, (const uint16_t*)A1.p, A1.ld, N1, 1, (float*)splitk_ws1};
+      {
+        pq_prof_scope prof(prof_label0, s);
+        const dim3 grid((M0 > N1 ? M0 : N1) / 64, splits, 2);
+        skinny_tn_pair_kernel<<<grid, 256, 0, s>>>(q0, q1, K / splits);
+        PQ_CHECK_LAUNCH("skinny_tn_pair_kernel");
+      }
+      pq_prof_scope prof(PQP_SPLITK_REDUCE, s);
+      pq_reduce_job none;
+      memset(&none, 0, sizeof(none));
+      const int rb0 = (int)(((size_t)M0 * (N0 / 8) + 255) / 256), rb1 = (int)(((size_t)M1 * (N1 / 8) + 255) / 256);
+      splitk_reduce_pair_kernel<<<rb0 + rb1 + (jobs ? 2 : 0), 256, 0, s>>>(splits, rb0, rb1, M0, N0, (const float*)splitk_ws0, e0, M1, N1,
+                                                                          (const float*)splitk_ws1, e1, jobs ? jobs[0] : none,
+                                                                          jobs ? jobs[1] : none);
+      PQ_CHECK_LAUNCH("splitk_reduce_pair_kernel");
+      if (jobs && jobs_done) *jobs_done = true;
+      return PQ_OK;
+    }
+  }
   const int nbm0 = (M0 + 127) / 128, nbn0 = (N0 + 127) / 128, nbm1 = (M1 + 127) / 128, nbn1 = (N1 + 127) / 128;
   const bool same = M0 > 0 && N0 > 0 && M1 > 0 && N1 > 0 && K > 0 && p0.bm == 128 && p1.bm == 128 && p0.splits == p1.splits &&
                     p0.kchunk == p1.kchunk && nbm0 * nbn0 == nbm1 * nbn1 && A0.kind == PQ_SRC_KS16 && B0.kind == PQ_SRC_KS16 &&

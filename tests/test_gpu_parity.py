@@ -185,7 +185,9 @@ def test_linear_config1_fp32():
                                          # fused GEMMs with a second contraction of one and of two whole steps
                                          (600, 1152, 1408, 64, True), (300, 640, 384, 128, True),
                                          # many tokens at rank 128: the streaming rank-r kernel computes H (ragged last block)
-                                         (1100, 640, 384, 128, True), (1024, 64, 256, 128, True)])
+                                         (1100, 640, 384, 128, True), (1024, 64, 256, 128, True),
+                                         # 2048 tokens or more in whole 512-token ranges: dB and dA take the streaming pair kernel
+                                         (2048, 192, 320, 128, True), (2560, 64, 64, 128, True)])
 def test_linear_ragged_multi_tile(T, K, N, r, bf16):
     say(f"linear ragged T={T} K={K} N={N} r={r} bf16={bf16}")
     c = wl.linear_case(500 + T + r, T, K, N, hp_rank=r, bf16=bf16, outlier_frac=0.02, outlier_scale=10.0)
