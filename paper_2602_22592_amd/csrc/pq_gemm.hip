@@ -1209,14 +1209,19 @@ constexpr int SK_BN = 128;
 // BM = 64: wavefront w computes rows 32 (w >> 1) and columns 64 (w & 1), six stages of 24 KB.  BM = 32: one row block,
 // wavefront w computes columns 32 w, seven stages of 20 KB (twice the workgroups for the same rows: B is streamed by
 // twice as many CUs, A by each of them half as long).
-template <bool BTR, int BM>
-__global__ __launch_bounds__(256) void skinny_gemm_kernel(const uint16_t* __restrict__ A, long lda,
-                                                         const uint16_t* __restrict__ B, long ldb, int M, int K,
+// I8: int8 operands (128 contraction elements per 128-byte step, exact int32 accumulation) and the de-quantising
+// epilogue of the INT8 high-precision branch: value = ((scale / row_div[m]) * acc) / col_div[n], each step rounded to fp32.
+template <bool BTR, int BM, bool I8>
+__global__ __launch_bounds__(256) void skinny_gemm_kernel(const void* __restrict__ A, long lda,
+                                                         const void* __restrict__ B, long ldb, int M, int K,
                                                          uint16_t* __restrict__ C, long ldc, float scale,
                                                          const uint16_t* __restrict__ comp, long ld_comp,
-                                                         double* __restrict__ partials) {
+                                                         double* __restrict__ partials, const float* __restrict__ row_div,
+                                                         const float* __restrict__ col_div) {
 #if defined(__HIP_DEVICE_COMPILE__)
   static_assert(BM == 64 || BM == 32, "one or two 32-row blocks");
+  static_assert(!(I8 && BTR), "int8 operands are contraction-contiguous");
+  constexpr int ES = I8 ? 1 : 2;                      // bytes per operand element
   constexpr int NA = BM / 8;                          // 1 KB load blocks of A per stage; B has 16
   constexpr int LPW = (NA + 16) / 4;                  // load blocks per wavefront and stage
   constexpr int NST = BM == 64 ? 6 : 7;               // ring stages
@@ -1230,7 +1235,7 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const uint16_t* __rest
   const int m0 = blockIdx.x * BM;
   const int wr0 = BM == 64 ? (wv >> 1) * 32 : 0;      // the wavefront's rows and columns inside the tile
   const int wc0 = BM == 64 ? (wv & 1) * 64 : wv * 32;
-  const int nkt = K >> 6;
+  const int nkt = (K * ES) >> 7;
   const uint32_t lds0 = (uint32_t)(size_t)smem;
 
   // direct loads: lane l of a load lands at byte 16 l of its 1 KB block.  A, and a contraction-contiguous B: a block is
@@ -1249,8 +1254,8 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const uint16_t* __rest
     } else {
       const int r = (b < NA ? b : b - NA) * 8 + (lane >> 3), pc = lane & 7;
       const int c = pc ^ ((r ^ (r >> 3)) & 7);
-      src[i] = b < NA ? (const char*)A + ((size_t)min(m0 + r, M - 1) * lda) * 2 + c * 16   // rows past the end: the last row
-                      : (const char*)B + ((size_t)r * ldb) * 2 + c * 16;
+      src[i] = b < NA ? (const char*)A + ((size_t)min(m0 + r, M - 1) * lda) * ES + c * 16   // rows past the end: the last row
+                      : (const char*)B + ((size_t)r * ldb) * ES + c * 16;
       adv[i] = 128;
     }
   }
@@ -1285,11 +1290,12 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const uint16_t* __rest
       }
     }
   }
-  f32x16_t acc[NJ];
+  using acc_t = typename std::conditional<I8, i32x16_t, f32x16_t>::type;
+  acc_t acc[NJ];
 #pragma unroll
   for (int j = 0; j < NJ; ++j)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+    for (int v = 0; v < 16; ++v) acc[j][v] = 0;
 
 #pragma unroll
   for (int st = 0; st < NST - 1; ++st) issue(min(st, nkt - 1), st);   // steps past the end: the last one again, never read
@@ -1357,7 +1363,10 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const uint16_t* __rest
       asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(fa[ks]), "+v"(fb[0][ks]), "+v"(fb[NJ - 1][ks]) : "n"((3 - (ks)) * RPS)); \
     else                                                                                                           \
       asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(fa[ks]), "+v"(fb[0][ks]) : "n"((3 - (ks)) * RPS));              \
-    _Pragma("unroll") for (int j = 0; j < NJ; ++j) PQ_MFMA_BF16(acc[j], fa[ks], fb[j][ks]);                        \
+    _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                                               \
+      if constexpr (I8) PQ_MFMA_I8(acc[j], fa[ks], fb[j][ks]);                                                     \
+      else PQ_MFMA_BF16(acc[j], fa[ks], fb[j][ks]);                                                                \
+    }                                                                                                              \
   } while (0)
       PQ_SK_MFMA(0);
       PQ_SK_MFMA(1);
@@ -1373,11 +1382,23 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const uint16_t* __rest
   const int m = m0 + wr0 + (lane & 31);
   double psum = 0.0;
   if (m < M) {
+    const float sc = row_div ? scale / row_div[m] : scale;
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int n = wc0 + j * 32 + 8 * g + 4 * h;
+        if constexpr (I8) {
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = __fmul_rn(sc, (float)acc[j][4 * g + e]);
+          if (col_div) {                             // uniform
+            const float4 cd = *reinterpret_cast<const float4*>(col_div + n);
+            v[0] = v[0] / cd.x; v[1] = v[1] / cd.y; v[2] = v[2] / cd.z; v[3] = v[3] / cd.w;
+          }
+          *reinterpret_cast<uint2*>(C + (size_t)m * ldc + n) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+          continue;
+        }
         if (comp) {                                  // uniform
           const uint2 u = *reinterpret_cast<const uint2*>(comp + (size_t)m * ld_comp + n);
           psum += (double)__uint_as_float(u.x << 16) * (double)acc[j][4 * g];
@@ -1385,8 +1406,8 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const uint16_t* __rest
           psum += (double)__uint_as_float(u.y << 16) * (double)acc[j][4 * g + 2];
           psum += (double)__uint_as_float(u.y & 0xFFFF0000u) * (double)acc[j][4 * g + 3];
         }
-        const float v0 = __fmul_rn(scale, acc[j][4 * g]), v1 = __fmul_rn(scale, acc[j][4 * g + 1]);
-        const float v2 = __fmul_rn(scale, acc[j][4 * g + 2]), v3 = __fmul_rn(scale, acc[j][4 * g + 3]);
+        const float v0 = __fmul_rn(sc, (float)acc[j][4 * g]), v1 = __fmul_rn(sc, (float)acc[j][4 * g + 1]);
+        const float v2 = __fmul_rn(sc, (float)acc[j][4 * g + 2]), v3 = __fmul_rn(sc, (float)acc[j][4 * g + 3]);
         *reinterpret_cast<uint2*>(C + (size_t)m * ldc + n) = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
       }
   }
@@ -1541,10 +1562,18 @@ __global__ __launch_bounds__(256) void skinny_tn_pair_kernel(skt_problem p0, skt
 // optionally with the dot product against a bf16 matrix of the output's shape.
 bool pq_skinny_applies(int M, int N, int K, const pq_operand& A, const pq_operand& B, const pq_epilogue& e) {
   const bool btr = B.kind == PQ_SRC_KS16;
-  return M >= 1024 && N == SK_BN && K >= 64 && K % 64 == 0 && A.kind == PQ_SRC_KC16 && (B.kind == PQ_SRC_KC16 || btr) && !A.kdiv &&
-         !B.kdiv && A.ld >= K && B.ld >= (btr ? N : K) && (A.ld * 2) % 16 == 0 && (B.ld * 2) % 16 == 0 && ((uintptr_t)A.p % 16) == 0 &&
-         ((uintptr_t)B.p % 16) == 0 && e.out_kind == PQ_OUT_BF16 && e.ldc >= N && (e.ldc * 2) % 8 == 0 && ((uintptr_t)e.C % 8) == 0 &&
-         !e.row_div && !e.col_div && !e.sign_bytes && !e.maskW && !e.accumulate && !e.dev_scale &&
+  const bool i8 = A.kind == PQ_SRC_KC8 && B.kind == PQ_SRC_KC8;
+  const bool b16 = A.kind == PQ_SRC_KC16 && (B.kind == PQ_SRC_KC16 || btr);
+  const long es = i8 ? 1 : 2;
+  if (!(i8 || b16)) return false;
+  if (!(M >= 1024 && N == SK_BN && K * es >= 128 && (K * es) % 128 == 0 && !A.kdiv && !B.kdiv && A.ld >= K && B.ld >= (btr ? N : K) &&
+        (A.ld * es) % 16 == 0 && (B.ld * es) % 16 == 0 && ((uintptr_t)A.p % 16) == 0 && ((uintptr_t)B.p % 16) == 0))
+    return false;
+  if (!(e.out_kind == PQ_OUT_BF16 && e.ldc >= N && (e.ldc * 2) % 8 == 0 && ((uintptr_t)e.C % 8) == 0 && !e.sign_bytes && !e.maskW &&
+        !e.accumulate && !e.dev_scale))
+    return false;
+  if (i8) return !e.dot_comp && !e.partials && (!e.col_div || ((uintptr_t)e.col_div % 16) == 0);   // de-quantising epilogue
+  return !e.row_div && !e.col_div &&
          (!e.dot_comp || (e.comp_kind == PQ_OUT_BF16 && e.partials && e.ld_comp >= N && (e.ld_comp * 2) % 8 == 0 &&
                           ((uintptr_t)e.dot_comp % 8) == 0)) &&
          (e.dot_comp || !e.partials);
@@ -1558,14 +1587,15 @@ int pq_skinny_blocks(int M) { return (M + PQ_SK_ROWS - 1) / PQ_SK_ROWS; }
 int pq_launch_skinny(int M, int K, const pq_operand& A, const pq_operand& B, const pq_epilogue& e, hipStream_t s, int prof_label) {
   pq_prof_scope prof(prof_label, s);
   const dim3 grid(pq_skinny_blocks(M)), block(256);
-  if (B.kind == PQ_SRC_KS16)
-    skinny_gemm_kernel<true, PQ_SK_ROWS><<<grid, block, 0, s>>>((const uint16_t*)A.p, A.ld, (const uint16_t*)B.p, B.ld, M, K,
-                                                                (uint16_t*)e.C, e.ldc, e.scale, (const uint16_t*)e.dot_comp, e.ld_comp,
-                                                                e.partials);
+  if (A.kind == PQ_SRC_KC8)
+    skinny_gemm_kernel<false, PQ_SK_ROWS, true><<<grid, block, 0, s>>>(A.p, A.ld, B.p, B.ld, M, K, (uint16_t*)e.C, e.ldc, e.scale, nullptr, 0,
+                                                                       nullptr, e.row_div, e.col_div);
+  else if (B.kind == PQ_SRC_KS16)
+    skinny_gemm_kernel<true, PQ_SK_ROWS, false><<<grid, block, 0, s>>>(A.p, A.ld, B.p, B.ld, M, K, (uint16_t*)e.C, e.ldc, e.scale,
+                                                                       (const uint16_t*)e.dot_comp, e.ld_comp, e.partials, nullptr, nullptr);
   else
-    skinny_gemm_kernel<false, PQ_SK_ROWS><<<grid, block, 0, s>>>((const uint16_t*)A.p, A.ld, (const uint16_t*)B.p, B.ld, M, K,
-                                                                 (uint16_t*)e.C, e.ldc, e.scale, (const uint16_t*)e.dot_comp, e.ld_comp,
-                                                                 e.partials);
+    skinny_gemm_kernel<false, PQ_SK_ROWS, false><<<grid, block, 0, s>>>(A.p, A.ld, B.p, B.ld, M, K, (uint16_t*)e.C, e.ldc, e.scale,
+                                                                        (const uint16_t*)e.dot_comp, e.ld_comp, e.partials, nullptr, nullptr);
   PQ_CHECK_LAUNCH("skinny_gemm_kernel");
   return PQ_OK;
 }

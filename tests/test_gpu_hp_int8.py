@@ -57,7 +57,8 @@ def _run_fwd(X, A, B, alpha, Y0=None):
 
 
 SHAPES = [(64, 256, 256, 32), (300, 2048, 1024, 64), (37, 512, 5504, 96), (513, 4096, 4096, 128), (1, 64, 32, 32),
-          (0, 64, 64, 32), (260, 1024, 288, 160)]
+          (0, 64, 64, 32), (260, 1024, 288, 160),
+          (1100, 512, 384, 128), (2048, 2048, 256, 128)]   # rank 128, 1024 tokens or more: the streaming rank-r kernel computes H
 
 
 @pytest.mark.parametrize("T,K,N,r", SHAPES)
