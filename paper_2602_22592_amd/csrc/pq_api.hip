@@ -614,7 +614,7 @@ extern "C" int pq_linear_norm_bwd(const pq_linear_desc* d, const void* dY, const
 // workspace: [dH T*r bf16][split-contraction slabs]
 // ---------------------------------------------------------------------------------------------
 namespace {
-struct hp8_layout { size_t Aq, gA, At, Bq, gB, Bt, H, Hq, gH, Ht, ctx_total, dH, splitk, ws_total; };
+struct hp8_layout { size_t Aq, gA, At, Bq, gB, Bt, H, Hq, gH, Ht, ctx_total, dH, splitk, splitk2, ws_total; };
 hp8_layout make_hp8_layout(int T, int K, int N, int r) {
   hp8_layout L;
   const size_t t = T, k = K, n = N, rr = r;
@@ -637,6 +637,7 @@ hp8_layout make_hp8_layout(int T, int K, int N, int r) {
     if (b > sk) sk = b;
   }
   L.splitk = w.take(sk);
+  L.splitk2 = w.take((r > 0 && K > 0) ? pq_plan_gemm(0, r, K, T).ws_bytes : 0);   // dA's slabs when dB and dA share a launch
   L.ws_total = w.off;
   return L;
 }
@@ -718,19 +719,11 @@ extern "C" int pq_hp_int8_bwd(const void* dY, const void* Xt, int32_t dtype, int
     e.C = dH; e.ldc = r; e.out_kind = PQ_OUT_BF16; e.scale = alpha;
     if (int err = pq_launch_gemm(0, T, r, N, a, b, e, s, PQP_GEMM_DH, sk)) return err;
   }
-  {  // dB = alpha * dY^T H~
-    pq_operand a{dY, N, PQ_SRC_KS16, nullptr};
-    pq_operand b{cx + L.Ht, r, PQ_SRC_KS16, nullptr};
-    pq_epilogue e = epi_zero();
-    e.C = dB; e.ldc = r; e.out_kind = PQ_OUT_F32; e.scale = alpha;
-    if (int err = pq_launch_gemm(0, N, r, T, a, b, e, s, PQP_GEMM_DB, sk)) return err;
-  }
-  {  // dA = dH^T X~   (dH already carries alpha)
-    pq_operand a{dH, r, PQ_SRC_KS16, nullptr};
-    pq_operand b{Xt, K, PQ_SRC_KS16, nullptr};
-    pq_epilogue e = epi_zero();
-    e.C = dA; e.ldc = K; e.out_kind = PQ_OUT_F32;
-    if (int err = pq_launch_gemm(0, r, K, T, a, b, e, s, PQP_GEMM_DA, sk)) return err;
+  {  // dB = alpha * dY^T H~ and dA = dH^T X~ (dH already carries alpha): one launch when their shapes allow it
+    pq_operand a0{dY, N, PQ_SRC_KS16, nullptr}, b0{cx + L.Ht, r, PQ_SRC_KS16, nullptr};
+    pq_operand a1{dH, r, PQ_SRC_KS16, nullptr}, b1{Xt, K, PQ_SRC_KS16, nullptr};
+    if (int err = pq_launch_gemm_pair_ks16(T, N, r, a0, b0, dB, r, alpha, r, K, a1, b1, dA, K, 1.0f, s, PQP_GEMM_DB, PQP_GEMM_DA, sk,
+                                           ws + L.splitk2, nullptr, nullptr)) return err;
   }
   if (T > 0) {  // dX (+)= dH A~
     pq_operand a{dH, r, PQ_SRC_KC16, nullptr};

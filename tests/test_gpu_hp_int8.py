@@ -96,7 +96,8 @@ def test_hp_int8_fwd_alpha_accumulate():
 
 
 @pytest.mark.parametrize("T,K,N,r", [(64, 256, 256, 32), (300, 2048, 1024, 64), (37, 512, 5504, 96),
-                                     (513, 4096, 4096, 128), (0, 64, 64, 32), (1100, 512, 384, 128)])
+                                     (513, 4096, 4096, 128), (0, 64, 64, 32), (1100, 512, 384, 128),
+                                     (2048, 192, 320, 128)])   # dB and dA in the streaming pair kernel
 def test_hp_int8_bwd_parity(T, K, N, r):
     say(f"hp_int8_bwd T={T} K={K} N={N} r={r}")
     X, A, B, dY = _case(1900 + T + r, T, K, N, r)
