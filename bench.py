@@ -34,7 +34,7 @@ PEAK_I8 = 5.0e15        # dense MFMA int8, OP/s
 
 # Measured HBM bytes per launch at the default workload (profiles/linear_fwd_bwd_config2_hbm_traffic.md):
 # (FETCH_SIZE KiB x 1.986 + WRITE_SIZE KiB x 1.000) x 1024
-TRAFFIC_BYTES = {"gemm_dW": 169352422, "gemm_dX": 78257595, "gemm_onebit_fwd": 63753159}
+TRAFFIC_BYTES = {"gemm_dW": 169672441, "gemm_dX": 78266530, "gemm_onebit_fwd": 63732934}
 
 
 def gemm_flops(T, K, N, r):
