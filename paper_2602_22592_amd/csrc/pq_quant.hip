@@ -545,6 +545,21 @@ __global__ __launch_bounds__(256) void pack_sign_kernel(const T* __restrict__ W,
   __shared__ double red[4];
   __shared__ float s_mu;
   __shared__ uint8_t tileb[32][64];
+  // the weights do not depend on the statistics: their eight chunks are requested first, so that their latency and
+  // the reduction of the partial sums overlap instead of standing in a row
+  constexpr int NU = sizeof(T) == 2 ? 1 : 2;          // 16-byte loads per 8 weights
+  const int n0 = blockIdx.y * 32, k0 = blockIdx.x * 512;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int k = k0 + lane * 8;
+  uint4 wv[8][NU];
+#pragma unroll
+  for (int rr = 0; rr < 8; ++rr) {
+    const int row = n0 + w * 8 + rr;
+    const bool in = row < N && k < K;
+    const uint4* src = reinterpret_cast<const uint4*>(W + (in ? (size_t)row * K + k : (size_t)0));   // element (0, 0) always exists
+#pragma unroll
+    for (int u = 0; u < NU; ++u) wv[rr][u] = src[u];
+  }
   double s = 0.0, a = 0.0;
   for (int i = threadIdx.x; i < G; i += 256) {
     s += partials[2 * i];
@@ -563,16 +578,13 @@ __global__ __launch_bounds__(256) void pack_sign_kernel(const T* __restrict__ W,
   }
   __syncthreads();
   const float mu = s_mu;
-  const int n0 = blockIdx.y * 32, k0 = blockIdx.x * 512;
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int k = k0 + lane * 8;
   const size_t kb = (size_t)K / 8;
 #pragma unroll
   for (int rr = 0; rr < 8; ++rr) {
     const int rl = w * 8 + rr, row = n0 + rl;
     uint32_t b = 0;
     if (row < N && k < K) {
-      b = sign_byte<T>(W + (size_t)row * K + k, mu);
+      b = sign_byte<T>(reinterpret_cast<const T*>(wv[rr]), mu);
       Pbytes[(size_t)row * kb + (k >> 3)] = (uint8_t)b;
     }
     tileb[rl][lane] = (uint8_t)b;
