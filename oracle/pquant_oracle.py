@@ -274,7 +274,8 @@ def ffn_fwd(X, W_up, W_gate, W_down, Up, Gate, Down, Wr, alpha, beta, top_k=1, b
     FFN^INT1: three pure 1-bit linears around a gated unit, hidden state re-quantised before the
     down projection:  U = L_up(Q(X)), G = L_gate(Q(X)), Hd = silu(G) * U, Y1 = L_down(Q(Hd)).
     U and G are rounded to the storage format (they are saved for the backward pass); Hd is formed
-    from the rounded values and quantised from fp32.  Experts are gated FFNs of hidden width r.
+    from the rounded values and quantised from fp32 (a reading: the paper states no storage precision; FP16
+    latent activations are what its mixed-precision training keeps, App. B).  Experts are gated FFNs of hidden width r.
     """
     X32 = np.asarray(X, dtype=F32)
     X64 = X32.astype(F64)
@@ -456,8 +457,11 @@ def rmsnorm_bwd(dXn, X, g, rstd):
 # activations"), for the two-factor branch B (A x) of a single linear
 # ----------------------------------------------------------------------------------------------
 def _dequant_scale(acc, g_row, g_col):
-    """fl32(fl32(fl32(1 / g_row) * fl32(acc)) / g_col): the order in which the library removes the two scales
-    from an integer accumulator (row scale as one reciprocal per row, column scale by division)."""
+    """De-quantisation of an integer accumulator whose two factors each carry a per-row AbsMax scale (Sec. 3.1:
+    the product of quantised operands is divided by their scales; Sec. 3.2 applies the activation quantiser to
+    the 8-bit weights as well).  The paper does not fix the order of the two fp32 operations; the reading taken is
+    fl32(fl32(fl32(1 / g_row) * fl32(acc)) / g_col): the token (row) scale comes off first as a reciprocal formed
+    once per row, the weight-row (column) scale second by division."""
     s = (F32(1.0) / g_row.astype(F32)).astype(F32)
     v = (s[:, None] * acc.astype(F32)).astype(F32)
     return (v / g_col.astype(F32)[None, :]).astype(F32)

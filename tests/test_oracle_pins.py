@@ -465,6 +465,32 @@ def test_stack_averages_q_k_v():
     np.testing.assert_array_equal(np.asarray(saved[0]["h1"], np.float32), h1)
 
 
+def test_stack_backward_carries_the_one_third_of_the_q_k_v_average():
+    """With W_q = W_k = W_v, the FFN switched off (W_down = 0 gives lambda = 0, alpha = 0) and a non-zero W_o, the
+    backward of one layer is d = dY + 3 * dX_q(dX_o(dY) / 3) = dY + dX_q(dX_o(dY)) by the linearity of the STE
+    backward, built here by hand from the pinned linear_bwd; the weight gradient of W_q sees a third of dX_o(dY).
+    A dropped or doubled 1/3 changes both."""
+    c = _tiny_stack(8, n_layers=1)
+    w = c["layers"][0]
+    w["Wk"] = w["Wq"].copy(); w["Wv"] = w["Wq"].copy()
+    w["W_down"] = np.zeros_like(w["W_down"]); w["alpha"] = 0.0
+    h0 = wl.bf16_round(c["table"][c["ids"]])
+    _, saved = po.stack_fwd(h0, c["layers"])
+    dY = c["dY"].astype(np.float64)
+    d0, grads = po.stack_bwd(dY, c["layers"], saved)
+    fq = po.linear_fwd(h0, w["Wq"], 0.0, 1.0)
+    m = wl.bf16_round(fq["Y"].astype(np.float32))
+    fo = po.linear_fwd(m, w["Wo"], 0.0, 1.0)
+    go = po.linear_bwd(dY, m, w["Wo"], 0.0, 1.0, fo)
+    assert np.abs(go["dX"]).max() > 0
+    gq = po.linear_bwd(go["dX"], h0, w["Wq"], 0.0, 1.0, fq)
+    ref = dY + gq["dX"]
+    assert np.abs(np.asarray(d0, np.float64) - ref).max() <= 1e-12 * np.abs(ref).max()
+    for n in ("Wq", "Wk", "Wv"):
+        assert np.abs(grads[0][n] - gq["dW"] / 3.0).max() <= 1e-12 * np.abs(gq["dW"]).max()
+    np.testing.assert_array_equal(grads[0]["Wo"], go["dW"])
+
+
 def test_stack_backward_is_linear_in_the_upstream_gradient():
     """The STE backward is a linear map of dY.  Scaling by 2 commutes with every rounding (exact), a sum of two
     upstream gradients gives the sum of the results up to the bf16 roundings of the stored gradients."""
