@@ -54,11 +54,15 @@ def binarise(W, mu):
 
 def pack_sign(S):
     """Pack +/-1 into uint32 words along d_in, bit j of word w <-> column 32 w + j, bit 1 <-> +1
-    (App. A: packed 1-bit storage; the paper packs 8 per byte, which is the same byte stream)."""
+    (App. A: packed 1-bit storage; the paper packs 8 per byte, which is the same byte stream).
+    A row whose length is not a multiple of 32 (Table 1: D_ff - r = 5076 for the 1.3B model) is padded to whole
+    words with +1 bits (a reading: the paper does not say how partial words are filled): a padded column only
+    ever meets an activation code of zero, so the pad value cannot reach an accumulator."""
     S = np.asarray(S)
     m, n = S.shape
-    assert n % 32 == 0
-    bits = (S > 0).reshape(m, n // 32, 32).astype(np.uint64)
+    npad = (-n) % 32
+    bits = np.concatenate([(S > 0), np.ones((m, npad), bool)], axis=1) if npad else (S > 0)
+    bits = bits.reshape(m, (n + npad) // 32, 32).astype(np.uint64)
     place = np.uint64(1) << np.arange(32, dtype=np.uint64)
     return (bits * place).sum(axis=2).astype(np.uint32)
 

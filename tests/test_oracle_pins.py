@@ -146,6 +146,42 @@ def test_onebit_acc_bruteforce_and_lut_route():
             assert int(acc[t, i]) == _lut_dot(q[t], P[i])
 
 
+def test_pack_sign_pads_partial_words_with_plus_one():
+    """Row lengths that are not multiples of 32 (Table 1: 5076 = 158 words + 20 bits): the last word is filled with
+    +1 bits.  Pins: brute force with Python integers, np.packbits on the padded signs, the round trip, and the fact
+    the padding exists for -- codes extended by zeros against the padded signs give the unpadded accumulator."""
+    rng = np.random.default_rng(44)
+    for m, n in ((3, 44), (5, 5076), (2, 20), (4, 96)):
+        S = np.where(rng.random((m, n)) < 0.5, 1, -1).astype(np.int8)
+        P = po.pack_sign(S)
+        nw = (n + 31) // 32
+        assert P.shape == (m, nw) and P.dtype == np.uint32
+        for i in range(m):
+            for w in range(nw):
+                word = 0
+                for j in range(32):
+                    k = 32 * w + j
+                    if k >= n or S[i, k] > 0:
+                        word |= 1 << j
+                assert int(P[i, w]) == word
+        padded = np.concatenate([S > 0, np.ones((m, 32 * nw - n), bool)], axis=1)
+        assert np.array_equal(P.view(np.uint8), np.packbits(padded, axis=1, bitorder="little"))
+        assert np.array_equal(po.unpack_sign(P, n), S)
+        q = rng.integers(-128, 128, size=(6, n)).astype(np.int8)
+        qp = np.concatenate([q, np.zeros((6, 32 * nw - n), np.int8)], axis=1)
+        assert np.array_equal(po.onebit_acc(qp, po.unpack_sign(P, 32 * nw)), po.onebit_acc(q, S))
+
+
+def test_ffn_paper_width_is_not_a_multiple_of_32():
+    """The oracle's FFN takes the paper's own 1-bit width (Table 1: D_ff - r = 5076 at D_model = 2048 for 1.3B; here the
+    same residues at a small size): no step of it needs whole words, and the hidden state has exactly F columns."""
+    c = wl.ffn_case(46, 9, 32, 52, 2, 8)              # 52 = 32 + 20, like 5076 = 158 * 32 + 20
+    f = po.ffn_fwd(c["X"], c["W_up"], c["W_gate"], c["W_down"], c["Up"], c["Gate"], c["Down"], c["Wr"], 2.0, 0.2)
+    assert f["Hd"].shape == (9, 52) and f["qh"].shape == (9, 52)
+    S = f["st"]["down"]["S"]
+    assert np.array_equal(f["acc_d"], po.onebit_acc(f["qh"], po.unpack_sign(po.pack_sign(S), 52)))
+
+
 def test_onebit_acc_fp32_blas_is_an_exact_second_route():
     rng = np.random.default_rng(8)
     q = rng.integers(-128, 128, size=(64, 5504)).astype(np.int8)
