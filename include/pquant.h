@@ -89,6 +89,18 @@ size_t pq_rmsnorm_bwd_workspace_bytes(int32_t T, int32_t K);
 int pq_rmsnorm_bwd(const void* dXn, const void* X, const void* gain, const float* rstd, int32_t dtype, int32_t T,
                    int32_t K, void* dX, float* dgain, void* workspace, size_t workspace_bytes, void* stream);
 
+/* pq_rmsnorm_bwd for callers that cannot allocate or bring a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments, results bit-identical to pq_rmsnorm_bwd, but
+ * the partial rows of dgain live in a device array that is part of the library image (each GPU the library runs
+ * on holds pq_rmsnorm_bwd_static_max_bytes() = 4 MiB of it until the process ends).  The call allocates nothing.
+ * Limit: ceil(T / 16) * K * 4 bytes must not exceed that size (e.g. T = 8192 at K = 2048), else
+ * PQ_ERR_WORKSPACE and nothing is launched.  Every call on a GPU uses that GPU's one array: calls that overlap
+ * on one GPU (two streams, two threads) race; calls on one stream are ordered.  Nothing needs clearing between
+ * calls: a call overwrites every partial row it later reads. */
+size_t pq_rmsnorm_bwd_static_max_bytes(void);
+int pq_rmsnorm_bwd_static(const void* dXn, const void* X, const void* gain, const float* rstd, int32_t dtype, int32_t T,
+                          int32_t K, void* dX, float* dgain, void* stream);
+
 /* Weight statistics + binariser + packer (Sec. 3.1 eqs. for W^INT1, mu, lambda; App. A packing).
  * mu and lambda are fp64 sums divided in fp64 and rounded once to fp32; bit = [W >= mu] (so W == mu
  * maps to +1).  packed [N][K/32] uint32: bit j of word w <-> column 32 w + j, 1 <-> +1 (the same byte

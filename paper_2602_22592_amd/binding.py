@@ -28,7 +28,7 @@ EXPORTS = [
     "pq_rmsnorm_quant_fwd", "pq_rmsnorm_bwd_workspace_bytes", "pq_rmsnorm_bwd",
     "pq_linear_norm_ctx_bytes", "pq_linear_norm_workspace_bytes", "pq_linear_norm_fwd", "pq_linear_norm_bwd",
     "pq_hp_int8_ctx_bytes", "pq_hp_int8_workspace_bytes", "pq_hp_int8_fwd", "pq_hp_int8_bwd", "pq_decode_gemv_int8",
-    "pq_decode_ffn_workspace_bytes", "pq_decode_ffn",
+    "pq_decode_ffn_workspace_bytes", "pq_decode_ffn", "pq_rmsnorm_bwd_static_max_bytes", "pq_rmsnorm_bwd_static",
 ]
 
 
@@ -75,7 +75,7 @@ def lib():
                      "pq_decode_workspace_bytes", "pq_pack_tiled64_bytes", "pq_ffn_ctx_bytes",
                      "pq_ffn_workspace_bytes", "pq_rmsnorm_bwd_workspace_bytes", "pq_linear_norm_ctx_bytes",
                      "pq_linear_norm_workspace_bytes", "pq_hp_int8_ctx_bytes", "pq_hp_int8_workspace_bytes",
-                     "pq_decode_ffn_workspace_bytes"):
+                     "pq_decode_ffn_workspace_bytes", "pq_rmsnorm_bwd_static_max_bytes"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -134,6 +134,16 @@ def rmsnorm_bwd_into(dXn, X, gain, rstd, dX, dgain, ws):
     T, K = X.shape
     _check(lib().pq_rmsnorm_bwd(_p(dXn), _p(X), _p(gain), _p(rstd), _dt(X), T, K, _p(dX), _p(dgain), _p(ws),
                                 C.c_size_t(ws.numel()), _stream()))
+
+
+def rmsnorm_bwd_static_into(dXn, X, gain, rstd, dX, dgain):
+    """pq_rmsnorm_bwd_static: no workspace argument, nothing allocated by the call."""
+    T, K = X.shape
+    _check(lib().pq_rmsnorm_bwd_static(_p(dXn), _p(X), _p(gain), _p(rstd), _dt(X), T, K, _p(dX), _p(dgain), _stream()))
+
+
+def rmsnorm_bwd_static_max_bytes():
+    return lib().pq_rmsnorm_bwd_static_max_bytes()
 
 
 def rmsnorm_quant_fwd(X, gain, eps, want_xn=True, want_xt=True, want_rstd=True):

@@ -223,6 +223,26 @@ extern "C" int pq_rmsnorm_bwd(const void* dXn, const void* X, const void* gain, 
   return pq_launch_rmsnorm_bwd(dXn, X, gain, rstd, dtype, T, K, dX, dgain, part, (hipStream_t)stream);
 }
 
+extern "C" size_t pq_rmsnorm_bwd_static_max_bytes(void) { return pq_static_scratch_bytes(); }
+
+extern "C" int pq_rmsnorm_bwd_static(const void* dXn, const void* X, const void* gain, const float* rstd, int32_t dtype, int32_t T,
+                                     int32_t K, void* dX, float* dgain, void* stream) {
+  if (int e = check_dtype(dtype)) return e;
+  PQ_REQUIRE(T >= 0 && K > 0, PQ_ERR_BAD_ARG, "bad size T=%d K=%d", T, K);
+  PQ_REQUIRE(K % 32 == 0, PQ_ERR_SHAPE, "K=%d must be a multiple of 32", K);
+  PQ_REQUIRE(K <= (dtype == PQ_F32 ? 2048 : 4096), PQ_ERR_SHAPE, "K=%d exceeds the row length this call keeps in registers", K);
+  PQ_REQUIRE(dgain && gain, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(T == 0 || (dXn && X && rstd && dX), PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(aligned16(dXn) && aligned16(X) && aligned16(gain) && aligned16(dX), PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
+  const size_t need = pq_rmsnorm_bwd_scratch_bytes(T, K);
+  PQ_REQUIRE(need <= pq_static_scratch_bytes(), PQ_ERR_WORKSPACE,
+             "T=%d x K=%d needs %zu bytes of partial rows, the static scratch holds %zu: use pq_rmsnorm_bwd with a workspace",
+             T, K, need, pq_static_scratch_bytes());
+  void* part = nullptr;
+  if (int e = pq_static_scratch(&part)) return e;
+  return pq_launch_rmsnorm_bwd(dXn, X, gain, rstd, dtype, T, K, dX, dgain, (float*)part, (hipStream_t)stream);
+}
+
 extern "C" size_t pq_pack_workspace_bytes(int32_t N, int32_t K) {
   (void)N; (void)K;
   return 2 * sizeof(double) * 1024;

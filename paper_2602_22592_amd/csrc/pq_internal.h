@@ -27,6 +27,10 @@ int pq_launch_rmsnorm_quant(const void* X, const void* gain, int dtype, int T, i
 size_t pq_rmsnorm_bwd_scratch_bytes(int T, int K);
 int pq_launch_rmsnorm_bwd(const void* dXn, const void* X, const void* gain, const float* rstd, int dtype, int T, int K, void* dX,
                           float* dgain, float* part, hipStream_t s);
+// The library's static device scratch (for entry points that must not allocate): its size, and its address on the
+// current device (looked up once per device).
+size_t pq_static_scratch_bytes();
+int pq_static_scratch(void** out);
 // Weight statistics, stage 1: per-block fp64 partial sums {sum W, sum |W|}.
 int pq_stats_blocks(size_t n_elems);
 // slabs != nullptr: `splits` fp32 slabs [M][N] of a deferred split contraction are summed in slab order into the bf16

@@ -1,5 +1,6 @@
 // Bandwidth-bound element kernels: AbsMax INT8 activation quantiser (Sec. 3.1), weight statistics
 // mu/lambda and the sign binariser/packer (Sec. 3.1, App. A), the router (Sec. 3.3).
+#include <mutex>
 #include "pq_internal.h"
 
 // ------------------------------------------------------------------------------------------
@@ -421,6 +422,34 @@ int pq_launch_rmsnorm_bwd(const void* dXn, const void* X, const void* gain, cons
   pq_prof_scope prof(PQP_NORM_BWD, s);
   rmsnorm_dgain_kernel<<<(K + 7) / 8, 256, 0, s>>>(part, (T + NORM_BWD_TPB - 1) / NORM_BWD_TPB, K, dgain);
   PQ_CHECK_LAUNCH("rmsnorm_dgain_kernel");
+  return PQ_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Scratch for callers that cannot allocate (code under graph capture, serving loops): a file-scope device array
+// that every GPU the library runs on holds until the process ends.  Its name is a host-side stand-in, not a
+// device address: the address is looked up once per device and only that pointer is handed to kernels.
+// ------------------------------------------------------------------------------------------
+constexpr size_t PQ_STATIC_SCRATCH_BYTES = (size_t)4 << 20;
+constexpr int PQ_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[PQ_STATIC_SCRATCH_BYTES];
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[PQ_MAX_DEVICES];
+
+size_t pq_static_scratch_bytes() { return PQ_STATIC_SCRATCH_BYTES; }
+
+int pq_static_scratch(void** out) {
+  int dev = -1;
+  PQ_CHECK_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= PQ_MAX_DEVICES) return pq_set_error(PQ_ERR_HIP, "device ordinal %d is outside 0..%d", dev, PQ_MAX_DEVICES - 1);
+  std::lock_guard<std::mutex> g(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    PQ_CHECK_HIP(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return pq_set_error(PQ_ERR_HIP, "hipGetSymbolAddress returned a NULL address for the static scratch");
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
   return PQ_OK;
 }
 
