@@ -17,7 +17,8 @@
  *     also need d_out % 32 == 0 and hp_rank % 8 == 0.
  *   - Return value: PQ_OK (0) or a negative pq_status.  Nothing throws or aborts;
  *     pq_last_error_string() gives the calling thread's last message.  Arguments are validated on
- *     the host before any kernel is launched, so a failed call has enqueued nothing.
+ *     the host before any kernel is launched, so a call refused for its arguments has enqueued nothing; a
+ *     PQ_ERR_HIP from a launch in the middle of a call's sequence leaves the earlier kernels of that call enqueued.
  */
 #ifndef PQUANT_H
 #define PQUANT_H
@@ -41,6 +42,9 @@ typedef enum pq_status {
 typedef enum pq_dtype { PQ_F32 = 0, PQ_BF16 = 1 } pq_dtype;
 typedef enum pq_w_kind { PQ_W_MASTER = 0, PQ_W_PACKED = 1 } pq_w_kind;
 typedef enum pq_ste_mode { PQ_STE_IDENTITY = 0, PQ_STE_CLIP = 1 } pq_ste_mode;
+/* Form of the high-precision branch (used when hp_rank > 0): 16-bit weights on the unquantised x (the FP16 variant of
+ * Sec. 4.6), or the INT8 form of Sec. 3.2 (8-bit weights quantised like the 8-bit activations; see pq_hp_int8_fwd). */
+typedef enum pq_hp_kind { PQ_HP_LOWRANK_BF16 = 0, PQ_HP_LOWRANK_INT8 = 1 } pq_hp_kind;
 
 /* One decoupled linear.  Plain data, passed by pointer (host memory). */
 typedef struct pq_linear_desc {
@@ -56,6 +60,7 @@ typedef struct pq_linear_desc {
   float ste_tau;
   float alpha;       /* scale of the high-precision branch (Sec. 3.2) */
   float beta;        /* scale of the 1-bit branch (Sec. 3.2) */
+  int32_t hp_kind;   /* pq_hp_kind; PQ_HP_LOWRANK_INT8 needs n_experts == 1, bf16 I/O, d_out and hp_rank multiples of 32 */
 } pq_linear_desc;
 
 int pq_version(void);
@@ -140,6 +145,11 @@ size_t pq_linear_workspace_bytes(const pq_linear_desc* desc);
  *     statistics are computed and stored in ctx.
  *   hpA: E == 1: [r][K]; E > 1: [E][r][K].   hpB: E == 1: [N][r]; E > 1: [E][N][r].  io_dtype.
  *   Wr [E][K] io_dtype, only for E > 1.  All three NULL when hp_rank == 0.
+ *   E > 1 (Sec. 3.3; bf16 I/O only, d_out % 32 == 0): the router of pq_router_topk selects top_k experts per token,
+ *   the tokens are permuted by expert (stable), H_e = X_e A_e^T and Y_e = H_e B_e^T run as grouped GEMMs over the
+ *   expert segments (both stored in bf16), and Y += alpha * sum_j gate_j Y_e_j in token order.
+ *   hp_kind == PQ_HP_LOWRANK_INT8 (E == 1): the branch of pq_hp_int8_fwd on the codes the 1-bit branch has just
+ *   formed (x is quantised once), added to the 1-bit branch's rounded output.
  *   Y [T][N] io_dtype out.
  *   ctx: pq_linear_ctx_bytes() bytes, or NULL for inference (nothing saved; no backward).
  *   workspace: pq_linear_workspace_bytes() bytes. */
@@ -151,7 +161,8 @@ int pq_linear_fwd(const pq_linear_desc* desc, const void* X, const void* W_or_pa
  * gamma carry no gradient.
  *   dY [T][N] io_dtype; X, W, hpA, hpB, Wr as given to forward; ctx as written by forward.
  *   dX [T][K] io_dtype out.  dW [N][K] fp32 out (gradient of the latent weight).
- *   dhpA, dhpB, dWr: fp32 out, shaped like hpA, hpB, Wr (NULL when that input is absent).
+ *   dhpA, dhpB, dWr: fp32 out, shaped like hpA, hpB, Wr (NULL when that input is absent).  For E > 1 the router's
+ *   softmax gate is differentiated too: dgate = alpha <dY_t, Y_e(x_t)>, dWr and its part of dX follow.
  *   dalpha_dbeta [2] fp32 out: {dL/dalpha, dL/dbeta}.
  * Reductions are two-stage with a fixed order: results are bit-identical from run to run. */
 int pq_linear_bwd(const pq_linear_desc* desc, const void* dY, const void* X, const void* W,

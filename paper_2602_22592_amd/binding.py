@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libpquant.so")
 PQ_F32, PQ_BF16 = 0, 1
 PQ_W_MASTER, PQ_W_PACKED = 0, 1
 PQ_STE_IDENTITY, PQ_STE_CLIP = 0, 1
+PQ_HP_LOWRANK_BF16, PQ_HP_LOWRANK_INT8 = 0, 1
 PQ_PACKED_ROWMAJOR, PQ_PACKED_TILED64 = 0, 1
 
 EXPORTS = [
@@ -35,7 +36,8 @@ EXPORTS = [
 class LinearDesc(C.Structure):
     _fields_ = [("tokens", C.c_int32), ("d_in", C.c_int32), ("d_out", C.c_int32), ("hp_rank", C.c_int32),
                 ("n_experts", C.c_int32), ("top_k", C.c_int32), ("io_dtype", C.c_int32), ("w_kind", C.c_int32),
-                ("ste_mode", C.c_int32), ("ste_tau", C.c_float), ("alpha", C.c_float), ("beta", C.c_float)]
+                ("ste_mode", C.c_int32), ("ste_tau", C.c_float), ("alpha", C.c_float), ("beta", C.c_float),
+                ("hp_kind", C.c_int32)]
 
 
 class DecodeDesc(C.Structure):
@@ -200,9 +202,9 @@ def onebit_acc(Xq, P, N):
 
 
 def make_desc(tokens, d_in, d_out, hp_rank=0, n_experts=1, top_k=1, io_dtype=PQ_BF16, w_kind=PQ_W_MASTER,
-              ste_mode=PQ_STE_IDENTITY, ste_tau=0.0, alpha=2.0, beta=0.2):
+              ste_mode=PQ_STE_IDENTITY, ste_tau=0.0, alpha=2.0, beta=0.2, hp_kind=PQ_HP_LOWRANK_BF16):
     return LinearDesc(tokens, d_in, d_out, hp_rank, n_experts, top_k, io_dtype, w_kind, ste_mode, ste_tau,
-                      alpha, beta)
+                      alpha, beta, hp_kind)
 
 
 class LinearBuffers:

@@ -98,8 +98,13 @@ pq_epilogue epi_zero() {
 struct lin_layout {
   // ctx (saved by forward for backward)
   size_t mulam, P, Pt, Xq, gamma, Xt, H, ctx_total;
+  // routed experts (n_experts > 1): routing decisions, the permuted activations, per-slot hidden states and outputs
+  size_t idx, gate, probs, counts, offsets, perm, inv, Xp, Hs, Ys;
+  // INT8 form of the dense branch: the ctx of pq_hp_int8_* behind the linear's own
+  size_t hp8, hp8_bytes;
   // workspace (scratch)
   size_t stat_partials, red_a, red_b, dH, w_Xq, w_gamma, w_H, splitk, splitk2, ws_total;
+  size_t dYp, rd, dHs, dXs, dlogit, dwr, hp8_ws, hp8_ws_bytes;
   int n_red_a, n_red_b;
 };
 
@@ -115,7 +120,10 @@ struct cursor {
 lin_layout make_layout(const pq_linear_desc& d) {
   lin_layout L;
   memset(&L, 0, sizeof(L));
-  const size_t T = d.tokens, K = d.d_in, N = d.d_out, r = d.hp_rank, es = esize(d.io_dtype);
+  const bool routed = d.n_experts > 1 && d.hp_rank > 0;
+  const bool hp8 = d.hp_kind == PQ_HP_LOWRANK_INT8 && d.hp_rank > 0;
+  // the dense-branch sections (H, dH, the rank-r GEMM plans) are sized for the dense branch only
+  const size_t T = d.tokens, K = d.d_in, N = d.d_out, r = (routed || hp8) ? 0 : d.hp_rank, es = esize(d.io_dtype);
   const int engine = d.io_dtype == PQ_BF16 ? 0 : 1;
   cursor c;
   L.mulam = c.take(2 * sizeof(float));
@@ -125,10 +133,20 @@ lin_layout make_layout(const pq_linear_desc& d) {
   L.gamma = c.take(T * sizeof(float));
   L.Xt = c.take(d.io_dtype == PQ_BF16 ? T * K * 2 : 0);
   L.H = c.take(T * r * es);
+  const size_t S = T * (size_t)d.top_k, E = d.n_experts, re = d.hp_rank;
+  if (routed) {
+    L.idx = c.take(S * 4); L.gate = c.take(S * 4); L.probs = c.take(T * E * 4);
+    L.counts = c.take(E * 4); L.offsets = c.take((E + 1) * 4); L.perm = c.take(S * 4); L.inv = c.take(S * 4);
+    L.Xp = c.take(S * K * 2); L.Hs = c.take(S * re * 2); L.Ys = c.take(S * N * 2);
+  }
+  if (hp8) {
+    L.hp8_bytes = pq_hp_int8_ctx_bytes(d.tokens, d.d_in, d.d_out, d.hp_rank);
+    L.hp8 = c.take(L.hp8_bytes);
+  }
   L.ctx_total = c.off > 0 ? c.off : 256;
   cursor w;
   L.stat_partials = w.take(2 * sizeof(double) * 1024);
-  const int Ti = d.tokens, Ki = d.d_in, Ni = d.d_out, ri = d.hp_rank;
+  const int Ti = d.tokens, Ki = d.d_in, Ni = d.d_out, ri = (int)r;
   L.n_red_a = r ? pq_plan_gemm(engine, Ti, ri, Ni).red_blocks : 0;       // dH GEMM
   if (r && pq_skinny_blocks(Ti) > L.n_red_a) L.n_red_a = pq_skinny_blocks(Ti);   // room for the streaming rank-r kernel's partials
   L.n_red_b = pq_plan_gemm(engine, Ni, Ki, Ti).red_blocks;                // dW GEMM
@@ -140,6 +158,11 @@ lin_layout make_layout(const pq_linear_desc& d) {
     const size_t b = pq_plan_gemm(engine, sh[0], sh[1], sh[2]).ws_bytes;
     if (b > sk) sk = b;
   }
+  if (routed) {
+    L.n_red_a = pq_rowdot_blocks((int)S);
+    if (8 * S * re * sizeof(float) > sk) sk = 8 * S * re * sizeof(float);   // narrow grouped GEMMs split the contraction up to 8 ways
+  }
+  if (hp8) L.n_red_a = pq_plan_gemm(0, Ti, d.hp_rank, Ni).red_blocks;      // the INT8 branch's dH GEMM leaves the partials of d alpha
   L.red_a = w.take(sizeof(double) * (size_t)(L.n_red_a > 0 ? L.n_red_a : 1));
   L.red_b = w.take(sizeof(double) * (size_t)L.n_red_b);
   L.dH = w.take(T * r * es);
@@ -149,6 +172,15 @@ lin_layout make_layout(const pq_linear_desc& d) {
   L.splitk = w.take(sk);
   // slabs of dA, which shares a launch with dB (whose slabs are in the region above)
   L.splitk2 = w.take((ri > 0 && Ki > 0) ? pq_plan_gemm(engine, ri, Ki, Ti).ws_bytes : 0);
+  if (routed) {
+    L.dYp = w.take(S * N * 2); L.rd = w.take(S * 4); L.dHs = w.take(S * re * 2); L.dXs = w.take(S * K * 2);
+    L.dlogit = w.take(T * E * 4);
+    L.dwr = w.take(pq_dwr_scratch_bytes(d.tokens, d.d_in, d.n_experts));
+  }
+  if (hp8) {
+    L.hp8_ws_bytes = pq_hp_int8_workspace_bytes(d.tokens, d.d_in, d.d_out, d.hp_rank);
+    L.hp8_ws = w.take(L.hp8_ws_bytes);
+  }
   L.ws_total = w.off;
   return L;
 }
@@ -170,8 +202,17 @@ int check_desc(const pq_linear_desc* d, bool training) {
     PQ_REQUIRE(d->d_out % 32 == 0, PQ_ERR_SHAPE, "training needs d_out=%d to be a multiple of 32", d->d_out);
     PQ_REQUIRE(d->w_kind == PQ_W_MASTER, PQ_ERR_BAD_ARG, "backward needs latent weights (PQ_W_MASTER)");
   }
-  PQ_REQUIRE(d->n_experts == 1 || d->hp_rank == 0, PQ_ERR_BAD_ARG,
-             "routed experts inside pq_linear_* are not available in this build (n_experts=%d)", d->n_experts);
+  PQ_REQUIRE(d->hp_kind == PQ_HP_LOWRANK_BF16 || d->hp_kind == PQ_HP_LOWRANK_INT8, PQ_ERR_BAD_ARG, "unknown hp_kind %d", d->hp_kind);
+  if (d->n_experts > 1 && d->hp_rank > 0) {
+    PQ_REQUIRE(d->io_dtype == PQ_BF16, PQ_ERR_DTYPE, "routed experts (n_experts=%d) run on bf16 I/O only", d->n_experts);
+    PQ_REQUIRE(d->hp_kind == PQ_HP_LOWRANK_BF16, PQ_ERR_BAD_ARG, "routed experts take the 16-bit form of the high-precision branch");
+    PQ_REQUIRE(d->d_out % 32 == 0, PQ_ERR_SHAPE, "routed experts need d_out=%d to be a multiple of 32", d->d_out);
+  }
+  if (d->hp_kind == PQ_HP_LOWRANK_INT8 && d->hp_rank > 0) {
+    PQ_REQUIRE(d->io_dtype == PQ_BF16, PQ_ERR_DTYPE, "the INT8 high-precision branch runs on bf16 I/O only");
+    PQ_REQUIRE(d->d_out % 32 == 0 && d->hp_rank % 32 == 0, PQ_ERR_SHAPE,
+               "the INT8 high-precision branch needs d_out=%d and hp_rank=%d to be multiples of 32", d->d_out, d->hp_rank);
+  }
   return PQ_OK;
 }
 
@@ -312,12 +353,17 @@ extern "C" size_t pq_linear_workspace_bytes(const pq_linear_desc* d) {
 static int linear_fwd_impl(const pq_linear_desc* d, const void* X, const void* W_or_packed,
                            const float* mu_lambda, const void* hpA, const void* hpB, const void* Wr, void* Y,
                            void* ctx, size_t ctx_bytes, void* workspace, size_t workspace_bytes, void* stream, bool prequant) {
-  (void)Wr;
   if (int e = check_desc(d, false)) return e;
   const lin_layout L = make_layout(*d);
-  const int T = d->tokens, K = d->d_in, N = d->d_out, r = d->hp_rank;
-  PQ_REQUIRE(X && W_or_packed && Y && workspace, PQ_ERR_BAD_ARG, "NULL buffer (X, W, Y or workspace)");
-  PQ_REQUIRE(r == 0 || (hpA && hpB), PQ_ERR_BAD_ARG, "hp_rank=%d but hpA/hpB is NULL", r);
+  const bool routed = d->n_experts > 1 && d->hp_rank > 0;                 // Sec. 3.3: top-k routed low-rank experts
+  const bool hp8 = d->hp_kind == PQ_HP_LOWRANK_INT8 && d->hp_rank > 0;    // Sec. 3.2: the branch in its INT8 form
+  // r is the rank of the dense 16-bit branch handled inline below; the other two forms run behind the 1-bit GEMM
+  const int T = d->tokens, K = d->d_in, N = d->d_out, r = (routed || hp8) ? 0 : d->hp_rank;
+  PQ_REQUIRE((d->tokens == 0 || (X && Y)) && W_or_packed && workspace, PQ_ERR_BAD_ARG, "NULL buffer (X, W, Y or workspace)");
+  PQ_REQUIRE(d->hp_rank == 0 || (hpA && hpB), PQ_ERR_BAD_ARG, "hp_rank=%d but hpA/hpB is NULL", d->hp_rank);
+  PQ_REQUIRE(!routed || Wr, PQ_ERR_BAD_ARG, "n_experts=%d needs the router weights Wr", d->n_experts);
+  PQ_REQUIRE(!(routed || hp8) || ctx, PQ_ERR_BAD_ARG, "routed experts and the INT8 high-precision branch need a ctx");
+  PQ_REQUIRE(aligned16(Wr), PQ_ERR_SHAPE, "Wr must be 16-byte aligned");
   PQ_REQUIRE(d->w_kind == PQ_W_MASTER || mu_lambda, PQ_ERR_BAD_ARG, "packed weights need mu_lambda");
   PQ_REQUIRE(d->w_kind == PQ_W_PACKED || ctx, PQ_ERR_BAD_ARG, "latent weights need a ctx to hold the packed bits");
   PQ_REQUIRE(aligned16(X) && aligned16(W_or_packed) && aligned16(Y) && aligned16(workspace) && aligned16(ctx) &&
@@ -385,7 +431,12 @@ static int linear_fwd_impl(const pq_linear_desc* d, const void* X, const void* W
     P = (const uint32_t*)W_or_packed;
     mulam = mu_lambda;
   }
-  if (T == 0) return PQ_OK;   // the weight side is still prepared, so a backward with no tokens is well defined
+  if (T == 0) {   // the weight side is still prepared, so a backward with no tokens is well defined
+    if (routed)   // ... and empty expert segments are left behind for it
+      return pq_launch_route((const int*)(cx + L.idx), 0, d->n_experts, (int*)(cx + L.counts), (int*)(cx + L.offsets),
+                             (int*)(cx + L.perm), (int*)(cx + L.inv), s);
+    return PQ_OK;
+  }
 
   if (!quant_done)
     if (int e = pq_launch_quant_act(X, d->io_dtype, T, K, Xq, gamma, Xt, s)) return e;
@@ -418,6 +469,39 @@ static int linear_fwd_impl(const pq_linear_desc* d, const void* X, const void* W
     e.C = Y; e.ldc = N; e.out_kind = ok; e.accumulate = 1; e.scale = d->alpha;
     if (int err = pq_launch_gemm(engine, T, N, r, A, B, e, s, PQP_GEMM_HP_Y, sk_ws)) return err;
   }
+  if (hp8)   // Y += alpha * B~ Q(A~ Q(x)) on the codes and gamma formed above
+    return pq_hp_int8_fwd(Xq, gamma, hpA, hpB, PQ_BF16, T, K, N, d->hp_rank, d->alpha, Y, 1, cx + L.hp8, L.hp8_bytes,
+                          ws + L.hp8_ws, L.hp8_ws_bytes, stream);
+  if (routed) {
+    // router -> stable permutation by expert -> gather -> H_e = X_e A_e^T -> Y_e = H_e B_e^T -> gate-weighted combine
+    const int E = d->n_experts, k = d->top_k, S = T * k, re = d->hp_rank;
+    int* idx = (int*)(cx + L.idx);
+    float* gate = (float*)(cx + L.gate);
+    int* offsets = (int*)(cx + L.offsets);
+    int* perm = (int*)(cx + L.perm);
+    int* inv = (int*)(cx + L.inv);
+    if (int e = pq_launch_router(X, Wr, PQ_BF16, T, K, E, k, idx, gate, (float*)(cx + L.probs), s)) return e;
+    if (int e = pq_launch_route(idx, S, E, (int*)(cx + L.counts), offsets, perm, inv, s)) return e;
+    if (int e = pq_launch_gather_rows(X, perm, k, S, K, cx + L.Xp, s)) return e;
+    pq_gemm_group g1{offsets, E, 1, 0, 0, S};
+    {
+      pq_operand A{cx + L.Xp, K, PQ_SRC_KC16, nullptr};
+      pq_operand B{hpA, K, PQ_SRC_KC16, nullptr};
+      pq_epilogue e = epi_zero();
+      e.C = cx + L.Hs; e.ldc = re; e.out_kind = PQ_OUT_BF16;
+      g1.b_stride = (long)re * K;
+      if (int err = pq_launch_gemm(0, S, re, K, A, B, e, s, PQP_GEMM_EXPERT, sk_ws, &g1)) return err;
+    }
+    {
+      pq_operand A{cx + L.Hs, re, PQ_SRC_KC16, nullptr};
+      pq_operand B{hpB, re, PQ_SRC_KC16, nullptr};
+      pq_epilogue e = epi_zero();
+      e.C = cx + L.Ys; e.ldc = N; e.out_kind = PQ_OUT_BF16;
+      g1.b_stride = (long)N * re;
+      if (int err = pq_launch_gemm(0, S, N, re, A, B, e, s, PQP_GEMM_EXPERT, sk_ws, &g1)) return err;
+    }
+    return pq_launch_combine_fwd(Y, cx + L.Ys, inv, gate, d->alpha, T, k, N, s);
+  }
   return PQ_OK;
 }
 
@@ -430,16 +514,24 @@ extern "C" int pq_linear_fwd(const pq_linear_desc* d, const void* X, const void*
 // ---------------------------------------------------------------------------------------------
 // STE backward
 // ---------------------------------------------------------------------------------------------
+// pq_hp_int8_bwd with the per-workgroup partial sums of <dY, Y_hp> (= d alpha) left in red_a when it is not NULL
+static int hp_int8_bwd_impl(const void* dY, const void* Xt, int32_t dtype, int32_t T, int32_t K, int32_t N, int32_t r, float alpha,
+                            const void* ctx, size_t ctx_bytes, void* dX, int32_t accumulate_dX, float* dA, float* dB, void* workspace,
+                            size_t workspace_bytes, void* stream, double* red_a);
+
 extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void* X, const void* W,
                              const void* hpA, const void* hpB, const void* Wr, const void* ctx, size_t ctx_bytes,
                              void* dX, float* dW, float* dhpA, float* dhpB, float* dWr, float* dalpha_dbeta,
                              void* workspace, size_t workspace_bytes, void* stream) {
-  (void)Wr; (void)dWr;
   if (int e = check_desc(d, true)) return e;
   const lin_layout L = make_layout(*d);
-  const int T = d->tokens, K = d->d_in, N = d->d_out, r = d->hp_rank;
-  PQ_REQUIRE(dY && X && ctx && dX && dW && dalpha_dbeta && workspace, PQ_ERR_BAD_ARG, "NULL buffer");
-  PQ_REQUIRE(r == 0 || (hpA && hpB && dhpA && dhpB), PQ_ERR_BAD_ARG, "hp_rank=%d but an hp buffer is NULL", r);
+  const bool routed = d->n_experts > 1 && d->hp_rank > 0;
+  const bool hp8 = d->hp_kind == PQ_HP_LOWRANK_INT8 && d->hp_rank > 0;
+  const int T = d->tokens, K = d->d_in, N = d->d_out, r = (routed || hp8) ? 0 : d->hp_rank;
+  PQ_REQUIRE((d->tokens == 0 || (dY && X && dX)) && ctx && dW && dalpha_dbeta && workspace, PQ_ERR_BAD_ARG, "NULL buffer");
+  PQ_REQUIRE(d->hp_rank == 0 || (hpA && hpB && dhpA && dhpB), PQ_ERR_BAD_ARG, "hp_rank=%d but an hp buffer is NULL", d->hp_rank);
+  PQ_REQUIRE(!routed || (Wr && dWr), PQ_ERR_BAD_ARG, "n_experts=%d needs Wr and dWr", d->n_experts);
+  PQ_REQUIRE(aligned16(Wr) && aligned16(dhpA) && aligned16(dhpB), PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
   PQ_REQUIRE(d->ste_mode == PQ_STE_IDENTITY || W, PQ_ERR_BAD_ARG, "PQ_STE_CLIP needs the latent W");
   PQ_REQUIRE(aligned16(dY) && aligned16(X) && aligned16(ctx) && aligned16(dX) && aligned16(dW) && aligned16(workspace) &&
                  aligned16(hpA) && aligned16(hpB) && aligned16(W), PQ_ERR_SHAPE, "buffers must be 16-byte aligned");
@@ -509,8 +601,63 @@ extern "C" int pq_linear_bwd(const pq_linear_desc* d, const void* dY, const void
     }
     if (int err = pq_launch_gemm(engine, N, K, T, A, B, e, s, PQP_GEMM_DW, sk_ws)) return err;
   }
+  if (routed) {
+    // Sec. 3.3 backward: upstream of expert e's output for slot (t, j) is alpha gate_tj dY_t; the gate itself
+    // receives dgate_tj = alpha <dY_t, Y_e(x_t)> and is differentiated through the softmax into Wr and X.
+    const int E = d->n_experts, k = d->top_k, S = T * k, re = d->hp_rank;
+    const int* idx = (const int*)(cx + L.idx);
+    const float* gate = (const float*)(cx + L.gate);
+    const int* offsets = (const int*)(cx + L.offsets);
+    const int* perm = (const int*)(cx + L.perm);
+    const int* inv = (const int*)(cx + L.inv);
+    float* rd = (float*)(ws + L.rd);
+    n_red_a = S > 0 ? pq_rowdot_blocks(S) : 0;
+    if (int e = pq_launch_gather_rows(dY, perm, k, S, N, ws + L.dYp, s)) return e;
+    if (int e = pq_launch_rowdot(ws + L.dYp, cx + L.Ys, perm, gate, S, N, rd, red_a, s)) return e;
+    if (int e = pq_launch_scale_rows(ws + L.dYp, perm, gate, d->alpha, S, N, s)) return e;   // dYp <- alpha gate dYp
+    pq_gemm_group g1{offsets, E, 1, 0, 0, S};
+    pq_gemm_group g2{offsets, E, 2, 0, 0, S};
+    if (S > 0) {  // dH_e = (alpha gate dY)_e B_e
+      pq_operand A{ws + L.dYp, N, PQ_SRC_KC16, nullptr};
+      pq_operand B{hpB, re, PQ_SRC_KS16, nullptr};
+      pq_epilogue e = epi_zero();
+      e.C = ws + L.dHs; e.ldc = re; e.out_kind = PQ_OUT_BF16;
+      g1.b_stride = (long)N * re;
+      if (int err = pq_launch_gemm(0, S, re, N, A, B, e, s, PQP_GEMM_EXPERT, sk_ws, &g1)) return err;
+    }
+    {  // per-expert weight gradients: the contraction runs over the expert's slots
+      pq_operand A{ws + L.dYp, N, PQ_SRC_KS16, nullptr};
+      pq_operand B{cx + L.Hs, re, PQ_SRC_KS16, nullptr};
+      pq_epilogue e = epi_zero();
+      e.C = dhpB; e.ldc = re; e.out_kind = PQ_OUT_F32;
+      g2.c_stride = (long)N * re;
+      if (int err = pq_launch_gemm(0, N, re, S, A, B, e, s, PQP_GEMM_EXPERT, sk_ws, &g2)) return err;
+      pq_operand A2{ws + L.dHs, re, PQ_SRC_KS16, nullptr};
+      pq_operand B2{cx + L.Xp, K, PQ_SRC_KS16, nullptr};
+      e.C = dhpA; e.ldc = K;
+      g2.c_stride = (long)re * K;
+      if (int err = pq_launch_gemm(0, re, K, S, A2, B2, e, s, PQP_GEMM_EXPERT, sk_ws, &g2)) return err;
+    }
+    if (S > 0) {  // dXs = dH_e A_e (slot order), then scattered back with the router's share
+      pq_operand A{ws + L.dHs, re, PQ_SRC_KC16, nullptr};
+      pq_operand B{hpA, K, PQ_SRC_KS16, nullptr};
+      pq_epilogue e = epi_zero();
+      e.C = ws + L.dXs; e.ldc = K; e.out_kind = PQ_OUT_BF16;
+      g1.b_stride = (long)re * K;
+      if (int err = pq_launch_gemm(0, S, K, re, A, B, e, s, PQP_GEMM_EXPERT, sk_ws, &g1)) return err;
+    }
+    float* dlogit = (float*)(ws + L.dlogit);
+    if (int e = pq_launch_router_bwd(rd, inv, idx, (const float*)(cx + L.probs), d->alpha, T, k, E, dlogit, s)) return e;
+    if (int e = pq_launch_dwr(dlogit, X, T, K, E, (float*)(ws + L.dwr), dWr, s)) return e;
+    if (int e = pq_launch_combine_bwd(dX, ws + L.dXs, inv, dlogit, Wr, T, k, K, E, s)) return e;
+  }
+  if (hp8) {   // STE backward of the INT8 branch on the de-quantised factors; its dH GEMM leaves the partials of d alpha
+    n_red_a = T > 0 ? pq_plan_gemm(0, T, d->hp_rank, N).red_blocks : 0;
+    if (int e = hp_int8_bwd_impl(dY, cx + L.Xt, PQ_BF16, T, K, N, d->hp_rank, d->alpha, cx + L.hp8, L.hp8_bytes, dX, 1, dhpA, dhpB,
+                                 ws + L.hp8_ws, L.hp8_ws_bytes, stream, red_a)) return e;
+  }
   // d alpha and d beta: both fixed-order sums of per-workgroup partials
-  const pq_reduce_job jobs[2] = {{red_a, (T > 0 && r > 0) ? n_red_a : 0, 1.0f, nullptr, dalpha_dbeta},
+  const pq_reduce_job jobs[2] = {{red_a, (T > 0 && (r > 0 || routed || hp8)) ? n_red_a : 0, 1.0f, nullptr, dalpha_dbeta},
                                  {red_b, L.n_red_b, 1.0f, mulam + 1, dalpha_dbeta + 1}};
   bool jobs_done = false;
   if (r > 0 && bf16 && T > 0) {
@@ -719,6 +866,13 @@ extern "C" int pq_hp_int8_fwd(const int8_t* Xq, const float* gamma_x, const void
 extern "C" int pq_hp_int8_bwd(const void* dY, const void* Xt, int32_t dtype, int32_t T, int32_t K, int32_t N, int32_t r,
                               float alpha, const void* ctx, size_t ctx_bytes, void* dX, int32_t accumulate_dX, float* dA, float* dB,
                               void* workspace, size_t workspace_bytes, void* stream) {
+  return hp_int8_bwd_impl(dY, Xt, dtype, T, K, N, r, alpha, ctx, ctx_bytes, dX, accumulate_dX, dA, dB, workspace, workspace_bytes, stream,
+                          nullptr);
+}
+
+static int hp_int8_bwd_impl(const void* dY, const void* Xt, int32_t dtype, int32_t T, int32_t K, int32_t N, int32_t r, float alpha,
+                            const void* ctx, size_t ctx_bytes, void* dX, int32_t accumulate_dX, float* dA, float* dB, void* workspace,
+                            size_t workspace_bytes, void* stream, double* red_a) {
   if (int e = check_hp8(dtype, T, K, N, r)) return e;
   const hp8_layout L = make_hp8_layout(T, K, N, r);
   PQ_REQUIRE(ctx && dA && dB && workspace, PQ_ERR_BAD_ARG, "NULL buffer (ctx, dA, dB or workspace)");
@@ -737,6 +891,9 @@ extern "C" int pq_hp_int8_bwd(const void* dY, const void* Xt, int32_t dtype, int
     pq_operand b{cx + L.Bt, r, PQ_SRC_KS16, nullptr};
     pq_epilogue e = epi_zero();
     e.C = dH; e.ldc = r; e.out_kind = PQ_OUT_BF16; e.scale = alpha;
+    if (red_a) {   // sum H~ .* (dY B~) = <dY, H~ B~^T>: the gradient of alpha, one partial per workgroup
+      e.dot_comp = cx + L.Ht; e.ld_comp = r; e.comp_kind = PQ_OUT_BF16; e.partials = red_a;
+    }
     if (int err = pq_launch_gemm(0, T, r, N, a, b, e, s, PQP_GEMM_DH, sk)) return err;
   }
   {  // dB = alpha * dY^T H~ and dA = dH^T X~ (dH already carries alpha): one launch when their shapes allow it

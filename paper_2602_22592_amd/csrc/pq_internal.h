@@ -189,6 +189,7 @@ int pq_launch_swiglu_bwd(const void* dHd, const void* U, const void* G, size_t n
 int pq_launch_expert_act(const void* ue, const void* ge, size_t n, void* a, hipStream_t s);
 int pq_launch_expert_act_bwd(const void* da, const void* ue, const void* ge, const void* a, const int* perm, const float* gate,
                              float alpha, int S, int r, void* du, void* dg, void* as, hipStream_t s);
+int pq_launch_scale_rows(void* A, const int* perm, const float* gate, float alpha, int S, int d, hipStream_t s);
 int pq_rowdot_blocks(int S);
 int pq_launch_rowdot(const void* A, const void* B, const int* perm, const float* gate, int S, int d, float* rd, double* partial,
                      hipStream_t s);

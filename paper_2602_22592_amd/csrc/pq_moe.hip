@@ -243,6 +243,23 @@ __global__ __launch_bounds__(256) void rowdot_kernel(const uint16_t* __restrict_
   if (threadIdx.x == 0) partial[blockIdx.x] = t;
 }
 
+// A[pos,:] *= alpha * gate[perm[pos]]  (rows of d bf16 in slot order, one wavefront per row): the upstream gradient of
+// an expert's output for slot (t, j) is alpha * gate[t][j] * dY[t]
+__global__ __launch_bounds__(256) void scale_rows_kernel(uint16_t* __restrict__ A, const int* __restrict__ perm,
+                                                         const float* __restrict__ gate, float alpha, int S, int d) {
+  const int pos = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (pos >= S) return;
+  const float sc = alpha * gate[perm[pos]];
+  uint4* a4 = reinterpret_cast<uint4*>(A + (size_t)pos * d);
+  for (int c = lane; c < d / 8; c += 64) {
+    float v[8];
+    unpack8(a4[c], v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] *= sc;
+    a4[c] = pack8(v);
+  }
+}
+
 // Y[t,:] += alpha * sum_j gate[t,j] * Ys[inv[t*k+j], :]   (one wavefront per token)
 __global__ __launch_bounds__(256) void combine_fwd_kernel(uint16_t* __restrict__ Y, const uint16_t* __restrict__ Ys,
                                                           const int* __restrict__ inv, const float* __restrict__ gate, float alpha,
@@ -481,6 +498,14 @@ int pq_launch_expert_act_bwd(const void* da, const void* ue, const void* ge, con
                                                                       (const uint16_t*)a, perm, gate, alpha, r, nvec, (uint16_t*)du,
                                                                       (uint16_t*)dg, (uint16_t*)as);
   PQ_CHECK_LAUNCH("expert_act_bwd_kernel");
+  return PQ_OK;
+}
+
+int pq_launch_scale_rows(void* A, const int* perm, const float* gate, float alpha, int S, int d, hipStream_t s) {
+  if (S <= 0) return PQ_OK;
+  pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
+  scale_rows_kernel<<<(S + 3) / 4, 256, 0, s>>>((uint16_t*)A, perm, gate, alpha, S, d);
+  PQ_CHECK_LAUNCH("scale_rows_kernel");
   return PQ_OK;
 }
 

@@ -1,8 +1,12 @@
 """Parity of the HIP path (through the C ABI) against the CPU oracle on identical seeded inputs.
 
 Bars: bit-exact for sign bits, packed words, INT8 codes, gamma, int32 accumulators and routing
-indices; max|a-b| / max|b| <= 1e-5 for fp32 I/O and <= 2e-2 for bf16 I/O on outputs and gradients.
+indices; max|a-b| / max|b| <= 1e-5 for fp32 I/O and <= 2e-2 for bf16 I/O on outputs and gradients, the same bar
+on the relative L2 error and, for gradients with an input-channel axis (dW, dA), on every input channel taken
+by itself (tests/parity_metrics.py).  Gradients that need every token of a full-size workload are compared with
+values the oracle wrote to tests/golden/full_size_*.npz (tests/golden/make_full_size_expected.py).
 """
+import os
 import numpy as np
 import pytest
 import torch
@@ -10,8 +14,10 @@ import torch
 from oracle import pquant_oracle as po
 from paper_2602_22592_amd import binding as pq
 from paper_2602_22592_amd import workloads as wl
+from parity_metrics import relerr, report
 
 pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 TOL = {False: 1e-5, True: 2e-2}
 
@@ -23,11 +29,6 @@ def dev(x, bf16=False):
 
 def host(t):
     return t.detach().float().cpu().numpy() if t.dtype == torch.bfloat16 else t.detach().cpu().numpy()
-
-
-def relerr(a, b):
-    a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
-    return float(np.abs(a - b).max() / max(np.abs(b).max(), 1e-30))
 
 
 def say(msg):
@@ -127,49 +128,64 @@ def test_router_topk(T, K, E, k, bf16):
 
 
 # ---------------------------------------------------------------------------- decoupled linear
-def run_linear(c, bf16, alpha, beta, ste_tau=None):
-    T, K, N, r = c["tokens"], c["d_in"], c["d_out"], c["hp_rank"]
-    desc = pq.make_desc(T, K, N, hp_rank=r, io_dtype=pq.PQ_BF16 if bf16 else pq.PQ_F32, alpha=alpha, beta=beta,
-                        ste_mode=pq.PQ_STE_CLIP if ste_tau is not None else pq.PQ_STE_IDENTITY,
+def run_linear(c, bf16, alpha, beta, ste_tau=None, top_k=1):
+    T, K, N, r, E = c["tokens"], c["d_in"], c["d_out"], c["hp_rank"], c.get("n_experts", 1)
+    desc = pq.make_desc(T, K, N, hp_rank=r, n_experts=E, top_k=top_k, io_dtype=pq.PQ_BF16 if bf16 else pq.PQ_F32,
+                        alpha=alpha, beta=beta, ste_mode=pq.PQ_STE_CLIP if ste_tau is not None else pq.PQ_STE_IDENTITY,
                         ste_tau=ste_tau or 0.0)
     bufs = pq.LinearBuffers(desc)
     dt = torch.bfloat16 if bf16 else torch.float32
     X, W, dY = dev(c["X"], bf16), dev(c["W"], bf16), dev(c["dY"], bf16)
     A = dev(c["A"], bf16) if r else None
     B = dev(c["B"], bf16) if r else None
+    Wr = dev(c["Wr"], bf16) if (r and E > 1) else None
     Y = torch.empty((T, N), dtype=dt, device="cuda")
-    pq.linear_fwd(desc, X, W, Y, bufs, A=A, B=B)
+    pq.linear_fwd(desc, X, W, Y, bufs, A=A, B=B, Wr=Wr)
     dX = torch.empty((T, K), dtype=dt, device="cuda")
     dW = torch.empty((N, K), dtype=torch.float32, device="cuda")
-    dA = torch.empty((r, K), dtype=torch.float32, device="cuda") if r else None
-    dB = torch.empty((N, r), dtype=torch.float32, device="cuda") if r else None
+    dA = torch.empty(c["A"].shape, dtype=torch.float32, device="cuda") if r else None
+    dB = torch.empty(c["B"].shape, dtype=torch.float32, device="cuda") if r else None
+    dWr = torch.empty(c["Wr"].shape, dtype=torch.float32, device="cuda") if Wr is not None else None
     dab = torch.empty((2,), dtype=torch.float32, device="cuda")
-    pq.linear_bwd(desc, dY, X, W, bufs, dX, dW, dab, A=A, B=B, dA=dA, dB=dB)
+    pq.linear_bwd(desc, dY, X, W, bufs, dX, dW, dab, A=A, B=B, Wr=Wr, dA=dA, dB=dB, dWr=dWr)
     torch.cuda.synchronize()
     return dict(Y=host(Y), dX=host(dX), dW=host(dW), dA=host(dA) if r else None, dB=host(dB) if r else None,
-                dab=host(dab))
+                dWr=host(dWr) if dWr is not None else None, dab=host(dab))
 
 
-def check_linear(c, bf16, alpha=2.0, beta=0.2, ste_tau=None):
-    r = c["hp_rank"]
-    got = run_linear(c, bf16, alpha, beta, ste_tau)
-    A, B = (c["A"], c["B"]) if r else (None, None)
-    f = po.linear_fwd(c["X"], c["W"], alpha, beta, A=A, B=B)
-    g = po.linear_bwd(c["dY"], c["X"], c["W"], alpha, beta, f, A=A, B=B,
-                      ste_tau=np.inf if ste_tau is None else np.float32(ste_tau))
-    tol = TOL[bf16]
-    errs = dict(Y=relerr(got["Y"], f["Y"]), dX=relerr(got["dX"], g["dX"]), dW=relerr(got["dW"], g["dW"]))
-    if r:
-        errs.update(dA=relerr(got["dA"], g["dA"]), dB=relerr(got["dB"], g["dB"]))
-    # scalar gradients: error relative to the natural scale of the sum (its root-sum-square of terms)
-    dY = c["dY"].astype(np.float64)
-    sb = max(abs(g["dbeta"]), np.sqrt(((dY * f["Y1_nobeta"]) ** 2).sum()))
-    sa = max(abs(g["dalpha"]), np.sqrt(((dY * f["Yhp"]) ** 2).sum()), 1e-30)
-    errs["dbeta"] = abs(got["dab"][1] - g["dbeta"]) / sb
-    errs["dalpha"] = abs(got["dab"][0] - g["dalpha"]) / sa
+def scalar_errs(got_dab, dalpha, dbeta, sa, sb):
+    """d alpha and d beta: error relative to the natural scale of the sum (the root-sum-square of its terms)."""
+    return {"dalpha": abs(got_dab[0] - dalpha) / max(abs(dalpha), sa, 1e-30),
+            "dbeta": abs(got_dab[1] - dbeta) / max(abs(dbeta), sb, 1e-30)}
+
+
+def assert_errs(errs, tol):
     say("  errors: " + ", ".join(f"{k}={v:.2e}" for k, v in errs.items()))
     for k, v in errs.items():
         assert v <= tol, f"{k}: {v} > {tol}"
+
+
+def check_linear(c, bf16, alpha=2.0, beta=0.2, ste_tau=None, top_k=1):
+    r, E = c["hp_rank"], c.get("n_experts", 1)
+    got = run_linear(c, bf16, alpha, beta, ste_tau, top_k)
+    A, B = (c["A"], c["B"]) if r else (None, None)
+    Wr = c["Wr"] if (r and E > 1) else None
+    f = po.linear_fwd(c["X"], c["W"], alpha, beta, A=A, B=B, Wr=Wr, top_k=top_k)
+    g = po.linear_bwd(c["dY"], c["X"], c["W"], alpha, beta, f, A=A, B=B, Wr=Wr,
+                      ste_tau=np.inf if ste_tau is None else np.float32(ste_tau))
+    errs = {}
+    errs.update(report("Y", got["Y"], f["Y"]))
+    errs.update(report("dX", got["dX"], g["dX"]))
+    errs.update(report("dW", got["dW"], g["dW"], per_channel=True))
+    if r:
+        errs.update(report("dA", got["dA"], g["dA"], per_channel=True))
+        errs.update(report("dB", got["dB"], g["dB"]))
+    if Wr is not None:
+        errs.update(report("dWr", got["dWr"], g["dWr"]))
+    dY = c["dY"].astype(np.float64)
+    errs.update(scalar_errs(got["dab"], g["dalpha"], g["dbeta"], np.sqrt(((dY * f["Yhp"]) ** 2).sum()),
+                            np.sqrt(((dY * f["Y1_nobeta"]) ** 2).sum())))
+    assert_errs(errs, TOL[bf16])
     return got
 
 
@@ -217,8 +233,10 @@ def test_linear_backward_is_deterministic():
 
 
 def test_linear_config2_full_size_sampled():
-    """Full bench shape (T=8192, 2048x2048, r=128, bf16) in the launch configuration bench.py times;
-    the oracle recomputes sampled tokens (rows of Y, dX) and sampled output channels (rows of dW, dB)."""
+    """Full bench shape (T=8192, 2048x2048, r=128, bf16) in the launch configuration bench.py times.  Rows of Y
+    and dX depend on their token alone: the oracle recomputes sampled tokens here.  dW, dA, dB, d alpha and d beta
+    sum over every token: they are compared with what oracle.linear_bwd gave on the whole workload
+    (tests/golden/full_size_config2.npz; dW and dB on sampled output channels, dA whole)."""
     say("linear config2 full size, sampled rows")
     c = wl.config2()
     got = run_linear(c, True, 2.0, 0.2)
@@ -226,14 +244,117 @@ def test_linear_config2_full_size_sampled():
     tok = np.sort(rng.choice(c["tokens"], 48, replace=False))
     f = po.linear_fwd(c["X"][tok], c["W"], 2.0, 0.2, A=c["A"], B=c["B"])
     g = po.linear_bwd(c["dY"][tok], c["X"][tok], c["W"], 2.0, 0.2, f, A=c["A"], B=c["B"])
-    eY, eX = relerr(got["Y"][tok], f["Y"]), relerr(got["dX"][tok], g["dX"])
-    # weight-side gradients need every token: recompute sampled output channels from the definitions
-    q, gamma = po.quant_act(c["X"])
-    ch = np.sort(rng.choice(c["d_out"], 32, replace=False))
+    errs = {}
+    errs.update(report("Y", got["Y"][tok], f["Y"]))
+    errs.update(report("dX", got["dX"][tok], g["dX"]))
+    ref = np.load(os.path.join(GOLDEN, "full_size_config2.npz"))
+    ch = ref["ch"]
+    errs.update(report("dW", got["dW"][ch], ref["dW"], per_channel=True))
+    errs.update(report("dB", got["dB"][ch], ref["dB"]))
+    errs.update(report("dA", got["dA"], ref["dA"], per_channel=True))
+    errs.update(scalar_errs(got["dab"], float(ref["dalpha"]), float(ref["dbeta"]), float(ref["dalpha_scale"]),
+                            float(ref["dbeta_scale"])))
+    assert_errs(errs, TOL[True])
+
+
+# ---------------------------------------------------------------------------- packed weights, inference, no tokens
+@pytest.mark.parametrize("T,K,N,r,bf16", [(1, 256, 72, 8, True), (64, 544, 416, 24, True), (1024, 2048, 2048, 128, True),
+                                         (64, 96, 72, 0, False), (300, 256, 264, 16, False)])
+@pytest.mark.parametrize("with_ctx", [False, True])
+def test_linear_fwd_on_packed_weights(T, K, N, r, bf16, with_ctx):
+    """PQ_W_PACKED: the bits and mu/lambda come from pq_pack_sign, the forward runs with ctx = NULL (inference: codes,
+    gamma and H live in the workspace) and with a ctx; d_out only needs to be a multiple of 8 here."""
+    say(f"linear fwd packed T={T} K={K} N={N} r={r} bf16={bf16} ctx={with_ctx}")
+    c = wl.linear_case(900 + T + r, T, K, N, hp_rank=r, bf16=bf16, outlier_frac=0.02, outlier_scale=10.0)
+    P, _, ml = pq.pack_sign(dev(c["W"], bf16))
+    desc = pq.make_desc(T, K, N, hp_rank=r, io_dtype=pq.PQ_BF16 if bf16 else pq.PQ_F32, w_kind=pq.PQ_W_PACKED)
+    bufs = pq.LinearBuffers(desc)
+    Y = torch.empty((T, N), dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda")
+    pq.linear_fwd(desc, dev(c["X"], bf16), P, Y, bufs, A=dev(c["A"], bf16) if r else None, B=dev(c["B"], bf16) if r else None,
+                  mu_lambda=ml, save=with_ctx)
+    torch.cuda.synchronize()
+    mu, lam = po.weight_stats(c["W"])
+    f = po.linear_fwd(c["X"], None, 2.0, 0.2, A=c["A"] if r else None, B=c["B"] if r else None,
+                      packed=po.pack_sign(po.binarise(c["W"], mu)), mu_lambda=(mu, lam))
+    assert_errs(report("Y", host(Y), f["Y"]), TOL[bf16])
+
+
+@pytest.mark.parametrize("bf16", [True, False])
+def test_linear_with_no_tokens(bf16):
+    """T = 0: the forward still prepares the weight side, the backward writes zero weight gradients (an empty sum)
+    and zero scalar gradients."""
+    say(f"linear T=0 bf16={bf16}")
+    c = wl.linear_case(950, 0, 96, 64, hp_rank=8, bf16=bf16)
+    got = run_linear(c, bf16, 2.0, 0.2)
+    for k in ("dW", "dA", "dB", "dab"):
+        assert np.all(got[k] == 0.0) and np.isfinite(got[k]).all(), k
+    if bf16:                                          # routed experts: empty expert segments
+        c = wl.linear_case(951, 0, 96, 64, hp_rank=8, n_experts=4, bf16=True)
+        got = run_linear(c, True, 2.0, 0.2, top_k=2)
+        for k in ("dW", "dA", "dB", "dWr", "dab"):
+            assert np.all(got[k] == 0.0) and np.isfinite(got[k]).all(), k
+
+
+# ---------------------------------------------------------------------------- routed low-rank experts (Sec. 3.3)
+@pytest.mark.parametrize("T,K,N,r,E,k", [(200, 96, 160, 8, 4, 1), (200, 96, 160, 8, 4, 2), (700, 256, 544, 32, 8, 1),
+                                         (130, 64, 64, 16, 2, 2), (1, 32, 32, 8, 8, 1), (1500, 1024, 288, 32, 8, 2),
+                                         (128, 4096, 11008, 64, 8, 2)])   # the decode layer's shape (config 4) in training
+def test_linear_routed_experts(T, K, N, r, E, k):
+    """E > 1 inside pq_linear_fwd / pq_linear_bwd: router, stable permutation, grouped expert GEMMs, gate-weighted
+    combine, and the backward through experts, gates and router (dA, dB, dWr, dX, d alpha)."""
+    say(f"linear routed T={T} K={K} N={N} r={r} E={E} k={k}")
+    c = wl.linear_case(1200 + T + k, T, K, N, hp_rank=r, n_experts=E, bf16=True, outlier_frac=0.02, outlier_scale=10.0)
+    check_linear(c, True, top_k=k)
+
+
+def test_linear_routed_experts_with_router_ties_and_unused_experts():
+    """Two identical router rows (ties go to the lower index, so the higher one is never first) and more experts than
+    tokens (empty expert segments)."""
+    c = wl.linear_case(1300, 5, 64, 96, hp_rank=8, n_experts=16, bf16=True)
+    c["Wr"][3] = c["Wr"][2]
+    check_linear(c, True, top_k=2)
+
+
+def test_linear_routed_experts_reject_fp32():
+    with pytest.raises(pq.PQError):
+        pq.LinearBuffers(pq.make_desc(16, 64, 64, hp_rank=8, n_experts=4, io_dtype=pq.PQ_F32))
+
+
+# ---------------------------------------------------------------------------- INT8 form of the dense branch via hp_kind
+@pytest.mark.parametrize("T,K,N,r", [(64, 256, 256, 32), (300, 1024, 768, 64), (1100, 512, 384, 128), (0, 64, 64, 32)])
+def test_linear_with_int8_high_precision_branch(T, K, N, r):
+    """hp_kind = PQ_HP_LOWRANK_INT8 through pq_linear_fwd / pq_linear_bwd (Sec. 3.2): the branch consumes the codes of
+    the 1-bit branch; expected values are oracle.linear_fwd without a branch plus oracle.hp_int8_fwd / hp_int8_bwd."""
+    say(f"linear hp_kind=INT8 T={T} K={K} N={N} r={r}")
+    c = wl.linear_case(1400 + T + r, T, K, N, hp_rank=r, bf16=True, outlier_frac=0.02, outlier_scale=10.0)
+    alpha, beta = 1.5, 0.3
+    desc = pq.make_desc(T, K, N, hp_rank=r, io_dtype=pq.PQ_BF16, alpha=alpha, beta=beta, hp_kind=pq.PQ_HP_LOWRANK_INT8)
+    bufs = pq.LinearBuffers(desc)
+    X, W, dY, A, B = (dev(c[n], True) for n in ("X", "W", "dY", "A", "B"))
+    Y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
+    pq.linear_fwd(desc, X, W, Y, bufs, A=A, B=B)
+    dX = torch.empty((T, K), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((N, K), dtype=torch.float32, device="cuda")
+    dA = torch.empty((r, K), dtype=torch.float32, device="cuda")
+    dB = torch.empty((N, r), dtype=torch.float32, device="cuda")
+    dab = torch.empty((2,), dtype=torch.float32, device="cuda")
+    pq.linear_bwd(desc, dY, X, W, bufs, dX, dW, dab, A=A, B=B, dA=dA, dB=dB)
+    torch.cuda.synchronize()
+    if T == 0:
+        assert not host(dW).any() and not host(dA).any() and not host(dB).any() and not host(dab).any()
+        return
+    f = po.linear_fwd(c["X"], c["W"], 0.0, beta)
+    h = po.hp_int8_fwd(None, c["A"], c["B"], bf16=True, q_gamma=(f["q"], f["gamma"]))
+    g = po.linear_bwd(c["dY"], c["X"], c["W"], 0.0, beta, f)
     dY64 = c["dY"].astype(np.float64)
-    dW_rows = 0.2 * ((dY64[:, ch] / gamma.astype(np.float64)[:, None]).T @ q.astype(np.float64))
-    H = c["X"].astype(np.float64) @ c["A"].astype(np.float64).T
-    dB_rows = 2.0 * (dY64[:, ch].T @ H)
-    eW, eB = relerr(got["dW"][ch], dW_rows), relerr(got["dB"][ch], dB_rows)
-    say(f"  errors: Y={eY:.2e} dX={eX:.2e} dW={eW:.2e} dB={eB:.2e}")
-    assert max(eY, eX, eW, eB) <= TOL[True]
+    gh = po.hp_int8_bwd(alpha * dY64, h)
+    errs = {}
+    errs.update(report("Y", host(Y), f["Y1"].astype(np.float64) + alpha * h["Yhp"].astype(np.float64)))
+    errs.update(report("dX", host(dX), g["dX"] + gh["dX"]))
+    errs.update(report("dW", host(dW), g["dW"], per_channel=True))
+    errs.update(report("dA", host(dA), gh["dA"], per_channel=True))
+    errs.update(report("dB", host(dB), gh["dB"]))
+    Yhp = h["Yhp"].astype(np.float64)
+    errs.update(scalar_errs(host(dab), float((dY64 * Yhp).sum()), g["dbeta"], np.sqrt(((dY64 * Yhp) ** 2).sum()),
+                            np.sqrt(((dY64 * f["Y1_nobeta"]) ** 2).sum())))
+    assert_errs(errs, TOL[True])
