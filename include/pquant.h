@@ -108,9 +108,12 @@ int pq_rmsnorm_bwd_static(const void* dXn, const void* X, const void* gain, cons
 
 /* Weight statistics + binariser + packer (Sec. 3.1 eqs. for W^INT1, mu, lambda; App. A packing).
  * mu and lambda are fp64 sums divided in fp64 and rounded once to fp32; bit = [W >= mu] (so W == mu
- * maps to +1).  packed [N][K/32] uint32: bit j of word w <-> column 32 w + j, 1 <-> +1 (the same byte
+ * maps to +1).  packed [N][ceil(K/32)] uint32: bit j of word w <-> column 32 w + j, 1 <-> +1 (the same byte
  * stream as 8 weights per byte, LSB first).  packed_t, if not NULL, receives the transposed packing
- * [K][N/32] (bit j of word w <-> row 32 w + j; needs N % 32 == 0).  mu_lambda [2] fp32 out.
+ * [K][ceil(N/32)] (bit j of word w <-> row 32 w + j).  mu_lambda [2] fp32 out.
+ * K must be a multiple of 4 and N*K of 8.  Widths that are not whole words (Table 1: D_ff - r = 5076 for the 1.3B
+ * model) are padded: bits beyond column K - 1 (row N - 1 in packed_t) are 1 (+1); they take no part in mu or
+ * lambda and only ever meet an activation code of zero.
  * workspace: at least pq_pack_workspace_bytes(N, K) bytes of scratch. */
 size_t pq_pack_workspace_bytes(int32_t N, int32_t K);
 int pq_pack_sign(const void* W, int32_t w_dtype, int32_t N, int32_t K, uint32_t* packed,
@@ -220,7 +223,9 @@ int pq_hp_int8_bwd(const void* dY, const void* Xt, int32_t dtype, int32_t T, int
  *   Up, Gate [E][r][d], Down [E][d][r], Wr [E][d] bf16;  Y [T][d] bf16 out.
  *   Backward (STE as in pq_linear_bwd): dX [T][d] bf16; dW_up, dW_gate [F][d], dW_down [d][F], dUp,
  *   dGate [E][r][d], dDown [E][d][r], dWr [E][d] fp32; dalpha_dbeta [2] fp32.
- * bf16 I/O only; d and F multiples of 32, r a multiple of 8, E <= 64. */
+ * bf16 I/O only; d a multiple of 32, F a multiple of 4, r a multiple of 8, E <= 64.  An F that is not a multiple of 32
+ * (Table 1: D_ff - r = 5076 for the 1.3B model) is padded to whole packed words inside the library: the padded hidden
+ * units carry zero codes and zero gradients and take no part in mu, lambda or any sum; the caller's tensors keep F. */
 typedef struct pq_ffn_desc {
   int32_t tokens, d_model, d_ffn, hp_rank, n_experts, top_k, io_dtype;
   float alpha, beta;

@@ -175,8 +175,8 @@ def rmsnorm_bwd(dXn, X, gain, rstd, ws=None):
 
 def pack_sign(W, transposed=False):
     N, K = W.shape
-    P = torch.empty((N, K // 32), dtype=torch.int32, device=W.device)
-    Pt = torch.empty((K, N // 32), dtype=torch.int32, device=W.device) if transposed else None
+    P = torch.empty((N, (K + 31) // 32), dtype=torch.int32, device=W.device)
+    Pt = torch.empty((K, (N + 31) // 32), dtype=torch.int32, device=W.device) if transposed else None
     ml = torch.empty((2,), dtype=torch.float32, device=W.device)
     nws = lib().pq_pack_workspace_bytes(N, K)
     ws = _bytes(nws, W.device)

@@ -294,8 +294,8 @@ extern "C" int pq_pack_sign(const void* W, int32_t w_dtype, int32_t N, int32_t K
                             void* stream) {
   if (int e = check_dtype(w_dtype)) return e;
   PQ_REQUIRE(N > 0 && K > 0, PQ_ERR_BAD_ARG, "bad size N=%d K=%d", N, K);
-  PQ_REQUIRE(K % 32 == 0, PQ_ERR_SHAPE, "K=%d must be a multiple of 32", K);
-  PQ_REQUIRE(packed_t == nullptr || N % 32 == 0, PQ_ERR_SHAPE, "transposed packing needs N=%d %% 32 == 0", N);
+  PQ_REQUIRE(K % 4 == 0, PQ_ERR_SHAPE, "K=%d must be a multiple of 4", K);
+  PQ_REQUIRE(((size_t)N * K) % 8 == 0, PQ_ERR_SHAPE, "N*K=%zu must be a multiple of 8", (size_t)N * K);
   PQ_REQUIRE(W && packed && mu_lambda && workspace, PQ_ERR_BAD_ARG, "NULL buffer");
   PQ_REQUIRE(aligned16(W) && aligned16(workspace), PQ_ERR_SHAPE, "W and workspace must be 16-byte aligned");
   PQ_REQUIRE(workspace_bytes >= pq_pack_workspace_bytes(N, K), PQ_ERR_WORKSPACE, "workspace too small: %zu < %zu",

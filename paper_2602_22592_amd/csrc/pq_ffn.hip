@@ -34,7 +34,9 @@ struct ffn_layout {
 ffn_layout make_layout(const pq_ffn_desc& d) {
   ffn_layout L;
   memset(&L, 0, sizeof(L));
-  const size_t T = d.tokens, D = d.d_model, F = d.d_ffn, r = d.hp_rank, E = d.n_experts, S = T * (size_t)d.top_k;
+  // F here is the padded width of the 1-bit FFN's hidden state: d_ffn rounded up to whole packed words (Table 1's
+  // 5076 -> 5088); every internal buffer uses it as its row length, the padded columns hold zero codes / gradients
+  const size_t T = d.tokens, D = d.d_model, F = ((size_t)d.d_ffn + 31) / 32 * 32, r = d.hp_rank, E = d.n_experts, S = T * (size_t)d.top_k;
   cursor c;
   L.ml_up = c.take(8); L.ml_gate = c.take(8); L.ml_down = c.take(8);
   L.P_up = c.take(F * D / 8); L.Pt_up = c.take(F * D / 8);
@@ -55,7 +57,7 @@ ffn_layout make_layout(const pq_ffn_desc& d) {
   L.red_a = w.take(sizeof(double) * (size_t)L.n_red_a);
   L.red_b = w.take(sizeof(double) * (size_t)L.n_red_b);
   size_t sk = 0;
-  const int Ti = d.tokens, Di = d.d_model, Fi = d.d_ffn;
+  const int Ti = d.tokens, Di = d.d_model, Fi = (int)F;
   const int shapes[4][3] = {{Di, Fi, Ti}, {Ti, Fi, Di}, {Ti, Di, Fi}, {Fi, Di, Ti}};
   for (const auto& sh : shapes) {
     if (sh[0] <= 0 || sh[1] <= 0) continue;
@@ -78,7 +80,7 @@ int check_ffn(const pq_ffn_desc* d) {
   PQ_REQUIRE(d != nullptr, PQ_ERR_BAD_ARG, "desc is NULL");
   PQ_REQUIRE(d->tokens >= 0 && d->d_model > 0 && d->d_ffn > 0 && d->hp_rank > 0, PQ_ERR_BAD_ARG, "bad dimension");
   PQ_REQUIRE(d->io_dtype == PQ_BF16, PQ_ERR_DTYPE, "the FFN path runs on bf16 I/O only");
-  PQ_REQUIRE(d->d_model % 32 == 0 && d->d_ffn % 32 == 0, PQ_ERR_SHAPE, "d_model=%d and d_ffn=%d must be multiples of 32",
+  PQ_REQUIRE(d->d_model % 32 == 0 && d->d_ffn % 4 == 0, PQ_ERR_SHAPE, "d_model=%d must be a multiple of 32 and d_ffn=%d of 4",
              d->d_model, d->d_ffn);
   PQ_REQUIRE(d->hp_rank % 8 == 0, PQ_ERR_SHAPE, "hp_rank=%d must be a multiple of 8", d->hp_rank);
   PQ_REQUIRE(d->n_experts >= 1 && d->n_experts <= 64, PQ_ERR_BAD_ARG, "n_experts=%d must be in 1..64", d->n_experts);
@@ -125,7 +127,8 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
   hipStream_t s = (hipStream_t)stream;
   char* cx = (char*)ctx;
   char* ws = (char*)workspace;
-  const int T = d->tokens, D = d->d_model, F = d->d_ffn, r = d->hp_rank, E = d->n_experts, k = d->top_k, S = T * k;
+  // Fv: the width of the 1-bit FFN as the caller's weights have it; F: that width in whole packed words
+  const int T = d->tokens, D = d->d_model, Fv = d->d_ffn, F = (Fv + 31) / 32 * 32, r = d->hp_rank, E = d->n_experts, k = d->top_k, S = T * k;
   double* part = (double*)(ws + L.stat);
   void* sk = ws + L.splitk;
 
@@ -133,14 +136,17 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
   float* gx = (float*)(cx + L.gx);
   const bool combo = T > 0 && D <= 8192;   // the quantiser of X shares the launch of W_up's statistics
   if (combo) {
-    const size_t n = (size_t)F * D;
+    const size_t n = (size_t)Fv * D;
     const int nb = pq_stats_blocks(n);
     if (int e = pq_launch_wstats_quant(W_up, n, part, nb, X, T, D, Xq, gx, (uint16_t*)(cx + L.Xt), s)) return e;
-    if (int e = pq_launch_pack(W_up, PQ_BF16, F, D, part, nb, (uint32_t*)(cx + L.P_up), (uint32_t*)(cx + L.Pt_up),
+    if (int e = pq_launch_pack(W_up, PQ_BF16, Fv, D, part, nb, (uint32_t*)(cx + L.P_up), (uint32_t*)(cx + L.Pt_up),
                                (float*)(cx + L.ml_up), s)) return e;
-  } else if (int e = pack_weight(W_up, F, D, cx, L.P_up, L.Pt_up, L.ml_up, part, s)) return e;
-  if (int e = pack_weight(W_gate, F, D, cx, L.P_gate, L.Pt_gate, L.ml_gate, part, s)) return e;
-  if (int e = pack_weight(W_down, D, F, cx, L.P_down, L.Pt_down, L.ml_down, part, s)) return e;
+  } else if (int e = pack_weight(W_up, Fv, D, cx, L.P_up, L.Pt_up, L.ml_up, part, s)) return e;
+  // the packer pads partial words with +1 bits (columns Fv.. of P_down's rows, rows Fv.. of the transposed packings of
+  // W_up and W_gate); rows Fv.. of P_up, P_gate and Pt_down are never written: whatever they hold lands in columns of
+  // U, G and dHd that the gated unit and its backward replace by zeros
+  if (int e = pack_weight(W_gate, Fv, D, cx, L.P_gate, L.Pt_gate, L.ml_gate, part, s)) return e;
+  if (int e = pack_weight(W_down, D, Fv, cx, L.P_down, L.Pt_down, L.ml_down, part, s)) return e;
   if (T == 0)  // no tokens: leave empty expert segments behind so that a backward call is well defined
     return pq_launch_route((const int*)(cx + L.idx), 0, E, (int*)(cx + L.counts), (int*)(cx + L.offsets), (int*)(cx + L.perm),
                            (int*)(cx + L.inv), s);
@@ -159,7 +165,7 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
   }
   int8_t* Hq = (int8_t*)(cx + L.Hq);
   float* gh = (float*)(cx + L.gh);
-  if (int e = pq_launch_swiglu_quant(cx + L.U, cx + L.G, T, F, Hq, gh, cx + L.Ht, s)) return e;
+  if (int e = pq_launch_swiglu_quant(cx + L.U, cx + L.G, T, F, Fv, Hq, gh, cx + L.Ht, s)) return e;
   {  // Y = beta * (lambda_d / gamma_h) * acc
     pq_operand A{Hq, F, PQ_SRC_KC8, nullptr};
     pq_operand B{cx + L.P_down, F / 8, PQ_SRC_BITS8, nullptr};
@@ -217,7 +223,7 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
   hipStream_t s = (hipStream_t)stream;
   const char* cx = (const char*)ctx;
   char* ws = (char*)workspace;
-  const int T = d->tokens, D = d->d_model, F = d->d_ffn, r = d->hp_rank, E = d->n_experts, k = d->top_k, S = T * k;
+  const int T = d->tokens, D = d->d_model, Fv = d->d_ffn, F = (Fv + 31) / 32 * 32, r = d->hp_rank, E = d->n_experts, k = d->top_k, S = T * k;
   void* sk = ws + L.splitk;
   const float* ml_up = (const float*)(cx + L.ml_up);
   const float* ml_gate = (const float*)(cx + L.ml_gate);
@@ -229,7 +235,8 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
     pq_operand A{dY, D, PQ_SRC_KS16, nullptr};
     pq_operand B{cx + L.Ht, F, PQ_SRC_KS16, nullptr};
     pq_epilogue e = epi0();
-    e.C = dW_down; e.ldc = F; e.out_kind = PQ_OUT_F32; e.scale = d->beta;
+    e.C = dW_down; e.ldc = Fv; e.out_kind = PQ_OUT_F32; e.scale = d->beta;
+    if (Fv != F) e.n_limit = Fv;                     // the padded columns (zero: Ht is zero there) are not part of dW_down
     e.sign_bytes = (const uint8_t*)(cx + L.P_down); e.ld_sign = F / 8; e.partials = red_b;
     if (int err = pq_launch_gemm(0, D, F, T, A, B, e, s, PQP_GEMM_DW, sk)) return err;
   }
@@ -241,7 +248,7 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
       e.C = ws + L.dHd; e.ldc = F; e.out_kind = PQ_OUT_BF16; e.scale = d->beta; e.dev_scale = ml_down + 1;
       if (int err = pq_launch_gemm(0, T, F, D, A, B, e, s, PQP_GEMM_DX, sk)) return err;
     }
-    if (int err = pq_launch_swiglu_bwd(ws + L.dHd, cx + L.U, cx + L.G, (size_t)T * F, ws + L.dU, ws + L.dG, s)) return err;
+    if (int err = pq_launch_swiglu_bwd(ws + L.dHd, cx + L.U, cx + L.G, T, F, Fv, ws + L.dU, ws + L.dG, s)) return err;
     {  // dX = lambda_u dU S_u + lambda_g dG S_g
       pq_operand A{ws + L.dU, F, PQ_SRC_KC16, nullptr};
       pq_operand B{cx + L.Pt_up, F / 8, PQ_SRC_BITS16, nullptr};
@@ -258,6 +265,7 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
     pq_operand B{cx + L.Xt, D, PQ_SRC_KS16, nullptr};
     pq_epilogue e = epi0();
     e.ldc = D; e.out_kind = PQ_OUT_F32;
+    if (Fv != F) e.m_limit = Fv;                     // rows Fv.. of the padded product do not exist in dW_up / dW_gate
     pq_operand A{ws + L.dU, F, PQ_SRC_KS16, nullptr};
     e.C = dW_up;
     if (int err = pq_launch_gemm(0, F, D, T, A, B, e, s, PQP_GEMM_DW, sk)) return err;

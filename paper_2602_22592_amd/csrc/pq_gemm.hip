@@ -239,6 +239,7 @@ __device__ __forceinline__ float load_io(const void* p, int kind, size_t i) {
 template <typename AccT>
 __device__ __forceinline__ void epi_elem(const pq_epilogue& e, epi_state& st, int m, int n, AccT acc, int acc_i) {
   const size_t ci = (size_t)m * e.ldc + n;
+  if ((e.m_limit > 0 && m >= e.m_limit) || (e.n_limit > 0 && n >= e.n_limit)) return;
   if (e.out_kind == PQ_OUT_I32) {
     ((int*)e.C)[ci] = acc_i;
     return;
@@ -290,9 +291,11 @@ template <bool INT8>
 __device__ __forceinline__ void epi_vec8(const pq_epilogue& e, epi_state& st, int m, int n, const uint4& r0,
                                          const uint4& r1, float row_scale = __builtin_nanf("")) {
   const size_t ci = (size_t)m * e.ldc + n;
+  if ((e.m_limit > 0 && m >= e.m_limit) || (e.n_limit > 0 && n >= e.n_limit)) return;
+  const bool half = e.n_limit > 0 && n + 8 > e.n_limit;   // only the first four columns exist
   if (e.out_kind == PQ_OUT_I32) {
     *reinterpret_cast<uint4*>((int*)e.C + ci) = r0;
-    *reinterpret_cast<uint4*>((int*)e.C + ci + 4) = r1;
+    if (!half) *reinterpret_cast<uint4*>((int*)e.C + ci + 4) = r1;
     return;
   }
   float acc[8];
@@ -339,12 +342,15 @@ __device__ __forceinline__ void epi_vec8(const pq_epilogue& e, epi_state& st, in
     for (int j = 0; j < 8; ++j) val[j] += c[j];
   }
   if (e.out_kind == PQ_OUT_BF16) {
-    *reinterpret_cast<uint4*>((uint16_t*)e.C + ci) =
-        make_uint4(pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3]), pack_bf16x2(val[4], val[5]),
-                   pack_bf16x2(val[6], val[7]));
+    if (half)
+      *reinterpret_cast<uint2*>((uint16_t*)e.C + ci) = make_uint2(pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3]));
+    else
+      *reinterpret_cast<uint4*>((uint16_t*)e.C + ci) =
+          make_uint4(pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3]), pack_bf16x2(val[4], val[5]),
+                     pack_bf16x2(val[6], val[7]));
   } else {
     *reinterpret_cast<float4*>((float*)e.C + ci) = make_float4(val[0], val[1], val[2], val[3]);
-    *reinterpret_cast<float4*>((float*)e.C + ci + 4) = make_float4(val[4], val[5], val[6], val[7]);
+    if (!half) *reinterpret_cast<float4*>((float*)e.C + ci + 4) = make_float4(val[4], val[5], val[6], val[7]);
   }
 }
 
@@ -1720,6 +1726,8 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
   memset(&ph2, 0, sizeof(ph2));
   if (phase2) ph2 = *phase2;
   if (ph2.K2 > 0 && (engine == 1 || grp.mode)) return pq_set_error(PQ_ERR_BAD_ARG, "a fused second contraction needs the plain MFMA engine");
+  if ((epi.n_limit > 0 || epi.m_limit > 0) && (epi.accumulate || epi.maskW || epi.dot_comp || epi.n_limit % 4 != 0))
+    return pq_set_error(PQ_ERR_BAD_ARG, "store limits go with plain stores and a column limit that is a multiple of 4");
   if (grp.mode && engine == 1) return pq_set_error(PQ_ERR_DTYPE, "grouped GEMMs run on the MFMA engine only (bf16 I/O)");
   // plain rank-128 products over many rows: the streaming kernel (callers that want per-block partial sums or the
   // slabs of a split contraction choose it themselves, since it changes how many of those there are)

@@ -100,6 +100,10 @@ struct pq_epilogue {
   int mask_kind;              // PQ_OUT_F32 / PQ_OUT_BF16
   const float* mu_dev;        // device pointer to mu
   float tau;
+  // optional store limits for outputs narrower than the computed tile range (padded widths): rows >= m_limit and
+  // columns >= n_limit are computed but not stored (0 = no limit; n_limit % 4 == 0; plain stores only: no
+  // accumulate, mask or dot_comp, whose loads would run past a row's end)
+  int m_limit, n_limit;
 };
 
 // Optional second contraction accumulated into the same output tile (the rank-r branch fused into
@@ -184,8 +188,9 @@ int pq_launch_decode_ffn(int L, int D, int F, int r, int E, int topk, float alph
 // ---- pq_moe.hip ---------------------------------------------------------------------------
 int pq_launch_route(const int* idx, int S, int E, int* counts, int* offsets, int* perm, int* inv, hipStream_t s);
 int pq_launch_gather_rows(const void* src, const int* perm, int k, int S, int d, void* dst, hipStream_t s);
-int pq_launch_swiglu_quant(const void* U, const void* G, int T, int F, int8_t* Hq, float* gamma, void* Ht, hipStream_t s);
-int pq_launch_swiglu_bwd(const void* dHd, const void* U, const void* G, size_t n, void* dU, void* dG, hipStream_t s);
+// rows of F elements of which the first Fv exist (padded widths): the rest is written as zero
+int pq_launch_swiglu_quant(const void* U, const void* G, int T, int F, int Fv, int8_t* Hq, float* gamma, void* Ht, hipStream_t s);
+int pq_launch_swiglu_bwd(const void* dHd, const void* U, const void* G, int T, int F, int Fv, void* dU, void* dG, hipStream_t s);
 int pq_launch_expert_act(const void* ue, const void* ge, size_t n, void* a, hipStream_t s);
 int pq_launch_expert_act_bwd(const void* da, const void* ue, const void* ge, const void* a, const int* perm, const float* gate,
                              float alpha, int S, int r, void* du, void* dg, void* as, hipStream_t s);

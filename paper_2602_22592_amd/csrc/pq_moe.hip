@@ -15,7 +15,9 @@ __device__ __forceinline__ void unpack8(const uint4& u, float* f) {
 __device__ __forceinline__ uint4 pack8(const float* f) {
   return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
 }
-__device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + expf(-x)); }
+// sigmoid through the hardware exponential and reciprocal (about 2 ulp each): with a correctly rounded expf and an IEEE
+// division per element the element-wise kernels of the gated unit are bound by their instruction count, not by memory
+__device__ __forceinline__ float sigmoidf_(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 __device__ __forceinline__ float siluf_(float x) { return x * sigmoidf_(x); }
 __device__ __forceinline__ float dsiluf_(float x) {
   const float s = sigmoidf_(x);
@@ -90,9 +92,12 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const uint16_t* __rest
 
 // ---- the gated unit with fused AbsMax re-quantisation (one wavefront per token) -------------
 //   Hd = silu(G) * U in fp32; gamma_h = 128 / max(|Hd|, 1e-5); Hq = codes; Ht = bf16(Hq / gamma_h)
+// Rows are F elements apart; only the first Fv columns exist (Fv % 4 == 0): the others are written as zero codes,
+// whatever U and G hold there (a width that is not a multiple of 32 is padded, Table 1: 5076 -> 5088).
+// All of a row's vectors are requested before the first is used, so a token costs one memory latency.
 template <int NV>
 __global__ __launch_bounds__(256) void swiglu_quant_kernel(const uint16_t* __restrict__ U, const uint16_t* __restrict__ G,
-                                                           int T, int F, int8_t* __restrict__ Hq, float* __restrict__ gamma,
+                                                           int T, int F, int Fv, int8_t* __restrict__ Hq, float* __restrict__ gamma,
                                                            uint16_t* __restrict__ Ht) {
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (t >= T) return;
@@ -101,32 +106,40 @@ __global__ __launch_bounds__(256) void swiglu_quant_kernel(const uint16_t* __res
   const int nvec = F / 8;
   float hd[NV > 0 ? NV : 1][8];
   float amax = 0.0f;
-  auto eval = [&](int c, float* h) {
+  auto gated = [&](const uint4& u, const uint4& g, int c, float* h) {
     float uf[8], gf[8];
-    unpack8(u4[c], uf);
-    unpack8(g4[c], gf);
+    unpack8(u, uf);
+    unpack8(g, gf);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) h[j] = siluf_(gf[j]) * uf[j];
+    for (int j = 0; j < 8; ++j) h[j] = (c * 8 + j < Fv) ? siluf_(gf[j]) * uf[j] : 0.0f;
   };
   if constexpr (NV > 0) {
+    uint4 ur[NV], gr[NV];
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       // unconditional (lanes past the end repeat the last vector, which cannot change the maximum): loads under
       // a branch would each get a wait of their own
-      eval(min(i * 64 + lane, nvec - 1), hd[i]);
+      const int c = min(i * 64 + lane, nvec - 1);
+      ur[i] = u4[c];
+      gr[i] = g4[c];
+    }
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      gated(ur[i], gr[i], min(i * 64 + lane, nvec - 1), hd[i]);
 #pragma unroll
       for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(hd[i][j]));
     }
   } else {
     for (int c = lane; c < nvec; c += 64) {
       float h[8];
-      eval(c, h);
+      gated(u4[c], g4[c], c, h);
 #pragma unroll
       for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(h[j]));
     }
   }
   amax = wave_max(amax);
   const float g = 128.0f / fmaxf(amax, 1e-5f);
+  const float ginv = 1.0f / g;                       // q / gamma as q * (1 / gamma): one division per token
   if (lane == 0) gamma[t] = g;
   auto emit = [&](int c, const float* h) {
     int q[8];
@@ -137,7 +150,7 @@ __global__ __launch_bounds__(256) void swiglu_quant_kernel(const uint16_t* __res
     *reinterpret_cast<uint2*>(Hq + (size_t)t * F + (size_t)c * 8) = make_uint2(w0, w1);
     float o[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) o[j] = (float)q[j] / g;
+    for (int j = 0; j < 8; ++j) o[j] = __fmul_rn((float)q[j], ginv);
     *reinterpret_cast<uint4*>(Ht + (size_t)t * F + (size_t)c * 8) = pack8(o);
   };
   if constexpr (NV > 0) {
@@ -149,28 +162,44 @@ __global__ __launch_bounds__(256) void swiglu_quant_kernel(const uint16_t* __res
   } else {
     for (int c = lane; c < nvec; c += 64) {
       float h[8];
-      eval(c, h);
+      gated(u4[c], g4[c], c, h);
       emit(c, h);
     }
   }
 }
 
-// dU = dHd * silu(G), dG = dHd * U * silu'(G)   (element-wise over T*F, 8 per thread)
+// dU = dHd * silu(G), dG = dHd * U * silu'(G)   (element-wise over rows of F elements of which the first Fv exist; the
+// others are written as zeros; two vectors of 8 per thread and pass)
 __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const uint16_t* __restrict__ dHd, const uint16_t* __restrict__ U,
-                                                         const uint16_t* __restrict__ G, size_t nvec, uint16_t* __restrict__ dU,
-                                                         uint16_t* __restrict__ dG) {
-  for (size_t c = (size_t)blockIdx.x * 256 + threadIdx.x; c < nvec; c += (size_t)gridDim.x * 256) {
-    float dh[8], uf[8], gf[8], du[8], dg[8];
-    unpack8(reinterpret_cast<const uint4*>(dHd)[c], dh);
-    unpack8(reinterpret_cast<const uint4*>(U)[c], uf);
-    unpack8(reinterpret_cast<const uint4*>(G)[c], gf);
+                                                         const uint16_t* __restrict__ G, size_t nvec, int F, int Fv,
+                                                         uint16_t* __restrict__ dU, uint16_t* __restrict__ dG) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  const int vpr = F / 8;                             // vectors per row
+  for (size_t c0 = (size_t)blockIdx.x * 256 + threadIdx.x; c0 < nvec; c0 += 2 * stride) {
+    const size_t c1 = c0 + stride;
+    const bool two = c1 < nvec;
+    const size_t cb = two ? c1 : c0;
+    const uint4 r0[3] = {reinterpret_cast<const uint4*>(dHd)[c0], reinterpret_cast<const uint4*>(U)[c0], reinterpret_cast<const uint4*>(G)[c0]};
+    const uint4 r1[3] = {reinterpret_cast<const uint4*>(dHd)[cb], reinterpret_cast<const uint4*>(U)[cb], reinterpret_cast<const uint4*>(G)[cb]};
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      du[j] = dh[j] * siluf_(gf[j]);
-      dg[j] = dh[j] * uf[j] * dsiluf_(gf[j]);
+    for (int q = 0; q < 2; ++q) {
+      if (q == 1 && !two) break;
+      const size_t c = q ? c1 : c0;
+      const int col = (int)(c % (size_t)vpr) * 8;
+      float dh[8], uf[8], gf[8], du[8], dg[8];
+      unpack8(q ? r1[0] : r0[0], dh);
+      unpack8(q ? r1[1] : r0[1], uf);
+      unpack8(q ? r1[2] : r0[2], gf);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float sg = sigmoidf_(gf[j]);
+        const bool ok = col + j < Fv;
+        du[j] = ok ? dh[j] * (gf[j] * sg) : 0.0f;
+        dg[j] = ok ? dh[j] * uf[j] * (sg * (1.0f + gf[j] * (1.0f - sg))) : 0.0f;
+      }
+      reinterpret_cast<uint4*>(dU)[c] = pack8(du);
+      reinterpret_cast<uint4*>(dG)[c] = pack8(dg);
     }
-    reinterpret_cast<uint4*>(dU)[c] = pack8(du);
-    reinterpret_cast<uint4*>(dG)[c] = pack8(dg);
   }
 }
 
@@ -455,27 +484,28 @@ int pq_launch_gather_rows(const void* src, const int* perm, int k, int S, int d,
   return PQ_OK;
 }
 
-int pq_launch_swiglu_quant(const void* U, const void* G, int T, int F, int8_t* Hq, float* gamma, void* Ht, hipStream_t s) {
+int pq_launch_swiglu_quant(const void* U, const void* G, int T, int F, int Fv, int8_t* Hq, float* gamma, void* Ht, hipStream_t s) {
   if (T == 0) return PQ_OK;
   pq_prof_scope prof(PQP_SWIGLU, s);
   const int per_lane = (F / 8 + 63) / 64;
   dim3 grid((T + 3) / 4), block(256);
   const uint16_t* u = (const uint16_t*)U;
   const uint16_t* g = (const uint16_t*)G;
-  if (per_lane <= 4) swiglu_quant_kernel<4><<<grid, block, 0, s>>>(u, g, T, F, Hq, gamma, (uint16_t*)Ht);
-  else if (per_lane <= 12) swiglu_quant_kernel<12><<<grid, block, 0, s>>>(u, g, T, F, Hq, gamma, (uint16_t*)Ht);
-  else swiglu_quant_kernel<0><<<grid, block, 0, s>>>(u, g, T, F, Hq, gamma, (uint16_t*)Ht);
+  if (per_lane <= 4) swiglu_quant_kernel<4><<<grid, block, 0, s>>>(u, g, T, F, Fv, Hq, gamma, (uint16_t*)Ht);
+  else if (per_lane <= 12) swiglu_quant_kernel<12><<<grid, block, 0, s>>>(u, g, T, F, Fv, Hq, gamma, (uint16_t*)Ht);
+  else swiglu_quant_kernel<0><<<grid, block, 0, s>>>(u, g, T, F, Fv, Hq, gamma, (uint16_t*)Ht);
   PQ_CHECK_LAUNCH("swiglu_quant_kernel");
   return PQ_OK;
 }
 
-int pq_launch_swiglu_bwd(const void* dHd, const void* U, const void* G, size_t n, void* dU, void* dG, hipStream_t s) {
+int pq_launch_swiglu_bwd(const void* dHd, const void* U, const void* G, int T, int F, int Fv, void* dU, void* dG, hipStream_t s) {
+  const size_t n = (size_t)T * F;
   if (n == 0) return PQ_OK;
   pq_prof_scope prof(PQP_SWIGLU, s);
   const size_t nvec = n / 8;
-  size_t blocks = (nvec + 255) / 256;
+  size_t blocks = (nvec + 511) / 512;                // two vectors per thread and pass
   if (blocks > 8192) blocks = 8192;
-  swiglu_bwd_kernel<<<(unsigned)blocks, 256, 0, s>>>((const uint16_t*)dHd, (const uint16_t*)U, (const uint16_t*)G, nvec,
+  swiglu_bwd_kernel<<<(unsigned)blocks, 256, 0, s>>>((const uint16_t*)dHd, (const uint16_t*)U, (const uint16_t*)G, nvec, F, Fv,
                                                     (uint16_t*)dU, (uint16_t*)dG);
   PQ_CHECK_LAUNCH("swiglu_bwd_kernel");
   return PQ_OK;

@@ -565,7 +565,12 @@ __device__ __forceinline__ uint32_t sign_byte<float>(const float* p, float mu) {
   return b;
 }
 
-template <typename T>
+// RAGGED: K is a multiple of 4 but not of 32, or N is not a multiple of 32 (Table 1: D_ff - r = 5076).  Rows may then start
+// on 8-byte (bf16) boundaries only and end inside a lane's 8 weights, so the weights are fetched as two halves of four, each
+// wholly inside or wholly outside its row; everything outside (columns K..Kp-1 of a packed row, Kp = K rounded up to whole
+// words, and rows N.. of the last word of the transposed packing) is packed as +1: a padded position only ever meets an
+// activation code (or gradient) of zero.
+template <typename T, bool RAGGED>
 __global__ __launch_bounds__(256) void pack_sign_kernel(const T* __restrict__ W, int N, int K,
                                                         const double* __restrict__ partials, int G,
                                                         uint8_t* __restrict__ Pbytes,
@@ -577,6 +582,7 @@ __global__ __launch_bounds__(256) void pack_sign_kernel(const T* __restrict__ W,
   // the weights do not depend on the statistics: their eight chunks are requested first, so that their latency and
   // the reduction of the partial sums overlap instead of standing in a row
   constexpr int NU = sizeof(T) == 2 ? 1 : 2;          // 16-byte loads per 8 weights
+  const int Kp = (K + 31) & ~31;
   const int n0 = blockIdx.y * 32, k0 = blockIdx.x * 512;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int k = k0 + lane * 8;
@@ -584,10 +590,24 @@ __global__ __launch_bounds__(256) void pack_sign_kernel(const T* __restrict__ W,
 #pragma unroll
   for (int rr = 0; rr < 8; ++rr) {
     const int row = n0 + w * 8 + rr;
-    const bool in = row < N && k < K;
-    const uint4* src = reinterpret_cast<const uint4*>(W + (in ? (size_t)row * K + k : (size_t)0));   // element (0, 0) always exists
+    if constexpr (RAGGED) {
+      // halves of four weights: 8 bytes (bf16) or 16 bytes (fp32), aligned because K % 4 == 0
+      const bool in0 = row < N && k + 4 <= K, in1 = row < N && k + 8 <= K;
+      const T* p0 = W + (in0 ? (size_t)row * K + k : (size_t)0);
+      const T* p1 = W + (in1 ? (size_t)row * K + k + 4 : (size_t)0);
+      if constexpr (sizeof(T) == 2) {
+        const uint2 a = *reinterpret_cast<const uint2*>(p0), b = *reinterpret_cast<const uint2*>(p1);
+        wv[rr][0] = make_uint4(a.x, a.y, b.x, b.y);
+      } else {
+        wv[rr][0] = *reinterpret_cast<const uint4*>(p0);
+        wv[rr][1] = *reinterpret_cast<const uint4*>(p1);
+      }
+    } else {
+      const bool in = row < N && k < K;
+      const uint4* src = reinterpret_cast<const uint4*>(W + (in ? (size_t)row * K + k : (size_t)0));   // element (0, 0) always exists
 #pragma unroll
-    for (int u = 0; u < NU; ++u) wv[rr][u] = src[u];
+      for (int u = 0; u < NU; ++u) wv[rr][u] = src[u];
+    }
   }
   double s = 0.0, a = 0.0;
   for (int i = threadIdx.x; i < G; i += 256) {
@@ -607,20 +627,24 @@ __global__ __launch_bounds__(256) void pack_sign_kernel(const T* __restrict__ W,
   }
   __syncthreads();
   const float mu = s_mu;
-  const size_t kb = (size_t)K / 8;
+  const size_t kb = (size_t)Kp / 8;
 #pragma unroll
   for (int rr = 0; rr < 8; ++rr) {
     const int rl = w * 8 + rr, row = n0 + rl;
-    uint32_t b = 0;
-    if (row < N && k < K) {
+    uint32_t b = RAGGED ? 0xFFu : 0u;
+    if (row < N && k < Kp) {
       b = sign_byte<T>(reinterpret_cast<const T*>(wv[rr]), mu);
+      if constexpr (RAGGED) {
+        if (k + 4 > K) b |= 0x0Fu;
+        if (k + 8 > K) b |= 0xF0u;
+      }
       Pbytes[(size_t)row * kb + (k >> 3)] = (uint8_t)b;
     }
     tileb[rl][lane] = (uint8_t)b;
   }
   if (Pt == nullptr) return;
   __syncthreads();
-  const size_t nw = (size_t)N / 32;
+  const size_t nw = ((size_t)N + 31) / 32;
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const int kk = threadIdx.x + h * 256;
@@ -636,13 +660,16 @@ __global__ __launch_bounds__(256) void pack_sign_kernel(const T* __restrict__ W,
 int pq_launch_pack(const void* W, int dtype, int N, int K, const double* partials, int nblocks,
                    uint32_t* P, uint32_t* Pt, float* mu_lambda, hipStream_t s) {
   pq_prof_scope prof(PQP_PACK, s);
-  dim3 grid((K + 511) / 512, (N + 31) / 32), block(256);
-  if (dtype == PQ_F32)
-    pack_sign_kernel<float><<<grid, block, 0, s>>>((const float*)W, N, K, partials, nblocks,
-                                                   (uint8_t*)P, Pt, mu_lambda);
-  else
-    pack_sign_kernel<uint16_t><<<grid, block, 0, s>>>((const uint16_t*)W, N, K, partials, nblocks,
-                                                      (uint8_t*)P, Pt, mu_lambda);
+  const int Kp = (K + 31) & ~31;
+  dim3 grid((Kp + 511) / 512, (N + 31) / 32), block(256);
+  const bool ragged = (K % 32 != 0) || (N % 32 != 0);
+  if (dtype == PQ_F32) {
+    if (ragged) pack_sign_kernel<float, true><<<grid, block, 0, s>>>((const float*)W, N, K, partials, nblocks, (uint8_t*)P, Pt, mu_lambda);
+    else pack_sign_kernel<float, false><<<grid, block, 0, s>>>((const float*)W, N, K, partials, nblocks, (uint8_t*)P, Pt, mu_lambda);
+  } else {
+    if (ragged) pack_sign_kernel<uint16_t, true><<<grid, block, 0, s>>>((const uint16_t*)W, N, K, partials, nblocks, (uint8_t*)P, Pt, mu_lambda);
+    else pack_sign_kernel<uint16_t, false><<<grid, block, 0, s>>>((const uint16_t*)W, N, K, partials, nblocks, (uint8_t*)P, Pt, mu_lambda);
+  }
   PQ_CHECK_LAUNCH("pack_sign_kernel");
   return PQ_OK;
 }

@@ -62,7 +62,9 @@ def check_ffn(c, top_k=1, alpha=2.0, beta=0.2):
 
 
 @pytest.mark.parametrize("T,D,F,E,r,k", [(200, 96, 160, 4, 8, 1), (200, 96, 160, 4, 8, 2), (700, 256, 544, 8, 32, 1),
-                                         (130, 64, 64, 2, 16, 2), (1, 32, 32, 8, 8, 1)])
+                                         (130, 64, 64, 2, 16, 2), (1, 32, 32, 8, 8, 1),
+                                         # hidden widths that are not whole packed words (like Table 1's 5076 = 158 * 32 + 20)
+                                         (200, 96, 172, 4, 8, 1), (130, 64, 52, 2, 16, 2), (300, 256, 500, 1, 32, 1)])
 def test_ffn_small(T, D, F, E, r, k):
     print(f"ffn T={T} d={D} F={F} E={E} r={r} k={k}", flush=True)
     check_ffn(wl.ffn_case(80 + T + k, T, D, F, E, r), top_k=k)
@@ -77,6 +79,14 @@ def test_ffn_scale_edge_cases():
 def test_ffn_config3_reduced_tokens():
     print("ffn config 3 shape at T=384 (d=2048, F=5504, E=8, r=32, top-1)", flush=True)
     check_ffn(wl.config3(tokens=384), top_k=1)
+
+
+@pytest.mark.parametrize("N", [1, 4])
+def test_ffn_paper_1p3b_shape_reduced_tokens(N):
+    """The paper's own 1.3B FFN (Table 1: D_model 2048, D_ff - r = 5076 one-bit hidden units, r = 384 per high-precision
+    branch; Sec. 3.3 / Sec. 4.4: N branches, one active per token) at 384 tokens."""
+    print(f"ffn paper-exact 1.3B shape, T=384, d=2048, F=5076, N={N} branches of r=384, top-1", flush=True)
+    check_ffn(wl.ffn_case(700 + N, 384, 2048, 5076, N, 384), top_k=1)
 
 
 def test_ffn_config3_full_size_sampled_tokens():

@@ -55,7 +55,10 @@ def test_quant_act_bit_exact(T, K, bf16):
 # ---------------------------------------------------------------------------- binariser / packer
 @pytest.mark.parametrize("N,K,bf16,tr", [(256, 256, False, True), (2048, 2048, True, True), (72, 96, True, False),
                                         (160, 544, False, True), (96, 5504, True, True), (32, 32, True, True),
-                                        (5504, 2048, True, True), (11008, 4096, True, False)])   # configs 3 and 4
+                                        (5504, 2048, True, True), (11008, 4096, True, False),   # configs 3 and 4
+                                        # widths that are not whole words (Table 1: D_ff - r = 5076): padded with +1 bits
+                                        (2048, 5076, True, True), (5076, 2048, True, True), (72, 44, False, True),
+                                        (37, 96, True, True), (50, 20, True, True)])
 def test_pack_sign_bit_exact(N, K, bf16, tr):
     say(f"pack_sign N={N} K={K} bf16={bf16} transposed={tr}")
     W = wl.normal(np.random.default_rng(200 + N), (N, K), 0.02, bf16)

@@ -47,7 +47,7 @@ def test_bad_arguments_are_refused_on_the_host(lib):
     assert lib.pq_quant_act(None, pq.PQ_BF16, 4, 64, fake, fake, None) == -1      # NULL
     assert lib.pq_quant_act(C.c_void_p(0x1004), pq.PQ_BF16, 4, 64, fake, fake, None) == -2   # alignment
     assert lib.pq_router_topk(fake, fake, pq.PQ_BF16, 4, 64, 8, 9, fake, fake, None, None) == -1
-    assert lib.pq_pack_sign(fake, pq.PQ_BF16, 40, 64, fake, fake, fake, fake, C.c_size_t(1 << 20), None) == -2
+    assert lib.pq_pack_sign(fake, pq.PQ_BF16, 40, 42, fake, fake, fake, fake, C.c_size_t(1 << 20), None) == -2   # K % 4
     assert lib.pq_pack_sign(fake, pq.PQ_BF16, 64, 64, fake, None, fake, fake, C.c_size_t(8), None) == -4
     d = pq.make_desc(16, 48, 64)
     assert lib.pq_linear_ctx_bytes(C.byref(d)) == 0                               # d_in % 32
