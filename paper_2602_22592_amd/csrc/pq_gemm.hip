@@ -20,6 +20,24 @@
 #include <type_traits>
 #include "pq_internal.h"
 
+#ifdef PQ_TRACE
+// Instrumented builds only (never the shipped library): cycle stamps of two workgroups of the streaming loops, taken at
+// points where no LDS read is outstanding (the stamp is a scalar-memory read and shares the counter LDS reads use).
+__device__ unsigned long long pq_trace_buf[6][8][64][2];   // [3 kernel kinds x 2 workgroups][wave][step][before/after the barrier]
+extern "C" int pq_debug_read_trace(unsigned long long* host_out) {
+  return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(pq_trace_buf), sizeof(unsigned long long) * 6 * 8 * 64 * 2) == hipSuccess ? 0 : -5;
+}
+#define PQ_STAMP(wg_slot, wave, step, which)                                                          \
+  do {                                                                                                \
+    if ((wg_slot) >= 0 && (step) < 64) {                                                              \
+      const unsigned long long t_ = __builtin_readcyclecounter();                                     \
+      if ((threadIdx.x & 63) == 0) pq_trace_buf[wg_slot][wave][step][which] = t_;                     \
+    }                                                                                                 \
+  } while (0)
+#else
+#define PQ_STAMP(wg_slot, wave, step, which) do { } while (0)
+#endif
+
 namespace {
 
 __device__ __forceinline__ uint4 mask4(const uint4& t, bool keep) {
@@ -382,6 +400,11 @@ typedef int pq_i32x2 __attribute__((ext_vector_type(2)));
 // The B fragment is passed as the first MFMA operand: the accumulator block is then the transpose of the usual
 // one, lane l holds output row (l & 31) and register v holds column 8 (v >> 2) + 4 (l >> 5) + (v & 3), i.e. runs of
 // four consecutive columns of one row, which the epilogue turns into 16-byte stores without going through LDS.
+// Wave priority for the phases between two barriers of a streaming loop: 3, 2, 1, 0 from the phase after the barrier to the
+// one before the next.  The two wavefronts of a SIMD then take turns: at equal priority the older one issues its group of
+// MFMAs, which drops it below the other, and so on -- without it the older wavefront wins every arbitration, runs through
+// its whole step and waits at the barrier while the younger one, alone on the SIMD, cannot hide its LDS latencies.
+#define PQ_SETPRIO(n) asm volatile("s_setprio %0" ::"n"(n))
 #define PQ_MFMA_BF16(acc, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %2, %1, %0" : "+v"(acc) : "v"(a), "v"(b))
 #define PQ_MFMA_I8(acc, a, b) asm volatile("v_mfma_i32_32x32x32_i8 %0, %2, %1, %0" : "+v"(acc) : "v"(a), "v"(b))
 
@@ -575,6 +598,10 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
     constexpr int AES = (AK == PQ_SRC_KC8) ? 1 : 2, BES = (BKIND == PQ_SRC_KC8) ? 1 : 2;
     const int wv = __builtin_amdgcn_readfirstlane(wave);
     const uint32_t lds0 = (uint32_t)(size_t)smem;
+#ifdef PQ_TRACE
+    const int trace_kind = INT8 ? 0 : (BBITS ? 1 : 2);
+    const int trace_slot = (blockIdx.y == 0 && blockIdx.z == 0 && (blockIdx.x == 0 || blockIdx.x == 100)) ? 2 * trace_kind + (blockIdx.x == 100) : -1;
+#endif
 
     // ---- direct loads: instruction block qi of an operand is 1 KB of its LDS tile --------------------
     const bool opB = !BREG && wv >= 4;                // wave-uniform
@@ -780,18 +807,24 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
         const bool wrap = (part == CH - 1);
         const int partn = wrap ? 0 : part + 1;
         const int bufn = wrap ? (buf == 2 ? 0 : buf + 1) : buf;
+        PQ_SETPRIO(2);
         read_a(G1, c1{}, so);
         G0.wait4();
         mfma_x(G0, fc, fn, prep(bq0, c1{}), prep(bq1, c1{}), c0{});
+        PQ_SETPRIO(1);
         read_a(G0, c2{}, so);
         G1.wait4();
         mfma_x(G1, fn, fc, prep(bq0, c2{}), prep(bq1, c2{}), c0{});
+        PQ_SETPRIO(0);
         read_a(G1, c3{}, so);
         G0.wait4();
         mfma_x(G0, fc, fn, prep(bq0, c3{}), prep(bq1, c3{}), c0{});
         G1.wait0();                                     // every LDS read of this step is complete
+        PQ_STAMP(trace_slot, wv, kt, 0);
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * IPW) : "memory");
         asm volatile("s_barrier" ::: "memory");
+        PQ_STAMP(trace_slot, wv, kt, 1);
+        PQ_SETPRIO(3);
         if (part == 0) issue_bits(min(chunk + 2, nch - 1), buf == 0 ? 2 : buf - 1);   // (buf + 2) mod 3
         issue(min(kt + NSTAGE, nkt - 1), st);           // refill the stage just read
         read_bits((uint32_t)(bufn * (BN * 32) + ((partn * RB) >> 4) * 512 + ((partn * RB) & 15)));   // past the last step: a place nobody uses
@@ -809,6 +842,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
         buf = bufn;
         chunk += wrap ? 1 : 0;
       }
+      PQ_SETPRIO(0);
       asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
 #undef PQ_EXPAND
 #undef PQ_MFMA_AB
@@ -871,22 +905,29 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
     }
     for (int kt = 0; kt < nkt; ++kt) {
       const uint32_t so = (kt & 1) ? (uint32_t)STAGE : 0u, sn = (kt & 1) ? 0u : (uint32_t)STAGE;
+      PQ_SETPRIO(2);
       read_set(F1, c1{}, so);
       F0.template wait<NR>();
       mfma_set(F0);
+      PQ_SETPRIO(1);
       read_set(F0, c2{}, so);
       F1.template wait<NR>();
       mfma_set(F1);
+      PQ_SETPRIO(0);
       read_set(F1, c3{}, so);
       F0.template wait<NR>();
       mfma_set(F0);
       F1.template wait<0>();                          // every LDS access of this step is complete
+      PQ_STAMP(trace_slot, wv, kt, 0);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the direct loads of the next stage have landed
       asm volatile("s_barrier" ::: "memory");
+      PQ_STAMP(trace_slot, wv, kt, 1);
+      PQ_SETPRIO(3);
       if (kt + 2 < nkt) issue(kt + 2, kt & 1);
       if (kt + 1 < nkt) read_set(F0, c0{}, sn);
       mfma_set(F1);
     }
+    PQ_SETPRIO(0);
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     }
 #endif
@@ -978,15 +1019,16 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
       sa2.load(ph2.A2, kn, ph2.K2);
       sb2.load(ph2.B2, kn, ph2.K2);
       __syncthreads();                               // this stage is complete; the other one is free again
+      read_frags(stage, 0, af[0], bf[0]);
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) {
-        read_frags(stage, ks, af[0], bf[0]);
+      for (int ks = 0; ks < NKS; ++ks) {             // the fragments of sub-step ks + 1 are read under the MFMAs of sub-step ks
+        if (ks + 1 < NKS) read_frags(stage, ks + 1, af[(ks + 1) & 1], bf[(ks + 1) & 1]);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
-            accf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, bf[0][j]),
-                                                                 __builtin_bit_cast(bf16x8_t, af[0][i]), accf[i][j], 0, 0, 0);
+            accf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, bf[ks & 1][j]),
+                                                                 __builtin_bit_cast(bf16x8_t, af[ks & 1][i]), accf[i][j], 0, 0, 0);
       }
       st2 ^= 1;
     }

@@ -1,5 +1,8 @@
 """The layer stack (q,k,v,o pure 1-bit linears + decoupled FFN per layer) chained on the GPU against
-the same chain of oracle calls, at 2 layers and T=256 (bf16; 2e-2 max-norm relative)."""
+the same chain of oracle calls, at 2 layers and T=256 (bf16; 2e-2 max-norm relative), and at the full
+per-layer shape of the 24-layer run against sampled tokens and stored full-size weight gradients."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -8,17 +11,14 @@ from oracle import pquant_oracle as po
 from paper_2602_22592_amd import binding as pq
 from paper_2602_22592_amd import workloads as wl
 from paper_2602_22592_amd.stack import Stack
+from parity_metrics import relerr, report
 
 pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 
 def dev(x):
     return torch.from_numpy(np.ascontiguousarray(x)).cuda().to(torch.bfloat16)
-
-
-def relerr(a, b):
-    a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
-    return float(np.abs(a - b).max() / max(np.abs(b).max(), 1e-30))
 
 
 @pytest.mark.parametrize("L,T,D,F,E,r", [(2, 256, 128, 352, 8, 32), (3, 100, 64, 96, 4, 8)])
@@ -45,8 +45,15 @@ def test_stack_two_layers(L, T, D, F, E, r):
         for n in ("Wq", "Wo", "W_up", "W_down", "Up", "Down", "Wr"):
             errs[f"{n}[{l}]"] = relerr(grads[l][n].cpu().numpy(), g_ref[l][n])
     print("  errors: " + ", ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
-    # routing decisions of later layers may flip on near-ties once bf16-level differences have propagated;
-    # the bar below holds when they agree, which they do for these seeds
+    # A routing decision of a later layer can flip on a near-tie once bf16-level differences have propagated into its
+    # router's input; the bar below holds when the decisions agree.  Name the tokens whose top-2 logit gap in the
+    # oracle is below what such differences can move (1e-2 of the logit scale): a failure with such tokens present
+    # is a routing flip, not an arithmetic error.
+    for l in range(L):
+        lg = np.sort(saved[l]["ff"]["logits"].astype(np.float64), axis=1)
+        gap = lg[:, -1] - lg[:, -2]
+        near = np.nonzero(gap < 1e-2 * max(np.abs(lg).max(), 1e-30))[0]
+        print(f"  layer {l}: tokens with a near-tie between their two best experts: {near.tolist()}", flush=True)
     assert max(errs.values()) <= 2e-2, errs
 
 
@@ -77,5 +84,17 @@ def test_stack_config5_layer_shape_sampled_tokens():
     d_ref, _ = po.stack_bwd(c["dY"][tok], c["layers"], saved)
     tk = torch.from_numpy(tok).cuda()
     errs = {"out": relerr(out[tk].float().cpu().numpy(), y_ref), "dh0": relerr(d0[tk].float().cpu().numpy(), d_ref)}
+    # weight gradients sum over all 16384 tokens: compared with the oracle's full-size run (tests/golden/full_size_stack.npz:
+    # sampled output channels of dWq of the first layer -- the end of the whole backward chain -- and of dWo and dW_down
+    # of the last layer, and the router-weight gradients of both layers)
+    ref = np.load(os.path.join(GOLDEN, "full_size_stack.npz"))
+    ch = ref["ch"]
+    errs.update(report("dWq[0]", grads[0]["Wq"].cpu().numpy()[ch], ref["Wq0"], per_channel=True))
+    errs.update(report("dWo[1]", grads[L - 1]["Wo"].cpu().numpy()[ch], ref["Wo1"], per_channel=True))
+    errs.update(report("dW_down[1]", grads[L - 1]["W_down"].cpu().numpy()[ch], ref["W_down1"], per_channel=True))
+    errs.update(report("dWr[0]", grads[0]["Wr"].cpu().numpy(), ref["Wr0"]))
+    errs.update(report("dWr[1]", grads[L - 1]["Wr"].cpu().numpy(), ref["Wr1"]))
     print("  errors: " + ", ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
+    print(f"  tokens of the last layer whose two best router logits are closer than 1e-3: {int((ref['gap1'] < 1e-3).sum())} of {T}",
+          flush=True)
     assert max(errs.values()) <= 2e-2, errs
