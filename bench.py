@@ -31,10 +31,67 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16 = 2.5e15      # dense MFMA bf16, FLOP/s
 PEAK_I8 = 5.0e15        # dense MFMA int8, OP/s
+PREWARM_S = 0.25        # seconds of the headline step run before its warm-up steps (reported as "prewarm_s")
 
-# Measured HBM bytes per launch at the default workload (profiles/linear_fwd_bwd_config2_hbm_traffic.md):
-# (FETCH_SIZE KiB x 1.986 + WRITE_SIZE KiB x 1.000) x 1024
-TRAFFIC_BYTES = {"gemm_dW": 169672441, "gemm_dX": 78266530, "gemm_onebit_fwd": 63732934}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+# kernel-name fragments of the three large GEMMs of the default workload (template arguments: ..., whole tiles, int8,
+# operand kinds of A and B, kinds of the fused second contraction, streaming loop)
+TRAFFIC_KERNELS = {"gemm_dW": "128, true, false, 1, 1, -1, -1, true>", "gemm_dX": "128, true, false, 0, 4, 0, 1, true>",
+                   "gemm_onebit_fwd": "128, true, true, 2, 3, 0, 0, true>", "decode_main_B1": "decode_gemv_tiled_kernel<1, false>",
+                   "decode_main_B8": "decode_gemm16_tiled_kernel<8, false>", "decode_prep_B1": "decode_prep_h_kernel<false>",
+                   "decode_prep_B8": "decode_prep_kernel", "decode_h_B8": "decode_h_kernel"}
+
+
+def csrc_sha():
+    """Digest of the kernel sources the loaded library was built from: measured traffic figures are only quoted for the
+    sources they were measured on."""
+    import hashlib
+    d = os.path.join(ROOT, "paper_2602_22592_amd", "csrc")
+    h = hashlib.sha256()
+    for fn in sorted(os.listdir(d)):
+        if fn.endswith((".hip", ".h")):
+            h.update(fn.encode()); h.update(open(os.path.join(d, fn), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def load_traffic():
+    """{label: HBM bytes per launch} from profiles/hbm_traffic.json (written by `bench.py --traffic-from`), or {} when the
+    file is missing or was measured on other kernel sources."""
+    try:
+        t = json.load(open(TRAFFIC_FILE))
+        if t.get("csrc_sha") != csrc_sha():
+            return {}
+        return {k: v["bytes"] for k, v in t["kernels"].items()}
+    except Exception:
+        return {}
+
+
+def write_traffic(fetch_csv, write_csv):
+    """Turns two rocprofv3 --pmc counter CSVs (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch) of a `--calibrate` run of this
+    script into profiles/hbm_traffic.json.  Each counter is scaled by what it reads for the calibration copy of known size."""
+    import collections
+    import csv
+
+    def avg(path):
+        agg = collections.defaultdict(list)
+        for r in csv.DictReader(open(path)):
+            agg[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+        return {k: sum(v) / len(v) for k, v in agg.items()}
+    F, W = avg(fetch_csv), avg(write_csv)
+    cal_f = next(v for k, v in F.items() if "gather_rows_kernel" in k)
+    cal_w = next(v for k, v in W.items() if "gather_rows_kernel" in k)
+    rows, cols = 65536, 2048
+    ff, fw = (rows * cols * 2 + rows * 4) / 1024.0 / cal_f, (rows * cols * 2) / 1024.0 / cal_w
+    out = {"csrc_sha": csrc_sha(), "fetch_factor": round(ff, 4), "write_factor": round(fw, 4),
+           "calibration": "gather_rows_kernel copy of 65536 x 2048 bf16", "kernels": {}}
+    for label, frag in TRAFFIC_KERNELS.items():
+        kf = [v for k, v in F.items() if frag in k]
+        kw = [v for k, v in W.items() if frag in k]
+        if kf and kw:
+            out["kernels"][label] = {"kernel": frag, "fetch_kib": round(kf[0], 1), "write_kib": round(kw[0], 1),
+                                     "bytes": int((kf[0] * ff + kw[0] * fw) * 1024)}
+    json.dump(out, open(TRAFFIC_FILE, "w"), indent=1)
+    print(json.dumps(out, indent=1))
 
 
 def gemm_flops(T, K, N, r):
@@ -103,14 +160,18 @@ def decode_bench(pq, torch, batch, n_layers=64, steps=100, warmup=20, int8_exper
     main_us = 1e3 * prof["decode_main"][0] / prof["decode_main"][1]
     prep_us = 1e3 * prof["decode_prep"][0] / prof["decode_prep"][1]
     h_us = 1e3 * prof["decode_h"][0] / prof["decode_h"][1] if "decode_h" in prof else 0.0   # batch 1: fused into prep
-    # algorithmic bytes of the main kernel per layer: packed bits + the selected experts' B rows + x, y
-    n_sel = k if batch == 1 else min(E, batch * k)          # upper bound on distinct experts per layer
-    main_bytes = n_layers * (N * K // 8 + n_sel * N * (r * eb + (4 if int8_experts else 0)) + batch * (K + 2 * N))
-    prep_bytes = n_layers * (batch * 2 * K + n_sel * r * K * eb + E * K * 2)    # x, the selected experts' A, router
-    return {"batch": batch, "experts": "int8" if int8_experts else "bf16", "layers_per_launch": n_layers, "main_kernel_us": round(main_us, 2),
+    # algorithmic bytes: packed bits + the rows of the DISTINCT experts a layer's tokens selected (read back from the
+    # routing decisions of the last call, outside every timed region) + router + x, y
+    idx = pq.decode_ws_idx(desc, ws).cpu().numpy().reshape(n_layers, -1)
+    n_sel = sum(len(set(row.tolist())) for row in idx)      # summed over the layers
+    main_bytes = n_layers * (N * K // 8 + batch * (K + 2 * N)) + n_sel * N * (r * eb + (4 if int8_experts else 0))
+    prep_bytes = n_layers * (batch * 2 * K + E * K * 2) + n_sel * r * K * eb    # x, router, the selected experts' A
+    whole = (main_bytes + prep_bytes) / total_us / 1e3
+    return {"batch": batch, "experts": "int8" if int8_experts else "bf16", "layers_per_launch": n_layers,
+            "distinct_experts_per_layer": round(n_sel / n_layers, 3), "main_kernel_us": round(main_us, 2),
             "prep_kernel_us": round(prep_us, 2), "h_kernel_us": round(h_us, 2), "launch_us": round(total_us, 2),
+            "whole_call_GBps": round(whole, 1), "whole_call_frac_hbm": round(whole / 8000.0, 4),
             "main_kernel_GBps": round(main_bytes / main_us / 1e3, 1), "main_kernel_frac_hbm": round(main_bytes / main_us / 1e3 / 8000.0, 4),
-            "whole_call_GBps": round((main_bytes + prep_bytes) / total_us / 1e3, 1),
             "us_per_layer": round(total_us / n_layers, 3), "bytes_per_layer": (main_bytes + prep_bytes) // n_layers}
 
 
@@ -254,7 +315,8 @@ def hp_int8_bench(pq, torch, T=8192, K=2048, N=2048, r=128, steps=100, warmup=20
 
 
 def ffn_bench(pq, torch, T=8192, D=2048, F=5504, E=8, r=32, steps=20, warmup=5):
-    """Config 3: the 1.3B-shaped decoupled FFN (three 1-bit projections + E=8 top-1 experts of width 32), fwd+bwd."""
+    """Config 3: the 1.3B-shaped decoupled FFN (three 1-bit projections + E=8 top-1 experts of width 32), fwd+bwd.
+    With F=5076, r=384 and E in {1, 2, 4, 8} it is the paper's own 1.3B FFN (Table 1) and its branch sweep (Sec. 4.4)."""
     g = torch.Generator(device="cuda").manual_seed(3)
     bf = torch.bfloat16
     rn = lambda *s, std=0.02: (torch.randn(s, device="cuda", generator=g) * std).to(bf)
@@ -272,9 +334,18 @@ def ffn_bench(pq, torch, T=8192, D=2048, F=5504, E=8, r=32, steps=20, warmup=5):
         pq.ffn_bwd(desc, dY, X, Up, Gate, Down, Wr, bufs, dX, *gr)
     ms = _time_steps(torch, step, steps, warmup)
     prof = _profile_steps(pq, torch, step, steps)
-    t_mfma = 3 * 2.0 * T * D * F / PEAK_I8 + 6 * 2.0 * T * D * F / PEAK_BF16       # experts are < 1 % of the flops
+    # one active expert per token: 3 projections of width r forward, 6 GEMMs backward (bf16)
+    t_mfma = 3 * 2.0 * T * D * F / PEAK_I8 + 6 * 2.0 * T * D * F / PEAK_BF16 + 9 * 2.0 * T * D * r / PEAK_BF16
+    # roofline of the label with the largest total time: its launches are GEMMs of 2 T D F flops each
+    big = {k: v for k, v in prof.items() if k in ("gemm_dW", "gemm_dX", "gemm_onebit_fwd")}
+    dom = max(big, key=lambda k: big[k][0])
+    peak = PEAK_I8 if dom == "gemm_onebit_fwd" else PEAK_BF16
+    ach = 2.0 * T * D * F * big[dom][1] / (big[dom][0] * 1e-3)
     return {"workload": f"tokens={T}, d_model={D}, d_ffn={F}, E={E} experts of width {r}, top-1, bf16, fwd+bwd",
             "ms_per_step": round(ms, 4), "tokens_per_s": round(T / ms * 1e3, 1), "mfma_frac_of_step": round(t_mfma / (ms * 1e-3), 4),
+            "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(ach / 1e12, 2), "peak": peak / 1e12,
+                         "unit": "TOP/s" if dom == "gemm_onebit_fwd" else "TFLOP/s", "frac": round(ach / peak, 4),
+                         "avg_us": round(1e3 * big[dom][0] / big[dom][1], 2), "traffic": None},
             "kernels_us_total_per_step": {k: round(1e3 * v[0] / steps, 1) for k, v in sorted(prof.items())}}
 
 
@@ -326,7 +397,15 @@ def main():
     ap.add_argument("--no-stack", action="store_true")
     ap.add_argument("--no-norm", action="store_true")
     ap.add_argument("--no-hp8", action="store_true")
+    ap.add_argument("--no-paper-ffn", action="store_true", help="skip the paper-exact 1.3B FFN (Table 1) and its branch sweep")
+    ap.add_argument("--no-decode-layer-sweep", action="store_true",
+                    help="skip batch-1 decode at 128 and 256 weight sets per launch (shows the rate does not lean on the last-level cache)")
+    ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                    help="no GPU work: turn two rocprofv3 --pmc counter CSVs of a --calibrate run into profiles/hbm_traffic.json")
     args = ap.parse_args()
+    if args.traffic_from:
+        write_traffic(*args.traffic_from)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -360,6 +439,9 @@ def main():
                                         "B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8),
                                         "B1_int8_experts": decode_bench(pq, torch, 1, int8_experts=True),
                                         "B8_int8_experts": decode_bench(pq, torch, 8, int8_experts=True)})
+        if not args.no_decode_layer_sweep:
+            section("decode_layer_sweep", lambda: {str(n): decode_bench(pq, torch, 1, n_layers=n, steps=50, warmup=10)
+                                                   for n in (128, 256)})
         section("decode_ffn", lambda: decode_ffn_bench(pq, torch))
     if not args.no_norm:
         section("rmsnorm_quant", lambda: norm_quant_bench(pq, torch))
@@ -383,7 +465,11 @@ def main():
         pq.linear_fwd(desc, X, W, Y, bufs, A=A, B=B)
         pq.linear_bwd(desc, dY, X, W, bufs, dX, dW, dab, A=A, B=B, dA=dA, dB=dB)
 
-    # timed region: warm-up, then exactly `steps` steps between synchronisations, no per-launch events
+    # The clocks of a GPU that has just run bandwidth-bound work (or none) take some tens of milliseconds of matrix work
+    # to settle: the same step is run back to back for `PREWARM_S` first, so that short timed regions (a handful of
+    # steps is 2 ms) measure the kernels and not that ramp.  Then the contract: `warmup` untimed steps, and exactly
+    # `steps` steps between synchronisations, no per-launch events.
+    _warm(torch, step, PREWARM_S)
     ms_per_step = _time_steps(torch, step, args.steps, args.warmup)
     # per-kernel durations: the same `steps` steps again with the library's HIP events around every launch (on the
     # launch stream); those events open gaps between launches, which is why they stay out of the timed region
@@ -393,12 +479,15 @@ def main():
     fl = gemm_flops(T, K, N, r)
     dom = max((k for k in kernels if k in fl), key=lambda k: kernels[k]["avg_us"] * kernels[k]["launches"])
     is_i8 = dom == "gemm_onebit_fwd"
-    achieved = fl[dom] / (kernels[dom]["avg_us"] * 1e-6) / 1e12
+    # the rank-r product dH A runs inside the dX launch (a second contraction into the same tile) when no launch carries
+    # the gemm_dX_hp label: its flops are part of that launch's algorithmic work
+    dom_flops = fl[dom] + (fl["gemm_dX_hp"] if dom == "gemm_dX" and "gemm_dX_hp" not in kernels and r > 0 else 0.0)
+    achieved = dom_flops / (kernels[dom]["avg_us"] * 1e-6) / 1e12
     peak = (PEAK_I8 if is_i8 else PEAK_BF16) / 1e12
     # HBM traffic of that kernel per launch: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch) scaled by what
     # the same counters read for a 256 MiB copy of known size (`--calibrate`), see profiles/; keyed by GEMM label
     # at the default workload, null for anything that was not profiled
-    traffic = TRAFFIC_BYTES.get(dom) if (T, K, N, r) == (8192, 2048, 2048, 128) else None
+    traffic = load_traffic().get(dom) if (T, K, N, r) == (8192, 2048, 2048, 128) else None
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": peak,
                 "unit": "TOP/s" if is_i8 else "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": traffic,
                 "avg_us": round(kernels[dom]["avg_us"], 2)}
@@ -406,7 +495,7 @@ def main():
     t_mfma = fl["gemm_onebit_fwd"] / PEAK_I8 + sum(v for k, v in fl.items() if k != "gemm_onebit_fwd") / PEAK_BF16
     out = {
         "metric": "decoupled-linear fwd+bwd tokens/s", "value": round(T / (ms_per_step * 1e-3), 1),
-        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "prewarm_s": PREWARM_S,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int8 (1-bit branch fwd) + bf16 (hp branch, backward), fp32 accumulate",
         "data": "synthetic",
@@ -433,6 +522,10 @@ def main():
         section("hp_int8_branch", lambda: hp_int8_bench(pq, torch))
     if not args.no_ffn:
         section("ffn_config3", lambda: ffn_bench(pq, torch))
+    if not args.no_paper_ffn:
+        # Table 1's 1.3B model: D_model 2048, D_ff - r = 5076 one-bit hidden units, r = 384 per high-precision branch;
+        # Sec. 4.4 / App. D scale the number of branches N (one active per token)
+        section("ffn_paper_1p3b", lambda: {f"N{n}": ffn_bench(pq, torch, F=5076, E=n, r=384, steps=10, warmup=3) for n in (1, 2, 4, 8)})
     if not args.no_stack:
         del X, W, dY, A, B, Y, dX, dW, bufs
         torch.cuda.empty_cache()

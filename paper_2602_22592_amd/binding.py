@@ -355,6 +355,15 @@ def decode_ws_hidden(desc, ws):
     return ws[off:off + L * B * k * r * 4].view(torch.float32).view(L, B, k, r)
 
 
+def decode_ws_idx(desc, ws):
+    """The selected expert indices [L][B][top_k] (int32) inside a decode workspace (section order as in decode_ws_hidden)."""
+    L, B, K, k = desc.n_layers, desc.batch, desc.d_in, desc.top_k
+    off = 0
+    for nbytes in (L * B * K, L * B * 8 * (K // 32) * 4, L * B * 4, L * B * 4):
+        off = (off + nbytes + 255) // 256 * 256
+    return ws[off:off + L * B * k * 4].view(torch.int32).view(L, B, k)
+
+
 def decode_ffn_workspace(desc, device="cuda"):
     n = lib().pq_decode_ffn_workspace_bytes(C.byref(desc))
     if n == 0:

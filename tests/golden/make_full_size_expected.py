@@ -6,6 +6,7 @@ library's results at the bench's launch configuration with these values; nothing
     python tests/golden/make_full_size_expected.py config2      # ~1 min   (T=8192, 2048x2048, r=128)
     python tests/golden/make_full_size_expected.py config3      # ~6 min   (T=8192, d=2048, F=5504, E=8 x 32)
     python tests/golden/make_full_size_expected.py stack        # ~30 min  (2 layers at T=16384, config-5 layer shape)
+    python tests/golden/make_full_size_expected.py stack1       # ~15 min  (1 layer at T=16384: the bar of a single layer applies)
 
 The integer products of the oracle run through NumPy's int64 matmul (no BLAS), hence the run times."""
 import os
@@ -71,8 +72,24 @@ def stack():
                         gap1=np.diff(np.sort(saved[L - 1]["ff"]["logits"], axis=1)[:, -2:], axis=1)[:, 0].astype(F32))
 
 
+def stack1():
+    L, T, D, F, E, r = 1, 16384, 2048, 5504, 8, 32
+    c = wl.stack_case(12, L, T, D, F, E, r, vocab=4096)
+    h0 = c["table"][c["ids"]]
+    y, saved = po.stack_fwd(h0, c["layers"], top_k=1)
+    d, grads = po.stack_bwd(c["dY"], c["layers"], saved)
+    rng = np.random.default_rng(51)
+    ch = np.sort(rng.choice(D, 16, replace=False))
+    chF = np.sort(rng.choice(F, 16, replace=False))
+    g = grads[0]
+    np.savez_compressed(os.path.join(HERE, "full_size_stack1.npz"), ch=ch, chF=chF, Wq=g["Wq"][ch].astype(F32), Wk=g["Wk"][ch].astype(F32),
+                        Wo=g["Wo"][ch].astype(F32), W_up=g["W_up"][chF].astype(F32), W_gate=g["W_gate"][chF].astype(F32),
+                        W_down=g["W_down"][ch].astype(F32), Wr=g["Wr"].astype(F32), Up=g["Up"][:, :8].astype(F32),
+                        Down=g["Down"][:, ch].astype(F32))
+
+
 if __name__ == "__main__":
     for name in sys.argv[1:]:
         t = time.time()
-        {"config2": config2, "config3": config3, "stack": stack}[name]()
+        {"config2": config2, "config3": config3, "stack": stack, "stack1": stack1}[name]()
         print(f"{name}: {time.time() - t:.0f} s", flush=True)
