@@ -1215,8 +1215,8 @@ int launch_mfma_cfg(const pq_gemm_plan& pl, int M, int N, int K, const pq_operan
     // whole tiles everywhere: the instantiation without validity masks
     const bool whole = grp.mode == 0 && M % 256 == 0 && N % 256 == 0 && K % EPB == 0 && pl.kchunk % EPB == 0 &&
                        ph2.K2 % 64 == 0;
-    // Streaming main loop: plain tiles (no expert segments), whole contraction steps in every split, rows of
-    // both operands 16-byte aligned.  Ragged M or N are fine there (edge rows are clamped, never stored).
+    // Streaming main loop: plain tiles or row groups (expert segments as row ranges), whole contraction steps in every
+    // split, rows of both operands 16-byte aligned.  Ragged M or N are fine there (edge rows are clamped, never stored).
     constexpr bool kinds_ok = (AK == PQ_SRC_KC16 || AK == PQ_SRC_KS16 || AK == PQ_SRC_KC8) &&
                               (BKIND == PQ_SRC_KC16 || BKIND == PQ_SRC_KS16 || BKIND == PQ_SRC_BITS8 || BKIND == PQ_SRC_BITS16);
     if constexpr (kinds_ok) {
@@ -1227,7 +1227,7 @@ int launch_mfma_cfg(const pq_gemm_plan& pl, int M, int N, int K, const pq_operan
       constexpr bool b_bits = (BKIND == PQ_SRC_BITS8 || BKIND == PQ_SRC_BITS16);
       const bool b_ok = b_bits ? (K % 128 == 0 && (pl.splits == 1 || pl.kchunk % 256 == 0) && B.ld % 16 == 0 && ((uintptr_t)B.p % 16) == 0) :
                         ((B.ld * 2) % 16 == 0 && ((uintptr_t)B.p % 16) == 0 && (BKIND != PQ_SRC_KS16 || N % 8 == 0));
-      const bool stream = grp.mode == 0 && K % EPB == 0 && pl.kchunk % EPB == 0 && a_ok && b_ok && M >= 1 && N >= 1;
+      const bool stream = (grp.mode == 0 || grp.mode == 1) && K % EPB == 0 && pl.kchunk % EPB == 0 && a_ok && b_ok && M >= 1 && N >= 1;
       if (stream) {
         if (whole) return launch_mfma<256, 256, 2, 4, 128, true, INT8, AK, BKIND, AK2, BK2, true>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
         return launch_mfma<256, 256, 2, 4, 128, false, INT8, AK, BKIND, AK2, BK2, true>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
@@ -1789,6 +1789,9 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
     pl.splits = 1;
     pl.kchunk = K > 0 ? K : 1;
     pl.bm = pl.bn = 128;
+    // wide row groups (experts of several hundred hidden units, Table 1: r = 384): the 256x256 streaming instantiation,
+    // whose loaders clamp a group's last rows like any ragged edge
+    if (grp.mode == 1 && N >= 256 && grp.max_rows >= 256 && K % 64 == 0) pl.bm = pl.bn = 256;
     // row groups with a narrow output and a long contraction (expert up/gate projections, their input
     // gradients): too few tiles to fill the chip, so the contraction is split as for plain GEMMs
     if (grp.mode == 1 && N <= 128 && K >= 1024 && splitk_ws) {
