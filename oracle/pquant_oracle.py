@@ -272,7 +272,7 @@ def _round_io(x, bf16):
     return torch.from_numpy(np.asarray(x, dtype=F32)).to(torch.bfloat16).to(torch.float32).numpy()
 
 
-def ffn_fwd(X, W_up, W_gate, W_down, Up, Gate, Down, Wr, alpha, beta, top_k=1, bf16=True):
+def ffn_fwd(X, W_up, W_gate, W_down, Up, Gate, Down, Wr, alpha, beta, top_k=1, bf16=True, experts="bf16"):
     """Y = alpha * sum_j gate_j FFN_e_j(X) + beta * FFN^INT1(X)   (Sec. 3.2 FFN equation, Sec. 3.3).
 
     FFN^INT1: three pure 1-bit linears around a gated unit, hidden state re-quantised before the
@@ -280,6 +280,13 @@ def ffn_fwd(X, W_up, W_gate, W_down, Up, Gate, Down, Wr, alpha, beta, top_k=1, b
     U and G are rounded to the storage format (they are saved for the backward pass); Hd is formed
     from the rounded values and quantised from fp32 (a reading: the paper states no storage precision; FP16
     latent activations are what its mixed-precision training keeps, App. B).  Experts are gated FFNs of hidden width r.
+
+    experts="int8" is the form the FFN equation of Sec. 3.2 prints (FFN^INT8): "8-bit weights are quantized identically
+    to 8-bit activations", read as the AbsMax quantiser of Sec. 3.1 per output channel, i.e. per row of Up_e, Gate_e
+    [r, d] and of Down_e [d, r]; the expert reads the codes and gamma of x that the 1-bit branch has formed (x is
+    quantised once); its hidden state a = silu(g) * u is stored in the I/O type and quantised again per token (an
+    8-bit activation like any other); u, g and the expert's output are exact integer accumulations de-quantised in the
+    order of _dequant_scale, u and g stored in the I/O type.
     """
     X32 = np.asarray(X, dtype=F32)
     X64 = X32.astype(F64)
@@ -304,21 +311,44 @@ def ffn_fwd(X, W_up, W_gate, W_down, Up, Gate, Down, Wr, alpha, beta, top_k=1, b
     ue = np.zeros((T, top_k, r), F64)
     ge = np.zeros((T, top_k, r), F64)
     Ys = np.zeros((T, top_k, d), F64)
+    ex8 = None
+    if experts == "int8":
+        qw = {n: [quant_act(np.asarray(W[e], dtype=F32)) for e in range(E)] for n, W in (("up", Up), ("gate", Gate), ("down", Down))}
+        qa = np.zeros((T, top_k, r), np.int8)
+        ga = np.zeros((T, top_k), F32)
+        a_st = np.zeros((T, top_k, r), F32)
     for j in range(top_k):
         for e in range(E):
             sel = np.nonzero(idx[:, j] == e)[0]
-            if sel.size:
+            if not sel.size:
+                continue
+            if experts == "int8":
+                (q_u, g_u), (q_g, g_g), (q_d, g_d) = qw["up"][e], qw["gate"][e], qw["down"][e]
+                qx = q[sel].astype(np.int64)
+                u = _round_io(_dequant_scale(qx @ q_u.astype(np.int64).T, gamma[sel], g_u), bf16)
+                g_ = _round_io(_dequant_scale(qx @ q_g.astype(np.int64).T, gamma[sel], g_g), bf16)
+                a = _round_io((_silu(g_.astype(F64)) * u.astype(F64)).astype(F32), bf16)
+                q_a, g_a = quant_act(a)
+                ue[sel, j], ge[sel, j] = u, g_
+                a_st[sel, j], qa[sel, j], ga[sel, j] = a, q_a, g_a
+                Ys[sel, j] = _dequant_scale(q_a.astype(np.int64) @ q_d.astype(np.int64).T, g_a, g_d)
+            else:
                 ue[sel, j] = X64[sel] @ Up64[e].T
                 ge[sel, j] = X64[sel] @ Gate64[e].T
                 Ys[sel, j] = (_silu(ge[sel, j]) * ue[sel, j]) @ Down64[e].T
+    if experts == "int8":
+        ex8 = dict(qw=qw, a=a_st, qa=qa, ga=ga)
     Yhp = (gate[:, :, None] * Ys).sum(axis=1)
     Y = F64(beta) * Y1 + F64(alpha) * Yhp
     return dict(Y=Y, Y1=Y1, Yhp=Yhp, q=q, gamma=gamma, U=U, G=G, Hd=Hd, qh=qh, gamma_h=gamma_h,
-                st=st, idx=idx, gate=gate, probs=p, logits=logits, ue=ue, ge=ge, Ys=Ys, acc_d=acc_d)
+                st=st, idx=idx, gate=gate, probs=p, logits=logits, ue=ue, ge=ge, Ys=Ys, acc_d=acc_d, ex8=ex8)
 
 
 def ffn_bwd(dY, X, Up, Gate, Down, Wr, alpha, beta, fwd):
-    """STE backward of ffn_fwd: identity through every quantiser, rounding and Sign."""
+    """STE backward of ffn_fwd: identity through every quantiser, rounding and Sign.  For INT8 experts (fwd["ex8"]) that
+    means (App. B.1) every product is differentiated with the de-quantised factors it multiplied: X~ = q_x / gamma_x,
+    Up~, Gate~, Down~ (rows over their gammas) and the hidden state a~ = q_a / gamma_a; the gated unit is differentiated
+    at the stored u and g.  The router still reads and is differentiated at the unquantised x."""
     dY64 = np.asarray(dY, dtype=F64)
     X64 = np.asarray(X, dtype=F64)
     al, be = F64(alpha), F64(beta)
@@ -342,6 +372,14 @@ def ffn_bwd(dY, X, Up, Gate, Down, Wr, alpha, beta, fwd):
     Up64, Gate64, Down64 = (np.asarray(a, dtype=F64) for a in (Up, Gate, Down))
     idx, gate, p = fwd["idx"], fwd["gate"], fwd["probs"]
     E = Up64.shape[0]
+    ex8 = fwd.get("ex8")
+    Xe = X64
+    if ex8 is not None:                                             # the experts' operands as they were multiplied
+        deq = lambda qg: qg[0].astype(F64) / qg[1].astype(F64)[:, None]
+        Up64 = np.stack([deq(ex8["qw"]["up"][e]) for e in range(E)])
+        Gate64 = np.stack([deq(ex8["qw"]["gate"][e]) for e in range(E)])
+        Down64 = np.stack([deq(ex8["qw"]["down"][e]) for e in range(E)])
+        Xe = fwd["q"].astype(F64) / fwd["gamma"].astype(F64)[:, None]
     Gr = al * dY64
     dUp, dGate, dDown = np.zeros_like(Up64), np.zeros_like(Gate64), np.zeros_like(Down64)
     dgate = np.einsum("ti,tji->tj", Gr, fwd["Ys"])
@@ -351,14 +389,14 @@ def ffn_bwd(dY, X, Up, Gate, Down, Wr, alpha, beta, fwd):
             if not sel.size:
                 continue
             u, gg = fwd["ue"][sel, j], fwd["ge"][sel, j]
-            a = _silu(gg) * u
+            a = _silu(gg) * u if ex8 is None else ex8["qa"][sel, j].astype(F64) / ex8["ga"][sel, j].astype(F64)[:, None]
             dy = gate[sel, j][:, None] * Gr[sel]
             dDown[e] += dy.T @ a
             da = dy @ Down64[e]
             du = da * _silu(gg)
             dg = da * u * _dsilu(gg)
-            dUp[e] += du.T @ X64[sel]
-            dGate[e] += dg.T @ X64[sel]
+            dUp[e] += du.T @ Xe[sel]
+            dGate[e] += dg.T @ Xe[sel]
             dX[sel] += du @ Up64[e] + dg @ Gate64[e]
     dWr, dX_r, dlogit = _router_bwd(dgate, idx, p, X64, np.asarray(Wr, dtype=F64))
     g.update(dX=dX + dX_r, dUp=dUp, dGate=dGate, dDown=dDown, dWr=dWr, dU=dU, dG=dG, dHd=dHd)

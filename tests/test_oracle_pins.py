@@ -451,6 +451,98 @@ def test_ffn_ste_chain_equals_gradients_of_the_smooth_surrogate():
     assert np.allclose(g["dW_gate"], _fd(l_in, Wg, 1e-5), rtol=1e-6, atol=1e-9)
 
 
+def _grid_rows(rng, shape):
+    """Rows whose entries already sit on their own AbsMax INT8 grid: integers in [-128, 127] with one -128 per row,
+    times a power of two, so that gamma = 128 / absmax is a power of two and quantising changes nothing."""
+    q = rng.integers(-127, 128, size=shape).astype(np.float64)
+    q[..., 0] = -128.0
+    return (q * 2.0 ** -9).astype(np.float32)
+
+
+def test_ffn_int8_experts_on_grid_inputs_equal_the_float_experts():
+    """Sec. 3.2, FFN^INT8: when x and the rows of Up_e, Gate_e, Down_e already lie on their INT8 grids, the quantisers
+    of the first two products change nothing, so u and g equal the float experts' exactly (fp32 I/O, small integers), and
+    the output differs from the float expert only by the re-quantisation of the hidden state: within a step of its grid
+    per hidden unit, summed against Down."""
+    rng = np.random.default_rng(61)
+    T, d, F, E, r = 7, 32, 32, 3, 8
+    c = wl.ffn_case(61, T, d, F, E, r, bf16=False)
+    X = _grid_rows(rng, (T, d)); Up = _grid_rows(rng, (E, r, d)); Gate = _grid_rows(rng, (E, r, d)); Down = _grid_rows(rng, (E, d, r))
+    args = (X, c["W_up"], c["W_gate"], c["W_down"], Up, Gate, Down, c["Wr"], 1.0, 0.0)
+    f8 = po.ffn_fwd(*args, top_k=2, bf16=False, experts="int8")
+    ff = po.ffn_fwd(*args, top_k=2, bf16=False)
+    assert np.array_equal(f8["idx"], ff["idx"])
+    assert np.allclose(f8["ue"], ff["ue"], rtol=1e-6, atol=0) and np.allclose(f8["ge"], ff["ge"], rtol=1e-6, atol=0)
+    a = f8["ex8"]["a"].astype(np.float64)
+    step = 1.0 / f8["ex8"]["ga"].astype(np.float64)                   # one code step of each (token, slot)
+    # half a step, a whole one only where +absmax saturates at code 127 (Sec. 3.1 quantiser)
+    dev = np.abs(f8["ex8"]["qa"] / f8["ex8"]["ga"][..., None] - a)
+    sat = f8["ex8"]["qa"] == 127
+    assert np.all(dev <= np.where(sat, 1.0, 0.5) * step[..., None] * (1 + 1e-4))
+    bound = step[..., None] * np.abs(Down.astype(np.float64)).sum(axis=2)[f8["idx"]]     # [T, k, d]
+    assert np.all(np.abs(f8["Ys"] - ff["Ys"]) <= bound * (1 + 1e-3) + 1e-9)
+    assert np.abs(f8["Ys"] - ff["Ys"]).max() > 0                       # ... and the re-quantisation is really there
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_ffn_int8_experts_track_the_float_experts(bf16):
+    """On ordinary inputs the INT8 experts stay within the quantisation error of the float experts: three quantised
+    operands with relative step 1/128 each."""
+    c = wl.ffn_case(62, 40, 64, 96, 4, 16, bf16=bf16, outlier_frac=0.0)
+    args = (c["X"], c["W_up"], c["W_gate"], c["W_down"], c["Up"], c["Gate"], c["Down"], c["Wr"], 2.0, 0.2)
+    f8 = po.ffn_fwd(*args, top_k=2, bf16=bf16, experts="int8")
+    ff = po.ffn_fwd(*args, top_k=2, bf16=bf16)
+    assert np.array_equal(f8["idx"], ff["idx"]) and np.array_equal(f8["Y1"], ff["Y1"])
+    err = np.abs(f8["Yhp"] - ff["Yhp"]).max() / np.abs(ff["Yhp"]).max()
+    assert 1e-4 < err < 5e-2
+    # codes of the weights are the activation quantiser applied to their rows
+    q_u, g_u = f8["ex8"]["qw"]["up"][1]
+    assert np.array_equal(q_u, po.quant_act(c["Up"][1])[0]) and np.array_equal(g_u, po.quant_act(c["Up"][1])[1])
+
+
+def test_ffn_int8_experts_backward_is_the_gradient_of_the_dequantised_surrogate():
+    """STE (App. B.1): with every quantiser read as the identity, the expert is Down~ a with a = silu(Gate~ x~) * (Up~ x~).
+    Finite differences of that smooth function at the de-quantised factors reproduce dUp, dGate and the experts' share
+    of dX; dDown is linear in Down~ with the quantised hidden state a~ held fixed.  The stored u, g (I/O rounding) and a~
+    (re-quantised) differ from the surrogate's exact values by their rounding, hence the tolerances."""
+    c = wl.ffn_case(63, 6, 32, 32, 2, 8, bf16=False, w_std=0.3, outlier_frac=0.0)
+    al = 1.7
+    args = (c["X"], c["W_up"], c["W_gate"], c["W_down"], c["Up"], c["Gate"], c["Down"], c["Wr"], al, 0.0)
+    f = po.ffn_fwd(*args, top_k=1, bf16=False, experts="int8")
+    dY = c["dY"].astype(np.float64)
+    g = po.ffn_bwd(dY, c["X"], c["Up"], c["Gate"], c["Down"], c["Wr"], al, 0.0, f)
+    E = 2
+    deq = lambda qg: qg[0].astype(np.float64) / qg[1].astype(np.float64)[:, None]
+    Upt = np.stack([deq(f["ex8"]["qw"]["up"][e]) for e in range(E)])
+    Gtt = np.stack([deq(f["ex8"]["qw"]["gate"][e]) for e in range(E)])
+    Dnt = np.stack([deq(f["ex8"]["qw"]["down"][e]) for e in range(E)])
+    Xt = f["q"].astype(np.float64) / f["gamma"].astype(np.float64)[:, None]
+    idx, gate = f["idx"][:, 0], f["gate"][:, 0].astype(np.float64)
+    sig = lambda z: 1.0 / (1.0 + np.exp(-z))
+
+    def loss(Up_, Gt_, Dn_, X_):
+        tot = 0.0
+        for t in range(6):
+            e = idx[t]
+            gg = Gt_[e] @ X_[t]; u = Up_[e] @ X_[t]
+            tot += al * gate[t] * float(dY[t] @ (Dn_[e] @ (gg * sig(gg) * u)))
+        return tot
+    fd_up = _fd(lambda: loss(Upt, Gtt, Dnt, Xt), Upt, 1e-5)
+    fd_gt = _fd(lambda: loss(Upt, Gtt, Dnt, Xt), Gtt, 1e-5)
+    fd_x = _fd(lambda: loss(Upt, Gtt, Dnt, Xt), Xt, 1e-5)
+    scale = lambda a: np.abs(a).max()
+    assert np.abs(g["dUp"] - fd_up).max() <= 2e-2 * scale(fd_up)
+    assert np.abs(g["dGate"] - fd_gt).max() <= 2e-2 * scale(fd_gt)
+    dX_router = po._router_bwd(g["dgate"] if "dgate" in g else np.einsum("ti,tji->tj", al * dY, f["Ys"]), f["idx"], f["probs"],
+                               c["X"].astype(np.float64), c["Wr"].astype(np.float64))[1]
+    assert np.abs((g["dX"] - dX_router) - fd_x).max() <= 2e-2 * scale(fd_x)
+    # dDown: linear in Down~ with the quantised hidden state fixed -- compare with the explicit sum over tokens
+    a_t = f["ex8"]["qa"][:, 0].astype(np.float64) / f["ex8"]["ga"][:, 0].astype(np.float64)[:, None]
+    for e in range(E):
+        ref = sum(al * gate[t] * np.outer(dY[t], a_t[t]) for t in range(6) if idx[t] == e)
+        assert np.allclose(g["dDown"][e], ref, rtol=1e-12, atol=1e-15)
+
+
 def test_workload_generators_are_seeded_and_bf16_exact():
     a, b = wl.config1(), wl.config1()
     assert all(np.array_equal(a[k], b[k]) for k in ("W", "X", "dY", "A", "B"))
