@@ -223,12 +223,20 @@ int pq_hp_int8_bwd(const void* dY, const void* Xt, int32_t dtype, int32_t T, int
  *   Up, Gate [E][r][d], Down [E][d][r], Wr [E][d] bf16;  Y [T][d] bf16 out.
  *   Backward (STE as in pq_linear_bwd): dX [T][d] bf16; dW_up, dW_gate [F][d], dW_down [d][F], dUp,
  *   dGate [E][r][d], dDown [E][d][r], dWr [E][d] fp32; dalpha_dbeta [2] fp32.
+ * hp_kind == PQ_HP_LOWRANK_INT8 (Sec. 3.2, FFN^INT8: the 8-bit weights are quantised like the 8-bit activations): the
+ * rows of Up_e, Gate_e [r][d] and Down_e [d][r] go through the quantiser of pq_quant_act; an expert reads the codes and
+ * gamma of x that the 1-bit branch formed, u = (q_x q_up^T) / (gamma_x gamma_up) and g likewise are stored in bf16,
+ * a = silu(g) * u is stored in bf16 and quantised again per token, and the expert's output is (q_a q_down^T) /
+ * (gamma_a gamma_down); both products are exact int32 and the scales come off as in pq_hp_int8_fwd.  The backward is
+ * the STE one on the de-quantised factors (X~ = q_x / gamma_x, Up~, Gate~, Down~, a~); the router reads x itself.
  * bf16 I/O only; d a multiple of 32, F a multiple of 4, r a multiple of 8, E <= 64.  An F that is not a multiple of 32
  * (Table 1: D_ff - r = 5076 for the 1.3B model) is padded to whole packed words inside the library: the padded hidden
  * units carry zero codes and zero gradients and take no part in mu, lambda or any sum; the caller's tensors keep F. */
 typedef struct pq_ffn_desc {
   int32_t tokens, d_model, d_ffn, hp_rank, n_experts, top_k, io_dtype;
   float alpha, beta;
+  int32_t hp_kind; /* pq_hp_kind of the experts: PQ_HP_LOWRANK_BF16 (16-bit weights on the unquantised x) or
+                      PQ_HP_LOWRANK_INT8 (the form the FFN equation of Sec. 3.2 prints; needs hp_rank % 32 == 0) */
 } pq_ffn_desc;
 size_t pq_ffn_ctx_bytes(const pq_ffn_desc* desc);
 size_t pq_ffn_workspace_bytes(const pq_ffn_desc* desc);

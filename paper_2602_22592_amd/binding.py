@@ -49,7 +49,7 @@ class DecodeDesc(C.Structure):
 class FFNDesc(C.Structure):
     _fields_ = [("tokens", C.c_int32), ("d_model", C.c_int32), ("d_ffn", C.c_int32), ("hp_rank", C.c_int32),
                 ("n_experts", C.c_int32), ("top_k", C.c_int32), ("io_dtype", C.c_int32), ("alpha", C.c_float),
-                ("beta", C.c_float)]
+                ("beta", C.c_float), ("hp_kind", C.c_int32)]
 
 
 class DecodeFFNDesc(C.Structure):

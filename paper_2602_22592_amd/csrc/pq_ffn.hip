@@ -1,7 +1,10 @@
 // The decoupled FFN (Sec. 3.2 FFN equation, Sec. 3.3):
 //     Y = beta * FFN_1bit(X) + alpha * sum_j gate_j * FFN_e_j(X)
 // FFN_1bit: three pure 1-bit linears around a gated unit, hidden state re-quantised before the down
-// projection; FFN_e: routed bf16 experts of hidden width r (permute -> grouped GEMMs -> combine).
+// projection; FFN_e: routed experts of hidden width r (permute -> grouped GEMMs -> combine), either on 16-bit
+// weights and the unquantised x, or in the INT8 form of the FFN equation: weight rows and the expert's hidden
+// state on the AbsMax grid, x's codes shared with the 1-bit branch, exact int32 products de-quantised in the
+// GEMM epilogue, and the STE backward on the de-quantised factors.
 // This file sequences the kernels; all arithmetic lives in pq_gemm.hip / pq_quant.hip / pq_moe.hip.
 #include <string.h>
 #include "pq_internal.h"
@@ -25,7 +28,10 @@ struct cursor {
 struct ffn_layout {
   // ctx
   size_t ml_up, ml_gate, ml_down, P_up, Pt_up, P_gate, Pt_gate, P_down, Pt_down, Xq, gx, Xt, U, G, Hq, gh, Ht;
-  size_t idx, gate, probs, counts, offsets, perm, inv, Xp, ue, ge, a, Ys, ctx_total;
+  size_t idx, gate, probs, counts, offsets, perm, inv, Xp, ue, ge, a, Ys;
+  // INT8 experts: codes, row scales and de-quantised bf16 copies of the expert weights; x's codes and gamma in slot
+  // order; the hidden state's codes, scales and de-quantised copy (Xp then holds the rows of X~ instead of X)
+  size_t UpQ, gUp, UpT, GateQ, gGate, GateT, DownQ, gDown, DownT, XqP, gxP, aQ, gA, aT, ctx_total;
   // workspace
   size_t stat, red_a, red_b, splitk, dHd, dU, dG, dYp, rd, da, du, dg, as, dXs, dlogit, dwr, ws_total;
   int n_red_a, n_red_b;
@@ -49,6 +55,13 @@ ffn_layout make_layout(const pq_ffn_desc& d) {
   L.counts = c.take(E * 4); L.offsets = c.take((E + 1) * 4); L.perm = c.take(S * 4); L.inv = c.take(S * 4);
   L.Xp = c.take(S * D * 2); L.ue = c.take(S * r * 2); L.ge = c.take(S * r * 2); L.a = c.take(S * r * 2);
   L.Ys = c.take(S * D * 2);
+  if (d.hp_kind == PQ_HP_LOWRANK_INT8) {
+    L.UpQ = c.take(E * r * D); L.gUp = c.take(E * r * 4); L.UpT = c.take(E * r * D * 2);
+    L.GateQ = c.take(E * r * D); L.gGate = c.take(E * r * 4); L.GateT = c.take(E * r * D * 2);
+    L.DownQ = c.take(E * D * r); L.gDown = c.take(E * D * 4); L.DownT = c.take(E * D * r * 2);
+    L.XqP = c.take(S * D); L.gxP = c.take(S * 4);
+    L.aQ = c.take(S * r); L.gA = c.take(S * 4); L.aT = c.take(S * r * 2);
+  }
   L.ctx_total = c.off;
   cursor w;
   L.stat = w.take(2 * sizeof(double) * 1024);
@@ -85,6 +98,10 @@ int check_ffn(const pq_ffn_desc* d) {
   PQ_REQUIRE(d->hp_rank % 8 == 0, PQ_ERR_SHAPE, "hp_rank=%d must be a multiple of 8", d->hp_rank);
   PQ_REQUIRE(d->n_experts >= 1 && d->n_experts <= 64, PQ_ERR_BAD_ARG, "n_experts=%d must be in 1..64", d->n_experts);
   PQ_REQUIRE(d->top_k >= 1 && d->top_k <= d->n_experts, PQ_ERR_BAD_ARG, "top_k=%d must be in 1..n_experts", d->top_k);
+  PQ_REQUIRE(d->hp_kind == PQ_HP_LOWRANK_BF16 || d->hp_kind == PQ_HP_LOWRANK_INT8, PQ_ERR_BAD_ARG, "hp_kind=%d is not a pq_hp_kind",
+             d->hp_kind);
+  PQ_REQUIRE(d->hp_kind != PQ_HP_LOWRANK_INT8 || d->hp_rank % 32 == 0, PQ_ERR_SHAPE, "INT8 experts need hp_rank=%d to be a multiple of 32",
+             d->hp_rank);
   return PQ_OK;
 }
 
@@ -147,6 +164,12 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
   // U, G and dHd that the gated unit and its backward replace by zeros
   if (int e = pack_weight(W_gate, Fv, D, cx, L.P_gate, L.Pt_gate, L.ml_gate, part, s)) return e;
   if (int e = pack_weight(W_down, D, Fv, cx, L.P_down, L.Pt_down, L.ml_down, part, s)) return e;
+  const bool hp8 = d->hp_kind == PQ_HP_LOWRANK_INT8;
+  if (hp8) {  // the experts' weight rows on the AbsMax grid (codes, gamma per row, de-quantised copy for the backward)
+    if (int e = pq_launch_quant_act(Up, PQ_BF16, E * r, D, (int8_t*)(cx + L.UpQ), (float*)(cx + L.gUp), (uint16_t*)(cx + L.UpT), s)) return e;
+    if (int e = pq_launch_quant_act(Gate, PQ_BF16, E * r, D, (int8_t*)(cx + L.GateQ), (float*)(cx + L.gGate), (uint16_t*)(cx + L.GateT), s)) return e;
+    if (int e = pq_launch_quant_act(Down, PQ_BF16, E * D, r, (int8_t*)(cx + L.DownQ), (float*)(cx + L.gDown), (uint16_t*)(cx + L.DownT), s)) return e;
+  }
   if (T == 0)  // no tokens: leave empty expert segments behind so that a backward call is well defined
     return pq_launch_route((const int*)(cx + L.idx), 0, E, (int*)(cx + L.counts), (int*)(cx + L.offsets), (int*)(cx + L.perm),
                            (int*)(cx + L.inv), s);
@@ -181,8 +204,36 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
   int* perm = (int*)(cx + L.perm);
   int* inv = (int*)(cx + L.inv);
   if (int e = pq_launch_route(idx, S, E, (int*)(cx + L.counts), offsets, perm, inv, s)) return e;
-  if (int e = pq_launch_gather_rows(X, perm, k, S, D, cx + L.Xp, s)) return e;
   pq_gemm_group g1{offsets, E, 1, 0, 0, S};
+  if (hp8) {
+    // slot-ordered X~ (for the backward), codes (int8 rows moved as D/2 16-bit units) and gamma of x
+    if (int e = pq_launch_gather_rows(cx + L.Xt, perm, k, S, D, cx + L.Xp, s)) return e;
+    if (int e = pq_launch_gather_rows(Xq, perm, k, S, D / 2, cx + L.XqP, s)) return e;
+    if (int e = pq_launch_gather_f32(gx, perm, k, S, (float*)(cx + L.gxP), s)) return e;
+    {  // u, g = (q_x q_w^T) / (gamma_x gamma_w), bf16
+      pq_operand A{cx + L.XqP, D, PQ_SRC_KC8, nullptr};
+      pq_operand B{cx + L.UpQ, D, PQ_SRC_KC8, nullptr};
+      pq_epilogue e = epi0();
+      e.C = cx + L.ue; e.ldc = r; e.out_kind = PQ_OUT_BF16; e.row_div = (const float*)(cx + L.gxP); e.col_div = (const float*)(cx + L.gUp);
+      g1.b_stride = (long)r * D; g1.coldiv_stride = r;
+      if (int err = pq_launch_gemm(0, S, r, D, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+      pq_operand Bg{cx + L.GateQ, D, PQ_SRC_KC8, nullptr};
+      e.C = cx + L.ge; e.col_div = (const float*)(cx + L.gGate);
+      if (int err = pq_launch_gemm(0, S, r, D, A, Bg, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+    }
+    if (int e = pq_launch_expert_act(cx + L.ue, cx + L.ge, (size_t)S * r, cx + L.a, s)) return e;
+    if (int e = pq_launch_quant_act(cx + L.a, PQ_BF16, S, r, (int8_t*)(cx + L.aQ), (float*)(cx + L.gA), (uint16_t*)(cx + L.aT), s)) return e;
+    {
+      pq_operand A{cx + L.aQ, r, PQ_SRC_KC8, nullptr};
+      pq_operand B{cx + L.DownQ, r, PQ_SRC_KC8, nullptr};
+      pq_epilogue e = epi0();
+      e.C = cx + L.Ys; e.ldc = D; e.out_kind = PQ_OUT_BF16; e.row_div = (const float*)(cx + L.gA); e.col_div = (const float*)(cx + L.gDown);
+      g1.b_stride = (long)D * r; g1.coldiv_stride = D;
+      if (int err = pq_launch_gemm(0, S, D, r, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+    }
+    return pq_launch_combine_fwd(Y, cx + L.Ys, inv, gate, d->alpha, T, k, D, s);
+  }
+  if (int e = pq_launch_gather_rows(X, perm, k, S, D, cx + L.Xp, s)) return e;
   {
     pq_operand A{cx + L.Xp, D, PQ_SRC_KC16, nullptr};
     pq_operand B{Up, D, PQ_SRC_KC16, nullptr};
@@ -225,6 +276,10 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
   char* ws = (char*)workspace;
   const int T = d->tokens, D = d->d_model, Fv = d->d_ffn, F = (Fv + 31) / 32 * 32, r = d->hp_rank, E = d->n_experts, k = d->top_k, S = T * k;
   void* sk = ws + L.splitk;
+  if (d->hp_kind == PQ_HP_LOWRANK_INT8) {  // STE: each product is differentiated with the de-quantised factors it multiplied
+    Up = cx + L.UpT; Gate = cx + L.GateT; Down = cx + L.DownT;
+  }
+  const void* a_fwd = d->hp_kind == PQ_HP_LOWRANK_INT8 ? cx + L.aT : cx + L.a;
   const float* ml_up = (const float*)(cx + L.ml_up);
   const float* ml_gate = (const float*)(cx + L.ml_gate);
   const float* ml_down = (const float*)(cx + L.ml_down);
@@ -295,7 +350,7 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
     g1.b_stride = (long)D * r;
     if (int err = pq_launch_gemm(0, S, r, D, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
   }
-  if (int e = pq_launch_expert_act_bwd(ws + L.da, cx + L.ue, cx + L.ge, cx + L.a, perm, gate, d->alpha, S, r, ws + L.du, ws + L.dg,
+  if (int e = pq_launch_expert_act_bwd(ws + L.da, cx + L.ue, cx + L.ge, a_fwd, perm, gate, d->alpha, S, r, ws + L.du, ws + L.dg,
                                        ws + L.as, s)) return e;
   {  // per-expert weight gradients: contraction over the expert's slots
     pq_operand A{ws + L.dYp, D, PQ_SRC_KS16, nullptr};

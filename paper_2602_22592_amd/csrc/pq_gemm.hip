@@ -536,6 +536,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
     m0 = grp.offsets[z] + t * BM;
     M = grp.offsets[z + 1];
     B.p = (const char*)B.p + (size_t)z * grp.b_stride * (BKIND == PQ_SRC_KC8 ? 1 : 2);
+    if (epi.col_div) epi.col_div += (size_t)z * grp.coldiv_stride;
   } else if (grp.mode == 2) {   // contraction range of group z, own output slab
     const int z = blockIdx.z;
     kb = grp.offsets[z];
@@ -1794,7 +1795,8 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
     if (grp.mode == 1 && N >= 256 && grp.max_rows >= 256 && K % 64 == 0) pl.bm = pl.bn = 256;
     // row groups with a narrow output and a long contraction (expert up/gate projections, their input
     // gradients): too few tiles to fill the chip, so the contraction is split as for plain GEMMs
-    if (grp.mode == 1 && N <= 128 && K >= 1024 && splitk_ws) {
+    // (a per-group column divisor is applied in the GEMM's own epilogue only: such products are not split)
+    if (grp.mode == 1 && N <= 128 && K >= 1024 && splitk_ws && !(epi.col_div && grp.coldiv_stride)) {
       const long tiles = (long)((grp.max_rows + 127) / 128 + grp.n_groups) * ((N + 127) / 128);
       long want = tiles > 0 ? 256 / tiles : 1;
       if (want > 8) want = 8;

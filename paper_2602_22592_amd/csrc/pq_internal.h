@@ -143,6 +143,7 @@ struct pq_gemm_group {
   long c_stride;
   int max_rows;
   pq_gemm_second second;
+  long coldiv_stride;  // mode 1: group e divides its columns by col_div[e * coldiv_stride + n] (per-expert weight-row scales)
 };
 
 struct pq_gemm_plan {
@@ -188,6 +189,8 @@ int pq_launch_decode_ffn(int L, int D, int F, int r, int E, int topk, float alph
 // ---- pq_moe.hip ---------------------------------------------------------------------------
 int pq_launch_route(const int* idx, int S, int E, int* counts, int* offsets, int* perm, int* inv, hipStream_t s);
 int pq_launch_gather_rows(const void* src, const int* perm, int k, int S, int d, void* dst, hipStream_t s);
+// dst[pos] = src[perm[pos] / k]  (fp32 scalars, e.g. a token's gamma carried to its slots)
+int pq_launch_gather_f32(const float* src, const int* perm, int k, int S, float* dst, hipStream_t s);
 // rows of F elements of which the first Fv exist (padded widths): the rest is written as zero
 int pq_launch_swiglu_quant(const void* U, const void* G, int T, int F, int Fv, int8_t* Hq, float* gamma, void* Ht, hipStream_t s);
 int pq_launch_swiglu_bwd(const void* dHd, const void* U, const void* G, int T, int F, int Fv, void* dU, void* dG, hipStream_t s);

@@ -90,6 +90,12 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const uint16_t* __rest
   for (int c = lane; c < d / 8; c += 64) d4[c] = s4[c];
 }
 
+__global__ __launch_bounds__(256) void gather_f32_kernel(const float* __restrict__ src, const int* __restrict__ perm, int k, int S,
+                                                         float* __restrict__ dst) {
+  const int pos = blockIdx.x * 256 + threadIdx.x;
+  if (pos < S) dst[pos] = src[perm[pos] / k];
+}
+
 // ---- the gated unit with fused AbsMax re-quantisation (one wavefront per token) -------------
 //   Hd = silu(G) * U in fp32; gamma_h = 128 / max(|Hd|, 1e-5); Hq = codes; Ht = bf16(Hq / gamma_h)
 // Rows are F elements apart; only the first Fv columns exist (Fv % 4 == 0): the others are written as zero codes,
@@ -481,6 +487,14 @@ int pq_launch_gather_rows(const void* src, const int* perm, int k, int S, int d,
   pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
   gather_rows_kernel<<<(S + 3) / 4, 256, 0, s>>>((const uint16_t*)src, perm, k, S, d, (uint16_t*)dst);
   PQ_CHECK_LAUNCH("gather_rows_kernel");
+  return PQ_OK;
+}
+
+int pq_launch_gather_f32(const float* src, const int* perm, int k, int S, float* dst, hipStream_t s) {
+  if (S == 0) return PQ_OK;
+  pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
+  gather_f32_kernel<<<(S + 255) / 256, 256, 0, s>>>(src, perm, k, S, dst);
+  PQ_CHECK_LAUNCH("gather_f32_kernel");
   return PQ_OK;
 }
 

@@ -21,9 +21,10 @@ def dev(x):
     return torch.from_numpy(np.ascontiguousarray(x)).cuda().to(torch.bfloat16)
 
 
-def run_ffn(c, top_k, alpha, beta):
+def run_ffn(c, top_k, alpha, beta, experts="bf16"):
     T, D, F, E, r = c["tokens"], c["d_model"], c["d_ffn"], c["n_experts"], c["hp_rank"]
-    desc = pq.FFNDesc(T, D, F, r, E, top_k, pq.PQ_BF16, alpha, beta)
+    kind = pq.PQ_HP_LOWRANK_INT8 if experts == "int8" else pq.PQ_HP_LOWRANK_BF16
+    desc = pq.FFNDesc(T, D, F, r, E, top_k, pq.PQ_BF16, alpha, beta, kind)
     bufs = pq.FFNBuffers(desc)
     t = {k: dev(c[k]) for k in ("X", "dY", "W_up", "W_gate", "W_down", "Up", "Gate", "Down", "Wr")}
     f32 = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
@@ -40,10 +41,10 @@ def run_ffn(c, top_k, alpha, beta):
     return res
 
 
-def check_ffn(c, top_k=1, alpha=2.0, beta=0.2):
-    got = run_ffn(c, top_k, alpha, beta)
+def check_ffn(c, top_k=1, alpha=2.0, beta=0.2, experts="bf16"):
+    got = run_ffn(c, top_k, alpha, beta, experts)
     f = po.ffn_fwd(c["X"], c["W_up"], c["W_gate"], c["W_down"], c["Up"], c["Gate"], c["Down"], c["Wr"], alpha, beta,
-                   top_k=top_k, bf16=True)
+                   top_k=top_k, bf16=True, experts=experts)
     g = po.ffn_bwd(c["dY"], c["X"], c["Up"], c["Gate"], c["Down"], c["Wr"], alpha, beta, f)
     errs = report("Y", got["Y"], f["Y"])
     errs.update(report("dX", got["dX"], g["dX"]))
@@ -87,6 +88,23 @@ def test_ffn_paper_1p3b_shape_reduced_tokens(N):
     branch; Sec. 3.3 / Sec. 4.4: N branches, one active per token) at 384 tokens."""
     print(f"ffn paper-exact 1.3B shape, T=384, d=2048, F=5076, N={N} branches of r=384, top-1", flush=True)
     check_ffn(wl.ffn_case(700 + N, 384, 2048, 5076, N, 384), top_k=1)
+
+
+@pytest.mark.parametrize("T,D,F,E,r,k", [(700, 256, 544, 8, 32, 1), (200, 96, 160, 4, 32, 2), (300, 256, 500, 1, 64, 1),
+                                         (1, 32, 32, 8, 32, 1), (384, 2048, 5504, 8, 32, 1), (384, 2048, 5076, 4, 384, 1)])
+def test_ffn_int8_experts(T, D, F, E, r, k):
+    """The experts in the INT8 form the FFN equation of Sec. 3.2 prints: weight rows and the expert's hidden state on the
+    AbsMax grid, x's codes shared with the 1-bit branch, STE backward on the de-quantised factors.  The last two shapes
+    are config 3 and the paper's 1.3B FFN (Table 1) at 384 tokens."""
+    print(f"ffn int8 experts T={T} d={D} F={F} E={E} r={r} k={k}", flush=True)
+    check_ffn(wl.ffn_case(180 + T + k + r, T, D, F, E, r), top_k=k, experts="int8")
+
+
+def test_ffn_int8_experts_rejects_ranks_that_are_not_whole_words():
+    with pytest.raises(pq.PQError):
+        pq.FFNBuffers(pq.FFNDesc(64, 64, 64, 8, 2, 1, pq.PQ_BF16, 1.0, 1.0, pq.PQ_HP_LOWRANK_INT8))
+    with pytest.raises(pq.PQError):
+        pq.FFNBuffers(pq.FFNDesc(64, 64, 64, 32, 2, 1, pq.PQ_BF16, 1.0, 1.0, 7))
 
 
 def test_ffn_config3_full_size_sampled_tokens():
