@@ -314,7 +314,7 @@ def hp_int8_bench(pq, torch, T=8192, K=2048, N=2048, r=128, steps=100, warmup=20
             "kernels_us": {k: round(1e3 * ms / n, 2) for k, (ms, n) in sorted(prof.items())}}
 
 
-def ffn_bench(pq, torch, T=8192, D=2048, F=5504, E=8, r=32, steps=20, warmup=5):
+def ffn_bench(pq, torch, T=8192, D=2048, F=5504, E=8, r=32, steps=20, warmup=5, int8_experts=False):
     """Config 3: the 1.3B-shaped decoupled FFN (three 1-bit projections + E=8 top-1 experts of width 32), fwd+bwd.
     With F=5076, r=384 and E in {1, 2, 4, 8} it is the paper's own 1.3B FFN (Table 1) and its branch sweep (Sec. 4.4)."""
     g = torch.Generator(device="cuda").manual_seed(3)
@@ -323,7 +323,7 @@ def ffn_bench(pq, torch, T=8192, D=2048, F=5504, E=8, r=32, steps=20, warmup=5):
     X = rn(T, D, std=1.0); dY = rn(T, D, std=1.0)
     W_up, W_gate, W_down = rn(F, D), rn(F, D), rn(D, F)
     Up, Gate, Down, Wr = rn(E, r, D), rn(E, r, D), rn(E, D, r), rn(E, D)
-    desc = pq.FFNDesc(T, D, F, r, E, 1, pq.PQ_BF16, 2.0, 0.2)
+    desc = pq.FFNDesc(T, D, F, r, E, 1, pq.PQ_BF16, 2.0, 0.2, pq.PQ_HP_LOWRANK_INT8 if int8_experts else pq.PQ_HP_LOWRANK_BF16)
     bufs = pq.FFNBuffers(desc)
     f32 = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
     Y = torch.empty((T, D), dtype=bf, device="cuda"); dX = torch.empty((T, D), dtype=bf, device="cuda")
@@ -341,7 +341,8 @@ def ffn_bench(pq, torch, T=8192, D=2048, F=5504, E=8, r=32, steps=20, warmup=5):
     dom = max(big, key=lambda k: big[k][0])
     peak = PEAK_I8 if dom == "gemm_onebit_fwd" else PEAK_BF16
     ach = 2.0 * T * D * F * big[dom][1] / (big[dom][0] * 1e-3)
-    return {"workload": f"tokens={T}, d_model={D}, d_ffn={F}, E={E} experts of width {r}, top-1, bf16, fwd+bwd",
+    return {"workload": f"tokens={T}, d_model={D}, d_ffn={F}, E={E} {'INT8' if int8_experts else 'bf16'} experts of width {r}, top-1, "
+                        "bf16 I/O, fwd+bwd",
             "ms_per_step": round(ms, 4), "tokens_per_s": round(T / ms * 1e3, 1), "mfma_frac_of_step": round(t_mfma / (ms * 1e-3), 4),
             "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(ach / 1e12, 2), "peak": peak / 1e12,
                          "unit": "TOP/s" if dom == "gemm_onebit_fwd" else "TFLOP/s", "frac": round(ach / peak, 4),
@@ -522,10 +523,14 @@ def main():
         section("hp_int8_branch", lambda: hp_int8_bench(pq, torch))
     if not args.no_ffn:
         section("ffn_config3", lambda: ffn_bench(pq, torch))
+        # the same FFN with its experts in the INT8 form of the FFN equation (Sec. 3.2)
+        section("ffn_config3_int8_experts", lambda: ffn_bench(pq, torch, int8_experts=True))
     if not args.no_paper_ffn:
         # Table 1's 1.3B model: D_model 2048, D_ff - r = 5076 one-bit hidden units, r = 384 per high-precision branch;
         # Sec. 4.4 / App. D scale the number of branches N (one active per token)
         section("ffn_paper_1p3b", lambda: {f"N{n}": ffn_bench(pq, torch, F=5076, E=n, r=384, steps=10, warmup=3) for n in (1, 2, 4, 8)})
+        section("ffn_paper_1p3b_int8_experts", lambda: {f"N{n}": ffn_bench(pq, torch, F=5076, E=n, r=384, steps=10, warmup=3, int8_experts=True)
+                                                         for n in (1, 8)})
     if not args.no_stack:
         del X, W, dY, A, B, Y, dX, dW, bufs
         torch.cuda.empty_cache()
