@@ -392,7 +392,8 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", action="store_true",
-                    help="also run a 256 MiB copy kernel of known size (scale for rocprofv3 --pmc byte counters)")
+                    help="counter run for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE: the default workload, batch-1 and batch-8 "
+                         "decode, and a 256 MiB copy kernel of known size that scales the byte counters; nothing else")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-ffn", action="store_true")
     ap.add_argument("--no-stack", action="store_true")
@@ -435,7 +436,12 @@ def main():
 
     # The bandwidth-bound sections run first: straight after 0.15 s of back-to-back MFMA work the same kernels read
     # 8-10 % slower (the chip's power management), which says nothing about them.
-    if not args.no_decode:
+    if args.calibrate:
+        # a counter run: only the workloads whose kernels are looked up in the counter files, so that a kernel name
+        # stands for one workload (the INT8-expert decode variants and the FFN stack launch the same kernels on other sizes)
+        args.no_ffn = args.no_stack = args.no_norm = args.no_hp8 = args.no_paper_ffn = args.no_cpu_baseline = True
+        section("decode_gemv", lambda: {"B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8)})
+    elif not args.no_decode:
         section("decode_gemv", lambda: {"metric": "1-bit decode GEMV HBM GB/s (4096->11008, E=8 top-2 r=64 experts)",
                                         "B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8),
                                         "B1_int8_experts": decode_bench(pq, torch, 1, int8_experts=True),

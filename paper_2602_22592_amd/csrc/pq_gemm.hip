@@ -561,6 +561,18 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
   sb.setup(B, n0, N, tid);
   const int nkt = ke > kb ? (ke - kb + EPB - 1) / EPB : 0;
   constexpr int NKS = KB / 32;   // MFMA issues along the contraction per LDS stage
+  // Streaming loop with a fused second contraction of one or two 64-element steps: its operand tiles (32 KB each:
+  // A2 step 0, B2 step 0, A2 step 1, B2 step 1) ride in on the ring's last four refills, which the main loop no longer
+  // needs, instead of being requested after it (a chain of four memory latencies in front of 64 MFMAs per wavefront).
+  // Tile j goes to ring stage (pf2_s0 + j) mod 4.
+  bool pf2 = false;                                  // uniform
+  const int pf2_s0 = nkt & 3;
+  if constexpr (DTL && BBITS && AK2 == PQ_SRC_KC16 && (BK2 == PQ_SRC_KC16 || BK2 == PQ_SRC_KS16)) {
+#ifndef PQ_NO_PF2
+    pf2 = ph2.K2 > 0 && ph2.K2 <= 128 && ph2.K2 % 64 == 0 && nkt >= 4 && ((uintptr_t)ph2.A2.p % 16) == 0 && (ph2.A2.ld * 2) % 16 == 0 &&
+          ((uintptr_t)ph2.B2.p % 16) == 0 && (ph2.B2.ld * 2) % 16 == 0 && (BK2 != PQ_SRC_KS16 || N % 8 == 0);
+#endif
+  }
 
   // per-thread LDS read offsets of the MFMA operand fragments (row part and swizzle part)
   int a_rb[TM], a_fx[TM], b_rb[TN], b_fx[TN];
@@ -641,6 +653,34 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
 #pragma unroll
       for (int i = 0; i < IPW; ++i)
         __builtin_amdgcn_global_load_lds(src[i] + (size_t)kt * adv, PQ_LDS_PTR(base + i * 1024), 16, 0, 0);
+    };
+    // tile j of the second contraction (step j >> 1; even: A2, odd: B2) into a ring stage, in the layouts of the
+    // loaders above; the addresses are formed here, in the four steps that use them, not kept across the loop
+    auto issue_ph2 = [&](int j, int stage) {
+      if constexpr (AK2 >= 0) {
+        unsigned char* base = smem + stage * STG + q0 * 1024;
+        const int k2 = (j >> 1) * 64;
+#pragma unroll
+        for (int i = 0; i < IPW; ++i) {
+          const int qi = q0 + i;
+          const char* g;
+          if (!(j & 1) || BK2 != PQ_SRC_KS16) {
+            const pq_operand& op = (j & 1) ? ph2.B2 : ph2.A2;
+            const int row0 = (j & 1) ? n0 : m0, rows = (j & 1) ? N : M;
+            const int r = qi * 8 + (lane >> 3), pc = lane & 7;
+            const int c = pc ^ ((r ^ (r >> 3)) & 7);
+            const int grow = min(row0 + r, rows - 1);
+            g = (const char*)op.p + ((size_t)grow * op.ld + k2) * 2 + c * 16;
+          } else {
+            const int t = qi * 2 + (lane >> 5), pc = lane & 31;
+            const int c = pc ^ (4 * (t & 3));
+            int col = n0 + c * 8;
+            if (col + 8 > N) col = n0;
+            g = (const char*)ph2.B2.p + ((size_t)(k2 + t) * ph2.B2.ld + col) * 2;
+          }
+          __builtin_amdgcn_global_load_lds(g, PQ_LDS_PTR(base + i * 1024), 16, 0, 0);
+        }
+      }
     };
     // Packed bits of B: a row's bits are fetched 32 bytes (CH steps) at a time, two lanes per row, so a chunk
     // (256 rows, 8 KB) is one 16-byte load instruction per wavefront every CH steps.  Lanes 0..31 take the first
@@ -827,7 +867,9 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
         PQ_STAMP(trace_slot, wv, kt, 1);
         PQ_SETPRIO(3);
         if (part == 0) issue_bits(min(chunk + 2, nch - 1), buf == 0 ? 2 : buf - 1);   // (buf + 2) mod 3
-        issue(min(kt + NSTAGE, nkt - 1), st);           // refill the stage just read
+        // refill the stage just read: with the step four ahead, or, once there is none, with a tile of the second contraction
+        if (pf2 && kt + NSTAGE >= nkt && kt + NSTAGE - nkt < (ph2.K2 >> 5)) issue_ph2(kt + NSTAGE - nkt, st);
+        else issue(min(kt + NSTAGE, nkt - 1), st);
         read_bits((uint32_t)(bufn * (BN * 32) + ((partn * RB) >> 4) * 512 + ((partn * RB) & 15)));   // past the last step: a place nobody uses
         read_a(G0, c0{}, sn);
         {
@@ -993,7 +1035,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
     sb2.setup(ph2.B2, n0, N, tid);
     // the first A2 tile (activation-sized, far away) is requested before the rescale arithmetic, the first B2 tile
     // (a small factor, cache-resident) after it: holding both across the rescale overflows the register file
-    if (ph2.K2 > 0) sa2.load(ph2.A2, 0, ph2.K2);
+    if (ph2.K2 > 0 && !pf2) sa2.load(ph2.A2, 0, ph2.K2);
     const float sc1 = ph2.dev_scale1 ? __fmul_rn(ph2.scale1, *ph2.dev_scale1) : ph2.scale1;
     if (ph2.row_div1) {                              // uniform: one divisor load and one division per row of the tile
       for (int r = tid; r < BM; r += NT) rowscale[r] = sc1 / ph2.row_div1[min(m0 + r, M - 1)];
@@ -1010,9 +1052,49 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
           accf[i][j][v] = (float)e1 * sr;
         }
     }
-    if (ph2.K2 > 0) sb2.load(ph2.B2, 0, ph2.K2);
+    if (pf2) {
+#if defined(__HIP_DEVICE_COMPILE__)
+      // both operands of every step already sit in the ring (all loads were waited for after the main loop)
+      typedef short v4s_t __attribute__((ext_vector_type(4)));
+      const int hh = lane >> 5;
+      for (int s2 = 0; s2 < (ph2.K2 >> 6); ++s2) {
+        const unsigned char* ta = smem + ((pf2_s0 + 2 * s2) & 3) * (BM * KB);
+        const unsigned char* tb = smem + ((pf2_s0 + 2 * s2 + 1) & 3) * (BM * KB);
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+          const int ch = 2 * ks + hh;
+          uint4 fa[TM], fb[TN];
+#pragma unroll
+          for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const uint4*>(ta + a_rb[i] + ((ch ^ a_fx[i]) << 4));
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            if constexpr (BK2 == PQ_SRC_KS16) {
+              // [64 contraction rows][256 columns] as it lies in memory, 16-byte chunks of a row swizzled by the row:
+              // two transposing reads (rows 16 ks + 8 h + (0..3), then + 4) make the operand of 8 contraction indices
+              const int tl = 8 * hh + ((lane & 15) >> 2), cl = 16 * ((lane >> 4) & 1) + 4 * (lane & 3), sw = 4 * ((lane & 15) >> 2);
+              const int col = wn0 + 32 * j + cl;
+              const unsigned char* pb = tb + ks * 8192 + tl * 512 + (((col >> 3) ^ sw) << 4) + (col & 7) * 2;
+              const v4s_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_t*)(pb));
+              const v4s_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_t*)(pb + 2048));
+              const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+              fb[j] = make_uint4(l2.x, l2.y, h2.x, h2.y);
+            } else {
+              fb[j] = *reinterpret_cast<const uint4*>(tb + (b_rb[j] - BM * KB) + ((ch ^ b_fx[j]) << 4));
+            }
+          }
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+              accf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fb[j]), __builtin_bit_cast(bf16x8_t, fa[i]),
+                                                                   accf[i][j], 0, 0, 0);
+        }
+      }
+#endif
+    }
+    if (ph2.K2 > 0 && !pf2) sb2.load(ph2.B2, 0, ph2.K2);
     int st2 = 0;
-    for (int k2 = 0; k2 < ph2.K2; k2 += KS2) {
+    for (int k2 = 0; k2 < (pf2 ? 0 : ph2.K2); k2 += KS2) {
       unsigned char* stage = smem + st2 * STAGE;
       sa2.store(stage, tid);
       sb2.store(stage + BM * KB, tid);

@@ -203,6 +203,9 @@ def test_linear_config1_fp32():
                                          # rank 64 / 128 with ragged token and channel tiles: the streaming loop of the
                                          # fused GEMMs with a second contraction of one and of two whole steps
                                          (600, 1152, 1408, 64, True), (300, 640, 384, 128, True),
+                                         # 7 and 5 contraction steps forward: the second contraction's tiles start in the
+                                         # ring's last and second stage
+                                         (300, 896, 384, 128, True), (280, 640, 896, 64, True),
                                          # many tokens at rank 128: the streaming rank-r kernel computes H (ragged last block)
                                          (1100, 640, 384, 128, True), (1024, 64, 256, 128, True),
                                          # 2048 tokens or more in whole 512-token ranges: dB and dA take the streaming pair kernel
