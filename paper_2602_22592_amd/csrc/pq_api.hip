@@ -161,6 +161,9 @@ lin_layout make_layout(const pq_linear_desc& d) {
   if (routed) {
     L.n_red_a = pq_rowdot_blocks((int)S);
     if (8 * S * re * sizeof(float) > sk) sk = 8 * S * re * sizeof(float);   // narrow grouped GEMMs split the contraction up to 8 ways
+    // so do the per-expert factor gradients over their slot ranges
+    if (pq_mode2_ws_bytes(Ni, (int)re, d.n_experts, (int)S) > sk) sk = pq_mode2_ws_bytes(Ni, (int)re, d.n_experts, (int)S);
+    if (pq_mode2_ws_bytes((int)re, Ki, d.n_experts, (int)S) > sk) sk = pq_mode2_ws_bytes((int)re, Ki, d.n_experts, (int)S);
   }
   if (hp8) L.n_red_a = pq_plan_gemm(0, Ti, d.hp_rank, Ni).red_blocks;      // the INT8 branch's dH GEMM leaves the partials of d alpha
   L.red_a = w.take(sizeof(double) * (size_t)(L.n_red_a > 0 ? L.n_red_a : 1));

@@ -79,6 +79,9 @@ ffn_layout make_layout(const pq_ffn_desc& d) {
   }
   // the expert up/gate projections and their input gradients split the contraction up to 8 ways: [8][S][r] fp32
   if (8 * S * r * sizeof(float) > sk) sk = 8 * S * r * sizeof(float);
+  // the per-expert weight gradients cut their slot ranges into pieces (slabs of all experts' outputs)
+  if (pq_mode2_ws_bytes((int)D, (int)r, (int)E, (int)S) > sk) sk = pq_mode2_ws_bytes((int)D, (int)r, (int)E, (int)S);
+  if (pq_mode2_ws_bytes((int)r, (int)D, (int)E, (int)S) > sk) sk = pq_mode2_ws_bytes((int)r, (int)D, (int)E, (int)S);
   L.splitk = w.take(sk);
   L.dHd = w.take(T * F * 2); L.dU = w.take(T * F * 2); L.dG = w.take(T * F * 2);
   L.dYp = w.take(S * D * 2); L.rd = w.take(S * 4);

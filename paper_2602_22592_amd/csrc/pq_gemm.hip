@@ -524,7 +524,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
   const int n0 = bn * BN;
   int kb = split * kchunk;
   int ke = min(K, kb + kchunk);
-  const int Mtot = M;           // rows of C (a split's slab has Mtot rows)
+  int Mtot = M;                 // rows of C (a split's slab has Mtot rows)
+  size_t slab_group = 0;        // offset of this group's rows in a slab (grouped contraction ranges)
   if (grp.mode == 1) {          // rows of group z: [offsets[z], offsets[z+1]); row tiles are numbered group after group
     int t = bm, z = 0;
     for (; z < grp.n_groups; ++z) {
@@ -541,6 +542,16 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
     const int z = blockIdx.z;
     kb = grp.offsets[z];
     ke = grp.offsets[z + 1];
+    if (gridDim.y > 1) {
+      // the group's range in gridDim.y pieces of whole 64-element steps (the last ones may be empty: they leave zeros);
+      // a slab holds the outputs of all groups, one under the other
+      int chunk = (ke - kb + (int)gridDim.y - 1) / (int)gridDim.y;
+      chunk = (chunk + 63) & ~63;
+      kb = min(ke, kb + split * chunk);
+      ke = min(ke, kb + chunk);
+      slab_group = (size_t)z * M * N;
+      Mtot = grp.n_groups * M;
+    }
     epi.C = (char*)epi.C + (size_t)z * grp.c_stride * (epi.out_kind == PQ_OUT_BF16 ? 2 : 4);
   }
 
@@ -1125,7 +1136,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
   // the raw fp32 accumulators go to this split's slab instead; splitk_reduce_kernel finishes the job.
   epi_state st;
   epi_begin(epi, st);
-  float* slab = splitk_part ? splitk_part + (size_t)split * Mtot * N : nullptr;
+  float* slab = splitk_part ? splitk_part + (size_t)split * Mtot * N + slab_group : nullptr;
   const bool row_scaled = !slab && epi.row_div != nullptr;   // uniform
   if (row_scaled) {
     for (int r = tid; r < BM; r += NT) rowscale[r] = st.sc0 / epi.row_div[min(m0 + r, M - 1)];
@@ -1840,6 +1851,22 @@ int pq_launch_gemm_pair_ks16(int K, int M0, int N0, const pq_operand& A0, const 
   return PQ_OK;
 }
 
+// Grouped contraction ranges (per-expert weight gradients): with few output tiles per group and few groups the launch is
+// far from a workgroup per CU, so every group's range is cut into up to 8 pieces whose slabs a second launch adds.
+int pq_mode2_splits(int M, int N, int n_groups, int total_k) {
+  if (M <= 0 || N <= 0 || n_groups <= 0) return 1;
+  const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128) * n_groups;
+  long want = 512 / tiles;
+  const long by_len = (long)total_k / n_groups / 256;   // pieces of about 256 contraction indices or more
+  if (want > by_len) want = by_len;
+  if (want > 8) want = 8;
+  return want > 1 ? (int)want : 1;
+}
+size_t pq_mode2_ws_bytes(int M, int N, int n_groups, int total_k) {
+  const int sp = pq_mode2_splits(M, N, n_groups, total_k);
+  return sp > 1 ? (size_t)sp * n_groups * M * N * sizeof(float) : 0;
+}
+
 int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const pq_operand& B,
                    const pq_epilogue& epi, hipStream_t s, int prof_label, void* splitk_ws,
                    const pq_gemm_group* group, const pq_phase2* phase2) {
@@ -1875,6 +1902,17 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
     // wide row groups (experts of several hundred hidden units, Table 1: r = 384): the 256x256 streaming instantiation,
     // whose loaders clamp a group's last rows like any ragged edge
     if (grp.mode == 1 && N >= 256 && grp.max_rows >= 256 && K % 64 == 0) pl.bm = pl.bn = 256;
+    // contraction ranges with a plain fp32 output whose groups lie one behind the other: cut the ranges (see above)
+    if (grp.mode == 2 && splitk_ws && epi.out_kind == PQ_OUT_F32 && epi.ldc == N && grp.c_stride == (long)M * N && N % 8 == 0 &&
+        !epi.partials && !epi.dot_comp && !epi.sign_bytes && !epi.maskW && !epi.accumulate && !epi.row_div && !epi.col_div &&
+        epi.m_limit == 0 && epi.n_limit == 0) {
+      const int sp = pq_mode2_splits(M, N, grp.n_groups, K);
+      if (sp > 1) {
+        pl.splits = sp;
+        pl.red_blocks = (int)(((size_t)grp.n_groups * M * (N / 8) + 255) / 256);
+        pl.ws_bytes = pq_mode2_ws_bytes(M, N, grp.n_groups, K);
+      }
+    }
     // row groups with a narrow output and a long contraction (expert up/gate projections, their input
     // gradients): too few tiles to fill the chip, so the contraction is split as for plain GEMMs
     // (a per-group column divisor is applied in the GEMM's own epilogue only: such products are not split)
@@ -1916,8 +1954,9 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
   if (rc != PQ_OK) return rc;
   if (pl.splits > 1 && !epi.defer_reduce) {
     pq_prof_scope prof(PQP_SPLITK_REDUCE, s);
-    if (int8) splitk_reduce_kernel<true><<<pl.red_blocks, 256, 0, s>>>(M, N, pl.splits, part, epi);
-    else splitk_reduce_kernel<false><<<pl.red_blocks, 256, 0, s>>>(M, N, pl.splits, part, epi);
+    const int Mred = grp.mode == 2 ? grp.n_groups * M : M;   // grouped ranges: the groups' outputs as one matrix
+    if (int8) splitk_reduce_kernel<true><<<pl.red_blocks, 256, 0, s>>>(Mred, N, pl.splits, part, epi);
+    else splitk_reduce_kernel<false><<<pl.red_blocks, 256, 0, s>>>(Mred, N, pl.splits, part, epi);
     PQ_CHECK_LAUNCH("splitk_reduce_kernel");
   }
   return PQ_OK;

@@ -154,6 +154,8 @@ struct pq_gemm_plan {
   size_t ws_bytes;   // scratch for the split slabs
 };
 pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8 = false, bool split_int8 = false);
+// Scratch a grouped launch over contraction ranges (mode 2; M x N per group, total_k indices over all groups) may use
+size_t pq_mode2_ws_bytes(int M, int N, int n_groups, int total_k);
 // Two bf16 GEMMs with contraction-strided operands on both sides (the rank-r weight gradients dA and dB) in one
 // launch when their plans agree (same tile shape, tile count and contraction split), else one after the other.
 // Both have plain epilogues: C (fp32) = scale * acc.
