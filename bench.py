@@ -175,8 +175,8 @@ def decode_bench(pq, torch, batch, n_layers=64, steps=100, warmup=20, int8_exper
             "us_per_layer": round(total_us / n_layers, 3), "bytes_per_layer": (main_bytes + prep_bytes) // n_layers}
 
 
-def decode_ffn_bench(pq, torch, n_layers=32, steps=100, warmup=20):
-    """The decoupled FFN at inference, one token per layer: 4096 -> 11008 -> 4096 packed 1-bit matrices with E=8
+def decode_ffn_bench(pq, torch, n_layers=32, steps=100, warmup=20, batch=1):
+    """The decoupled FFN at inference, `batch` tokens per layer: 4096 -> 11008 -> 4096 packed 1-bit matrices with E=8
     top-2 experts of hidden width 64, `n_layers` distinct FFNs per call (541 MB of bits)."""
     D, F, E, r, k = 4096, 11008, 8, 64, 2
     g = torch.Generator(device="cuda").manual_seed(9)
@@ -184,22 +184,24 @@ def decode_ffn_bench(pq, torch, n_layers=32, steps=100, warmup=20):
     rnd = lambda *s: torch.randint(-2**31, 2**31 - 1, s, dtype=torch.int32, device="cuda", generator=g)
     Pug = rnd(n_layers, 2, ((F + 63) // 64) * 64 * (D // 32))     # random bits, already in the row-interleaved order
     Pd = rnd(n_layers, ((D + 63) // 64) * 64 * (F // 32))
-    X = torch.randn((n_layers, D), device="cuda", generator=g).to(bf)
+    X = torch.randn((n_layers, batch, D), device="cuda", generator=g).to(bf)
     UpGate = (torch.randn((n_layers, E, 2 * r, D), device="cuda", generator=g) * 0.02).to(bf)
     Down = (torch.randn((n_layers, E, D, r), device="cuda", generator=g) * 0.02).to(bf)
     Wr = (torch.randn((n_layers, E, D), device="cuda", generator=g) * 0.02).to(bf)
     sug = torch.from_numpy(np.full((n_layers, 2), np.float16(0.016)).view(np.int16)).cuda()
     sd = torch.from_numpy(np.full(n_layers, np.float16(0.4 * 0.016)).view(np.int16)).cuda()
-    Y = torch.empty((n_layers, D), dtype=bf, device="cuda")
-    desc = pq.DecodeFFNDesc(D, F, r, E, k, n_layers, 1.5)
+    Y = torch.empty((n_layers, batch, D), dtype=bf, device="cuda")
+    desc = pq.DecodeFFNDesc(D, F, r, E, k, n_layers, 1.5, batch)
     ws = pq.decode_ffn_workspace(desc)
     run = lambda: pq.decode_ffn(desc, X, Pug, sug, Pd, sd, UpGate, Down, Wr, Y, ws)
     _warm(torch, run)
     total_us = 1e3 * _time_steps(torch, run, steps, warmup)
     prof = _profile_steps(pq, torch, run, steps)
-    # algorithmic bytes per layer: three packed matrices, the selected experts (2r x D and D x r bf16), router, x, y
-    per_layer = 3 * D * F // 8 + k * (2 * r * D + D * r) * 2 + E * D * 2 + 4 * D
-    return {"layers_per_call": n_layers, "call_us": round(total_us, 2), "us_per_layer": round(total_us / n_layers, 3),
+    # algorithmic bytes per layer: three packed matrices, the distinct selected experts (2r x D and D x r bf16; the
+    # expected number of distinct experts over the batch's independent top-k choices), router, x, y
+    distinct = E * (1.0 - (1.0 - k / E) ** batch) if batch > 1 else k
+    per_layer = int(3 * D * F // 8 + distinct * (2 * r * D + D * r) * 2 + E * D * 2 + batch * 4 * D)
+    return {"batch": batch, "layers_per_call": n_layers, "call_us": round(total_us, 2), "us_per_layer": round(total_us / n_layers, 3),
             "bytes_per_layer": per_layer, "whole_call_GBps": round(per_layer * n_layers / total_us / 1e3, 1),
             "frac_hbm": round(per_layer * n_layers / total_us / 1e3 / 8000.0, 4),
             "kernels_us_total_per_call": {k_: round(1e3 * ms / steps, 2) for k_, (ms, n) in sorted(prof.items())}}
@@ -450,6 +452,7 @@ def main():
             section("decode_layer_sweep", lambda: {str(n): decode_bench(pq, torch, 1, n_layers=n, steps=50, warmup=10)
                                                    for n in (128, 256)})
         section("decode_ffn", lambda: decode_ffn_bench(pq, torch))
+        section("decode_ffn_B8", lambda: decode_ffn_bench(pq, torch, batch=8))
     if not args.no_norm:
         section("rmsnorm_quant", lambda: norm_quant_bench(pq, torch))
     torch.cuda.empty_cache()

@@ -319,7 +319,12 @@ int pq_decode_gemv_int8(const pq_decode_desc* desc, const void* X, const uint32_
  *   accumulators of the up and gate products, for tests).
  * Four launches: quantiser + router + expert hidden pairs; the 2 L up/gate products; gated unit + quantiser of
  * Hd; the L down products with the experts' down projections.
- * Limits: D % 128 == 0, F % 128 == 0, both <= 16384; r % 8 == 0, r > 0; 1 <= top_k <= E <= 64. */
+ * Limits: D % 128 == 0, F % 128 == 0, both <= 16384; r % 8 == 0, r > 0; 1 <= top_k <= E <= 64.
+ * batch = B > 1 (small-batch decoding, App. A): B tokens per layer through the same stages on the small-batch kernels;
+ *   X and Y are [L][B][D], acc_upgate [L][2][B][F]; the up and gate products of a layer read the layer's B quantised
+ *   tokens once per workgroup, every expert selected by some token is read once per output tile.
+ *   Further limits: B <= 16, r % 32 == 0, (E r) % 64 == 0, and 8 (B <= 8) or 16 token rows of codes (D resp. F bytes
+ *   each) plus the expert hidden states (2 * rows * E * r bytes, at least 8 KiB) must fit 160 KiB of LDS. */
 typedef struct pq_decode_ffn_desc {
   int32_t d_model;   /* D */
   int32_t d_ffn;     /* F */
@@ -328,6 +333,7 @@ typedef struct pq_decode_ffn_desc {
   int32_t top_k;
   int32_t n_layers;  /* L */
   float alpha;
+  int32_t batch;     /* B: tokens per layer, 1..16 (0 stands for 1) */
 } pq_decode_ffn_desc;
 size_t pq_decode_ffn_workspace_bytes(const pq_decode_ffn_desc* desc);
 int pq_decode_ffn(const pq_decode_ffn_desc* desc, const void* X, const uint32_t* packed_upgate, const uint16_t* scale_upgate,

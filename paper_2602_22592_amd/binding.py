@@ -54,7 +54,7 @@ class FFNDesc(C.Structure):
 
 class DecodeFFNDesc(C.Structure):
     _fields_ = [("d_model", C.c_int32), ("d_ffn", C.c_int32), ("hp_rank", C.c_int32), ("n_experts", C.c_int32),
-                ("top_k", C.c_int32), ("n_layers", C.c_int32), ("alpha", C.c_float)]
+                ("top_k", C.c_int32), ("n_layers", C.c_int32), ("alpha", C.c_float), ("batch", C.c_int32)]
 
 
 class PQError(RuntimeError):

@@ -1017,16 +1017,27 @@ int check_dffn(const pq_decode_ffn_desc* d) {
   PQ_REQUIRE(d->hp_rank % 8 == 0, PQ_ERR_SHAPE, "hp_rank=%d must be a multiple of 8", d->hp_rank);
   PQ_REQUIRE(d->n_experts >= 1 && d->n_experts <= 64, PQ_ERR_BAD_ARG, "n_experts=%d must be in 1..64", d->n_experts);
   PQ_REQUIRE(d->top_k >= 1 && d->top_k <= d->n_experts, PQ_ERR_BAD_ARG, "top_k=%d must be in 1..n_experts", d->top_k);
+  PQ_REQUIRE(d->batch >= 0 && d->batch <= 16, PQ_ERR_BAD_ARG, "batch=%d must be in 1..16 (0 stands for 1)", d->batch);
+  if (d->batch > 1) {
+    PQ_REQUIRE(d->hp_rank % 32 == 0 && (d->n_experts * d->hp_rank) % 64 == 0, PQ_ERR_SHAPE,
+               "batch > 1 needs hp_rank=%d %% 32 == 0 and n_experts * hp_rank %% 64 == 0", d->hp_rank);
+    // LDS of the small-batch kernels: 8 or 16 token rows of codes, and for the down product the expert hidden states
+    const size_t toks = d->batch <= 8 ? 8 : 16;
+    const size_t hm = 2 * toks * (size_t)d->n_experts * d->hp_rank;
+    PQ_REQUIRE(toks * (size_t)d->d_model + 8192 <= 160 * 1024 && toks * (size_t)d->d_ffn + (hm < 8192 ? 8192 : hm) <= 160 * 1024,
+               PQ_ERR_SHAPE, "activations and expert hidden states of %d tokens do not fit the 160 KiB LDS", d->batch);
+  }
   return PQ_OK;
 }
 dffn_layout make_dffn_layout(const pq_decode_ffn_desc& d) {
-  pq_decode_desc d1{1, d.d_model, d.d_ffn, 2 * d.hp_rank, d.n_experts, d.top_k, d.n_layers, PQ_PACKED_TILED64, d.alpha};
-  pq_decode_desc d2{1, d.d_ffn, d.d_model, d.hp_rank, d.n_experts, d.top_k, d.n_layers, PQ_PACKED_TILED64, d.alpha};
+  const int B = d.batch > 1 ? d.batch : 1;
+  pq_decode_desc d1{B, d.d_model, d.d_ffn, 2 * d.hp_rank, d.n_experts, d.top_k, d.n_layers, PQ_PACKED_TILED64, d.alpha};
+  pq_decode_desc d2{B, d.d_ffn, d.d_model, d.hp_rank, d.n_experts, d.top_k, d.n_layers, PQ_PACKED_TILED64, d.alpha};
   size_t off[7];
   dffn_layout L;
   cursor c;
   L.ws1 = c.take(pq_decode_ws_layout(d1, off));
-  L.UG = c.take((size_t)2 * d.n_layers * d.d_ffn * 2);
+  L.UG = c.take((size_t)2 * d.n_layers * B * d.d_ffn * 2);
   L.ws2 = c.take(pq_decode_ws_layout(d2, off));
   L.total = c.off;
   return L;
@@ -1049,7 +1060,7 @@ extern "C" int pq_decode_ffn(const pq_decode_ffn_desc* d, const void* X, const u
   const dffn_layout L = make_dffn_layout(*d);
   PQ_REQUIRE(workspace_bytes >= L.total, PQ_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, L.total);
   char* ws = (char*)workspace;
-  return pq_launch_decode_ffn(d->n_layers, d->d_model, d->d_ffn, d->hp_rank, d->n_experts, d->top_k, d->alpha, X, packed_upgate,
+  return pq_launch_decode_ffn(d->n_layers, d->batch > 1 ? d->batch : 1, d->d_model, d->d_ffn, d->hp_rank, d->n_experts, d->top_k, d->alpha, X, packed_upgate,
                               scale_upgate, packed_down, scale_down, UpGate, Down, Wr, Y, acc_upgate, ws + L.UG, ws + L.ws1, ws + L.ws2,
                               (hipStream_t)stream);
 }

@@ -945,6 +945,7 @@ struct gemm16_params {
   int B, N, K, E, r, topk;
   float alpha;
   const float* gB;        // INT8 experts: [L][E][N] gammas of the rows of hpB (then hpB is int8 [L][E][N][r])
+  int xshare;             // > 1: that many consecutive weight sets read the same tokens (codes, row sums, gammas of set / xshare)
 };
 
 constexpr int G16_RT = 4;                           // 16-row MFMA tiles per wavefront
@@ -1187,7 +1188,8 @@ __global__ __launch_bounds__(256, 4) void decode_gemm16_tiled_kernel(gemm16_para
   uint4 w[8];
 #pragma unroll
   for (int jj = 0; jj < 8; ++jj) w[jj] = nt_load16(Pg + (size_t)(jj < nq ? jj : nq - 1) * 64);
-  const unsigned long long used = g16_stage_inputs<TOKS, I8>(p, layer, xs, hm);   // overlaps the first loads
+  const int lx = p.xshare > 1 ? layer / p.xshare : layer;   // the token block this weight set reads
+  const unsigned long long used = g16_stage_inputs<TOKS, I8>(p, lx, xs, hm);   // overlaps the first loads
   const bool active = grp < G;                        // idle wavefronts of the last workgroup still meet the barrier
 
   // experts selected by at least one token of the batch (dense-masked bf16 MFMA, 32 columns of r per issue)
@@ -1317,8 +1319,8 @@ __global__ __launch_bounds__(256, 4) void decode_gemm16_tiled_kernel(gemm16_para
   __builtin_amdgcn_wave_barrier();
   uint16_t* stage = reinterpret_cast<uint16_t*>(patch);
   if (i < p.B) {
-    const float sc = fp16_bits_to_f32(p.scale[layer]) / p.gamma[layer * p.B + i];
-    const int rs = p.rowsum[layer * p.B + i];
+    const float sc = fp16_bits_to_f32(p.scale[layer]) / p.gamma[lx * p.B + i];
+    const int rs = p.rowsum[lx * p.B + i];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       float y[4];
@@ -1362,15 +1364,17 @@ __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + expf(-x));
 // eighth of the columns, which is the expensive part of the quantiser.
 constexpr int FFN_MID_PARTS = 8;
 
-__global__ __launch_bounds__(256) void decode_ffn_mid_kernel(const uint16_t* __restrict__ UG, int F, int r, int topk,
+__global__ __launch_bounds__(256) void decode_ffn_mid_kernel(const uint16_t* __restrict__ UG, int B, int F, int r, int topk,
                                                              const float* __restrict__ hug, float* __restrict__ act,
                                                              int8_t* __restrict__ xq, uint32_t* __restrict__ planes,
                                                              int* __restrict__ rowsum, float* __restrict__ gamma) {
   extern __shared__ __attribute__((aligned(16))) float xs[];   // Hd as fp32 [F]
   __shared__ prep_shared sh;
-  const int layer = blockIdx.x / FFN_MID_PARTS, part = blockIdx.x % FFN_MID_PARTS, tid = threadIdx.x;
-  const uint4* u4 = reinterpret_cast<const uint4*>(UG + (size_t)(2 * layer) * F);
-  const uint4* g4 = reinterpret_cast<const uint4*>(UG + (size_t)(2 * layer + 1) * F);
+  // row = (layer, token); U and G of a layer are two weight sets' outputs, [2 layer + {0, 1}][B][F]
+  const int row = blockIdx.x / FFN_MID_PARTS, part = blockIdx.x % FFN_MID_PARTS, tid = threadIdx.x;
+  const int lay = row / B, tok = row - lay * B;
+  const uint4* u4 = reinterpret_cast<const uint4*>(UG + ((size_t)(2 * lay) * B + tok) * F);
+  const uint4* g4 = reinterpret_cast<const uint4*>(UG + ((size_t)(2 * lay + 1) * B + tok) * F);
   float amax = 0.0f;
   for (int cb = tid; cb < F / 8; cb += 1024) {        // eight loads in flight per thread
     uint4 uu[4], gg[4];
@@ -1401,11 +1405,11 @@ __global__ __launch_bounds__(256) void decode_ffn_mid_kernel(const uint16_t* __r
   if (part == 0)
     for (int o = tid; o < topk * r; o += 256) {
       const int j = o / r, i = o - j * r;
-      const float* hp = hug + ((size_t)layer * topk + j) * 2 * r;
-      act[(size_t)layer * topk * r + o] = silu_f(hp[r + i]) * hp[i];
+      const float* hp = hug + ((size_t)row * topk + j) * 2 * r;
+      act[(size_t)row * topk * r + o] = silu_f(hp[r + i]) * hp[i];
     }
   __syncthreads();                                    // xs complete
-  prep_quantise_slice(amax, (size_t)layer, F, xs, sh, xq, planes, rowsum, gamma, part, FFN_MID_PARTS);
+  prep_quantise_slice(amax, (size_t)row, F, xs, sh, xq, planes, rowsum, gamma, part, FFN_MID_PARTS);
 }
 
 }  // namespace
@@ -1424,11 +1428,90 @@ static int decode_raise_lds_limits() {
   return PQ_OK;
 }
 
-int pq_launch_decode_ffn(int L, int D, int F, int r, int E, int topk, float alpha, const void* X, const uint32_t* packed_upgate,
+static int decode_set_gemm16_limits() {
+  static bool attr_set = false;
+  if (attr_set) return PQ_OK;
+  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<16, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+  attr_set = true;
+  return PQ_OK;
+}
+
+// Several tokens per layer (2..16): the same four stages on the small-batch kernels.  The up and gate products are
+// 2 L weight sets that read their layer's token block (codes staged once per workgroup), the expert hidden pairs come
+// from the per-slot kernel at rank 2 r, the gated unit and the quantiser of Hd run per (layer, token), and the down
+// product carries the experts' down projections.
+static int launch_decode_ffn_batch(int L, int B, int D, int F, int r, int E, int topk, float alpha, const void* X,
+                                   const uint32_t* packed_upgate, const uint16_t* scale_upgate, const uint32_t* packed_down,
+                                   const uint16_t* scale_down, const void* UpGate, const void* Down, const void* Wr, void* Y,
+                                   int32_t* acc_upgate, void* UG, void* ws1, void* ws2, hipStream_t s) {
+  if (int e = decode_set_gemm16_limits()) return e;
+  pq_decode_desc d1{B, D, F, 2 * r, E, topk, L, PQ_PACKED_TILED64, alpha};
+  pq_decode_desc d2{B, F, D, r, E, topk, L, PQ_PACKED_TILED64, alpha};
+  size_t o1[7], o2[7];
+  pq_decode_ws_layout(d1, o1);
+  pq_decode_ws_layout(d2, o2);
+  char* w1 = (char*)ws1;
+  char* w2 = (char*)ws2;
+  int8_t* xq1 = (int8_t*)(w1 + o1[0]); uint32_t* pl1 = (uint32_t*)(w1 + o1[1]); int* rs1 = (int*)(w1 + o1[2]);
+  float* gm1 = (float*)(w1 + o1[3]); int* idx = (int*)(w1 + o1[4]); float* gate = (float*)(w1 + o1[5]); float* hug = (float*)(w1 + o1[6]);
+  int8_t* xq2 = (int8_t*)(w2 + o2[0]); uint32_t* pl2 = (uint32_t*)(w2 + o2[1]); int* rs2 = (int*)(w2 + o2[2]);
+  float* gm2 = (float*)(w2 + o2[3]); float* act = (float*)(w2 + o2[6]);
+  const int toks = B <= 8 ? 8 : 16;
+  {
+    pq_prof_scope prof(PQP_DECODE_PREP, s);
+    decode_prep_kernel<<<L * B * 2, 256, (size_t)D * sizeof(float), s>>>((const uint16_t*)X, (const uint16_t*)Wr, B, D, E, topk, xq1, pl1, rs1,
+                                                                        gm1, idx, gate);
+    PQ_CHECK_LAUNCH("decode_prep_kernel");
+  }
+  {  // hidden pairs [Up_e x ; Gate_e x] of every (token, selected expert)
+    pq_prof_scope prof(PQP_DECODE_H, s);
+    const int total = L * B * topk * 2 * r;
+    decode_h_kernel<<<(total + 3) / 4, 256, 0, s>>>((const uint16_t*)X, (const uint16_t*)UpGate, idx, B, D, E, 2 * r, topk, total, hug);
+    PQ_CHECK_LAUNCH("decode_h_kernel");
+  }
+  {  // U and G
+    pq_prof_scope prof(PQP_DECODE_MAIN, s);
+    gemm16_params p{packed_upgate, scale_upgate, xq1, rs1, gm1, nullptr, nullptr, nullptr, nullptr, (uint16_t*)UG, acc_upgate,
+                    B, F, D, 0, 0, 0, alpha, nullptr, 2};
+    const size_t lds = (size_t)toks * D + 8192;
+    dim3 grid(((F + 63) / 64 + 3) / 4, 2 * L);
+    if (toks == 8) decode_gemm16_tiled_kernel<8><<<grid, 256, lds, s>>>(p);
+    else decode_gemm16_tiled_kernel<16><<<grid, 256, lds, s>>>(p);
+    PQ_CHECK_LAUNCH("decode_gemm16_tiled_kernel");
+  }
+  {
+    pq_prof_scope prof(PQP_SWIGLU, s);
+    decode_ffn_mid_kernel<<<L * B * FFN_MID_PARTS, 256, (size_t)F * sizeof(float), s>>>((const uint16_t*)UG, B, F, r, topk, hug, act, xq2, pl2,
+                                                                                       rs2, gm2);
+    PQ_CHECK_LAUNCH("decode_ffn_mid_kernel");
+  }
+  {  // down product + experts' down projections
+    pq_prof_scope prof(PQP_DECODE_MAIN, s);
+    gemm16_params p{packed_down, scale_down, xq2, rs2, gm2, (const uint16_t*)Down, idx, gate, act, (uint16_t*)Y, nullptr,
+                    B, D, F, E, r, topk, alpha, nullptr, 1};
+    const size_t hm = 2 * (size_t)toks * E * r;
+    const size_t lds = (size_t)toks * F + (hm > 8192 ? hm : 8192);
+    dim3 grid(((D + 63) / 64 + 3) / 4, L);
+    if (toks == 8) decode_gemm16_tiled_kernel<8><<<grid, 256, lds, s>>>(p);
+    else decode_gemm16_tiled_kernel<16><<<grid, 256, lds, s>>>(p);
+    PQ_CHECK_LAUNCH("decode_gemm16_tiled_kernel");
+  }
+  return PQ_OK;
+}
+
+int pq_launch_decode_ffn(int L, int B, int D, int F, int r, int E, int topk, float alpha, const void* X, const uint32_t* packed_upgate,
                          const uint16_t* scale_upgate, const uint32_t* packed_down, const uint16_t* scale_down,
                          const void* UpGate, const void* Down, const void* Wr, void* Y, int32_t* acc_upgate, void* UG,
                          void* ws1, void* ws2, hipStream_t s) {
   if (int e = decode_raise_lds_limits()) return e;
+  if (B > 1)
+    return launch_decode_ffn_batch(L, B, D, F, r, E, topk, alpha, X, packed_upgate, scale_upgate, packed_down, scale_down, UpGate, Down, Wr,
+                                   Y, acc_upgate, UG, ws1, ws2, s);
   pq_decode_desc d1{1, D, F, 2 * r, E, topk, L, PQ_PACKED_TILED64, alpha};
   pq_decode_desc d2{1, F, D, r, E, topk, L, PQ_PACKED_TILED64, alpha};
   size_t o1[7], o2[7];
@@ -1457,7 +1540,7 @@ int pq_launch_decode_ffn(int L, int D, int F, int r, int E, int topk, float alph
   }
   {  // gated unit, quantiser of Hd, experts' gated unit
     pq_prof_scope prof(PQP_SWIGLU, s);
-    decode_ffn_mid_kernel<<<L * FFN_MID_PARTS, 256, (size_t)F * sizeof(float), s>>>((const uint16_t*)UG, F, r, topk, hug, act, xq2, pl2, rs2, gm2);
+    decode_ffn_mid_kernel<<<L * FFN_MID_PARTS, 256, (size_t)F * sizeof(float), s>>>((const uint16_t*)UG, 1, F, r, topk, hug, act, xq2, pl2, rs2, gm2);
     PQ_CHECK_LAUNCH("decode_ffn_mid_kernel");
   }
   {  // down product + experts' down projections
@@ -1551,21 +1634,12 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
     }
   } else {
     gemm16_params p{packed, scale_fp16, xq, rowsum, gamma, (const uint16_t*)hpB, idx, gate, h, (uint16_t*)Y, acc_out,
-                    B, N, K, d.n_experts, r, d.top_k, d.alpha, gB};
+                    B, N, K, d.n_experts, r, d.top_k, d.alpha, gB, 1};
     const int toks = B <= 8 ? 8 : 16;
     const bool tiled = d.packed_layout == PQ_PACKED_TILED64;
     const size_t hm_bytes = 2 * (size_t)toks * d.n_experts * r;
     const size_t lds = (size_t)toks * K + (tiled ? (hm_bytes > 8192 ? hm_bytes : 8192) : hm_bytes);
-    static bool attr_set = false;
-    if (!attr_set) {
-      PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-      PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-      PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-      PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-      PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-      PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<16, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-      attr_set = true;
-    }
+    if (int e = decode_set_gemm16_limits()) return e;
     if (tiled) {
       dim3 grid(((N + 63) / 64 + 3) / 4, L);
       if (i8) {

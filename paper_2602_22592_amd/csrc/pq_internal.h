@@ -183,7 +183,7 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
                      const void* hpA, const void* hpB, const void* Wr, void* Y, int32_t* acc_out, void* workspace,
                      hipStream_t s, const float* gA = nullptr, const float* gB = nullptr);
 int pq_launch_retile64(const uint32_t* packed, int N, int K, uint32_t* tiled, hipStream_t s);
-int pq_launch_decode_ffn(int L, int D, int F, int r, int E, int topk, float alpha, const void* X, const uint32_t* packed_upgate,
+int pq_launch_decode_ffn(int L, int B, int D, int F, int r, int E, int topk, float alpha, const void* X, const uint32_t* packed_upgate,
                          const uint16_t* scale_upgate, const uint32_t* packed_down, const uint16_t* scale_down,
                          const void* UpGate, const void* Down, const void* Wr, void* Y, int32_t* acc_upgate, void* UG,
                          void* ws1, void* ws2, hipStream_t s);

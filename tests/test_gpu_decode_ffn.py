@@ -23,16 +23,17 @@ def relerr(a, b):
     return float(np.abs(a - b).max() / max(np.abs(b).max(), 1e-30))
 
 
-def _case(seed, L, D, F, E, r):
+def _case(seed, L, D, F, E, r, B=1):
     rng = np.random.default_rng(seed)
-    return dict(X=wl.activations(rng, L, D, bf16=True), Wu=wl.normal(rng, (L, F, D), 0.02, True),
+    return dict(X=wl.activations(rng, L * B, D, bf16=True).reshape(L, B, D), Wu=wl.normal(rng, (L, F, D), 0.02, True),
                 Wg=wl.normal(rng, (L, F, D), 0.02, True), Wd=wl.normal(rng, (L, D, F), 0.02, True),
                 Up=wl.normal(rng, (L, E, r, D), 0.02, True), Gate=wl.normal(rng, (L, E, r, D), 0.02, True),
                 Down=wl.normal(rng, (L, E, D, r), 0.02, True), Wr=wl.normal(rng, (L, E, D), 0.02, True))
 
 
-def check(L, D, F, E, r, k, alpha=1.5, beta=0.4, seed=0):
-    c = _case(300 + D + F + seed, L, D, F, E, r)
+def check(L, D, F, E, r, k, alpha=1.5, beta=0.4, seed=0, B=1):
+    """B tokens per layer: every token of a layer is checked against the oracle's per-token FFN on that layer's weights."""
+    c = _case(300 + D + F + seed + B, L, D, F, E, r, B)
     pu, pd, su, sd, lams = [], [], [], [], []
     for l in range(L):                                   # offline: binarise, pack, re-tile, fold the scalars to fp16
         Pu, _, mlu = pq.pack_sign(dev(c["Wu"][l], True))
@@ -48,11 +49,11 @@ def check(L, D, F, E, r, k, alpha=1.5, beta=0.4, seed=0):
     packed_d = torch.stack(pd).contiguous()
     scale_ug = dev(np.array(su, np.float16).view(np.int16))
     scale_d = dev(np.array(sd, np.float16).view(np.int16))
-    desc = pq.DecodeFFNDesc(D, F, r, E, k, L, alpha)
+    desc = pq.DecodeFFNDesc(D, F, r, E, k, L, alpha, B)
     ws = pq.decode_ffn_workspace(desc)
     UpGate = dev(np.concatenate([c["Up"], c["Gate"]], axis=2), True)      # [L][E][2r][D]
-    Y = torch.empty((L, D), dtype=torch.bfloat16, device="cuda")
-    acc = torch.empty((L, 2, F), dtype=torch.int32, device="cuda")
+    Y = torch.empty((L, B, D), dtype=torch.bfloat16, device="cuda")
+    acc = torch.empty((L, 2, B, F), dtype=torch.int32, device="cuda")
     pq.decode_ffn(desc, dev(c["X"], True), packed_ug, scale_ug, packed_d, scale_d, UpGate, dev(c["Down"], True),
                   dev(c["Wr"], True), Y, ws, acc_upgate=acc)
     torch.cuda.synchronize()
@@ -64,11 +65,12 @@ def check(L, D, F, E, r, k, alpha=1.5, beta=0.4, seed=0):
             mu, lam = po.weight_stats(W)
             refs.append((po.pack_sign(po.binarise(W, mu)), lam))
         assert tuple(np.float32(x[1]) for x in refs) == lams[l]
-        f = po.decode_ffn(c["X"][l:l + 1], refs[0][0], refs[1][0], refs[2][0], refs[0][1], refs[1][1], refs[2][1],
+        f = po.decode_ffn(c["X"][l], refs[0][0], refs[1][0], refs[2][0], refs[0][1], refs[1][1], refs[2][1],
                           c["Up"][l], c["Gate"][l], c["Down"][l], c["Wr"][l], alpha, beta, top_k=k)
-        assert np.array_equal(acc[l, 0].astype(np.int64), f["acc_u"][0]), f"layer {l}: up accumulators differ"
-        assert np.array_equal(acc[l, 1].astype(np.int64), f["acc_g"][0]), f"layer {l}: gate accumulators differ"
-        worst = max(worst, relerr(Y[l], f["Y"][0]))
+        assert np.array_equal(acc[l, 0].astype(np.int64), f["acc_u"]), f"layer {l}: up accumulators differ"
+        assert np.array_equal(acc[l, 1].astype(np.int64), f["acc_g"]), f"layer {l}: gate accumulators differ"
+        for b in range(B):
+            worst = max(worst, relerr(Y[l, b], f["Y"][b]))
     print(f"  decode FFN max-norm relative error {worst:.2e}", flush=True)
     assert worst <= 2e-2
 
@@ -78,6 +80,27 @@ def check(L, D, F, E, r, k, alpha=1.5, beta=0.4, seed=0):
 def test_decode_ffn(L, D, F, E, r, k):
     print(f"decode FFN: L={L} D={D} F={F} E={E} r={r} k={k}", flush=True)
     check(L, D, F, E, r, k)
+
+
+@pytest.mark.parametrize("L,B,D,F,E,r,k", [(2, 2, 256, 384, 4, 32, 2), (1, 8, 640, 1152, 8, 32, 3), (2, 5, 2048, 5504, 8, 32, 1),
+                                           (1, 16, 512, 640, 2, 64, 1), (1, 11, 384, 256, 4, 32, 2)])
+def test_decode_ffn_small_batch(L, B, D, F, E, r, k):
+    """Several tokens per layer (App. A, small-batch decoding): the accumulators of the up and gate products bit-exact
+    per token, every token's output within 2e-2 of the oracle's per-token FFN."""
+    print(f"decode FFN batch: L={L} B={B} D={D} F={F} E={E} r={r} k={k}", flush=True)
+    check(L, D, F, E, r, k, B=B)
+
+
+def test_decode_ffn_config4_shape_batch8():
+    print("decode FFN 4096 -> 11008 -> 4096, E=8 top-2 r=64, 8 tokens, two layers", flush=True)
+    check(2, 4096, 11008, 8, 64, 2, B=8)
+
+
+def test_decode_ffn_batch_limits():
+    with pytest.raises(pq.PQError):
+        pq.decode_ffn_workspace(pq.DecodeFFNDesc(256, 256, 16, 4, 2, 1, 1.0, 4))    # batch > 1 needs r % 32 == 0
+    with pytest.raises(pq.PQError):
+        pq.decode_ffn_workspace(pq.DecodeFFNDesc(256, 256, 32, 4, 2, 1, 1.0, 17))   # at most 16 tokens
 
 
 def test_decode_ffn_config4_shape():
