@@ -441,7 +441,7 @@ def main():
     if args.calibrate:
         # a counter run: only the workloads whose kernels are looked up in the counter files, so that a kernel name
         # stands for one workload (the INT8-expert decode variants and the FFN stack launch the same kernels on other sizes)
-        args.no_ffn = args.no_stack = args.no_norm = args.no_hp8 = args.no_paper_ffn = args.no_cpu_baseline = True
+        args.no_ffn = args.no_stack = args.no_hp8 = args.no_paper_ffn = args.no_cpu_baseline = True
         section("decode_gemv", lambda: {"B1": decode_bench(pq, torch, 1), "B8": decode_bench(pq, torch, 8)})
     elif not args.no_decode:
         section("decode_gemv", lambda: {"metric": "1-bit decode GEMV HBM GB/s (4096->11008, E=8 top-2 r=64 experts)",
