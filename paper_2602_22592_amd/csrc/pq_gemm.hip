@@ -3,14 +3,16 @@
 //
 //   C[m][n] (+)= epilogue( sum_k A(m,k) * B(n,k) )
 //
-// Both operands are staged through LDS as tiles of ROWS x 128 bytes with the contraction index
-// contiguous (64 bf16 or 128 int8 per row), whatever their layout in HBM:
-//   KC16 / KC8   contraction-contiguous rows are copied 16 bytes at a time;
-//   KS16         contraction-strided sources (the transposed operands of the weight-gradient
-//                GEMMs) are read as 8x8 blocks of 16-bit elements, transposed in registers with
-//                byte permutes and written as 16-byte chunks;
-//   BITS8/BITS16 packed sign bits are expanded to +/-1 (int8 or bf16) on the way into LDS, so the
-//                1-bit weights cross HBM and L2 as bits (Sec. 3.1 W^INT1; App. A packing).
+// Operand sources (the 1-bit weights cross HBM and L2 as bits in every case: Sec. 3.1 W^INT1; App. A packing):
+//   KC16 / KC8   contraction-contiguous rows, 16 bytes at a time;
+//   KS16         contraction-strided sources (the transposed operands of the weight-gradient GEMMs);
+//   BITS8/BITS16 packed sign bits, expanded to +/-1 (int8 or bf16).
+// Two main loops share the kernel.  The streaming loop (256x256 tiles, whole contraction steps) sends operands from
+// global memory straight into LDS: KC tiles as ROWS x 128 bytes, KS16 tiles as they lie in memory (read back with the
+// transposing LDS read), and packed bits stay packed in LDS and are expanded in registers next to the MFMAs that consume
+// them.  The register-staged loop (ragged contraction steps, 128x128 tiles, grouped contraction ranges) stages every
+// operand as ROWS x 128 bytes with the contraction index contiguous: KS16 blocks are transposed in registers with byte
+// permutes, bits are expanded on the way into LDS.
 // A wavefront owns a (BM/WGM) x (BN/WGN) sub-tile as 32x32 MFMA blocks:
 //   v_mfma_f32_32x32x16_bf16 / v_mfma_i32_32x32x32_i8, 16 bytes of operand per lane per issue.
 // LDS rows are 128 bytes with the 16-byte chunk index XOR-swizzled by the row so that the MFMA
