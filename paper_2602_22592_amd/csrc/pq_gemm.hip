@@ -1144,6 +1144,96 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
     for (int r = tid; r < BM; r += NT) rowscale[r] = st.sc0 / epi.row_div[min(m0 + r, M - 1)];
     __syncthreads();
   }
+#ifdef PQ_NO_STAGE
+  constexpr bool CAN_STAGE = false;
+#else
+  constexpr bool CAN_STAGE = (BM == 256 && BN == 256 && SMEM_BYTES >= 8 * 16384);
+#endif
+  const bool staged = CAN_STAGE && (slab || ((epi.out_kind == PQ_OUT_BF16 || epi.out_kind == PQ_OUT_F32) && epi.m_limit == 0 &&
+                                             epi.n_limit == 0 && !epi.col_div && !epi.maskW && !epi.accumulate && !epi.dot_comp &&
+                                             !epi.sign_bytes));   // uniform
+  if (staged) {
+    const bool o16 = !slab && epi.out_kind == PQ_OUT_BF16;
+    int tid_e = threadIdx.x;
+    asm volatile("" : "+v"(tid_e));
+    const int lane_e = tid_e & 63, wave_e = tid_e >> 6;
+    const int wm0_e = (wave_e / WGN) * WM, wn0_e = (wave_e % WGN) * WN;
+    unsigned char* wreg = smem + wave_e * 16384;
+    char* outp = slab ? (char*)slab : (char*)epi.C;
+    const size_t ldo = slab ? (size_t)N * 4 : (size_t)epi.ldc * (o16 ? 2 : 4);
+    const int hh = lane_e >> 5;
+    auto run = [&](auto o16_c) {
+    constexpr bool o16 = decltype(o16_c)::value;
+#pragma unroll
+    for (int pass = 0; pass < (o16 ? 1 : 2); ++pass) {
+#pragma unroll
+      for (int ii = 0; ii < (o16 ? TM : TM / 2); ++ii) {
+        const int i = o16 ? ii : pass * (TM / 2) + ii;
+        const int rl = ii * 32 + (lane_e & 31);
+        const int m = m0 + wm0_e + i * 32 + (lane_e & 31);
+        const float rs = row_scaled ? rowscale[m - m0] : __builtin_nanf("");
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            uint32_t w[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+              if (slab) {
+                // copy the element out first: a vector element is not a bit_cast-able lvalue
+                if constexpr (PH2) { const float e = accf[i][j][4 * g + t]; w[t] = __float_as_uint(e); }
+                else { const auto e = acc[i][j][4 * g + t]; w[t] = __builtin_bit_cast(uint32_t, e); }
+              } else {
+                const float sc = row_scaled ? rs : st.sc0;
+                float a;
+                if constexpr (PH2) a = accf[i][j][4 * g + t];
+                else a = (float)acc[i][j][4 * g + t];
+                w[t] = __float_as_uint(__fmul_rn(sc, a));
+              }
+            }
+            if constexpr (o16) {
+              const uint2 o = make_uint2(pack_bf16x2(__uint_as_float(w[0]), __uint_as_float(w[1])),
+                                         pack_bf16x2(__uint_as_float(w[2]), __uint_as_float(w[3])));
+              *reinterpret_cast<uint2*>(wreg + rl * 128 + (((j * 4 + g) ^ (rl & 7)) << 4) + hh * 8) = o;
+            } else {
+              // written as asm with two wait states behind it: the compiler puts no distance between a 16-byte LDS store and a
+              // VALU write to its data registers (it does for 16-byte global stores), and a staged epilogue whose last store was
+              // followed at once by such writes lost that store's data in part
+              const i32x4_t o = {(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+              const uint32_t ad = (uint32_t)(size_t)(wreg + rl * 256 + (((j * 8 + 2 * g + hh) ^ (rl & 7)) << 4));
+              asm volatile("ds_write_b128 %0, %1\n\ts_nop 1" ::"v"(ad), "v"(o) : "memory");
+            }
+          }
+        }
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_wave_barrier();
+      if constexpr (o16) {
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+          const int rl = it * 8 + (lane_e >> 3), c = lane_e & 7;
+          const uint4 v = *reinterpret_cast<const uint4*>(wreg + rl * 128 + ((c ^ (rl & 7)) << 4));
+          const int m = m0 + wm0_e + rl, n = n0 + wn0_e + c * 8;
+          if (m < M && n < N) *reinterpret_cast<uint4*>(outp + (size_t)m * ldo + (size_t)n * 2) = v;
+        }
+      } else {
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+          const int rl = it * 4 + (lane_e >> 4), c = lane_e & 15;
+          const uint4 v = *reinterpret_cast<const uint4*>(wreg + rl * 256 + ((c ^ (rl & 7)) << 4));
+          const int m = m0 + wm0_e + pass * 64 + rl, n = n0 + wn0_e + c * 4;
+          if (m < M && n < N) *reinterpret_cast<uint4*>(outp + (size_t)m * ldo + (size_t)n * 4) = v;
+        }
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_wave_barrier();
+    }
+    };
+    if (o16) run(std::true_type{});
+    else run(std::false_type{});
+    if (!slab) epi_end<NT>(epi, st, red, blockIdx.x);
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int m = m0 + wm0 + i * 32 + (lane & 31);
