@@ -1149,8 +1149,9 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
 #else
   constexpr bool CAN_STAGE = (BM == 256 && BN == 256 && SMEM_BYTES >= 8 * 16384);
 #endif
-  const bool staged = CAN_STAGE && (slab || ((epi.out_kind == PQ_OUT_BF16 || epi.out_kind == PQ_OUT_F32) && epi.m_limit == 0 &&
-                                             epi.n_limit == 0 && !epi.col_div && !epi.maskW && !epi.accumulate && !epi.dot_comp &&
+  // (store limits: fp32 outputs only, where a 16-byte chunk is four columns and the column limit a multiple of four)
+  const bool staged = CAN_STAGE && (slab || ((epi.out_kind == PQ_OUT_F32 || (epi.out_kind == PQ_OUT_BF16 && epi.m_limit == 0 && epi.n_limit == 0)) &&
+                                             !epi.col_div && !epi.maskW && !epi.accumulate && !epi.dot_comp &&
                                              !epi.sign_bytes));   // uniform
   if (staged) {
     const bool o16 = !slab && epi.out_kind == PQ_OUT_BF16;
@@ -1162,6 +1163,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
     char* outp = slab ? (char*)slab : (char*)epi.C;
     const size_t ldo = slab ? (size_t)N * 4 : (size_t)epi.ldc * (o16 ? 2 : 4);
     const int hh = lane_e >> 5;
+    const int mlim = (!slab && epi.m_limit > 0 && epi.m_limit < M) ? epi.m_limit : M;
+    const int nlim = (!slab && epi.n_limit > 0 && epi.n_limit < N) ? epi.n_limit : N;
     auto run = [&](auto o16_c) {
     constexpr bool o16 = decltype(o16_c)::value;
 #pragma unroll
@@ -1222,7 +1225,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
           const int rl = it * 4 + (lane_e >> 4), c = lane_e & 15;
           const uint4 v = *reinterpret_cast<const uint4*>(wreg + rl * 256 + ((c ^ (rl & 7)) << 4));
           const int m = m0 + wm0_e + pass * 64 + rl, n = n0 + wn0_e + c * 4;
-          if (m < M && n < N) *reinterpret_cast<uint4*>(outp + (size_t)m * ldo + (size_t)n * 4) = v;
+          if (m < mlim && n < nlim) *reinterpret_cast<uint4*>(outp + (size_t)m * ldo + (size_t)n * 4) = v;
         }
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
