@@ -1382,6 +1382,218 @@ __global__ __launch_bounds__(256) void ref_gemm_kernel(int M, int N, int K, pq_o
   epi_end<256>(epi, st, red, blockIdx.y * gridDim.x + blockIdx.x);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Weight-gradient GEMMs (both operands bf16 with the contraction index as rows: dW = dY^T X over the tokens):
+// a 256x256 tile on FOUR wavefronts.
+// ---------------------------------------------------------------------------------------------
+// With real (non-constant) operand data the chip runs these kernels against its power limit: the shader clock of the
+// eight-wavefront kernel above falls from 2.3 GHz on all-zero operands to 1.7 GHz on normally distributed ones, and what
+// LDS reads and direct loads cost shows as clock, not as stalls.  A wavefront that owns 128x128 of the tile reads eight
+// operand blocks per sixteen MFMAs where a 128x64 one reads six per eight: a third less LDS traffic for the same products.
+// Its 256 accumulator registers live in AGPRs (one wavefront per SIMD has 512 registers), which leaves the arch VGPRs for
+// two fragment sets.  One wavefront per SIMD keeps the matrix pipe busy on its own as long as every wait it meets has
+// been satisfied long before, so the order below is fixed (volatile asm statements): a stage is 32 contraction rows
+// ([32][512 B] per operand, chunk c of row t at chunk c ^ 4 (t & 3), as in the streaming loop above), the ring has four
+// stages, and per stage a wavefront issues 32 MFMAs in four groups of eight: behind each MFMA of groups 0 and 2 goes one
+// operand block (two transposing reads) of the fragment set after the current one, behind each MFMA of group 1 one direct
+// load of the stage three ahead.  The single barrier of a stage sits between groups 0 and 1: by then the wavefront's own
+// loads of the next stage have landed (vmcnt), after it everybody's have and nobody reads the stage before the current
+// one, whose slot the new loads take.  Past the last stage the loads re-request the last one into a free slot, so the
+// counters stay uniform.
+// The epilogue passes the accumulators through the wavefront's 32 KB of the ring, 64 rows at a time, and reads whole
+// 512-byte rows back: raw slabs of a split contraction and plain fp32 outputs leave as 16-byte stores of whole rows, every
+// other epilogue goes through epi_vec8 with eight consecutive columns per lane.
+#define PQ_MFMA_BF16_ACC(acc, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %2, %1, %0" : "+a"(acc) : "v"(a), "v"(b))
+struct pq_frag_set_w4 {
+  pq_i32x2 h[16];   // h[2q], h[2q+1]: the halves of operand block q; q = 0..3 rows of A (tile rows), 4..7 rows of B (tile columns)
+  __device__ __forceinline__ i32x4_t op(int q) const { return i32x4_t{h[2 * q][0], h[2 * q][1], h[2 * q + 1][0], h[2 * q + 1][1]}; }
+  __device__ __forceinline__ void wait_all() {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(h[0]), "+v"(h[1]), "+v"(h[2]), "+v"(h[3]), "+v"(h[4]), "+v"(h[5]), "+v"(h[6]), "+v"(h[7]), "+v"(h[8]), "+v"(h[9]),
+                   "+v"(h[10]), "+v"(h[11]), "+v"(h[12]), "+v"(h[13]), "+v"(h[14]), "+v"(h[15]));
+  }
+};
+
+__global__ __launch_bounds__(256) void gemm_tn_w4_kernel(int M, int N, int K, pq_operand A, pq_operand B, pq_epilogue epi, int nbn,
+                                                          int total_tiles, int kchunk, float* splitk_part) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  constexpr int STG = 32768;
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * STG];
+  __shared__ double red[4];
+  int pid = blockIdx.x, split = blockIdx.y;
+  {   // XCD-aware order, as in mfma_gemm_kernel
+    const int nb = total_tiles * (int)gridDim.y;
+    if ((nb & 7) == 0) {
+      const int lin = blockIdx.x + total_tiles * blockIdx.y;
+      const int w = (lin & 7) * (nb >> 3) + (lin >> 3);
+      split = w / total_tiles;
+      pid = w - split * total_tiles;
+    }
+  }
+  const int bm = pid / nbn, bn = pid % nbn;
+  const int m0 = bm * 256, n0 = bn * 256;
+  const int kb = split * kchunk, ke = min(K, kb + kchunk);
+  const int nkt = ke > kb ? (ke - kb) >> 5 : 0;      // whole stages (the launcher checks)
+  const int lane = threadIdx.x & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm0 = (wv >> 1) * 128, wn0 = (wv & 1) * 128;
+  const uint32_t lds0 = (uint32_t)(size_t)smem;
+
+  f32x16_t acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // direct loads: instruction block qi of an operand is 1 KB of its stage (two contraction rows); a wavefront owns four
+  // blocks of each operand.  Columns past the end fetch the tile's first chunk (any valid address: never stored).
+  const char* src[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int qi = wv * 4 + (i & 3);
+    const int t = qi * 2 + (lane >> 5), pc = lane & 31;
+    const int c = pc ^ (4 * (t & 3));
+    const pq_operand& op = i < 4 ? A : B;
+    const int col0 = i < 4 ? m0 : n0, cols = i < 4 ? M : N;
+    int col = col0 + c * 8;
+    if (col + 8 > cols) col = col0;
+    src[i] = (const char*)op.p + ((size_t)(kb + t) * op.ld + col) * 2;
+  }
+  const size_t advA = (size_t)32 * A.ld * 2, advB = (size_t)32 * B.ld * 2;
+  auto issue1 = [&](int kt, int slot, int i) {
+    unsigned char* base = smem + slot * STG + wv * 4096;
+    if (i < 4) __builtin_amdgcn_global_load_lds(src[i] + (size_t)kt * advA, PQ_LDS_PTR(base + i * 1024), 16, 0, 0);
+    else __builtin_amdgcn_global_load_lds(src[i] + (size_t)kt * advB, PQ_LDS_PTR(base + 16384 + (i - 4) * 1024), 16, 0, 0);
+  };
+
+  // fragment read addresses (slot 0, contraction rows 0..15): see the transposing reads of the streaming loop
+  uint32_t ad[8];
+  {
+    const int h = lane >> 5;
+    const int tl = 8 * h + ((lane & 15) >> 2), cl = 16 * ((lane >> 4) & 1) + 4 * (lane & 3), sw = 4 * ((lane & 15) >> 2);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int col = (q < 4 ? wm0 + 32 * q : wn0 + 32 * (q - 4)) + cl;
+      ad[q] = lds0 + (q < 4 ? 0 : 16384) + tl * 512 + (((col >> 3) ^ sw) << 4) + (col & 7) * 2;
+    }
+  }
+  pq_frag_set_w4 F0, F1;
+  auto rd = [&](pq_frag_set_w4& F, int q, uint32_t so, auto ks_c) {
+    constexpr int ks = decltype(ks_c)::value;
+    const uint32_t pa = ad[q] + so;
+    PQ_DS_READ_TR(F.h[2 * q], pa, ks * 8192);
+    PQ_DS_READ_TR(F.h[2 * q + 1], pa, ks * 8192 + 2048);
+  };
+  auto mf = [&](const pq_frag_set_w4& X, int n) {
+    const int i = n >> 2, j = (n & 3) ^ ((i & 1) ? 3 : 0);   // a block of B stays for two MFMAs in a row
+    PQ_MFMA_BF16_ACC(acc[i][j], X.op(i), X.op(4 + j));
+  };
+  using c0 = std::integral_constant<int, 0>;
+  using c1 = std::integral_constant<int, 1>;
+
+  if (nkt > 0) {
+#pragma unroll
+    for (int u = 0; u < 3; ++u)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) issue1(min(u, nkt - 1), u, i);
+    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    asm volatile("s_barrier" ::: "memory");
+#pragma unroll
+    for (int q = 0; q < 8; ++q) rd(F0, q, 0u, c0{});
+  }
+  for (int kt = 0; kt < nkt; ++kt) {
+    const uint32_t so = (uint32_t)(kt & 3) * STG, sn = (uint32_t)((kt + 1) & 3) * STG;
+    const int ktl = min(kt + 3, nkt - 1), sl = (kt + 3) & 3;
+    F0.wait_all();
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      mf(F0, n);
+      rd(F1, n, so, c1{});
+    }
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // the wavefront's own loads of stage kt+1 have landed
+    asm volatile("s_barrier" ::: "memory");            // everybody's have; nobody reads stage kt-1 any more
+#pragma unroll
+    for (int n = 8; n < 16; ++n) {
+      mf(F0, n);
+      issue1(ktl, sl, n - 8);
+    }
+    F1.wait_all();
+#pragma unroll
+    for (int n = 0; n < 16; ++n) {
+      mf(F1, n);
+      if (n < 8) rd(F0, n, sn, c0{});                  // past the last stage: a slot nobody uses
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+  asm volatile("s_barrier" ::: "memory");
+
+  // ---- epilogue ----------------------------------------------------------------------------------
+  epi_state st;
+  epi_begin(epi, st);
+  float* slab = splitk_part ? splitk_part + (size_t)split * M * N : nullptr;
+  const bool plain = !slab && epi.out_kind == PQ_OUT_F32 && !epi.col_div && !epi.maskW && !epi.accumulate && !epi.dot_comp &&
+                     !epi.sign_bytes;                 // uniform
+  unsigned tid_e = threadIdx.x;
+  asm volatile("" : "+v"(tid_e));
+  const int lane_e = tid_e & 63, wave_e = tid_e >> 6;
+  const int wm_e = (wave_e >> 1) * 128, wn_e = (wave_e & 1) * 128;
+  unsigned char* wreg = smem + wave_e * STG;
+  const int mlim = (!slab && epi.m_limit > 0 && epi.m_limit < M) ? epi.m_limit : M;
+  const int nlim = (!slab && epi.n_limit > 0 && epi.n_limit < N) ? epi.n_limit : N;
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int i = 2 * pass + ii;
+          // (copy the elements out first: a vector element is not a bit_cast-able lvalue)
+          const float w0 = acc[i][j][4 * g], w1 = acc[i][j][4 * g + 1], w2 = acc[i][j][4 * g + 2], w3 = acc[i][j][4 * g + 3];
+          const i32x4_t o = {(int)__float_as_uint(w0), (int)__float_as_uint(w1), (int)__float_as_uint(w2), (int)__float_as_uint(w3)};
+          const int rl = ii * 32 + (lane_e & 31);
+          const uint32_t adw = (uint32_t)(size_t)(wreg + rl * 512 + (((j * 8 + 2 * g + (lane_e >> 5)) ^ (rl & 31)) << 4));
+          // (asm with two wait states behind it: see the staged epilogue of mfma_gemm_kernel)
+          asm volatile("ds_write_b128 %0, %1\n\ts_nop 1" ::"v"(adw), "v"(o) : "memory");
+        }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_wave_barrier();
+    if (slab || plain) {
+      char* outp = slab ? (char*)slab : (char*)epi.C;
+      const size_t ldo = (slab ? (size_t)N : (size_t)epi.ldc) * 4;
+#pragma unroll 4
+      for (int it = 0; it < 32; ++it) {
+        const int rl = it * 2 + (lane_e >> 5), c = lane_e & 31;
+        uint4 v = *reinterpret_cast<const uint4*>(wreg + rl * 512 + ((c ^ (rl & 31)) << 4));
+        if (!slab) {
+          v.x = __float_as_uint(__fmul_rn(st.sc0, __uint_as_float(v.x)));
+          v.y = __float_as_uint(__fmul_rn(st.sc0, __uint_as_float(v.y)));
+          v.z = __float_as_uint(__fmul_rn(st.sc0, __uint_as_float(v.z)));
+          v.w = __float_as_uint(__fmul_rn(st.sc0, __uint_as_float(v.w)));
+        }
+        const int m = m0 + wm_e + pass * 64 + rl, n = n0 + wn_e + c * 4;
+        if (m < mlim && n < nlim) *reinterpret_cast<uint4*>(outp + (size_t)m * ldo + (size_t)n * 4) = v;
+      }
+    } else {
+#pragma unroll 2
+      for (int it = 0; it < 16; ++it) {
+        const int rl = it * 4 + (lane_e >> 4), c = (lane_e & 15) * 2;
+        const uint4 r0 = *reinterpret_cast<const uint4*>(wreg + rl * 512 + ((c ^ (rl & 31)) << 4));
+        const uint4 r1 = *reinterpret_cast<const uint4*>(wreg + rl * 512 + (((c + 1) ^ (rl & 31)) << 4));
+        const int m = m0 + wm_e + pass * 64 + rl, n = n0 + wn_e + c * 4;
+        if (m < M && n < N) epi_vec8<false>(epi, st, m, n, r0, r1);
+      }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_wave_barrier();
+  }
+  if (!slab) epi_end<256>(epi, st, red, blockIdx.x);
+#endif
+}
+
 template <int BM, int BN, int WGM, int WGN, int KB, bool FAST, bool INT8, int AK, int BKIND, int AK2 = -1, int BK2 = -1, bool DTL = false>
 int launch_mfma(const pq_gemm_plan& pl, int M, int N, int K, const pq_operand& A, const pq_operand& B,
                 const pq_epilogue& epi, hipStream_t s, float* part, const pq_gemm_group& grp, const pq_phase2& ph2) {
@@ -1417,6 +1629,19 @@ int launch_mfma_cfg(const pq_gemm_plan& pl, int M, int N, int K, const pq_operan
       const bool b_ok = b_bits ? (K % 128 == 0 && (pl.splits == 1 || pl.kchunk % 256 == 0) && B.ld % 16 == 0 && ((uintptr_t)B.p % 16) == 0) :
                         ((B.ld * 2) % 16 == 0 && ((uintptr_t)B.p % 16) == 0 && (BKIND != PQ_SRC_KS16 || N % 8 == 0));
       const bool stream = (grp.mode == 0 || grp.mode == 1) && K % EPB == 0 && pl.kchunk % EPB == 0 && a_ok && b_ok && M >= 1 && N >= 1;
+#ifndef PQ_NO_W4
+      // weight gradients: the four-wavefront kernel (whole 32-row stages in every split; no per-row divisor, no int32 output)
+      if constexpr (AK == PQ_SRC_KS16 && BKIND == PQ_SRC_KS16 && AK2 < 0) {
+        if (grp.mode == 0 && ph2.K2 == 0 && K % 32 == 0 && pl.kchunk % 32 == 0 && a_ok && b_ok && !A.kdiv && !B.kdiv && !epi.row_div &&
+            epi.out_kind != PQ_OUT_I32) {
+          const int nbm = (M + 255) / 256, nbn = (N + 255) / 256;
+          dim3 grid(nbm * nbn, pl.splits), block(256);
+          gemm_tn_w4_kernel<<<grid, block, 0, s>>>(M, N, K, A, B, epi, nbn, nbm * nbn, pl.kchunk, pl.splits > 1 ? part : nullptr);
+          PQ_CHECK_LAUNCH("gemm_tn_w4_kernel");
+          return PQ_OK;
+        }
+      }
+#endif
       if (stream) {
         if (whole) return launch_mfma<256, 256, 2, 4, 128, true, INT8, AK, BKIND, AK2, BK2, true>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
         return launch_mfma<256, 256, 2, 4, 128, false, INT8, AK, BKIND, AK2, BK2, true>(pl, M, N, K, A, B, epi, s, part, grp, ph2);
