@@ -385,6 +385,38 @@ def stack_bench(pq, torch, L=24, T=16384, D=2048, F=5504, E=8, r=32, steps=2, wa
             "mfma_frac_of_step": round(t_mfma / (ms * 1e-3), 4)}
 
 
+def vendor_gemm_context(torch, X, W, dY, steps=100, warmup=10):
+    """Context, not product: what the vendor GEMM library (through torch.matmul, bf16) needs on this machine for plain GEMMs
+    of the step's three shapes on the same operands, and for a large square GEMM on normal and on all-zero operands.
+    With real operand data the chip runs matrix work against its power limit (the shader clock falls with the toggling
+    of the data), so the nominal 2.5 PFLOP/s is not what any kernel is measured against in practice."""
+    T, K = X.shape
+    N = W.shape[0]
+    def t(f, n=steps):
+        for _ in range(warmup):
+            f()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n
+    out = {}
+    for name, f in (("fwd_X_Wt", lambda: torch.matmul(X, W.t())), ("dX_dY_W", lambda: torch.matmul(dY, W)),
+                    ("dW_dYt_X", lambda: torch.matmul(dY.t(), X))):
+        us = t(f)
+        out[name] = {"us": round(us, 1), "TFLOP/s": round(2.0 * T * K * N / us / 1e6, 0)}
+    n = 8192
+    for data in ("normal", "zero"):
+        a = torch.randn((n, n), device="cuda").to(torch.bfloat16) if data == "normal" else torch.zeros((n, n), dtype=torch.bfloat16, device="cuda")
+        b = a.clone()
+        us = t(lambda: torch.matmul(a, b.t()), 20)
+        out[f"square_8192_{data}"] = {"us": round(us, 1), "TFLOP/s": round(2.0 * n ** 3 / us / 1e6, 0)}
+        del a, b
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -401,6 +433,7 @@ def main():
     ap.add_argument("--no-stack", action="store_true")
     ap.add_argument("--no-norm", action="store_true")
     ap.add_argument("--no-hp8", action="store_true")
+    ap.add_argument("--no-vendor-context", action="store_true", help="skip the vendor-library GEMM timings (context only)")
     ap.add_argument("--no-paper-ffn", action="store_true", help="skip the paper-exact 1.3B FFN (Table 1) and its branch sweep")
     ap.add_argument("--no-decode-layer-sweep", action="store_true",
                     help="skip batch-1 decode at 128 and 256 weight sets per launch (shows the rate does not lean on the last-level cache)")
@@ -528,6 +561,8 @@ def main():
         out["calibration_copy"] = {"kernel": "gather_rows_kernel", "read_bytes": rows * cols * 2 + rows * 4,
                                    "write_bytes": rows * cols * 2}
         del src, dst, ids
+    if not args.no_vendor_context and not args.calibrate:
+        section("vendor_gemm_context", lambda: vendor_gemm_context(torch, X, W, dY))
     if not args.no_hp8:
         section("hp_int8_branch", lambda: hp_int8_bench(pq, torch))
     if not args.no_ffn:

@@ -29,11 +29,14 @@ struct ffn_layout {
   // ctx
   size_t ml_up, ml_gate, ml_down, P_up, Pt_up, P_gate, Pt_gate, P_down, Pt_down, Xq, gx, Xt, U, G, Hq, gh, Ht;
   size_t idx, gate, probs, counts, offsets, perm, inv, Xp, ue, ge, a, Ys;
+  // bf16 experts: Up and Gate of every expert as one [E][2 r][D] matrix (both projections are one product whose output
+  // [S][2 r] starts at ue: the left half of a row is u, the right half g)
+  size_t UG;
   // INT8 experts: codes, row scales and de-quantised bf16 copies of the expert weights; x's codes and gamma in slot
   // order; the hidden state's codes, scales and de-quantised copy (Xp then holds the rows of X~ instead of X)
   size_t UpQ, gUp, UpT, GateQ, gGate, GateT, DownQ, gDown, DownT, XqP, gxP, aQ, gA, aT, ctx_total;
   // workspace
-  size_t stat, red_a, red_b, splitk, dHd, dU, dG, dYp, rd, da, du, dg, as, dXs, dlogit, dwr, ws_total;
+  size_t stat, red_a, red_b, splitk, dHd, dU, dG, dYp, rd, da, du, dg, as, dXs, dlogit, dwr, dUG, ws_total;
   int n_red_a, n_red_b;
 };
 
@@ -53,7 +56,7 @@ ffn_layout make_layout(const pq_ffn_desc& d) {
   L.Hq = c.take(T * F); L.gh = c.take(T * 4); L.Ht = c.take(T * F * 2);
   L.idx = c.take(S * 4); L.gate = c.take(S * 4); L.probs = c.take(T * E * 4);
   L.counts = c.take(E * 4); L.offsets = c.take((E + 1) * 4); L.perm = c.take(S * 4); L.inv = c.take(S * 4);
-  L.Xp = c.take(S * D * 2); L.ue = c.take(S * r * 2); L.ge = c.take(S * r * 2); L.a = c.take(S * r * 2);
+  L.Xp = c.take(S * D * 2); L.ue = c.take(2 * S * r * 2); L.ge = L.ue + S * r * 2; L.a = c.take(S * r * 2);
   L.Ys = c.take(S * D * 2);
   if (d.hp_kind == PQ_HP_LOWRANK_INT8) {
     L.UpQ = c.take(E * r * D); L.gUp = c.take(E * r * 4); L.UpT = c.take(E * r * D * 2);
@@ -61,6 +64,8 @@ ffn_layout make_layout(const pq_ffn_desc& d) {
     L.DownQ = c.take(E * D * r); L.gDown = c.take(E * D * 4); L.DownT = c.take(E * D * r * 2);
     L.XqP = c.take(S * D); L.gxP = c.take(S * 4);
     L.aQ = c.take(S * r); L.gA = c.take(S * 4); L.aT = c.take(S * r * 2);
+  } else {
+    L.UG = c.take(E * 2 * r * D * 2);
   }
   L.ctx_total = c.off;
   cursor w;
@@ -82,12 +87,15 @@ ffn_layout make_layout(const pq_ffn_desc& d) {
   // the per-expert weight gradients cut their slot ranges into pieces (slabs of all experts' outputs)
   if (pq_mode2_ws_bytes((int)D, (int)r, (int)E, (int)S) > sk) sk = pq_mode2_ws_bytes((int)D, (int)r, (int)E, (int)S);
   if (pq_mode2_ws_bytes((int)r, (int)D, (int)E, (int)S) > sk) sk = pq_mode2_ws_bytes((int)r, (int)D, (int)E, (int)S);
+  if (pq_mode2_ws_bytes(2 * (int)r, (int)D, (int)E, (int)S) > sk) sk = pq_mode2_ws_bytes(2 * (int)r, (int)D, (int)E, (int)S);
+  if (8 * S * 2 * r * sizeof(float) > sk) sk = 8 * S * 2 * r * sizeof(float);
   L.splitk = w.take(sk);
   L.dHd = w.take(T * F * 2); L.dU = w.take(T * F * 2); L.dG = w.take(T * F * 2);
   L.dYp = w.take(S * D * 2); L.rd = w.take(S * 4);
-  L.da = w.take(S * r * 2); L.du = w.take(S * r * 2); L.dg = w.take(S * r * 2); L.as = w.take(S * r * 2);
+  L.da = w.take(S * r * 2); L.du = w.take(2 * S * r * 2); L.dg = L.du + S * r * 2; L.as = w.take(S * r * 2);
   L.dXs = w.take(S * D * 2); L.dlogit = w.take(T * E * 4);
   L.dwr = w.take(pq_dwr_scratch_bytes((int)T, (int)D, (int)E));
+  if (d.hp_kind != PQ_HP_LOWRANK_INT8) L.dUG = w.take(E * 2 * r * D * 4);
   L.ws_total = w.off;
   return L;
 }
@@ -224,7 +232,7 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
       e.C = cx + L.ge; e.col_div = (const float*)(cx + L.gGate);
       if (int err = pq_launch_gemm(0, S, r, D, A, Bg, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
     }
-    if (int e = pq_launch_expert_act(cx + L.ue, cx + L.ge, (size_t)S * r, cx + L.a, s)) return e;
+    if (int e = pq_launch_expert_act(cx + L.ue, cx + L.ge, r, S, r, cx + L.a, s)) return e;
     if (int e = pq_launch_quant_act(cx + L.a, PQ_BF16, S, r, (int8_t*)(cx + L.aQ), (float*)(cx + L.gA), (uint16_t*)(cx + L.aT), s)) return e;
     {
       pq_operand A{cx + L.aQ, r, PQ_SRC_KC8, nullptr};
@@ -237,18 +245,17 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
     return pq_launch_combine_fwd(Y, cx + L.Ys, inv, gate, d->alpha, T, k, D, s);
   }
   if (int e = pq_launch_gather_rows(X, perm, k, S, D, cx + L.Xp, s)) return e;
+  // [u | g] = Xp [Up_e; Gate_e]^T: both projections as one product with 2 r outputs per slot
+  if (int e = pq_launch_concat_expert_rows(Up, Gate, E, r, D, cx + L.UG, s)) return e;
   {
     pq_operand A{cx + L.Xp, D, PQ_SRC_KC16, nullptr};
-    pq_operand B{Up, D, PQ_SRC_KC16, nullptr};
+    pq_operand B{cx + L.UG, D, PQ_SRC_KC16, nullptr};
     pq_epilogue e = epi0();
-    e.C = cx + L.ue; e.ldc = r; e.out_kind = PQ_OUT_BF16;
-    g1.b_stride = (long)r * D;
-    if (int err = pq_launch_gemm(0, S, r, D, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
-    pq_operand Bg{Gate, D, PQ_SRC_KC16, nullptr};
-    e.C = cx + L.ge;
-    if (int err = pq_launch_gemm(0, S, r, D, A, Bg, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+    e.C = cx + L.ue; e.ldc = 2 * r; e.out_kind = PQ_OUT_BF16;
+    g1.b_stride = (long)2 * r * D;
+    if (int err = pq_launch_gemm(0, S, 2 * r, D, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
   }
-  if (int e = pq_launch_expert_act(cx + L.ue, cx + L.ge, (size_t)S * r, cx + L.a, s)) return e;
+  if (int e = pq_launch_expert_act(cx + L.ue, cx + L.ue + (size_t)r * 2, 2 * r, S, r, cx + L.a, s)) return e;
   {
     pq_operand A{cx + L.a, r, PQ_SRC_KC16, nullptr};
     pq_operand B{Down, r, PQ_SRC_KC16, nullptr};
@@ -353,8 +360,15 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
     g1.b_stride = (long)D * r;
     if (int err = pq_launch_gemm(0, S, r, D, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
   }
-  if (int e = pq_launch_expert_act_bwd(ws + L.da, cx + L.ue, cx + L.ge, a_fwd, perm, gate, d->alpha, S, r, ws + L.du, ws + L.dg,
-                                       ws + L.as, s)) return e;
+  const bool hp8 = d->hp_kind == PQ_HP_LOWRANK_INT8;
+  // bf16 experts: u | g and du | dg lie side by side in [S][2 r] matrices (Up and Gate are one weight matrix per expert)
+  if (hp8) {
+    if (int e = pq_launch_expert_act_bwd(ws + L.da, cx + L.ue, cx + L.ge, a_fwd, perm, gate, d->alpha, S, r, r, ws + L.du, ws + L.dg,
+                                         ws + L.as, s)) return e;
+  } else {
+    if (int e = pq_launch_expert_act_bwd(ws + L.da, cx + L.ue, cx + L.ue + (size_t)r * 2, a_fwd, perm, gate, d->alpha, S, r, 2 * r,
+                                         ws + L.du, ws + L.du + (size_t)r * 2, ws + L.as, s)) return e;
+  }
   {  // per-expert weight gradients: contraction over the expert's slots
     pq_operand A{ws + L.dYp, D, PQ_SRC_KS16, nullptr};
     pq_operand B{ws + L.as, r, PQ_SRC_KS16, nullptr};
@@ -363,15 +377,23 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
     g2.c_stride = (long)D * r;
     if (int err = pq_launch_gemm(0, D, r, S, A, B, e, s, PQP_GEMM_EXPERT, sk, &g2)) return err;
     pq_operand Bx{cx + L.Xp, D, PQ_SRC_KS16, nullptr};
-    pq_operand Au{ws + L.du, r, PQ_SRC_KS16, nullptr};
-    e.C = dUp; e.ldc = D;
-    g2.c_stride = (long)r * D;
-    if (int err = pq_launch_gemm(0, r, D, S, Au, Bx, e, s, PQP_GEMM_EXPERT, sk, &g2)) return err;
-    pq_operand Ag{ws + L.dg, r, PQ_SRC_KS16, nullptr};
-    e.C = dGate;
-    if (int err = pq_launch_gemm(0, r, D, S, Ag, Bx, e, s, PQP_GEMM_EXPERT, sk, &g2)) return err;
+    if (hp8) {
+      pq_operand Au{ws + L.du, r, PQ_SRC_KS16, nullptr};
+      e.C = dUp; e.ldc = D;
+      g2.c_stride = (long)r * D;
+      if (int err = pq_launch_gemm(0, r, D, S, Au, Bx, e, s, PQP_GEMM_EXPERT, sk, &g2)) return err;
+      pq_operand Ag{ws + L.dg, r, PQ_SRC_KS16, nullptr};
+      e.C = dGate;
+      if (int err = pq_launch_gemm(0, r, D, S, Ag, Bx, e, s, PQP_GEMM_EXPERT, sk, &g2)) return err;
+    } else {   // d[Up_e; Gate_e] = [du | dg]^T Xp, then split into the caller's two gradients
+      pq_operand Aug{ws + L.du, 2 * r, PQ_SRC_KS16, nullptr};
+      e.C = ws + L.dUG; e.ldc = D;
+      g2.c_stride = (long)2 * r * D;
+      if (int err = pq_launch_gemm(0, 2 * r, D, S, Aug, Bx, e, s, PQP_GEMM_EXPERT, sk, &g2)) return err;
+      if (int err = pq_launch_split_expert_rows((const float*)(ws + L.dUG), E, r, D, dUp, dGate, s)) return err;
+    }
   }
-  if (S > 0) {  // dXs = du Up_e + dg Gate_e  (slot order)
+  if (S > 0 && hp8) {  // dXs = du Up_e + dg Gate_e  (slot order)
     pq_operand A{ws + L.du, r, PQ_SRC_KC16, nullptr};
     pq_operand B{Up, D, PQ_SRC_KS16, nullptr};
     pq_epilogue e = epi0();
@@ -382,6 +404,13 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
     pq_operand B2{Gate, D, PQ_SRC_KS16, nullptr};
     e.accumulate = 1;
     if (int err = pq_launch_gemm(0, S, D, r, A2, B2, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+  } else if (S > 0) {  // dXs = [du | dg] [Up_e; Gate_e]
+    pq_operand A{ws + L.du, 2 * r, PQ_SRC_KC16, nullptr};
+    pq_operand B{cx + L.UG, D, PQ_SRC_KS16, nullptr};
+    pq_epilogue e = epi0();
+    e.C = ws + L.dXs; e.ldc = D; e.out_kind = PQ_OUT_BF16;
+    g1.b_stride = (long)2 * r * D;
+    if (int err = pq_launch_gemm(0, S, D, 2 * r, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
   }
   float* dlogit = (float*)(ws + L.dlogit);
   if (int e = pq_launch_router_bwd(rd, inv, idx, (const float*)(cx + L.probs), d->alpha, T, k, E, dlogit, s)) return e;

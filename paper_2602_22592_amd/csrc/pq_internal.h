@@ -196,9 +196,13 @@ int pq_launch_gather_f32(const float* src, const int* perm, int k, int S, float*
 // rows of F elements of which the first Fv exist (padded widths): the rest is written as zero
 int pq_launch_swiglu_quant(const void* U, const void* G, int T, int F, int Fv, int8_t* Hq, float* gamma, void* Ht, hipStream_t s);
 int pq_launch_swiglu_bwd(const void* dHd, const void* U, const void* G, int T, int F, int Fv, void* dU, void* dG, hipStream_t s);
-int pq_launch_expert_act(const void* ue, const void* ge, size_t n, void* a, hipStream_t s);
+// ue, ge (and du, dg) have a row stride of ld elements: r, or 2 r when both lie side by side in one [S][2 r] matrix
+int pq_launch_expert_act(const void* ue, const void* ge, int ld, int S, int r, void* a, hipStream_t s);
 int pq_launch_expert_act_bwd(const void* da, const void* ue, const void* ge, const void* a, const int* perm, const float* gate,
-                             float alpha, int S, int r, void* du, void* dg, void* as, hipStream_t s);
+                             float alpha, int S, int r, int ld, void* du, void* dg, void* as, hipStream_t s);
+// UG[e] = [Up[e]; Gate[e]] (bf16 [E][2 r][d]) and the split of its fp32 gradient back into dUp, dGate
+int pq_launch_concat_expert_rows(const void* up, const void* gate_w, int E, int r, int d, void* ug, hipStream_t s);
+int pq_launch_split_expert_rows(const float* dug, int E, int r, int d, float* dup, float* dgate, hipStream_t s);
 int pq_launch_scale_rows(void* A, const int* perm, const float* gate, float alpha, int S, int d, hipStream_t s);
 int pq_rowdot_blocks(int S);
 int pq_launch_rowdot(const void* A, const void* B, const int* perm, const float* gate, int S, int d, float* rd, double* partial,

@@ -25,16 +25,18 @@ __device__ __forceinline__ float dsiluf_(float x) {
 }
 
 // Stable counting sort of the slots (slot = token * k + j) by expert: perm[pos] = slot, inv[slot] = pos,
-// offsets[e] = first position of expert e.  One workgroup of 16 wavefronts.  The expert ids (< 64) are first
-// copied into LDS as bytes (LDS_IDS; otherwise every scan re-reads them from global memory); a wavefront owns
-// the experts e = w, w + 16, ...: it counts them, the counts are scanned, then it assigns positions in slot
-// order (rank inside a batch of 64 slots by ballot prefix).
+// offsets[e] = first position of expert e.  One workgroup of 16 wavefronts, each owning a contiguous range of whole
+// 64-slot batches.  The expert ids (< 64) are first copied into LDS as bytes (LDS_IDS; otherwise both passes read them
+// from global memory).  Pass 1: lane e of a wavefront counts expert e in the wavefront's range (one ballot per batch and
+// expert).  The counts are scanned over (expert, wavefront), which gives every wavefront the first position of each
+// expert's slots inside its range.  Pass 2: the same walk assigns positions in slot order (rank inside a batch by
+// ballot prefix), lane e carrying expert e's running position.
 template <bool LDS_IDS>
 __global__ __launch_bounds__(1024) void route_kernel(const int* __restrict__ idx, int S, int E, int* __restrict__ counts,
                                                      int* __restrict__ offsets, int* __restrict__ perm,
                                                      int* __restrict__ inv) {
   extern __shared__ unsigned char s_ids[];
-  __shared__ int s_cnt[64], s_off[65];
+  __shared__ int s_cnt[16][64], s_off[65];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   if constexpr (LDS_IDS) {
     for (int s = threadIdx.x; s < S; s += 1024) s_ids[s] = (unsigned char)idx[s];
@@ -45,36 +47,49 @@ __global__ __launch_bounds__(1024) void route_kernel(const int* __restrict__ idx
     if constexpr (LDS_IDS) return s_ids[s];
     else return idx[s];
   };
-  for (int e = wave; e < E; e += 16) {
-    int cnt = 0;
-    for (int s0 = 0; s0 < S; s0 += 64) cnt += __builtin_popcountll(__ballot(id_at(s0 + lane) == e));
-    if (lane == 0) s_cnt[e] = cnt;
+  const int nb = (S + 63) / 64, per = (nb + 15) / 16;
+  const int b0 = min(nb, wave * per), b1 = min(nb, b0 + per);
+  int cnt = 0;                                      // lane e: slots of expert e in this wavefront's range
+  for (int b = b0; b < b1; ++b) {
+    const int id = id_at(b * 64 + lane);
+    for (int e = 0; e < E; ++e) {
+      const int c = __builtin_popcountll(__ballot(id == e));
+      if (lane == e) cnt += c;
+    }
   }
+  s_cnt[wave][lane] = cnt;
   __syncthreads();
   if (threadIdx.x == 0) {
     int run = 0;
     for (int e = 0; e < E; ++e) {
+      int tot = 0;
+      for (int w = 0; w < 16; ++w) tot += s_cnt[w][e];
       s_off[e] = run;
       offsets[e] = run;
-      counts[e] = s_cnt[e];
-      run += s_cnt[e];
+      counts[e] = tot;
+      run += tot;
     }
     s_off[E] = run;
     offsets[E] = run;
   }
   __syncthreads();
-  for (int e = wave; e < E; e += 16) {
-    int running = s_off[e];
-    for (int s0 = 0; s0 < S; s0 += 64) {
-      const int s = s0 + lane;
-      const bool match = id_at(s) == e;
-      const unsigned long long m = __ballot(match);
-      if (match) {
-        const int pos = running + __builtin_popcountll(m & ((1ull << lane) - 1ull));
+  int running = 0;                                  // lane e: next position of expert e for this wavefront
+  if (lane < E) {
+    running = s_off[lane];
+    for (int w = 0; w < wave; ++w) running += s_cnt[w][lane];
+  }
+  for (int b = b0; b < b1; ++b) {
+    const int s = b * 64 + lane;
+    const int id = id_at(s);
+    for (int e = 0; e < E; ++e) {
+      const unsigned long long m = __ballot(id == e);
+      const int base = __shfl(running, e);
+      if (id == e) {
+        const int pos = base + __builtin_popcountll(m & ((1ull << lane) - 1ull));
         perm[pos] = s;
         inv[s] = pos;
       }
-      running += __builtin_popcountll(m);
+      if (lane == e) running += __builtin_popcountll(m);
     }
   }
 }
@@ -210,14 +225,16 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const uint16_t* __restr
 }
 
 // ---- expert activation ----------------------------------------------------------------------
-// a = silu(ge) * ue  over S*r elements (slot order)
+// a = silu(ge) * ue  over S rows of r elements (slot order); ue and ge have a row stride of ld elements (r, or 2 r when
+// both lie side by side in one [S][2 r] product)
 __global__ __launch_bounds__(256) void expert_act_kernel(const uint16_t* __restrict__ ue, const uint16_t* __restrict__ ge,
-                                                         size_t nvec, uint16_t* __restrict__ a) {
+                                                         int ld, int r, size_t nvec, uint16_t* __restrict__ a) {
   const size_t c = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (c >= nvec) return;
+  const size_t pos = c / (size_t)(r / 8), in = pos * ld + (c - pos * (size_t)(r / 8)) * 8;
   float uf[8], gf[8], o[8];
-  unpack8(reinterpret_cast<const uint4*>(ue)[c], uf);
-  unpack8(reinterpret_cast<const uint4*>(ge)[c], gf);
+  unpack8(*reinterpret_cast<const uint4*>(ue + in), uf);
+  unpack8(*reinterpret_cast<const uint4*>(ge + in), gf);
 #pragma unroll
   for (int j = 0; j < 8; ++j) o[j] = siluf_(gf[j]) * uf[j];
   reinterpret_cast<uint4*>(a)[c] = pack8(o);
@@ -227,16 +244,17 @@ __global__ __launch_bounds__(256) void expert_act_kernel(const uint16_t* __restr
 __global__ __launch_bounds__(256) void expert_act_bwd_kernel(const uint16_t* __restrict__ da, const uint16_t* __restrict__ ue,
                                                              const uint16_t* __restrict__ ge, const uint16_t* __restrict__ a,
                                                              const int* __restrict__ perm, const float* __restrict__ gate,
-                                                             float alpha, int r, size_t nvec, uint16_t* __restrict__ du,
+                                                             float alpha, int r, int ld, size_t nvec, uint16_t* __restrict__ du,
                                                              uint16_t* __restrict__ dg, uint16_t* __restrict__ as) {
   const size_t c = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (c >= nvec) return;
   const int pos = (int)(c / (size_t)(r / 8));
+  const size_t in = (size_t)pos * ld + (c - (size_t)pos * (r / 8)) * 8;   // ue, ge, du, dg: row stride ld (r or 2 r)
   const float sc = alpha * gate[perm[pos]];
   float d[8], uf[8], gf[8], af[8], o1[8], o2[8], o3[8];
   unpack8(reinterpret_cast<const uint4*>(da)[c], d);
-  unpack8(reinterpret_cast<const uint4*>(ue)[c], uf);
-  unpack8(reinterpret_cast<const uint4*>(ge)[c], gf);
+  unpack8(*reinterpret_cast<const uint4*>(ue + in), uf);
+  unpack8(*reinterpret_cast<const uint4*>(ge + in), gf);
   unpack8(reinterpret_cast<const uint4*>(a)[c], af);
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
@@ -245,9 +263,31 @@ __global__ __launch_bounds__(256) void expert_act_bwd_kernel(const uint16_t* __r
     o2[j] = dj * uf[j] * dsiluf_(gf[j]);
     o3[j] = sc * af[j];
   }
-  reinterpret_cast<uint4*>(du)[c] = pack8(o1);
-  reinterpret_cast<uint4*>(dg)[c] = pack8(o2);
+  *reinterpret_cast<uint4*>(du + in) = pack8(o1);
+  *reinterpret_cast<uint4*>(dg + in) = pack8(o2);
   reinterpret_cast<uint4*>(as)[c] = pack8(o3);
+}
+
+// Up and Gate of every expert as one matrix: UG[e][j][:] = Up[e][j][:] for j < r, Gate[e][j - r][:] for r <= j < 2 r
+// (bf16 rows of d elements, d % 8 == 0), so that both projections are one product with 2 r outputs
+__global__ __launch_bounds__(256) void concat_expert_rows_kernel(const uint16_t* __restrict__ up, const uint16_t* __restrict__ gate_w,
+                                                                 int r, int d, size_t nvec, uint16_t* __restrict__ ug) {
+  const size_t c = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (c >= nvec) return;
+  const size_t row = c / (size_t)(d / 8), ch = c - row * (size_t)(d / 8);
+  const size_t e = row / (size_t)(2 * r), j = row - e * (size_t)(2 * r);
+  const uint16_t* src = j < (size_t)r ? up + (e * r + j) * (size_t)d : gate_w + (e * r + (j - r)) * (size_t)d;
+  reinterpret_cast<uint4*>(ug)[c] = reinterpret_cast<const uint4*>(src)[ch];
+}
+// and back for the gradients (fp32 rows of d elements, d % 4 == 0)
+__global__ __launch_bounds__(256) void split_expert_rows_kernel(const float* __restrict__ dug, int r, int d, size_t nvec,
+                                                                float* __restrict__ dup, float* __restrict__ dgate) {
+  const size_t c = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (c >= nvec) return;
+  const size_t row = c / (size_t)(d / 4), ch = c - row * (size_t)(d / 4);
+  const size_t e = row / (size_t)(2 * r), j = row - e * (size_t)(2 * r);
+  float* dst = j < (size_t)r ? dup + (e * r + j) * (size_t)d : dgate + (e * r + (j - r)) * (size_t)d;
+  reinterpret_cast<uint4*>(dst)[ch] = reinterpret_cast<const uint4*>(dug)[c];
 }
 
 // rd[pos] = <A[pos,:], B[pos,:]> (fp32), partial[block] = sum gate[perm[pos]] * rd[pos]  (for d alpha)
@@ -525,21 +565,40 @@ int pq_launch_swiglu_bwd(const void* dHd, const void* U, const void* G, int T, i
   return PQ_OK;
 }
 
-int pq_launch_expert_act(const void* ue, const void* ge, size_t n, void* a, hipStream_t s) {
+int pq_launch_expert_act(const void* ue, const void* ge, int ld, int S, int r, void* a, hipStream_t s) {
+  const size_t n = (size_t)S * r;
   if (n == 0) return PQ_OK;
   pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
-  expert_act_kernel<<<(unsigned)((n / 8 + 255) / 256), 256, 0, s>>>((const uint16_t*)ue, (const uint16_t*)ge, n / 8, (uint16_t*)a);
+  expert_act_kernel<<<(unsigned)((n / 8 + 255) / 256), 256, 0, s>>>((const uint16_t*)ue, (const uint16_t*)ge, ld, r, n / 8, (uint16_t*)a);
   PQ_CHECK_LAUNCH("expert_act_kernel");
   return PQ_OK;
 }
 
+int pq_launch_concat_expert_rows(const void* up, const void* gate_w, int E, int r, int d, void* ug, hipStream_t s) {
+  const size_t nvec = (size_t)E * 2 * r * (d / 8);
+  if (nvec == 0) return PQ_OK;
+  pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
+  concat_expert_rows_kernel<<<(unsigned)((nvec + 255) / 256), 256, 0, s>>>((const uint16_t*)up, (const uint16_t*)gate_w, r, d, nvec, (uint16_t*)ug);
+  PQ_CHECK_LAUNCH("concat_expert_rows_kernel");
+  return PQ_OK;
+}
+
+int pq_launch_split_expert_rows(const float* dug, int E, int r, int d, float* dup, float* dgate, hipStream_t s) {
+  const size_t nvec = (size_t)E * 2 * r * (d / 4);
+  if (nvec == 0) return PQ_OK;
+  pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
+  split_expert_rows_kernel<<<(unsigned)((nvec + 255) / 256), 256, 0, s>>>(dug, r, d, nvec, dup, dgate);
+  PQ_CHECK_LAUNCH("split_expert_rows_kernel");
+  return PQ_OK;
+}
+
 int pq_launch_expert_act_bwd(const void* da, const void* ue, const void* ge, const void* a, const int* perm, const float* gate,
-                             float alpha, int S, int r, void* du, void* dg, void* as, hipStream_t s) {
+                             float alpha, int S, int r, int ld, void* du, void* dg, void* as, hipStream_t s) {
   if (S == 0) return PQ_OK;
   pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
   const size_t nvec = (size_t)S * r / 8;
   expert_act_bwd_kernel<<<(unsigned)((nvec + 255) / 256), 256, 0, s>>>((const uint16_t*)da, (const uint16_t*)ue, (const uint16_t*)ge,
-                                                                      (const uint16_t*)a, perm, gate, alpha, r, nvec, (uint16_t*)du,
+                                                                      (const uint16_t*)a, perm, gate, alpha, r, ld, nvec, (uint16_t*)du,
                                                                       (uint16_t*)dg, (uint16_t*)as);
   PQ_CHECK_LAUNCH("expert_act_bwd_kernel");
   return PQ_OK;

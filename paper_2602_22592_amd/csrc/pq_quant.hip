@@ -675,47 +675,72 @@ int pq_launch_pack(const void* W, int dtype, int N, int K, const double* partial
 }
 
 // ------------------------------------------------------------------------------------------
-// Router: one wavefront per token, fp64 dot products against all E router rows, then lane 0
-// rounds the logits to fp32, selects the top-k (ties to the lower index) and evaluates the
-// softmax in fp64.
+// Router: a wavefront takes TB tokens at once (a router row converted to fp64 serves all of them): fp64 dot products
+// against all E router rows, lane l accumulating the 16-byte chunks l, l + 64, ... of a token row in order, then the
+// wave sums; lane tb (< TB) rounds token tb's logits to fp32, selects the top-k (ties to the lower index) and evaluates
+// the softmax in fp64.
 // ------------------------------------------------------------------------------------------
-template <typename T, int EMAX>
+template <typename T, int EMAX, int TB>
 __global__ __launch_bounds__(256) void router_kernel(const T* __restrict__ X, const T* __restrict__ Wr,
                                                      int Tn, int K, int E, int k, int* __restrict__ idx,
                                                      float* __restrict__ gate, float* __restrict__ probs) {
   constexpr int V = vec16<T>::V;
   const int lane = threadIdx.x & 63;
-  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (t >= Tn) return;
-  const uint4* xr = reinterpret_cast<const uint4*>(X + (size_t)t * K);
+  const int t0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * TB;
+  if (t0 >= Tn) return;
   const int nvec = K / V;
-  double acc[EMAX];
+  double acc[TB][EMAX];
 #pragma unroll
-  for (int e = 0; e < EMAX; ++e) acc[e] = 0.0;
+  for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e) acc[tb][e] = 0.0;
   // Router rows are requested unconditionally, eight at a time (rows past E repeat the last one and their sums
-  // are never used): a load under a branch gets a wait of its own, which made this loop a chain of latencies.
+  // are never used; tokens past the end repeat the last token): a load under a branch gets a wait of its own, which
+  // made this loop a chain of latencies.
   for (int c = lane; c < nvec; c += 64) {
-    float xf[V];
-    const uint4 xv = xr[c];
+    double xd[TB][V];
+    uint4 xv[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) xv[tb] = reinterpret_cast<const uint4*>(X + (size_t)min(t0 + tb, Tn - 1) * K)[c];
 #pragma unroll
     for (int e0 = 0; e0 < EMAX; e0 += 8) {
       uint4 wv[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) wv[u] = reinterpret_cast<const uint4*>(Wr + (size_t)min(e0 + u, E - 1) * K)[c];
-      if (e0 == 0) vec16<T>::unpack(xv, xf);
+      if (e0 == 0) {
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) {
+          float xf[V];
+          vec16<T>::unpack(xv[tb], xf);
+#pragma unroll
+          for (int j = 0; j < V; ++j) xd[tb][j] = (double)xf[j];
+        }
+      }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         float wf[V];
         vec16<T>::unpack(wv[u], wf);
 #pragma unroll
-        for (int j = 0; j < V; ++j) acc[e0 + u] += (double)xf[j] * (double)wf[j];
+        for (int j = 0; j < V; ++j) {
+          const double wd = (double)wf[j];
+#pragma unroll
+          for (int tb = 0; tb < TB; ++tb) acc[tb][e0 + u] += xd[tb][j] * wd;
+        }
       }
     }
   }
-  double logit[EMAX];
+  double logit[EMAX];                                 // lane tb: the logits of token t0 + tb
 #pragma unroll
-  for (int e = 0; e < EMAX; ++e) logit[e] = (double)(float)wave_sum_d(acc[e]);  // one rounding to fp32
-  if (lane != 0) return;
+  for (int e = 0; e < EMAX; ++e) logit[e] = 0.0;
+#pragma unroll
+  for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e) {
+      const double v = (double)(float)wave_sum_d(acc[tb][e]);  // one rounding to fp32
+      if (lane == tb) logit[e] = v;
+    }
+  const int t = t0 + lane;
+  if (lane >= TB || t >= Tn) return;
   double mx = -1e300;
 #pragma unroll
   for (int e = 0; e < EMAX; ++e)
@@ -751,10 +776,10 @@ __global__ __launch_bounds__(256) void router_kernel(const T* __restrict__ X, co
 template <typename T>
 static int launch_router_t(const T* X, const T* Wr, int Tn, int K, int E, int k, int* idx, float* gate,
                            float* probs, hipStream_t s) {
-  dim3 grid((Tn + 3) / 4), block(256);
-  if (E <= 8) router_kernel<T, 8><<<grid, block, 0, s>>>(X, Wr, Tn, K, E, k, idx, gate, probs);
-  else if (E <= 16) router_kernel<T, 16><<<grid, block, 0, s>>>(X, Wr, Tn, K, E, k, idx, gate, probs);
-  else router_kernel<T, 64><<<grid, block, 0, s>>>(X, Wr, Tn, K, E, k, idx, gate, probs);
+  dim3 block(256);
+  if (E <= 8) router_kernel<T, 8, 4><<<dim3((Tn + 15) / 16), block, 0, s>>>(X, Wr, Tn, K, E, k, idx, gate, probs);
+  else if (E <= 16) router_kernel<T, 16, 2><<<dim3((Tn + 7) / 8), block, 0, s>>>(X, Wr, Tn, K, E, k, idx, gate, probs);
+  else router_kernel<T, 64, 1><<<dim3((Tn + 3) / 4), block, 0, s>>>(X, Wr, Tn, K, E, k, idx, gate, probs);
   PQ_CHECK_LAUNCH("router_kernel");
   return PQ_OK;
 }

@@ -304,6 +304,7 @@ def test_linear_with_no_tokens(bf16):
 # ---------------------------------------------------------------------------- routed low-rank experts (Sec. 3.3)
 @pytest.mark.parametrize("T,K,N,r,E,k", [(200, 96, 160, 8, 4, 1), (200, 96, 160, 8, 4, 2), (700, 256, 544, 32, 8, 1),
                                          (130, 64, 64, 16, 2, 2), (1, 32, 32, 8, 8, 1), (1500, 1024, 288, 32, 8, 2),
+                                         (1100, 128, 96, 8, 40, 3), (3000, 64, 64, 8, 16, 1),   # many experts; slot ranges of several batches per wavefront
                                          (128, 4096, 11008, 64, 8, 2)])   # the decode layer's shape (config 4) in training
 def test_linear_routed_experts(T, K, N, r, E, k):
     """E > 1 inside pq_linear_fwd / pq_linear_bwd: router, stable permutation, grouped expert GEMMs, gate-weighted
