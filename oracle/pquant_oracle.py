@@ -22,6 +22,9 @@ Readings taken where the paper is silent or garbled (each also listed in the des
   * router: logits on raw X, top-k on logits (ties -> lower index), gates = softmax over all experts,
     not renormalised.
   * STE: identity through Sign and Q; mu, lambda, gamma carry no gradient.
+  * group-wise weight scales (Sec. 4.6 ablation, contrast only): groups of 64 consecutive input columns of an output row,
+    one scale per group = mean |W| of the group, held in 16 bits (fp16, rounded from its fp32 value); mu and the signs are
+    those of the per-tensor form.
   * the normalisation in front of the quantiser is RMSNorm with a per-channel gain g and an eps inside the
     square root (App. B names RMSNorm, Sec. 3.1 prints LayerNorm; neither gives gain or eps).
 """
@@ -603,3 +606,39 @@ def decode_ffn(x, P_up, P_gate, P_down, lam_up, lam_gate, lam_down, Up, Gate, Do
 def bits_per_weight(frac_1bit, frac_8bit):
     """Average bit-width of a decoupled layer (Table 1 percentages -> the 'Bit' column of Table 2)."""
     return frac_1bit * 1.0 + frac_8bit * 8.0
+
+
+# ----------------------------------------------------------------------------------------------
+# Sec. 4.6 ablation (contrast only): group-wise scales of the 1-bit weights
+# ----------------------------------------------------------------------------------------------
+def groupwise_scales(W, group=64):
+    """lambda[i, g] = mean_{j in group g} |W[i, j]| for groups of `group` consecutive input columns, as the 16-bit value the
+    ablation stores per group: the exact mean rounded to fp32, then to fp16 (returned as fp32)."""
+    W64 = np.abs(np.asarray(W, dtype=F64))
+    m, n = W64.shape
+    assert n % group == 0
+    lam = W64.reshape(m, n // group, group).sum(axis=2) / F64(group)
+    return lam.astype(F32).astype(np.float16).astype(F32)
+
+
+def groupwise_fwd(X, W, beta, group=64):
+    """1-bit linear with one scale per `group` weights instead of one per tensor (the group-wise variant the paper
+    evaluates and rejects in Sec. 4.6): Y[t, i] = beta / gamma_t * sum_g lambda[i, g] * sum_{j in g} S[i, j] q[t, j],
+    with mu, S = Sign(W - mu) and the activation quantiser of Sec. 3.1.  group = 0 gives the per-tensor form."""
+    mu, lam = weight_stats(W)
+    S = binarise(W, mu).astype(np.int64)
+    q, gamma = quant_act(X)
+    q64 = q.astype(np.int64)
+    T, n = q64.shape
+    m = S.shape[0]
+    if group == 0:
+        Y = F64(beta) * F64(lam) * (q64 @ S.T).astype(F64) / gamma.astype(F64)[:, None]
+        return dict(Y=Y, q=q, gamma=gamma, mu=mu, lam=lam)
+    lg = groupwise_scales(W, group).astype(F64)          # [m, n/group]
+    G = n // group
+    Y = np.zeros((T, m), F64)
+    for g in range(G):
+        part = q64[:, g * group:(g + 1) * group] @ S[:, g * group:(g + 1) * group].T   # exact integers
+        Y += part.astype(F64) * lg[None, :, g]
+    Y = F64(beta) * Y / gamma.astype(F64)[:, None]
+    return dict(Y=Y, q=q, gamma=gamma, mu=mu, lam_group=lg.astype(F32))

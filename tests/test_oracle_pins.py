@@ -916,3 +916,80 @@ def test_decode_ffn_agrees_with_the_training_forward_and_with_chained_decode_pro
         float(dec["gate"][t, jj]) * (y if jj == j else float((np.asarray(Down[int(dec["idx"][t, jj])], np.float64) @ dec["act"][t, jj])[i]))
         for jj in range(2))
     assert abs(want - dec["Y"][t, i]) <= 1e-9 * max(1.0, abs(want))
+
+
+# ---------------------------------------------------------------------------- group-wise scales (Sec. 4.6 ablation)
+def test_groupwise_scales_hand_case_and_sixteen_bit_rounding():
+    """One row, two groups of four: means 2.5 and 0.1 (the latter is not an fp16 number: 0.0999755859375 is)."""
+    W = np.array([[1.0, -2.0, 3.0, -4.0, 0.1, -0.1, 0.1, -0.1]], np.float64)
+    lg = po.groupwise_scales(W, group=4)
+    assert lg.shape == (1, 2) and lg.dtype == np.float32
+    assert lg[0, 0] == np.float32(2.5)
+    assert lg[0, 1] == np.float32(0.0999755859375)
+
+
+def test_groupwise_forward_bruteforce():
+    """Python-loop evaluation of the defining double sum on a tiny case (no matmul, no reshape)."""
+    rng = np.random.default_rng(2301)
+    T, n, m, group = 3, 8, 2, 4
+    X = rng.standard_normal((T, n)).astype(np.float32)
+    W = (0.05 * rng.standard_normal((m, n))).astype(np.float32)
+    out = po.groupwise_fwd(X, W, beta=1.5, group=group)
+    mu = np.float32(np.float64(W.astype(np.float64).sum()) / W.size)
+    for t in range(T):
+        amax = max(abs(float(v)) for v in X[t])
+        gamma = np.float32(128.0) / np.float32(amax)
+        q = [int(np.clip(np.rint(np.float32(X[t, j]) * gamma), -128, 127)) for j in range(n)]
+        for i in range(m):
+            y = 0.0
+            for g in range(n // group):
+                cols = range(g * group, (g + 1) * group)
+                lam = float(np.float16(np.float32(sum(abs(float(W[i, j])) for j in cols) / group)))
+                y += lam * sum((1 if W[i, j] >= mu else -1) * q[j] for j in cols)
+            assert out["Y"][t, i] == pytest.approx(1.5 * y / float(gamma), rel=1e-12, abs=1e-300)
+
+
+def test_groupwise_reduces_to_per_tensor_when_all_magnitudes_agree():
+    """|W| constant (an fp16 number): every group scale equals lambda, so the group-wise product is the per-tensor one."""
+    rng = np.random.default_rng(2302)
+    T, n, m = 5, 128, 7
+    c = np.float32(0.03125)
+    W = (c * rng.choice([-1.0, 1.0], size=(m, n))).astype(np.float32)
+    X = rng.standard_normal((T, n)).astype(np.float32)
+    a = po.groupwise_fwd(X, W, beta=0.7, group=64)
+    b = po.groupwise_fwd(X, W, beta=0.7, group=0)
+    assert np.all(a["lam_group"] == c) and b["lam"] == c
+    np.testing.assert_allclose(a["Y"], b["Y"], rtol=1e-13, atol=0)
+    # and the per-tensor form is the 1-bit linear of the layer forward (alpha = 0, no branch), whose scale products are
+    # rounded to fp32 once each
+    ref = po.linear_fwd(X, W, alpha=0.0, beta=0.7)
+    np.testing.assert_allclose(b["Y"], ref["Y"], rtol=1e-6, atol=1e-300)
+
+
+def test_groupwise_one_group_per_row_is_the_channel_wise_closed_form():
+    rng = np.random.default_rng(2303)
+    T, n, m = 4, 64, 6
+    W = (0.02 * rng.standard_normal((m, n))).astype(np.float32)
+    X = rng.standard_normal((T, n)).astype(np.float32)
+    out = po.groupwise_fwd(X, W, beta=1.0, group=n)
+    mu, _ = po.weight_stats(W)
+    S = po.binarise(W, mu).astype(np.float64)
+    q, gamma = po.quant_act(X)
+    lam_row = np.abs(W.astype(np.float64)).mean(axis=1).astype(np.float32).astype(np.float16).astype(np.float64)
+    ref = (q.astype(np.float64) @ S.T) * lam_row[None, :] / gamma.astype(np.float64)[:, None]
+    np.testing.assert_allclose(out["Y"], ref, rtol=1e-13, atol=0)
+
+
+def test_groupwise_tracks_the_weights_better_than_one_scale():
+    """What the ablation is about: with per-group scales lambda_g Sign(W - mu) is closer to W than with one lambda
+    whenever the magnitude varies along a row (here: by a factor of four between the halves of every row)."""
+    rng = np.random.default_rng(2304)
+    m, n = 16, 256
+    W = (0.02 * rng.standard_normal((m, n))).astype(np.float32)
+    W[:, n // 2:] *= 4.0
+    mu, lam = po.weight_stats(W)
+    S = po.binarise(W, mu).astype(np.float64)
+    lg = np.repeat(po.groupwise_scales(W, 64).astype(np.float64), 64, axis=1)
+    err_group = np.linalg.norm(lg * S - W)
+    err_tensor = np.linalg.norm(float(lam) * S - W)
+    assert err_group < 0.9 * err_tensor
