@@ -417,6 +417,23 @@ def vendor_gemm_context(torch, X, W, dY, steps=100, warmup=10):
     return out
 
 
+def groupwise_contrast(pq, torch, X, W, steps=50, warmup=10):
+    """Sec. 4.6's group-wise(64) weight scales against the per-tensor scale, both in the contrast kernel (forward only:
+    quantiser, statistics, packing, group scales, GEMM), plus the GEMM launch alone from the library's events."""
+    out = {"workload": f"tokens={X.shape[0]}, d_in={X.shape[1]}, d_out={W.shape[0]}, bf16 in, fp32 out, forward only"}
+    for group, key in ((64, "group64"), (0, "per_tensor_same_kernel")):
+        Y = pq.groupwise_fwd(X, W, 1.0, group=group)
+        fn = lambda: pq.groupwise_fwd(X, W, 1.0, group=group, Y=Y)
+        ms = _time_steps(torch, fn, steps, warmup)
+        prof = _profile_steps(pq, torch, fn, steps)
+        gemm = prof.get("gemm_onebit_fwd")
+        out[key] = {"call_us": round(1e3 * ms, 1), "gemm_us": round(1e3 * gemm[0] / gemm[1], 1) if gemm else None}
+    g, p = out["group64"]["gemm_us"], out["per_tensor_same_kernel"]["gemm_us"]
+    out["gemm_ratio_group_over_per_tensor"] = round(g / p, 2) if g and p else None
+    out["scale_bytes_per_weight_bit"] = {"group64": 16 / 64, "per_tensor": 0.0}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -433,6 +450,7 @@ def main():
     ap.add_argument("--no-stack", action="store_true")
     ap.add_argument("--no-norm", action="store_true")
     ap.add_argument("--no-hp8", action="store_true")
+    ap.add_argument("--no-groupwise", action="store_true", help="skip the group-wise(64) scale contrast (Sec. 4.6)")
     ap.add_argument("--no-vendor-context", action="store_true", help="skip the vendor-library GEMM timings (context only)")
     ap.add_argument("--no-paper-ffn", action="store_true", help="skip the paper-exact 1.3B FFN (Table 1) and its branch sweep")
     ap.add_argument("--no-decode-layer-sweep", action="store_true",
@@ -563,6 +581,8 @@ def main():
         del src, dst, ids
     if not args.no_vendor_context and not args.calibrate:
         section("vendor_gemm_context", lambda: vendor_gemm_context(torch, X, W, dY))
+    if not args.calibrate and not args.no_groupwise:
+        section("groupwise_contrast", lambda: groupwise_contrast(pq, torch, X, W))
     if not args.no_hp8:
         section("hp_int8_branch", lambda: hp_int8_bench(pq, torch))
     if not args.no_ffn:

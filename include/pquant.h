@@ -212,6 +212,22 @@ int pq_hp_int8_bwd(const void* dY, const void* Xt, int32_t dtype, int32_t T, int
                    float alpha, const void* ctx, size_t ctx_bytes, void* dX, int32_t accumulate_dX, float* dA, float* dB,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* Group-wise scales of the 1-bit weights, the variant Sec. 4.6 evaluates against the per-tensor scale and rejects
+ * (one 16-bit scale per 64 one-bit weights: metadata overhead, unfriendly to hardware).  Built as a measured contrast,
+ * forward only:
+ *     group = 64:  Y[t][n] = beta / gamma_t * sum_g lambda[n][g] * sum_{k in group g} S[n][k] q[t][k],
+ *                  lambda[n][g] = mean |W[n][64 g .. 64 g + 63]| rounded to fp32 and then to fp16;
+ *     group = 0:   the per-tensor product of Sec. 3.1, Y[t][n] = beta * lambda / gamma_t * sum_k S[n][k] q[t][k], in the
+ *                  same kernel (int32 accumulation over the whole contraction), so that the two timings differ by the
+ *                  group scales alone.
+ * mu, S = Sign(W - mu), q and gamma are those of pq_linear_fwd (Sec. 3.1).
+ *   X [T][K], W [N][K] bf16 (dtype must be PQ_BF16);  Y [T][N] fp32, overwritten;  K % 64 == 0, N % 32 == 0.
+ *   workspace: device memory of pq_groupwise_workspace_bytes(T, K, N) bytes (codes, scales, packed signs, group scales);
+ *   the caller keeps ownership of every buffer.  Errors as everywhere: a negative pq_status, message via pq_last_error. */
+size_t pq_groupwise_workspace_bytes(int32_t T, int32_t K, int32_t N);
+int pq_groupwise_fwd(const void* X, const void* W, int32_t dtype, int32_t T, int32_t K, int32_t N, int32_t group, float beta,
+                     float* Y, void* workspace, size_t workspace_bytes, void* stream);
+
 /* The decoupled FFN (Sec. 3.2 FFN equation; Sec. 3.3):
  *     Y = beta * FFN_1bit(X) + alpha * sum_j gate_j(X) * FFN_e_j(X)
  * FFN_1bit: U = L_up(Q(X)), G = L_gate(Q(X)) (pure 1-bit linears, Sec. 3.1), Hd = silu(G) * U,

@@ -30,6 +30,7 @@ EXPORTS = [
     "pq_linear_norm_ctx_bytes", "pq_linear_norm_workspace_bytes", "pq_linear_norm_fwd", "pq_linear_norm_bwd",
     "pq_hp_int8_ctx_bytes", "pq_hp_int8_workspace_bytes", "pq_hp_int8_fwd", "pq_hp_int8_bwd", "pq_decode_gemv_int8",
     "pq_decode_ffn_workspace_bytes", "pq_decode_ffn", "pq_rmsnorm_bwd_static_max_bytes", "pq_rmsnorm_bwd_static",
+    "pq_groupwise_workspace_bytes", "pq_groupwise_fwd",
 ]
 
 
@@ -296,6 +297,23 @@ def hp_int8_bwd(dY, Xt, alpha, bufs, dX, dA, dB, accumulate_dX=False):
     _check(lib().pq_hp_int8_bwd(_p(dY), _p(Xt), _dt(dY), T, K, N, r, C.c_float(alpha), _p(bufs.ctx),
                                 C.c_size_t(bufs.ctx.numel()), _p(dX), int(accumulate_dX), _p(dA), _p(dB), _p(bufs.ws),
                                 C.c_size_t(bufs.ws.numel()), _stream()))
+
+
+def groupwise_fwd(X, W, beta, group=64, Y=None, ws=None):
+    """Sec. 4.6 contrast: the 1-bit forward with one fp16 scale per 64 weights (group=64) or the per-tensor scale in the
+    same kernel (group=0).  X [T][K], W [N][K] bf16 on the device; returns Y [T][N] fp32."""
+    import torch
+    T, K = X.shape
+    N = W.shape[0]
+    lib().pq_groupwise_workspace_bytes.restype = C.c_size_t
+    nbytes = lib().pq_groupwise_workspace_bytes(T, K, N)
+    if ws is None:
+        ws = torch.empty((max(int(nbytes), 256),), dtype=torch.uint8, device=X.device)
+    if Y is None:
+        Y = torch.empty((T, N), dtype=torch.float32, device=X.device)
+    _check(lib().pq_groupwise_fwd(_p(X), _p(W), _dt(X), T, K, N, int(group), C.c_float(beta), _p(Y), _p(ws),
+                                  C.c_size_t(ws.numel()), _stream()))
+    return Y
 
 
 def prof_enable(on=True):

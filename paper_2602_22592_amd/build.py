@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpquant.so")
-SOURCES = ["pq_api.hip", "pq_quant.hip", "pq_gemm.hip", "pq_decode.hip", "pq_moe.hip", "pq_ffn.hip"]
+SOURCES = ["pq_api.hip", "pq_quant.hip", "pq_gemm.hip", "pq_decode.hip", "pq_moe.hip", "pq_ffn.hip", "pq_groupwise.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
