@@ -445,7 +445,10 @@ static int linear_fwd_impl(const pq_linear_desc* d, const void* X, const void* W
     if (int e = pq_launch_quant_act(X, d->io_dtype, T, K, Xq, gamma, Xt, s)) return e;
 
   // bf16 I/O with a live hp branch: the rank-r product H B^T is accumulated into the 1-bit GEMM's tile
-  const bool fuse_hp = bf16 && r > 0 && d->alpha != 0.0f && pq_plan_gemm(0, T, N, K, true).splits == 1;
+  // (the fused form carries beta / alpha through the tile: only while that ratio stays far from the fp32 range, otherwise
+  // the two branches are scaled separately as in the Sec. 3.2 sum)
+  const bool fuse_hp = bf16 && r > 0 && d->alpha != 0.0f && fabsf(d->alpha) >= 9.5367431640625e-7f * fabsf(d->beta) &&
+                       pq_plan_gemm(0, T, N, K, true).splits == 1;
   if (r > 0 && !H_done)
     if (int err = launch_H(false)) return err;
   {  // 1-bit branch: Y = fl32(fl32(beta*lambda)/gamma_t) * acc   [+ alpha * H B^T when fused]

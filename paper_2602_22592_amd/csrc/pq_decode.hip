@@ -17,6 +17,8 @@
 //             dense-masked bf16 MFMA over the experts that some token of the batch selected.
 // Several independent layers (weight sets) can be processed by one launch (grid.y), which is how
 // the bench keeps the working set larger than the Infinity Cache.
+#include <mutex>
+
 #include "pq_internal.h"
 #include <type_traits>
 
@@ -1417,28 +1419,38 @@ __global__ __launch_bounds__(256) void decode_ffn_mid_kernel(const uint16_t* __r
 // The per-token kernels stage one token as fp32 (plus its codes for INT8 experts) in dynamic LDS next to a small
 // static block: above 64 KB in total the launch needs the limit raised once per process.
 static int decode_raise_lds_limits() {
-  static bool done = false;
-  if (done) return PQ_OK;
-  const int lim = 96 * 1024;
-  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_prep_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lim));
-  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_prep_h_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, lim));
-  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_prep_h_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, lim));
-  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_ffn_mid_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lim));
-  done = true;
-  return PQ_OK;
+  static std::once_flag once;
+  static int rc = PQ_OK;
+  std::call_once(once, [] {
+    const int lim = 96 * 1024;
+    auto set = [&](const void* f) {
+      if (rc == PQ_OK && hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lim) != hipSuccess)
+        rc = pq_set_error(PQ_ERR_HIP, "hipFuncSetAttribute failed for a decode kernel");
+    };
+    set((const void*)decode_prep_kernel);
+    set((const void*)decode_prep_h_kernel<false>);
+    set((const void*)decode_prep_h_kernel<true>);
+    set((const void*)decode_ffn_mid_kernel);
+  });
+  return rc;
 }
 
 static int decode_set_gemm16_limits() {
-  static bool attr_set = false;
-  if (attr_set) return PQ_OK;
-  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-  PQ_CHECK_HIP(hipFuncSetAttribute((const void*)decode_gemm16_tiled_kernel<16, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-  attr_set = true;
-  return PQ_OK;
+  static std::once_flag once;
+  static int rc = PQ_OK;
+  std::call_once(once, [] {
+    auto set = [&](const void* f) {
+      if (rc == PQ_OK && hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+        rc = pq_set_error(PQ_ERR_HIP, "hipFuncSetAttribute failed for a decode kernel");
+    };
+    set((const void*)decode_gemm16_kernel<8>);
+    set((const void*)decode_gemm16_kernel<16>);
+    set((const void*)decode_gemm16_tiled_kernel<8>);
+    set((const void*)decode_gemm16_tiled_kernel<16>);
+    set((const void*)decode_gemm16_tiled_kernel<8, true>);
+    set((const void*)decode_gemm16_tiled_kernel<16, true>);
+  });
+  return rc;
 }
 
 // Several tokens per layer (2..16): the same four stages on the small-batch kernels.  The up and gate products are

@@ -2,6 +2,8 @@
 // histogram and stable permutation, row gather, the gated unit with fused AbsMax re-quantisation,
 // expert activation forward/backward, gate/alpha reductions, router backward, scatter-combine.
 // All tensors here are bf16 unless noted; every reduction has a fixed order.
+#include <mutex>
+
 #include "pq_internal.h"
 
 namespace {
@@ -509,11 +511,13 @@ int pq_launch_lincomb(void* out, const void* x0, const void* x1, const void* x2,
 int pq_launch_route(const int* idx, int S, int E, int* counts, int* offsets, int* perm, int* inv, hipStream_t s) {
   pq_prof_scope prof(PQP_MOE_ROUTE, s);
   if (S <= 96 * 1024) {
-    static bool attr_set = false;
-    if (!attr_set) {
-      PQ_CHECK_HIP(hipFuncSetAttribute((const void*)route_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
-      attr_set = true;
-    }
+    static std::once_flag once;
+    static int rc = PQ_OK;
+    std::call_once(once, [] {
+      if (hipFuncSetAttribute((const void*)route_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024) != hipSuccess)
+        rc = pq_set_error(PQ_ERR_HIP, "hipFuncSetAttribute failed for route_kernel");
+    });
+    if (rc != PQ_OK) return rc;
     route_kernel<true><<<1, 1024, (size_t)((S + 15) / 16 * 16), s>>>(idx, S, E, counts, offsets, perm, inv);
   } else {
     route_kernel<false><<<1, 1024, 0, s>>>(idx, S, E, counts, offsets, perm, inv);

@@ -225,6 +225,15 @@ def test_linear_ste_clip_and_scale_edge_cases(bf16):
     check_linear(c, bf16, alpha=0.0, beta=0.7)
 
 
+def test_linear_with_a_feature_scale_far_below_the_other():
+    """alpha twelve orders of magnitude below beta: the fused forward (which carries beta / alpha through the tile) steps
+    aside for the two separately scaled branches of the Sec. 3.2 sum; everything stays finite and on the oracle."""
+    say("linear alpha=1e-12, beta=0.2, bf16, fused-path shape")
+    c = wl.linear_case(610, 300, 640, 384, hp_rank=128, bf16=True)
+    got = check_linear(c, True, alpha=1e-12, beta=0.2)
+    assert np.isfinite(got["Y"]).all() and np.isfinite(got["dX"]).all()
+
+
 def test_linear_config2_reduced_tokens_bf16():
     say("linear config2 shape at T=1024 (2048x2048, r=128), bf16")
     check_linear(wl.config2(tokens=1024), True)
