@@ -2236,8 +2236,12 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
     // row groups with a narrow output and a long contraction (expert up/gate projections, their input
     // gradients): too few tiles to fill the chip, so the contraction is split as for plain GEMMs
     // (a per-group column divisor is applied in the GEMM's own epilogue only: such products are not split)
-    if (grp.mode == 1 && N <= 128 && K >= 1024 && splitk_ws && !(epi.col_div && grp.coldiv_stride)) {
-      const long tiles = (long)((grp.max_rows + 127) / 128 + grp.n_groups) * ((N + 127) / 128);
+    // (likewise experts of several hundred hidden units on the 256x256 tiles: Table 1's r = 384 gives 99 tiles at 8192 slots)
+    const bool wide_few = pl.bm == 256 && (long)((grp.max_rows + 255) / 256 + grp.n_groups) * ((N + 255) / 256) <= 128 && K % 512 == 0 &&
+                          epi.out_kind == PQ_OUT_BF16 && !epi.accumulate && !epi.row_div;
+    if (grp.mode == 1 && (N <= 128 || wide_few) && K >= 1024 && splitk_ws && !(epi.col_div && grp.coldiv_stride)) {
+      const long tiles = wide_few ? (long)((grp.max_rows + 255) / 256 + grp.n_groups) * ((N + 255) / 256)
+                                  : (long)((grp.max_rows + 127) / 128 + grp.n_groups) * ((N + 127) / 128);
       long want = tiles > 0 ? 256 / tiles : 1;
       if (want > 8) want = 8;
       if (want > 1) {
