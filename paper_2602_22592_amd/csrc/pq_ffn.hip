@@ -76,7 +76,10 @@ ffn_layout make_layout(const pq_ffn_desc& d) {
   L.red_b = w.take(sizeof(double) * (size_t)L.n_red_b);
   size_t sk = 0;
   const int Ti = d.tokens, Di = d.d_model, Fi = (int)F;
-  const int shapes[4][3] = {{Di, Fi, Ti}, {Ti, Fi, Di}, {Ti, Di, Fi}, {Fi, Di, Ti}};
+  // (the last six: the expert products of a single high-precision branch, which run as plain GEMMs over all slots)
+  const int Si = (int)S, ri = (int)r;
+  const int shapes[10][3] = {{Di, Fi, Ti}, {Ti, Fi, Di}, {Ti, Di, Fi}, {Fi, Di, Ti},
+                             {Si, 2 * ri, Di}, {Si, ri, Di}, {Si, Di, 2 * ri}, {Si, Di, ri}, {Di, ri, Si}, {2 * ri, Di, Si}};
   for (const auto& sh : shapes) {
     if (sh[0] <= 0 || sh[1] <= 0) continue;
     const size_t b = pq_plan_gemm(0, sh[0], sh[1], sh[2]).ws_bytes;
@@ -216,6 +219,9 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
   int* inv = (int*)(cx + L.inv);
   if (int e = pq_launch_route(idx, S, E, (int*)(cx + L.counts), offsets, perm, inv, s)) return e;
   pq_gemm_group g1{offsets, E, 1, 0, 0, S};
+  // a single branch (the paper's default, N = 1): every slot belongs to it, so its products are plain GEMMs over all slots
+  // (they then take the split rules and kernels of plain GEMMs, the four-wavefront weight-gradient kernel among them)
+  const pq_gemm_group* pg1 = (E == 1 && !hp8) ? nullptr : &g1;
   if (hp8) {
     // slot-ordered X~ (for the backward), codes (int8 rows moved as D/2 16-bit units) and gamma of x
     if (int e = pq_launch_gather_rows(cx + L.Xt, perm, k, S, D, cx + L.Xp, s)) return e;
@@ -253,7 +259,7 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
     pq_epilogue e = epi0();
     e.C = cx + L.ue; e.ldc = 2 * r; e.out_kind = PQ_OUT_BF16;
     g1.b_stride = (long)2 * r * D;
-    if (int err = pq_launch_gemm(0, S, 2 * r, D, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+    if (int err = pq_launch_gemm(0, S, 2 * r, D, A, B, e, s, PQP_GEMM_EXPERT, sk, pg1)) return err;
   }
   if (int e = pq_launch_expert_act(cx + L.ue, cx + L.ue + (size_t)r * 2, 2 * r, S, r, cx + L.a, s)) return e;
   {
@@ -262,7 +268,7 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
     pq_epilogue e = epi0();
     e.C = cx + L.Ys; e.ldc = D; e.out_kind = PQ_OUT_BF16;
     g1.b_stride = (long)D * r;
-    if (int err = pq_launch_gemm(0, S, D, r, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+    if (int err = pq_launch_gemm(0, S, D, r, A, B, e, s, PQP_GEMM_EXPERT, sk, pg1)) return err;
   }
   return pq_launch_combine_fwd(Y, cx + L.Ys, inv, gate, d->alpha, T, k, D, s);
 }
@@ -352,15 +358,18 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
                                          dalpha_dbeta + 1, s)) return e;
   pq_gemm_group g1{offsets, E, 1, 0, 0, S};
   pq_gemm_group g2{offsets, E, 2, 0, 0, S};
+  const bool hp8 = d->hp_kind == PQ_HP_LOWRANK_INT8;
+  const bool one = E == 1 && !hp8;                   // a single branch: plain GEMMs over all slots (see the forward)
+  const pq_gemm_group* pg1 = one ? nullptr : &g1;
+  const pq_gemm_group* pg2 = one ? nullptr : &g2;
   if (S > 0) {  // da = dYp Down_e  (scaled by alpha*gate inside the activation backward)
     pq_operand A{ws + L.dYp, D, PQ_SRC_KC16, nullptr};
     pq_operand B{Down, r, PQ_SRC_KS16, nullptr};
     pq_epilogue e = epi0();
     e.C = ws + L.da; e.ldc = r; e.out_kind = PQ_OUT_BF16;
     g1.b_stride = (long)D * r;
-    if (int err = pq_launch_gemm(0, S, r, D, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+    if (int err = pq_launch_gemm(0, S, r, D, A, B, e, s, PQP_GEMM_EXPERT, sk, pg1)) return err;
   }
-  const bool hp8 = d->hp_kind == PQ_HP_LOWRANK_INT8;
   // bf16 experts: u | g and du | dg lie side by side in [S][2 r] matrices (Up and Gate are one weight matrix per expert)
   if (hp8) {
     if (int e = pq_launch_expert_act_bwd(ws + L.da, cx + L.ue, cx + L.ge, a_fwd, perm, gate, d->alpha, S, r, r, ws + L.du, ws + L.dg,
@@ -375,21 +384,21 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
     pq_epilogue e = epi0();
     e.C = dDown; e.ldc = r; e.out_kind = PQ_OUT_F32;
     g2.c_stride = (long)D * r;
-    if (int err = pq_launch_gemm(0, D, r, S, A, B, e, s, PQP_GEMM_EXPERT, sk, &g2)) return err;
+    if (int err = pq_launch_gemm(0, D, r, S, A, B, e, s, PQP_GEMM_EXPERT, sk, pg2)) return err;
     pq_operand Bx{cx + L.Xp, D, PQ_SRC_KS16, nullptr};
     if (hp8) {
       pq_operand Au{ws + L.du, r, PQ_SRC_KS16, nullptr};
       e.C = dUp; e.ldc = D;
       g2.c_stride = (long)r * D;
-      if (int err = pq_launch_gemm(0, r, D, S, Au, Bx, e, s, PQP_GEMM_EXPERT, sk, &g2)) return err;
+      if (int err = pq_launch_gemm(0, r, D, S, Au, Bx, e, s, PQP_GEMM_EXPERT, sk, pg2)) return err;
       pq_operand Ag{ws + L.dg, r, PQ_SRC_KS16, nullptr};
       e.C = dGate;
-      if (int err = pq_launch_gemm(0, r, D, S, Ag, Bx, e, s, PQP_GEMM_EXPERT, sk, &g2)) return err;
+      if (int err = pq_launch_gemm(0, r, D, S, Ag, Bx, e, s, PQP_GEMM_EXPERT, sk, pg2)) return err;
     } else {   // d[Up_e; Gate_e] = [du | dg]^T Xp, then split into the caller's two gradients
       pq_operand Aug{ws + L.du, 2 * r, PQ_SRC_KS16, nullptr};
       e.C = ws + L.dUG; e.ldc = D;
       g2.c_stride = (long)2 * r * D;
-      if (int err = pq_launch_gemm(0, 2 * r, D, S, Aug, Bx, e, s, PQP_GEMM_EXPERT, sk, &g2)) return err;
+      if (int err = pq_launch_gemm(0, 2 * r, D, S, Aug, Bx, e, s, PQP_GEMM_EXPERT, sk, pg2)) return err;
       if (int err = pq_launch_split_expert_rows((const float*)(ws + L.dUG), E, r, D, dUp, dGate, s)) return err;
     }
   }
@@ -399,18 +408,18 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
     pq_epilogue e = epi0();
     e.C = ws + L.dXs; e.ldc = D; e.out_kind = PQ_OUT_BF16;
     g1.b_stride = (long)r * D;
-    if (int err = pq_launch_gemm(0, S, D, r, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+    if (int err = pq_launch_gemm(0, S, D, r, A, B, e, s, PQP_GEMM_EXPERT, sk, pg1)) return err;
     pq_operand A2{ws + L.dg, r, PQ_SRC_KC16, nullptr};
     pq_operand B2{Gate, D, PQ_SRC_KS16, nullptr};
     e.accumulate = 1;
-    if (int err = pq_launch_gemm(0, S, D, r, A2, B2, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+    if (int err = pq_launch_gemm(0, S, D, r, A2, B2, e, s, PQP_GEMM_EXPERT, sk, pg1)) return err;
   } else if (S > 0) {  // dXs = [du | dg] [Up_e; Gate_e]
     pq_operand A{ws + L.du, 2 * r, PQ_SRC_KC16, nullptr};
     pq_operand B{cx + L.UG, D, PQ_SRC_KS16, nullptr};
     pq_epilogue e = epi0();
     e.C = ws + L.dXs; e.ldc = D; e.out_kind = PQ_OUT_BF16;
     g1.b_stride = (long)2 * r * D;
-    if (int err = pq_launch_gemm(0, S, D, 2 * r, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+    if (int err = pq_launch_gemm(0, S, D, 2 * r, A, B, e, s, PQP_GEMM_EXPERT, sk, pg1)) return err;
   }
   float* dlogit = (float*)(ws + L.dlogit);
   if (int e = pq_launch_router_bwd(rd, inv, idx, (const float*)(cx + L.probs), d->alpha, T, k, E, dlogit, s)) return e;
