@@ -213,15 +213,21 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
   // routed experts: router -> stable permutation by expert -> gather -> grouped GEMMs -> combine
   int* idx = (int*)(cx + L.idx);
   float* gate = (float*)(cx + L.gate);
-  if (int e = pq_launch_router(X, Wr, PQ_BF16, T, D, E, k, idx, gate, (float*)(cx + L.probs), s)) return e;
   int* offsets = (int*)(cx + L.offsets);
   int* perm = (int*)(cx + L.perm);
   int* inv = (int*)(cx + L.inv);
-  if (int e = pq_launch_route(idx, S, E, (int*)(cx + L.counts), offsets, perm, inv, s)) return e;
+  // a single branch (the paper's default, N = 1) has nothing to route: gate 1, identity permutation, X itself in slot order
+  const bool one = E == 1 && !hp8;
+  if (one) {
+    if (int e = pq_launch_route_single(S, idx, gate, (float*)(cx + L.probs), (int*)(cx + L.counts), offsets, perm, inv, s)) return e;
+  } else {
+    if (int e = pq_launch_router(X, Wr, PQ_BF16, T, D, E, k, idx, gate, (float*)(cx + L.probs), s)) return e;
+    if (int e = pq_launch_route(idx, S, E, (int*)(cx + L.counts), offsets, perm, inv, s)) return e;
+  }
   pq_gemm_group g1{offsets, E, 1, 0, 0, S};
   // a single branch (the paper's default, N = 1): every slot belongs to it, so its products are plain GEMMs over all slots
   // (they then take the split rules and kernels of plain GEMMs, the four-wavefront weight-gradient kernel among them)
-  const pq_gemm_group* pg1 = (E == 1 && !hp8) ? nullptr : &g1;
+  const pq_gemm_group* pg1 = one ? nullptr : &g1;
   if (hp8) {
     // slot-ordered X~ (for the backward), codes (int8 rows moved as D/2 16-bit units) and gamma of x
     if (int e = pq_launch_gather_rows(cx + L.Xt, perm, k, S, D, cx + L.Xp, s)) return e;
@@ -250,11 +256,13 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
     }
     return pq_launch_combine_fwd(Y, cx + L.Ys, inv, gate, d->alpha, T, k, D, s);
   }
-  if (int e = pq_launch_gather_rows(X, perm, k, S, D, cx + L.Xp, s)) return e;
+  const void* xp = one ? X : cx + L.Xp;
+  if (!one)
+    if (int e = pq_launch_gather_rows(X, perm, k, S, D, cx + L.Xp, s)) return e;
   // [u | g] = Xp [Up_e; Gate_e]^T: both projections as one product with 2 r outputs per slot
   if (int e = pq_launch_concat_expert_rows(Up, Gate, E, r, D, cx + L.UG, s)) return e;
   {
-    pq_operand A{cx + L.Xp, D, PQ_SRC_KC16, nullptr};
+    pq_operand A{xp, D, PQ_SRC_KC16, nullptr};
     pq_operand B{cx + L.UG, D, PQ_SRC_KC16, nullptr};
     pq_epilogue e = epi0();
     e.C = cx + L.ue; e.ldc = 2 * r; e.out_kind = PQ_OUT_BF16;
@@ -351,19 +359,22 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
   const int* perm = (const int*)(cx + L.perm);
   const int* inv = (const int*)(cx + L.inv);
   float* rd = (float*)(ws + L.rd);
-  if (int e = pq_launch_gather_rows(dY, perm, k, S, D, ws + L.dYp, s)) return e;
-  if (int e = pq_launch_rowdot(ws + L.dYp, cx + L.Ys, perm, gate, S, D, rd, red_a, s)) return e;
+  const bool hp8 = d->hp_kind == PQ_HP_LOWRANK_INT8;
+  const bool one = E == 1 && !hp8;                   // a single branch: identity permutation, plain GEMMs over all slots (see the forward)
+  const void* dyp = one ? dY : ws + L.dYp;
+  const void* xp = one ? X : cx + L.Xp;
+  if (!one)
+    if (int e = pq_launch_gather_rows(dY, perm, k, S, D, ws + L.dYp, s)) return e;
+  if (int e = pq_launch_rowdot(dyp, cx + L.Ys, perm, gate, S, D, rd, red_a, s)) return e;
   // d alpha (row dots above) and d beta (partials of the dW_down GEMM): one launch for both fixed-order sums
   if (int e = pq_launch_reduce_partials2(red_a, S > 0 ? L.n_red_a : 0, 1.0f, nullptr, dalpha_dbeta, red_b, L.n_red_b, 1.0f, ml_down + 1,
                                          dalpha_dbeta + 1, s)) return e;
   pq_gemm_group g1{offsets, E, 1, 0, 0, S};
   pq_gemm_group g2{offsets, E, 2, 0, 0, S};
-  const bool hp8 = d->hp_kind == PQ_HP_LOWRANK_INT8;
-  const bool one = E == 1 && !hp8;                   // a single branch: plain GEMMs over all slots (see the forward)
   const pq_gemm_group* pg1 = one ? nullptr : &g1;
   const pq_gemm_group* pg2 = one ? nullptr : &g2;
   if (S > 0) {  // da = dYp Down_e  (scaled by alpha*gate inside the activation backward)
-    pq_operand A{ws + L.dYp, D, PQ_SRC_KC16, nullptr};
+    pq_operand A{dyp, D, PQ_SRC_KC16, nullptr};
     pq_operand B{Down, r, PQ_SRC_KS16, nullptr};
     pq_epilogue e = epi0();
     e.C = ws + L.da; e.ldc = r; e.out_kind = PQ_OUT_BF16;
@@ -379,13 +390,13 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
                                          ws + L.du, ws + L.du + (size_t)r * 2, ws + L.as, s)) return e;
   }
   {  // per-expert weight gradients: contraction over the expert's slots
-    pq_operand A{ws + L.dYp, D, PQ_SRC_KS16, nullptr};
+    pq_operand A{dyp, D, PQ_SRC_KS16, nullptr};
     pq_operand B{ws + L.as, r, PQ_SRC_KS16, nullptr};
     pq_epilogue e = epi0();
     e.C = dDown; e.ldc = r; e.out_kind = PQ_OUT_F32;
     g2.c_stride = (long)D * r;
     if (int err = pq_launch_gemm(0, D, r, S, A, B, e, s, PQP_GEMM_EXPERT, sk, pg2)) return err;
-    pq_operand Bx{cx + L.Xp, D, PQ_SRC_KS16, nullptr};
+    pq_operand Bx{xp, D, PQ_SRC_KS16, nullptr};
     if (hp8) {
       pq_operand Au{ws + L.du, r, PQ_SRC_KS16, nullptr};
       e.C = dUp; e.ldc = D;
@@ -422,6 +433,10 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
     if (int err = pq_launch_gemm(0, S, D, 2 * r, A, B, e, s, PQP_GEMM_EXPERT, sk, pg1)) return err;
   }
   float* dlogit = (float*)(ws + L.dlogit);
+  if (one) {   // softmax over one logit is constant: no gradient reaches the router
+    if (int e = pq_launch_zero_f32(dWr, (size_t)D, s)) return e;
+    return pq_launch_combine_bwd(dX, ws + L.dXs, inv, nullptr, Wr, T, k, D, 0, s);
+  }
   if (int e = pq_launch_router_bwd(rd, inv, idx, (const float*)(cx + L.probs), d->alpha, T, k, E, dlogit, s)) return e;
   if (int e = pq_launch_dwr(dlogit, X, T, D, E, (float*)(ws + L.dwr), dWr, s)) return e;
   return pq_launch_combine_bwd(dX, ws + L.dXs, inv, dlogit, Wr, T, k, D, E, s);

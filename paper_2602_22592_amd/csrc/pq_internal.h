@@ -200,6 +200,9 @@ int pq_launch_swiglu_bwd(const void* dHd, const void* U, const void* G, int T, i
 int pq_launch_expert_act(const void* ue, const void* ge, int ld, int S, int r, void* a, hipStream_t s);
 int pq_launch_expert_act_bwd(const void* da, const void* ue, const void* ge, const void* a, const int* perm, const float* gate,
                              float alpha, int S, int r, int ld, void* du, void* dg, void* as, hipStream_t s);
+// one expert, top-1: expert 0, gate 1, identity permutation, one segment (what router + counting sort would produce)
+int pq_launch_route_single(int S, int* idx, float* gate, float* probs, int* counts, int* offsets, int* perm, int* inv, hipStream_t s);
+int pq_launch_zero_f32(float* p, size_t n, hipStream_t s);
 // UG[e] = [Up[e]; Gate[e]] (bf16 [E][2 r][d]) and the split of its fp32 gradient back into dUp, dGate
 int pq_launch_concat_expert_rows(const void* up, const void* gate_w, int E, int r, int d, void* ug, hipStream_t s);
 int pq_launch_split_expert_rows(const float* dug, int E, int r, int d, float* dup, float* dgate, hipStream_t s);

@@ -96,6 +96,29 @@ __global__ __launch_bounds__(1024) void route_kernel(const int* __restrict__ idx
   }
 }
 
+// One expert (a single high-precision branch, top-1): what the router and the counting sort produce is known beforehand:
+// expert 0 with gate softmax([logit]) = 1 for every token, the identity permutation, one segment of all slots.
+__global__ __launch_bounds__(256) void route_single_kernel(int S, int* __restrict__ idx, float* __restrict__ gate, float* __restrict__ probs,
+                                                           int* __restrict__ counts, int* __restrict__ offsets, int* __restrict__ perm,
+                                                           int* __restrict__ inv) {
+  const int s = blockIdx.x * 256 + threadIdx.x;
+  if (s == 0) {
+    counts[0] = S;
+    offsets[0] = 0;
+    offsets[1] = S;
+  }
+  if (s >= S) return;
+  idx[s] = 0;
+  gate[s] = 1.0f;
+  probs[s] = 1.0f;
+  perm[s] = s;
+  inv[s] = s;
+}
+__global__ __launch_bounds__(256) void zero_f32_kernel(float* __restrict__ p, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0.0f;
+}
+
 // dst[pos][:] = src[perm[pos] / k][:]   (rows of d bf16, d % 8 == 0), one wavefront per row
 __global__ __launch_bounds__(256) void gather_rows_kernel(const uint16_t* __restrict__ src, const int* __restrict__ perm, int k,
                                                           int S, int d, uint16_t* __restrict__ dst) {
@@ -523,6 +546,21 @@ int pq_launch_route(const int* idx, int S, int E, int* counts, int* offsets, int
     route_kernel<false><<<1, 1024, 0, s>>>(idx, S, E, counts, offsets, perm, inv);
   }
   PQ_CHECK_LAUNCH("route_kernel");
+  return PQ_OK;
+}
+
+int pq_launch_route_single(int S, int* idx, float* gate, float* probs, int* counts, int* offsets, int* perm, int* inv, hipStream_t s) {
+  pq_prof_scope prof(PQP_MOE_ROUTE, s);
+  route_single_kernel<<<(S + 256) / 256, 256, 0, s>>>(S, idx, gate, probs, counts, offsets, perm, inv);
+  PQ_CHECK_LAUNCH("route_single_kernel");
+  return PQ_OK;
+}
+
+int pq_launch_zero_f32(float* p, size_t n, hipStream_t s) {
+  if (n == 0) return PQ_OK;
+  pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
+  zero_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(p, n);
+  PQ_CHECK_LAUNCH("zero_f32_kernel");
   return PQ_OK;
 }
 
