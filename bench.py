@@ -36,7 +36,7 @@ PREWARM_S = 0.25        # seconds of the headline step run before its warm-up st
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
 # kernel-name fragments of the three large GEMMs of the default workload (template arguments: ..., whole tiles, int8,
 # operand kinds of A and B, kinds of the fused second contraction, streaming loop)
-TRAFFIC_KERNELS = {"gemm_dW": "128, true, false, 1, 1, -1, -1, true>", "gemm_dX": "128, true, false, 0, 4, 0, 1, true>",
+TRAFFIC_KERNELS = {"gemm_dW": "gemm_tn_w4_kernel", "gemm_dX": "128, true, false, 0, 4, 0, 1, true>",
                    "gemm_onebit_fwd": "128, true, true, 2, 3, 0, 0, true>", "decode_main_B1": "decode_gemv_tiled_kernel<1, false>",
                    "decode_main_B8": "decode_gemm16_tiled_kernel<8, false>", "decode_prep_B1": "decode_prep_h_kernel<false>",
                    "decode_prep_B8": "decode_prep_kernel", "decode_h_B8": "decode_h_kernel"}
