@@ -535,6 +535,81 @@ __global__ __launch_bounds__(256) void decode_h_kernel(const uint16_t* __restric
   if (lane == 0) h[o] = acc;
 }
 
+// The same hidden states computed expert by expert (K = 512 NV <= 4096, at most 64 slots per layer): a workgroup owns
+// HG_ROWS rows of one expert of one layer, a wavefront two of them, held packed in registers (a row of 4096 bf16 is
+// eight 16-byte pieces per lane); every token of the batch that selected the expert is then run against them, so an
+// expert's rows are read from memory once instead of once per selecting token.  The layer's selections are fetched with
+// one vector load and turned into a mask of the expert's slots (a scan with scalar loads is a chain of memory latencies);
+// workgroups of experts nobody selected return at once.  Per (slot, row) the sum runs in the order of decode_h_kernel.
+constexpr int HG_ROWS = 8;
+template <int NV>
+__global__ __launch_bounds__(256) void decode_h_grouped_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ hpA,
+                                                               const int* __restrict__ idx, int B, int E, int r, int topk,
+                                                               float* __restrict__ h) {
+  constexpr int K = 512 * NV;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int ngrp = r / HG_ROWS;
+  const int rg = blockIdx.x % ngrp, le = blockIdx.x / ngrp;    // le = layer * E + e
+  const int layer = le / E, e = le - layer * E;
+  const int nslot = B * topk;
+  const int sel = lane < nslot ? idx[(size_t)layer * nslot + lane] : -1;
+  unsigned long long users = __ballot(sel == e);
+  if (users == 0ull) return;
+  const int r0 = rg * HG_ROWS + 2 * wave;
+  const uint4* a0 = reinterpret_cast<const uint4*>(hpA + ((size_t)le * r + r0) * K) + lane;
+  const uint4* a1 = a0 + K / 8;
+  uint4 av0[NV], av1[NV];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    av0[i] = nt_load16(a0 + 64 * i);
+    av1[i] = nt_load16(a1 + 64 * i);
+  }
+  while (users) {
+    const int sl = __builtin_ctzll(users);
+    users &= users - 1ull;
+    const uint4* x4 = reinterpret_cast<const uint4*>(X + ((size_t)layer * B + sl / topk) * K) + lane;
+    uint4 xv[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) xv[i] = x4[64 * i];
+    float s0 = 0.0f, s1 = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      // (the rows stay packed: without this the unpacked halves are hoisted out of the loop and held in 128 more registers)
+      asm volatile("" : "+v"(av0[i].x), "+v"(av0[i].y), "+v"(av0[i].z), "+v"(av0[i].w), "+v"(av1[i].x), "+v"(av1[i].y), "+v"(av1[i].z), "+v"(av1[i].w));
+      const uint4 x = xv[i], a = av0[i], b = av1[i];
+      s0 += __uint_as_float(a.x << 16) * __uint_as_float(x.x << 16) + __uint_as_float(a.x & 0xFFFF0000u) * __uint_as_float(x.x & 0xFFFF0000u);
+      s0 += __uint_as_float(a.y << 16) * __uint_as_float(x.y << 16) + __uint_as_float(a.y & 0xFFFF0000u) * __uint_as_float(x.y & 0xFFFF0000u);
+      s0 += __uint_as_float(a.z << 16) * __uint_as_float(x.z << 16) + __uint_as_float(a.z & 0xFFFF0000u) * __uint_as_float(x.z & 0xFFFF0000u);
+      s0 += __uint_as_float(a.w << 16) * __uint_as_float(x.w << 16) + __uint_as_float(a.w & 0xFFFF0000u) * __uint_as_float(x.w & 0xFFFF0000u);
+      s1 += __uint_as_float(b.x << 16) * __uint_as_float(x.x << 16) + __uint_as_float(b.x & 0xFFFF0000u) * __uint_as_float(x.x & 0xFFFF0000u);
+      s1 += __uint_as_float(b.y << 16) * __uint_as_float(x.y << 16) + __uint_as_float(b.y & 0xFFFF0000u) * __uint_as_float(x.y & 0xFFFF0000u);
+      s1 += __uint_as_float(b.z << 16) * __uint_as_float(x.z << 16) + __uint_as_float(b.z & 0xFFFF0000u) * __uint_as_float(x.z & 0xFFFF0000u);
+      s1 += __uint_as_float(b.w << 16) * __uint_as_float(x.w << 16) + __uint_as_float(b.w & 0xFFFF0000u) * __uint_as_float(x.w & 0xFFFF0000u);
+    }
+    s0 = wave_sum(s0);
+    s1 = wave_sum(s1);
+    if (lane == 0) {
+      float* hs = h + ((size_t)layer * nslot + sl) * r + r0;
+      hs[0] = s0;
+      hs[1] = s1;
+    }
+  }
+}
+
+// launches the expert-grouped kernel when the shape allows it (then returns true)
+static bool launch_h_grouped(const uint16_t* X, const uint16_t* A, const int* idx, int L, int B, int K, int E, int r, int topk, float* h,
+                             hipStream_t s) {
+  if (r % HG_ROWS != 0 || B * topk > 64) return false;
+  const dim3 grid(L * E * (r / HG_ROWS)), block(256);
+  if (K == 4096) decode_h_grouped_kernel<8><<<grid, block, 0, s>>>(X, A, idx, B, E, r, topk, h);
+  else if (K == 2048) decode_h_grouped_kernel<4><<<grid, block, 0, s>>>(X, A, idx, B, E, r, topk, h);
+  else if (K == 1024) decode_h_grouped_kernel<2><<<grid, block, 0, s>>>(X, A, idx, B, E, r, topk, h);
+  else if (K == 512) decode_h_grouped_kernel<1><<<grid, block, 0, s>>>(X, A, idx, B, E, r, topk, h);
+  else return false;
+  return true;
+}
+
 // ------------------------------------------------------------------------------------------
 // Batch 1: bit-plane GEMV.  A wavefront owns ROWS_PER_WAVE consecutive rows; 8 lanes share a row.
 // In step i a lane holds words 32 i + 4 (lane % 8) + {0..3} of its row, so the 8 lanes of a row read
@@ -1112,8 +1187,8 @@ __global__ __launch_bounds__(256) void decode_gemm16_kernel(gemm16_params p) {
             const int e = (e0 + q < p.E && ((used >> (e0 + q)) & 1ull)) ? e0 + q : -1;
             const uint16_t* br = p.hpB + ((size_t)layer * p.E + (e < 0 ? 0 : e)) * p.N * p.r + roff + 32 * hf;
             if (e >= 0) {                            // block-uniform
-              a0[q] = nt_load16(reinterpret_cast<const uint4*>(br));
-              a1[q] = nt_load16(reinterpret_cast<const uint4*>(br + (two ? 32 : 0)));
+              a0[q] = *reinterpret_cast<const uint4*>(br);          // (plain loads: two halves of the same lines, see the tiled kernel)
+              a1[q] = *reinterpret_cast<const uint4*>(br + (two ? 32 : 0));
             } else {
               a0[q] = make_uint4(0, 0, 0, 0);
               a1[q] = make_uint4(0, 0, 0, 0);
@@ -1262,8 +1337,10 @@ __global__ __launch_bounds__(256, 4) void decode_gemm16_tiled_kernel(gemm16_para
         uint4 a0[4], a1[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-          a0[t] = nt_load16(reinterpret_cast<const uint4*>(Be + roff[t] + 32 * hf));
-          a1[t] = nt_load16(reinterpret_cast<const uint4*>(Be + roff[t] + 32 * hf + (two ? 32 : 0)));
+          // plain loads: the two instructions take the two halves of the same 128-byte lines (16 rows x 64 B each), and
+          // with the non-temporal hint the second half was fetched from memory again (1.15 x the algorithmic bytes)
+          a0[t] = *reinterpret_cast<const uint4*>(Be + roff[t] + 32 * hf);
+          a1[t] = *reinterpret_cast<const uint4*>(Be + roff[t] + 32 * hf + (two ? 32 : 0));
         }
         const int col = e * p.r + 32 * hf + 8 * g;
         const uint4 b0 = *reinterpret_cast<const uint4*>(hm + (size_t)il * Er + (((col >> 3) ^ (il & 7)) << 3));
@@ -1483,7 +1560,8 @@ static int launch_decode_ffn_batch(int L, int B, int D, int F, int r, int E, int
   {  // hidden pairs [Up_e x ; Gate_e x] of every (token, selected expert)
     pq_prof_scope prof(PQP_DECODE_H, s);
     const int total = L * B * topk * 2 * r;
-    decode_h_kernel<<<(total + 3) / 4, 256, 0, s>>>((const uint16_t*)X, (const uint16_t*)UpGate, idx, B, D, E, 2 * r, topk, total, hug);
+    if (!launch_h_grouped((const uint16_t*)X, (const uint16_t*)UpGate, idx, L, B, D, E, 2 * r, topk, hug, s))
+      decode_h_kernel<<<(total + 3) / 4, 256, 0, s>>>((const uint16_t*)X, (const uint16_t*)UpGate, idx, B, D, E, 2 * r, topk, total, hug);
     PQ_CHECK_LAUNCH("decode_h_kernel");
   }
   {  // U and G
@@ -1622,7 +1700,8 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
         decode_h_int8_kernel<<<L * d.n_experts * (r / H8_ROWS), 256, 0, s>>>((const uint16_t*)X, (const int8_t*)hpA, gA, gamma, idx, B, K,
                                                                            d.n_experts, r, d.top_k, h);
       } else
-        decode_h_kernel<<<(total + 3) / 4, 256, 0, s>>>((const uint16_t*)X, (const uint16_t*)hpA, idx, B, K, d.n_experts, r, d.top_k, total, h);
+        if (!launch_h_grouped((const uint16_t*)X, (const uint16_t*)hpA, idx, L, B, K, d.n_experts, r, d.top_k, h, s))
+          decode_h_kernel<<<(total + 3) / 4, 256, 0, s>>>((const uint16_t*)X, (const uint16_t*)hpA, idx, B, K, d.n_experts, r, d.top_k, total, h);
       PQ_CHECK_LAUNCH("decode_h_kernel");
     }
   }
