@@ -39,7 +39,7 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
 TRAFFIC_KERNELS = {"gemm_dW": "gemm_tn_w4_kernel", "gemm_dX": "128, true, false, 0, 4, 0, 1, true>",
                    "gemm_onebit_fwd": "128, true, true, 2, 3, 0, 0, true>", "decode_main_B1": "decode_gemv_tiled_kernel<1, false>",
                    "decode_main_B8": "decode_gemm16_tiled_kernel<8, false>", "decode_prep_B1": "decode_prep_h_kernel<false>",
-                   "decode_prep_B8": "decode_prep_kernel", "decode_h_B8": "decode_h_kernel"}
+                   "decode_prep_B8": "decode_prep_kernel", "decode_h_B8": "decode_h_grouped_kernel<8>"}
 
 
 def csrc_sha():
