@@ -486,6 +486,68 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(uint16_t* __restrict__
   }
 }
 
+// The same with the router matrix in LDS (E * d bf16 <= 64 KB, E <= 64) and a token's pieces requested together: NC
+// 16-byte pieces per lane (d = 512 NC), up to KMAX slots per token; lane e fetches dlogit[t][e] once and hands it round.
+// (In the loop above every dlogit and router piece is a load of its own with a wait behind it: 32 cache round trips
+// per lane and token at 8 experts.)  A workgroup takes CB_TOK tokens per wavefront, so the router matrix is staged once
+// per 4 * CB_TOK tokens.  Same sums in the same order as above.
+constexpr int CB_TOK = 4;
+template <int NC, int KMAX>
+__global__ __launch_bounds__(256) void combine_bwd_lds_kernel(uint16_t* __restrict__ dX, const uint16_t* __restrict__ dXs,
+                                                              const int* __restrict__ inv, const float* __restrict__ dlogit,
+                                                              const uint16_t* __restrict__ Wr, int T, int k, int E) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char wr_s[];   // [E][d] bf16
+  constexpr int d = 512 * NC;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  {
+    const int nvec = E * d / 8;
+    for (int c = threadIdx.x; c < nvec; c += 256) reinterpret_cast<uint4*>(wr_s)[c] = reinterpret_cast<const uint4*>(Wr)[c];
+  }
+  __syncthreads();
+  for (int q = 0; q < CB_TOK; ++q) {
+    const int t = (blockIdx.x * 4 + wave) * CB_TOK + q;
+    if (t >= T) break;                                // wave-uniform
+    int pos[KMAX];
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) pos[j] = inv[t * k + min(j, k - 1)];
+    const float dlv = lane < E ? dlogit[(size_t)t * E + lane] : 0.0f;
+    uint4* x4 = reinterpret_cast<uint4*>(dX + (size_t)t * d) + lane;
+    uint4 xv[NC], sv[KMAX][NC];
+#pragma unroll
+    for (int i = 0; i < NC; ++i) xv[i] = x4[64 * i];
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j)
+#pragma unroll
+      for (int i = 0; i < NC; ++i) sv[j][i] = reinterpret_cast<const uint4*>(dXs + (size_t)pos[j] * d)[lane + 64 * i];
+    float acc[NC][8];
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+      unpack8(xv[i], acc[i]);
+#pragma unroll
+      for (int j = 0; j < KMAX; ++j) {
+        if (j < k) {
+          float v[8];
+          unpack8(sv[j][i], v);
+#pragma unroll
+          for (int u = 0; u < 8; ++u) acc[i][u] += v[u];
+        }
+      }
+    }
+    for (int e = 0; e < E; ++e) {
+      const float dl = __shfl(dlv, e);
+#pragma unroll
+      for (int i = 0; i < NC; ++i) {
+        float w[8];
+        unpack8(reinterpret_cast<const uint4*>(wr_s + (size_t)e * d * 2)[lane + 64 * i], w);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc[i][u] += dl * w[u];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NC; ++i) x4[64 * i] = pack8(acc[i]);
+  }
+}
+
 // out = sum_i c[i] * x[i]  (up to 4 bf16 tensors, fp32 arithmetic, one rounding): the glue between
 // the linears of a layer stack (residual adds, the stand-in for the attention core)
 __global__ __launch_bounds__(256) void lincomb_kernel(uint16_t* __restrict__ out, const uint16_t* x0, const uint16_t* x1,
@@ -699,7 +761,14 @@ int pq_launch_combine_bwd(void* dX, const void* dXs, const int* inv, const float
                           hipStream_t s) {
   if (T == 0) return PQ_OK;
   pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
-  combine_bwd_kernel<<<(T + 3) / 4, 256, 0, s>>>((uint16_t*)dX, (const uint16_t*)dXs, inv, dlogit, (const uint16_t*)Wr, T, k, d, E);
+  const size_t wr_bytes = (size_t)E * d * 2;
+  const int grid_l = (T + 4 * CB_TOK - 1) / (4 * CB_TOK);
+  if (E > 0 && E <= 64 && k <= 2 && wr_bytes <= 64 * 1024 && d == 2048)
+    combine_bwd_lds_kernel<4, 2><<<grid_l, 256, wr_bytes, s>>>((uint16_t*)dX, (const uint16_t*)dXs, inv, dlogit, (const uint16_t*)Wr, T, k, E);
+  else if (E > 0 && E <= 64 && k <= 2 && wr_bytes <= 64 * 1024 && d == 4096)
+    combine_bwd_lds_kernel<8, 2><<<grid_l, 256, wr_bytes, s>>>((uint16_t*)dX, (const uint16_t*)dXs, inv, dlogit, (const uint16_t*)Wr, T, k, E);
+  else
+    combine_bwd_kernel<<<(T + 3) / 4, 256, 0, s>>>((uint16_t*)dX, (const uint16_t*)dXs, inv, dlogit, (const uint16_t*)Wr, T, k, d, E);
   PQ_CHECK_LAUNCH("combine_bwd_kernel");
   return PQ_OK;
 }
