@@ -1011,7 +1011,7 @@ extern "C" int pq_decode_gemv_int8(const pq_decode_desc* d, const void* X, const
 // [decode workspace of the down stage]
 // ---------------------------------------------------------------------------------------------
 namespace {
-struct dffn_layout { size_t ws1, UG, ws2, total; };
+struct dffn_layout { size_t ws1, UG, ws2, amax, total; };
 int check_dffn(const pq_decode_ffn_desc* d) {
   PQ_REQUIRE(d != nullptr, PQ_ERR_BAD_ARG, "desc is NULL");
   PQ_REQUIRE(d->d_model > 0 && d->d_ffn > 0 && d->hp_rank > 0 && d->n_layers >= 1, PQ_ERR_BAD_ARG, "bad dimension");
@@ -1042,6 +1042,7 @@ dffn_layout make_dffn_layout(const pq_decode_ffn_desc& d) {
   L.ws1 = c.take(pq_decode_ws_layout(d1, off));
   L.UG = c.take((size_t)2 * d.n_layers * B * d.d_ffn * 2);
   L.ws2 = c.take(pq_decode_ws_layout(d2, off));
+  L.amax = c.take((size_t)d.n_layers * B * 8 * sizeof(float));   // the parts' maxima of the gated hidden state
   L.total = c.off;
   return L;
 }
@@ -1065,7 +1066,7 @@ extern "C" int pq_decode_ffn(const pq_decode_ffn_desc* d, const void* X, const u
   char* ws = (char*)workspace;
   return pq_launch_decode_ffn(d->n_layers, d->batch > 1 ? d->batch : 1, d->d_model, d->d_ffn, d->hp_rank, d->n_experts, d->top_k, d->alpha, X, packed_upgate,
                               scale_upgate, packed_down, scale_down, UpGate, Down, Wr, Y, acc_upgate, ws + L.UG, ws + L.ws1, ws + L.ws2,
-                              (hipStream_t)stream);
+                              (float*)(ws + L.amax), (hipStream_t)stream);
 }
 
 extern "C" size_t pq_pack_tiled64_bytes(int32_t N, int32_t K) {

@@ -129,11 +129,13 @@ __device__ __forceinline__ void prep_quantise(float amax, size_t tok, int K, con
   if (tid == 0) rowsum[tok] = sh.isum[0] + sh.isum[1] + sh.isum[2] + sh.isum[3];
 }
 
-// (part, parts): several workgroups may share one token; each forms gamma and the row sum for itself (cheap) but
-// writes codes and bit planes only for every parts-th group of 256 columns, and part 0 writes gamma and the row sum.
-__device__ __forceinline__ void prep_quantise_slice(float amax, size_t tok, int K, const float* xs, prep_shared& sh,
-                                              int8_t* __restrict__ xq, uint32_t* __restrict__ planes,
-                                              int* __restrict__ rowsum, float* __restrict__ gamma, int part, int parts) {
+// The quantiser for a workgroup that holds only its own column groups of a token (group gr of 256 columns belongs to part gr % parts;
+// own[256 i + c] is column 256 (part + parts i) + c): codes and bit planes of those columns, gamma by part 0, and the
+// row sum as an integer atomic add of the part's share (the caller has it zeroed by an earlier kernel of the call;
+// integer sums do not depend on the order).
+__device__ __forceinline__ void prep_quantise_own(float amax, size_t tok, int K, const float* own, prep_shared& sh,
+                                                  int8_t* __restrict__ xq, uint32_t* __restrict__ planes,
+                                                  int* __restrict__ rowsum, float* __restrict__ gamma, int part, int parts) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   amax = wave_max(amax);
   if (lane == 0) sh.red[wave] = amax;
@@ -146,21 +148,18 @@ __device__ __forceinline__ void prep_quantise_slice(float amax, size_t tok, int 
   }
   __syncthreads();
   const float g = sh.gamma;
-  // lane <-> column, a wave-wide ballot per bit plane yields two words
   int isum = 0;
-  for (int k0 = wave * 64; k0 < K; k0 += 256) {
-    const float y = __fmul_rn(xs[k0 + lane], g);
+  for (int gi = 0;; ++gi) {
+    const int k0 = (part + parts * gi) * 256 + wave * 64;
+    if (k0 >= K) break;                               // wave-uniform (K % 64 == 0)
+    const float y = __fmul_rn(own[gi * 256 + wave * 64 + lane], g);
     const float r = fminf(fmaxf(rintf(y), -128.0f), 127.0f);
     const int q = (int)r;
     isum += q;
-    if (parts > 1 && (k0 >> 8) % parts != part) continue;     // uniform: another workgroup writes these 256 columns
-    // code order inside a 32-column group follows the byte order the small-batch MFMA kernels derive
-    // from a weight word: column 8 b + t sits at byte 4 (7 - t) + b
     xq[tok * K + k0 + (lane & 32) + 4 * (7 - (lane & 7)) + ((lane & 31) >> 3)] = (int8_t)q;
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
       const unsigned long long m = __ballot(((uint32_t)q >> p) & 1u);
-      // plane words are grouped per 128 columns: [token][K/128][plane][4 words]
       if (lane < 2) {
         const int wd = (k0 >> 5) + lane;
         planes[((tok * (K / 128) + (wd >> 2)) * 8 + p) * 4 + (wd & 3)] = (uint32_t)(m >> (32 * lane));
@@ -171,7 +170,7 @@ __device__ __forceinline__ void prep_quantise_slice(float amax, size_t tok, int 
   for (int o = 32; o > 0; o >>= 1) isum += __shfl_xor(isum, o, 64);
   if (lane == 0) sh.isum[wave] = isum;
   __syncthreads();
-  if (tid == 0 && part == 0) rowsum[tok] = sh.isum[0] + sh.isum[1] + sh.isum[2] + sh.isum[3];
+  if (tid == 0) atomicAdd(&rowsum[tok], sh.isum[0] + sh.isum[1] + sh.isum[2] + sh.isum[3]);
 }
 
 // Router of one token: fp64 logits rounded once to fp32, top-k on logits (ties to the lower index), softmax
@@ -241,7 +240,7 @@ __global__ __launch_bounds__(256) void decode_prep_kernel(const uint16_t* __rest
                                                           int B, int K, int E, int topk, int8_t* __restrict__ xq,
                                                           uint32_t* __restrict__ planes, int* __restrict__ rowsum,
                                                           float* __restrict__ gamma, int* __restrict__ idx,
-                                                          float* __restrict__ gate) {
+                                                          float* __restrict__ gate, int* __restrict__ zero_rs) {
   extern __shared__ __attribute__((aligned(16))) float xs[];   // the token's activations as fp32 [K]
   __shared__ prep_shared sh;
   // two workgroups per token when there is a router: one quantises, the other routes (independent work
@@ -251,6 +250,7 @@ __global__ __launch_bounds__(256) void decode_prep_kernel(const uint16_t* __rest
   const int layer = (int)(tok / B);
   const float amax = prep_load_x(X, tok, K, xs);
   if (!split || (blockIdx.x & 1) == 0) {
+    if (zero_rs && threadIdx.x == 0) zero_rs[tok] = 0;   // a row sum that a later kernel of the call adds up with atomics
     prep_quantise(amax, tok, K, xs, sh, xq, planes, rowsum, gamma);
   } else {
     __syncthreads();                                  // xs complete
@@ -277,7 +277,7 @@ __global__ __launch_bounds__(256) void decode_prep_h_kernel(const uint16_t* __re
                                                             int parts, int8_t* __restrict__ xq, uint32_t* __restrict__ planes,
                                                             int* __restrict__ rowsum, float* __restrict__ gamma,
                                                             int* __restrict__ idx, float* __restrict__ gate,
-                                                            float* __restrict__ h) {
+                                                            float* __restrict__ h, int* __restrict__ zero_rs) {
   extern __shared__ __attribute__((aligned(16))) float xs[];
   __shared__ prep_shared sh;
   const uint16_t* __restrict__ hpA = (const uint16_t*)hpA_;
@@ -298,6 +298,7 @@ __global__ __launch_bounds__(256) void decode_prep_h_kernel(const uint16_t* __re
   const size_t tok = layer;
   const float amax = prep_load_x(X, tok, K, xs);
   if (part == 0) {
+    if (zero_rs && threadIdx.x == 0) zero_rs[tok] = 0;   // see decode_prep_kernel
     prep_quantise(amax, tok, K, xs, sh, xq, planes, rowsum, gamma);
     return;
   }
@@ -1439,46 +1440,41 @@ __global__ __launch_bounds__(256, 4) void decode_gemm16_tiled_kernel(gemm16_para
 // experts' gated unit a = silu(Gate_e x) * (Up_e x) to the hidden pairs the prep kernel left in hug [topk][2r].
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + expf(-x)); }
-// Workgroups per layer: each forms all of Hd (its maximum decides gamma) but writes codes and planes for an
-// eighth of the columns, which is the expensive part of the quantiser.
+// Workgroups per (layer, token): each owns every eighth group of 256 columns of Hd.  The row's maximum decides gamma, so
+// the work is two passes (two launches): the parts' maxima, then the quantiser of the own groups (6 KB of LDS per
+// workgroup, all workgroups of a batch resident at once); the row sum is added up over the parts with integer atomics.
 constexpr int FFN_MID_PARTS = 8;
 
-__global__ __launch_bounds__(256) void decode_ffn_mid_kernel(const uint16_t* __restrict__ UG, int B, int F, int r, int topk,
-                                                             const float* __restrict__ hug, float* __restrict__ act,
-                                                             int8_t* __restrict__ xq, uint32_t* __restrict__ planes,
-                                                             int* __restrict__ rowsum, float* __restrict__ gamma) {
-  extern __shared__ __attribute__((aligned(16))) float xs[];   // Hd as fp32 [F]
-  __shared__ prep_shared sh;
-  // row = (layer, token); U and G of a layer are two weight sets' outputs, [2 layer + {0, 1}][B][F]
+// Hd = silu(G) * U for one vector (eight columns) of a row
+__device__ __forceinline__ void ffn_hd8(const uint4& uu, const uint4& gg, float* hd) {
+  const uint32_t uw[4] = {uu.x, uu.y, uu.z, uu.w}, gw[4] = {gg.x, gg.y, gg.z, gg.w};
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    hd[2 * t] = silu_f(__uint_as_float(gw[t] << 16)) * __uint_as_float(uw[t] << 16);
+    hd[2 * t + 1] = silu_f(__uint_as_float(gw[t] & 0xFFFF0000u)) * __uint_as_float(uw[t] & 0xFFFF0000u);
+  }
+}
+
+// Pass 1 (one workgroup per (layer, token, part)): Hd over the part's own column groups, its largest magnitude to
+// amax_part[row][part]; part 0 also applies the experts' gated unit.  Thread i of a workgroup owns vector i % 32 of its
+// (i / 32)-th, (i / 32 + 8)-th, ... own group.
+__global__ __launch_bounds__(256) void decode_ffn_amax_kernel(const uint16_t* __restrict__ UG, int B, int F, int r, int topk,
+                                                              const float* __restrict__ hug, float* __restrict__ act,
+                                                              float* __restrict__ amax_part) {
+  __shared__ float red[4];
   const int row = blockIdx.x / FFN_MID_PARTS, part = blockIdx.x % FFN_MID_PARTS, tid = threadIdx.x;
   const int lay = row / B, tok = row - lay * B;
   const uint4* u4 = reinterpret_cast<const uint4*>(UG + ((size_t)(2 * lay) * B + tok) * F);
   const uint4* g4 = reinterpret_cast<const uint4*>(UG + ((size_t)(2 * lay + 1) * B + tok) * F);
+  const int nvec = F / 8;
   float amax = 0.0f;
-  for (int cb = tid; cb < F / 8; cb += 1024) {        // eight loads in flight per thread
-    uint4 uu[4], gg[4];
+  for (int gi = tid >> 5; (part + FFN_MID_PARTS * gi) * 32 < nvec; gi += 8) {
+    const int c = (part + FFN_MID_PARTS * gi) * 32 + (tid & 31);
+    if (c < nvec) {
+      float hd[8];
+      ffn_hd8(u4[c], g4[c], hd);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int cc = min(cb + 256 * i, F / 8 - 1);
-      uu[i] = u4[cc];
-      gg[i] = g4[cc];
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = cb + 256 * i;
-      if (c < F / 8) {
-        const uint32_t uw[4] = {uu[i].x, uu[i].y, uu[i].z, uu[i].w}, gw[4] = {gg[i].x, gg[i].y, gg[i].z, gg[i].w};
-        float hd[8];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          hd[2 * t] = silu_f(__uint_as_float(gw[t] << 16)) * __uint_as_float(uw[t] << 16);
-          hd[2 * t + 1] = silu_f(__uint_as_float(gw[t] & 0xFFFF0000u)) * __uint_as_float(uw[t] & 0xFFFF0000u);
-        }
-#pragma unroll
-        for (int t = 0; t < 8; ++t) amax = fmaxf(amax, fabsf(hd[t]));
-        *reinterpret_cast<float4*>(xs + 8 * c) = make_float4(hd[0], hd[1], hd[2], hd[3]);
-        *reinterpret_cast<float4*>(xs + 8 * c + 4) = make_float4(hd[4], hd[5], hd[6], hd[7]);
-      }
+      for (int t = 0; t < 8; ++t) amax = fmaxf(amax, fabsf(hd[t]));
     }
   }
   if (part == 0)
@@ -1487,14 +1483,50 @@ __global__ __launch_bounds__(256) void decode_ffn_mid_kernel(const uint16_t* __r
       const float* hp = hug + ((size_t)row * topk + j) * 2 * r;
       act[(size_t)row * topk * r + o] = silu_f(hp[r + i]) * hp[i];
     }
+  amax = wave_max(amax);
+  if ((tid & 63) == 0) red[tid >> 6] = amax;
+  __syncthreads();
+  if (tid == 0) amax_part[(size_t)row * FFN_MID_PARTS + part] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+// Pass 2: the row's maximum from the eight parts, then the part's own column groups again (from cache) through the
+// quantiser: codes, bit planes, gamma by part 0, the row sum by integer atomics.
+__global__ __launch_bounds__(256) void decode_ffn_mid_kernel(const uint16_t* __restrict__ UG, int B, int F,
+                                                             const float* __restrict__ amax_part,
+                                                             int8_t* __restrict__ xq, uint32_t* __restrict__ planes,
+                                                             int* __restrict__ rowsum, float* __restrict__ gamma) {
+  extern __shared__ __attribute__((aligned(16))) float xs[];   // this part's column groups of Hd as fp32
+  __shared__ prep_shared sh;
+  // row = (layer, token); U and G of a layer are two weight sets' outputs, [2 layer + {0, 1}][B][F]
+  const int row = blockIdx.x / FFN_MID_PARTS, part = blockIdx.x % FFN_MID_PARTS, tid = threadIdx.x;
+  const int lay = row / B, tok = row - lay * B;
+  const uint4* u4 = reinterpret_cast<const uint4*>(UG + ((size_t)(2 * lay) * B + tok) * F);
+  const uint4* g4 = reinterpret_cast<const uint4*>(UG + ((size_t)(2 * lay + 1) * B + tok) * F);
+  const int nvec = F / 8;
+  float amax = 0.0f;
+#pragma unroll
+  for (int q = 0; q < FFN_MID_PARTS; ++q) amax = fmaxf(amax, amax_part[(size_t)row * FFN_MID_PARTS + q]);
+  for (int gi = tid >> 5; (part + FFN_MID_PARTS * gi) * 32 < nvec; gi += 8) {
+    const int c = (part + FFN_MID_PARTS * gi) * 32 + (tid & 31);
+    float hd[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (c < nvec) ffn_hd8(u4[c], g4[c], hd);
+    float* dst = xs + gi * 256 + 8 * (tid & 31);
+    *reinterpret_cast<float4*>(dst) = make_float4(hd[0], hd[1], hd[2], hd[3]);
+    *reinterpret_cast<float4*>(dst + 4) = make_float4(hd[4], hd[5], hd[6], hd[7]);
+  }
   __syncthreads();                                    // xs complete
-  prep_quantise_slice(amax, (size_t)row, F, xs, sh, xq, planes, rowsum, gamma, part, FFN_MID_PARTS);
+  prep_quantise_own(amax, (size_t)row, F, xs, sh, xq, planes, rowsum, gamma, part, FFN_MID_PARTS);
 }
 
 }  // namespace
 
 // The per-token kernels stage one token as fp32 (plus its codes for INT8 experts) in dynamic LDS next to a small
 // static block: above 64 KB in total the launch needs the limit raised once per process.
+static size_t ffn_mid_lds_bytes(int F) {
+  const int groups = (F + 255) / 256;
+  return (size_t)((groups + FFN_MID_PARTS - 1) / FFN_MID_PARTS) * 256 * sizeof(float);
+}
+
 static int decode_raise_lds_limits() {
   static std::once_flag once;
   static int rc = PQ_OK;
@@ -1537,7 +1569,7 @@ static int decode_set_gemm16_limits() {
 static int launch_decode_ffn_batch(int L, int B, int D, int F, int r, int E, int topk, float alpha, const void* X,
                                    const uint32_t* packed_upgate, const uint16_t* scale_upgate, const uint32_t* packed_down,
                                    const uint16_t* scale_down, const void* UpGate, const void* Down, const void* Wr, void* Y,
-                                   int32_t* acc_upgate, void* UG, void* ws1, void* ws2, hipStream_t s) {
+                                   int32_t* acc_upgate, void* UG, void* ws1, void* ws2, float* amax_part, hipStream_t s) {
   if (int e = decode_set_gemm16_limits()) return e;
   pq_decode_desc d1{B, D, F, 2 * r, E, topk, L, PQ_PACKED_TILED64, alpha};
   pq_decode_desc d2{B, F, D, r, E, topk, L, PQ_PACKED_TILED64, alpha};
@@ -1554,7 +1586,7 @@ static int launch_decode_ffn_batch(int L, int B, int D, int F, int r, int E, int
   {
     pq_prof_scope prof(PQP_DECODE_PREP, s);
     decode_prep_kernel<<<L * B * 2, 256, (size_t)D * sizeof(float), s>>>((const uint16_t*)X, (const uint16_t*)Wr, B, D, E, topk, xq1, pl1, rs1,
-                                                                        gm1, idx, gate);
+                                                                        gm1, idx, gate, rs2);
     PQ_CHECK_LAUNCH("decode_prep_kernel");
   }
   {  // hidden pairs [Up_e x ; Gate_e x] of every (token, selected expert)
@@ -1576,8 +1608,9 @@ static int launch_decode_ffn_batch(int L, int B, int D, int F, int r, int E, int
   }
   {
     pq_prof_scope prof(PQP_SWIGLU, s);
-    decode_ffn_mid_kernel<<<L * B * FFN_MID_PARTS, 256, (size_t)F * sizeof(float), s>>>((const uint16_t*)UG, B, F, r, topk, hug, act, xq2, pl2,
-                                                                                       rs2, gm2);
+    decode_ffn_amax_kernel<<<L * B * FFN_MID_PARTS, 256, 0, s>>>((const uint16_t*)UG, B, F, r, topk, hug, act, amax_part);
+    PQ_CHECK_LAUNCH("decode_ffn_amax_kernel");
+    decode_ffn_mid_kernel<<<L * B * FFN_MID_PARTS, 256, ffn_mid_lds_bytes(F), s>>>((const uint16_t*)UG, B, F, amax_part, xq2, pl2, rs2, gm2);
     PQ_CHECK_LAUNCH("decode_ffn_mid_kernel");
   }
   {  // down product + experts' down projections
@@ -1597,11 +1630,11 @@ static int launch_decode_ffn_batch(int L, int B, int D, int F, int r, int E, int
 int pq_launch_decode_ffn(int L, int B, int D, int F, int r, int E, int topk, float alpha, const void* X, const uint32_t* packed_upgate,
                          const uint16_t* scale_upgate, const uint32_t* packed_down, const uint16_t* scale_down,
                          const void* UpGate, const void* Down, const void* Wr, void* Y, int32_t* acc_upgate, void* UG,
-                         void* ws1, void* ws2, hipStream_t s) {
+                         void* ws1, void* ws2, float* amax_part, hipStream_t s) {
   if (int e = decode_raise_lds_limits()) return e;
   if (B > 1)
     return launch_decode_ffn_batch(L, B, D, F, r, E, topk, alpha, X, packed_upgate, scale_upgate, packed_down, scale_down, UpGate, Down, Wr,
-                                   Y, acc_upgate, UG, ws1, ws2, s);
+                                   Y, acc_upgate, UG, ws1, ws2, amax_part, s);
   pq_decode_desc d1{1, D, F, 2 * r, E, topk, L, PQ_PACKED_TILED64, alpha};
   pq_decode_desc d2{1, F, D, r, E, topk, L, PQ_PACKED_TILED64, alpha};
   size_t o1[7], o2[7];
@@ -1617,7 +1650,7 @@ int pq_launch_decode_ffn(int L, int B, int D, int F, int r, int E, int topk, flo
     pq_prof_scope prof(PQP_DECODE_PREP, s);
     const int parts = 1 + (topk * 2 * r + PREP_H_ROWS - 1) / PREP_H_ROWS;
     decode_prep_h_kernel<false><<<L * parts, 256, (size_t)D * sizeof(float), s>>>((const uint16_t*)X, (const uint16_t*)Wr, UpGate, nullptr, D, E,
-                                                                                 2 * r, topk, parts, xq1, pl1, rs1, gm1, idx, gate, hug);
+                                                                                 2 * r, topk, parts, xq1, pl1, rs1, gm1, idx, gate, hug, rs2);
     PQ_CHECK_LAUNCH("decode_prep_h_kernel");
   }
   {  // U and G: 2 L weight sets, each pair reading its layer's token once quantised
@@ -1630,7 +1663,9 @@ int pq_launch_decode_ffn(int L, int B, int D, int F, int r, int E, int topk, flo
   }
   {  // gated unit, quantiser of Hd, experts' gated unit
     pq_prof_scope prof(PQP_SWIGLU, s);
-    decode_ffn_mid_kernel<<<L * FFN_MID_PARTS, 256, (size_t)F * sizeof(float), s>>>((const uint16_t*)UG, 1, F, r, topk, hug, act, xq2, pl2, rs2, gm2);
+    decode_ffn_amax_kernel<<<L * FFN_MID_PARTS, 256, 0, s>>>((const uint16_t*)UG, 1, F, r, topk, hug, act, amax_part);
+    PQ_CHECK_LAUNCH("decode_ffn_amax_kernel");
+    decode_ffn_mid_kernel<<<L * FFN_MID_PARTS, 256, ffn_mid_lds_bytes(F), s>>>((const uint16_t*)UG, 1, F, amax_part, xq2, pl2, rs2, gm2);
     PQ_CHECK_LAUNCH("decode_ffn_mid_kernel");
   }
   {  // down product + experts' down projections
@@ -1680,17 +1715,17 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
     const int parts = 1 + (d.top_k * r + PREP_H_ROWS - 1) / PREP_H_ROWS;
     if (i8)
       decode_prep_h_kernel<true><<<L * parts, 256, (size_t)K * 5, s>>>((const uint16_t*)X, (const uint16_t*)Wr, hpA, gA, K, E, r, d.top_k,
-                                                                      parts, xq, planes, rowsum, gamma, idx, gate, h);
+                                                                      parts, xq, planes, rowsum, gamma, idx, gate, h, nullptr);
     else
       decode_prep_h_kernel<false><<<L * parts, 256, (size_t)K * sizeof(float), s>>>((const uint16_t*)X, (const uint16_t*)Wr, hpA, nullptr,
                                                                                    K, E, r, d.top_k, parts, xq, planes, rowsum, gamma,
-                                                                                   idx, gate, h);
+                                                                                   idx, gate, h, nullptr);
     PQ_CHECK_LAUNCH("decode_prep_h_kernel");
   } else {
     {
       pq_prof_scope prof(PQP_DECODE_PREP, s);
       decode_prep_kernel<<<L * B * (E > 0 ? 2 : 1), 256, (size_t)K * sizeof(float), s>>>((const uint16_t*)X, (const uint16_t*)Wr, B, K, E, d.top_k, xq,
-                                                                      planes, rowsum, gamma, idx, gate);
+                                                                      planes, rowsum, gamma, idx, gate, nullptr);
       PQ_CHECK_LAUNCH("decode_prep_kernel");
     }
     if (r > 0) {

@@ -186,7 +186,7 @@ int pq_launch_retile64(const uint32_t* packed, int N, int K, uint32_t* tiled, hi
 int pq_launch_decode_ffn(int L, int B, int D, int F, int r, int E, int topk, float alpha, const void* X, const uint32_t* packed_upgate,
                          const uint16_t* scale_upgate, const uint32_t* packed_down, const uint16_t* scale_down,
                          const void* UpGate, const void* Down, const void* Wr, void* Y, int32_t* acc_upgate, void* UG,
-                         void* ws1, void* ws2, hipStream_t s);
+                         void* ws1, void* ws2, float* amax_part, hipStream_t s);   // amax_part: [L][B][8] floats of scratch
 
 // ---- pq_moe.hip ---------------------------------------------------------------------------
 int pq_launch_route(const int* idx, int S, int E, int* counts, int* offsets, int* perm, int* inv, hipStream_t s);
