@@ -72,6 +72,8 @@ def test_decode_gemv_batch1(L, B, K, N, E, r, k, tiled):
 
 
 @pytest.mark.parametrize("L,B,K,N,E,r,k", [(1, 3, 512, 200, 4, 32, 2), (2, 8, 1024, 1028, 8, 64, 2), (1, 16, 512, 64, 2, 32, 1),
+                                           # widths 2048 and 512 of the expert-by-expert hidden-state kernel; 128 slots per layer (per-slot kernel)
+                                           (2, 5, 2048, 264, 8, 64, 2), (1, 16, 512, 64, 8, 32, 8),
                                            (1, 2, 4096, 300, 1, 0, 1), (1, 5, 1536, 520, 8, 32, 3)])
 @pytest.mark.parametrize("tiled", [False, True])
 def test_decode_small_batch(L, B, K, N, E, r, k, tiled):
