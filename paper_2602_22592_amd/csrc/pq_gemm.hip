@@ -579,7 +579,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void mfma_gemm_kernel(int M, int N,
   // needs, instead of being requested after it (a chain of four memory latencies in front of 64 MFMAs per wavefront).
   // Tile j goes to ring stage (pf2_s0 + j) mod 4.
   bool pf2 = false;                                  // uniform
-  const int pf2_s0 = nkt & 3;
+  [[maybe_unused]] const int pf2_s0 = nkt & 3;
   if constexpr (DTL && BBITS && AK2 == PQ_SRC_KC16 && (BK2 == PQ_SRC_KC16 || BK2 == PQ_SRC_KS16)) {
 #ifndef PQ_NO_PF2
     pf2 = ph2.K2 > 0 && ph2.K2 <= 128 && ph2.K2 % 64 == 0 && nkt >= 4 && ((uintptr_t)ph2.A2.p % 16) == 0 && (ph2.A2.ld * 2) % 16 == 0 &&
