@@ -256,6 +256,13 @@ typedef struct pq_ffn_desc {
 } pq_ffn_desc;
 size_t pq_ffn_ctx_bytes(const pq_ffn_desc* desc);
 size_t pq_ffn_workspace_bytes(const pq_ffn_desc* desc);
+/* Where pq_ffn_fwd leaves the intermediate results it stores in ctx (byte offset and size of a section; rows of U, G and
+ * Hq are d_ffn rounded up to a multiple of 32 long): the codes and gammas of x (Sec. 3.1 quantiser), U and G (bf16), the
+ * codes and gammas of the gated hidden state Hd.  For inspection; the layout is otherwise the library's own. */
+typedef enum pq_ffn_ctx_section_id {
+  PQ_FFN_CTX_XQ = 0, PQ_FFN_CTX_GAMMA_X = 1, PQ_FFN_CTX_U = 2, PQ_FFN_CTX_G = 3, PQ_FFN_CTX_HQ = 4, PQ_FFN_CTX_GAMMA_H = 5
+} pq_ffn_ctx_section_id;
+int pq_ffn_ctx_section(const pq_ffn_desc* desc, int32_t section, size_t* offset, size_t* bytes);
 int pq_ffn_fwd(const pq_ffn_desc* desc, const void* X, const void* W_up, const void* W_gate, const void* W_down,
                const void* Up, const void* Gate, const void* Down, const void* Wr, void* Y, void* ctx,
                size_t ctx_bytes, void* workspace, size_t workspace_bytes, void* stream);

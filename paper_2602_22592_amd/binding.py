@@ -30,7 +30,7 @@ EXPORTS = [
     "pq_linear_norm_ctx_bytes", "pq_linear_norm_workspace_bytes", "pq_linear_norm_fwd", "pq_linear_norm_bwd",
     "pq_hp_int8_ctx_bytes", "pq_hp_int8_workspace_bytes", "pq_hp_int8_fwd", "pq_hp_int8_bwd", "pq_decode_gemv_int8",
     "pq_decode_ffn_workspace_bytes", "pq_decode_ffn", "pq_rmsnorm_bwd_static_max_bytes", "pq_rmsnorm_bwd_static",
-    "pq_groupwise_workspace_bytes", "pq_groupwise_fwd",
+    "pq_groupwise_workspace_bytes", "pq_groupwise_fwd", "pq_ffn_ctx_section",
 ]
 
 
@@ -414,6 +414,16 @@ class FFNBuffers:
             raise PQError(f"bad FFN descriptor: {lib().pq_last_error_string().decode()}")
         self.ctx = _bytes(nctx, device)
         self.ws = ws if ws is not None else _bytes(nws, device)
+
+
+FFN_CTX_XQ, FFN_CTX_GAMMA_X, FFN_CTX_U, FFN_CTX_G, FFN_CTX_HQ, FFN_CTX_GAMMA_H = range(6)
+
+
+def ffn_ctx_section(desc, bufs, section):
+    """The bytes of one stored intermediate of pq_ffn_fwd inside bufs.ctx (a uint8 view)."""
+    off, n = C.c_size_t(0), C.c_size_t(0)
+    _check(lib().pq_ffn_ctx_section(C.byref(desc), int(section), C.byref(off), C.byref(n)))
+    return bufs.ctx[off.value:off.value + n.value]
 
 
 def ffn_fwd(desc, X, W_up, W_gate, W_down, Up, Gate, Down, Wr, Y, bufs):

@@ -139,6 +139,24 @@ extern "C" size_t pq_ffn_ctx_bytes(const pq_ffn_desc* d) {
   if (check_ffn(d) != PQ_OK) return 0;
   return make_layout(*d).ctx_total;
 }
+// Where pq_ffn_fwd leaves what it stores in ctx (for inspection: tests compare the stored codes with the oracle's).
+extern "C" int pq_ffn_ctx_section(const pq_ffn_desc* d, int32_t section, size_t* offset, size_t* bytes) {
+  if (int e = check_ffn(d)) return e;
+  PQ_REQUIRE(offset && bytes, PQ_ERR_BAD_ARG, "NULL result pointer");
+  const ffn_layout L = make_layout(*d);
+  const size_t T = d->tokens, D = d->d_model, F = ((size_t)d->d_ffn + 31) / 32 * 32;
+  switch (section) {
+    case PQ_FFN_CTX_XQ: *offset = L.Xq; *bytes = T * D; break;
+    case PQ_FFN_CTX_GAMMA_X: *offset = L.gx; *bytes = T * 4; break;
+    case PQ_FFN_CTX_U: *offset = L.U; *bytes = T * F * 2; break;
+    case PQ_FFN_CTX_G: *offset = L.G; *bytes = T * F * 2; break;
+    case PQ_FFN_CTX_HQ: *offset = L.Hq; *bytes = T * F; break;
+    case PQ_FFN_CTX_GAMMA_H: *offset = L.gh; *bytes = T * 4; break;
+    default: return pq_set_error(PQ_ERR_BAD_ARG, "unknown ctx section %d", section);
+  }
+  return PQ_OK;
+}
+
 extern "C" size_t pq_ffn_workspace_bytes(const pq_ffn_desc* d) {
   if (check_ffn(d) != PQ_OK) return 0;
   return make_layout(*d).ws_total;

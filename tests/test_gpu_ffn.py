@@ -71,6 +71,42 @@ def test_ffn_small(T, D, F, E, r, k):
     check_ffn(wl.ffn_case(80 + T + k, T, D, F, E, r), top_k=k)
 
 
+@pytest.mark.parametrize("T,D,F,E,r", [(300, 256, 544, 4, 32), (130, 256, 500, 2, 32)])
+def test_ffn_stored_intermediates_at_code_level(T, D, F, E, r):
+    """What pq_ffn_fwd stores for the backward, compared with the oracle piece by piece: the codes and gammas of x bit for
+    bit; U and G to one bf16 rounding; the codes of the gated hidden state Hd = silu(G) U to one step (the kernel forms
+    Hd in fp32 with the hardware exponential and reciprocal, the oracle in fp64, so a value next to a rounding boundary
+    may land on the neighbouring code) on a small share of the entries, and its gammas to 1e-3; the padded columns of a
+    width that is not a multiple of 32 hold zero codes."""
+    print(f"ffn stored intermediates T={T} D={D} F={F} E={E} r={r}", flush=True)
+    c = wl.ffn_case(2600 + F, T, D, F, E, r)
+    desc = pq.FFNDesc(T, D, F, r, E, 1, pq.PQ_BF16, 2.0, 0.2, pq.PQ_HP_LOWRANK_BF16)
+    bufs = pq.FFNBuffers(desc)
+    t = {k: dev(c[k]) for k in ("X", "W_up", "W_gate", "W_down", "Up", "Gate", "Down", "Wr")}
+    Y = torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
+    pq.ffn_fwd(desc, t["X"], t["W_up"], t["W_gate"], t["W_down"], t["Up"], t["Gate"], t["Down"], t["Wr"], Y, bufs)
+    torch.cuda.synchronize()
+    f = po.ffn_fwd(c["X"], c["W_up"], c["W_gate"], c["W_down"], c["Up"], c["Gate"], c["Down"], c["Wr"], 2.0, 0.2, top_k=1, bf16=True)
+    Fp = (F + 31) // 32 * 32
+    sec = lambda which: pq.ffn_ctx_section(desc, bufs, which)
+    xq = sec(pq.FFN_CTX_XQ).view(torch.int8).view(T, D).cpu().numpy()
+    gx = sec(pq.FFN_CTX_GAMMA_X).view(torch.float32).cpu().numpy()
+    assert np.array_equal(xq, f["q"]) and np.array_equal(gx, f["gamma"])
+    for name, which in (("U", pq.FFN_CTX_U), ("G", pq.FFN_CTX_G)):
+        got = sec(which).view(torch.bfloat16).view(T, Fp)[:, :F].float().cpu().numpy().astype(np.float64)
+        ref = np.asarray(f[name], np.float64)
+        assert np.all(np.abs(got - ref) <= 2.0 ** -7 * np.abs(ref) + 1e-30), name      # one bf16 rounding
+        assert np.mean(got != ref) < 0.02, name
+    hq = sec(pq.FFN_CTX_HQ).view(torch.int8).view(T, Fp).cpu().numpy().astype(np.int64)
+    gh = sec(pq.FFN_CTX_GAMMA_H).view(torch.float32).cpu().numpy().astype(np.float64)
+    assert np.all(hq[:, F:] == 0)
+    d = np.abs(hq[:, :F] - f["qh"].astype(np.int64))
+    share = float(np.mean(d != 0))
+    print(f"  Hd codes: largest difference {d.max()}, share of entries that differ {share:.4f}", flush=True)
+    assert d.max() <= 1 and share < 0.05
+    assert np.abs(gh - f["gamma_h"].astype(np.float64)).max() <= 1e-3 * np.abs(f["gamma_h"]).max()
+
+
 def test_ffn_scale_edge_cases():
     c = wl.ffn_case(90, 150, 64, 96, 4, 8)
     check_ffn(c, alpha=0.0, beta=0.7)
