@@ -316,6 +316,33 @@ def hp_int8_bench(pq, torch, T=8192, K=2048, N=2048, r=128, steps=100, warmup=20
             "kernels_us": {k: round(1e3 * ms / n, 2) for k, (ms, n) in sorted(prof.items())}}
 
 
+def fp32_io_bench(pq, torch, c, steps=5, warmup=2):
+    """The config-2 step with fp32 activations and gradients: every GEMM except the int8 one runs on the fp64 matrix
+    instructions (the path the tight-tolerance parity tests use).  Reported so that its cost is known; fp64 MFMA peak
+    78.6 TFLOP/s."""
+    T, K, N, r = c["tokens"], c["d_in"], c["d_out"], c["hp_rank"]
+    to = lambda x: torch.from_numpy(x).cuda().float()
+    X, W, dY, A, B = to(c["X"]), to(c["W"]), to(c["dY"]), to(c["A"]), to(c["B"])
+    desc = pq.make_desc(T, K, N, hp_rank=r, io_dtype=pq.PQ_F32, alpha=c["alpha"], beta=c["beta"])
+    bufs = pq.LinearBuffers(desc)
+    f32 = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
+    Y, dX, dW, dA, dB, dab = f32(T, N), f32(T, K), f32(N, K), f32(r, K), f32(N, r), f32(2)
+
+    def step():
+        pq.linear_fwd(desc, X, W, Y, bufs, A=A, B=B)
+        pq.linear_bwd(desc, dY, X, W, bufs, dX, dW, dab, A=A, B=B, dA=dA, dB=dB)
+
+    ms = _time_steps(torch, step, steps, warmup)
+    prof = _profile_steps(pq, torch, step, steps)
+    k_us = {k: round(1e3 * t / n, 1) for k, (t, n) in sorted(prof.items())}
+    big = 2.0 * T * K * N
+    return {"workload": "tokens=%d, d_in=%d, d_out=%d, r=%d, fp32 I/O, fwd+bwd" % (T, K, N, r), "ms_per_step": round(ms, 3),
+            "tokens_per_s": round(T / (ms * 1e-3), 1),
+            "gemm_dX_fp64_TFLOPs": round(big / (k_us["gemm_dX"] * 1e-6) / 1e12, 1) if "gemm_dX" in k_us else None,
+            "gemm_dW_fp64_TFLOPs": round(big / (k_us["gemm_dW"] * 1e-6) / 1e12, 1) if "gemm_dW" in k_us else None,
+            "kernels_us": k_us}
+
+
 def ffn_bench(pq, torch, T=8192, D=2048, F=5504, E=8, r=32, steps=20, warmup=5, int8_experts=False):
     """Config 3: the 1.3B-shaped decoupled FFN (three 1-bit projections + E=8 top-1 experts of width 32), fwd+bwd.
     With F=5076, r=384 and E in {1, 2, 4, 8} it is the paper's own 1.3B FFN (Table 1) and its branch sweep (Sec. 4.4)."""
@@ -450,6 +477,7 @@ def main():
     ap.add_argument("--no-stack", action="store_true")
     ap.add_argument("--no-norm", action="store_true")
     ap.add_argument("--no-hp8", action="store_true")
+    ap.add_argument("--no-fp32-io", action="store_true", help="skip the fp32 I/O step at the config-2 shape (fp64 matrix instructions)")
     ap.add_argument("--no-groupwise", action="store_true", help="skip the group-wise(64) scale contrast (Sec. 4.6)")
     ap.add_argument("--no-vendor-context", action="store_true", help="skip the vendor-library GEMM timings (context only)")
     ap.add_argument("--no-paper-ffn", action="store_true", help="skip the paper-exact 1.3B FFN (Table 1) and its branch sweep")
@@ -585,6 +613,8 @@ def main():
         section("groupwise_contrast", lambda: groupwise_contrast(pq, torch, X, W))
     if not args.no_hp8:
         section("hp_int8_branch", lambda: hp_int8_bench(pq, torch))
+    if not args.no_fp32_io and not args.calibrate:
+        section("fp32_io_config2_shape", lambda: fp32_io_bench(pq, torch, c))
     if not args.no_ffn:
         section("ffn_config3", lambda: ffn_bench(pq, torch))
         # the same FFN with its experts in the INT8 form of the FFN equation (Sec. 3.2)

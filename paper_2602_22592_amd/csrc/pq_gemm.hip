@@ -1,5 +1,5 @@
 // Tiled MFMA GEMM for gfx950 with pluggable operand sources and epilogues, plus a
-// reference-precision engine (fp64 accumulate) used for fp32 I/O.
+// reference-precision engine (fp64 products and sums on the fp64 matrix instruction) used for fp32 I/O.
 //
 //   C[m][n] (+)= epilogue( sum_k A(m,k) * B(n,k) )
 //
@@ -1347,38 +1347,139 @@ __global__ __launch_bounds__(256) void splitk_reduce_pair_kernel(int splits, int
 }
 
 // ---------------------------------------------------------------------------------------------
-// Reference-precision engine: one thread per output element, fp64 accumulation, any source kind.
+// Reference-precision engine (fp32 I/O): any source kind, products and sums in fp64 on the matrix pipe
+// (v_mfma_f64_16x16x4_f64).  A workgroup owns a 128x128 tile, a wavefront 64x64 of it; sixteen contraction
+// indices of both operands are converted to fp64 on the way into LDS ([k][row], row stride 129 doubles).
 // ---------------------------------------------------------------------------------------------
+template <int KIND>
 __device__ __forceinline__ double ref_elem(const pq_operand& op, int row, int k) {
-  double v;
-  switch (op.kind) {
-    case PQ_SRC_KC32: v = ((const float*)op.p)[(size_t)row * op.ld + k]; break;
-    case PQ_SRC_KS32: v = ((const float*)op.p)[(size_t)k * op.ld + row]; break;
-    case PQ_SRC_KC16: v = bf16_to_f32(((const uint16_t*)op.p)[(size_t)row * op.ld + k]); break;
-    case PQ_SRC_KS16: v = bf16_to_f32(((const uint16_t*)op.p)[(size_t)k * op.ld + row]); break;
-    case PQ_SRC_KC8: v = ((const int8_t*)op.p)[(size_t)row * op.ld + k]; break;
-    case PQ_SRC_KS8: v = ((const int8_t*)op.p)[(size_t)k * op.ld + row]; break;
-    default: {
-      const uint32_t byte = ((const uint8_t*)op.p)[(size_t)row * op.ld + (k >> 3)];
-      v = ((byte >> (k & 7)) & 1u) ? 1.0 : -1.0;
-    }
+  if constexpr (KIND == PQ_SRC_KC32) return ((const float*)op.p)[(size_t)row * op.ld + k];
+  else if constexpr (KIND == PQ_SRC_KS32) return ((const float*)op.p)[(size_t)k * op.ld + row];
+  else if constexpr (KIND == PQ_SRC_KC16) return bf16_to_f32(((const uint16_t*)op.p)[(size_t)row * op.ld + k]);
+  else if constexpr (KIND == PQ_SRC_KS16) return bf16_to_f32(((const uint16_t*)op.p)[(size_t)k * op.ld + row]);
+  else if constexpr (KIND == PQ_SRC_KC8) return ((const int8_t*)op.p)[(size_t)row * op.ld + k];
+  else if constexpr (KIND == PQ_SRC_KS8) return ((const int8_t*)op.p)[(size_t)k * op.ld + row];
+  else {                                                // packed bits: one bit per weight, set = +1
+    const uint32_t byte = ((const uint8_t*)op.p)[(size_t)row * op.ld + (k >> 3)];
+    return ((byte >> (k & 7)) & 1u) ? 1.0 : -1.0;
   }
-  if (op.kdiv) v /= (double)op.kdiv[k];
-  return v;
 }
 
-__global__ __launch_bounds__(256) void ref_gemm_kernel(int M, int N, int K, pq_operand A, pq_operand B,
-                                                       pq_epilogue epi) {
+constexpr int REF_KB = 16;
+// 128x128 tiles, or 64x64 when those would leave half of the compute units without one
+static int ref_tile(int M, int N) { return (long)((M + 127) / 128) * ((N + 127) / 128) < 128 ? 64 : 128; }
+
+// Sixteen contraction indices of TILE rows, fetched into registers (rows and indices past the end become zeros) and
+// later written to LDS as [k][row].  Sources whose rows are contiguous in memory are read with the row index fastest
+// over the lanes, the others with the contraction index.
+template <int TILE>
+struct ref_stage {
+  static constexpr int PER = TILE / 16, LD = TILE + 1;
+  double v[PER];
+  __device__ __forceinline__ static void where(bool rows_fastest, int j, int& kk, int& rl) {
+    const int tid = threadIdx.x;
+    kk = rows_fastest ? tid / TILE + (256 / TILE) * j : (tid & 15);
+    rl = rows_fastest ? tid % TILE : (tid >> 4) + 16 * j;
+  }
+  // All loads of a step are issued back to back (addresses clamped into the matrix, the kind decided once), so a
+  // step waits for one memory latency and not for one per element.
+  template <int KIND>
+  __device__ __forceinline__ void fetch_kind(const pq_operand& op, int row0, int rows, int k0, int K) {
+    constexpr bool rows_fastest = KIND == PQ_SRC_KS32 || KIND == PQ_SRC_KS16 || KIND == PQ_SRC_KS8;
+    double d[PER];
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      int kk, rl;
+      where(rows_fastest, j, kk, rl);
+      v[j] = ref_elem<KIND>(op, min(row0 + rl, rows - 1), min(k0 + kk, K - 1));
+      d[j] = op.kdiv ? (double)op.kdiv[min(k0 + kk, K - 1)] : 1.0;
+    }
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      int kk, rl;
+      where(rows_fastest, j, kk, rl);
+      if (op.kdiv) v[j] /= d[j];
+      if (row0 + rl >= rows || k0 + kk >= K) v[j] = 0.0;
+    }
+  }
+  __device__ __forceinline__ void fetch(const pq_operand& op, int row0, int rows, int k0, int K) {
+    switch (op.kind) {                                  // uniform
+      case PQ_SRC_KC32: fetch_kind<PQ_SRC_KC32>(op, row0, rows, k0, K); break;
+      case PQ_SRC_KS32: fetch_kind<PQ_SRC_KS32>(op, row0, rows, k0, K); break;
+      case PQ_SRC_KC16: fetch_kind<PQ_SRC_KC16>(op, row0, rows, k0, K); break;
+      case PQ_SRC_KS16: fetch_kind<PQ_SRC_KS16>(op, row0, rows, k0, K); break;
+      case PQ_SRC_KC8: fetch_kind<PQ_SRC_KC8>(op, row0, rows, k0, K); break;
+      case PQ_SRC_KS8: fetch_kind<PQ_SRC_KS8>(op, row0, rows, k0, K); break;
+      default: fetch_kind<PQ_SRC_BITSF>(op, row0, rows, k0, K);   // packed bits, whatever the engine they were declared for
+    }
+  }
+  __device__ __forceinline__ void store(const pq_operand& op, double* dst) const {
+    const bool rows_fastest = op.kind == PQ_SRC_KS32 || op.kind == PQ_SRC_KS16 || op.kind == PQ_SRC_KS8;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      int kk, rl;
+      where(rows_fastest, j, kk, rl);
+      dst[kk * LD + rl] = v[j];
+    }
+  }
+};
+
+template <int TILE>
+__global__ __launch_bounds__(256) void ref_gemm_kernel(int M, int N, int K, pq_operand A, pq_operand B, pq_epilogue epi) {
+  typedef double f64x4_t __attribute__((ext_vector_type(4)));
+  constexpr int LD = TILE + 1, WT = TILE / 2, NB = WT / 16;   // a wavefront owns WT x WT: NB x NB blocks of 16x16
+  __shared__ double As[REF_KB * LD], Bs[REF_KB * LD];
   __shared__ double red[4];
-  const int n = blockIdx.x * 16 + (threadIdx.x & 15);
-  const int m = blockIdx.y * 16 + (threadIdx.x >> 4);
+  const int m0 = blockIdx.y * TILE, n0 = blockIdx.x * TILE;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = (wave >> 1) * WT, wn = (wave & 1) * WT;
+  const int li = lane & 15, lk = lane >> 4;
+  f64x4_t acc[NB][NB];
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j) acc[i][j] = f64x4_t{0.0, 0.0, 0.0, 0.0};
+  ref_stage<TILE> ra, rb;
+  if (K > 0) {
+    ra.fetch(A, m0, M, 0, K);
+    rb.fetch(B, n0, N, 0, K);
+  }
+  for (int k0 = 0; k0 < K; k0 += REF_KB) {
+    ra.store(A, As);
+    rb.store(B, Bs);
+    __syncthreads();
+    if (k0 + REF_KB < K) {                               // the next step's elements travel while this one multiplies
+      ra.fetch(A, m0, M, k0 + REF_KB, K);
+      rb.fetch(B, n0, N, k0 + REF_KB, K);
+    }
+#pragma unroll
+    for (int kk = 0; kk < REF_KB; kk += 4) {
+      // operand layout of the instruction: lane (li, lk) holds element (row li, contraction index lk) of either side
+      double a[NB], b[NB];
+#pragma unroll
+      for (int i = 0; i < NB; ++i) a[i] = As[(kk + lk) * LD + wm + 16 * i + li];
+#pragma unroll
+      for (int j = 0; j < NB; ++j) b[j] = Bs[(kk + lk) * LD + wn + 16 * j + li];
+#pragma unroll
+      for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
   epi_state st;
   epi_begin(epi, st);
-  if (m < M && n < N) {
-    double acc = 0.0;
-    for (int k = 0; k < K; ++k) acc += ref_elem(A, m, k) * ref_elem(B, n, k);
-    epi_elem<double>(epi, st, m, n, acc, (int)acc);
-  }
+  // result layout: register v of lane (li, lk) is element (row lk + 4 v, column li) of the 16x16 block
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int m = m0 + wm + 16 * i + lk + 4 * v, n = n0 + wn + 16 * j + li;
+        const double c = acc[i][j][v];
+        if (m < M && n < N) epi_elem<double>(epi, st, m, n, c, (int)c);
+      }
   epi_end<256>(epi, st, red, blockIdx.y * gridDim.x + blockIdx.x);
 }
 
@@ -2070,9 +2171,9 @@ pq_gemm_plan pq_plan_gemm(int engine, int M, int N, int K, bool int8, bool split
   memset(&pl, 0, sizeof(pl));
   pl.splits = 1;
   if (engine == 1) {
-    pl.bm = pl.bn = 16;
+    pl.bm = pl.bn = ref_tile(M, N);
     pl.kchunk = K;
-    pl.red_blocks = ((M + 15) / 16) * ((N + 15) / 16);
+    pl.red_blocks = ((M + pl.bm - 1) / pl.bm) * ((N + pl.bn - 1) / pl.bn);
     return pl;
   }
   const bool big = (M >= 256 && N >= 256);
@@ -2207,8 +2308,10 @@ int pq_launch_gemm(int engine, int M, int N, int K, const pq_operand& A, const p
     return pq_launch_skinny(M, K, A, B, epi, s, prof_label);
   if (engine == 1) {
     pq_prof_scope prof(prof_label, s);
-    dim3 grid((N + 15) / 16, (M + 15) / 16), block(256);
-    ref_gemm_kernel<<<grid, block, 0, s>>>(M, N, K, A, B, epi);
+    const int tile = ref_tile(M, N);
+    dim3 grid((N + tile - 1) / tile, (M + tile - 1) / tile), block(256);
+    if (tile == 64) ref_gemm_kernel<64><<<grid, block, 0, s>>>(M, N, K, A, B, epi);
+    else ref_gemm_kernel<128><<<grid, block, 0, s>>>(M, N, K, A, B, epi);
     PQ_CHECK_LAUNCH("ref_gemm_kernel");
     return PQ_OK;
   }

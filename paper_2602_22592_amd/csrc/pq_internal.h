@@ -119,7 +119,7 @@ struct pq_phase2 {
 };
 
 // C[M][N] (+)= epilogue( sum_k A(m,k) * B(n,k) ).  `engine` 0 = MFMA (bf16 or int8 operands),
-// 1 = reference precision (fp64 accumulate, any operand kind).
+// 1 = reference precision (fp64 products and sums on the fp64 MFMA, any operand kind).
 // Grouped execution over expert segments (Sec. 3.3): `offsets` [n_groups+1] is a device array of
 // slot positions.  mode 1: rows [offsets[e], offsets[e+1]) of A and C belong to group e and use
 // B + e*b_stride (elements of B's type) -- the per-expert GEMMs of the forward pass;  mode 2: the
