@@ -284,7 +284,8 @@ int pq_ffn_bwd(const pq_ffn_desc* desc, const void* dY, const void* X, const voi
  * Limits: 1 <= B <= 16; K % 128 == 0 (K % 512 == 0 for B > 1 on the row-major packing); N % 4 == 0;
  * r % 8 == 0 (B == 1) or r % 32 == 0 and (E r) % 64 == 0 (B > 1); for B > 1 the codes and expert
  * hidden states of 8 (B <= 8) or 16 token rows must fit the LDS: rows * (K + 2 E r) <= 160 KiB
- * (row-interleaved packing: rows * K + max(8 KiB, 2 rows E r)).  Violations return PQ_ERR_SHAPE. */
+ * (row-interleaved packing: the codes pass through in blocks, min(rows * K, 32 KiB) + max(8 KiB, 2 rows E r)).
+ * Violations return PQ_ERR_SHAPE. */
 typedef enum pq_packed_layout {
   PQ_PACKED_ROWMAJOR = 0, /* [N][K/32], as written by pq_pack_sign */
   PQ_PACKED_TILED64 = 1   /* [ceil(N/64)][K/128][64][4]: rows interleaved by 64 (pq_pack_retile64); any batch, the fast layout */
@@ -346,8 +347,8 @@ int pq_decode_gemv_int8(const pq_decode_desc* desc, const void* X, const uint32_
  * batch = B > 1 (small-batch decoding, App. A): B tokens per layer through the same stages on the small-batch kernels;
  *   X and Y are [L][B][D], acc_upgate [L][2][B][F]; the up and gate products of a layer read the layer's B quantised
  *   tokens once per workgroup, every expert selected by some token is read once per output tile.
- *   Further limits: B <= 16, r % 32 == 0, (E r) % 64 == 0, and 8 (B <= 8) or 16 token rows of codes (D resp. F bytes
- *   each) plus the expert hidden states (2 * rows * E * r bytes, at least 8 KiB) must fit 160 KiB of LDS. */
+ *   Further limits: B <= 16, r % 32 == 0, (E r) % 64 == 0, and the expert hidden states of 8 (B <= 8) or 16 token rows
+ *   (2 * rows * E * r bytes, at least 8 KiB) must fit 160 KiB of LDS next to a 32 KiB block of codes. */
 typedef struct pq_decode_ffn_desc {
   int32_t d_model;   /* D */
   int32_t d_ffn;     /* F */

@@ -950,7 +950,9 @@ int check_decode(const pq_decode_desc* d) {
     const size_t toks = d->batch <= 8 ? 8 : 16;
     const size_t er = d->hp_rank > 0 ? (size_t)d->n_experts * d->hp_rank : 0;
     const size_t hm = 2 * toks * er;
-    PQ_REQUIRE(toks * (size_t)d->d_in + ((tiled && hm < 8192) ? 8192 : hm) <= 160 * 1024, PQ_ERR_SHAPE,
+    // (the row-interleaved kernel walks the codes in blocks of 32 KiB)
+    const size_t codes = tiled && toks * (size_t)d->d_in > 32768 ? 32768 : toks * (size_t)d->d_in;
+    PQ_REQUIRE(codes + ((tiled && hm < 8192) ? 8192 : hm) <= 160 * 1024, PQ_ERR_SHAPE,
                "activations and expert hidden states do not fit the 160 KiB LDS");
   }
   return PQ_OK;
@@ -1024,11 +1026,11 @@ int check_dffn(const pq_decode_ffn_desc* d) {
   if (d->batch > 1) {
     PQ_REQUIRE(d->hp_rank % 32 == 0 && (d->n_experts * d->hp_rank) % 64 == 0, PQ_ERR_SHAPE,
                "batch > 1 needs hp_rank=%d %% 32 == 0 and n_experts * hp_rank %% 64 == 0", d->hp_rank);
-    // LDS of the small-batch kernels: 8 or 16 token rows of codes, and for the down product the expert hidden states
+    // LDS of the small-batch kernels: a block of the 8 or 16 token rows of codes, and for the down product the expert hidden states
     const size_t toks = d->batch <= 8 ? 8 : 16;
     const size_t hm = 2 * toks * (size_t)d->n_experts * d->hp_rank;
-    PQ_REQUIRE(toks * (size_t)d->d_model + 8192 <= 160 * 1024 && toks * (size_t)d->d_ffn + (hm < 8192 ? 8192 : hm) <= 160 * 1024,
-               PQ_ERR_SHAPE, "activations and expert hidden states of %d tokens do not fit the 160 KiB LDS", d->batch);
+    PQ_REQUIRE(32768 + (hm < 8192 ? 8192 : hm) <= 160 * 1024, PQ_ERR_SHAPE,
+               "expert hidden states of %d tokens do not fit the 160 KiB LDS next to a 32 KiB block of codes", d->batch);
   }
   return PQ_OK;
 }

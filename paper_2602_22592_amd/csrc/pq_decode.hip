@@ -1026,28 +1026,36 @@ struct gemm16_params {
   int xshare;             // > 1: that many consecutive weight sets read the same tokens (codes, row sums, gammas of set / xshare)
 };
 
+constexpr int G16_LDS_CODE_BYTES = 32768;           // LDS the row-interleaved kernel spends on the batch's codes
 constexpr int G16_RT = 4;                           // 16-row MFMA tiles per wavefront
 constexpr int G16_ROWS_PER_WAVE = 16 * G16_RT;
 constexpr int G16_ROWS_PER_BLOCK = 4 * G16_ROWS_PER_WAVE;
 
 // Stages the batch's INT8 codes and the gate-weighted expert hidden states into LDS and returns the mask
-// of experts that some token selected.  xs: [TOKS][K] int8, 16-byte chunk c of token j at chunk c ^ (j & 7);
+// of experts that some token selected.  xs: [TOKS][kcols] int8, 16-byte chunk c of token j at chunk c ^ (j & 7);
 // hm: [TOKS][E*r] bf16 (zero where a token did not select the expert), same chunk swizzle.
 // I8: hm holds INT8 codes instead ([TOKS][E*r] bytes, 16-byte chunk c of token j at chunk c ^ (j & 7)): every
 // selected (token, expert) hidden state is put on the INT8 grid with its own gamma (Sec. 3.1 quantiser), one
 // wavefront per slot; behind the codes sit 1/gamma_h and the gate per (token, expert), zero where not selected.
-template <int TOKS, bool I8 = false>
-__device__ __forceinline__ unsigned long long g16_stage_inputs(const gemm16_params& p, int layer, unsigned char* xs,
-                                                               uint16_t* hm) {
-  const int tid = threadIdx.x;
-  const int K = p.K, Er = p.E * p.r;
-  const int kch = K / 16;
-  for (int c = tid; c < TOKS * kch; c += 256) {
+// Columns [k0, k0 + kcols) of the batch's codes into xs, rows `stride` bytes apart (kcols and stride multiples of 128)
+template <int TOKS>
+__device__ __forceinline__ void g16_stage_codes(const gemm16_params& p, int layer, unsigned char* xs, int k0, int kcols, int stride) {
+  const int kch = kcols / 16;
+  for (int c = threadIdx.x; c < TOKS * kch; c += 256) {
     const int j = c / kch, cc = c % kch;
     uint4 v = make_uint4(0, 0, 0, 0);
-    if (j < p.B) v = *reinterpret_cast<const uint4*>(p.xq + ((size_t)layer * p.B + j) * K + cc * 16);
-    *reinterpret_cast<uint4*>(xs + (size_t)j * K + ((cc ^ (j & 7)) << 4)) = v;
+    if (j < p.B) v = *reinterpret_cast<const uint4*>(p.xq + ((size_t)layer * p.B + j) * p.K + k0 + cc * 16);
+    *reinterpret_cast<uint4*>(xs + (size_t)j * stride + ((cc ^ (j & 7)) << 4)) = v;
   }
+}
+
+// kcols: how many columns of the codes are staged now (all K, or the first block of a kernel that walks K in blocks)
+template <int TOKS, bool I8 = false>
+__device__ __forceinline__ unsigned long long g16_stage_inputs(const gemm16_params& p, int layer, unsigned char* xs,
+                                                               uint16_t* hm, int kcols) {
+  const int tid = threadIdx.x;
+  const int Er = p.E * p.r;
+  g16_stage_codes<TOKS>(p, layer, xs, 0, kcols, kcols);
   for (int c = tid; c < TOKS * Er / 8; c += 256) reinterpret_cast<uint4*>(hm)[c] = make_uint4(0, 0, 0, 0);
   __syncthreads();
   unsigned long long used = 0ull;
@@ -1110,7 +1118,7 @@ __global__ __launch_bounds__(256) void decode_gemm16_kernel(gemm16_params p) {
   const int K = p.K, Er = p.E * p.r;
   unsigned char* xs = dsm;
   uint16_t* hm = reinterpret_cast<uint16_t*>(dsm + TOKS * (size_t)K);
-  const unsigned long long used = g16_stage_inputs<TOKS>(p, layer, xs, hm);
+  const unsigned long long used = g16_stage_inputs<TOKS>(p, layer, xs, hm, K);
 
   const int i = lane & 15, g = lane >> 4;
   const int il = i & (TOKS - 1);                     // LDS row read for MFMA column i
@@ -1241,14 +1249,17 @@ __global__ __launch_bounds__(256) void decode_gemm16_kernel(gemm16_params p) {
 template <int TOKS, bool I8 = false>
 __global__ __launch_bounds__(256, 4) void decode_gemm16_tiled_kernel(gemm16_params p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char dsm[];
-  // dsm: xq [TOKS][K] int8, then a region that first holds Hm [TOKS][E*r] bf16 (expert phase) and afterwards
+  // dsm: xq [TOKS][min(K, KC)] int8 (one block of the codes), then a region that first holds Hm [TOKS][E*r] bf16 (expert phase) and afterwards
   // the four 2 KB wave-private patches (1-bit phase and output staging); it is max(8 KB, Hm) long
   const int layer = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int K = p.K, Er = p.E * p.r;
+  // the codes pass through LDS in blocks of KC columns (32 KB whatever the batch), so that four workgroups fit a CU at any K
+  constexpr int KC = G16_LDS_CODE_BYTES / TOKS;
+  const int KCs = K < KC ? K : KC;                    // row stride of xs
   unsigned char* xs = dsm;
-  uint16_t* hm = reinterpret_cast<uint16_t*>(dsm + TOKS * (size_t)K);
-  uint32_t* patch = reinterpret_cast<uint32_t*>(dsm + TOKS * (size_t)K) + wave * 512;
+  uint16_t* hm = reinterpret_cast<uint16_t*>(dsm + TOKS * (size_t)KCs);
+  uint32_t* patch = reinterpret_cast<uint32_t*>(dsm + TOKS * (size_t)KCs) + wave * 512;
   const int i = lane & 15, g = lane >> 4;
   const int il = i & (TOKS - 1);
   const int G = (p.N + 63) / 64;
@@ -1267,7 +1278,7 @@ __global__ __launch_bounds__(256, 4) void decode_gemm16_tiled_kernel(gemm16_para
 #pragma unroll
   for (int jj = 0; jj < 8; ++jj) w[jj] = nt_load16(Pg + (size_t)(jj < nq ? jj : nq - 1) * 64);
   const int lx = p.xshare > 1 ? layer / p.xshare : layer;   // the token block this weight set reads
-  const unsigned long long used = g16_stage_inputs<TOKS, I8>(p, lx, xs, hm);   // overlaps the first loads
+  const unsigned long long used = g16_stage_inputs<TOKS, I8>(p, lx, xs, hm, KCs);   // overlaps the first loads
   const bool active = grp < G;                        // idle wavefronts of the last workgroup still meet the barrier
 
   // experts selected by at least one token of the batch (dense-masked bf16 MFMA, 32 columns of r per issue)
@@ -1362,6 +1373,7 @@ __global__ __launch_bounds__(256, 4) void decode_gemm16_tiled_kernel(gemm16_para
 
   // Passes of 8 chunks; whole passes carry no condition (one basic block: the accumulators stay put and
   // the MFMAs of one chunk overlap the LDS round trip of the next), the ragged last pass checks each chunk.
+  int qb = 0;                                         // first 128-column chunk of the staged block
   auto pass = [&](const int q0, auto full_tag) {
     constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
@@ -1373,9 +1385,9 @@ __global__ __launch_bounds__(256, 4) void decode_gemm16_tiled_kernel(gemm16_para
         w[jj] = nt_load16(Pg + (size_t)(qn < nq ? qn : nq - 1) * 64);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        const int chunk = 8 * (q0 + jj) + 2 * g;      // 16-column chunk of the activation row
-        const uint4 act0 = *reinterpret_cast<const uint4*>(xs + (size_t)il * K + ((chunk ^ (il & 7)) << 4));
-        const uint4 act1 = *reinterpret_cast<const uint4*>(xs + (size_t)il * K + (((chunk + 1) ^ (il & 7)) << 4));
+        const int chunk = 8 * (q0 - qb + jj) + 2 * g; // 16-column chunk of the staged part of the activation row
+        const uint4 act0 = *reinterpret_cast<const uint4*>(xs + (size_t)il * KCs + ((chunk ^ (il & 7)) << 4));
+        const uint4 act1 = *reinterpret_cast<const uint4*>(xs + (size_t)il * KCs + (((chunk + 1) ^ (il & 7)) << 4));
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const uint32_t x = buf[(16 * t + i) * 4 + g];
@@ -1389,10 +1401,22 @@ __global__ __launch_bounds__(256, 4) void decode_gemm16_tiled_kernel(gemm16_para
       }
     }
   };
+  constexpr int QPC = KC / 128;                       // 128-column chunks per block (a multiple of 8)
+  for (qb = 0; qb < nq; qb += QPC) {
+    if (qb > 0) {                                     // next block of the codes; the weight loads in flight carry on
+      __syncthreads();
+      const int left = K - qb * 128;
+      g16_stage_codes<TOKS>(p, lx, xs, qb * 128, left < KC ? left : KC, KCs);
+      __syncthreads();
+    }
+    if (active) {
+      const int qe = nq < qb + QPC ? nq : qb + QPC;
+      int q0 = qb;
+      for (; q0 + 8 <= qe; q0 += 8) pass(q0, std::true_type{});
+      if (q0 < qe) pass(q0, std::false_type{});         // only the last block can be ragged
+    }
+  }
   if (!active) return;                                // no workgroup barrier below
-  int q0 = 0;
-  for (; q0 + 8 <= nq; q0 += 8) pass(q0, std::true_type{});
-  if (q0 < nq) pass(q0, std::false_type{});
 
   // D[row 4 g + v][token i] -> patch as [token][64 rows] bf16, then 128-byte runs per token
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -1522,6 +1546,12 @@ __global__ __launch_bounds__(256) void decode_ffn_mid_kernel(const uint16_t* __r
 
 // The per-token kernels stage one token as fp32 (plus its codes for INT8 experts) in dynamic LDS next to a small
 // static block: above 64 KB in total the launch needs the limit raised once per process.
+// LDS of the row-interleaved small-batch kernel for the codes: the whole rows, or one block of them
+static size_t g16_tiled_code_bytes(int toks, int K) {
+  const size_t all = (size_t)toks * K;
+  return all < (size_t)G16_LDS_CODE_BYTES ? all : (size_t)G16_LDS_CODE_BYTES;
+}
+
 static size_t ffn_mid_lds_bytes(int F) {
   const int groups = (F + 255) / 256;
   return (size_t)((groups + FFN_MID_PARTS - 1) / FFN_MID_PARTS) * 256 * sizeof(float);
@@ -1600,7 +1630,7 @@ static int launch_decode_ffn_batch(int L, int B, int D, int F, int r, int E, int
     pq_prof_scope prof(PQP_DECODE_MAIN, s);
     gemm16_params p{packed_upgate, scale_upgate, xq1, rs1, gm1, nullptr, nullptr, nullptr, nullptr, (uint16_t*)UG, acc_upgate,
                     B, F, D, 0, 0, 0, alpha, nullptr, 2};
-    const size_t lds = (size_t)toks * D + 8192;
+    const size_t lds = g16_tiled_code_bytes(toks, D) + 8192;
     dim3 grid(((F + 63) / 64 + 3) / 4, 2 * L);
     if (toks == 8) decode_gemm16_tiled_kernel<8><<<grid, 256, lds, s>>>(p);
     else decode_gemm16_tiled_kernel<16><<<grid, 256, lds, s>>>(p);
@@ -1618,7 +1648,7 @@ static int launch_decode_ffn_batch(int L, int B, int D, int F, int r, int E, int
     gemm16_params p{packed_down, scale_down, xq2, rs2, gm2, (const uint16_t*)Down, idx, gate, act, (uint16_t*)Y, nullptr,
                     B, D, F, E, r, topk, alpha, nullptr, 1};
     const size_t hm = 2 * (size_t)toks * E * r;
-    const size_t lds = (size_t)toks * F + (hm > 8192 ? hm : 8192);
+    const size_t lds = g16_tiled_code_bytes(toks, F) + (hm > 8192 ? hm : 8192);
     dim3 grid(((D + 63) / 64 + 3) / 4, L);
     if (toks == 8) decode_gemm16_tiled_kernel<8><<<grid, 256, lds, s>>>(p);
     else decode_gemm16_tiled_kernel<16><<<grid, 256, lds, s>>>(p);
@@ -1764,7 +1794,7 @@ int pq_launch_decode(const pq_decode_desc& d, const void* X, const uint32_t* pac
     const int toks = B <= 8 ? 8 : 16;
     const bool tiled = d.packed_layout == PQ_PACKED_TILED64;
     const size_t hm_bytes = 2 * (size_t)toks * d.n_experts * r;
-    const size_t lds = (size_t)toks * K + (tiled ? (hm_bytes > 8192 ? hm_bytes : 8192) : hm_bytes);
+    const size_t lds = tiled ? g16_tiled_code_bytes(toks, K) + (hm_bytes > 8192 ? hm_bytes : 8192) : (size_t)toks * K + hm_bytes;
     if (int e = decode_set_gemm16_limits()) return e;
     if (tiled) {
       dim3 grid(((N + 63) / 64 + 3) / 4, L);

@@ -82,7 +82,9 @@ def test_decode_small_batch(L, B, K, N, E, r, k, tiled):
                  tiled=tiled)
 
 
-@pytest.mark.parametrize("L,B,K,N,E,r,k", [(1, 4, 640, 132, 4, 32, 2), (2, 9, 1408, 260, 2, 64, 1)])
+@pytest.mark.parametrize("L,B,K,N,E,r,k", [(1, 4, 640, 132, 4, 32, 2), (2, 9, 1408, 260, 2, 64, 1),
+                                           # the codes pass through LDS in blocks of 32 KB: three blocks, the last one ragged
+                                           (1, 16, 4352, 132, 4, 32, 2), (1, 7, 8960, 200, 2, 32, 1)])
 def test_decode_small_batch_tiled_ragged_k(L, B, K, N, E, r, k):
     """Row-interleaved packing takes any d_in that is a multiple of 128 (here not of 512) and a ragged last group."""
     print(f"decode tiled B={B}: L={L} K={K} N={N} E={E} r={r} k={k}", flush=True)

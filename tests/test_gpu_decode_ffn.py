@@ -83,7 +83,9 @@ def test_decode_ffn(L, D, F, E, r, k):
 
 
 @pytest.mark.parametrize("L,B,D,F,E,r,k", [(2, 2, 256, 384, 4, 32, 2), (1, 8, 640, 1152, 8, 32, 3), (2, 5, 2048, 5504, 8, 32, 1),
-                                           (1, 16, 512, 640, 2, 64, 1), (1, 11, 384, 256, 4, 32, 2)])
+                                           (1, 16, 512, 640, 2, 64, 1), (1, 11, 384, 256, 4, 32, 2),
+                                           # 16 tokens x 11008 codes are more than the LDS: the down product walks them in blocks
+                                           (1, 16, 256, 11008, 2, 64, 1)])
 def test_decode_ffn_small_batch(L, B, D, F, E, r, k):
     """Several tokens per layer (App. A, small-batch decoding): the accumulators of the up and gate products bit-exact
     per token, every token's output within 2e-2 of the oracle's per-token FFN."""
