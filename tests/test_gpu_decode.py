@@ -187,3 +187,13 @@ def test_decode_largest_d_in():
     check_decode(wl.decode_case(95, 1, d_in=16384, d_out=72, n_experts=2, hp_rank=16, n_layers=1), top_k=1, tiled=True)
     print("decode INT8 experts d_in = 13056", flush=True)
     check_decode_int8(wl.decode_case(96, 1, d_in=13056, d_out=72, n_experts=2, hp_rank=32, n_layers=1), top_k=1, tiled=True)
+
+
+def test_decode_largest_d_in_small_batch():
+    """d_in = 16384 with 16 and with 8 tokens on the row-interleaved packing: 256 KB resp. 128 KB of codes walk through
+    32 KB of LDS in eight resp. four blocks; the INT8 experts at batch 8 likewise."""
+    for B in (16, 8):
+        print(f"decode d_in = 16384, B = {B}", flush=True)
+        check_decode(wl.decode_case(97 + B, B, d_in=16384, d_out=136, n_experts=2, hp_rank=32, n_layers=1), top_k=1, tiled=True)
+    print("decode INT8 experts d_in = 12800, B = 8", flush=True)
+    check_decode_int8(wl.decode_case(99, 8, d_in=12800, d_out=136, n_experts=2, hp_rank=64, n_layers=1), top_k=1, tiled=True)

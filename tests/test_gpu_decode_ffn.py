@@ -122,3 +122,5 @@ def test_decode_ffn_expert_term_alone_and_limits():
 def test_decode_ffn_largest_d_ffn():
     print("decode FFN d_ffn = 16384", flush=True)
     check(1, 128, 16384, 2, 8, 1)
+    print("decode FFN d_ffn = 16384, 16 tokens", flush=True)
+    check(1, 128, 16384, 2, 64, 1, B=16)
