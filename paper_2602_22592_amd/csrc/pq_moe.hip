@@ -41,7 +41,17 @@ __global__ __launch_bounds__(1024) void route_kernel(const int* __restrict__ idx
   __shared__ int s_cnt[16][64], s_off[65];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   if constexpr (LDS_IDS) {
-    for (int s = threadIdx.x; s < S; s += 1024) s_ids[s] = (unsigned char)idx[s];
+    // eight loads per thread in flight (indices clamped, the store conditional): one memory latency per 8192 slots
+    for (int s0 = 0; s0 < S; s0 += 8192) {
+      int v[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) v[q] = idx[min(s0 + q * 1024 + (int)threadIdx.x, S - 1)];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int s = s0 + q * 1024 + (int)threadIdx.x;
+        if (s < S) s_ids[s] = (unsigned char)v[q];
+      }
+    }
     __syncthreads();
   }
   auto id_at = [&](int s) -> int {
@@ -61,18 +71,27 @@ __global__ __launch_bounds__(1024) void route_kernel(const int* __restrict__ idx
   }
   s_cnt[wave][lane] = cnt;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int run = 0;
-    for (int e = 0; e < E; ++e) {
-      int tot = 0;
-      for (int w = 0; w < 16; ++w) tot += s_cnt[w][e];
-      s_off[e] = run;
-      offsets[e] = run;
-      counts[e] = tot;
-      run += tot;
+  if (wave == 0) {                                  // lane e: expert e's total, then the exclusive prefix over the experts (E <= 64)
+    int tot = 0;
+    if (lane < E) {
+#pragma unroll
+      for (int w = 0; w < 16; ++w) tot += s_cnt[w][lane];
     }
-    s_off[E] = run;
-    offsets[E] = run;
+    int incl = tot;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int up = __shfl_up(incl, d);
+      if (lane >= d) incl += up;
+    }
+    if (lane < E) {
+      s_off[lane] = incl - tot;
+      offsets[lane] = incl - tot;
+      counts[lane] = tot;
+    }
+    if (lane == E - 1) {
+      s_off[E] = incl;
+      offsets[E] = incl;
+    }
   }
   __syncthreads();
   int running = 0;                                  // lane e: next position of expert e for this wavefront
@@ -83,15 +102,18 @@ __global__ __launch_bounds__(1024) void route_kernel(const int* __restrict__ idx
   for (int b = b0; b < b1; ++b) {
     const int s = b * 64 + lane;
     const int id = id_at(s);
+    int pos = 0;
     for (int e = 0; e < E; ++e) {
       const unsigned long long m = __ballot(id == e);
-      const int base = __shfl(running, e);
-      if (id == e) {
-        const int pos = base + __builtin_popcountll(m & ((1ull << lane) - 1ull));
-        perm[pos] = s;
-        inv[s] = pos;
-      }
+      const int base = __builtin_amdgcn_readlane(running, e);   // e is uniform: a scalar read, not a trip through LDS
+      if (id == e) pos = base + __builtin_popcountll(m & ((1ull << lane) - 1ull));
       if (lane == e) running += __builtin_popcountll(m);
+    }
+    // one pair of stores per 64 slots (a store under each expert's branch made the single CU's memory pipe the bottleneck:
+    // 2 E store instructions per block and wavefront)
+    if (id >= 0) {
+      perm[pos] = s;
+      inv[s] = pos;
     }
   }
 }
@@ -405,29 +427,46 @@ __global__ __launch_bounds__(256) void router_bwd_kernel(const float* __restrict
 // A workgroup covers 256 columns of one chunk: thread = (token subgroup sg, column group cg); it walks the
 // 32 tokens t0 + sg, t0 + sg + 8, ... with 16-byte loads of 8 columns, then the 8 subgroups are summed in LDS
 // in a fixed order.
+constexpr int DWR_CHUNK = 128;                      // tokens per workgroup (a multiple of 64)
 __global__ __launch_bounds__(256) void dwr_partial_kernel(const float* __restrict__ dlogit, const uint16_t* __restrict__ X, int T,
                                                           int d, int E, float* __restrict__ part) {
   __shared__ float red[8][4][8][32];                 // [subgroup][expert % 4][column % 8][column group]
+  __shared__ __attribute__((aligned(16))) float sdl[DWR_CHUNK][8];   // the chunk's dlogit for the eight experts of a pass (zero past E and past T)
   const int tid = threadIdx.x, cg = tid & 31, sg = tid >> 5;
   const int c0 = blockIdx.x * 256 + cg * 8;
-  const int t0 = blockIdx.y * 256, t1 = min(T, t0 + 256);
+  const int t0 = blockIdx.y * DWR_CHUNK;
   const bool okc = c0 < d;                            // d % 8 == 0
   for (int e0 = 0; e0 < E; e0 += 8) {
+    // every load below is unconditional (indices clamped into the arrays, the value masked afterwards): a load under
+    // a branch waits for its own latency, and the loop over tokens becomes a chain of them
+    for (int o = tid; o < DWR_CHUNK * 8; o += 256) {
+      const int tt = o >> 3, u = o & 7;
+      const float g = dlogit[(size_t)min(t0 + tt, T - 1) * E + min(e0 + u, E - 1)];
+      sdl[tt][u] = (t0 + tt < T && e0 + u < E) ? g : 0.0f;
+    }
+    __syncthreads();
     float acc[8][8];
 #pragma unroll
     for (int u = 0; u < 8; ++u)
 #pragma unroll
       for (int j = 0; j < 8; ++j) acc[u][j] = 0.0f;
     if (okc) {
-#pragma unroll 4
-      for (int t = t0 + sg; t < t1; t += 8) {
-        float x[8];
-        unpack8(*reinterpret_cast<const uint4*>(X + (size_t)t * d + c0), x);
+      for (int grp = 0; grp < DWR_CHUNK / 64; ++grp) {   // eight of the subgroup's tokens at a time, their loads issued together
+        uint4 xv[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const float g = (e0 + u < E) ? dlogit[(size_t)t * E + e0 + u] : 0.0f;
+        for (int q = 0; q < 8; ++q)
+          xv[q] = *reinterpret_cast<const uint4*>(X + (size_t)min(t0 + sg + 8 * (8 * grp + q), T - 1) * d + c0);
 #pragma unroll
-          for (int j = 0; j < 8; ++j) acc[u][j] += g * x[j];
+        for (int q = 0; q < 8; ++q) {
+          const int tt = sg + 8 * (8 * grp + q);
+          const float4 ga = *reinterpret_cast<const float4*>(&sdl[tt][0]), gb = *reinterpret_cast<const float4*>(&sdl[tt][4]);
+          const float g[8] = {ga.x, ga.y, ga.z, ga.w, gb.x, gb.y, gb.z, gb.w};
+          float x[8];
+          unpack8(xv[q], x);
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[u][j] += g[u] * x[j];
         }
       }
     }
@@ -451,11 +490,18 @@ __global__ __launch_bounds__(256) void dwr_partial_kernel(const float* __restric
     }
   }
 }
+// dWr = the chunks' partial sums added in chunk order (eight loads in flight per thread)
 __global__ __launch_bounds__(256) void dwr_final_kernel(const float* __restrict__ part, int nchunks, int n, float* __restrict__ dWr) {
   const int i = blockIdx.x * 256 + threadIdx.x;   // e * d + c
   if (i >= n) return;
   float acc = 0.0f;
-  for (int tc = 0; tc < nchunks; ++tc) acc += part[(size_t)tc * n + i];
+  for (int tc = 0; tc < nchunks; tc += 8) {
+    float v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = part[(size_t)min(tc + q, nchunks - 1) * n + i];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc += (tc + q < nchunks) ? v[q] : 0.0f;
+  }
   dWr[i] = acc;
 }
 
@@ -743,10 +789,10 @@ int pq_launch_router_bwd(const float* rd, const int* inv, const int* idx, const 
   return PQ_OK;
 }
 
-size_t pq_dwr_scratch_bytes(int T, int d, int E) { return (size_t)((T + 255) / 256) * E * d * sizeof(float); }
+size_t pq_dwr_scratch_bytes(int T, int d, int E) { return (size_t)((T + DWR_CHUNK - 1) / DWR_CHUNK) * E * d * sizeof(float); }
 int pq_launch_dwr(const float* dlogit, const void* X, int T, int d, int E, float* part, float* dWr, hipStream_t s) {
   pq_prof_scope prof(PQP_MOE_ELEMENTWISE, s);
-  const int nchunks = (T + 255) / 256;
+  const int nchunks = (T + DWR_CHUNK - 1) / DWR_CHUNK;
   if (nchunks > 0) {
     dim3 grid((d + 255) / 256, nchunks);
     dwr_partial_kernel<<<grid, 256, 0, s>>>(dlogit, (const uint16_t*)X, T, d, E, part);

@@ -674,11 +674,32 @@ int pq_launch_pack(const void* W, int dtype, int N, int K, const double* partial
   return PQ_OK;
 }
 
+// N values per lane summed over the wavefront, transposed: every exchange step halves the values a lane carries (the
+// lane with the step's bit set keeps the upper half and hands over the lower), so that after log2(N) steps a lane holds
+// one value -- lane l the one with index l / (64 / N) -- and the remaining steps are plain exchanges.  The additions
+// are those of the butterfly sum (same pairs, same order), at a quarter of the instructions.  Every index is static.
+template <int N, int OFF>
+__device__ __forceinline__ void wave_sum_transposed(double* v, int lane) {
+  if constexpr (N > 1) {
+    const bool up = (lane & OFF) != 0;
+#pragma unroll
+    for (int i = 0; i < N / 2; ++i) {
+      const double send = up ? v[i] : v[i + N / 2];
+      const double keep = up ? v[i + N / 2] : v[i];
+      v[i] = keep + __shfl_xor(send, OFF, 64);
+    }
+    if constexpr (OFF > 1) wave_sum_transposed<N / 2, OFF / 2>(v, lane);
+  } else {
+    v[0] += __shfl_xor(v[0], OFF, 64);
+    if constexpr (OFF > 1) wave_sum_transposed<1, OFF / 2>(v, lane);
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // Router: a wavefront takes TB tokens at once (a router row converted to fp64 serves all of them): fp64 dot products
 // against all E router rows, lane l accumulating the 16-byte chunks l, l + 64, ... of a token row in order, then the
-// wave sums; lane tb (< TB) rounds token tb's logits to fp32, selects the top-k (ties to the lower index) and evaluates
-// the softmax in fp64.
+// wave sums, which leave one (token, expert) pair per lane; that lane rounds the logit to fp32 and evaluates its term
+// of the softmax in fp64; the first lane of a token's group selects the top-k (ties to the lower index).
 // ------------------------------------------------------------------------------------------
 template <typename T, int EMAX, int TB>
 __global__ __launch_bounds__(256) void router_kernel(const T* __restrict__ X, const T* __restrict__ Wr,
@@ -729,42 +750,45 @@ __global__ __launch_bounds__(256) void router_kernel(const T* __restrict__ X, co
       }
     }
   }
-  double logit[EMAX];                                 // lane tb: the logits of token t0 + tb
-#pragma unroll
-  for (int e = 0; e < EMAX; ++e) logit[e] = 0.0;
+  // Sums over the wavefront, transposed (see wave_sum_transposed): lane l ends with the sum of value l / ST.
+  constexpr int NV = TB * EMAX, ST = 64 / NV;
+  static_assert(NV == 32 || NV == 64, "a wavefront carries 32 or 64 (token, expert) sums");
+  double v[NV];
 #pragma unroll
   for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
-    for (int e = 0; e < EMAX; ++e) {
-      const double v = (double)(float)wave_sum_d(acc[tb][e]);  // one rounding to fp32
-      if (lane == tb) logit[e] = v;
-    }
-  const int t = t0 + lane;
-  if (lane >= TB || t >= Tn) return;
-  double mx = -1e300;
+    for (int e = 0; e < EMAX; ++e) v[tb * EMAX + e] = acc[tb][e];
+  wave_sum_transposed<NV, 32>(v, lane);
+  // lane l: pair (token tb, expert e); one exponential and one division per lane
+  const int vi = lane / ST, tb = vi / EMAX, e = vi % EMAX;
+  const double lg = (double)(float)v[0];              // one rounding to fp32
+  const bool live = e < E;
+  double mx = live ? lg : -1e300;
 #pragma unroll
-  for (int e = 0; e < EMAX; ++e)
-    if (e < E) mx = fmax(mx, logit[e]);
-  double p[EMAX];
-  double den = 0.0;
+  for (int off = ST; off < ST * EMAX; off <<= 1) mx = fmax(mx, __shfl_xor(mx, off, 64));
+  double pr = live ? exp(lg - mx) : 0.0;
+  double den = pr;
 #pragma unroll
-  for (int e = 0; e < EMAX; ++e) {
-    p[e] = (e < E) ? exp(logit[e] - mx) : 0.0;
-    den += p[e];
+  for (int off = ST; off < ST * EMAX; off <<= 1) den += __shfl_xor(den, off, 64);
+  pr /= den;
+  const int t = t0 + tb;
+  if (probs && live && t < Tn && lane % ST == 0) probs[(size_t)t * E + e] = (float)pr;
+  // the token's logits and probabilities into every lane of its group, then the top-k (ties to the lower index)
+  double logit[EMAX], p[EMAX];
+#pragma unroll
+  for (int ee = 0; ee < EMAX; ++ee) {
+    logit[ee] = __shfl(lg, (tb * EMAX + ee) * ST, 64);
+    p[ee] = __shfl(pr, (tb * EMAX + ee) * ST, 64);
   }
-#pragma unroll
-  for (int e = 0; e < EMAX; ++e) {
-    p[e] /= den;
-    if (probs && e < E) probs[(size_t)t * E + e] = (float)p[e];
-  }
+  if (lane % (ST * EMAX) != 0 || t >= Tn) return;     // the group's first lane writes the token's choice
   unsigned long long taken = 0ull;
   for (int j = 0; j < k; ++j) {
     int best = -1;
     double bv = 0.0, bp = 0.0;
 #pragma unroll
-    for (int e = 0; e < EMAX; ++e) {
-      if (e < E && !((taken >> e) & 1ull) && (best < 0 || logit[e] > bv)) {
-        best = e; bv = logit[e]; bp = p[e];
+    for (int ee = 0; ee < EMAX; ++ee) {
+      if (ee < E && !((taken >> ee) & 1ull) && (best < 0 || logit[ee] > bv)) {
+        best = ee; bv = logit[ee]; bp = p[ee];
       }
     }
     taken |= 1ull << best;
