@@ -65,7 +65,9 @@ def check_ffn(c, top_k=1, alpha=2.0, beta=0.2, experts="bf16"):
 @pytest.mark.parametrize("T,D,F,E,r,k", [(200, 96, 160, 4, 8, 1), (200, 96, 160, 4, 8, 2), (700, 256, 544, 8, 32, 1),
                                          (130, 64, 64, 2, 16, 2), (1, 32, 32, 8, 8, 1),
                                          # hidden widths that are not whole packed words (like Table 1's 5076 = 158 * 32 + 20)
-                                         (200, 96, 172, 4, 8, 1), (130, 64, 52, 2, 16, 2), (300, 256, 500, 1, 32, 1)])
+                                         (200, 96, 172, 4, 8, 1), (130, 64, 52, 2, 16, 2), (300, 256, 500, 1, 32, 1),
+                                         # 1024 slots and more over ragged expert segments (one case with 64 experts, some of them empty)
+                                         (1500, 128, 96, 4, 16, 2), (1100, 64, 64, 64, 8, 1), (1030, 192, 160, 3, 56, 1)])
 def test_ffn_small(T, D, F, E, r, k):
     print(f"ffn T={T} d={D} F={F} E={E} r={r} k={k}", flush=True)
     check_ffn(wl.ffn_case(80 + T + k, T, D, F, E, r), top_k=k)
