@@ -30,6 +30,20 @@ def _declared_functions():
     return names
 
 
+def test_public_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 (no C++ or torch types in it) and as C++."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no host C compiler")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "pquant.h"\nint main(void) { return (int)sizeof(pq_linear_desc) == 0; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    if shutil.which("g++") is not None:
+        subprocess.run(["g++", "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)], check=True)
+
+
 def test_every_declared_symbol_is_exported(lib):
     declared = _declared_functions()
     assert {"pq_linear_fwd", "pq_linear_bwd", "pq_pack_sign", "pq_router_topk"} <= declared
