@@ -29,12 +29,13 @@ struct ffn_layout {
   // ctx
   size_t ml_up, ml_gate, ml_down, P_up, Pt_up, P_gate, Pt_gate, P_down, Pt_down, Xq, gx, Xt, U, G, Hq, gh, Ht;
   size_t idx, gate, probs, counts, offsets, perm, inv, Xp, ue, ge, a, Ys;
-  // bf16 experts: Up and Gate of every expert as one [E][2 r][D] matrix (both projections are one product whose output
-  // [S][2 r] starts at ue: the left half of a row is u, the right half g)
+  // Up and Gate of every expert as one [E][2 r][D] matrix (both projections are one product whose output [S][2 r] starts
+  // at ue: the left half of a row is u, the right half g)
   size_t UG;
-  // INT8 experts: codes, row scales and de-quantised bf16 copies of the expert weights; x's codes and gamma in slot
-  // order; the hidden state's codes, scales and de-quantised copy (Xp then holds the rows of X~ instead of X)
-  size_t UpQ, gUp, UpT, GateQ, gGate, GateT, DownQ, gDown, DownT, XqP, gxP, aQ, gA, aT, ctx_total;
+  // INT8 experts: codes, row scales and de-quantised bf16 copies of the expert weights (of the rows of UG, and of Down);
+  // x's codes and gamma in slot order; the hidden state's codes, scales and de-quantised copy (Xp then holds the rows of
+  // X~ instead of X)
+  size_t UGQ, gUG, UGT, DownQ, gDown, DownT, XqP, gxP, aQ, gA, aT, ctx_total;
   // workspace
   size_t stat, red_a, red_b, splitk, dHd, dU, dG, dYp, rd, da, du, dg, as, dXs, dlogit, dwr, dUG, ws_total;
   int n_red_a, n_red_b;
@@ -59,14 +60,13 @@ ffn_layout make_layout(const pq_ffn_desc& d) {
   L.Xp = c.take(S * D * 2); L.ue = c.take(2 * S * r * 2); L.ge = L.ue + S * r * 2; L.a = c.take(S * r * 2);
   L.Ys = c.take(S * D * 2);
   if (d.hp_kind == PQ_HP_LOWRANK_INT8) {
-    L.UpQ = c.take(E * r * D); L.gUp = c.take(E * r * 4); L.UpT = c.take(E * r * D * 2);
-    L.GateQ = c.take(E * r * D); L.gGate = c.take(E * r * 4); L.GateT = c.take(E * r * D * 2);
+    // rows of [Up_e; Gate_e] (one [2 r][D] matrix per expert, as in the bf16 form): codes, gammas, de-quantised copy
+    L.UGQ = c.take(E * 2 * r * D); L.gUG = c.take(E * 2 * r * 4); L.UGT = c.take(E * 2 * r * D * 2);
     L.DownQ = c.take(E * D * r); L.gDown = c.take(E * D * 4); L.DownT = c.take(E * D * r * 2);
     L.XqP = c.take(S * D); L.gxP = c.take(S * 4);
     L.aQ = c.take(S * r); L.gA = c.take(S * 4); L.aT = c.take(S * r * 2);
-  } else {
-    L.UG = c.take(E * 2 * r * D * 2);
   }
+  L.UG = c.take(E * 2 * r * D * 2);
   L.ctx_total = c.off;
   cursor w;
   L.stat = w.take(2 * sizeof(double) * 1024);
@@ -76,10 +76,10 @@ ffn_layout make_layout(const pq_ffn_desc& d) {
   L.red_b = w.take(sizeof(double) * (size_t)L.n_red_b);
   size_t sk = 0;
   const int Ti = d.tokens, Di = d.d_model, Fi = (int)F;
-  // (the last six: the expert products of a single high-precision branch, which run as plain GEMMs over all slots)
+  // (the last seven: the expert products of a single high-precision branch, which run as plain GEMMs over all slots)
   const int Si = (int)S, ri = (int)r;
-  const int shapes[10][3] = {{Di, Fi, Ti}, {Ti, Fi, Di}, {Ti, Di, Fi}, {Fi, Di, Ti},
-                             {Si, 2 * ri, Di}, {Si, ri, Di}, {Si, Di, 2 * ri}, {Si, Di, ri}, {Di, ri, Si}, {2 * ri, Di, Si}};
+  const int shapes[11][3] = {{Di, Fi, Ti}, {Ti, Fi, Di}, {Ti, Di, Fi}, {Fi, Di, Ti},
+                             {Si, 2 * ri, Di}, {Si, ri, Di}, {Si, Di, 2 * ri}, {Si, Di, ri}, {Di, ri, Si}, {2 * ri, Di, Si}, {ri, Di, Si}};
   for (const auto& sh : shapes) {
     if (sh[0] <= 0 || sh[1] <= 0) continue;
     const size_t b = pq_plan_gemm(0, sh[0], sh[1], sh[2]).ws_bytes;
@@ -98,7 +98,7 @@ ffn_layout make_layout(const pq_ffn_desc& d) {
   L.da = w.take(S * r * 2); L.du = w.take(2 * S * r * 2); L.dg = L.du + S * r * 2; L.as = w.take(S * r * 2);
   L.dXs = w.take(S * D * 2); L.dlogit = w.take(T * E * 4);
   L.dwr = w.take(pq_dwr_scratch_bytes((int)T, (int)D, (int)E));
-  if (d.hp_kind != PQ_HP_LOWRANK_INT8) L.dUG = w.take(E * 2 * r * D * 4);
+  L.dUG = w.take(E * 2 * r * D * 4);
   L.ws_total = w.off;
   return L;
 }
@@ -198,8 +198,8 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
   if (int e = pack_weight(W_down, D, Fv, cx, L.P_down, L.Pt_down, L.ml_down, part, s)) return e;
   const bool hp8 = d->hp_kind == PQ_HP_LOWRANK_INT8;
   if (hp8) {  // the experts' weight rows on the AbsMax grid (codes, gamma per row, de-quantised copy for the backward)
-    if (int e = pq_launch_quant_act(Up, PQ_BF16, E * r, D, (int8_t*)(cx + L.UpQ), (float*)(cx + L.gUp), (uint16_t*)(cx + L.UpT), s)) return e;
-    if (int e = pq_launch_quant_act(Gate, PQ_BF16, E * r, D, (int8_t*)(cx + L.GateQ), (float*)(cx + L.gGate), (uint16_t*)(cx + L.GateT), s)) return e;
+    if (int e = pq_launch_concat_expert_rows(Up, Gate, E, r, D, cx + L.UG, s)) return e;
+    if (int e = pq_launch_quant_act(cx + L.UG, PQ_BF16, E * 2 * r, D, (int8_t*)(cx + L.UGQ), (float*)(cx + L.gUG), (uint16_t*)(cx + L.UGT), s)) return e;
     if (int e = pq_launch_quant_act(Down, PQ_BF16, E * D, r, (int8_t*)(cx + L.DownQ), (float*)(cx + L.gDown), (uint16_t*)(cx + L.DownT), s)) return e;
   }
   if (T == 0)  // no tokens: leave empty expert segments behind so that a backward call is well defined
@@ -235,7 +235,7 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
   int* perm = (int*)(cx + L.perm);
   int* inv = (int*)(cx + L.inv);
   // a single branch (the paper's default, N = 1) has nothing to route: gate 1, identity permutation, X itself in slot order
-  const bool one = E == 1 && !hp8;
+  const bool one = E == 1;
   if (one) {
     if (int e = pq_launch_route_single(S, idx, gate, (float*)(cx + L.probs), (int*)(cx + L.counts), offsets, perm, inv, s)) return e;
   } else {
@@ -247,22 +247,24 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
   // (they then take the split rules and kernels of plain GEMMs, the four-wavefront weight-gradient kernel among them)
   const pq_gemm_group* pg1 = one ? nullptr : &g1;
   if (hp8) {
-    // slot-ordered X~ (for the backward), codes (int8 rows moved as D/2 16-bit units) and gamma of x
-    if (int e = pq_launch_gather_rows(cx + L.Xt, perm, k, S, D, cx + L.Xp, s)) return e;
-    if (int e = pq_launch_gather_rows(Xq, perm, k, S, D / 2, cx + L.XqP, s)) return e;
-    if (int e = pq_launch_gather_f32(gx, perm, k, S, (float*)(cx + L.gxP), s)) return e;
-    {  // u, g = (q_x q_w^T) / (gamma_x gamma_w), bf16
-      pq_operand A{cx + L.XqP, D, PQ_SRC_KC8, nullptr};
-      pq_operand B{cx + L.UpQ, D, PQ_SRC_KC8, nullptr};
-      pq_epilogue e = epi0();
-      e.C = cx + L.ue; e.ldc = r; e.out_kind = PQ_OUT_BF16; e.row_div = (const float*)(cx + L.gxP); e.col_div = (const float*)(cx + L.gUp);
-      g1.b_stride = (long)r * D; g1.coldiv_stride = r;
-      if (int err = pq_launch_gemm(0, S, r, D, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
-      pq_operand Bg{cx + L.GateQ, D, PQ_SRC_KC8, nullptr};
-      e.C = cx + L.ge; e.col_div = (const float*)(cx + L.gGate);
-      if (int err = pq_launch_gemm(0, S, r, D, A, Bg, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+    // slot-ordered X~ (for the backward), codes (int8 rows moved as D/2 16-bit units) and gamma of x; with a single
+    // branch the slot order is the token order and the originals serve
+    const void* xqp = one ? (const void*)Xq : (const void*)(cx + L.XqP);
+    const float* gxp = one ? (const float*)gx : (const float*)(cx + L.gxP);
+    if (!one) {
+      if (int e = pq_launch_gather_rows(cx + L.Xt, perm, k, S, D, cx + L.Xp, s)) return e;
+      if (int e = pq_launch_gather_rows(Xq, perm, k, S, D / 2, cx + L.XqP, s)) return e;
+      if (int e = pq_launch_gather_f32(gx, perm, k, S, (float*)(cx + L.gxP), s)) return e;
     }
-    if (int e = pq_launch_expert_act(cx + L.ue, cx + L.ge, r, S, r, cx + L.a, s)) return e;
+    {  // [u | g] = (q_x q_w^T) / (gamma_x gamma_w), bf16: both projections as one product with 2 r outputs per slot
+      pq_operand A{xqp, D, PQ_SRC_KC8, nullptr};
+      pq_operand B{cx + L.UGQ, D, PQ_SRC_KC8, nullptr};
+      pq_epilogue e = epi0();
+      e.C = cx + L.ue; e.ldc = 2 * r; e.out_kind = PQ_OUT_BF16; e.row_div = gxp; e.col_div = (const float*)(cx + L.gUG);
+      g1.b_stride = (long)2 * r * D; g1.coldiv_stride = 2 * r;
+      if (int err = pq_launch_gemm(0, S, 2 * r, D, A, B, e, s, PQP_GEMM_EXPERT, sk, pg1)) return err;
+    }
+    if (int e = pq_launch_expert_act(cx + L.ue, cx + L.ue + (size_t)r * 2, 2 * r, S, r, cx + L.a, s)) return e;
     if (int e = pq_launch_quant_act(cx + L.a, PQ_BF16, S, r, (int8_t*)(cx + L.aQ), (float*)(cx + L.gA), (uint16_t*)(cx + L.aT), s)) return e;
     {
       pq_operand A{cx + L.aQ, r, PQ_SRC_KC8, nullptr};
@@ -270,7 +272,7 @@ extern "C" int pq_ffn_fwd(const pq_ffn_desc* d, const void* X, const void* W_up,
       pq_epilogue e = epi0();
       e.C = cx + L.Ys; e.ldc = D; e.out_kind = PQ_OUT_BF16; e.row_div = (const float*)(cx + L.gA); e.col_div = (const float*)(cx + L.gDown);
       g1.b_stride = (long)D * r; g1.coldiv_stride = D;
-      if (int err = pq_launch_gemm(0, S, D, r, A, B, e, s, PQP_GEMM_EXPERT, sk, &g1)) return err;
+      if (int err = pq_launch_gemm(0, S, D, r, A, B, e, s, PQP_GEMM_EXPERT, sk, pg1)) return err;
     }
     return pq_launch_combine_fwd(Y, cx + L.Ys, inv, gate, d->alpha, T, k, D, s);
   }
@@ -319,7 +321,7 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
   const int T = d->tokens, D = d->d_model, Fv = d->d_ffn, F = (Fv + 31) / 32 * 32, r = d->hp_rank, E = d->n_experts, k = d->top_k, S = T * k;
   void* sk = ws + L.splitk;
   if (d->hp_kind == PQ_HP_LOWRANK_INT8) {  // STE: each product is differentiated with the de-quantised factors it multiplied
-    Up = cx + L.UpT; Gate = cx + L.GateT; Down = cx + L.DownT;
+    Down = cx + L.DownT;
   }
   const void* a_fwd = d->hp_kind == PQ_HP_LOWRANK_INT8 ? cx + L.aT : cx + L.a;
   const float* ml_up = (const float*)(cx + L.ml_up);
@@ -378,9 +380,10 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
   const int* inv = (const int*)(cx + L.inv);
   float* rd = (float*)(ws + L.rd);
   const bool hp8 = d->hp_kind == PQ_HP_LOWRANK_INT8;
-  const bool one = E == 1 && !hp8;                   // a single branch: identity permutation, plain GEMMs over all slots (see the forward)
+  const bool one = E == 1;                           // a single branch: identity permutation, plain GEMMs over all slots (see the forward)
   const void* dyp = one ? dY : ws + L.dYp;
-  const void* xp = one ? X : cx + L.Xp;
+  // what the up and gate products multiplied: X, or with INT8 experts its de-quantised codes
+  const void* xp = one ? (hp8 ? (const void*)(cx + L.Xt) : X) : (const void*)(cx + L.Xp);
   if (!one)
     if (int e = pq_launch_gather_rows(dY, perm, k, S, D, ws + L.dYp, s)) return e;
   if (int e = pq_launch_rowdot(dyp, cx + L.Ys, perm, gate, S, D, rd, red_a, s)) return e;
@@ -399,14 +402,9 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
     g1.b_stride = (long)D * r;
     if (int err = pq_launch_gemm(0, S, r, D, A, B, e, s, PQP_GEMM_EXPERT, sk, pg1)) return err;
   }
-  // bf16 experts: u | g and du | dg lie side by side in [S][2 r] matrices (Up and Gate are one weight matrix per expert)
-  if (hp8) {
-    if (int e = pq_launch_expert_act_bwd(ws + L.da, cx + L.ue, cx + L.ge, a_fwd, perm, gate, d->alpha, S, r, r, ws + L.du, ws + L.dg,
-                                         ws + L.as, s)) return e;
-  } else {
-    if (int e = pq_launch_expert_act_bwd(ws + L.da, cx + L.ue, cx + L.ue + (size_t)r * 2, a_fwd, perm, gate, d->alpha, S, r, 2 * r,
-                                         ws + L.du, ws + L.du + (size_t)r * 2, ws + L.as, s)) return e;
-  }
+  // u | g and du | dg lie side by side in [S][2 r] matrices (Up and Gate are one weight matrix per expert, in both forms)
+  if (int e = pq_launch_expert_act_bwd(ws + L.da, cx + L.ue, cx + L.ue + (size_t)r * 2, a_fwd, perm, gate, d->alpha, S, r, 2 * r,
+                                       ws + L.du, ws + L.du + (size_t)r * 2, ws + L.as, s)) return e;
   {  // per-expert weight gradients: contraction over the expert's slots
     pq_operand A{dyp, D, PQ_SRC_KS16, nullptr};
     pq_operand B{ws + L.as, r, PQ_SRC_KS16, nullptr};
@@ -415,15 +413,7 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
     g2.c_stride = (long)D * r;
     if (int err = pq_launch_gemm(0, D, r, S, A, B, e, s, PQP_GEMM_EXPERT, sk, pg2)) return err;
     pq_operand Bx{xp, D, PQ_SRC_KS16, nullptr};
-    if (hp8) {
-      pq_operand Au{ws + L.du, r, PQ_SRC_KS16, nullptr};
-      e.C = dUp; e.ldc = D;
-      g2.c_stride = (long)r * D;
-      if (int err = pq_launch_gemm(0, r, D, S, Au, Bx, e, s, PQP_GEMM_EXPERT, sk, pg2)) return err;
-      pq_operand Ag{ws + L.dg, r, PQ_SRC_KS16, nullptr};
-      e.C = dGate;
-      if (int err = pq_launch_gemm(0, r, D, S, Ag, Bx, e, s, PQP_GEMM_EXPERT, sk, pg2)) return err;
-    } else {   // d[Up_e; Gate_e] = [du | dg]^T Xp, then split into the caller's two gradients
+    {   // d[Up_e; Gate_e] = [du | dg]^T Xp, then split into the caller's two gradients
       pq_operand Aug{ws + L.du, 2 * r, PQ_SRC_KS16, nullptr};
       e.C = ws + L.dUG; e.ldc = D;
       g2.c_stride = (long)2 * r * D;
@@ -431,20 +421,9 @@ extern "C" int pq_ffn_bwd(const pq_ffn_desc* d, const void* dY, const void* X, c
       if (int err = pq_launch_split_expert_rows((const float*)(ws + L.dUG), E, r, D, dUp, dGate, s)) return err;
     }
   }
-  if (S > 0 && hp8) {  // dXs = du Up_e + dg Gate_e  (slot order)
-    pq_operand A{ws + L.du, r, PQ_SRC_KC16, nullptr};
-    pq_operand B{Up, D, PQ_SRC_KS16, nullptr};
-    pq_epilogue e = epi0();
-    e.C = ws + L.dXs; e.ldc = D; e.out_kind = PQ_OUT_BF16;
-    g1.b_stride = (long)r * D;
-    if (int err = pq_launch_gemm(0, S, D, r, A, B, e, s, PQP_GEMM_EXPERT, sk, pg1)) return err;
-    pq_operand A2{ws + L.dg, r, PQ_SRC_KC16, nullptr};
-    pq_operand B2{Gate, D, PQ_SRC_KS16, nullptr};
-    e.accumulate = 1;
-    if (int err = pq_launch_gemm(0, S, D, r, A2, B2, e, s, PQP_GEMM_EXPERT, sk, pg1)) return err;
-  } else if (S > 0) {  // dXs = [du | dg] [Up_e; Gate_e]
+  if (S > 0) {  // dXs = [du | dg] [Up_e; Gate_e]  (INT8 experts: the de-quantised rows)
     pq_operand A{ws + L.du, 2 * r, PQ_SRC_KC16, nullptr};
-    pq_operand B{cx + L.UG, D, PQ_SRC_KS16, nullptr};
+    pq_operand B{hp8 ? cx + L.UGT : cx + L.UG, D, PQ_SRC_KS16, nullptr};
     pq_epilogue e = epi0();
     e.C = ws + L.dXs; e.ldc = D; e.out_kind = PQ_OUT_BF16;
     g1.b_stride = (long)2 * r * D;

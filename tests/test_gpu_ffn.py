@@ -129,7 +129,9 @@ def test_ffn_paper_1p3b_shape_reduced_tokens(N):
 
 
 @pytest.mark.parametrize("T,D,F,E,r,k", [(700, 256, 544, 8, 32, 1), (200, 96, 160, 4, 32, 2), (300, 256, 500, 1, 64, 1),
-                                         (1, 32, 32, 8, 32, 1), (384, 2048, 5504, 8, 32, 1), (384, 2048, 5076, 4, 384, 1)])
+                                         (1, 32, 32, 8, 32, 1), (384, 2048, 5504, 8, 32, 1), (384, 2048, 5076, 4, 384, 1),
+                                         # a single INT8 branch (the paper's default N = 1 in the form Sec. 3.2 prints): no routing
+                                         (1100, 128, 96, 1, 32, 1), (384, 2048, 5076, 1, 384, 1)])
 def test_ffn_int8_experts(T, D, F, E, r, k):
     """The experts in the INT8 form the FFN equation of Sec. 3.2 prints: weight rows and the expert's hidden state on the
     AbsMax grid, x's codes shared with the 1-bit branch, STE backward on the de-quantised factors.  The last two shapes
